@@ -92,7 +92,7 @@ WORKLOADS: Dict[str, Workload] = {
     "cfg3_qwen_64k_dynamic": Workload(
         name="cfg3_qwen_64k_dynamic", wid=3, n_layers=28, batch=1, **QWEN, context=65536,
         k_small=4096, stride=5, n_steps=200, dynamic=True, threshold=0.9,
-        kv_recipe="zipf", q_recipe="topic_ar1", q_rho=0.99, q_sigma=0.141,
+        kv_recipe="zipf", q_recipe="topic_ar1", q_rho=0.97, q_sigma=0.243,   # trigger fires every 10-15 steps
         extra={"n_affine": 512, "beta": 1.0, "topic_gain": 0.5}),
     "cfg4_llama_batch16_ragged": Workload(
         name="cfg4_llama_batch16_ragged", wid=4, n_layers=4, batch=16, **LLAMA,

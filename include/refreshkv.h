@@ -1,0 +1,183 @@
+/*
+ * refreshkv.h -- C ABI of the RefreshKV decode-attention library for AMD MI355X (gfx950).
+ *
+ * RefreshKV (arXiv 2411.05787, Section 2.2 "Methodology and Implementation") decodes with
+ * two KV caches per layer: the full cache C_f, which is never evicted, and a small cache
+ * C_p of K rows that is rebuilt from C_f after every full-attention step.  This library
+ * holds the attention-side hot path of one layer:
+ *
+ *   rk_full_attn        full-attention step over C_f that also returns the attention
+ *                       scores of the current token            (Section 2.2, "Decoding with
+ *                       full cache"; Appendix A.1 "Compatibility with Flash Attention")
+ *   rk_topk_select      the K tokens that refresh C_p: max over the query heads of a GQA
+ *                       group, max-pool over neighbouring tokens, top-K
+ *                       (Section 2.2 "Prefilling stage" + its GQA footnote; Appendix A.1
+ *                       "Baseline Settings": kernel size 7; Appendix A.3)
+ *   rk_gather_small_kv  rebuild C_p from the selected rows of C_f         (Section 2.2)
+ *   rk_partial_attn     partial-attention step over C_p plus the tokens decoded since the
+ *                       refresh                      (Section 2.2, "Decoding with partial cache")
+ *   rk_query_sim        the query-similarity test that decides whether a full step is
+ *                       needed          (Section 2.2, "Deciding when to decode with full cache")
+ *
+ * General rules
+ * -------------
+ * - Every tensor pointer is a DEVICE pointer owned by the caller; `stream` is a hipStream_t
+ *   passed as void* (NULL = the default stream).  A call validates its arguments on the host,
+ *   then only enqueues kernels on `stream`: it never synchronises, allocates or frees, and the
+ *   library keeps no state between calls.  Calls that share a workspace must be ordered on one
+ *   stream (or otherwise serialised).
+ * - bf16 tensors are 16-bit patterns (upper half of IEEE fp32).  head_dim must be 128, rows of
+ *   128 elements are contiguous, and K/V base pointers and strides must keep rows 16-byte
+ *   aligned.  Strides are counted in elements.
+ * - Query head h reads KV head h / G with G = n_q_heads / n_kv_heads (1 <= G <= 8).
+ * - `seq_lens` is a device int32[batch]: the number of valid rows of each sequence in C_f, the
+ *   current token included.  `max_len` is a host-side upper bound of it, used to size grids; a
+ *   sequence longer than `max_len` is processed only up to `max_len`.
+ * - `pred` / `pred_val`: optional device int32[batch] predicate.  When `pred` is not NULL the
+ *   call does nothing for sequence b unless pred[b] == pred_val.  This lets a caller enqueue
+ *   both branches of the dynamic schedule without reading the trigger back to the host.
+ * - Return value: RK_OK, or a negative rk_status.  On error nothing was enqueued.
+ *   Arithmetic: bf16 inputs, fp32 accumulation, bf16 outputs (round to nearest even).
+ */
+#ifndef REFRESHKV_H
+#define REFRESHKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum rk_status {
+    RK_OK = 0,
+    RK_ERR_INVALID_ARG = -1,   /* NULL pointer, non-positive size, misaligned pointer/stride  */
+    RK_ERR_UNSUPPORTED = -2,   /* head_dim != 128, G > 8, k too large, aggregation != max ... */
+    RK_ERR_WORKSPACE   = -3,   /* workspace NULL, misaligned or smaller than rk_workspace_bytes */
+    RK_ERR_HIP         = -4    /* a HIP runtime call failed (launch error)                    */
+} rk_status;
+
+#define RK_AGG_MAX 0           /* aggregation across the query heads of a GQA group: max      */
+
+#define RK_HEAD_DIM 128
+#define RK_MAX_GROUP 8
+#define RK_MAX_K 16384         /* largest small-cache size rk_topk_select accepts              */
+#define RK_MAX_POOL_W 63       /* largest (odd) max-pool window                                */
+
+/* Geometry of one attention layer; `scale` multiplies q.k before the softmax. */
+typedef struct rk_geom {
+    int32_t batch;
+    int32_t n_q_heads;
+    int32_t n_kv_heads;
+    int32_t head_dim;
+    float   scale;
+} rk_geom;
+
+/* A KV cache: k and v are bf16 [batch, n_kv_heads, capacity, head_dim] with element strides
+ * stride_b (between sequences) and stride_h (between KV heads); the row stride is head_dim.
+ * `capacity` is the number of rows allocated per (sequence, KV head): the kernels never touch
+ * a row at or beyond it, whatever the device-side lengths and indices say. */
+typedef struct rk_kv {
+    const void* k;
+    const void* v;
+    int64_t stride_b;
+    int64_t stride_h;
+    int64_t capacity;
+} rk_kv;
+
+/* Library version (major * 10000 + minor * 100 + patch). */
+int rk_version(void);
+
+/* Static string for a status code. */
+const char* rk_status_string(int status);
+
+/* Bytes of device workspace that any call of this library needs for the given geometry, a
+ * context of at most max_len rows and a small cache of at most max_k rows.  Host-only. */
+size_t rk_workspace_bytes(const rk_geom* geom, int32_t max_len, int32_t max_k);
+
+/* Prepare a workspace (256-byte aligned device memory of at least rk_workspace_bytes) for its
+ * first use with this geometry: zeroes the arrival counters the kernels keep in it (a small
+ * fill kernel on `stream`).  Call once after allocating it, on the stream that will use it.
+ * The kernels leave the counters zero again after every call, so no further initialisation
+ * is needed. */
+int rk_workspace_init(const rk_geom* geom, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Full-attention decode step.
+ *   for every sequence b and query head h (KV head g = h / G), over rows j < seq_lens[b]:
+ *     s[j]   = scale * <q[b,h,:], K[b,g,j,:]>
+ *     a[j]   = exp(s[j] - max_j s) / sum_j exp(s[j] - max_j s)
+ *     out[b,h,:] = sum_j a[j] * V[b,g,j,:]              lse[b,h] = log sum_j exp(s[j])
+ *   q       bf16 [batch, n_q_heads, 128] contiguous
+ *   full    the cache C_f
+ *   out     bf16 [batch, n_q_heads, 128] contiguous
+ *   weights fp32 [batch, n_q_heads, w_stride] or NULL: weights[b,h,j] = a[j] for
+ *           j < seq_lens[b]; other entries are not written.  w_stride >= max_len.
+ *   lse     fp32 [batch, n_q_heads] or NULL.
+ * A sequence with seq_lens[b] == 0 gets out = 0 and lse = -inf. */
+int rk_full_attn(const rk_geom* geom, const void* q, rk_kv full,
+                 const int32_t* seq_lens, int32_t max_len,
+                 void* out, float* weights, int64_t w_stride, float* lse,
+                 const int32_t* pred, int32_t pred_val,
+                 void* workspace, size_t workspace_bytes, void* stream);
+
+/* Selection of the rows that refresh the small cache.
+ *   for every sequence b and KV head g, with n = seq_lens[b]:
+ *     A[j] = max over the G heads h of group g of weights[b,h,j]
+ *     P[j] = max of A over the window of pool_w positions centred on j, clipped to [0, n)
+ *     idx[b,g,0 .. k') = the k' = min(k, n) positions of largest P, ordered by P descending,
+ *                        equal P by ascending position;  idx[b,g,k' .. k) = -1
+ *     sel_scores[b,g,i] = P[idx[b,g,i]] (0 where idx is -1), when sel_scores is not NULL
+ *   weights must be non-negative and free of NaN (softmax output).  pool_w odd, 1..63
+ *   (7 in the paper, 1 = no pooling).  agg must be RK_AGG_MAX.  1 <= k <= RK_MAX_K.
+ *   idx int32 [batch, n_kv_heads, k]; sel_scores fp32 of the same shape or NULL. */
+int rk_topk_select(const rk_geom* geom, const float* weights, int64_t w_stride,
+                   const int32_t* seq_lens, int32_t max_len,
+                   int32_t k, int32_t pool_w, int32_t agg,
+                   int32_t* idx, float* sel_scores,
+                   const int32_t* pred, int32_t pred_val,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
+/* Rebuild the small cache: small.k[b,g,i,:] = full.k[b,g,idx[b,g,i],:] and the same for v, for
+ * every i < k with idx >= 0 (bit copies).  Slots whose idx is negative are left untouched.
+ * A slot whose idx is >= the capacity of `full` is skipped as well.  `small` must hold at least
+ * k rows per head and is written through its (const-declared) pointers. */
+int rk_gather_small_kv(const rk_geom* geom, rk_kv full, const int32_t* idx, int32_t k,
+                       rk_kv small, const int32_t* pred, int32_t pred_val, void* stream);
+
+/* Partial-attention decode step: the softmax attention of rk_full_attn, but over the row list
+ *   small rows 0 .. min(n_sel, tail_start[b]) - 1, then
+ *   full  rows tail_start[b] .. seq_lens[b] - 1   (the tokens decoded since the refresh,
+ *                                                  the current one included)
+ * tail_start is a device int32[batch]: seq_lens at the last refresh.  max_recent is a host
+ * upper bound of seq_lens[b] - tail_start[b].  With n_sel = K all selected rows are read;
+ * with n_sel = K - (seq_lens - tail_start) the small cache keeps a fixed size and drops its
+ * lowest-scored rows first (the small cache is in descending score order).
+ * No attention scores are returned.  An empty row list gives out = 0. */
+int rk_partial_attn(const rk_geom* geom, const void* q, rk_kv small, int32_t n_sel,
+                    rk_kv full, const int32_t* tail_start, const int32_t* seq_lens,
+                    int32_t max_recent, void* out,
+                    const int32_t* pred, int32_t pred_val,
+                    void* workspace, size_t workspace_bytes, void* stream);
+
+/* Query-similarity trigger.
+ *   qbar[b,:] = mean over the query heads of q[b,h,:]                        (fp32)
+ *   sim[b]    = <qbar, q_ref[b]> / (max(|qbar|, 1e-8) * max(|q_ref[b]|, 1e-8))
+ *   need_full[b] = (sim[b] <= threshold) || force_full
+ *   if need_full[b]: q_ref[b,:] = qbar[b,:]
+ * q_ref fp32 [batch, 128] is read and updated in place; sim fp32 [batch]; need_full
+ * int32 [batch] (0/1).  Pass force_full = 1 on steps that are full by schedule (fixed stride,
+ * first step) so that the reference follows the most recent full step. */
+int rk_query_sim(const rk_geom* geom, const void* q, float* q_ref, float threshold,
+                 int32_t force_full, float* sim, int32_t* need_full, void* stream);
+
+/* Bookkeeping of a refresh: tail_start[b] = seq_lens[b] for every sequence the predicate
+ * selects (all when pred is NULL).  After a full step + refresh the rows "decoded since the
+ * refresh" start at the current length (Section 2.2: the partial cache then grows by the
+ * tokens decoded with it).  Both arrays are device int32[batch]. */
+int rk_mark_refresh(const rk_geom* geom, const int32_t* seq_lens, int32_t* tail_start,
+                    const int32_t* pred, int32_t pred_val, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* REFRESHKV_H */

@@ -1,0 +1,18 @@
+"""RefreshKV decode-attention hot path for AMD MI355X (gfx950).
+
+A thin ctypes binding over ``librefreshkv.so`` (hand-written HIP; C ABI declared in
+``include/refreshkv.h``).  Every function here only marshals arguments: all arithmetic runs
+in the HIP kernels.  PyTorch tensors are used as device memory and for the current stream.
+
+Importing this package loads the shared library and fails if it has not been built
+(``python -m paper_2411_05787_amd.build``): there is no CPU fallback.
+"""
+from .binding import (LIB_PATH, RkError, Geom, Workspace, lib, version, status_string, workspace_bytes,
+                      rk_workspace_init, rk_full_attn, rk_topk_select, rk_gather_small_kv,
+                      rk_partial_attn, rk_query_sim, rk_mark_refresh, EXPORTS)
+from .schedule import RefreshKVLayer
+
+__all__ = ["LIB_PATH", "RkError", "Geom", "Workspace", "lib", "version", "status_string",
+           "workspace_bytes", "rk_workspace_init", "rk_full_attn", "rk_topk_select",
+           "rk_gather_small_kv", "rk_partial_attn", "rk_query_sim", "rk_mark_refresh", "EXPORTS",
+           "RefreshKVLayer"]

@@ -1,0 +1,231 @@
+"""ctypes binding of librefreshkv.so: same names as the C ABI, torch tensors for device memory.
+
+Argument marshalling only.  Shapes and dtypes are checked here so that a wrong tensor is an
+exception on the host and never a bad pointer on the GPU.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "librefreshkv.so")
+
+EXPORTS = ["rk_version", "rk_status_string", "rk_workspace_bytes", "rk_workspace_init",
+           "rk_full_attn", "rk_topk_select", "rk_gather_small_kv", "rk_partial_attn",
+           "rk_query_sim", "rk_mark_refresh"]
+
+RK_AGG_MAX = 0
+
+
+class RkError(RuntimeError):
+    def __init__(self, fn: str, status: int):
+        super().__init__("%s failed: %s (%d)" % (fn, status_string(status), status))
+        self.status = status
+
+
+class _Geom(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("scale", C.c_float)]
+
+
+class _Kv(C.Structure):
+    _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("stride_b", C.c_int64), ("stride_h", C.c_int64),
+                ("capacity", C.c_int64)]
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("librefreshkv.so is not built (%s missing); run "
+                          "`python -m paper_2411_05787_amd.build` first. There is no fallback path." % LIB_PATH)
+    l = C.CDLL(LIB_PATH)
+    P, I32, I64, SZ = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
+    G = C.POINTER(_Geom)
+    l.rk_version.restype = C.c_int
+    l.rk_version.argtypes = []
+    l.rk_status_string.restype = C.c_char_p
+    l.rk_status_string.argtypes = [C.c_int]
+    l.rk_workspace_bytes.restype = SZ
+    l.rk_workspace_bytes.argtypes = [G, I32, I32]
+    l.rk_workspace_init.restype = C.c_int
+    l.rk_workspace_init.argtypes = [G, P, SZ, P]
+    l.rk_full_attn.restype = C.c_int
+    l.rk_full_attn.argtypes = [G, P, _Kv, P, I32, P, P, I64, P, P, I32, P, SZ, P]
+    l.rk_topk_select.restype = C.c_int
+    l.rk_topk_select.argtypes = [G, P, I64, P, I32, I32, I32, I32, P, P, P, I32, P, SZ, P]
+    l.rk_gather_small_kv.restype = C.c_int
+    l.rk_gather_small_kv.argtypes = [G, _Kv, P, I32, _Kv, P, I32, P]
+    l.rk_partial_attn.restype = C.c_int
+    l.rk_partial_attn.argtypes = [G, P, _Kv, I32, _Kv, P, P, I32, P, P, I32, P, SZ, P]
+    l.rk_query_sim.restype = C.c_int
+    l.rk_query_sim.argtypes = [G, P, P, C.c_float, I32, P, P, P]
+    l.rk_mark_refresh.restype = C.c_int
+    l.rk_mark_refresh.argtypes = [G, P, P, P, I32, P]
+    return l
+
+
+lib = _load()
+
+
+def version() -> int:
+    return int(lib.rk_version())
+
+
+def status_string(status: int) -> str:
+    return lib.rk_status_string(int(status)).decode()
+
+
+@dataclass(frozen=True)
+class Geom:
+    batch: int
+    n_q_heads: int
+    n_kv_heads: int
+    head_dim: int
+    scale: float
+
+    def c(self) -> _Geom:
+        return _Geom(self.batch, self.n_q_heads, self.n_kv_heads, self.head_dim, self.scale)
+
+
+def _check(fn: str, rc: int) -> None:
+    if rc != 0:
+        raise RkError(fn, rc)
+
+
+def _dev(t: Optional[torch.Tensor], dtype, name: str, shape=None, optional=False) -> Optional[int]:
+    if t is None:
+        if optional:
+            return None
+        raise ValueError("%s is required" % name)
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise ValueError("%s must be a tensor in GPU memory" % name)
+    if t.dtype != dtype:
+        raise ValueError("%s must be %s, got %s" % (name, dtype, t.dtype))
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError("%s must have shape %s, got %s" % (name, tuple(shape), tuple(t.shape)))
+    return t.data_ptr()
+
+
+def _kv(geom: Geom, K: torch.Tensor, V: torch.Tensor, name: str, min_rows: int = 0) -> _Kv:
+    for t, n in ((K, name + ".k"), (V, name + ".v")):
+        if not isinstance(t, torch.Tensor) or not t.is_cuda or t.dtype != torch.bfloat16:
+            raise ValueError("%s must be a bf16 tensor in GPU memory" % n)
+        if t.dim() != 4 or t.shape[0] != geom.batch or t.shape[1] != geom.n_kv_heads or t.shape[3] != geom.head_dim:
+            raise ValueError("%s must be [batch, n_kv_heads, capacity, head_dim], got %s" % (n, tuple(t.shape)))
+        if t.stride(3) != 1 or t.stride(2) != geom.head_dim:
+            raise ValueError("%s rows must be contiguous" % n)
+        if t.shape[2] < min_rows:
+            raise ValueError("%s holds %d rows, %d needed" % (n, t.shape[2], min_rows))
+    if K.stride() != V.stride() or K.shape != V.shape:
+        raise ValueError("%s: k and v must share shape and strides" % name)
+    return _Kv(K.data_ptr(), V.data_ptr(), K.stride(0), K.stride(1), K.shape[2])
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, torch.cuda.Stream):
+        return stream.cuda_stream
+    return int(stream)
+
+
+def workspace_bytes(geom: Geom, max_len: int, max_k: int) -> int:
+    n = int(lib.rk_workspace_bytes(C.byref(geom.c()), int(max_len), int(max_k)))
+    if n == 0:
+        raise RkError("rk_workspace_bytes", -1)
+    return n
+
+
+class Workspace:
+    """Device scratch for one stream: allocated once, initialised once."""
+
+    def __init__(self, geom: Geom, max_len: int, max_k: int, device="cuda", stream=None):
+        self.geom = geom
+        self.max_len = int(max_len)
+        self.nbytes = workspace_bytes(geom, max_len, max_k)
+        self.buf = torch.empty(self.nbytes + 256, dtype=torch.uint8, device=device)
+        self.ptr = (self.buf.data_ptr() + 255) // 256 * 256
+        rk_workspace_init(geom, self, stream=stream)
+
+
+def rk_workspace_init(geom: Geom, ws: Workspace, stream=None) -> None:
+    _check("rk_workspace_init", lib.rk_workspace_init(C.byref(geom.c()), ws.ptr, ws.nbytes, _stream(stream)))
+
+
+def rk_full_attn(geom: Geom, q, K, V, seq_lens, max_len: int, out, weights=None, lse=None,
+                 pred=None, pred_val: int = 0, workspace: Workspace = None, stream=None) -> None:
+    B, Hq, D = geom.batch, geom.n_q_heads, geom.head_dim
+    if max_len > K.shape[2]:
+        raise ValueError("max_len %d exceeds the cache capacity %d" % (max_len, K.shape[2]))
+    w_stride = 0
+    if weights is not None:
+        if weights.dim() != 3 or weights.shape[0] != B or weights.shape[1] != Hq or weights.shape[2] < max_len:
+            raise ValueError("weights must be [batch, n_q_heads, >= max_len]")
+        w_stride = weights.shape[2]
+    _check("rk_full_attn", lib.rk_full_attn(
+        C.byref(geom.c()), _dev(q, torch.bfloat16, "q", (B, Hq, D)), _kv(geom, K, V, "full"),
+        _dev(seq_lens, torch.int32, "seq_lens", (B,)), int(max_len),
+        _dev(out, torch.bfloat16, "out", (B, Hq, D)),
+        _dev(weights, torch.float32, "weights", optional=True), w_stride,
+        _dev(lse, torch.float32, "lse", (B, Hq), optional=True),
+        _dev(pred, torch.int32, "pred", (B,), optional=True), int(pred_val),
+        workspace.ptr, workspace.nbytes, _stream(stream)))
+
+
+def rk_topk_select(geom: Geom, weights, seq_lens, max_len: int, k: int, pool_w: int, idx,
+                   sel_scores=None, agg: int = RK_AGG_MAX, pred=None, pred_val: int = 0,
+                   workspace: Workspace = None, stream=None) -> None:
+    B, Hq, Hkv = geom.batch, geom.n_q_heads, geom.n_kv_heads
+    if weights.dim() != 3 or weights.shape[0] != B or weights.shape[1] != Hq or weights.shape[2] < max_len:
+        raise ValueError("weights must be [batch, n_q_heads, >= max_len]")
+    _check("rk_topk_select", lib.rk_topk_select(
+        C.byref(geom.c()), _dev(weights, torch.float32, "weights"), weights.shape[2],
+        _dev(seq_lens, torch.int32, "seq_lens", (B,)), int(max_len), int(k), int(pool_w), int(agg),
+        _dev(idx, torch.int32, "idx", (B, Hkv, k)),
+        _dev(sel_scores, torch.float32, "sel_scores", (B, Hkv, k), optional=True),
+        _dev(pred, torch.int32, "pred", (B,), optional=True), int(pred_val),
+        workspace.ptr, workspace.nbytes, _stream(stream)))
+
+
+def rk_gather_small_kv(geom: Geom, K, V, idx, k: int, small_K, small_V, pred=None, pred_val: int = 0,
+                       stream=None) -> None:
+    B, Hkv = geom.batch, geom.n_kv_heads
+    _check("rk_gather_small_kv", lib.rk_gather_small_kv(
+        C.byref(geom.c()), _kv(geom, K, V, "full"), _dev(idx, torch.int32, "idx", (B, Hkv, k)), int(k),
+        _kv(geom, small_K, small_V, "small", min_rows=k),
+        _dev(pred, torch.int32, "pred", (B,), optional=True), int(pred_val), _stream(stream)))
+
+
+def rk_partial_attn(geom: Geom, q, small_K, small_V, n_sel: int, K, V, tail_start, seq_lens,
+                    max_recent: int, out, pred=None, pred_val: int = 0, workspace: Workspace = None,
+                    stream=None) -> None:
+    B, Hq, D = geom.batch, geom.n_q_heads, geom.head_dim
+    _check("rk_partial_attn", lib.rk_partial_attn(
+        C.byref(geom.c()), _dev(q, torch.bfloat16, "q", (B, Hq, D)),
+        _kv(geom, small_K, small_V, "small", min_rows=n_sel), int(n_sel), _kv(geom, K, V, "full"),
+        _dev(tail_start, torch.int32, "tail_start", (B,)), _dev(seq_lens, torch.int32, "seq_lens", (B,)),
+        int(max_recent), _dev(out, torch.bfloat16, "out", (B, Hq, D)),
+        _dev(pred, torch.int32, "pred", (B,), optional=True), int(pred_val),
+        workspace.ptr, workspace.nbytes, _stream(stream)))
+
+
+def rk_query_sim(geom: Geom, q, q_ref, threshold: float, force_full: bool, sim, need_full, stream=None) -> None:
+    B, Hq, D = geom.batch, geom.n_q_heads, geom.head_dim
+    _check("rk_query_sim", lib.rk_query_sim(
+        C.byref(geom.c()), _dev(q, torch.bfloat16, "q", (B, Hq, D)), _dev(q_ref, torch.float32, "q_ref", (B, D)),
+        float(threshold), 1 if force_full else 0, _dev(sim, torch.float32, "sim", (B,)),
+        _dev(need_full, torch.int32, "need_full", (B,)), _stream(stream)))
+
+
+def rk_mark_refresh(geom: Geom, seq_lens, tail_start, pred=None, pred_val: int = 0, stream=None) -> None:
+    B = geom.batch
+    _check("rk_mark_refresh", lib.rk_mark_refresh(
+        C.byref(geom.c()), _dev(seq_lens, torch.int32, "seq_lens", (B,)),
+        _dev(tail_start, torch.int32, "tail_start", (B,)),
+        _dev(pred, torch.int32, "pred", (B,), optional=True), int(pred_val), _stream(stream)))

@@ -1,0 +1,53 @@
+// Entry points that launch no compute: version, status strings, workspace sizing and set-up.
+#include "rk_internal.h"
+
+using namespace rk;
+
+extern "C" int rk_version(void) { return 100; }   // 0.1.0
+
+extern "C" const char* rk_status_string(int status) {
+    switch (status) {
+        case RK_OK: return "ok";
+        case RK_ERR_INVALID_ARG: return "invalid argument";
+        case RK_ERR_UNSUPPORTED: return "unsupported configuration";
+        case RK_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+        case RK_ERR_HIP: return "HIP runtime error";
+        default: return "unknown status";
+    }
+}
+
+extern "C" size_t rk_workspace_bytes(const rk_geom* geom, int32_t max_len, int32_t max_k) {
+    if (check_geom(geom) != RK_OK || max_len <= 0 || max_k < 0) return 0;
+    return carve(geom, max_len, max_k, nullptr).total;
+}
+
+namespace rk {
+// A fill kernel instead of hipMemsetAsync, so that the call can sit inside a captured graph.
+__global__ void zero_words_kernel(int32_t* p, size_t n) {
+    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+__global__ void mark_refresh_kernel(const int32_t* seq_lens, int32_t* tail_start, int32_t batch,
+                                    const int32_t* pred, int32_t pred_val) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b < batch && (pred == nullptr || pred[b] == pred_val)) tail_start[b] = seq_lens[b];
+}
+}  // namespace rk
+
+extern "C" int rk_mark_refresh(const rk_geom* geom, const int32_t* seq_lens, int32_t* tail_start,
+                               const int32_t* pred, int32_t pred_val, void* stream) {
+    if (check_geom(geom) != RK_OK || !seq_lens || !tail_start) return RK_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(mark_refresh_kernel, dim3((geom->batch + 63) / 64), dim3(64), 0, (hipStream_t)stream,
+                       seq_lens, tail_start, geom->batch, pred, pred_val);
+    return launch_status();
+}
+
+extern "C" int rk_workspace_init(const rk_geom* geom, void* workspace, size_t workspace_bytes, void* stream) {
+    if (check_geom(geom) != RK_OK) return RK_ERR_INVALID_ARG;
+    if (!workspace || ((uintptr_t)workspace & 255u) != 0) return RK_ERR_WORKSPACE;
+    const size_t n = (size_t)geom->batch * geom->n_kv_heads;     // one arrival counter each
+    if (workspace_bytes < align_up(n * sizeof(int32_t), 256)) return RK_ERR_WORKSPACE;
+    hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+                       (int32_t*)workspace, n);
+    return launch_status();
+}

@@ -1,0 +1,457 @@
+// Split-K decode attention for gfx950: rk_full_attn and rk_partial_attn.
+//
+// One workgroup reduces a chunk of KV rows of one (sequence, KV head) for all G query heads
+// of the GQA group, so every K/V byte is read from HBM once.  The workgroup that arrives
+// last for a (sequence, KV head) merges the partial results and writes the output.
+//
+// Data path per wavefront and iteration (ROWS = 16 * TILES rows):
+//   K rows  -> registers in MFMA operand layout (16-byte loads, no LDS)
+//   S = Q K^T on the matrix cores: v_mfma_f32_16x16x32_bf16, M = query heads (padded to 16),
+//             N = 16 rows, contraction over head_dim in 4 steps
+//   softmax bookkeeping (running max / sum) on the lanes that hold S
+//   P (and the raw scores when they are returned) cross to the V layout through LDS
+//   O += P V on the vector ALU: each lane owns 8 consecutive dims of one row in four,
+//             V rows loaded with fully coalesced 16-byte loads
+#include "rk_internal.h"
+#include "rk_device.h"
+
+namespace rk {
+
+struct AttnParams {
+    const uint16_t* q;                 // bf16 [B, Hq, 128]
+    const uint16_t* k1; const uint16_t* v1; int64_t s1_b, s1_h;   // small cache (TWO_SEG only)
+    const uint16_t* k2; const uint16_t* v2; int64_t s2_b, s2_h;   // full cache
+    const int32_t* tail_start;         // TWO_SEG only
+    const int32_t* seq_lens;
+    int32_t n_sel;                     // rows taken from the small cache (TWO_SEG only)
+    int32_t max_rows2;                 // host bound on the rows taken from the full cache
+    int32_t cap1, cap2;                // rows allocated in the small / full cache
+    int32_t chunk;                     // rows per workgroup
+    int32_t Hq, Hkv;
+    float scale;
+    uint16_t* out;                     // bf16 [B, Hq, 128]
+    float* weights; int64_t w_stride;  // raw scores go here first (EMIT only)
+    float* lse;                        // fp32 [B, Hq], never NULL here
+    const int32_t* pred; int32_t pred_val;
+    int32_t* counters; float* part_ml; float* part_o; int32_t max_chunks;
+};
+
+// Merge of the partial results of one (sequence, KV head); run by one whole workgroup.
+//   M = max_c m_c;  L = sum_c e^{m_c - M} l_c;  out = sum_c e^{m_c - M} o_c / L;  lse = M + ln L
+template <int G, int NW>
+__device__ void merge_partials(const AttnParams& p, int b, int g, int nchunks, float* sW, float* sRed,
+                               float* sM, float* sL) {
+    constexpr int NT = NW * 64;
+    const int tid = threadIdx.x;
+    const int64_t bg = (int64_t)b * p.Hkv + g;
+    const float* ml = p.part_ml + bg * kMaxChunks * G * 2;
+    const float* po = p.part_o + bg * p.max_chunks * G * kD;
+#pragma unroll
+    for (int gi = 0; gi < G; ++gi) {
+        float mx = -INFINITY;
+        for (int c = tid; c < nchunks; c += NT) mx = fmaxf(mx, ml[(c * G + gi) * 2]);
+        mx = block_max<NW>(mx, sRed);
+        float ls = 0.f;
+        for (int c = tid; c < nchunks; c += NT) {
+            const float mc = ml[(c * G + gi) * 2];
+            const float wgt = (mc == -INFINITY) ? 0.f : fast_exp2((mc - mx) * kLog2e);
+            sW[c * G + gi] = wgt;
+            ls += wgt * ml[(c * G + gi) * 2 + 1];
+        }
+        ls = block_sum<NW>(ls, sRed);
+        if (tid == 0) { sM[gi] = mx; sL[gi] = ls; }
+    }
+    __syncthreads();
+    for (int e = tid; e < G * kD; e += NT) {
+        const int gi = e / kD;
+        float acc = 0.f;
+#pragma unroll 4
+        for (int c = 0; c < nchunks; ++c) acc += sW[c * G + gi] * po[(int64_t)c * G * kD + e];
+        const float L = sL[gi];
+        const float o = L > 0.f ? acc / L : 0.f;
+        p.out[((int64_t)b * p.Hq + g * G) * kD + e] = f32_to_bf16(o);
+    }
+    if (tid < G) {
+        const float L = sL[tid];
+        p.lse[(int64_t)b * p.Hq + g * G + tid] = L > 0.f ? sM[tid] + logf(L) : -INFINITY;
+    }
+}
+
+template <int G, int NW, int TILES, bool EMIT, bool TWO_SEG>
+__global__ __launch_bounds__(NW * 64)
+void attn_split_kernel(const AttnParams p) {
+    constexpr int GP = (G + 3) / 4 * 4;      // heads padded to whole MFMA accumulator registers
+    constexpr int NC = GP / 4;               // 16-lane groups whose accumulators hold real heads
+    constexpr int ROWS = TILES * 16;         // rows per wavefront per iteration
+    constexpr int NV = ROWS / 4;             // V loads per lane per iteration
+    constexpr int RG = (G <= 4) ? 4 : 2;     // row groups of a wavefront kept apart in LDS
+    constexpr int NT = NW * 64;
+
+    const int c = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+    if (p.pred != nullptr && p.pred[b] != p.pred_val) return;
+
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int n16 = lane & 15, c4 = lane >> 4;     // S layout: row n16, heads 4*c4 .. 4*c4+3
+    const int db = lane & 15, rg = lane >> 4;      // V layout: dims 8*db .. 8*db+7, rows = rg mod 4
+
+    // ---- the row list of this (sequence, KV head) ----
+    // (device-side lengths are clamped to the allocated rows: no access leaves the caches)
+    const int len = min(p.seq_lens[b], p.cap2);
+    int n1 = 0, start2 = 0;
+    if (TWO_SEG) {
+        const int t0 = min(max(p.tail_start[b], 0), p.cap2);
+        n1 = min(min(p.n_sel, t0), p.cap1);
+        n1 = max(n1, 0);
+        start2 = t0;
+    }
+    const int n2 = min(max(len - start2, 0), p.max_rows2);
+    const int n = n1 + n2;
+    const int nchunks = max(1, (n + p.chunk - 1) / p.chunk);
+    if (c >= nchunks) return;
+    const int row0 = c * p.chunk;
+    const int row1 = min(n, row0 + p.chunk);
+
+    const uint16_t* kb1 = nullptr; const uint16_t* vb1 = nullptr;
+    if (TWO_SEG) {
+        kb1 = p.k1 + (int64_t)b * p.s1_b + (int64_t)g * p.s1_h;
+        vb1 = p.v1 + (int64_t)b * p.s1_b + (int64_t)g * p.s1_h;
+    }
+    // row r of the list lives at base2 + (start2 + r - n1) * 128 once r >= n1
+    const uint16_t* kb2 = p.k2 + (int64_t)b * p.s2_b + (int64_t)g * p.s2_h + (int64_t)(start2 - n1) * kD;
+    const uint16_t* vb2 = p.v2 + (int64_t)b * p.s2_b + (int64_t)g * p.s2_h + (int64_t)(start2 - n1) * kD;
+
+    __shared__ __attribute__((aligned(16))) float sP[NW][ROWS][GP];
+    __shared__ __attribute__((aligned(16))) float sS[EMIT ? NW : 1][EMIT ? ROWS : 1][GP];
+    __shared__ __attribute__((aligned(16))) float sAlpha[NW][GP];
+    __shared__ __attribute__((aligned(16))) float sMw[NW][GP];
+    __shared__ __attribute__((aligned(16))) float sLw[NW][GP];
+    __shared__ __attribute__((aligned(16))) float sO[NW * RG][G][kD];   // reused by the merge
+    __shared__ float sRed[NW];
+    __shared__ float sMf[GP], sLf[GP];
+    __shared__ int sTicket;
+    static_assert(sizeof(float) * NW * RG * G * kD >= sizeof(float) * kMaxChunks * G,
+                  "merge weights must fit in the output staging buffer");
+
+    // ---- Q as the A operand: lane (n16, c4) holds head n16, dims 8*(4*kk + c4) .. +7 ----
+    bf16x8 qa[4];
+    {
+        const uint16_t* qrow = p.q + ((int64_t)b * p.Hq + (int64_t)g * G + (n16 < G ? n16 : 0)) * kD;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            uint4 u = *reinterpret_cast<const uint4*>(qrow + (kk * 4 + c4) * 8);
+            if (n16 >= G) u = make_uint4(0, 0, 0, 0);
+            qa[kk] = __builtin_bit_cast(bf16x8, u);
+        }
+    }
+
+    float m_run[4], l_run[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { m_run[i] = -INFINITY; l_run[i] = 0.f; }
+    float o[G][8];
+#pragma unroll
+    for (int gi = 0; gi < G; ++gi)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[gi][e] = 0.f;
+
+    for (int r = row0 + w * ROWS; r < row1; r += NW * ROWS) {
+        // ---- loads: rows past the end of the chunk re-read its last row (masked below) ----
+        uint4 kreg[TILES][4];
+#pragma unroll
+        for (int t = 0; t < TILES; ++t) {
+            const int row = min(r + t * 16 + n16, row1 - 1);
+            const uint16_t* base = (TWO_SEG && row < n1) ? kb1 : kb2;
+            const uint16_t* rp = base + (int64_t)row * kD + c4 * 8;
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) kreg[t][kk] = *reinterpret_cast<const uint4*>(rp + kk * 32);
+        }
+        uint4 vreg[NV];
+#pragma unroll
+        for (int jj = 0; jj < NV; ++jj) {
+            const int row = min(r + jj * 4 + rg, row1 - 1);
+            const uint16_t* base = (TWO_SEG && row < n1) ? vb1 : vb2;
+            vreg[jj] = *reinterpret_cast<const uint4*>(base + (int64_t)row * kD + db * 8);
+        }
+
+        // ---- S = Q K^T: lane (n16, c4) gets heads 4*c4+i of row r + 16 t + n16 ----
+        float s[TILES][4];
+#pragma unroll
+        for (int t = 0; t < TILES; ++t) {
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[kk], __builtin_bit_cast(bf16x8, kreg[t][kk]),
+                                                              acc, 0, 0, 0);
+            const bool valid = (r + t * 16 + n16) < row1;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) s[t][i] = valid ? acc[i] * p.scale : -INFINITY;
+        }
+
+        // ---- running softmax statistics of this wavefront ----
+        float alpha[4], pr[TILES][4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float mx = s[0][i];
+#pragma unroll
+            for (int t = 1; t < TILES; ++t) mx = fmaxf(mx, s[t][i]);
+            mx = row16_max(mx);
+            const float m_new = fmaxf(m_run[i], mx);       // finite: row r is always valid
+            alpha[i] = fast_exp2((m_run[i] - m_new) * kLog2e);
+            m_run[i] = m_new;
+            float ps = 0.f;
+#pragma unroll
+            for (int t = 0; t < TILES; ++t) {
+                pr[t][i] = fast_exp2((s[t][i] - m_new) * kLog2e);
+                ps += pr[t][i];
+            }
+            l_run[i] = l_run[i] * alpha[i] + ps;            // per-lane share, summed at the end
+        }
+        if (c4 < NC) {
+#pragma unroll
+            for (int t = 0; t < TILES; ++t) {
+                *reinterpret_cast<float4*>(&sP[w][t * 16 + n16][c4 * 4]) =
+                    make_float4(pr[t][0], pr[t][1], pr[t][2], pr[t][3]);
+                if (EMIT)
+                    *reinterpret_cast<float4*>(&sS[w][t * 16 + n16][c4 * 4]) =
+                        make_float4(s[t][0], s[t][1], s[t][2], s[t][3]);
+            }
+            if (n16 == 0)
+                *reinterpret_cast<float4*>(&sAlpha[w][c4 * 4]) = make_float4(alpha[0], alpha[1], alpha[2], alpha[3]);
+        }
+        wave_lds_sync();
+
+        // ---- raw scores out, one row per lane: 256-byte stores per head ----
+        if (EMIT) {
+            if (lane < ROWS && r + lane < row1) {
+                float sv[GP];
+#pragma unroll
+                for (int q4 = 0; q4 < NC; ++q4) {
+                    const float4 t4 = *reinterpret_cast<const float4*>(&sS[w][lane][q4 * 4]);
+                    sv[q4 * 4 + 0] = t4.x; sv[q4 * 4 + 1] = t4.y; sv[q4 * 4 + 2] = t4.z; sv[q4 * 4 + 3] = t4.w;
+                }
+                float* wrow = p.weights + ((int64_t)b * p.Hq + (int64_t)g * G) * p.w_stride + r + lane;
+#pragma unroll
+                for (int gi = 0; gi < G; ++gi) wrow[(int64_t)gi * p.w_stride] = sv[gi];
+            }
+        }
+
+        // ---- O = alpha O + P V ----
+        {
+            float al[GP];
+#pragma unroll
+            for (int q4 = 0; q4 < NC; ++q4) {
+                const float4 t4 = *reinterpret_cast<const float4*>(&sAlpha[w][q4 * 4]);
+                al[q4 * 4 + 0] = t4.x; al[q4 * 4 + 1] = t4.y; al[q4 * 4 + 2] = t4.z; al[q4 * 4 + 3] = t4.w;
+            }
+#pragma unroll
+            for (int gi = 0; gi < G; ++gi)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[gi][e] *= al[gi];
+        }
+#pragma unroll
+        for (int jj = 0; jj < NV; ++jj) {
+            float pv[GP];
+#pragma unroll
+            for (int q4 = 0; q4 < NC; ++q4) {
+                const float4 t4 = *reinterpret_cast<const float4*>(&sP[w][jj * 4 + rg][q4 * 4]);
+                pv[q4 * 4 + 0] = t4.x; pv[q4 * 4 + 1] = t4.y; pv[q4 * 4 + 2] = t4.z; pv[q4 * 4 + 3] = t4.w;
+            }
+            const uint4 u = vreg[jj];
+            const float vf[8] = {bf16_lo(u.x), bf16_hi(u.x), bf16_lo(u.y), bf16_hi(u.y),
+                                 bf16_lo(u.z), bf16_hi(u.z), bf16_lo(u.w), bf16_hi(u.w)};
+#pragma unroll
+            for (int gi = 0; gi < G; ++gi)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) o[gi][e] = fmaf(pv[gi], vf[e], o[gi][e]);
+        }
+        wave_lds_sync();      // sP / sAlpha are rewritten by the next iteration
+    }
+
+    // ---- wavefront results to LDS ----
+#pragma unroll
+    for (int i = 0; i < 4; ++i) l_run[i] = row16_sum(l_run[i]);
+    if (c4 < NC && n16 == 0) {
+        *reinterpret_cast<float4*>(&sMw[w][c4 * 4]) = make_float4(m_run[0], m_run[1], m_run[2], m_run[3]);
+        *reinterpret_cast<float4*>(&sLw[w][c4 * 4]) = make_float4(l_run[0], l_run[1], l_run[2], l_run[3]);
+    }
+    if (RG == 2) {
+#pragma unroll
+        for (int gi = 0; gi < G; ++gi)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[gi][e] += __shfl_xor(o[gi][e], 32);
+    }
+    if (rg < RG) {
+#pragma unroll
+        for (int gi = 0; gi < G; ++gi) {
+            float4* dst = reinterpret_cast<float4*>(&sO[w * RG + rg][gi][db * 8]);
+            dst[0] = make_float4(o[gi][0], o[gi][1], o[gi][2], o[gi][3]);
+            dst[1] = make_float4(o[gi][4], o[gi][5], o[gi][6], o[gi][7]);
+        }
+    }
+    __syncthreads();
+
+    // ---- merge the NW wavefronts and publish the partial result of this chunk ----
+    const int64_t bg = (int64_t)b * p.Hkv + g;
+    float* ml = p.part_ml + (bg * kMaxChunks + c) * G * 2;
+    float* po = p.part_o + (bg * p.max_chunks + c) * G * kD;
+    for (int e = tid; e < G * kD; e += NT) {
+        const int gi = e / kD, d = e % kD;
+        float M = sMw[0][gi];
+#pragma unroll
+        for (int ww = 1; ww < NW; ++ww) M = fmaxf(M, sMw[ww][gi]);
+        float acc = 0.f, L = 0.f;
+#pragma unroll
+        for (int ww = 0; ww < NW; ++ww) {
+            const float mw = sMw[ww][gi];
+            const float sc = (mw == -INFINITY) ? 0.f : fast_exp2((mw - M) * kLog2e);
+            float part = 0.f;
+#pragma unroll
+            for (int rr = 0; rr < RG; ++rr) part += sO[ww * RG + rr][gi][d];
+            acc += sc * part;
+            L += sc * sLw[ww][gi];
+        }
+        po[e] = acc;
+        if (d == 0) { ml[gi * 2] = M; ml[gi * 2 + 1] = L; }
+    }
+
+    // ---- the workgroup that arrives last for (b, g) merges all chunks ----
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) sTicket = atomicAdd(&p.counters[bg], 1);
+    __syncthreads();
+    if (sTicket != nchunks - 1) return;
+    __threadfence();
+    merge_partials<G, NW>(p, b, g, nchunks, &sO[0][0][0], sRed, sMf, sLf);
+    if (tid == 0) p.counters[bg] = 0;      // ready for the next call
+}
+
+// weights[b,h,j] = exp(s[b,h,j] - lse[b,h]) in place, j < seq_lens[b].
+__global__ __launch_bounds__(256)
+void normalise_weights_kernel(float* weights, int64_t w_stride, const float* lse, const int32_t* seq_lens,
+                              int32_t max_len, int32_t Hq, const int32_t* pred, int32_t pred_val) {
+    const int b = blockIdx.z, h = blockIdx.y;
+    if (pred != nullptr && pred[b] != pred_val) return;
+    const int len = min(seq_lens[b], max_len);
+    const float l = lse[(int64_t)b * Hq + h];
+    float* row = weights + ((int64_t)b * Hq + h) * w_stride;
+    const int j0 = blockIdx.x * 1024 + threadIdx.x;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int j = j0 + i * 256;
+        if (j < len) row[j] = expf(row[j] - l);
+    }
+}
+
+template <int G, bool EMIT, bool TWO_SEG>
+static int launch_split_g(const AttnParams& p, int batch, int nchunk_grid, hipStream_t st) {
+    dim3 grid(nchunk_grid, p.Hkv, batch);
+    if (p.chunk >= 256) {
+        hipLaunchKernelGGL((attn_split_kernel<G, 4, 4, EMIT, TWO_SEG>), grid, dim3(256), 0, st, p);
+    } else if (p.chunk >= 128) {
+        hipLaunchKernelGGL((attn_split_kernel<G, 4, 2, EMIT, TWO_SEG>), grid, dim3(256), 0, st, p);
+    } else {
+        hipLaunchKernelGGL((attn_split_kernel<G, 4, 1, EMIT, TWO_SEG>), grid, dim3(256), 0, st, p);
+    }
+    return launch_status();
+}
+
+template <bool EMIT, bool TWO_SEG>
+static int launch_split(const AttnParams& p, int batch, int G, int nchunk_grid, hipStream_t st) {
+    switch (G) {
+        case 1: return launch_split_g<1, EMIT, TWO_SEG>(p, batch, nchunk_grid, st);
+        case 2: return launch_split_g<2, EMIT, TWO_SEG>(p, batch, nchunk_grid, st);
+        case 3: return launch_split_g<3, EMIT, TWO_SEG>(p, batch, nchunk_grid, st);
+        case 4: return launch_split_g<4, EMIT, TWO_SEG>(p, batch, nchunk_grid, st);
+        case 5: return launch_split_g<5, EMIT, TWO_SEG>(p, batch, nchunk_grid, st);
+        case 6: return launch_split_g<6, EMIT, TWO_SEG>(p, batch, nchunk_grid, st);
+        case 7: return launch_split_g<7, EMIT, TWO_SEG>(p, batch, nchunk_grid, st);
+        case 8: return launch_split_g<8, EMIT, TWO_SEG>(p, batch, nchunk_grid, st);
+        default: return RK_ERR_UNSUPPORTED;
+    }
+}
+
+}  // namespace rk
+
+using namespace rk;
+
+extern "C" int rk_full_attn(const rk_geom* geom, const void* q, rk_kv full,
+                            const int32_t* seq_lens, int32_t max_len,
+                            void* out, float* weights, int64_t w_stride, float* lse,
+                            const int32_t* pred, int32_t pred_val,
+                            void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_geom(geom);
+    if (rc != RK_OK) return rc;
+    if (!q || !out || !seq_lens || max_len <= 0) return RK_ERR_INVALID_ARG;
+    if (!aligned16(q) || ((uintptr_t)out & 1u)) return RK_ERR_INVALID_ARG;
+    if ((rc = check_kv(full)) != RK_OK) return rc;
+    if (weights && (w_stride < max_len || ((uintptr_t)weights & 3u))) return RK_ERR_INVALID_ARG;
+    Workspace ws;
+    if ((rc = check_workspace(geom, max_len, 0, workspace, workspace_bytes, &ws)) != RK_OK) return rc;
+
+    const int G = geom->n_q_heads / geom->n_kv_heads;
+    AttnParams p{};
+    p.q = (const uint16_t*)q;
+    p.k2 = (const uint16_t*)full.k; p.v2 = (const uint16_t*)full.v;
+    p.s2_b = full.stride_b; p.s2_h = full.stride_h;
+    p.seq_lens = seq_lens;
+    p.n_sel = 0;
+    p.max_rows2 = max_len;
+    p.cap1 = 0; p.cap2 = (int32_t)full.capacity;
+    p.chunk = attn_chunk_rows(max_len, (int64_t)geom->batch * geom->n_kv_heads);
+    p.Hq = geom->n_q_heads; p.Hkv = geom->n_kv_heads;
+    p.scale = geom->scale;
+    p.out = (uint16_t*)out;
+    p.weights = weights; p.w_stride = w_stride;
+    p.lse = lse ? lse : ws.lse;
+    p.pred = pred; p.pred_val = pred_val;
+    p.counters = ws.counters; p.part_ml = ws.part_ml; p.part_o = ws.part_o; p.max_chunks = ws.max_chunks;
+    const int nchunk_grid = (max_len + p.chunk - 1) / p.chunk;
+    hipStream_t st = (hipStream_t)stream;
+    if (weights) {
+        rc = launch_split<true, false>(p, geom->batch, G, nchunk_grid, st);
+        if (rc != RK_OK) return rc;
+        dim3 grid((max_len + 1023) / 1024, geom->n_q_heads, geom->batch);
+        hipLaunchKernelGGL(normalise_weights_kernel, grid, dim3(256), 0, st, weights, w_stride, p.lse, seq_lens,
+                           max_len, geom->n_q_heads, pred, pred_val);
+        return launch_status();
+    }
+    return launch_split<false, false>(p, geom->batch, G, nchunk_grid, st);
+}
+
+extern "C" int rk_partial_attn(const rk_geom* geom, const void* q, rk_kv small, int32_t n_sel,
+                               rk_kv full, const int32_t* tail_start, const int32_t* seq_lens,
+                               int32_t max_recent, void* out,
+                               const int32_t* pred, int32_t pred_val,
+                               void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_geom(geom);
+    if (rc != RK_OK) return rc;
+    if (!q || !out || !seq_lens || !tail_start || n_sel < 0 || max_recent < 0) return RK_ERR_INVALID_ARG;
+    if (n_sel + (int64_t)max_recent <= 0 || n_sel + (int64_t)max_recent > INT32_MAX) return RK_ERR_INVALID_ARG;
+    if (!aligned16(q) || ((uintptr_t)out & 1u)) return RK_ERR_INVALID_ARG;
+    if ((rc = check_kv(full)) != RK_OK) return rc;
+    if (n_sel > 0 && (rc = check_kv(small)) != RK_OK) return rc;
+    const int max_rows = n_sel + max_recent;
+    Workspace ws;
+    if ((rc = check_workspace(geom, max_rows, 0, workspace, workspace_bytes, &ws)) != RK_OK) return rc;
+
+    const int G = geom->n_q_heads / geom->n_kv_heads;
+    AttnParams p{};
+    p.q = (const uint16_t*)q;
+    p.k1 = (const uint16_t*)small.k; p.v1 = (const uint16_t*)small.v;
+    p.s1_b = small.stride_b; p.s1_h = small.stride_h;
+    p.k2 = (const uint16_t*)full.k; p.v2 = (const uint16_t*)full.v;
+    p.s2_b = full.stride_b; p.s2_h = full.stride_h;
+    p.tail_start = tail_start;
+    p.seq_lens = seq_lens;
+    p.n_sel = n_sel;
+    p.max_rows2 = max_recent;
+    p.cap1 = n_sel > 0 ? (int32_t)small.capacity : 0; p.cap2 = (int32_t)full.capacity;
+    p.chunk = attn_chunk_rows(max_rows, (int64_t)geom->batch * geom->n_kv_heads);
+    p.Hq = geom->n_q_heads; p.Hkv = geom->n_kv_heads;
+    p.scale = geom->scale;
+    p.out = (uint16_t*)out;
+    p.lse = ws.lse;
+    p.pred = pred; p.pred_val = pred_val;
+    p.counters = ws.counters; p.part_ml = ws.part_ml; p.part_o = ws.part_o; p.max_chunks = ws.max_chunks;
+    const int nchunk_grid = (max_rows + p.chunk - 1) / p.chunk;
+    return launch_split<false, true>(p, geom->batch, G, nchunk_grid, (hipStream_t)stream);
+}

@@ -1,0 +1,100 @@
+// Shared host-side plumbing of the library: workspace layout, argument checks, launch checks.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "../../include/refreshkv.h"
+
+namespace rk {
+
+constexpr int kD = RK_HEAD_DIM;          // head_dim
+constexpr int kMinChunk = 64;            // smallest number of KV rows one workgroup reduces
+constexpr int kMaxChunks = 512;          // most partial results one (sequence, KV head) produces
+
+// Rows per workgroup of the split attention kernels: a power of two in [64, 4096], chosen so
+// that a launch has enough workgroups to fill the chip but no (sequence, KV head) produces
+// more than kMaxChunks partial results.
+static inline int attn_chunk_rows(int64_t max_rows, int64_t n_problems) {
+    const int64_t target_wgs = 1024;
+    int64_t chunk = kMinChunk;
+    while (chunk < 4096 && (max_rows + chunk - 1) / chunk * n_problems > target_wgs) chunk *= 2;
+    while ((max_rows + chunk - 1) / chunk > kMaxChunks) chunk *= 2;
+    return (int)chunk;
+}
+
+static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Device workspace, carved in this order (every region 256-byte aligned):
+//   counters  int32 [B*Hkv]                  arrival tickets of the split attention kernel
+//   lse       fp32  [B*Hq]                   log-sum-exp when the caller does not ask for it
+//   part_ml   fp32  [B*Hkv][kMaxChunks][G][2] running max and sum of every partial result
+//   part_o    fp32  [B*Hkv][nch][G][128]     unnormalised partial outputs
+//   pooled    fp32  [B*Hkv][max_len]         group-max, pooled scores of the selection
+struct Workspace {
+    int32_t* counters;
+    float* lse;
+    float* part_ml;
+    float* part_o;
+    float* pooled;
+    int max_chunks;       // nch above
+    size_t total;
+};
+
+static inline int max_chunks_for(int64_t max_len) {
+    int64_t n = (max_len + kMinChunk - 1) / kMinChunk;
+    if (n > kMaxChunks) n = kMaxChunks;
+    if (n < 1) n = 1;
+    return (int)n;
+}
+
+static inline Workspace carve(const rk_geom* g, int64_t max_len, int64_t /*max_k*/, void* base) {
+    Workspace w;
+    const size_t problems = (size_t)g->batch * g->n_kv_heads;
+    const size_t G = (size_t)(g->n_q_heads / g->n_kv_heads);
+    w.max_chunks = max_chunks_for(max_len);
+    char* p = (char*)base;
+    size_t off = 0;
+    w.counters = (int32_t*)(p + off); off += align_up(problems * sizeof(int32_t), 256);
+    w.lse = (float*)(p + off);        off += align_up((size_t)g->batch * g->n_q_heads * sizeof(float), 256);
+    w.part_ml = (float*)(p + off);    off += align_up(problems * kMaxChunks * G * 2 * sizeof(float), 256);
+    w.part_o = (float*)(p + off);     off += align_up(problems * w.max_chunks * G * kD * sizeof(float), 256);
+    w.pooled = (float*)(p + off);     off += align_up(problems * (size_t)(max_len > 0 ? max_len : 1) * sizeof(float), 256);
+    w.total = off;
+    return w;
+}
+
+static inline int check_geom(const rk_geom* g) {
+    if (!g) return RK_ERR_INVALID_ARG;
+    if (g->batch <= 0 || g->n_q_heads <= 0 || g->n_kv_heads <= 0) return RK_ERR_INVALID_ARG;
+    if (g->n_q_heads % g->n_kv_heads != 0) return RK_ERR_INVALID_ARG;
+    if (g->head_dim != kD) return RK_ERR_UNSUPPORTED;
+    if (g->n_q_heads / g->n_kv_heads > RK_MAX_GROUP) return RK_ERR_UNSUPPORTED;
+    if (g->batch > 65535 || g->n_kv_heads > 65535) return RK_ERR_UNSUPPORTED;
+    return RK_OK;
+}
+
+static inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+static inline int check_kv(const rk_kv& c) {
+    if (!c.k || !c.v) return RK_ERR_INVALID_ARG;
+    if (!aligned16(c.k) || !aligned16(c.v)) return RK_ERR_INVALID_ARG;
+    if (c.stride_b < 0 || c.stride_h < 0 || c.capacity <= 0 || c.capacity > INT32_MAX) return RK_ERR_INVALID_ARG;
+    if (c.stride_b % 8 != 0 || c.stride_h % 8 != 0) return RK_ERR_INVALID_ARG;
+    return RK_OK;
+}
+
+static inline int check_workspace(const rk_geom* g, int64_t max_len, int64_t max_k, void* ws,
+                                  size_t bytes, Workspace* out) {
+    if (!ws || ((uintptr_t)ws & 255u) != 0) return RK_ERR_WORKSPACE;
+    *out = carve(g, max_len, max_k, ws);
+    if (bytes < out->total) return RK_ERR_WORKSPACE;
+    return RK_OK;
+}
+
+static inline int launch_status() {
+    return hipGetLastError() == hipSuccess ? RK_OK : RK_ERR_HIP;
+}
+
+}  // namespace rk

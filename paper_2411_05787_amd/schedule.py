@@ -1,0 +1,100 @@
+"""Host-side schedule of one RefreshKV attention layer (Section 2.2 of the paper).
+
+Only sequencing lives here: which of the library's calls are enqueued at step t.  Nothing is
+read back from the GPU; with the dynamic trigger both branches are enqueued and the device
+predicate written by ``rk_query_sim`` switches one of them off per sequence.
+
+State of a layer (all caller-visible tensors, so a run can be checkpointed and resumed):
+full cache K/V, seq_lens, small cache, idx, q_ref, tail_start, need_full.
+"""
+from __future__ import annotations
+
+from typing import Optional
+
+import torch
+
+from . import binding as rk
+
+
+class RefreshKVLayer:
+    def __init__(self, geom: rk.Geom, K: torch.Tensor, V: torch.Tensor, seq_lens: torch.Tensor,
+                 max_len: int, k_small: int, stride: int, pool_w: int = 7, dynamic: bool = False,
+                 threshold: float = 0.0, evict_lowest: bool = False,
+                 workspace: Optional[rk.Workspace] = None, weights: Optional[torch.Tensor] = None):
+        """K, V: bf16 [B, Hkv, capacity, D] holding seq_lens[b] rows; seq_lens int32 [B] on the
+        GPU; max_len: host upper bound of seq_lens now (kept up to date by :meth:`advance`)."""
+        dev = K.device
+        B, Hq, Hkv, D = geom.batch, geom.n_q_heads, geom.n_kv_heads, geom.head_dim
+        self.geom, self.K, self.V, self.seq_lens = geom, K, V, seq_lens
+        self.capacity = K.shape[2]
+        self.max_len = int(max_len)
+        self.k_small, self.stride, self.pool_w = int(k_small), int(stride), int(pool_w)
+        self.dynamic, self.threshold, self.evict_lowest = bool(dynamic), float(threshold), bool(evict_lowest)
+        self.ws = workspace if workspace is not None else rk.Workspace(geom, self.capacity, k_small, device=dev)
+        self.weights = weights if weights is not None else torch.empty(B, Hq, self.capacity, dtype=torch.float32, device=dev)
+        self.small_K = torch.zeros(B, Hkv, k_small, D, dtype=torch.bfloat16, device=dev)
+        self.small_V = torch.zeros(B, Hkv, k_small, D, dtype=torch.bfloat16, device=dev)
+        self.idx = torch.full((B, Hkv, k_small), -1, dtype=torch.int32, device=dev)
+        self.q_ref = torch.zeros(B, D, dtype=torch.float32, device=dev)
+        self.sim = torch.zeros(B, dtype=torch.float32, device=dev)
+        self.need_full = torch.zeros(B, dtype=torch.int32, device=dev)
+        self.tail_start = seq_lens.clone()
+        self.out = torch.empty(B, Hq, D, dtype=torch.bfloat16, device=dev)
+        self.recent_bound = 0          # host bound of seq_lens - tail_start
+
+    # -- cache growth is the caller's copy; this keeps the host bounds in step with it
+    def append(self, k_row: torch.Tensor, v_row: torch.Tensor, shared_lens: bool = False) -> None:
+        """Write the new token's (k, v) rows [B, Hkv, D] at position seq_lens[b] and grow.
+
+        shared_lens: seq_lens is shared with other layers and is incremented elsewhere."""
+        if self.max_len + 1 > self.capacity:
+            raise ValueError("KV cache capacity exceeded")
+        B, Hkv = self.geom.batch, self.geom.n_kv_heads
+        pos = self.seq_lens.to(torch.int64)[:, None, None, None].expand(B, Hkv, 1, self.geom.head_dim)
+        self.K.scatter_(2, pos, k_row[:, :, None, :])
+        self.V.scatter_(2, pos, v_row[:, :, None, :])
+        if not shared_lens:
+            self.seq_lens += 1
+        self.advance()
+
+    def advance(self) -> None:
+        self.max_len += 1
+        self.recent_bound += 1
+
+    def _full(self, q, out, pred=None, stream=None) -> None:
+        g = self.geom
+        rk.rk_full_attn(g, q, self.K, self.V, self.seq_lens, self.max_len, out, weights=self.weights,
+                        pred=pred, pred_val=1, workspace=self.ws, stream=stream)
+        rk.rk_topk_select(g, self.weights, self.seq_lens, self.max_len, self.k_small, self.pool_w, self.idx,
+                          pred=pred, pred_val=1, workspace=self.ws, stream=stream)
+        rk.rk_gather_small_kv(g, self.K, self.V, self.idx, self.k_small, self.small_K, self.small_V,
+                              pred=pred, pred_val=1, stream=stream)
+        rk.rk_mark_refresh(g, self.seq_lens, self.tail_start, pred=pred, pred_val=1, stream=stream)
+
+    def _partial(self, q, out, pred=None, stream=None) -> None:
+        if self.evict_lowest and not self.dynamic:
+            n_sel = max(self.k_small - self.recent_bound, 0)      # exact: all sequences refreshed together
+        else:
+            n_sel = self.k_small
+        rk.rk_partial_attn(self.geom, q, self.small_K, self.small_V, n_sel, self.K, self.V, self.tail_start,
+                           self.seq_lens, max(self.recent_bound, 1), out, pred=pred, pred_val=0,
+                           workspace=self.ws, stream=stream)
+
+    def step(self, t: int, q: torch.Tensor, out: Optional[torch.Tensor] = None, stream=None) -> str:
+        """Attention of decode step t (t = 0: the prefill-equivalent initialisation).
+
+        Returns which calls were enqueued: "full", "partial", or "both" (dynamic test step)."""
+        out = self.out if out is None else out
+        scheduled = t == 0 or (self.stride > 0 and t % self.stride == 0)
+        if t == 0 or (scheduled and not self.dynamic):
+            rk.rk_query_sim(self.geom, q, self.q_ref, self.threshold, True, self.sim, self.need_full, stream=stream)
+            self._full(q, out, stream=stream)
+            self.recent_bound = 0
+            return "full"
+        if scheduled and self.dynamic:
+            rk.rk_query_sim(self.geom, q, self.q_ref, self.threshold, False, self.sim, self.need_full, stream=stream)
+            self._partial(q, out, pred=self.need_full, stream=stream)
+            self._full(q, out, pred=self.need_full, stream=stream)
+            return "both"
+        self._partial(q, out, stream=stream)
+        return "partial"

@@ -1,0 +1,113 @@
+"""The C-ABI library loads, exports what include/refreshkv.h declares, and rejects bad
+arguments on the host before anything is launched (no GPU needed)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def rk():
+    import paper_2411_05787_amd as lib      # raises when the library is not built
+    return lib
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "refreshkv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(rk_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_and_binding_agree(rk):
+    names = declared_functions()
+    assert "rk_full_attn" in names and "rk_topk_select" in names and "rk_gather_small_kv" in names
+    assert "rk_partial_attn" in names and "rk_query_sim" in names
+    assert sorted(rk.EXPORTS) == names
+
+
+def test_every_declared_symbol_is_exported(rk):
+    lib = C.CDLL(rk.LIB_PATH)
+    for name in declared_functions():
+        assert hasattr(lib, name), name
+
+
+def test_version_and_status_strings(rk):
+    assert rk.version() >= 100
+    assert rk.status_string(0) == "ok"
+    for code in (-1, -2, -3, -4):
+        assert rk.status_string(code) not in ("ok", "unknown status")
+    assert rk.status_string(-99) == "unknown status"
+
+
+def test_workspace_bytes_grows_and_rejects(rk):
+    g = rk.Geom(1, 32, 8, 128, 0.0884)
+    a, b = rk.workspace_bytes(g, 2048, 256), rk.workspace_bytes(g, 32768, 2048)
+    assert 0 < a < b and a % 256 == 0 and b % 256 == 0
+    for bad in (rk.Geom(1, 32, 8, 64, 1.0), rk.Geom(1, 30, 8, 128, 1.0), rk.Geom(0, 32, 8, 128, 1.0),
+                rk.Geom(1, 32, 2, 128, 1.0)):
+        with pytest.raises(rk.RkError):
+            rk.workspace_bytes(bad, 1024, 64)
+
+
+def test_host_side_argument_checks_return_before_any_launch(rk):
+    """Raw ctypes calls with pointers that are never dereferenced: every one must be refused."""
+    from paper_2411_05787_amd.binding import _Geom, _Kv
+    lib = rk.lib
+    g = _Geom(1, 32, 8, 128, 0.0884)
+    fake = 0x10000                                # aligned, non-null, never touched
+    kv = _Kv(fake, fake, 8 * 4096 * 128, 4096 * 128, 4096)
+    ws_bytes = rk.workspace_bytes(rk.Geom(1, 32, 8, 128, 0.0884), 4096, 256)
+    full = lambda **kw: lib.rk_full_attn(C.byref(kw.get("g", g)), kw.get("q", fake), kw.get("kv", kv),
+                                         kw.get("sl", fake), kw.get("max_len", 4096), fake, kw.get("w", None),
+                                         kw.get("ws_stride", 0), None, None, 0, kw.get("ws", fake + 0x100000 - 0x10000),
+                                         kw.get("wsb", ws_bytes), None)
+    assert full(g=_Geom(1, 32, 8, 64, 1.0)) == -2                       # head_dim
+    assert full(g=_Geom(1, 72, 8, 128, 1.0)) == -2                      # group of 9
+    assert full(g=_Geom(1, 33, 8, 128, 1.0)) == -1                      # heads do not divide
+    assert full(q=None) == -1
+    assert full(sl=None) == -1
+    assert full(max_len=0) == -1
+    assert full(kv=_Kv(fake + 2, fake, 0, 0, 4096)) == -1                     # misaligned K
+    assert full(kv=_Kv(fake, fake, 12, 128, 4096)) == -1                      # stride not a multiple of 8
+    assert full(kv=_Kv(fake, fake, 0, 0, 0)) == -1                      # no rows allocated
+    assert full(w=fake, ws_stride=100) == -1                            # weights rows shorter than max_len
+    assert full(ws=None) == -3
+    assert full(ws=fake + 4) == -3                                      # misaligned workspace
+    assert full(wsb=1024) == -3                                         # too small
+    topk = lambda **kw: lib.rk_topk_select(C.byref(g), fake, 4096, fake, 4096, kw.get("k", 256), kw.get("pool", 7),
+                                           kw.get("agg", 0), fake, None, None, 0, 0x100000, ws_bytes, None)
+    assert topk(k=0) == -1
+    assert topk(k=16385) == -2
+    assert topk(pool=4) == -1
+    assert topk(pool=65) == -2
+    assert topk(agg=1) == -2
+    assert lib.rk_gather_small_kv(C.byref(g), kv, None, 16, kv, None, 0, None) == -1
+    assert lib.rk_gather_small_kv(C.byref(g), kv, fake, 0, kv, None, 0, None) == -1
+    assert lib.rk_partial_attn(C.byref(g), fake, kv, -1, kv, fake, fake, 4, fake, None, 0, 0x100000, ws_bytes, None) == -1
+    assert lib.rk_partial_attn(C.byref(g), fake, kv, 0, kv, fake, fake, 0, fake, None, 0, 0x100000, ws_bytes, None) == -1
+    assert lib.rk_partial_attn(C.byref(g), fake, kv, 16, kv, None, fake, 4, fake, None, 0, 0x100000, ws_bytes, None) == -1
+    assert lib.rk_query_sim(C.byref(g), fake, None, 0.5, 0, fake, fake, None) == -1
+    assert lib.rk_mark_refresh(C.byref(g), None, fake, None, 0, None) == -1
+    assert lib.rk_workspace_init(C.byref(g), None, 4096, None) == -3
+    assert lib.rk_workspace_init(C.byref(g), 0x100000, 16, None) == -3
+
+
+def test_binding_refuses_cpu_tensors(rk):
+    import torch
+    g = rk.Geom(1, 4, 2, 128, 1.0)
+    q = torch.zeros(1, 4, 128, dtype=torch.bfloat16)
+    with pytest.raises(ValueError):
+        rk.rk_query_sim(g, q, torch.zeros(1, 128), 0.5, False, torch.zeros(1), torch.zeros(1, dtype=torch.int32))
+
+
+def test_chunk_policy_host_logic():
+    """The split policy (host logic in the binding's library) keeps partial counts bounded:
+    checked through rk_workspace_bytes, which sizes the partial-result area from it."""
+    import paper_2411_05787_amd as rk
+    g = rk.Geom(1, 32, 8, 128, 1.0)
+    small, big = rk.workspace_bytes(g, 64 * 512, 16), rk.workspace_bytes(g, 64 * 512 * 4, 16)
+    # beyond 512 chunks of 64 rows the partial area stops growing; only the pooled scores grow
+    assert big - small == 8 * (64 * 512 * 3) * 4

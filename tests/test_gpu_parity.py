@@ -1,0 +1,368 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle.
+
+Same seeded inputs on both sides; the oracle never sees anything the GPU produced.
+Tolerances: outputs <= 2e-2 max-abs (and one bf16 step); attention weights 1e-5 relative
+(sanity; measured error is ~1e-6); indices exact except across oracle score gaps <= 1e-6
+relative; gathers bit-exact.
+"""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import gen
+import oracle
+from helpers import assert_out_close, assert_idx_equivalent
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def rk():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2411_05787_amd as lib     # raises if the HIP library is not built
+    return lib
+
+
+def say(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def rand_case(seed, B, Hq, Hkv, cap, gain=1.0, D=128):
+    g = torch.Generator().manual_seed(seed)
+    q = torch.randn(B, Hq, D, generator=g).to(torch.bfloat16)
+    K = (torch.randn(B, Hkv, cap, D, generator=g) * gain).to(torch.bfloat16)
+    V = torch.randn(B, Hkv, cap, D, generator=g).to(torch.bfloat16)
+    return q, K, V
+
+
+def gpu_full(rk, geom, q, K, V, lens, max_len, want_weights=True, pred=None, pred_val=0, out_init=None):
+    dev = "cuda"
+    B, Hq = geom.batch, geom.n_q_heads
+    ws = rk.Workspace(geom, K.shape[2], 16)
+    out = torch.zeros(B, Hq, 128, dtype=torch.bfloat16, device=dev) if out_init is None else out_init.clone().to(dev)
+    w = torch.full((B, Hq, K.shape[2]), -7.0, dtype=torch.float32, device=dev) if want_weights else None
+    lse = torch.full((B, Hq), 123.0, dtype=torch.float32, device=dev)
+    sl = torch.tensor(lens, dtype=torch.int32, device=dev)
+    rk.rk_full_attn(geom, q.to(dev), K.to(dev), V.to(dev), sl, max_len, out, weights=w, lse=lse,
+                    pred=None if pred is None else torch.tensor(pred, dtype=torch.int32, device=dev),
+                    pred_val=pred_val, workspace=ws)
+    torch.cuda.synchronize()
+    return gen.bf16_bits(out), (None if w is None else w.cpu().numpy()), lse.cpu().numpy()
+
+
+FULL_CASES = [
+    # name, B, Hq, Hkv, lens, cap        (row counts chosen to hit ragged tails and every tile path)
+    ("llama_ragged", 2, 32, 8, [700, 333], 768),
+    ("qwen_g7", 1, 28, 4, [1000], 1024),
+    ("mha_g1", 1, 4, 4, [130], 256),
+    ("g2", 2, 8, 4, [65, 64], 128),
+    ("g8", 1, 16, 2, [517], 640),
+    ("g3_g5_like", 1, 15, 3, [97], 128),
+    ("len1_and_len0", 3, 8, 2, [1, 0, 17], 64),
+    ("tiles2_path", 4, 32, 8, [2100, 1500, 2099, 64], 2112),     # chunk 128
+    ("tiles4_path", 4, 32, 8, [4200, 4100, 255, 257], 4224),     # chunk 256
+]
+
+
+@pytest.mark.parametrize("case", FULL_CASES, ids=[c[0] for c in FULL_CASES])
+def test_full_attn_matches_oracle(rk, case):
+    name, B, Hq, Hkv, lens, cap = case
+    say("full_attn case", case)
+    q, K, V = rand_case(100 + len(name), B, Hq, Hkv, cap)
+    scale = float(np.float32(1 / np.sqrt(128)))
+    geom = rk.Geom(B, Hq, Hkv, 128, scale)
+    out, w, lse = gpu_full(rk, geom, q, K, V, lens, max(max(lens), 1))
+    o_ref, w_ref, lse_ref = oracle.full_attn(gen.bf16_bits(q), gen.bf16_bits(K), gen.bf16_bits(V), lens, scale)
+    assert_out_close(out, o_ref, name)
+    for b in range(B):
+        n = lens[b]
+        if n == 0:
+            assert (lse[b] == -np.inf).all() and (out[b] == 0).all()
+            continue
+        rel = np.abs(w[b, :, :n] - w_ref[b, :, :n]) / w_ref[b, :, :n]
+        assert rel.max() < 1e-5, "weights rel err %.3g" % rel.max()
+        assert np.abs(w[b, :, :n].sum(axis=1) - 1).max() < 1e-5
+        assert (w[b, :, n:] == -7.0).all(), "weights beyond len must not be written"
+        assert np.abs(lse[b] - lse_ref[b]).max() < 1e-5
+    # without weights: same output bits
+    out2, _, lse2 = gpu_full(rk, geom, q, K, V, lens, max(max(lens), 1), want_weights=False)
+    assert (out2 == out).all() and (lse2 == lse).all()
+
+
+def test_full_attn_planted_keys_and_max_len_clamp(rk):
+    say("full_attn planted / clamp")
+    B, Hq, Hkv, cap = 1, 32, 8, 2048
+    q, K, V = rand_case(7, B, Hq, Hkv, cap)
+    K[:, :, ::131] *= 4.0                                   # a few dominant keys per head
+    scale = float(np.float32(1 / np.sqrt(128)))
+    geom = rk.Geom(B, Hq, Hkv, 128, scale)
+    out, w, _ = gpu_full(rk, geom, q, K, V, [2048], 2048)
+    o_ref, w_ref, _ = oracle.full_attn(gen.bf16_bits(q), gen.bf16_bits(K), gen.bf16_bits(V), [2048], scale)
+    assert_out_close(out, o_ref)
+    assert (np.abs(w[0, :, :2048] - w_ref[0]) / w_ref[0]).max() < 1e-5
+    # a sequence longer than max_len is processed up to max_len
+    out_c, _, _ = gpu_full(rk, geom, q, K, V, [2048], 1000)
+    o_c, _, _ = oracle.full_attn(gen.bf16_bits(q), gen.bf16_bits(K), gen.bf16_bits(V), [1000], scale)
+    assert_out_close(out_c, o_c)
+
+
+def test_full_attn_predicate_skips_sequences(rk):
+    say("full_attn predicate")
+    B, Hq, Hkv, cap = 3, 8, 2, 256
+    q, K, V = rand_case(9, B, Hq, Hkv, cap)
+    scale = 0.1
+    geom = rk.Geom(B, Hq, Hkv, 128, scale)
+    init = torch.full((B, Hq, 128), 5.0, dtype=torch.bfloat16)
+    out, w, lse = gpu_full(rk, geom, q, K, V, [200, 100, 256], 256, pred=[1, 0, 1], pred_val=1, out_init=init)
+    o_ref, _, _ = oracle.full_attn(gen.bf16_bits(q), gen.bf16_bits(K), gen.bf16_bits(V), [200, 100, 256], scale)
+    assert_out_close(out[[0, 2]], o_ref[[0, 2]])
+    assert (out[1] == gen.bf16_bits(init)[1]).all() and (w[1] == -7.0).all() and (lse[1] == 123.0).all()
+
+
+TOPK_CASES = [
+    # name, B, Hq, Hkv, lens, k, pool_w, kind
+    ("lognormal_pool7", 2, 8, 2, [5000, 3777], 256, 7, "lognormal"),
+    ("lognormal_pool1", 1, 4, 1, [4096], 100, 1, "lognormal"),
+    ("ties_pool7", 2, 6, 2, [3000, 2999], 333, 7, "ties"),
+    ("ties_pool1_k1", 1, 2, 2, [1500], 1, 1, "ties"),
+    ("k_ge_len", 2, 4, 2, [50, 7], 64, 7, "lognormal"),
+    ("len0", 2, 4, 2, [0, 20], 8, 3, "lognormal"),
+    ("big_k", 1, 4, 1, [40000], 8192, 7, "lognormal"),
+    ("max_k_ties", 1, 2, 1, [33000], 16384, 7, "ties"),
+    ("pool63", 1, 2, 1, [2000], 128, 63, "lognormal"),
+]
+
+
+@pytest.mark.parametrize("case", TOPK_CASES, ids=[c[0] for c in TOPK_CASES])
+def test_topk_select_exact(rk, case):
+    name, B, Hq, Hkv, lens, k, pool_w, kind = case
+    say("topk case", case)
+    n = max(max(lens), 1)
+    w = gen.make_weights(B, Hq, n, seed=len(name) * 13 + k, kind=kind)
+    geom = rk.Geom(B, Hq, Hkv, 128, 1.0)
+    ws = rk.Workspace(geom, n, k)
+    idx = torch.full((B, Hkv, k), -5, dtype=torch.int32, device="cuda")
+    sel = torch.full((B, Hkv, k), -5.0, dtype=torch.float32, device="cuda")
+    sl = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    rk.rk_topk_select(geom, w.cuda(), sl, n, k, pool_w, idx, sel_scores=sel, workspace=ws)
+    torch.cuda.synchronize()
+    i_ref, s_ref = oracle.topk_select(w.numpy(), lens, Hkv, k, pool_w)
+    assert (idx.cpu().numpy() == i_ref).all()
+    assert (sel.cpu().numpy() == s_ref).all()
+    # same call again: deterministic
+    idx2 = torch.empty_like(idx)
+    rk.rk_topk_select(geom, w.cuda(), sl, n, k, pool_w, idx2, workspace=ws)
+    torch.cuda.synchronize()
+    assert (idx2 == idx).all()
+
+
+def test_gather_bit_exact(rk):
+    say("gather")
+    B, Hkv, cap, k = 3, 4, 500, 77
+    _, K, V = rand_case(21, B, 4, Hkv, cap)
+    g = torch.Generator().manual_seed(3)
+    idx = torch.randint(0, cap, (B, Hkv, k), generator=g, dtype=torch.int32)
+    idx[1, 2, 50:] = -1
+    geom = rk.Geom(B, 4, Hkv, 128, 1.0)
+    sK = torch.full((B, Hkv, k + 3, 128), 9.0, dtype=torch.bfloat16, device="cuda")
+    sV = torch.full((B, Hkv, k + 3, 128), 9.0, dtype=torch.bfloat16, device="cuda")
+    rk.rk_gather_small_kv(geom, K.cuda(), V.cuda(), idx.cuda(), k, sK, sV)
+    torch.cuda.synchronize()
+    rK = np.full((B, Hkv, k + 3, 128), gen.bf16_bits(torch.tensor(9.0, dtype=torch.bfloat16)), dtype=np.uint16)
+    rV = rK.copy()
+    oracle.gather_small_kv(gen.bf16_bits(K), gen.bf16_bits(V), idx.numpy(), rK, rV)
+    assert (gen.bf16_bits(sK) == rK).all() and (gen.bf16_bits(sV) == rV).all()
+
+
+PARTIAL_CASES = [
+    # name, B, Hq, Hkv, lens, recent, k, n_sel
+    ("llama_k256_r3", 2, 32, 8, [900, 650], [3, 0], 256, 256),
+    ("qwen_k100_r17", 1, 28, 4, [700], [17], 100, 100),
+    ("evict_lowest", 1, 8, 2, [600], [5], 64, 59),
+    ("recent_only", 1, 8, 2, [300], [9], 16, 0),
+    ("clamped_n_sel", 2, 4, 4, [40, 500], [2, 1], 128, 128),
+    ("k2048_many_chunks", 1, 32, 8, [5000], [10], 2048, 2048),
+    ("tiles2", 4, 32, 8, [4000, 3000, 2500, 2600], [20, 1, 0, 7], 2080, 2080),
+]
+
+
+@pytest.mark.parametrize("case", PARTIAL_CASES, ids=[c[0] for c in PARTIAL_CASES])
+def test_partial_attn_matches_oracle(rk, case):
+    name, B, Hq, Hkv, lens, recent, k, n_sel = case
+    say("partial case", case)
+    cap = max(lens) + 8
+    q, K, V = rand_case(300 + len(name), B, Hq, Hkv, cap)
+    scale = float(np.float32(1 / np.sqrt(128)))
+    geom = rk.Geom(B, Hq, Hkv, 128, scale)
+    tail = [l - r for l, r in zip(lens, recent)]
+    g = torch.Generator().manual_seed(5)
+    idx = torch.full((B, Hkv, k), -1, dtype=torch.int32)
+    for b in range(B):
+        kk = min(k, tail[b])
+        for h in range(Hkv):
+            idx[b, h, :kk] = torch.randperm(tail[b], generator=g)[:kk].to(torch.int32)
+    sK = torch.zeros(B, Hkv, k, 128, dtype=torch.bfloat16, device="cuda")
+    sV = torch.zeros_like(sK)
+    Kd, Vd = K.cuda(), V.cuda()
+    rk.rk_gather_small_kv(geom, Kd, Vd, idx.cuda(), k, sK, sV)
+    ws = rk.Workspace(geom, cap, k)
+    out = torch.zeros(B, Hq, 128, dtype=torch.bfloat16, device="cuda")
+    rk.rk_partial_attn(geom, q.cuda(), sK, sV, n_sel, Kd, Vd, torch.tensor(tail, dtype=torch.int32, device="cuda"),
+                       torch.tensor(lens, dtype=torch.int32, device="cuda"), max(max(recent), 1), out, workspace=ws)
+    torch.cuda.synchronize()
+    rK = np.zeros((B, Hkv, k, 128), dtype=np.uint16); rV = rK.copy()
+    oracle.gather_small_kv(gen.bf16_bits(K), gen.bf16_bits(V), idx.numpy(), rK, rV)
+    o_ref = oracle.partial_attn(gen.bf16_bits(q), rK, rV, n_sel, gen.bf16_bits(K), gen.bf16_bits(V), tail, lens, scale)
+    assert_out_close(gen.bf16_bits(out), o_ref, name)
+
+
+def test_query_sim_matches_oracle(rk):
+    say("query_sim")
+    B, Hq = 4, 28
+    g = torch.Generator().manual_seed(8)
+    q = torch.randn(B, Hq, 128, generator=g).to(torch.bfloat16)
+    ref = torch.randn(B, 128, generator=g)
+    ref[0] = q[0].float().mean(0)                    # sim = 1
+    ref[1] = -q[1].float().mean(0) * 2               # sim = -1
+    geom = rk.Geom(B, Hq, 4, 128, 1.0)
+    for thr, force in ((0.5, False), (-2.0, False), (0.5, True)):
+        q_ref = ref.clone().cuda()
+        sim = torch.zeros(B, device="cuda"); need = torch.full((B,), -1, dtype=torch.int32, device="cuda")
+        rk.rk_query_sim(geom, q.cuda(), q_ref, thr, force, sim, need)
+        torch.cuda.synchronize()
+        s_ref, n_ref, r_ref = oracle.query_sim(gen.bf16_bits(q), ref.double().numpy(), thr, force)
+        assert np.abs(sim.cpu().numpy() - s_ref).max() < 1e-5
+        assert (need.cpu().numpy().astype(bool) == n_ref).all()
+        assert np.abs(q_ref.cpu().numpy() - r_ref).max() < 1e-6
+
+
+# ----------------------------------------------------------------------------- whole loop
+def run_gpu_loop(rk, w: gen.Workload, layer: int, K, V, q_steps, new_k, new_v, lens0, evict_lowest=False):
+    """Drive the library through the decode schedule; returns per-step outputs and snapshots."""
+    dev = "cuda"
+    geom = rk.Geom(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.scale)
+    Kd, Vd = K.to(dev).clone(), V.to(dev).clone()
+    sl = lens0.to(dev).clone()
+    lay = rk.RefreshKVLayer(geom, Kd, Vd, sl, int(lens0.max()), w.k_small, w.stride, pool_w=w.pool_w,
+                            dynamic=w.dynamic, threshold=w.threshold, evict_lowest=evict_lowest)
+    qd, nk, nv = q_steps.to(dev), new_k.to(dev), new_v.to(dev)
+    outs, idxs, needs, sims, kinds = [], [], [], [], []
+    for t in range(w.n_steps + 1):
+        if t >= 1:
+            lay.append(nk[t - 1], nv[t - 1])
+        kinds.append(lay.step(t, qd[t]))
+        outs.append(lay.out.clone()); idxs.append(lay.idx.clone())
+        needs.append(lay.need_full.clone()); sims.append(lay.sim.clone())
+    torch.cuda.synchronize()
+    return dict(outs=np.stack([gen.bf16_bits(o) for o in outs]), idx=[i.cpu().numpy() for i in idxs],
+                need=np.stack([n.cpu().numpy() for n in needs]), sims=np.stack([s.cpu().numpy() for s in sims]),
+                kinds=kinds, K=gen.bf16_bits(Kd), V=gen.bf16_bits(Vd), lens=sl.cpu().numpy())
+
+
+def check_loop(rk, w: gen.Workload, evict_lowest=False):
+    K, V = gen.make_kv(w, 0)
+    q = gen.make_queries(w, 0)
+    nk, nv = gen.make_new_rows(w, 0)
+    lens0 = gen.seq_lens(w)
+    got = run_gpu_loop(rk, w, 0, K, V, q, nk, nv, lens0, evict_lowest)
+    ref = oracle.decode_loop(gen.bf16_bits(q), gen.bf16_bits(K), gen.bf16_bits(V), gen.bf16_bits(nk),
+                             gen.bf16_bits(nv), lens0.numpy(), w.scale, w.k_small, w.stride, pool_w=w.pool_w,
+                             dynamic=w.dynamic, threshold=w.threshold, evict_lowest=evict_lowest)
+    assert (got["K"] == ref["k"]).all() and (got["V"] == ref["v"]).all() and (got["lens"] == ref["lens"]).all()
+    G = w.group
+    n_diff = 0
+    lens = lens0.numpy().astype(np.int64).copy()
+    last_full_scores = {}
+    for t in range(w.n_steps + 1):
+        if t >= 1:
+            lens += 1
+        for b in range(w.batch):
+            if ref["full"][t, b]:
+                # oracle pooled scores of this refresh, for the gap test on indices
+                wts = oracle.full_attn(gen.bf16_bits(q[t, b:b + 1]), ref["k"][b:b + 1], ref["v"][b:b + 1],
+                                       [lens[b]], w.scale)[1].astype(np.float32)
+                for g in range(w.n_kv_heads):
+                    last_full_scores[(b, g)] = (oracle.pooled_group_scores(wts[0, g * G:(g + 1) * G], w.pool_w),
+                                                int(lens[b]))
+            if w.dynamic and t >= 1 and t % w.stride == 0:
+                s_ref = ref["sims"][t, b]
+                assert abs(got["sims"][t, b] - s_ref) < 1e-5
+                if abs(s_ref - w.threshold) > 1e-5:
+                    assert bool(got["need"][t, b]) == bool(ref["full"][t, b]), "trigger decision differs at t=%d" % t
+            for g in range(w.n_kv_heads):
+                P, n = last_full_scores[(b, g)]
+                n_diff += assert_idx_equivalent(got["idx"][t][b, g], ref["idx"][t][b, g], P, n, w.k_small,
+                                                "t=%d b=%d g=%d" % (t, b, g))
+        assert_out_close(got["outs"][t], ref["outs"][t], "%s t=%d" % (w.name, t))
+    return got, ref, n_diff
+
+
+def test_loop_cfg1_every_step(rk):
+    w = gen.WORKLOADS["cfg1_llama_2k"]
+    say("loop", w.name)
+    got, ref, n_diff = check_loop(rk, w)
+    assert got["kinds"] == ["full" if f else "partial" for f in ref["full"][:, 0]]
+    assert sum(k == "full" for k in got["kinds"]) == 9          # t = 0 and 8 strided refreshes
+    say("cfg1: index entries differing within the gap tolerance:", n_diff)
+
+
+def test_loop_cfg1_fixed_size_small_cache(rk):
+    w = gen.shrink(gen.WORKLOADS["cfg1_llama_2k"], context=1024, k_small=128, n_steps=12, stride=6)
+    say("loop evict-lowest", w.name)
+    check_loop(rk, w, evict_lowest=True)
+
+
+def test_loop_dynamic_trigger_qwen_small(rk):
+    w = gen.shrink(gen.WORKLOADS["cfg3_qwen_64k_dynamic"], context=3000, k_small=256, n_steps=40)
+    say("loop dynamic", w.name)
+    got, ref, _ = check_loop(rk, w)
+    fired = int(ref["full"][1:, 0].sum())
+    tested = w.n_steps // w.stride
+    assert 0 < fired < tested, "want a mix of fired and not fired tests (fired %d of %d)" % (fired, tested)
+
+
+def test_loop_batched_ragged_small(rk):
+    w = gen.shrink(gen.WORKLOADS["cfg4_llama_batch16_ragged"], batch=5, context=1500, ragged=(300, 1500),
+                   k_small=128, n_steps=17, stride=8)
+    say("loop batched ragged", w.name, gen.seq_lens(w).tolist())
+    check_loop(rk, w)
+
+
+def test_loop_clustered_keys_small(rk):
+    w = gen.shrink(gen.WORKLOADS["cfg5_llama_128k"], context=6000, k_small=384, n_steps=9, stride=4)
+    say("loop clustered", w.name)
+    check_loop(rk, w)
+
+
+# ----------------------------------------------------------------------------- full sizes
+FULL_SIZE = ["cfg2_llama_32k", "cfg3_qwen_64k_dynamic", "cfg5_llama_128k"]
+
+
+@pytest.mark.parametrize("name", FULL_SIZE)
+def test_full_size_one_layer_refresh_and_partial(rk, name):
+    """One layer at the benchmark's real shape, in the launch configuration bench.py times:
+    full step + selection + gather + a partial step 3 tokens later, all against the oracle."""
+    w = gen.shrink(gen.WORKLOADS[name], n_layers=1, n_steps=3, stride=100, dynamic=False)
+    say("full size", w.name, "L", w.context, "K", w.k_small)
+    K, V = gen.make_kv(w, 0, device="cuda")
+    q = gen.make_queries(w, 0)
+    nk, nv = gen.make_new_rows(w, 0)
+    lens0 = gen.seq_lens(w)
+    Kc, Vc = K.cpu(), V.cpu()
+    got = run_gpu_loop(rk, w, 0, K, V, q, nk, nv, lens0)
+    say("  gpu done; running oracle")
+    ref = oracle.decode_loop(gen.bf16_bits(q), gen.bf16_bits(Kc), gen.bf16_bits(Vc), gen.bf16_bits(nk),
+                             gen.bf16_bits(nv), lens0.numpy(), w.scale, w.k_small, w.stride, pool_w=w.pool_w)
+    for t in range(w.n_steps + 1):
+        assert_out_close(got["outs"][t], ref["outs"][t], "%s t=%d" % (name, t))
+    wts = oracle.full_attn(gen.bf16_bits(q[0]), gen.bf16_bits(Kc), gen.bf16_bits(Vc), lens0.numpy(), w.scale)[1]
+    wts = wts.astype(np.float32)
+    G = w.group
+    n_diff = 0
+    for g in range(w.n_kv_heads):
+        P = oracle.pooled_group_scores(wts[0, g * G:(g + 1) * G], w.pool_w)
+        n_diff += assert_idx_equivalent(got["idx"][0][0, g], ref["idx"][0][0, g], P, w.context, w.k_small, "g=%d" % g)
+    say("  index entries differing within the gap tolerance:", n_diff, "of", w.n_kv_heads * w.k_small)

@@ -1,0 +1,280 @@
+#!/usr/bin/env python3
+"""Benchmark of the RefreshKV decode-attention hot path on one MI355X.
+
+A "step" is one decode step of the whole hot path over all layers of the workload: per layer
+the query-similarity bookkeeping, then either full attention + top-K selection + gather
+(every S-th step) or partial attention over the small cache.  K/V are synthetic and already
+resident in HBM; the rows that later steps "append" are pre-written, so a step only advances
+seq_lens (the append itself is the caller's 4 KB copy, outside this library).
+
+Prints ONE JSON line (see the keys below).  Beside the headline it carries
+  roofline      achieved HBM GB/s of the dominant HBM-bound kernel (the split full-attention
+                kernel) = algorithmic bytes per launch / its average duration, measured here
+                with HIP events on the launch stream around back-to-back launches of that
+                kernel alone (rk_full_attn_scores), one per layer;
+  cpu_baseline  the CPU oracle timed on this machine's host cores on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published peak
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="cfg2_llama_32k")
+    ap.add_argument("--layers", type=int, default=0, help="override the number of layers (0 = workload's)")
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-layers", type=int, default=4, help="layers of the oracle sample")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the path has no multi-GPU part); got --gpus %d" % args.gpus,
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import gen
+    import paper_2411_05787_amd as rk
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = "cuda"
+    w = gen.WORKLOADS[args.workload]
+    n_layers = args.layers or w.n_layers
+    T = args.warmup + args.steps
+    L0 = w.context
+    # rows for every future step are pre-written: context' = L0 + T, seq_lens starts at L0
+    w_alloc = gen.shrink(w, context=L0 + T + 8, n_steps=0)
+    geom = rk.Geom(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.scale)
+    B, Hq, Hkv, D = w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim
+
+    t_setup = time.time()
+    kv = [gen.make_kv(w_alloc, l, device=dev) for l in range(n_layers)]
+    cap = kv[0][0].shape[2]
+    lens0 = gen.seq_lens(w)
+    seq_lens = lens0.to(dev)
+    wq = gen.shrink(w, n_steps=T)
+    q_steps = torch.stack([gen.make_queries(wq, l) for l in range(n_layers)], dim=1).to(dev)   # [T+1, nl, B, Hq, D]
+    q_cur = torch.empty(n_layers, B, Hq, D, dtype=torch.bfloat16, device=dev)
+    max_len_bound = int(lens0.max()) + T + 1
+    ws = rk.Workspace(geom, cap, w.k_small)
+    weights = torch.empty(B, Hq, cap, dtype=torch.float32, device=dev)
+    layers = [rk.RefreshKVLayer(geom, kv[l][0], kv[l][1], seq_lens, int(lens0.max()), w.k_small, w.stride,
+                                pool_w=w.pool_w, dynamic=w.dynamic, threshold=w.threshold,
+                                workspace=ws, weights=weights) for l in range(n_layers)]
+    for lay in layers:
+        lay.use_static_bounds(max_len_bound, max(w.stride, 1))
+    torch.cuda.synchronize()
+    setup_s = time.time() - t_setup
+
+    def enqueue_step(t: int):
+        """Everything of decode step t on the current stream (q_cur already holds the queries)."""
+        if t >= 1:
+            seq_lens.add_(1)
+        kind = None
+        for l, lay in enumerate(layers):
+            kind = lay.step(t, q_cur[l])
+        return kind
+
+    def is_full(t):
+        return t == 0 or (w.stride > 0 and t % w.stride == 0)
+
+    # t = 0: prefill-equivalent initialisation (full step everywhere), eager
+    q_cur.copy_(q_steps[0])
+    enqueue_step(0)
+    torch.cuda.synchronize()
+
+    graphs = {}
+    if not args.no_graph:
+        # capture one full-style and one partial-style step; the device-side seq_lens/tail_start
+        # make a replay do the right thing at any later step.  Capturing advances seq_lens like a
+        # real step would not (nothing runs during capture), so no state is disturbed.
+        side = torch.cuda.Stream()
+        for kind, t_like in (("partial", 1), ("full", w.stride if w.stride > 0 else 0)):
+            if kind == "full" and w.stride <= 0:
+                continue
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                enqueue_step(t_like)
+            graphs[kind] = g
+        torch.cuda.synchronize()
+
+    def run_step(t: int):
+        q_cur.copy_(q_steps[t], non_blocking=True)
+        kind = "full" if is_full(t) else ("both" if (w.dynamic and t % w.stride == 0) else "partial")
+        if graphs and kind in graphs:
+            graphs[kind].replay()
+        else:
+            enqueue_step(t)
+        return kind
+
+    for t in range(1, args.warmup + 1):
+        run_step(t)
+    torch.cuda.synchronize()
+
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    kinds = []
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i, t in enumerate(range(args.warmup + 1, T + 1)):
+        ev[i][0].record()
+        kinds.append(run_step(t))
+        ev[i][1].record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    wall_ms = (t1 - t0) * 1e3
+    ms_per_step = wall_ms / args.steps
+    per_kind = {}
+    for (a, b), k in zip(ev, kinds):
+        per_kind.setdefault(k, []).append(a.elapsed_time(b) * 1e3)
+    med = {k: float(np.median(v)) / n_layers for k, v in per_kind.items()}      # us per layer
+    final_len = int(seq_lens.max().item())
+    assert final_len == int(lens0.max()) + T, (final_len, int(lens0.max()) + T)
+
+    # ---- per-call-class GPU time (graph of n_layers calls each), cold last-level cache ----
+    def graph_us(fn, reps=3):
+        s = torch.cuda.Stream()
+        s.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(s):
+            for l in range(min(2, n_layers)):
+                fn(l)
+        torch.cuda.current_stream().wait_stream(s)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for l in range(n_layers):
+                fn(l)
+        g.replay(); torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ts = []
+        for _ in range(reps):
+            a.record(); g.replay(); b.record(); torch.cuda.synchronize()
+            ts.append(a.elapsed_time(b) * 1e3 / n_layers)
+        return float(np.median(ts))
+
+    out = layers[0].out
+    Lb = max_len_bound
+    klass = {
+        "full_attn": graph_us(lambda l: rk.rk_full_attn(geom, q_cur[l], *kv[l], seq_lens, Lb, out, weights=weights, workspace=ws)),
+        "topk_select": graph_us(lambda l: rk.rk_topk_select(geom, weights, seq_lens, Lb, w.k_small, w.pool_w, layers[l].idx, workspace=ws)),
+        "gather_small_kv": graph_us(lambda l: rk.rk_gather_small_kv(geom, *kv[l], layers[l].idx, w.k_small, layers[l].small_K, layers[l].small_V)),
+        "partial_attn": graph_us(lambda l: rk.rk_partial_attn(geom, q_cur[l], layers[l].small_K, layers[l].small_V, w.k_small, *kv[l],
+                                                               layers[l].tail_start, seq_lens, max(w.stride, 1), out, workspace=ws)),
+        "query_sim": graph_us(lambda l: rk.rk_query_sim(geom, q_cur[l], layers[l].q_ref, w.threshold, False, layers[l].sim, layers[l].need_full)),
+    }
+
+    # ---- roofline of the split full-attention kernel ----
+    # rk_full_attn_scores launches that kernel alone.  One launch per layer (round-robin, so the
+    # 256 MB last-level cache never holds the rows about to be read) is captured in a HIP graph;
+    # HIP events on the launch stream bracket each replay; average = elapsed / launches.
+    scores_buf = weights
+    def roof_call(l):
+        rk.rk_full_attn_scores(geom, q_cur[l], *kv[l], seq_lens, Lb, scores_buf, workspace=ws)
+    roof_reps = 4
+    per_replay = []
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        roof_call(0)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g_roof = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g_roof):
+        for l in range(n_layers):
+            roof_call(l)
+    g_roof.replay(); torch.cuda.synchronize()
+    ea, eb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for _ in range(roof_reps):
+        ea.record(); g_roof.replay(); eb.record(); torch.cuda.synchronize()
+        per_replay.append(ea.elapsed_time(eb) * 1e3 / n_layers)
+    split_us = float(np.mean(per_replay))
+    n_roof_launches = roof_reps * n_layers
+    rows = int(seq_lens.sum().item())                    # rows streamed per launch (all sequences)
+    bytes_kv = 2 * Hkv * D * 2 * rows                    # K and V rows, bf16
+    bytes_w = 4 * Hq * rows                              # raw scores written by the same kernel
+    algo_bytes = bytes_kv + bytes_w
+    achieved = algo_bytes / (split_us * 1e-6) / 1e9
+    roofline = {"bound": "hbm", "kernel": "rk::attn_split_kernel<%d, 4, 4, true, false> (first kernel of rk_full_attn when weights are returned)" % w.group,
+                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                "avg_launch_us": round(split_us, 2), "launches": n_roof_launches, "algorithmic_bytes": algo_bytes}
+
+    # ---- CPU oracle on a bounded sample of the same workload ----
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        try:
+            from threadpoolctl import threadpool_info
+            threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            threads = 1
+        n_cpu = min(args.cpu_layers, n_layers)
+        period = max(w.stride, 1)
+        tot = {"full": 0.0, "refresh": 0.0, "partial": 0.0}
+        lens_np = lens0.numpy().astype(np.int64)
+        for l in range(n_cpu):
+            Kb, Vb = gen.bf16_bits(kv[l][0]), gen.bf16_bits(kv[l][1])
+            qb = gen.bf16_bits(q_steps[:period + 1, l])
+            c0 = time.perf_counter()
+            o, wts, _ = oracle.full_attn(qb[0], Kb, Vb, lens_np, w.scale)
+            c1 = time.perf_counter()
+            idx, _ = oracle.topk_select(wts.astype(np.float32), lens_np, Hkv, w.k_small, w.pool_w)
+            sk = np.zeros((B, Hkv, w.k_small, D), dtype=np.uint16); sv = sk.copy()
+            oracle.gather_small_kv(Kb, Vb, idx, sk, sv)
+            c2 = time.perf_counter()
+            for r in range(1, period):
+                oracle.partial_attn(qb[r], sk, sv, w.k_small, Kb, Vb, lens_np, lens_np + r, w.scale)
+            c3 = time.perf_counter()
+            tot["full"] += c1 - c0; tot["refresh"] += c2 - c1; tot["partial"] += c3 - c2
+            del Kb, Vb
+        steps_cpu = n_cpu * period
+        cpu_us = (tot["full"] + tot["refresh"] + tot["partial"]) / steps_cpu * 1e6
+        cpu = {"value": round(cpu_us, 1), "unit": "us/step/layer", "cores": int(threads), "kind": "oracle",
+               "host_cpus": os.cpu_count(),
+               "sample": "%d layers x one stride period (1 full step + selection + gather, %d partial steps) of %s"
+                         % (n_cpu, period - 1, w.name),
+               "full_us": round(tot["full"] / n_cpu * 1e6, 1), "refresh_us": round(tot["refresh"] / n_cpu * 1e6, 1),
+               "partial_us": round(tot["partial"] / max(n_cpu * (period - 1), 1) * 1e6, 1)}
+
+    us_per_step_layer = ms_per_step * 1e3 / n_layers
+    n_full = sum(k == "full" for k in kinds)
+    result = {
+        "metric": "decode attention us/step/layer (full vs partial) + achieved HBM GB/s vs peak",
+        "value": round(us_per_step_layer, 3), "unit": "us/step/layer",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "layers": n_layers, "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv,
+                   "head_dim": D, "context": L0, "k_small": w.k_small, "stride": w.stride, "pool_w": w.pool_w,
+                   "schedule": "dynamic" if w.dynamic else "fixed", "full_steps": n_full,
+                   "partial_steps": args.steps - n_full, "launch": "eager" if args.no_graph else "hip_graph"},
+        "step_us_per_layer": {k: round(v, 2) for k, v in med.items()},
+        "call_us_per_layer": {k: round(v, 2) for k, v in klass.items()},
+        "full_over_partial": round(klass["full_attn"] / klass["partial_attn"], 2),
+        "full_attn_GBps": round((bytes_kv + bytes_w) / (klass["full_attn"] * 1e-6) / 1e9, 1),
+        "partial_attn_GBps": round(2 * Hkv * D * 2 * (w.k_small + 1) * B / (klass["partial_attn"] * 1e-6) / 1e9, 1),
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "setup_s": round(setup_s, 1),
+    }
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -120,6 +120,19 @@ int rk_full_attn(const rk_geom* geom, const void* q, rk_kv full,
                  const int32_t* pred, int32_t pred_val,
                  void* workspace, size_t workspace_bytes, void* stream);
 
+/* First phase of rk_full_attn by itself: the kernel that streams C_f once.  It writes the raw
+ * scores scores[b,h,j] = scale * <q[b,h,:], K[b,g,j,:]> (j < seq_lens[b]) and leaves per-chunk
+ * partial results in the workspace; out, lse and the normalised weights are NOT produced
+ * (rk_full_attn = this kernel + a short finishing kernel that merges the partial results and
+ * turns the scores into weights; Section 2.2 "Decoding with full cache", Appendix A.1).
+ * Exposed so that a benchmark can time the HBM-bound kernel alone, launch after launch.
+ * scores: fp32 [batch, n_q_heads, s_stride], s_stride >= max_len. */
+int rk_full_attn_scores(const rk_geom* geom, const void* q, rk_kv full,
+                        const int32_t* seq_lens, int32_t max_len,
+                        float* scores, int64_t s_stride,
+                        const int32_t* pred, int32_t pred_val,
+                        void* workspace, size_t workspace_bytes, void* stream);
+
 /* Selection of the rows that refresh the small cache.
  *   for every sequence b and KV head g, with n = seq_lens[b]:
  *     A[j] = max over the G heads h of group g of weights[b,h,j]

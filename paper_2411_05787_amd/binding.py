@@ -16,7 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "librefreshkv.so")
 
 EXPORTS = ["rk_version", "rk_status_string", "rk_workspace_bytes", "rk_workspace_init",
-           "rk_full_attn", "rk_topk_select", "rk_gather_small_kv", "rk_partial_attn",
+           "rk_full_attn", "rk_full_attn_scores", "rk_topk_select", "rk_gather_small_kv", "rk_partial_attn",
            "rk_query_sim", "rk_mark_refresh"]
 
 RK_AGG_MAX = 0
@@ -38,11 +38,11 @@ class _Kv(C.Structure):
                 ("capacity", C.c_int64)]
 
 
-def _load() -> C.CDLL:
-    if not os.path.exists(LIB_PATH):
+def _load(path: str = LIB_PATH) -> C.CDLL:
+    if not os.path.exists(path):
         raise ImportError("librefreshkv.so is not built (%s missing); run "
-                          "`python -m paper_2411_05787_amd.build` first. There is no fallback path." % LIB_PATH)
-    l = C.CDLL(LIB_PATH)
+                          "`python -m paper_2411_05787_amd.build` first. There is no fallback path." % path)
+    l = C.CDLL(path)
     P, I32, I64, SZ = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
     G = C.POINTER(_Geom)
     l.rk_version.restype = C.c_int
@@ -55,6 +55,8 @@ def _load() -> C.CDLL:
     l.rk_workspace_init.argtypes = [G, P, SZ, P]
     l.rk_full_attn.restype = C.c_int
     l.rk_full_attn.argtypes = [G, P, _Kv, P, I32, P, P, I64, P, P, I32, P, SZ, P]
+    l.rk_full_attn_scores.restype = C.c_int
+    l.rk_full_attn_scores.argtypes = [G, P, _Kv, P, I32, P, I64, P, I32, P, SZ, P]
     l.rk_topk_select.restype = C.c_int
     l.rk_topk_select.argtypes = [G, P, I64, P, I32, I32, I32, I32, P, P, P, I32, P, SZ, P]
     l.rk_gather_small_kv.restype = C.c_int
@@ -174,6 +176,21 @@ def rk_full_attn(geom: Geom, q, K, V, seq_lens, max_len: int, out, weights=None,
         _dev(out, torch.bfloat16, "out", (B, Hq, D)),
         _dev(weights, torch.float32, "weights", optional=True), w_stride,
         _dev(lse, torch.float32, "lse", (B, Hq), optional=True),
+        _dev(pred, torch.int32, "pred", (B,), optional=True), int(pred_val),
+        workspace.ptr, workspace.nbytes, _stream(stream)))
+
+
+def rk_full_attn_scores(geom: Geom, q, K, V, seq_lens, max_len: int, scores, pred=None, pred_val: int = 0,
+                        workspace: Workspace = None, stream=None) -> None:
+    B, Hq, D = geom.batch, geom.n_q_heads, geom.head_dim
+    if max_len > K.shape[2]:
+        raise ValueError("max_len %d exceeds the cache capacity %d" % (max_len, K.shape[2]))
+    if scores.dim() != 3 or scores.shape[0] != B or scores.shape[1] != Hq or scores.shape[2] < max_len:
+        raise ValueError("scores must be [batch, n_q_heads, >= max_len]")
+    _check("rk_full_attn_scores", lib.rk_full_attn_scores(
+        C.byref(geom.c()), _dev(q, torch.bfloat16, "q", (B, Hq, D)), _kv(geom, K, V, "full"),
+        _dev(seq_lens, torch.int32, "seq_lens", (B,)), int(max_len),
+        _dev(scores, torch.float32, "scores"), scores.shape[2],
         _dev(pred, torch.int32, "pred", (B,), optional=True), int(pred_val),
         workspace.ptr, workspace.nbytes, _stream(stream)))
 

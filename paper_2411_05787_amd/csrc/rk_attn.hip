@@ -4,6 +4,13 @@
 // of the GQA group, so every K/V byte is read from HBM once.  The workgroup that arrives
 // last for a (sequence, KV head) merges the partial results and writes the output.
 //
+// Hand-over between workgroups (which may sit on different XCDs, each with its own L2):
+// partial results are written with agent-scope atomic stores and read with agent-scope atomic
+// loads, i.e. write-through / coherent accesses; a writer waits until its stores are
+// acknowledged (s_waitcnt vmcnt(0)) before it takes its arrival ticket with an agent-scope
+// atomic add.  No cache-wide release/acquire fence is used: on this chip one such fence per
+// workgroup writes back and invalidates a whole L2 and costs more than the attention itself.
+//
 // Data path per wavefront and iteration (ROWS = 16 * TILES rows):
 //   K rows  -> registers in MFMA operand layout (16-byte loads, no LDS)
 //   S = Q K^T on the matrix cores: v_mfma_f32_16x16x32_bf16, M = query heads (padded to 16),
@@ -36,44 +43,84 @@ struct AttnParams {
     int32_t* counters; float* part_ml; float* part_o; int32_t max_chunks;
 };
 
+__device__ __forceinline__ void coherent_store2(float* p, float a, float b) {
+    const uint64_t v = (uint64_t)__float_as_uint(a) | ((uint64_t)__float_as_uint(b) << 32);
+    __hip_atomic_store(reinterpret_cast<uint64_t*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint64_t coherent_load2(const float* p) {
+    return __hip_atomic_load(reinterpret_cast<const uint64_t*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float lo_f(uint64_t v) { return __uint_as_float((uint32_t)v); }
+__device__ __forceinline__ float hi_f(uint64_t v) { return __uint_as_float((uint32_t)(v >> 32)); }
+// All global stores this thread issued so far are acknowledged once this returns.
+__device__ __forceinline__ void wait_stores_acknowledged() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 // Merge of the partial results of one (sequence, KV head); run by one whole workgroup.
 //   M = max_c m_c;  L = sum_c e^{m_c - M} l_c;  out = sum_c e^{m_c - M} o_c / L;  lse = M + ln L
 template <int G, int NW>
-__device__ void merge_partials(const AttnParams& p, int b, int g, int nchunks, float* sW, float* sRed,
-                               float* sM, float* sL) {
+__device__ void merge_partials(const AttnParams& p, int b, int g, int nchunks, float* sW, float* sLc,
+                               float* sM, double* sL) {
     constexpr int NT = NW * 64;
-    const int tid = threadIdx.x;
+    constexpr int BATCH = kMergeChunks;           // coherent loads in flight per thread: all of them
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int64_t bg = (int64_t)b * p.Hkv + g;
     const float* ml = p.part_ml + bg * kMaxChunks * G * 2;
     const float* po = p.part_o + bg * p.max_chunks * G * kD;
+    // (max, sum) of every chunk and head: one round trip to memory, then everything is in LDS
+    const int n_ml = nchunks * G;
+    for (int i0 = 0; i0 < n_ml; i0 += NT * 4) {
+        uint64_t v[4];
 #pragma unroll
-    for (int gi = 0; gi < G; ++gi) {
-        float mx = -INFINITY;
-        for (int c = tid; c < nchunks; c += NT) mx = fmaxf(mx, ml[(c * G + gi) * 2]);
-        mx = block_max<NW>(mx, sRed);
-        float ls = 0.f;
-        for (int c = tid; c < nchunks; c += NT) {
-            const float mc = ml[(c * G + gi) * 2];
-            const float wgt = (mc == -INFINITY) ? 0.f : fast_exp2((mc - mx) * kLog2e);
-            sW[c * G + gi] = wgt;
-            ls += wgt * ml[(c * G + gi) * 2 + 1];
+        for (int u = 0; u < 4; ++u) v[u] = coherent_load2(ml + (int64_t)min(i0 + u * NT + tid, n_ml - 1) * 2);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = i0 + u * NT + tid;
+            if (i < n_ml) { sW[i] = lo_f(v[u]); sLc[i] = hi_f(v[u]); }
         }
-        ls = block_sum<NW>(ls, sRed);
-        if (tid == 0) { sM[gi] = mx; sL[gi] = ls; }
     }
     __syncthreads();
-    for (int e = tid; e < G * kD; e += NT) {
-        const int gi = e / kD;
-        float acc = 0.f;
-#pragma unroll 4
-        for (int c = 0; c < nchunks; ++c) acc += sW[c * G + gi] * po[(int64_t)c * G * kD + e];
-        const float L = sL[gi];
-        const float o = L > 0.f ? acc / L : 0.f;
-        p.out[((int64_t)b * p.Hq + g * G) * kD + e] = f32_to_bf16(o);
+    // one wavefront per head: M = max_c m_c, w_c = e^{m_c - M} (overwrites m_c), L = sum_c w_c l_c
+    for (int gi = w; gi < G; gi += NW) {
+        float mx = -INFINITY;
+        for (int c = lane; c < nchunks; c += 64) mx = fmaxf(mx, sW[c * G + gi]);
+        mx = wave_max(mx);
+        double ls = 0.0;                          // the sum that normalises every weight: fp64
+        for (int c = lane; c < nchunks; c += 64) {
+            const float mc = sW[c * G + gi];
+            const float wgt = (mc == -INFINITY) ? 0.f : fast_exp2((mc - mx) * kLog2e);
+            sW[c * G + gi] = wgt;
+            ls += (double)wgt * (double)sLc[c * G + gi];
+        }
+#pragma unroll
+        for (int m = 1; m < 64; m <<= 1) ls += __shfl_xor(ls, m);
+        if (lane == 0) { sM[gi] = mx; sL[gi] = ls; }
+    }
+    __syncthreads();
+    for (int e2 = tid; e2 < G * kD / 2; e2 += NT) {          // two consecutive dims per thread
+        const int gi = (2 * e2) / kD;
+        float acc0 = 0.f, acc1 = 0.f;
+        for (int c0 = 0; c0 < nchunks; c0 += BATCH) {
+            uint64_t v[BATCH];
+#pragma unroll
+            for (int u = 0; u < BATCH; ++u) {
+                const int c = min(c0 + u, nchunks - 1);
+                v[u] = coherent_load2(po + (int64_t)c * G * kD + 2 * e2);
+            }
+#pragma unroll
+            for (int u = 0; u < BATCH; ++u) {
+                const float wgt = (c0 + u < nchunks) ? sW[(c0 + u) * G + gi] : 0.f;
+                acc0 = fmaf(wgt, lo_f(v[u]), acc0);
+                acc1 = fmaf(wgt, hi_f(v[u]), acc1);
+            }
+        }
+        const float L = (float)sL[gi];
+        const float inv = L > 0.f ? 1.f / L : 0.f;
+        const uint32_t packed = (uint32_t)f32_to_bf16(acc0 * inv) | ((uint32_t)f32_to_bf16(acc1 * inv) << 16);
+        reinterpret_cast<uint32_t*>(p.out + ((int64_t)b * p.Hq + g * G) * kD)[e2] = packed;
     }
     if (tid < G) {
-        const float L = sL[tid];
-        p.lse[(int64_t)b * p.Hq + g * G + tid] = L > 0.f ? sM[tid] + logf(L) : -INFINITY;
+        const double L = sL[tid];
+        p.lse[(int64_t)b * p.Hq + g * G + tid] = L > 0.0 ? (float)((double)sM[tid] + log(L)) : -INFINITY;
     }
 }
 
@@ -126,11 +173,10 @@ void attn_split_kernel(const AttnParams p) {
     __shared__ __attribute__((aligned(16))) float sMw[NW][GP];
     __shared__ __attribute__((aligned(16))) float sLw[NW][GP];
     __shared__ __attribute__((aligned(16))) float sO[NW * RG][G][kD];   // reused by the merge
-    __shared__ float sRed[NW];
-    __shared__ float sMf[GP], sLf[GP];
+    __shared__ float sMf[GP];
+    __shared__ double sLf[GP];
     __shared__ int sTicket;
-    static_assert(sizeof(float) * NW * RG * G * kD >= sizeof(float) * kMaxChunks * G,
-                  "merge weights must fit in the output staging buffer");
+    static_assert(NW * RG * G * kD >= 2 * kMergeChunks * G, "merge scratch must fit in the output staging buffer");
 
     // ---- Q as the A operand: lane (n16, c4) holds head n16, dims 8*(4*kk + c4) .. +7 ----
     bf16x8 qa[4];
@@ -293,51 +339,138 @@ void attn_split_kernel(const AttnParams p) {
     const int64_t bg = (int64_t)b * p.Hkv + g;
     float* ml = p.part_ml + (bg * kMaxChunks + c) * G * 2;
     float* po = p.part_o + (bg * p.max_chunks + c) * G * kD;
-    for (int e = tid; e < G * kD; e += NT) {
-        const int gi = e / kD, d = e % kD;
+    for (int e2 = tid; e2 < G * kD / 2; e2 += NT) {           // two consecutive dims per thread
+        const int gi = (2 * e2) / kD, d = (2 * e2) % kD;
         float M = sMw[0][gi];
 #pragma unroll
         for (int ww = 1; ww < NW; ++ww) M = fmaxf(M, sMw[ww][gi]);
-        float acc = 0.f, L = 0.f;
+        float acc0 = 0.f, acc1 = 0.f, L = 0.f;
 #pragma unroll
         for (int ww = 0; ww < NW; ++ww) {
             const float mw = sMw[ww][gi];
             const float sc = (mw == -INFINITY) ? 0.f : fast_exp2((mw - M) * kLog2e);
-            float part = 0.f;
+            float p0 = 0.f, p1 = 0.f;
 #pragma unroll
-            for (int rr = 0; rr < RG; ++rr) part += sO[ww * RG + rr][gi][d];
-            acc += sc * part;
-            L += sc * sLw[ww][gi];
+            for (int rr = 0; rr < RG; ++rr) {
+                const float2 t2 = *reinterpret_cast<const float2*>(&sO[ww * RG + rr][gi][d]);
+                p0 += t2.x; p1 += t2.y;
+            }
+            acc0 = fmaf(sc, p0, acc0);
+            acc1 = fmaf(sc, p1, acc1);
+            L = fmaf(sc, sLw[ww][gi], L);
         }
-        po[e] = acc;
-        if (d == 0) { ml[gi * 2] = M; ml[gi * 2 + 1] = L; }
+        if (EMIT) {       // merged by the next kernel: ordinary stores
+            *reinterpret_cast<float2*>(po + 2 * e2) = make_float2(acc0, acc1);
+            if (d == 0) *reinterpret_cast<float2*>(ml + gi * 2) = make_float2(M, L);
+        } else {
+            coherent_store2(po + 2 * e2, acc0, acc1);
+            if (d == 0) coherent_store2(ml + gi * 2, M, L);
+        }
     }
+    if (EMIT) return;
 
     // ---- the workgroup that arrives last for (b, g) merges all chunks ----
-    __threadfence();
+    wait_stores_acknowledged();
     __syncthreads();
-    if (tid == 0) sTicket = atomicAdd(&p.counters[bg], 1);
+    if (tid == 0) sTicket = __hip_atomic_fetch_add(&p.counters[bg], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     if (sTicket != nchunks - 1) return;
-    __threadfence();
-    merge_partials<G, NW>(p, b, g, nchunks, &sO[0][0][0], sRed, sMf, sLf);
-    if (tid == 0) p.counters[bg] = 0;      // ready for the next call
+    merge_partials<G, NW>(p, b, g, nchunks, &sO[0][0][0], &sO[0][0][0] + kMergeChunks * G, sMf, sLf);
+    if (tid == 0) __hip_atomic_store(&p.counters[bg], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // next call
 }
 
-// weights[b,h,j] = exp(s[b,h,j] - lse[b,h]) in place, j < seq_lens[b].
+// Second kernel of a full step that returns the attention weights.  Every workgroup first
+// rebuilds lse of its (sequence, query head) from the per-chunk (max, sum) pairs, in fp64.
+// Workgroup x = 0 then merges the partial outputs of that head; workgroups x >= 1 turn
+// kNormTile raw scores each into weights[b,h,j] = exp(s[b,h,j] - lse[b,h]), in place.  The
+// exponent is formed as an exact fp32 pair (two-sum) minus the low part of lse, so a weight
+// carries the error of its score and of expf only (a plain fp32 subtraction alone would cost
+// up to 5e-7 relative, which is the size of the gaps that decide the selection).
+constexpr int kNormTile = 4096;
+
 __global__ __launch_bounds__(256)
-void normalise_weights_kernel(float* weights, int64_t w_stride, const float* lse, const int32_t* seq_lens,
-                              int32_t max_len, int32_t Hq, const int32_t* pred, int32_t pred_val) {
-    const int b = blockIdx.z, h = blockIdx.y;
-    if (pred != nullptr && pred[b] != pred_val) return;
-    const int len = min(seq_lens[b], max_len);
-    const float l = lse[(int64_t)b * Hq + h];
-    float* row = weights + ((int64_t)b * Hq + h) * w_stride;
-    const int j0 = blockIdx.x * 1024 + threadIdx.x;
+void merge_normalise_kernel(const AttnParams p, int G) {
+    const int x = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    if (p.pred != nullptr && p.pred[b] != p.pred_val) return;
+    const int tid = threadIdx.x;
+    const int g = h / G, gi = h % G;
+    const int len = min(max(min(p.seq_lens[b], p.cap2), 0), p.max_rows2);
+    const int nchunks = max(1, (len + p.chunk - 1) / p.chunk);
+    const int j0 = (x - 1) * kNormTile;
+    if (x >= 1 && j0 >= len) return;
+
+    __shared__ __attribute__((aligned(8))) float sRed[8];
+    __shared__ float sW[kMaxChunks];
+    __shared__ float sLse[2];
+    __shared__ double sL64;
+    __shared__ float sAcc[4][kD];
+
+    const int64_t bg = (int64_t)b * p.Hkv + g;
+    const float* ml = p.part_ml + (bg * kMaxChunks * G + gi) * 2;
+    float m = -INFINITY, l = 0.f;
+    if (tid < nchunks) {                                   // nchunks <= kMaxChunks == blockDim
+        const float2 t2 = *reinterpret_cast<const float2*>(ml + (int64_t)tid * G * 2);
+        m = t2.x; l = t2.y;
+    }
+    const float M = block_max<4>(m, sRed);
+    const float wgt = (m == -INFINITY) ? 0.f : fast_exp2((m - M) * kLog2e);
+    if (tid < nchunks) sW[tid] = wgt;
+    const double L64 = block_sum_f64<4>((double)wgt * (double)l, reinterpret_cast<double*>(sRed));
+    if (tid == 0) {
+        float hi = -INFINITY, lo = 0.f;
+        if (L64 > 0.0) {
+            const double l64 = (double)M + log(L64);
+            hi = (float)l64;
+            lo = (float)(l64 - (double)hi);
+        }
+        sLse[0] = hi; sLse[1] = lo; sL64 = L64;
+    }
+    __syncthreads();
+
+    if (x == 0) {
+        // out[b,h,:] = sum_c w_c o_c[h,:] / L: four groups of 64 lanes take every fourth chunk
+        const int cg = tid >> 6, d2 = tid & 63;
+        const float* po = p.part_o + (bg * p.max_chunks * G + gi) * kD + 2 * d2;
+        float acc0 = 0.f, acc1 = 0.f;
+        constexpr int BATCH = 16;
+        for (int c0 = cg; c0 < nchunks; c0 += 4 * BATCH) {
+            float2 v[BATCH];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int j = j0 + i * 256;
-        if (j < len) row[j] = expf(row[j] - l);
+            for (int u = 0; u < BATCH; ++u) {
+                const int c = min(c0 + 4 * u, nchunks - 1);
+                v[u] = *reinterpret_cast<const float2*>(po + (int64_t)c * G * kD);
+            }
+#pragma unroll
+            for (int u = 0; u < BATCH; ++u) {
+                const float wc = (c0 + 4 * u < nchunks) ? sW[c0 + 4 * u] : 0.f;
+                acc0 = fmaf(wc, v[u].x, acc0);
+                acc1 = fmaf(wc, v[u].y, acc1);
+            }
+        }
+        sAcc[cg][2 * d2] = acc0; sAcc[cg][2 * d2 + 1] = acc1;
+        __syncthreads();
+        if (tid < kD) {
+            const float L = (float)sL64;
+            const float o = L > 0.f ? (sAcc[0][tid] + sAcc[1][tid] + sAcc[2][tid] + sAcc[3][tid]) / L : 0.f;
+            p.out[((int64_t)b * p.Hq + h) * kD + tid] = f32_to_bf16(o);
+        }
+        if (tid == 0) p.lse[(int64_t)b * p.Hq + h] = sLse[0];
+        return;
+    }
+
+    const float nl = -sLse[0], ll = sLse[1];
+    float* row = p.weights + ((int64_t)b * p.Hq + h) * p.w_stride;
+#pragma unroll 4
+    for (int i = 0; i < kNormTile / 256; ++i) {
+        const int j = j0 + i * 256 + tid;
+        if (j < len) {
+            const float s = row[j];
+            const float hi = s + nl;
+            const float bp = hi - s;
+            const float lo = (s - (hi - bp)) + (nl - bp) - ll;     // s - lse = hi + lo, |lo| << 1
+            const float e = expf(hi);
+            row[j] = fmaf(e, lo, e);
+        }
     }
 }
 
@@ -373,14 +506,14 @@ static int launch_split(const AttnParams& p, int batch, int G, int nchunk_grid, 
 
 using namespace rk;
 
-extern "C" int rk_full_attn(const rk_geom* geom, const void* q, rk_kv full,
-                            const int32_t* seq_lens, int32_t max_len,
-                            void* out, float* weights, int64_t w_stride, float* lse,
-                            const int32_t* pred, int32_t pred_val,
-                            void* workspace, size_t workspace_bytes, void* stream) {
+static int full_attn_impl(const rk_geom* geom, const void* q, rk_kv full,
+                          const int32_t* seq_lens, int32_t max_len,
+                          void* out, float* weights, int64_t w_stride, float* lse,
+                          const int32_t* pred, int32_t pred_val,
+                          void* workspace, size_t workspace_bytes, void* stream, bool scores_only) {
     int rc = check_geom(geom);
     if (rc != RK_OK) return rc;
-    if (!q || !out || !seq_lens || max_len <= 0) return RK_ERR_INVALID_ARG;
+    if (!q || (!out && !scores_only) || !seq_lens || max_len <= 0) return RK_ERR_INVALID_ARG;
     if (!aligned16(q) || ((uintptr_t)out & 1u)) return RK_ERR_INVALID_ARG;
     if ((rc = check_kv(full)) != RK_OK) return rc;
     if (weights && (w_stride < max_len || ((uintptr_t)weights & 3u))) return RK_ERR_INVALID_ARG;
@@ -396,7 +529,7 @@ extern "C" int rk_full_attn(const rk_geom* geom, const void* q, rk_kv full,
     p.n_sel = 0;
     p.max_rows2 = max_len;
     p.cap1 = 0; p.cap2 = (int32_t)full.capacity;
-    p.chunk = attn_chunk_rows(max_len, (int64_t)geom->batch * geom->n_kv_heads);
+    p.chunk = attn_chunk_rows(max_len, (int64_t)geom->batch * geom->n_kv_heads, weights ? kMaxChunks : kMergeChunks);
     p.Hq = geom->n_q_heads; p.Hkv = geom->n_kv_heads;
     p.scale = geom->scale;
     p.out = (uint16_t*)out;
@@ -408,13 +541,31 @@ extern "C" int rk_full_attn(const rk_geom* geom, const void* q, rk_kv full,
     hipStream_t st = (hipStream_t)stream;
     if (weights) {
         rc = launch_split<true, false>(p, geom->batch, G, nchunk_grid, st);
-        if (rc != RK_OK) return rc;
-        dim3 grid((max_len + 1023) / 1024, geom->n_q_heads, geom->batch);
-        hipLaunchKernelGGL(normalise_weights_kernel, grid, dim3(256), 0, st, weights, w_stride, p.lse, seq_lens,
-                           max_len, geom->n_q_heads, pred, pred_val);
+        if (rc != RK_OK || scores_only) return rc;
+        dim3 grid(1 + (max_len + kNormTile - 1) / kNormTile, geom->n_q_heads, geom->batch);
+        hipLaunchKernelGGL(merge_normalise_kernel, grid, dim3(256), 0, st, p, G);
         return launch_status();
     }
     return launch_split<false, false>(p, geom->batch, G, nchunk_grid, st);
+}
+
+extern "C" int rk_full_attn(const rk_geom* geom, const void* q, rk_kv full,
+                            const int32_t* seq_lens, int32_t max_len,
+                            void* out, float* weights, int64_t w_stride, float* lse,
+                            const int32_t* pred, int32_t pred_val,
+                            void* workspace, size_t workspace_bytes, void* stream) {
+    return full_attn_impl(geom, q, full, seq_lens, max_len, out, weights, w_stride, lse, pred, pred_val,
+                          workspace, workspace_bytes, stream, false);
+}
+
+extern "C" int rk_full_attn_scores(const rk_geom* geom, const void* q, rk_kv full,
+                                   const int32_t* seq_lens, int32_t max_len,
+                                   float* scores, int64_t s_stride,
+                                   const int32_t* pred, int32_t pred_val,
+                                   void* workspace, size_t workspace_bytes, void* stream) {
+    if (!scores) return RK_ERR_INVALID_ARG;
+    return full_attn_impl(geom, q, full, seq_lens, max_len, nullptr, scores, s_stride, nullptr, pred, pred_val,
+                          workspace, workspace_bytes, stream, true);
 }
 
 extern "C" int rk_partial_attn(const rk_geom* geom, const void* q, rk_kv small, int32_t n_sel,
@@ -445,7 +596,7 @@ extern "C" int rk_partial_attn(const rk_geom* geom, const void* q, rk_kv small, 
     p.n_sel = n_sel;
     p.max_rows2 = max_recent;
     p.cap1 = n_sel > 0 ? (int32_t)small.capacity : 0; p.cap2 = (int32_t)full.capacity;
-    p.chunk = attn_chunk_rows(max_rows, (int64_t)geom->batch * geom->n_kv_heads);
+    p.chunk = attn_chunk_rows(max_rows, (int64_t)geom->batch * geom->n_kv_heads, kMergeChunks);
     p.Hq = geom->n_q_heads; p.Hkv = geom->n_kv_heads;
     p.scale = geom->scale;
     p.out = (uint16_t*)out;

@@ -83,6 +83,21 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
     return r;
 }
 
+// fp64 sum over the workgroup; `red` holds NW doubles.
+template <int NW>
+__device__ __forceinline__ double block_sum_f64(double v, double* red) {
+#pragma unroll
+    for (int m = 1; m < 64; m <<= 1) v += __shfl_xor(v, m);
+    if (NW == 1) return v;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    double r = red[0];
+#pragma unroll
+    for (int i = 1; i < NW; ++i) r += red[i];
+    return r;
+}
+
 // Orders LDS traffic of the lanes of one wavefront: what was written before is visible to
 // every lane after.  Lanes of a wavefront run in lockstep, so no hardware barrier is needed,
 // only the compiler and the LDS queue have to be told.

@@ -11,16 +11,22 @@ namespace rk {
 
 constexpr int kD = RK_HEAD_DIM;          // head_dim
 constexpr int kMinChunk = 64;            // smallest number of KV rows one workgroup reduces
-constexpr int kMaxChunks = 512;          // most partial results one (sequence, KV head) produces
+constexpr int kMaxChunks = 256;          // most partial results one (sequence, KV head) produces
+constexpr int kMergeChunks = 64;         // ... when the split kernel itself merges them
+#ifndef RK_TARGET_WGS
+#define RK_TARGET_WGS 1024               // workgroups a split launch aims for (256 CUs)
+#endif
 
-// Rows per workgroup of the split attention kernels: a power of two in [64, 4096], chosen so
-// that a launch has enough workgroups to fill the chip but no (sequence, KV head) produces
-// more than kMaxChunks partial results.
-static inline int attn_chunk_rows(int64_t max_rows, int64_t n_problems) {
-    const int64_t target_wgs = 1024;
+// Rows per workgroup of the split attention kernels: a power of two >= 64, the smallest for
+// which a launch has at most RK_TARGET_WGS workgroups and no (sequence, KV head) more than
+// `chunk_limit` partial results.  When the last workgroup of a (sequence, KV head) merges the
+// partial results inside the split kernel the limit is kMergeChunks: that many results are
+// fetched in one round trip (64 loads in flight per lane); more would serialise round trips.
+static inline int attn_chunk_rows(int64_t max_rows, int64_t n_problems, int chunk_limit) {
     int64_t chunk = kMinChunk;
-    while (chunk < 4096 && (max_rows + chunk - 1) / chunk * n_problems > target_wgs) chunk *= 2;
-    while ((max_rows + chunk - 1) / chunk > kMaxChunks) chunk *= 2;
+    while ((max_rows + chunk - 1) / chunk > chunk_limit ||
+           ((max_rows + chunk - 1) / chunk * n_problems > RK_TARGET_WGS && (max_rows + chunk - 1) / chunk > 1))
+        chunk *= 2;
     return (int)chunk;
 }
 

@@ -41,6 +41,15 @@ class RefreshKVLayer:
         self.tail_start = seq_lens.clone()
         self.out = torch.empty(B, Hq, D, dtype=torch.bfloat16, device=dev)
         self.recent_bound = 0          # host bound of seq_lens - tail_start
+        self._static = False
+
+    def use_static_bounds(self, max_len: int, max_recent: int) -> None:
+        """Freeze the host-side bounds (grid sizes) so that a step can be captured in a HIP graph
+        and replayed at later steps: max_len bounds seq_lens for the whole run, max_recent bounds
+        the rows decoded between two refreshes.  The kernels read the true lengths on the GPU."""
+        if max_len > self.capacity:
+            raise ValueError("max_len exceeds the cache capacity")
+        self.max_len, self.recent_bound, self._static = int(max_len), int(max_recent), True
 
     # -- cache growth is the caller's copy; this keeps the host bounds in step with it
     def append(self, k_row: torch.Tensor, v_row: torch.Tensor, shared_lens: bool = False) -> None:
@@ -58,8 +67,9 @@ class RefreshKVLayer:
         self.advance()
 
     def advance(self) -> None:
-        self.max_len += 1
-        self.recent_bound += 1
+        if not self._static:
+            self.max_len += 1
+            self.recent_bound += 1
 
     def _full(self, q, out, pred=None, stream=None) -> None:
         g = self.geom
@@ -89,7 +99,8 @@ class RefreshKVLayer:
         if t == 0 or (scheduled and not self.dynamic):
             rk.rk_query_sim(self.geom, q, self.q_ref, self.threshold, True, self.sim, self.need_full, stream=stream)
             self._full(q, out, stream=stream)
-            self.recent_bound = 0
+            if not self._static:
+                self.recent_bound = 0
             return "full"
         if scheduled and self.dynamic:
             rk.rk_query_sim(self.geom, q, self.q_ref, self.threshold, False, self.sim, self.need_full, stream=stream)

@@ -122,6 +122,28 @@ def test_full_attn_predicate_skips_sequences(rk):
     assert (out[1] == gen.bf16_bits(init)[1]).all() and (w[1] == -7.0).all() and (lse[1] == 123.0).all()
 
 
+def test_full_attn_scores_phase_alone(rk):
+    """rk_full_attn_scores: the streaming kernel by itself leaves scale * q.k in the buffer."""
+    say("full_attn_scores")
+    B, Hq, Hkv, cap = 2, 8, 2, 1100
+    lens = [1100, 37]
+    q, K, V = rand_case(33, B, Hq, Hkv, cap)
+    scale = float(np.float32(1 / np.sqrt(128)))
+    geom = rk.Geom(B, Hq, Hkv, 128, scale)
+    ws = rk.Workspace(geom, cap, 16)
+    sc = torch.full((B, Hq, cap), -7.0, dtype=torch.float32, device="cuda")
+    rk.rk_full_attn_scores(geom, q.cuda(), K.cuda(), V.cuda(), torch.tensor(lens, dtype=torch.int32, device="cuda"),
+                           cap, sc, workspace=ws)
+    torch.cuda.synchronize()
+    _, w_ref, lse_ref = oracle.full_attn(gen.bf16_bits(q), gen.bf16_bits(K), gen.bf16_bits(V), lens, scale)
+    got = sc.cpu().numpy()
+    for b in range(B):
+        n = lens[b]
+        s_ref = np.log(w_ref[b, :, :n]) + lse_ref[b][:, None]          # s = ln a + lse
+        assert np.abs(got[b, :, :n] - s_ref).max() < 2e-6
+        assert (got[b, :, n:] == -7.0).all()
+
+
 TOPK_CASES = [
     # name, B, Hq, Hkv, lens, k, pool_w, kind
     ("lognormal_pool7", 2, 8, 2, [5000, 3777], 256, 7, "lognormal"),

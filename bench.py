@@ -206,14 +206,29 @@ def main():
         per_replay.append(ea.elapsed_time(eb) * 1e3 / n_layers)
     split_us = float(np.mean(per_replay))
     n_roof_launches = roof_reps * n_layers
+    # one plain copy of known size: the kernel against which profiler byte counters are scaled
+    cal_src = kv[0][0].view(-1)                          # K of layer 0: B * Hkv * capacity * 256 bytes
+    cal_dst = torch.empty_like(cal_src)
+    calibration_bytes = rk.rk_calibration_copy(cal_dst, cal_src)
+    torch.cuda.synchronize()
+    del cal_dst
     rows = int(seq_lens.sum().item())                    # rows streamed per launch (all sequences)
     bytes_kv = 2 * Hkv * D * 2 * rows                    # K and V rows, bf16
     bytes_w = 4 * Hq * rows                              # raw scores written by the same kernel
     algo_bytes = bytes_kv + bytes_w
     achieved = algo_bytes / (split_us * 1e-6) / 1e9
-    roofline = {"bound": "hbm", "kernel": "rk::attn_split_kernel<%d, 4, 4, true, false> (first kernel of rk_full_attn when weights are returned)" % w.group,
+    # HBM traffic of that kernel from profiler byte counters, when a committed PMC summary exists
+    traffic = None
+    pmc_path = os.path.join(ROOT, "profiles", "bench_%s_pmc.json" % w.name)
+    if os.path.exists(pmc_path):
+        with open(pmc_path) as f:
+            pmc = json.load(f)
+        k = pmc["attn_split"]
+        traffic = int(k["fetch_kib"] * 1024 * pmc["fetch_scale"] + k["write_kib"] * 1024 * pmc["write_scale"])
+    tiles = 2 if w.group <= 4 else 1
+    roofline = {"bound": "hbm", "kernel": "rk::attn_split_kernel<%d, 4, %d, true, false> (first kernel of rk_full_attn when weights are returned)" % (w.group, tiles),
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                 "avg_launch_us": round(split_us, 2), "launches": n_roof_launches, "algorithmic_bytes": algo_bytes}
 
     # ---- CPU oracle on a bounded sample of the same workload ----
@@ -271,6 +286,7 @@ def main():
         "partial_attn_GBps": round(2 * Hkv * D * 2 * (w.k_small + 1) * B / (klass["partial_attn"] * 1e-6) / 1e9, 1),
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "calibration_copy_bytes": calibration_bytes,
         "setup_s": round(setup_s, 1),
     }
     print(json.dumps(result))

@@ -153,9 +153,13 @@ int rk_topk_select(const rk_geom* geom, const float* weights, int64_t w_stride,
 /* Rebuild the small cache: small.k[b,g,i,:] = full.k[b,g,idx[b,g,i],:] and the same for v, for
  * every i < k with idx >= 0 (bit copies).  Slots whose idx is negative are left untouched.
  * A slot whose idx is >= the capacity of `full` is skipped as well.  `small` must hold at least
- * k rows per head and is written through its (const-declared) pointers. */
+ * k rows per head and is written through its (const-declared) pointers.
+ * Refresh bookkeeping in the same launch: when tail_start is not NULL (seq_lens then required),
+ * tail_start[b] = seq_lens[b] for every sequence the predicate selects, i.e. the rows "decoded
+ * since the refresh" start at the current length (what rk_mark_refresh does on its own). */
 int rk_gather_small_kv(const rk_geom* geom, rk_kv full, const int32_t* idx, int32_t k,
-                       rk_kv small, const int32_t* pred, int32_t pred_val, void* stream);
+                       rk_kv small, const int32_t* seq_lens, int32_t* tail_start,
+                       const int32_t* pred, int32_t pred_val, void* stream);
 
 /* Partial-attention decode step: the softmax attention of rk_full_attn, but over the row list
  *   small rows 0 .. min(n_sel, tail_start[b]) - 1, then
@@ -182,6 +186,12 @@ int rk_partial_attn(const rk_geom* geom, const void* q, rk_kv small, int32_t n_s
  * first step) so that the reference follows the most recent full step. */
 int rk_query_sim(const rk_geom* geom, const void* q, float* q_ref, float threshold,
                  int32_t force_full, float* sim, int32_t* need_full, void* stream);
+
+/* Plain device-to-device copy of `bytes` bytes (a multiple of 16; both pointers 16-byte aligned)
+ * with 16-byte loads and stores, one launch.  It exists so that a profiler run of the benchmark
+ * holds a kernel whose HBM traffic is known exactly (bytes read + bytes written), against which
+ * the byte counters read for the attention kernels are scaled. */
+int rk_calibration_copy(void* dst, const void* src, size_t bytes, void* stream);
 
 /* Bookkeeping of a refresh: tail_start[b] = seq_lens[b] for every sequence the predicate
  * selects (all when pred is NULL).  After a full step + refresh the rows "decoded since the

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(HERE, "librefreshkv.so")
 
 EXPORTS = ["rk_version", "rk_status_string", "rk_workspace_bytes", "rk_workspace_init",
            "rk_full_attn", "rk_full_attn_scores", "rk_topk_select", "rk_gather_small_kv", "rk_partial_attn",
-           "rk_query_sim", "rk_mark_refresh"]
+           "rk_query_sim", "rk_mark_refresh", "rk_calibration_copy"]
 
 RK_AGG_MAX = 0
 
@@ -60,11 +60,13 @@ def _load(path: str = LIB_PATH) -> C.CDLL:
     l.rk_topk_select.restype = C.c_int
     l.rk_topk_select.argtypes = [G, P, I64, P, I32, I32, I32, I32, P, P, P, I32, P, SZ, P]
     l.rk_gather_small_kv.restype = C.c_int
-    l.rk_gather_small_kv.argtypes = [G, _Kv, P, I32, _Kv, P, I32, P]
+    l.rk_gather_small_kv.argtypes = [G, _Kv, P, I32, _Kv, P, P, P, I32, P]
     l.rk_partial_attn.restype = C.c_int
     l.rk_partial_attn.argtypes = [G, P, _Kv, I32, _Kv, P, P, I32, P, P, I32, P, SZ, P]
     l.rk_query_sim.restype = C.c_int
     l.rk_query_sim.argtypes = [G, P, P, C.c_float, I32, P, P, P]
+    l.rk_calibration_copy.restype = C.c_int
+    l.rk_calibration_copy.argtypes = [P, P, SZ, P]
     l.rk_mark_refresh.restype = C.c_int
     l.rk_mark_refresh.argtypes = [G, P, P, P, I32, P]
     return l
@@ -210,12 +212,14 @@ def rk_topk_select(geom: Geom, weights, seq_lens, max_len: int, k: int, pool_w: 
         workspace.ptr, workspace.nbytes, _stream(stream)))
 
 
-def rk_gather_small_kv(geom: Geom, K, V, idx, k: int, small_K, small_V, pred=None, pred_val: int = 0,
-                       stream=None) -> None:
+def rk_gather_small_kv(geom: Geom, K, V, idx, k: int, small_K, small_V, seq_lens=None, tail_start=None,
+                       pred=None, pred_val: int = 0, stream=None) -> None:
     B, Hkv = geom.batch, geom.n_kv_heads
     _check("rk_gather_small_kv", lib.rk_gather_small_kv(
         C.byref(geom.c()), _kv(geom, K, V, "full"), _dev(idx, torch.int32, "idx", (B, Hkv, k)), int(k),
         _kv(geom, small_K, small_V, "small", min_rows=k),
+        _dev(seq_lens, torch.int32, "seq_lens", (B,), optional=True),
+        _dev(tail_start, torch.int32, "tail_start", (B,), optional=True),
         _dev(pred, torch.int32, "pred", (B,), optional=True), int(pred_val), _stream(stream)))
 
 
@@ -246,3 +250,15 @@ def rk_mark_refresh(geom: Geom, seq_lens, tail_start, pred=None, pred_val: int =
         C.byref(geom.c()), _dev(seq_lens, torch.int32, "seq_lens", (B,)),
         _dev(tail_start, torch.int32, "tail_start", (B,)),
         _dev(pred, torch.int32, "pred", (B,), optional=True), int(pred_val), _stream(stream)))
+
+
+def rk_calibration_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> int:
+    """Copies src to dst (same byte size, contiguous GPU tensors); returns the bytes copied."""
+    for t, n in ((dst, "dst"), (src, "src")):
+        if not isinstance(t, torch.Tensor) or not t.is_cuda or not t.is_contiguous():
+            raise ValueError("%s must be a contiguous tensor in GPU memory" % n)
+    nbytes = src.numel() * src.element_size()
+    if nbytes != dst.numel() * dst.element_size():
+        raise ValueError("dst and src must have the same size in bytes")
+    _check("rk_calibration_copy", lib.rk_calibration_copy(dst.data_ptr(), src.data_ptr(), nbytes, _stream(stream)))
+    return nbytes

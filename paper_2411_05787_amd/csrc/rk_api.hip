@@ -27,12 +27,24 @@ __global__ void zero_words_kernel(int32_t* p, size_t n) {
     const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = 0;
 }
+__global__ __launch_bounds__(256) void calibration_copy_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+
 __global__ void mark_refresh_kernel(const int32_t* seq_lens, int32_t* tail_start, int32_t batch,
                                     const int32_t* pred, int32_t pred_val) {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b < batch && (pred == nullptr || pred[b] == pred_val)) tail_start[b] = seq_lens[b];
 }
 }  // namespace rk
+
+extern "C" int rk_calibration_copy(void* dst, const void* src, size_t bytes, void* stream) {
+    if (!dst || !src || bytes == 0 || bytes % 16 != 0 || !aligned16(dst) || !aligned16(src)) return RK_ERR_INVALID_ARG;
+    const size_t n = bytes / 16;
+    const unsigned grid = (unsigned)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096);
+    hipLaunchKernelGGL(calibration_copy_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, (uint4*)dst, (const uint4*)src, n);
+    return launch_status();
+}
 
 extern "C" int rk_mark_refresh(const rk_geom* geom, const int32_t* seq_lens, int32_t* tail_start,
                                const int32_t* pred, int32_t pred_val, void* stream) {
@@ -45,7 +57,7 @@ extern "C" int rk_mark_refresh(const rk_geom* geom, const int32_t* seq_lens, int
 extern "C" int rk_workspace_init(const rk_geom* geom, void* workspace, size_t workspace_bytes, void* stream) {
     if (check_geom(geom) != RK_OK) return RK_ERR_INVALID_ARG;
     if (!workspace || ((uintptr_t)workspace & 255u) != 0) return RK_ERR_WORKSPACE;
-    const size_t n = (size_t)geom->batch * geom->n_kv_heads;     // one arrival counter each
+    const size_t n = zeroed_words(geom);     // arrival counters, candidate counters, histograms
     if (workspace_bytes < align_up(n * sizeof(int32_t), 256)) return RK_ERR_WORKSPACE;
     hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
                        (int32_t*)workspace, n);

@@ -16,9 +16,12 @@
 //   S = Q K^T on the matrix cores: v_mfma_f32_16x16x32_bf16, M = query heads (padded to 16),
 //             N = 16 rows, contraction over head_dim in 4 steps
 //   softmax bookkeeping (running max / sum) on the lanes that hold S
-//   P (and the raw scores when they are returned) cross to the V layout through LDS
+//   P crosses to the V layout through LDS; raw scores (when weights are returned) are stored
+//             straight from the S layout
 //   O += P V on the vector ALU: each lane owns 8 consecutive dims of one row in four,
 //             V rows loaded with fully coalesced 16-byte loads
+// The K and V registers are double-buffered: the loads of a wavefront's next tile are issued
+// before the current tile is computed.
 #include "rk_internal.h"
 #include "rk_device.h"
 
@@ -61,22 +64,42 @@ template <int G, int NW>
 __device__ void merge_partials(const AttnParams& p, int b, int g, int nchunks, float* sW, float* sLc,
                                float* sM, double* sL) {
     constexpr int NT = NW * 64;
-    constexpr int BATCH = kMergeChunks;           // coherent loads in flight per thread: all of them
+    constexpr int PER = G * kD / 2;               // pairs of consecutive dims to produce
+    constexpr int ROUNDS = (PER + NT - 1) / NT;   // per thread: 1 (G <= 4) or 2
+    constexpr int SUB = 16;                       // loads are issued in uniform groups of 16 chunks
+    static_assert(kMergeChunks % SUB == 0, "chunk groups");
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int64_t bg = (int64_t)b * p.Hkv + g;
     const float* ml = p.part_ml + bg * kMaxChunks * G * 2;
     const float* po = p.part_o + bg * p.max_chunks * G * kD;
-    // (max, sum) of every chunk and head: one round trip to memory, then everything is in LDS
     const int n_ml = nchunks * G;
-    for (int i0 = 0; i0 < n_ml; i0 += NT * 4) {
-        uint64_t v[4];
+
+    // Everything that has to come from memory is requested up front, in one round trip:
+    // the (max, sum) pairs of every chunk and head, and this thread's slice of every partial output.
+    uint64_t vml[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) v[u] = coherent_load2(ml + (int64_t)min(i0 + u * NT + tid, n_ml - 1) * 2);
+    for (int u = 0; u < 4; ++u) vml[u] = coherent_load2(ml + (int64_t)min(u * NT + tid, n_ml - 1) * 2);
+    uint64_t v[kMergeChunks];
+    auto request = [&](int r) {
+        const int e2 = min(r * NT + tid, PER - 1);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const int i = i0 + u * NT + tid;
-            if (i < n_ml) { sW[i] = lo_f(v[u]); sLc[i] = hi_f(v[u]); }
+        for (int c0 = 0; c0 < kMergeChunks; c0 += SUB) {
+            if (c0 < nchunks) {                   // uniform over the workgroup
+#pragma unroll
+                for (int u = 0; u < SUB; ++u)
+                    v[c0 + u] = coherent_load2(po + (int64_t)min(c0 + u, nchunks - 1) * G * kD + 2 * e2);
+            } else {
+#pragma unroll
+                for (int u = 0; u < SUB; ++u) v[c0 + u] = 0;
+            }
         }
+    };
+    request(0);
+    static_assert(4 * NT >= kMergeChunks * RK_MAX_GROUP || NW < 4, "one batch covers all (chunk, head) pairs");
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int i = u * NT + tid;
+        if (i < n_ml) { sW[i] = lo_f(vml[u]); sLc[i] = hi_f(vml[u]); }
     }
     __syncthreads();
     // one wavefront per head: M = max_c m_c, w_c = e^{m_c - M} (overwrites m_c), L = sum_c w_c l_c
@@ -84,7 +107,7 @@ __device__ void merge_partials(const AttnParams& p, int b, int g, int nchunks, f
         float mx = -INFINITY;
         for (int c = lane; c < nchunks; c += 64) mx = fmaxf(mx, sW[c * G + gi]);
         mx = wave_max(mx);
-        double ls = 0.0;                          // the sum that normalises every weight: fp64
+        double ls = 0.0;                          // the sum that normalises the output: fp64
         for (int c = lane; c < nchunks; c += 64) {
             const float mc = sW[c * G + gi];
             const float wgt = (mc == -INFINITY) ? 0.f : fast_exp2((mc - mx) * kLog2e);
@@ -96,27 +119,24 @@ __device__ void merge_partials(const AttnParams& p, int b, int g, int nchunks, f
         if (lane == 0) { sM[gi] = mx; sL[gi] = ls; }
     }
     __syncthreads();
-    for (int e2 = tid; e2 < G * kD / 2; e2 += NT) {          // two consecutive dims per thread
-        const int gi = (2 * e2) / kD;
-        float acc0 = 0.f, acc1 = 0.f;
-        for (int c0 = 0; c0 < nchunks; c0 += BATCH) {
-            uint64_t v[BATCH];
 #pragma unroll
-            for (int u = 0; u < BATCH; ++u) {
-                const int c = min(c0 + u, nchunks - 1);
-                v[u] = coherent_load2(po + (int64_t)c * G * kD + 2 * e2);
-            }
+    for (int r = 0; r < ROUNDS; ++r) {
+        if (r > 0) request(r);                    // G > 4: a second round trip for the other half
+        const int e2 = r * NT + tid;
+        if (e2 < PER) {
+            const int gi = (2 * e2) / kD;
+            float acc0 = 0.f, acc1 = 0.f;
 #pragma unroll
-            for (int u = 0; u < BATCH; ++u) {
-                const float wgt = (c0 + u < nchunks) ? sW[(c0 + u) * G + gi] : 0.f;
-                acc0 = fmaf(wgt, lo_f(v[u]), acc0);
-                acc1 = fmaf(wgt, hi_f(v[u]), acc1);
+            for (int c = 0; c < kMergeChunks; ++c) {
+                const float wgt = (c < nchunks) ? sW[c * G + gi] : 0.f;
+                acc0 = fmaf(wgt, lo_f(v[c]), acc0);
+                acc1 = fmaf(wgt, hi_f(v[c]), acc1);
             }
+            const float L = (float)sL[gi];
+            const float inv = L > 0.f ? 1.f / L : 0.f;
+            const uint32_t packed = (uint32_t)f32_to_bf16(acc0 * inv) | ((uint32_t)f32_to_bf16(acc1 * inv) << 16);
+            reinterpret_cast<uint32_t*>(p.out + ((int64_t)b * p.Hq + g * G) * kD)[e2] = packed;
         }
-        const float L = (float)sL[gi];
-        const float inv = L > 0.f ? 1.f / L : 0.f;
-        const uint32_t packed = (uint32_t)f32_to_bf16(acc0 * inv) | ((uint32_t)f32_to_bf16(acc1 * inv) << 16);
-        reinterpret_cast<uint32_t*>(p.out + ((int64_t)b * p.Hq + g * G) * kD)[e2] = packed;
     }
     if (tid < G) {
         const double L = sL[tid];
@@ -124,8 +144,9 @@ __device__ void merge_partials(const AttnParams& p, int b, int g, int nchunks, f
     }
 }
 
+// Two wavefronts per SIMD (<= 256 registers each) whenever the accumulators leave room for it.
 template <int G, int NW, int TILES, bool EMIT, bool TWO_SEG>
-__global__ __launch_bounds__(NW * 64)
+__global__ __launch_bounds__(NW * 64, (G <= 4 || TILES == 1) ? 2 : 1)
 void attn_split_kernel(const AttnParams p) {
     constexpr int GP = (G + 3) / 4 * 4;      // heads padded to whole MFMA accumulator registers
     constexpr int NC = GP / 4;               // 16-lane groups whose accumulators hold real heads
@@ -140,6 +161,25 @@ void attn_split_kernel(const AttnParams p) {
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int n16 = lane & 15, c4 = lane >> 4;     // S layout: row n16, heads 4*c4 .. 4*c4+3
     const int db = lane & 15, rg = lane >> 4;      // V layout: dims 8*db .. 8*db+7, rows = rg mod 4
+
+    // ---- K rows of the first tile are requested before any length is known ----
+    // Rows below `spec_rows` exist whatever the device-side lengths say (small cache: the first
+    // n_sel rows; full cache: its capacity), so a chunk that lies wholly below it may be read
+    // at once; rows that turn out to be past the end are masked like any other.  This takes the
+    // round trip for seq_lens / tail_start off the critical path of every workgroup.
+    const int r_first = c * p.chunk + w * ROWS;
+    const int spec_rows = TWO_SEG ? min(p.n_sel, p.cap1) : p.cap2;
+    const bool spec = (int64_t)(c + 1) * p.chunk <= spec_rows;
+    uint4 kA[TILES][4], vA[NV], kB[TILES][4], vB[NV];
+    if (spec) {
+        const uint16_t* kspec = (TWO_SEG ? p.k1 + (int64_t)b * p.s1_b + (int64_t)g * p.s1_h
+                                         : p.k2 + (int64_t)b * p.s2_b + (int64_t)g * p.s2_h) + c4 * 8;
+#pragma unroll
+        for (int t = 0; t < TILES; ++t)
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+                kA[t][kk] = *reinterpret_cast<const uint4*>(kspec + (int64_t)(r_first + t * 16 + n16) * kD + kk * 32);
+    }
 
     // ---- the row list of this (sequence, KV head) ----
     // (device-side lengths are clamped to the allocated rows: no access leaves the caches)
@@ -168,7 +208,6 @@ void attn_split_kernel(const AttnParams p) {
     const uint16_t* vb2 = p.v2 + (int64_t)b * p.s2_b + (int64_t)g * p.s2_h + (int64_t)(start2 - n1) * kD;
 
     __shared__ __attribute__((aligned(16))) float sP[NW][ROWS][GP];
-    __shared__ __attribute__((aligned(16))) float sS[EMIT ? NW : 1][EMIT ? ROWS : 1][GP];
     __shared__ __attribute__((aligned(16))) float sAlpha[NW][GP];
     __shared__ __attribute__((aligned(16))) float sMw[NW][GP];
     __shared__ __attribute__((aligned(16))) float sLw[NW][GP];
@@ -199,9 +238,8 @@ void attn_split_kernel(const AttnParams p) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) o[gi][e] = 0.f;
 
-    for (int r = row0 + w * ROWS; r < row1; r += NW * ROWS) {
-        // ---- loads: rows past the end of the chunk re-read its last row (masked below) ----
-        uint4 kreg[TILES][4];
+    // ---- loads: rows past the end of the chunk re-read its last row (masked later) ----
+    auto load_k = [&](uint4 (&kreg)[TILES][4], int r) {
 #pragma unroll
         for (int t = 0; t < TILES; ++t) {
             const int row = min(r + t * 16 + n16, row1 - 1);
@@ -210,14 +248,16 @@ void attn_split_kernel(const AttnParams p) {
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk) kreg[t][kk] = *reinterpret_cast<const uint4*>(rp + kk * 32);
         }
-        uint4 vreg[NV];
+    };
+    auto load_v = [&](uint4 (&vreg)[NV], int r) {
 #pragma unroll
         for (int jj = 0; jj < NV; ++jj) {
             const int row = min(r + jj * 4 + rg, row1 - 1);
             const uint16_t* base = (TWO_SEG && row < n1) ? vb1 : vb2;
             vreg[jj] = *reinterpret_cast<const uint4*>(base + (int64_t)row * kD + db * 8);
         }
-
+    };
+    auto compute_tile = [&](uint4 (&kreg)[TILES][4], uint4 (&vreg)[NV], int r) {
         // ---- S = Q K^T: lane (n16, c4) gets heads 4*c4+i of row r + 16 t + n16 ----
         float s[TILES][4];
 #pragma unroll
@@ -230,6 +270,22 @@ void attn_split_kernel(const AttnParams p) {
             const bool valid = (r + t * 16 + n16) < row1;
 #pragma unroll
             for (int i = 0; i < 4; ++i) s[t][i] = valid ? acc[i] * p.scale : -INFINITY;
+        }
+
+        // ---- raw scores out, straight from the lanes that hold them: 16 consecutive rows of one
+        //      head are a 64-byte segment ----
+        if (EMIT) {
+            if (c4 < NC) {
+                float* wrow = p.weights + ((int64_t)b * p.Hq + (int64_t)g * G + c4 * 4) * p.w_stride + r + n16;
+#pragma unroll
+                for (int t = 0; t < TILES; ++t) {
+                    if (r + t * 16 + n16 < row1) {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            if (c4 * 4 + i < G) wrow[(int64_t)i * p.w_stride + t * 16] = s[t][i];
+                    }
+                }
+            }
         }
 
         // ---- running softmax statistics of this wavefront ----
@@ -256,29 +312,11 @@ void attn_split_kernel(const AttnParams p) {
             for (int t = 0; t < TILES; ++t) {
                 *reinterpret_cast<float4*>(&sP[w][t * 16 + n16][c4 * 4]) =
                     make_float4(pr[t][0], pr[t][1], pr[t][2], pr[t][3]);
-                if (EMIT)
-                    *reinterpret_cast<float4*>(&sS[w][t * 16 + n16][c4 * 4]) =
-                        make_float4(s[t][0], s[t][1], s[t][2], s[t][3]);
             }
             if (n16 == 0)
                 *reinterpret_cast<float4*>(&sAlpha[w][c4 * 4]) = make_float4(alpha[0], alpha[1], alpha[2], alpha[3]);
         }
         wave_lds_sync();
-
-        // ---- raw scores out, one row per lane: 256-byte stores per head ----
-        if (EMIT) {
-            if (lane < ROWS && r + lane < row1) {
-                float sv[GP];
-#pragma unroll
-                for (int q4 = 0; q4 < NC; ++q4) {
-                    const float4 t4 = *reinterpret_cast<const float4*>(&sS[w][lane][q4 * 4]);
-                    sv[q4 * 4 + 0] = t4.x; sv[q4 * 4 + 1] = t4.y; sv[q4 * 4 + 2] = t4.z; sv[q4 * 4 + 3] = t4.w;
-                }
-                float* wrow = p.weights + ((int64_t)b * p.Hq + (int64_t)g * G) * p.w_stride + r + lane;
-#pragma unroll
-                for (int gi = 0; gi < G; ++gi) wrow[(int64_t)gi * p.w_stride] = sv[gi];
-            }
-        }
 
         // ---- O = alpha O + P V ----
         {
@@ -309,7 +347,30 @@ void attn_split_kernel(const AttnParams p) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) o[gi][e] = fmaf(pv[gi], vf[e], o[gi][e]);
         }
-        wave_lds_sync();      // sP / sAlpha are rewritten by the next iteration
+        wave_lds_sync();      // sP / sAlpha are rewritten by the next tile
+    };
+
+    // Two register buffers: the loads of the next tile are in flight while this one is computed,
+    // so a wavefront never stops requesting memory while it has rows left.
+    {
+        const int step = NW * ROWS;
+        int r = r_first;
+        if (r < row1) {
+            // the early request stands unless part of this chunk maps to the tail of the full cache
+            const bool spec_ok = spec && (!TWO_SEG || (c + 1) * p.chunk <= n1);
+            if (!spec_ok) load_k(kA, r);
+            load_v(vA, r);
+        }
+        while (r < row1) {
+            const int rn = r + step;
+            if (rn < row1) { load_k(kB, rn); load_v(vB, rn); }
+            compute_tile(kA, vA, r);
+            if (rn >= row1) break;
+            const int rnn = rn + step;
+            if (rnn < row1) { load_k(kA, rnn); load_v(vA, rnn); }
+            compute_tile(kB, vB, rn);
+            r = rnn;
+        }
     }
 
     // ---- wavefront results to LDS ----
@@ -404,14 +465,35 @@ void merge_normalise_kernel(const AttnParams p, int G) {
     __shared__ float sLse[2];
     __shared__ double sL64;
     __shared__ float sAcc[4][kD];
+    constexpr int PER = kNormTile / 256;         // scores per thread
+    constexpr int BATCH = 16;                    // partial outputs per thread and round trip
 
     const int64_t bg = (int64_t)b * p.Hkv + g;
     const float* ml = p.part_ml + (bg * kMaxChunks * G + gi) * 2;
+    float* row = p.weights + ((int64_t)b * p.Hq + h) * p.w_stride;
+    const int cg = tid >> 6, d2 = tid & 63;
+    const float* po = p.part_o + (bg * p.max_chunks * G + gi) * kD + 2 * d2;
+
+    // ---- request everything this workgroup needs before the first wait ----
     float m = -INFINITY, l = 0.f;
     if (tid < nchunks) {                                   // nchunks <= kMaxChunks == blockDim
         const float2 t2 = *reinterpret_cast<const float2*>(ml + (int64_t)tid * G * 2);
         m = t2.x; l = t2.y;
     }
+    float sc[PER];
+    float2 v[BATCH];
+    if (x >= 1) {
+#pragma unroll
+        for (int i = 0; i < PER; ++i) {
+            const int j = j0 + i * 256 + tid;
+            sc[i] = (j < len) ? row[j] : 0.f;
+        }
+    } else {
+#pragma unroll
+        for (int u = 0; u < BATCH; ++u) v[u] = *reinterpret_cast<const float2*>(po + (int64_t)min(cg + 4 * u, nchunks - 1) * G * kD);
+    }
+
+    // ---- lse of (b, h) in fp64 ----
     const float M = block_max<4>(m, sRed);
     const float wgt = (m == -INFINITY) ? 0.f : fast_exp2((m - M) * kLog2e);
     if (tid < nchunks) sW[tid] = wgt;
@@ -429,16 +511,12 @@ void merge_normalise_kernel(const AttnParams p, int G) {
 
     if (x == 0) {
         // out[b,h,:] = sum_c w_c o_c[h,:] / L: four groups of 64 lanes take every fourth chunk
-        const int cg = tid >> 6, d2 = tid & 63;
-        const float* po = p.part_o + (bg * p.max_chunks * G + gi) * kD + 2 * d2;
         float acc0 = 0.f, acc1 = 0.f;
-        constexpr int BATCH = 16;
         for (int c0 = cg; c0 < nchunks; c0 += 4 * BATCH) {
-            float2 v[BATCH];
+            if (c0 != cg) {
 #pragma unroll
-            for (int u = 0; u < BATCH; ++u) {
-                const int c = min(c0 + 4 * u, nchunks - 1);
-                v[u] = *reinterpret_cast<const float2*>(po + (int64_t)c * G * kD);
+                for (int u = 0; u < BATCH; ++u)
+                    v[u] = *reinterpret_cast<const float2*>(po + (int64_t)min(c0 + 4 * u, nchunks - 1) * G * kD);
             }
 #pragma unroll
             for (int u = 0; u < BATCH; ++u) {
@@ -459,12 +537,11 @@ void merge_normalise_kernel(const AttnParams p, int G) {
     }
 
     const float nl = -sLse[0], ll = sLse[1];
-    float* row = p.weights + ((int64_t)b * p.Hq + h) * p.w_stride;
-#pragma unroll 4
-    for (int i = 0; i < kNormTile / 256; ++i) {
+#pragma unroll
+    for (int i = 0; i < PER; ++i) {
         const int j = j0 + i * 256 + tid;
         if (j < len) {
-            const float s = row[j];
+            const float s = sc[i];
             const float hi = s + nl;
             const float bp = hi - s;
             const float lo = (s - (hi - bp)) + (nl - bp) - ll;     // s - lse = hi + lo, |lo| << 1
@@ -477,10 +554,12 @@ void merge_normalise_kernel(const AttnParams p, int G) {
 template <int G, bool EMIT, bool TWO_SEG>
 static int launch_split_g(const AttnParams& p, int batch, int nchunk_grid, hipStream_t st) {
     dim3 grid(nchunk_grid, p.Hkv, batch);
-    if (p.chunk >= 256) {
-        hipLaunchKernelGGL((attn_split_kernel<G, 4, 4, EMIT, TWO_SEG>), grid, dim3(256), 0, st, p);
-    } else if (p.chunk >= 128) {
-        hipLaunchKernelGGL((attn_split_kernel<G, 4, 2, EMIT, TWO_SEG>), grid, dim3(256), 0, st, p);
+#ifndef RK_BIG_TILES
+#define RK_BIG_TILES 2
+#endif
+    if (p.chunk >= 128) {       // 32 rows per wavefront and tile (16 for the larger groups, whose
+                                // accumulators take the registers); >= 2 tiles per wavefront from chunk 256 up
+        hipLaunchKernelGGL((attn_split_kernel<G, 4, (G <= 4 ? RK_BIG_TILES : 1), EMIT, TWO_SEG>), grid, dim3(256), 0, st, p);
     } else {
         hipLaunchKernelGGL((attn_split_kernel<G, 4, 1, EMIT, TWO_SEG>), grid, dim3(256), 0, st, p);
     }

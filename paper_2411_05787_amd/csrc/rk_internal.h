@@ -14,39 +14,63 @@ constexpr int kMinChunk = 64;            // smallest number of KV rows one workg
 constexpr int kMaxChunks = 256;          // most partial results one (sequence, KV head) produces
 constexpr int kMergeChunks = 64;         // ... when the split kernel itself merges them
 #ifndef RK_TARGET_WGS
-#define RK_TARGET_WGS 1024               // workgroups a split launch aims for (256 CUs)
+#define RK_TARGET_WGS 512                // workgroups a split launch aims for (2 per CU, all resident)
 #endif
 
-// Rows per workgroup of the split attention kernels: a power of two >= 64, the smallest for
-// which a launch has at most RK_TARGET_WGS workgroups and no (sequence, KV head) more than
-// `chunk_limit` partial results.  When the last workgroup of a (sequence, KV head) merges the
-// partial results inside the split kernel the limit is kMergeChunks: that many results are
-// fetched in one round trip (64 loads in flight per lane); more would serialise round trips.
+// Rows per workgroup of the split attention kernels: a power of two >= 64.  No (sequence, KV
+// head) may produce more than `chunk_limit` partial results; within that, the largest chunk that
+// still gives the launch at least RK_TARGET_WGS workgroups (fewer, larger chunks mean fewer
+// partial results to merge, but below two workgroups per CU the chip is no longer kept busy).
+// When the last workgroup of a (sequence, KV head) merges the partial results inside the split
+// kernel the limit is kMergeChunks: that many results are fetched in one round trip.
 static inline int attn_chunk_rows(int64_t max_rows, int64_t n_problems, int chunk_limit) {
+    auto nch = [&](int64_t chunk) { return (max_rows + chunk - 1) / chunk; };
     int64_t chunk = kMinChunk;
-    while ((max_rows + chunk - 1) / chunk > chunk_limit ||
-           ((max_rows + chunk - 1) / chunk * n_problems > RK_TARGET_WGS && (max_rows + chunk - 1) / chunk > 1))
-        chunk *= 2;
+    while (nch(chunk) > chunk_limit) chunk *= 2;
+    while (nch(2 * chunk) * n_problems >= RK_TARGET_WGS) chunk *= 2;
     return (int)chunk;
 }
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-// Device workspace, carved in this order (every region 256-byte aligned):
+constexpr int kHistBins = 2048;          // first-level histogram of the selection: top 11 key bits
+constexpr int kMaxCandidates = 16384;    // most candidates the fast selection path sorts in LDS
+
+// Candidate slots per (sequence, KV head) of the selection: the K winners plus the rest of the
+// histogram bin that holds the K-th score.
+static inline int topk_cand_cap(int64_t k) {
+    int64_t c = 1024;
+    while (c < 2 * k && c < kMaxCandidates) c *= 2;
+    return (int)c;
+}
+
+// Device workspace, carved in this order (every region 256-byte aligned).  The first two
+// regions must be zero whenever no call is in flight: rk_workspace_init clears them once and
+// the kernels that use them leave them cleared.
 //   counters  int32 [B*Hkv]                  arrival tickets of the split attention kernel
+//   hist      uint32 [B*Hkv][kHistBins]      first-level histogram of the pooled scores
 //   lse       fp32  [B*Hq]                   log-sum-exp when the caller does not ask for it
 //   part_ml   fp32  [B*Hkv][kMaxChunks][G][2] running max and sum of every partial result
 //   part_o    fp32  [B*Hkv][nch][G][128]     unnormalised partial outputs
-//   pooled    fp32  [B*Hkv][max_len]         group-max, pooled scores of the selection
+//   pooled    fp32  [B*Hkv][max_len up to a multiple of 4]   group-max, pooled scores of the selection
 struct Workspace {
     int32_t* counters;
+    uint32_t* hist;
     float* lse;
     float* part_ml;
     float* part_o;
     float* pooled;
+    int cand_cap;         // candidate slots the selection sorts in LDS
     int max_chunks;       // nch above
     size_t total;
 };
+
+// Row stride of the pooled-score area: rows are read with 16-byte loads.
+static inline int64_t pooled_row_stride(int64_t max_len) { return (max_len + 3) / 4 * 4; }
+
+static inline size_t zeroed_words(const rk_geom* g) {
+    return (size_t)g->batch * g->n_kv_heads * (1 + (size_t)kHistBins);
+}
 
 static inline int max_chunks_for(int64_t max_len) {
     int64_t n = (max_len + kMinChunk - 1) / kMinChunk;
@@ -55,18 +79,22 @@ static inline int max_chunks_for(int64_t max_len) {
     return (int)n;
 }
 
-static inline Workspace carve(const rk_geom* g, int64_t max_len, int64_t /*max_k*/, void* base) {
+static inline Workspace carve(const rk_geom* g, int64_t max_len, int64_t max_k, void* base) {
     Workspace w;
     const size_t problems = (size_t)g->batch * g->n_kv_heads;
     const size_t G = (size_t)(g->n_q_heads / g->n_kv_heads);
     w.max_chunks = max_chunks_for(max_len);
     char* p = (char*)base;
     size_t off = 0;
-    w.counters = (int32_t*)(p + off); off += align_up(problems * sizeof(int32_t), 256);
+    // the two zero-kept regions are contiguous (no padding between them)
+    w.counters = (int32_t*)(p + off); off += problems * sizeof(int32_t);
+    w.hist = (uint32_t*)(p + off);    off += problems * kHistBins * sizeof(uint32_t);
+    off = align_up(off, 256);
     w.lse = (float*)(p + off);        off += align_up((size_t)g->batch * g->n_q_heads * sizeof(float), 256);
     w.part_ml = (float*)(p + off);    off += align_up(problems * kMaxChunks * G * 2 * sizeof(float), 256);
     w.part_o = (float*)(p + off);     off += align_up(problems * w.max_chunks * G * kD * sizeof(float), 256);
-    w.pooled = (float*)(p + off);     off += align_up(problems * (size_t)(max_len > 0 ? max_len : 1) * sizeof(float), 256);
+    w.pooled = (float*)(p + off);     off += align_up(problems * (size_t)pooled_row_stride(max_len > 0 ? max_len : 1) * sizeof(float), 256);
+    w.cand_cap = topk_cand_cap(max_k > 0 ? max_k : 1);
     w.total = off;
     return w;
 }

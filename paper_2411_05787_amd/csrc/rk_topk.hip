@@ -1,13 +1,26 @@
 // rk_topk_select for gfx950: group max + max-pool, then an exact, tie-correct top-K.
 //
-// Kernel 1 (whole chip): P[j] = max over the G heads of the group and over the pooling window
-//   of the attention weights, staged through LDS so that every weight is read once.
-// Kernel 2 (one workgroup per (sequence, KV head)): radix select on the order-preserving
-//   32-bit image of P (three histogram passes: 11 + 11 + 10 bits) finds the K-th largest value
-//   T exactly; every position with P > T is taken, positions with P == T are taken in
-//   ascending position until K are reached; the winners are then sorted in LDS (bitonic) on
-//   the 64-bit key (P image, ~position), which is the required order: score descending, equal
-//   scores by ascending position.  Integer comparisons only: the result is exact.
+// The order is decided on the order-preserving 32-bit image of the pooled score P (integer
+// compares only, so the result is exact): larger image first, equal images by lower position.
+//
+// Kernel 1, whole chip (pool_hist_kernel): P[j] = max over the G heads of the group and over the
+//   pooling window, staged through LDS so that every weight is read once; P is stored and its
+//   top 11 image bits are histogrammed (LDS, then one global atomic per non-empty bin).
+// Kernel 2, one workgroup of 1024 threads per (sequence, KV head) (select_kernel): finds, from
+//   the histogram, the bin b1 that holds the K-th largest score; every position in that bin or a
+//   higher one is a candidate (the K winners plus the rest of one bin).  The candidates are
+//   bucket-sorted in LDS on the 64-bit item (P image, ~position): 128 buckets per histogram bin
+//   for the 16 bins from b1 up (4 octaves of score), one more bucket for everything above;
+//   pass A over P counts the buckets, a scan turns counts into offsets, pass B over P drops every
+//   candidate into its bucket, and each candidate's final rank is its bucket offset plus the
+//   number of larger items in its own bucket (a few dozen compares).  Ranks below K' are written
+//   out directly: idx comes out in rank order.  The kernel also clears the histogram for the
+//   next call.
+// Degenerate score distributions take slower exact paths in kernel 2: a bucket with more than
+// 1024 items -> the candidates are bitonic-sorted instead; more candidates than fit in LDS (e.g.
+// all scores equal) -> radix select over P (two more histogram passes, 11 + 10 bits) finds the
+// K-th largest image T, positions with P > T and the first positions with P == T are collected
+// in position order, then bitonic-sorted.
 #include "rk_internal.h"
 #include "rk_device.h"
 
@@ -15,21 +28,40 @@ namespace rk {
 
 constexpr int kPoolTile = 1024;
 constexpr int kSelThreads = 1024;
-constexpr int kSelWaves = kSelThreads / 64;
+constexpr int kHistShift = 32 - 11;
+constexpr int kSubBits = 7;                              // buckets per histogram bin: 128
+constexpr int kBucketBins = 16;                          // histogram bins resolved into buckets
+constexpr int kBuckets = kBucketBins << kSubBits;        // 2048, plus one bucket for all above
+constexpr int kBucketLimit = 1024;                       // larger buckets: sort instead of ranking
+static_assert(kHistBins == 1 << 11, "first-level histogram is 11 bits wide");
+
+// Order-preserving map float -> uint32 (larger float <=> larger key) and its inverse.
+__device__ __forceinline__ uint32_t key_of(float x) {
+    const uint32_t u = __float_as_uint(x);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float value_of(uint32_t k) {
+    return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
+}
+__device__ __forceinline__ uint64_t item_of(uint32_t key, int j) {
+    return ((uint64_t)key << 32) | (uint64_t)(0xFFFFFFFFu - (uint32_t)j);
+}
 
 __global__ __launch_bounds__(256)
-void pool_scores_kernel(const float* __restrict__ weights, int64_t w_stride, const int32_t* seq_lens,
-                        int32_t max_len, int32_t Hq, int32_t Hkv, int32_t G, int32_t half,
-                        float* __restrict__ pooled, int64_t pooled_stride,
-                        const int32_t* pred, int32_t pred_val) {
+void pool_hist_kernel(const float* __restrict__ weights, int64_t w_stride, const int32_t* seq_lens,
+                      int32_t max_len, int32_t Hq, int32_t Hkv, int32_t G, int32_t half,
+                      float* __restrict__ pooled, int64_t pooled_stride, uint32_t* __restrict__ hist,
+                      const int32_t* pred, int32_t pred_val) {
     const int g = blockIdx.y, b = blockIdx.z;
     if (pred != nullptr && pred[b] != pred_val) return;
     const int len = min(seq_lens[b], max_len);
     const int j0 = blockIdx.x * kPoolTile;
     if (j0 >= len) return;
     __shared__ float sA[kPoolTile + RK_MAX_POOL_W - 1];
+    __shared__ uint32_t sH[kHistBins];
     const float* wg = weights + ((int64_t)b * Hq + (int64_t)g * G) * w_stride;
     const int span = kPoolTile + 2 * half;
+    for (int i = threadIdx.x; i < kHistBins; i += 256) sH[i] = 0;
     for (int i = threadIdx.x; i < span; i += 256) {
         const int j = j0 - half + i;
         float a = -INFINITY;                     // outside [0, len): never wins a max
@@ -40,29 +72,31 @@ void pool_scores_kernel(const float* __restrict__ weights, int64_t w_stride, con
         sA[i] = a;
     }
     __syncthreads();
-    float* out = pooled + ((int64_t)b * Hkv + g) * pooled_stride;
+    const int64_t bg = (int64_t)b * Hkv + g;
+    float* out = pooled + bg * pooled_stride;
     for (int i = threadIdx.x; i < kPoolTile; i += 256) {
         const int j = j0 + i;
         if (j < len) {
             float m = sA[i];
             for (int d = 1; d <= 2 * half; ++d) m = fmaxf(m, sA[i + d]);
-            out[j] = m + 0.0f;                   // -0 becomes +0: one bit pattern per value
+            m += 0.0f;                           // -0 becomes +0: one bit pattern per value
+            out[j] = m;
+            atomicAdd(&sH[key_of(m) >> kHistShift], 1u);
         }
+    }
+    __syncthreads();
+    uint32_t* gh = hist + bg * kHistBins;
+    for (int i = threadIdx.x; i < kHistBins; i += 256) {
+        const uint32_t c = sH[i];
+        if (c != 0) atomicAdd(&gh[i], c);
     }
 }
 
-// Order-preserving map float -> uint32 (larger float <=> larger key) and its inverse.
-__device__ __forceinline__ uint32_t key_of(float x) {
-    const uint32_t u = __float_as_uint(x);
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-__device__ __forceinline__ float value_of(uint32_t k) {
-    return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
-}
-
-// Inclusive prefix sum over the kSelThreads threads of the workgroup, in thread order.
-// `scratch` holds kSelWaves + 1 words.  Returns the inclusive sum; *total gets the block sum.
+// Inclusive prefix sum over the NT threads of the workgroup, in thread order.  `scratch` holds
+// NT / 64 words.  Returns the inclusive sum; *total gets the workgroup sum.
+template <int NT>
 __device__ __forceinline__ uint32_t block_inclusive_scan(uint32_t v, uint32_t* scratch, uint32_t* total) {
+    constexpr int NWV = NT / 64;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     uint32_t x = v;
 #pragma unroll
@@ -75,7 +109,7 @@ __device__ __forceinline__ uint32_t block_inclusive_scan(uint32_t v, uint32_t* s
     __syncthreads();
     uint32_t base = 0, tot = 0;
 #pragma unroll
-    for (int i = 0; i < kSelWaves; ++i) {
+    for (int i = 0; i < NWV; ++i) {
         const uint32_t s = scratch[i];
         if (i < w) base += s;
         tot += s;
@@ -84,16 +118,38 @@ __device__ __forceinline__ uint32_t block_inclusive_scan(uint32_t v, uint32_t* s
     return x + base;
 }
 
-// One histogram pass of the radix select.  On entry the keys still in play are those with
-// (key & mask) == prefix and the kk-th largest of them is wanted.  Bins are `bits` wide at
-// `shift`.  Returns through LDS (sOut[0] = bin holding the kk-th largest, sOut[1] = number of
-// candidates in higher bins).
+// Given a histogram of NB bins (LDS or global) find the bin that holds the kk-th largest entry,
+// counting from the top bin down: sOut[0] = that bin, sOut[1] = entries in higher bins.
+// All NT threads call; the result is valid after the call (it ends with a barrier).
+template <int NT, int NB>
+__device__ void find_bin_from_top(const uint32_t* hist, uint32_t kk, uint32_t* sScan, uint32_t* sOut) {
+    constexpr int BPT = NB / NT;
+    static_assert(BPT >= 1 && BPT * NT == NB, "bins divide evenly over the threads");
+    const int rt = NT - 1 - (int)threadIdx.x;       // thread 0 owns the top bins
+    uint32_t h[BPT];
+    uint32_t local = 0;
+#pragma unroll
+    for (int i = 0; i < BPT; ++i) { h[i] = hist[rt * BPT + i]; local += h[i]; }
+    uint32_t total;
+    const uint32_t incl = block_inclusive_scan<NT>(local, sScan, &total);   // entries in bins >= BPT*rt
+    uint32_t above = incl - local;
+    if (above < kk && kk <= incl) {
+#pragma unroll
+        for (int i = BPT - 1; i >= 0; --i) {
+            if (above + h[i] >= kk) { sOut[0] = (uint32_t)(rt * BPT + i); sOut[1] = above; break; }
+            above += h[i];
+        }
+    }
+    __syncthreads();
+}
+
+// One histogram pass of the slow-path radix select.  On entry the keys still in play are those
+// with (key & mask) == prefix and the kk-th largest of them is wanted.  Bins are BITS wide at
+// `shift`.  Result in sOut as for find_bin_from_top.
 template <int BITS>
 __device__ void radix_pass(const float* __restrict__ P, int n, uint32_t prefix, uint32_t mask, int shift,
                            uint32_t kk, uint32_t* sHist, uint32_t* sScan, uint32_t* sOut) {
     constexpr int NB = 1 << BITS;
-    constexpr int BPT = NB / kSelThreads;          // bins per thread: 2 (11 bits) or 1 (10 bits)
-    static_assert(BPT >= 1, "at least one bin per thread");
     const int tid = threadIdx.x;
     for (int i = tid; i < NB; i += kSelThreads) sHist[i] = 0;
     __syncthreads();
@@ -102,20 +158,48 @@ __device__ void radix_pass(const float* __restrict__ P, int n, uint32_t prefix, 
         if ((key & mask) == prefix) atomicAdd(&sHist[(key >> shift) & (NB - 1)], 1u);
     }
     __syncthreads();
-    // thread t owns bins [BPT*t, BPT*t + BPT); scan from the top: reverse the thread order
-    const int rt = kSelThreads - 1 - tid;
-    uint32_t local = 0;
-#pragma unroll
-    for (int i = 0; i < BPT; ++i) local += sHist[rt * BPT + i];
-    uint32_t total;
-    const uint32_t incl = block_inclusive_scan(local, sScan, &total);   // bins >= BPT*rt
-    uint32_t above = incl - local;                                       // bins >= BPT*(rt+1)
-    if (above < kk && kk <= incl) {
-#pragma unroll
-        for (int i = BPT - 1; i >= 0; --i) {
-            const uint32_t h = sHist[rt * BPT + i];
-            if (above + h >= kk) { sOut[0] = (uint32_t)(rt * BPT + i); sOut[1] = above; break; }
-            above += h;
+    find_bin_from_top<kSelThreads, NB>(sHist, kk, sScan, sOut);
+}
+
+// Sorts sKeys[0 .. npad) descending (npad a power of two); all kSelThreads threads call.
+// Wavefront w owns the compare-exchange pairs [w * PW, (w + 1) * PW), PW = npad / 2 / 16.  For a
+// stride <= PW those pairs only touch the wavefront's own 2 * PW elements, so such stages are
+// separated by a wavefront-local ordering of LDS traffic; only the strides above PW (10 of the
+// 78 stages at npad = 4096) need a workgroup barrier.
+__device__ void bitonic_sort_desc(uint64_t* sKeys, int npad) {
+    constexpr int NWV = kSelThreads / 64;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int half = npad >> 1;
+    if (half < kSelThreads) {
+        // small lists: one pair per thread at most, plain barriers
+        for (int size = 2; size <= npad; size <<= 1) {
+            for (int stride = size >> 1; stride > 0; stride >>= 1) {
+                if (tid < half) {
+                    const int lo = ((tid & ~(stride - 1)) << 1) | (tid & (stride - 1));
+                    const int hi = lo + stride;
+                    const bool desc = (lo & size) == 0;
+                    const uint64_t a = sKeys[lo], c = sKeys[hi];
+                    if ((a < c) == desc) { sKeys[lo] = c; sKeys[hi] = a; }
+                }
+                __syncthreads();
+            }
+        }
+        return;
+    }
+    const int PW = half / NWV;                    // pairs per wavefront, a multiple of 64
+    bool need_barrier = false;                    // the previous stage crossed wavefront blocks
+    for (int size = 2; size <= npad; size <<= 1) {
+        for (int stride = size >> 1; stride > 0; stride >>= 1) {
+            const bool cross = stride > PW;
+            if (cross || need_barrier) __syncthreads(); else wave_lds_sync();
+            for (int i = w * PW + lane; i < (w + 1) * PW; i += 64) {
+                const int lo = ((i & ~(stride - 1)) << 1) | (i & (stride - 1));
+                const int hi = lo + stride;
+                const bool desc = (lo & size) == 0;
+                const uint64_t a = sKeys[lo], c = sKeys[hi];
+                if ((a < c) == desc) { sKeys[lo] = c; sKeys[hi] = a; }
+            }
+            need_barrier = cross;
         }
     }
     __syncthreads();
@@ -123,79 +207,163 @@ __device__ void radix_pass(const float* __restrict__ P, int n, uint32_t prefix, 
 
 __global__ __launch_bounds__(kSelThreads)
 void select_kernel(const float* __restrict__ pooled, int64_t pooled_stride, const int32_t* seq_lens,
-                   int32_t max_len, int32_t k, int32_t kpad_max, int32_t* __restrict__ idx,
-                   float* __restrict__ sel_scores, const int32_t* pred, int32_t pred_val) {
+                   int32_t max_len, int32_t k, uint32_t* __restrict__ hist, int32_t cand_cap,
+                   int32_t* __restrict__ idx, float* __restrict__ sel_scores,
+                   const int32_t* pred, int32_t pred_val) {
     const int g = blockIdx.x, b = blockIdx.y, Hkv = gridDim.x;
     if (pred != nullptr && pred[b] != pred_val) return;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    uint64_t* sKeys = reinterpret_cast<uint64_t*>(smem);                   // [kpad_max]
-    uint32_t* sHist = reinterpret_cast<uint32_t*>(sKeys + kpad_max);       // [2048]
-    uint32_t* sScan = sHist + 2048;                                        // [kSelWaves]
-    uint32_t* sOut = sScan + kSelWaves;                                    // [2]
+    uint64_t* sKeys = reinterpret_cast<uint64_t*>(smem);                   // [cand_cap]
+    uint32_t* sHist = reinterpret_cast<uint32_t*>(sKeys + cand_cap);       // [2 * (kBuckets + 1)]: bucket
+                                                                           // arrays, or the radix histogram
+    uint32_t* sScan = sHist + 2 * (kBuckets + 1);                          // [16]
+    uint32_t* sOut = sScan + kSelThreads / 64;                             // [2]
     uint32_t* sCount = sOut + 2;                                           // [1]
 
     const int tid = threadIdx.x;
     const int n = min(seq_lens[b], max_len);
     const int kprime = min(k, max(n, 0));
-    const int64_t ob = ((int64_t)b * Hkv + g) * k;
-    if (kprime <= 0) {
+    const int64_t bg = (int64_t)b * Hkv + g;
+    const int64_t ob = bg * k;
+    if (kprime <= 0) {                      // nothing was histogrammed for an empty sequence
         for (int i = tid; i < k; i += kSelThreads) { idx[ob + i] = -1; if (sel_scores) sel_scores[ob + i] = 0.f; }
         return;
     }
-    const float* P = pooled + ((int64_t)b * Hkv + g) * pooled_stride;
+    const float* P = pooled + bg * pooled_stride;
+    uint32_t* gh = hist + bg * kHistBins;
 
-    // ---- exact K-th largest key T ----
-    uint32_t prefix = 0, mask = 0, kk = (uint32_t)kprime;
-    radix_pass<11>(P, n, prefix, mask, 21, kk, sHist, sScan, sOut);
-    prefix |= sOut[0] << 21; mask |= 0x7FFu << 21; kk -= sOut[1];
-    __syncthreads();
-    radix_pass<11>(P, n, prefix, mask, 10, kk, sHist, sScan, sOut);
-    prefix |= sOut[0] << 10; mask |= 0x7FFu << 10; kk -= sOut[1];
-    __syncthreads();
-    radix_pass<10>(P, n, prefix, mask, 0, kk, sHist, sScan, sOut);
-    const uint32_t T = prefix | sOut[0];
-    const uint32_t need_eq = kk - sOut[1];          // >= 1 positions with key == T are taken
-    const uint32_t n_gt = (uint32_t)kprime - need_eq;
     if (tid == 0) *sCount = 0;
-    __syncthreads();
+    find_bin_from_top<kSelThreads, kHistBins>(gh, (uint32_t)kprime, sScan, sOut);
+    const uint32_t b1 = sOut[0];
+    const uint32_t above = sOut[1];
+    const uint32_t count_ge = above + gh[b1];
+    __syncthreads();                        // every thread has read the histogram: clear it
+    for (int i = tid; i < kHistBins; i += kSelThreads) gh[i] = 0;
 
-    // ---- collect: every key > T, and the first need_eq positions with key == T ----
-    uint32_t base_eq = 0;
-    for (int tile0 = 0; tile0 < n; tile0 += kSelThreads) {
-        const int j = tile0 + tid;
-        const bool in = j < n;
-        const uint32_t key = in ? key_of(P[j]) : 0u;
-        const uint64_t item = ((uint64_t)key << 32) | (uint64_t)(0xFFFFFFFFu - (uint32_t)j);
-        if (in && key > T) sKeys[atomicAdd(sCount, 1u)] = item;
-        const bool eq = in && key == T;
-        if (base_eq < need_eq) {                    // uniform over the workgroup
-            if (__syncthreads_or(eq ? 1 : 0)) {
-                uint32_t total;
-                const uint32_t incl = block_inclusive_scan(eq ? 1u : 0u, sScan, &total);
-                const uint32_t rank = base_eq + incl - 1u;
-                if (eq && rank < need_eq) sKeys[n_gt + rank] = item;
-                base_eq += total;
-            }
-        }
+    // Visits every candidate (position in bin b1 or above) of P: one float compare per element,
+    // `visit(key, j)` runs for the candidates only.  The first 32 scores of every thread (the
+    // whole row up to 32768 positions) are loaded once, 16-byte loads all in flight together,
+    // and stay in registers for both passes; longer rows re-read the rest from memory.
+    const float thr = value_of(b1 << kHistShift);        // lowest score of bin b1 (scores are >= 0)
+    constexpr int NV = 8;
+    const float4* P4 = reinterpret_cast<const float4*>(P);
+    const int nvec = (n + 3) >> 2;
+    float4 held[NV];
+#pragma unroll
+    for (int u = 0; u < NV; ++u) {
+        const int v = u * kSelThreads + tid;
+        held[u] = (v < nvec) ? P4[v] : make_float4(-1.f, -1.f, -1.f, -1.f);
     }
-    int kpad = 1;
-    while (kpad < kprime) kpad <<= 1;
-    for (int i = kprime + tid; i < kpad; i += kSelThreads) sKeys[i] = 0;   // sorts behind every real item
-    __syncthreads();
-
-    // ---- bitonic sort, descending ----
-    for (int size = 2; size <= kpad; size <<= 1) {
-        for (int stride = size >> 1; stride > 0; stride >>= 1) {
-            for (int i = tid; i < (kpad >> 1); i += kSelThreads) {
-                const int lo = ((i & ~(stride - 1)) << 1) | (i & (stride - 1));
-                const int hi = lo + stride;
-                const bool desc = (lo & size) == 0;
-                const uint64_t a = sKeys[lo], c = sKeys[hi];
-                if ((a < c) == desc) { sKeys[lo] = c; sKeys[hi] = a; }
+    auto visit4 = [&](const float4 x, int j, auto&& visit) {
+        if (x.x >= thr || x.y >= thr || x.z >= thr || x.w >= thr) {
+            if (x.x >= thr && j + 0 < n) visit(key_of(x.x), j + 0);
+            if (x.y >= thr && j + 1 < n) visit(key_of(x.y), j + 1);
+            if (x.z >= thr && j + 2 < n) visit(key_of(x.z), j + 2);
+            if (x.w >= thr && j + 3 < n) visit(key_of(x.w), j + 3);
+        }
+    };
+    auto for_each_candidate = [&](auto&& visit) {
+#pragma unroll
+        for (int u = 0; u < NV; ++u) visit4(held[u], (u * kSelThreads + tid) << 2, visit);
+        constexpr int UN = 8;
+        for (int v0 = NV * kSelThreads; v0 < nvec; v0 += kSelThreads * UN) {
+            float4 pv[UN];
+#pragma unroll
+            for (int u = 0; u < UN; ++u) {
+                const int v = v0 + u * kSelThreads + tid;
+                pv[u] = (v < nvec) ? P4[v] : make_float4(-1.f, -1.f, -1.f, -1.f);
             }
+#pragma unroll
+            for (int u = 0; u < UN; ++u) visit4(pv[u], (v0 + u * kSelThreads + tid) << 2, visit);
+        }
+    };
+    auto bucket_of = [&](uint32_t key) -> uint32_t {
+        return min((key >> (kHistShift - kSubBits)) - (b1 << kSubBits), (uint32_t)kBuckets);
+    };
+    int nvalid;                             // entries of sKeys that are real (sorting paths)
+    if (count_ge <= (uint32_t)cand_cap) {
+        // ---- candidates = every position in bin b1 or above ----
+        uint32_t* sCnt = sHist;                         // [kBuckets + 1] bucket sizes, then fill marks
+        uint32_t* sStart = sHist + kBuckets + 1;        // [kBuckets + 1] bucket offsets
+        for (int i = tid; i < kBuckets + 1; i += kSelThreads) sCnt[i] = 0;
+        __syncthreads();
+        // pass A: bucket sizes
+        for_each_candidate([&](uint32_t key, int) { atomicAdd(&sCnt[bucket_of(key)], 1u); });
+        __syncthreads();
+        // offsets from the top bucket down: thread 0 owns the two highest regular buckets
+        const int rt = kSelThreads - 1 - tid;
+        const uint32_t c0 = sCnt[2 * rt], c1 = sCnt[2 * rt + 1], cov = sCnt[kBuckets];
+        const bool big = c0 > (uint32_t)kBucketLimit || c1 > (uint32_t)kBucketLimit || cov > (uint32_t)kBucketLimit;
+        uint32_t total;
+        const uint32_t incl = block_inclusive_scan<kSelThreads>(c0 + c1, sScan, &total);
+        const uint32_t above2 = incl - (c0 + c1) + cov;
+        if (!__syncthreads_or(big ? 1 : 0)) {
+            sStart[2 * rt + 1] = above2;      sCnt[2 * rt + 1] = above2;
+            sStart[2 * rt] = above2 + c1;     sCnt[2 * rt] = above2 + c1;
+            if (tid == 0) { sStart[kBuckets] = 0; sCnt[kBuckets] = 0; }
             __syncthreads();
+            // pass B: every candidate into its bucket (order inside a bucket is arbitrary)
+            for_each_candidate([&](uint32_t key, int j) {
+                sKeys[atomicAdd(&sCnt[bucket_of(key)], 1u)] = item_of(key, j);
+            });
+            __syncthreads();
+            // rank = bucket offset + larger items in the same bucket; ranks < K' are the answer
+            for (int e = tid; e < (int)count_ge; e += kSelThreads) {
+                const uint64_t item = sKeys[e];
+                const uint32_t bk = bucket_of((uint32_t)(item >> 32));
+                const uint32_t lo = sStart[bk], hi = sCnt[bk];
+                uint32_t r = lo;
+                for (uint32_t x = lo; x < hi; ++x) r += (sKeys[x] > item) ? 1u : 0u;
+                if (r < (uint32_t)kprime) {
+                    idx[ob + r] = (int32_t)(0xFFFFFFFFu - (uint32_t)(item & 0xFFFFFFFFu));
+                    if (sel_scores) sel_scores[ob + r] = value_of((uint32_t)(item >> 32));
+                }
+            }
+            for (int i = kprime + tid; i < k; i += kSelThreads) {
+                idx[ob + i] = -1;
+                if (sel_scores) sel_scores[ob + i] = 0.f;
+            }
+            return;
         }
+        // a huge bucket (many equal or nearly equal scores): collect and sort instead
+        for_each_candidate([&](uint32_t key, int j) { sKeys[atomicAdd(sCount, 1u)] = item_of(key, j); });
+        nvalid = (int)count_ge;
+    } else {
+        // ---- slow path: exact K-th largest image T by radix select over P ----
+        uint32_t prefix = b1 << kHistShift, mask = 0x7FFu << kHistShift, kk = (uint32_t)kprime - above;
+        __syncthreads();
+        radix_pass<11>(P, n, prefix, mask, 10, kk, sHist, sScan, sOut);
+        prefix |= sOut[0] << 10; mask |= 0x7FFu << 10; kk -= sOut[1];
+        __syncthreads();
+        radix_pass<10>(P, n, prefix, mask, 0, kk, sHist, sScan, sOut);
+        const uint32_t T = prefix | sOut[0];
+        const uint32_t need_eq = kk - sOut[1];          // >= 1 positions with image == T are taken
+        const uint32_t n_gt = (uint32_t)kprime - need_eq;
+        __syncthreads();
+        uint32_t base_eq = 0;
+        for (int tile0 = 0; tile0 < n; tile0 += kSelThreads) {
+            const int j = tile0 + tid;
+            const bool in = j < n;
+            const uint32_t key = in ? key_of(P[j]) : 0u;
+            if (in && key > T) sKeys[atomicAdd(sCount, 1u)] = item_of(key, j);
+            const bool eq = in && key == T;
+            if (base_eq < need_eq) {                    // uniform over the workgroup
+                if (__syncthreads_or(eq ? 1 : 0)) {
+                    uint32_t total;
+                    const uint32_t incl = block_inclusive_scan<kSelThreads>(eq ? 1u : 0u, sScan, &total);
+                    const uint32_t rank = base_eq + incl - 1u;
+                    if (eq && rank < need_eq) sKeys[n_gt + rank] = item_of(key, j);
+                    base_eq += total;
+                }
+            }
+        }
+        nvalid = kprime;
     }
+    int npad = 1;
+    while (npad < nvalid) npad <<= 1;
+    for (int i = nvalid + tid; i < npad; i += kSelThreads) sKeys[i] = 0;   // sorts behind every real item
+    __syncthreads();
+    bitonic_sort_desc(sKeys, npad);
     for (int i = tid; i < k; i += kSelThreads) {
         if (i < kprime) {
             const uint64_t item = sKeys[i];
@@ -228,16 +396,10 @@ extern "C" int rk_topk_select(const rk_geom* geom, const float* weights, int64_t
     hipStream_t st = (hipStream_t)stream;
     const int G = geom->n_q_heads / geom->n_kv_heads;
 
-    dim3 pgrid((max_len + kPoolTile - 1) / kPoolTile, geom->n_kv_heads, geom->batch);
-    hipLaunchKernelGGL(pool_scores_kernel, pgrid, dim3(256), 0, st, weights, w_stride, seq_lens, max_len,
-                       geom->n_q_heads, geom->n_kv_heads, G, (pool_w - 1) / 2, ws.pooled, (int64_t)max_len,
-                       pred, pred_val);
-    if ((rc = launch_status()) != RK_OK) return rc;
-
-    int kpad = 1;
-    while (kpad < k) kpad <<= 1;
-    const size_t lds = (size_t)kpad * sizeof(uint64_t) + (2048 + kSelWaves + 2 + 1) * sizeof(uint32_t);
-    static size_t lds_allowed = 48 * 1024;       // grows monotonically; set before the first large launch
+    // the sort kernel may need more than the default dynamic LDS: ask before anything is enqueued
+    const size_t lds = (size_t)ws.cand_cap * sizeof(uint64_t) +
+                       (2 * (kBuckets + 1) + kSelThreads / 64 + 2 + 1) * sizeof(uint32_t);
+    static size_t lds_allowed = 48 * 1024;       // grows monotonically
     if (lds > lds_allowed) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
@@ -246,8 +408,15 @@ extern "C" int rk_topk_select(const rk_geom* geom, const float* weights, int64_t
         }
         lds_allowed = lds;
     }
+
+    const int64_t pooled_stride = pooled_row_stride(max_len);      // rows start 16-byte aligned
+    dim3 pgrid((max_len + kPoolTile - 1) / kPoolTile, geom->n_kv_heads, geom->batch);
+    hipLaunchKernelGGL(pool_hist_kernel, pgrid, dim3(256), 0, st, weights, w_stride, seq_lens, max_len,
+                       geom->n_q_heads, geom->n_kv_heads, G, (pool_w - 1) / 2, ws.pooled, pooled_stride, ws.hist,
+                       pred, pred_val);
+    if ((rc = launch_status()) != RK_OK) return rc;
     dim3 sgrid(geom->n_kv_heads, geom->batch);
-    hipLaunchKernelGGL(select_kernel, sgrid, dim3(kSelThreads), lds, st, ws.pooled, (int64_t)max_len, seq_lens,
-                       max_len, k, kpad, idx, sel_scores, pred, pred_val);
+    hipLaunchKernelGGL(select_kernel, sgrid, dim3(kSelThreads), lds, st, ws.pooled, pooled_stride, seq_lens,
+                       max_len, k, ws.hist, ws.cand_cap, idx, sel_scores, pred, pred_val);
     return launch_status();
 }

@@ -78,8 +78,8 @@ class RefreshKVLayer:
         rk.rk_topk_select(g, self.weights, self.seq_lens, self.max_len, self.k_small, self.pool_w, self.idx,
                           pred=pred, pred_val=1, workspace=self.ws, stream=stream)
         rk.rk_gather_small_kv(g, self.K, self.V, self.idx, self.k_small, self.small_K, self.small_V,
+                              seq_lens=self.seq_lens, tail_start=self.tail_start,
                               pred=pred, pred_val=1, stream=stream)
-        rk.rk_mark_refresh(g, self.seq_lens, self.tail_start, pred=pred, pred_val=1, stream=stream)
 
     def _partial(self, q, out, pred=None, stream=None) -> None:
         if self.evict_lowest and not self.dynamic:
@@ -97,7 +97,8 @@ class RefreshKVLayer:
         out = self.out if out is None else out
         scheduled = t == 0 or (self.stride > 0 and t % self.stride == 0)
         if t == 0 or (scheduled and not self.dynamic):
-            rk.rk_query_sim(self.geom, q, self.q_ref, self.threshold, True, self.sim, self.need_full, stream=stream)
+            if self.dynamic:        # the trigger's reference follows every full step; a fixed stride never reads it
+                rk.rk_query_sim(self.geom, q, self.q_ref, self.threshold, True, self.sim, self.need_full, stream=stream)
             self._full(q, out, stream=stream)
             if not self._static:
                 self.recent_bound = 0

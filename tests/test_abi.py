@@ -84,8 +84,9 @@ def test_host_side_argument_checks_return_before_any_launch(rk):
     assert topk(pool=4) == -1
     assert topk(pool=65) == -2
     assert topk(agg=1) == -2
-    assert lib.rk_gather_small_kv(C.byref(g), kv, None, 16, kv, None, 0, None) == -1
-    assert lib.rk_gather_small_kv(C.byref(g), kv, fake, 0, kv, None, 0, None) == -1
+    assert lib.rk_gather_small_kv(C.byref(g), kv, None, 16, kv, None, None, None, 0, None) == -1
+    assert lib.rk_gather_small_kv(C.byref(g), kv, fake, 0, kv, None, None, None, 0, None) == -1
+    assert lib.rk_gather_small_kv(C.byref(g), kv, fake, 16, kv, None, fake, None, 0, None) == -1   # tail_start without seq_lens
     assert lib.rk_partial_attn(C.byref(g), fake, kv, -1, kv, fake, fake, 4, fake, None, 0, 0x100000, ws_bytes, None) == -1
     assert lib.rk_partial_attn(C.byref(g), fake, kv, 0, kv, fake, fake, 0, fake, None, 0, 0x100000, ws_bytes, None) == -1
     assert lib.rk_partial_attn(C.byref(g), fake, kv, 16, kv, None, fake, 4, fake, None, 0, 0x100000, ws_bytes, None) == -1

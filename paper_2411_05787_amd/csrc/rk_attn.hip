@@ -11,17 +11,22 @@
 // atomic add.  No cache-wide release/acquire fence is used: on this chip one such fence per
 // workgroup writes back and invalidates a whole L2 and costs more than the attention itself.
 //
-// Data path per wavefront and iteration (ROWS = 16 * TILES rows):
+// Data path per wavefront and tile of 32 rows:
 //   K rows  -> registers in MFMA operand layout (16-byte loads, no LDS)
-//   S = Q K^T on the matrix cores: v_mfma_f32_16x16x32_bf16, M = query heads (padded to 16),
-//             N = 16 rows, contraction over head_dim in 4 steps
-//   softmax bookkeeping (running max / sum) on the lanes that hold S
-//   P crosses to the V layout through LDS; raw scores (when weights are returned) are stored
-//             straight from the S layout
-//   O += P V on the vector ALU: each lane owns 8 consecutive dims of one row in four,
-//             V rows loaded with fully coalesced 16-byte loads
-// The K and V registers are double-buffered: the loads of a wavefront's next tile are issued
-// before the current tile is computed.
+//   S^T = K Q^T on the matrix cores: v_mfma_f32_16x16x32_bf16, M = 16 rows, N = query heads
+//             (padded to 16), contraction over head_dim in 4 steps; a lane ends up with four
+//             consecutive rows of one head
+//   softmax bookkeeping (running max / sum per head) on those lanes; raw scores (when weights
+//             are returned) are stored straight from them
+//   O += P V on the matrix cores as well: P is already in operand layout (the contraction slots
+//             of P V are numbered the way S^T left the rows in the lanes), split into two bf16
+//             operands hi + lo so that it keeps ~17 bits; V rows are loaded with fully coalesced
+//             16-byte loads, staged in LDS, and read back transposed (ds_read_b64_tr_b16) as the
+//             other operand.  The fp32 O accumulators (8 tiles of 16 dims x 16 heads) do not
+//             grow with the group size.
+// The rows of a wavefront's next tile are requested as soon as the registers of the current tile
+// are consumed (K after S^T, V after the copy to LDS), so loads are in flight during the rest of
+// the tile's work.
 #include "rk_internal.h"
 #include "rk_device.h"
 
@@ -41,6 +46,7 @@ struct AttnParams {
     float scale;
     uint16_t* out;                     // bf16 [B, Hq, 128]
     float* weights; int64_t w_stride;  // raw scores go here first (EMIT only)
+    int32_t w_vec;                     // rows of `weights` start 16-byte aligned: vector stores allowed
     float* lse;                        // fp32 [B, Hq], never NULL here
     const int32_t* pred; int32_t pred_val;
     int32_t* counters; float* part_ml; float* part_o; int32_t max_chunks;
@@ -95,7 +101,7 @@ __device__ void merge_partials(const AttnParams& p, int b, int g, int nchunks, f
         }
     };
     request(0);
-    static_assert(4 * NT >= kMergeChunks * RK_MAX_GROUP || NW < 4, "one batch covers all (chunk, head) pairs");
+    static_assert(4 * NT >= kMergeChunks * G, "one batch covers all (chunk, head) pairs");
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
         const int i = u * NT + tid;
@@ -144,23 +150,44 @@ __device__ void merge_partials(const AttnParams& p, int b, int g, int nchunks, f
     }
 }
 
-// Two wavefronts per SIMD (<= 256 registers each) whenever the accumulators leave room for it.
-template <int G, int NW, int TILES, bool EMIT, bool TWO_SEG>
-__global__ __launch_bounds__(NW * 64, (G <= 4 || TILES == 1) ? 2 : 1)
+// ds_read_b64_tr_b16: every 16 lanes hand in 16 addresses of 4 consecutive bf16 (a 16 x 4
+// matrix M, row = lane) and lane i gets back M[i/4 + 4e][i%4] for e = 0..3.
+typedef short v4s __attribute__((ext_vector_type(4)));
+typedef short v8s __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));      // 16 bytes in four registers
+__device__ __forceinline__ v4s lds_read_tr16(const uint16_t* ptr) {
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s*)ptr);
+}
+// Two fp32 -> packed bf16 pair, round to nearest even (v_cvt_pk_bf16_f32).
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    const f32x2 v = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
+
+// Roles of lane (n16, c4) = (lane % 16, lane / 16) of a wavefront, per tile of 32 rows:
+//   K operand   row n16 of a 16-row half tile, dims 8*(4*kk + c4) .. +7, kk = 0..3
+//   Q operand   head n16 (zero beyond G), same dims
+//   S^T result  head n16, rows 4*c4 + i (i = 0..3) of each half tile
+//   V load      rows c4 + 4*jj (jj = 0..7), dims 8*n16 .. +7
+//   P operand   head n16, contraction slot e = 4*t + i  <->  row 16*t + 4*c4 + i
+//   V operand   dim 16*dt + n16, the same slots (LDS transpose read)
+//   O result    dim 16*dt + n16, heads 4*c4 + i
+template <int G, int NW, bool EMIT, bool TWO_SEG>
+__global__ __launch_bounds__(NW * 64, 2)
 void attn_split_kernel(const AttnParams p) {
-    constexpr int GP = (G + 3) / 4 * 4;      // heads padded to whole MFMA accumulator registers
-    constexpr int NC = GP / 4;               // 16-lane groups whose accumulators hold real heads
-    constexpr int ROWS = TILES * 16;         // rows per wavefront per iteration
-    constexpr int NV = ROWS / 4;             // V loads per lane per iteration
-    constexpr int RG = (G <= 4) ? 4 : 2;     // row groups of a wavefront kept apart in LDS
+    constexpr int ROWS = 32;                 // rows per wavefront and tile = contraction depth of P V
+    constexpr int NV = ROWS / 4;             // V loads per lane and tile
+    constexpr int NC = (G + 3) / 4;          // lane groups whose O accumulators hold real heads
     constexpr int NT = NW * 64;
+    constexpr int VS = kD + 8;               // LDS row stride of the V tile (272 bytes: rows spread over banks)
 
     const int c = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
     if (p.pred != nullptr && p.pred[b] != p.pred_val) return;
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const int n16 = lane & 15, c4 = lane >> 4;     // S layout: row n16, heads 4*c4 .. 4*c4+3
-    const int db = lane & 15, rg = lane >> 4;      // V layout: dims 8*db .. 8*db+7, rows = rg mod 4
+    const int n16 = lane & 15, c4 = lane >> 4;
 
     // ---- K rows of the first tile are requested before any length is known ----
     // Rows below `spec_rows` exist whatever the device-side lengths say (small cache: the first
@@ -170,15 +197,27 @@ void attn_split_kernel(const AttnParams p) {
     const int r_first = c * p.chunk + w * ROWS;
     const int spec_rows = TWO_SEG ? min(p.n_sel, p.cap1) : p.cap2;
     const bool spec = (int64_t)(c + 1) * p.chunk <= spec_rows;
-    uint4 kA[TILES][4], vA[NV], kB[TILES][4], vB[NV];
+    u32x4 kA[2][4], vA[NV];
     if (spec) {
         const uint16_t* kspec = (TWO_SEG ? p.k1 + (int64_t)b * p.s1_b + (int64_t)g * p.s1_h
                                          : p.k2 + (int64_t)b * p.s2_b + (int64_t)g * p.s2_h) + c4 * 8;
 #pragma unroll
-        for (int t = 0; t < TILES; ++t)
+        for (int t = 0; t < 2; ++t)
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk)
-                kA[t][kk] = *reinterpret_cast<const uint4*>(kspec + (int64_t)(r_first + t * 16 + n16) * kD + kk * 32);
+                kA[t][kk] = *reinterpret_cast<const u32x4*>(kspec + (int64_t)(r_first + t * 16 + n16) * kD + kk * 32);
+    }
+
+    // ---- Q: head n16, dims 8*(4*kk + c4) .. +7 ----
+    bf16x8 qa[4];
+    {
+        const uint16_t* qrow = p.q + ((int64_t)b * p.Hq + (int64_t)g * G + (n16 < G ? n16 : 0)) * kD;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            uint4 u = *reinterpret_cast<const uint4*>(qrow + (kk * 4 + c4) * 8);
+            if (n16 >= G) u = make_uint4(0, 0, 0, 0);
+            qa[kk] = __builtin_bit_cast(bf16x8, u);
+        }
     }
 
     // ---- the row list of this (sequence, KV head) ----
@@ -207,192 +246,146 @@ void attn_split_kernel(const AttnParams p) {
     const uint16_t* kb2 = p.k2 + (int64_t)b * p.s2_b + (int64_t)g * p.s2_h + (int64_t)(start2 - n1) * kD;
     const uint16_t* vb2 = p.v2 + (int64_t)b * p.s2_b + (int64_t)g * p.s2_h + (int64_t)(start2 - n1) * kD;
 
-    __shared__ __attribute__((aligned(16))) float sP[NW][ROWS][GP];
-    __shared__ __attribute__((aligned(16))) float sAlpha[NW][GP];
-    __shared__ __attribute__((aligned(16))) float sMw[NW][GP];
-    __shared__ __attribute__((aligned(16))) float sLw[NW][GP];
-    __shared__ __attribute__((aligned(16))) float sO[NW * RG][G][kD];   // reused by the merge
-    __shared__ float sMf[GP];
-    __shared__ double sLf[GP];
+    __shared__ __attribute__((aligned(16))) uint16_t sV[NW][ROWS][VS];
+    __shared__ __attribute__((aligned(16))) float sAlpha[NW][16];
+    __shared__ __attribute__((aligned(16))) float sMw[NW][16];
+    __shared__ __attribute__((aligned(16))) float sLw[NW][16];
+    __shared__ __attribute__((aligned(16))) float sO[NW][G][kD];       // reused by the merge
+    __shared__ float sMf[8];
+    __shared__ double sLf[8];
     __shared__ int sTicket;
-    static_assert(NW * RG * G * kD >= 2 * kMergeChunks * G, "merge scratch must fit in the output staging buffer");
+    static_assert(NW * G * kD >= 2 * kMergeChunks * G, "merge scratch must fit in the output staging buffer");
 
-    // ---- Q as the A operand: lane (n16, c4) holds head n16, dims 8*(4*kk + c4) .. +7 ----
-    bf16x8 qa[4];
-    {
-        const uint16_t* qrow = p.q + ((int64_t)b * p.Hq + (int64_t)g * G + (n16 < G ? n16 : 0)) * kD;
+    float m_run = -INFINITY, l_run = 0.f;          // of head n16, over the rows this lane group saw
+    f32x4 acc_o[8];
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            uint4 u = *reinterpret_cast<const uint4*>(qrow + (kk * 4 + c4) * 8);
-            if (n16 >= G) u = make_uint4(0, 0, 0, 0);
-            qa[kk] = __builtin_bit_cast(bf16x8, u);
-        }
-    }
-
-    float m_run[4], l_run[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) { m_run[i] = -INFINITY; l_run[i] = 0.f; }
-    float o[G][8];
-#pragma unroll
-    for (int gi = 0; gi < G; ++gi)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) o[gi][e] = 0.f;
+    for (int dt = 0; dt < 8; ++dt) acc_o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     // ---- loads: rows past the end of the chunk re-read its last row (masked later) ----
-    auto load_k = [&](uint4 (&kreg)[TILES][4], int r) {
+    auto load_k = [&](int r) {
 #pragma unroll
-        for (int t = 0; t < TILES; ++t) {
+        for (int t = 0; t < 2; ++t) {
             const int row = min(r + t * 16 + n16, row1 - 1);
             const uint16_t* base = (TWO_SEG && row < n1) ? kb1 : kb2;
             const uint16_t* rp = base + (int64_t)row * kD + c4 * 8;
 #pragma unroll
-            for (int kk = 0; kk < 4; ++kk) kreg[t][kk] = *reinterpret_cast<const uint4*>(rp + kk * 32);
+            for (int kk = 0; kk < 4; ++kk) kA[t][kk] = *reinterpret_cast<const u32x4*>(rp + kk * 32);
         }
     };
-    auto load_v = [&](uint4 (&vreg)[NV], int r) {
+    auto load_v = [&](int r) {
 #pragma unroll
         for (int jj = 0; jj < NV; ++jj) {
-            const int row = min(r + jj * 4 + rg, row1 - 1);
+            const int row = min(r + jj * 4 + c4, row1 - 1);
             const uint16_t* base = (TWO_SEG && row < n1) ? vb1 : vb2;
-            vreg[jj] = *reinterpret_cast<const uint4*>(base + (int64_t)row * kD + db * 8);
+            vA[jj] = *reinterpret_cast<const u32x4*>(base + (int64_t)row * kD + n16 * 8);
         }
     };
-    auto compute_tile = [&](uint4 (&kreg)[TILES][4], uint4 (&vreg)[NV], int r) {
-        // ---- S = Q K^T: lane (n16, c4) gets heads 4*c4+i of row r + 16 t + n16 ----
-        float s[TILES][4];
+    // One tile.  The K registers are free again once S^T is computed and the V registers once the
+    // tile sits in LDS: the next tile's rows are requested at those two points, so its loads are
+    // in flight during the rest of this tile's work.
+    auto compute_tile = [&](int r, int r_next) {
+        // ---- S^T = K Q^T on the matrix cores: head n16, rows r + 16 t + 4 c4 + i ----
+        float s[2][4];
 #pragma unroll
-        for (int t = 0; t < TILES; ++t) {
+        for (int t = 0; t < 2; ++t) {
             f32x4 acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk)
-                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(qa[kk], __builtin_bit_cast(bf16x8, kreg[t][kk]),
-                                                              acc, 0, 0, 0);
-            const bool valid = (r + t * 16 + n16) < row1;
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kA[t][kk]), qa[kk], acc, 0, 0, 0);
 #pragma unroll
-            for (int i = 0; i < 4; ++i) s[t][i] = valid ? acc[i] * p.scale : -INFINITY;
+            for (int i = 0; i < 4; ++i) s[t][i] = (r + t * 16 + 4 * c4 + i < row1) ? acc[i] * p.scale : -INFINITY;
         }
-
-        // ---- raw scores out, straight from the lanes that hold them: 16 consecutive rows of one
-        //      head are a 64-byte segment ----
+        if (r_next < row1) load_k(r_next);
+        // ---- raw scores out: four consecutive rows of one head per lane, one 16-byte store
+        //      where the row of the weights tensor allows it ----
         if (EMIT) {
-            if (c4 < NC) {
-                float* wrow = p.weights + ((int64_t)b * p.Hq + (int64_t)g * G + c4 * 4) * p.w_stride + r + n16;
+            if (n16 < G) {
+                float* wrow = p.weights + ((int64_t)b * p.Hq + (int64_t)g * G + n16) * p.w_stride + r + 4 * c4;
 #pragma unroll
-                for (int t = 0; t < TILES; ++t) {
-                    if (r + t * 16 + n16 < row1) {
+                for (int t = 0; t < 2; ++t) {
+                    const int first = r + t * 16 + 4 * c4;
+                    if (p.w_vec && first + 4 <= row1) {
+                        *reinterpret_cast<float4*>(wrow + t * 16) = make_float4(s[t][0], s[t][1], s[t][2], s[t][3]);
+                    } else {
 #pragma unroll
                         for (int i = 0; i < 4; ++i)
-                            if (c4 * 4 + i < G) wrow[(int64_t)i * p.w_stride + t * 16] = s[t][i];
+                            if (first + i < row1) wrow[t * 16 + i] = s[t][i];
                     }
                 }
             }
         }
-
-        // ---- running softmax statistics of this wavefront ----
-        float alpha[4], pr[TILES][4];
+        // ---- running softmax statistics of head n16 (row r itself is always valid: finite max) ----
+        float mx = fmaxf(fmaxf(fmaxf(s[0][0], s[0][1]), fmaxf(s[0][2], s[0][3])),
+                         fmaxf(fmaxf(s[1][0], s[1][1]), fmaxf(s[1][2], s[1][3])));
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run, mx);
+        const float alpha = fast_exp2((m_run - m_new) * kLog2e);
+        m_run = m_new;
+        float pr[8], ps = 0.f;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            float mx = s[0][i];
-#pragma unroll
-            for (int t = 1; t < TILES; ++t) mx = fmaxf(mx, s[t][i]);
-            mx = row16_max(mx);
-            const float m_new = fmaxf(m_run[i], mx);       // finite: row r is always valid
-            alpha[i] = fast_exp2((m_run[i] - m_new) * kLog2e);
-            m_run[i] = m_new;
-            float ps = 0.f;
-#pragma unroll
-            for (int t = 0; t < TILES; ++t) {
-                pr[t][i] = fast_exp2((s[t][i] - m_new) * kLog2e);
-                ps += pr[t][i];
-            }
-            l_run[i] = l_run[i] * alpha[i] + ps;            // per-lane share, summed at the end
+        for (int e = 0; e < 8; ++e) {
+            pr[e] = fast_exp2((s[e >> 2][e & 3] - m_new) * kLog2e);
+            ps += pr[e];
         }
-        if (c4 < NC) {
+        l_run = l_run * alpha + ps;                 // this lane group's share, summed at the end
+        // ---- P as two bf16 operands: P = hi + lo to about 2^-17 ----
+        uint32_t ph[4], pl[4];
 #pragma unroll
-            for (int t = 0; t < TILES; ++t) {
-                *reinterpret_cast<float4*>(&sP[w][t * 16 + n16][c4 * 4]) =
-                    make_float4(pr[t][0], pr[t][1], pr[t][2], pr[t][3]);
-            }
-            if (n16 == 0)
-                *reinterpret_cast<float4*>(&sAlpha[w][c4 * 4]) = make_float4(alpha[0], alpha[1], alpha[2], alpha[3]);
+        for (int e2 = 0; e2 < 4; ++e2) {
+            ph[e2] = pack_bf16(pr[2 * e2], pr[2 * e2 + 1]);
+            pl[e2] = pack_bf16(pr[2 * e2] - bf16_lo(ph[e2]), pr[2 * e2 + 1] - bf16_hi(ph[e2]));
         }
+        const bf16x8 p_hi = __builtin_bit_cast(bf16x8, make_uint4(ph[0], ph[1], ph[2], ph[3]));
+        const bf16x8 p_lo = __builtin_bit_cast(bf16x8, make_uint4(pl[0], pl[1], pl[2], pl[3]));
+        // ---- V tile and the rescale factors cross lanes through LDS ----
+        if (c4 == 0) sAlpha[w][n16] = alpha;
+#pragma unroll
+        for (int jj = 0; jj < NV; ++jj) *reinterpret_cast<u32x4*>(&sV[w][jj * 4 + c4][n16 * 8]) = vA[jj];
+        if (r_next < row1) load_v(r_next);
         wave_lds_sync();
-
-        // ---- O = alpha O + P V ----
-        {
-            float al[GP];
+        if (__any(alpha != 1.0f)) {                 // the running max moved (always on the first tile)
+            const float4 al = *reinterpret_cast<const float4*>(&sAlpha[w][(c4 < NC ? c4 : 0) * 4]);
 #pragma unroll
-            for (int q4 = 0; q4 < NC; ++q4) {
-                const float4 t4 = *reinterpret_cast<const float4*>(&sAlpha[w][q4 * 4]);
-                al[q4 * 4 + 0] = t4.x; al[q4 * 4 + 1] = t4.y; al[q4 * 4 + 2] = t4.z; al[q4 * 4 + 3] = t4.w;
+            for (int dt = 0; dt < 8; ++dt) {
+                acc_o[dt][0] *= al.x; acc_o[dt][1] *= al.y; acc_o[dt][2] *= al.z; acc_o[dt][3] *= al.w;
             }
-#pragma unroll
-            for (int gi = 0; gi < G; ++gi)
-#pragma unroll
-                for (int e = 0; e < 8; ++e) o[gi][e] *= al[gi];
         }
+        // ---- O += P V on the matrix cores, V operands by LDS transpose reads ----
+        const uint16_t* vsrc = &sV[w][4 * c4 + (n16 >> 2)][4 * (n16 & 3)];
 #pragma unroll
-        for (int jj = 0; jj < NV; ++jj) {
-            float pv[GP];
-#pragma unroll
-            for (int q4 = 0; q4 < NC; ++q4) {
-                const float4 t4 = *reinterpret_cast<const float4*>(&sP[w][jj * 4 + rg][q4 * 4]);
-                pv[q4 * 4 + 0] = t4.x; pv[q4 * 4 + 1] = t4.y; pv[q4 * 4 + 2] = t4.z; pv[q4 * 4 + 3] = t4.w;
-            }
-            const uint4 u = vreg[jj];
-            const float vf[8] = {bf16_lo(u.x), bf16_hi(u.x), bf16_lo(u.y), bf16_hi(u.y),
-                                 bf16_lo(u.z), bf16_hi(u.z), bf16_lo(u.w), bf16_hi(u.w)};
-#pragma unroll
-            for (int gi = 0; gi < G; ++gi)
-#pragma unroll
-                for (int e = 0; e < 8; ++e) o[gi][e] = fmaf(pv[gi], vf[e], o[gi][e]);
+        for (int dt = 0; dt < 8; ++dt) {
+            const v4s v0 = lds_read_tr16(vsrc + dt * 16);
+            const v4s v1 = lds_read_tr16(vsrc + 16 * VS + dt * 16);
+            const bf16x8 vb = __builtin_bit_cast(bf16x8, __builtin_shufflevector(v0, v1, 0, 1, 2, 3, 4, 5, 6, 7));
+            acc_o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(p_hi, vb, acc_o[dt], 0, 0, 0);
+            acc_o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(p_lo, vb, acc_o[dt], 0, 0, 0);
         }
-        wave_lds_sync();      // sP / sAlpha are rewritten by the next tile
+        wave_lds_sync();      // sV / sAlpha are rewritten by the next tile
     };
 
-    // Two register buffers: the loads of the next tile are in flight while this one is computed,
-    // so a wavefront never stops requesting memory while it has rows left.
     {
         const int step = NW * ROWS;
         int r = r_first;
         if (r < row1) {
             // the early request stands unless part of this chunk maps to the tail of the full cache
             const bool spec_ok = spec && (!TWO_SEG || (c + 1) * p.chunk <= n1);
-            if (!spec_ok) load_k(kA, r);
-            load_v(vA, r);
+            if (!spec_ok) load_k(r);
+            load_v(r);
         }
-        while (r < row1) {
-            const int rn = r + step;
-            if (rn < row1) { load_k(kB, rn); load_v(vB, rn); }
-            compute_tile(kA, vA, r);
-            if (rn >= row1) break;
-            const int rnn = rn + step;
-            if (rnn < row1) { load_k(kA, rnn); load_v(vA, rnn); }
-            compute_tile(kB, vB, rn);
-            r = rnn;
-        }
+        for (; r < row1; r += step) compute_tile(r, r + step);
     }
 
     // ---- wavefront results to LDS ----
+    l_run += __shfl_xor(l_run, 16);
+    l_run += __shfl_xor(l_run, 32);
+    if (c4 == 0) { sMw[w][n16] = m_run; sLw[w][n16] = l_run; }
+    if (c4 < NC) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) l_run[i] = row16_sum(l_run[i]);
-    if (c4 < NC && n16 == 0) {
-        *reinterpret_cast<float4*>(&sMw[w][c4 * 4]) = make_float4(m_run[0], m_run[1], m_run[2], m_run[3]);
-        *reinterpret_cast<float4*>(&sLw[w][c4 * 4]) = make_float4(l_run[0], l_run[1], l_run[2], l_run[3]);
-    }
-    if (RG == 2) {
+        for (int dt = 0; dt < 8; ++dt)
 #pragma unroll
-        for (int gi = 0; gi < G; ++gi)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) o[gi][e] += __shfl_xor(o[gi][e], 32);
-    }
-    if (rg < RG) {
-#pragma unroll
-        for (int gi = 0; gi < G; ++gi) {
-            float4* dst = reinterpret_cast<float4*>(&sO[w * RG + rg][gi][db * 8]);
-            dst[0] = make_float4(o[gi][0], o[gi][1], o[gi][2], o[gi][3]);
-            dst[1] = make_float4(o[gi][4], o[gi][5], o[gi][6], o[gi][7]);
-        }
+            for (int i = 0; i < 4; ++i)
+                if (4 * c4 + i < G) sO[w][4 * c4 + i][dt * 16 + n16] = acc_o[dt][i];
     }
     __syncthreads();
 
@@ -410,14 +403,9 @@ void attn_split_kernel(const AttnParams p) {
         for (int ww = 0; ww < NW; ++ww) {
             const float mw = sMw[ww][gi];
             const float sc = (mw == -INFINITY) ? 0.f : fast_exp2((mw - M) * kLog2e);
-            float p0 = 0.f, p1 = 0.f;
-#pragma unroll
-            for (int rr = 0; rr < RG; ++rr) {
-                const float2 t2 = *reinterpret_cast<const float2*>(&sO[ww * RG + rr][gi][d]);
-                p0 += t2.x; p1 += t2.y;
-            }
-            acc0 = fmaf(sc, p0, acc0);
-            acc1 = fmaf(sc, p1, acc1);
+            const float2 t2 = *reinterpret_cast<const float2*>(&sO[ww][gi][d]);
+            acc0 = fmaf(sc, t2.x, acc0);
+            acc1 = fmaf(sc, t2.y, acc1);
             L = fmaf(sc, sLw[ww][gi], L);
         }
         if (EMIT) {       // merged by the next kernel: ordinary stores
@@ -554,15 +542,8 @@ void merge_normalise_kernel(const AttnParams p, int G) {
 template <int G, bool EMIT, bool TWO_SEG>
 static int launch_split_g(const AttnParams& p, int batch, int nchunk_grid, hipStream_t st) {
     dim3 grid(nchunk_grid, p.Hkv, batch);
-#ifndef RK_BIG_TILES
-#define RK_BIG_TILES 2
-#endif
-    if (p.chunk >= 128) {       // 32 rows per wavefront and tile (16 for the larger groups, whose
-                                // accumulators take the registers); >= 2 tiles per wavefront from chunk 256 up
-        hipLaunchKernelGGL((attn_split_kernel<G, 4, (G <= 4 ? RK_BIG_TILES : 1), EMIT, TWO_SEG>), grid, dim3(256), 0, st, p);
-    } else {
-        hipLaunchKernelGGL((attn_split_kernel<G, 4, 1, EMIT, TWO_SEG>), grid, dim3(256), 0, st, p);
-    }
+    // four wavefronts of 32 rows per iteration; with 64-row chunks two of them only help to merge
+    hipLaunchKernelGGL((attn_split_kernel<G, 4, EMIT, TWO_SEG>), grid, dim3(256), 0, st, p);
     return launch_status();
 }
 
@@ -613,6 +594,7 @@ static int full_attn_impl(const rk_geom* geom, const void* q, rk_kv full,
     p.scale = geom->scale;
     p.out = (uint16_t*)out;
     p.weights = weights; p.w_stride = w_stride;
+    p.w_vec = (weights && (w_stride % 4 == 0) && aligned16(weights)) ? 1 : 0;
     p.lse = lse ? lse : ws.lse;
     p.pred = pred; p.pred_val = pred_val;
     p.counters = ws.counters; p.part_ml = ws.part_ml; p.part_o = ws.part_o; p.max_chunks = ws.max_chunks;

@@ -10,7 +10,7 @@
 namespace rk {
 
 constexpr int kD = RK_HEAD_DIM;          // head_dim
-constexpr int kMinChunk = 64;            // smallest number of KV rows one workgroup reduces
+constexpr int kMinChunk = 128;           // smallest number of KV rows one workgroup reduces: 4 wavefronts x 32
 constexpr int kMaxChunks = 256;          // most partial results one (sequence, KV head) produces
 constexpr int kMergeChunks = 64;         // ... when the split kernel itself merges them
 #ifndef RK_TARGET_WGS

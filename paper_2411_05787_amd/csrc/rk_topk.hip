@@ -9,18 +9,20 @@
 // Kernel 2, one workgroup of 1024 threads per (sequence, KV head) (select_kernel): finds, from
 //   the histogram, the bin b1 that holds the K-th largest score; every position in that bin or a
 //   higher one is a candidate (the K winners plus the rest of one bin).  The candidates are
-//   bucket-sorted in LDS on the 64-bit item (P image, ~position): 128 buckets per histogram bin
-//   for the 16 bins from b1 up (4 octaves of score), one more bucket for everything above;
+//   bucket-sorted in LDS on the 64-bit item (P image, ~position): 2048 buckets of equal width
+//   from the lowest candidate image up to the bin of the 64-th largest score, one more bucket
+//   for everything above (fewer than 64 items);
 //   pass A over P counts the buckets, a scan turns counts into offsets, pass B over P drops every
 //   candidate into its bucket, and each candidate's final rank is its bucket offset plus the
 //   number of larger items in its own bucket (a few dozen compares).  Ranks below K' are written
 //   out directly: idx comes out in rank order.  The kernel also clears the histogram for the
 //   next call.
-// Degenerate score distributions take slower exact paths in kernel 2: a bucket with more than
-// 1024 items -> the candidates are bitonic-sorted instead; more candidates than fit in LDS (e.g.
-// all scores equal) -> radix select over P (two more histogram passes, 11 + 10 bits) finds the
-// K-th largest image T, positions with P > T and the first positions with P == T are collected
-// in position order, then bitonic-sorted.
+// Dense or degenerate score distributions take further exact steps in kernel 2: more candidates
+// than fit in LDS -> bin b1 is cut once more by the next 11 image bits (one more pass over P) and
+// only its upper part stays a candidate; a bucket with more than 1024 items -> the candidates
+// are bitonic-sorted instead of ranked; still too many candidates (e.g. all scores equal) ->
+// a last radix pass (10 bits) finds the K-th largest image T exactly, positions with P > T and
+// the first positions with P == T are collected in position order, then bitonic-sorted.
 #include "rk_internal.h"
 #include "rk_device.h"
 
@@ -29,10 +31,9 @@ namespace rk {
 constexpr int kPoolTile = 1024;
 constexpr int kSelThreads = 1024;
 constexpr int kHistShift = 32 - 11;
-constexpr int kSubBits = 7;                              // buckets per histogram bin: 128
-constexpr int kBucketBins = 16;                          // histogram bins resolved into buckets
-constexpr int kBuckets = kBucketBins << kSubBits;        // 2048, plus one bucket for all above
+constexpr int kBuckets = 2048;                           // regular buckets, plus one for all above
 constexpr int kBucketLimit = 1024;                       // larger buckets: sort instead of ranking
+constexpr int kTopLoose = 64;                            // scores above the bucketed range: fewer than this
 static_assert(kHistBins == 1 << 11, "first-level histogram is 11 bits wide");
 
 // Order-preserving map float -> uint32 (larger float <=> larger key) and its inverse.
@@ -236,15 +237,39 @@ void select_kernel(const float* __restrict__ pooled, int64_t pooled_stride, cons
     find_bin_from_top<kSelThreads, kHistBins>(gh, (uint32_t)kprime, sScan, sOut);
     const uint32_t b1 = sOut[0];
     const uint32_t above = sOut[1];
-    const uint32_t count_ge = above + gh[b1];
+    uint32_t count_ge = above + gh[b1];
+    __syncthreads();
+    // The bin that holds the kTopLoose-th largest score bounds the bucketed range from above, so
+    // that the one bucket for "everything above" stays small (its items are ranked by a loop over
+    // the whole bucket).
+    find_bin_from_top<kSelThreads, kHistBins>(gh, min((uint32_t)kprime, (uint32_t)kTopLoose), sScan, sOut);
+    const uint32_t key_top = (sOut[0] + 1u) << kHistShift;      // sOut[0] >= b1; wraps to 0 for the last bin
     __syncthreads();                        // every thread has read the histogram: clear it
     for (int i = tid; i < kHistBins; i += kSelThreads) gh[i] = 0;
+
+    // Candidates are the positions whose image is >= key_thr.  Normally that is "bin b1 or above";
+    // if those are too many for LDS, bin b1 is cut once more by the next 11 image bits.
+    uint32_t key_thr = b1 << kHistShift;
+    uint32_t prefix = key_thr, mask = 0x7FFu << kHistShift, kk = (uint32_t)kprime - above;   // radix-select state
+    bool refined = false;
+    if (count_ge > (uint32_t)cand_cap) {
+        radix_pass<11>(P, n, prefix, mask, 10, kk, sHist, sScan, sOut);
+        const uint32_t b2 = sOut[0];
+        count_ge = above + sOut[1] + sHist[b2];
+        prefix |= b2 << 10; mask |= 0x7FFu << 10; kk -= sOut[1];
+        key_thr = prefix;
+        refined = true;
+        __syncthreads();
+    }
+    // bucket width: the smallest power of two for which [key_thr, key_top) fits in kBuckets buckets
+    int bucket_shift = 0;
+    while (((key_top - 1u - key_thr) >> bucket_shift) >= (uint32_t)kBuckets) ++bucket_shift;
 
     // Visits every candidate (position in bin b1 or above) of P: one float compare per element,
     // `visit(key, j)` runs for the candidates only.  The first 32 scores of every thread (the
     // whole row up to 32768 positions) are loaded once, 16-byte loads all in flight together,
     // and stay in registers for both passes; longer rows re-read the rest from memory.
-    const float thr = value_of(b1 << kHistShift);        // lowest score of bin b1 (scores are >= 0)
+    const float thr = value_of(key_thr);                 // lowest candidate score (scores are >= 0)
     constexpr int NV = 8;
     const float4* P4 = reinterpret_cast<const float4*>(P);
     const int nvec = (n + 3) >> 2;
@@ -278,7 +303,7 @@ void select_kernel(const float* __restrict__ pooled, int64_t pooled_stride, cons
         }
     };
     auto bucket_of = [&](uint32_t key) -> uint32_t {
-        return min((key >> (kHistShift - kSubBits)) - (b1 << kSubBits), (uint32_t)kBuckets);
+        return min((key - key_thr) >> bucket_shift, (uint32_t)kBuckets);
     };
     int nvalid;                             // entries of sKeys that are real (sorting paths)
     if (count_ge <= (uint32_t)cand_cap) {
@@ -330,11 +355,12 @@ void select_kernel(const float* __restrict__ pooled, int64_t pooled_stride, cons
         nvalid = (int)count_ge;
     } else {
         // ---- slow path: exact K-th largest image T by radix select over P ----
-        uint32_t prefix = b1 << kHistShift, mask = 0x7FFu << kHistShift, kk = (uint32_t)kprime - above;
         __syncthreads();
-        radix_pass<11>(P, n, prefix, mask, 10, kk, sHist, sScan, sOut);
-        prefix |= sOut[0] << 10; mask |= 0x7FFu << 10; kk -= sOut[1];
-        __syncthreads();
+        if (!refined) {
+            radix_pass<11>(P, n, prefix, mask, 10, kk, sHist, sScan, sOut);
+            prefix |= sOut[0] << 10; mask |= 0x7FFu << 10; kk -= sOut[1];
+            __syncthreads();
+        }
         radix_pass<10>(P, n, prefix, mask, 0, kk, sHist, sScan, sOut);
         const uint32_t T = prefix | sOut[0];
         const uint32_t need_eq = kk - sOut[1];          // >= 1 positions with image == T are taken

@@ -157,6 +157,8 @@ TOPK_CASES = [
     ("big_k", 1, 4, 1, [40000], 8192, 7, "lognormal"),
     ("max_k_ties", 1, 2, 1, [33000], 16384, 7, "ties"),
     ("pool63", 1, 2, 1, [2000], 128, 63, "lognormal"),
+    ("refine_path", 1, 2, 1, [90000], 14000, 1, "lognormal"),     # more candidates than LDS holds: bin cut again
+    ("ragged_batch", 5, 8, 2, [70000, 3, 1025, 64, 31999], 1024, 7, "lognormal"),
 ]
 
 

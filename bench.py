@@ -78,7 +78,7 @@ def main():
     weights = torch.empty(B, Hq, cap, dtype=torch.float32, device=dev)
     layers = [rk.RefreshKVLayer(geom, kv[l][0], kv[l][1], seq_lens, int(lens0.max()), w.k_small, w.stride,
                                 pool_w=w.pool_w, dynamic=w.dynamic, threshold=w.threshold,
-                                workspace=ws, weights=weights) for l in range(n_layers)]
+                                workspace=ws) for l in range(n_layers)]
     for lay in layers:
         lay.use_static_bounds(max_len_bound, max(w.stride, 1))
     torch.cuda.synchronize()
@@ -173,6 +173,8 @@ def main():
     Lb = max_len_bound
     klass = {
         "full_attn": graph_us(lambda l: rk.rk_full_attn(geom, q_cur[l], *kv[l], seq_lens, Lb, out, weights=weights, workspace=ws)),
+        "full_attn_select": graph_us(lambda l: rk.rk_full_attn_select(geom, q_cur[l], *kv[l], seq_lens, Lb, out, w.k_small, w.pool_w,
+                                                                       layers[l].idx, workspace=ws)),
         "topk_select": graph_us(lambda l: rk.rk_topk_select(geom, weights, seq_lens, Lb, w.k_small, w.pool_w, layers[l].idx, workspace=ws)),
         "gather_small_kv": graph_us(lambda l: rk.rk_gather_small_kv(geom, *kv[l], layers[l].idx, w.k_small, layers[l].small_K, layers[l].small_V)),
         "partial_attn": graph_us(lambda l: rk.rk_partial_attn(geom, q_cur[l], layers[l].small_K, layers[l].small_V, w.k_small, *kv[l],
@@ -225,8 +227,7 @@ def main():
             pmc = json.load(f)
         k = pmc["attn_split"]
         traffic = int(k["fetch_kib"] * 1024 * pmc["fetch_scale"] + k["write_kib"] * 1024 * pmc["write_scale"])
-    tiles = 2 if w.group <= 4 else 1
-    roofline = {"bound": "hbm", "kernel": "rk::attn_split_kernel<%d, 4, %d, true, false> (first kernel of rk_full_attn when weights are returned)" % (w.group, tiles),
+    roofline = {"bound": "hbm", "kernel": "rk::attn_split_kernel<%d, 4, true, false> (first kernel of rk_full_attn when weights are returned)" % w.group,
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                 "avg_launch_us": round(split_us, 2), "launches": n_roof_launches, "algorithmic_bytes": algo_bytes}

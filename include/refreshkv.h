@@ -13,6 +13,7 @@
  *                       group, max-pool over neighbouring tokens, top-K
  *                       (Section 2.2 "Prefilling stage" + its GQA footnote; Appendix A.1
  *                       "Baseline Settings": kernel size 7; Appendix A.3)
+ *   rk_full_attn_select the two steps above in one call (what a full step of the method does)
  *   rk_gather_small_kv  rebuild C_p from the selected rows of C_f         (Section 2.2)
  *   rk_partial_attn     partial-attention step over C_p plus the tokens decoded since the
  *                       refresh                      (Section 2.2, "Decoding with partial cache")
@@ -149,6 +150,20 @@ int rk_topk_select(const rk_geom* geom, const float* weights, int64_t w_stride,
                    int32_t* idx, float* sel_scores,
                    const int32_t* pred, int32_t pred_val,
                    void* workspace, size_t workspace_bytes, void* stream);
+
+/* The two calls above in one: a full-attention step whose attention weights go straight into
+ * the selection (Section 2.2, "Decoding with full cache": every full step is followed by the
+ * refresh of the small cache).  Results are those of rk_full_attn followed by rk_topk_select on
+ * its weights; the weights stay in the workspace between the kernels, one launch and one pass
+ * over them are saved.  `weights` may be NULL when the caller does not want them returned
+ * (otherwise as in rk_full_attn); every other argument as in the two calls. */
+int rk_full_attn_select(const rk_geom* geom, const void* q, rk_kv full,
+                        const int32_t* seq_lens, int32_t max_len,
+                        void* out, float* weights, int64_t w_stride, float* lse,
+                        int32_t k, int32_t pool_w, int32_t agg,
+                        int32_t* idx, float* sel_scores,
+                        const int32_t* pred, int32_t pred_val,
+                        void* workspace, size_t workspace_bytes, void* stream);
 
 /* Rebuild the small cache: small.k[b,g,i,:] = full.k[b,g,idx[b,g,i],:] and the same for v, for
  * every i < k with idx >= 0 (bit copies).  Slots whose idx is negative are left untouched.

@@ -5,15 +5,17 @@ A thin ctypes binding over ``librefreshkv.so`` (hand-written HIP; C ABI declared
 in the HIP kernels.  PyTorch tensors are used as device memory and for the current stream.
 
 Importing this package loads the shared library and fails if it has not been built
-(``python -m paper_2411_05787_amd.build``): there is no CPU fallback.
+(``python paper_2411_05787_amd/build.py``): there is no CPU fallback.
 """
 from .binding import (LIB_PATH, RkError, Geom, Workspace, lib, version, status_string, workspace_bytes,
-                      rk_workspace_init, rk_full_attn, rk_full_attn_scores, rk_topk_select, rk_gather_small_kv,
+                      rk_workspace_init, rk_full_attn, rk_full_attn_scores, rk_topk_select, rk_full_attn_select,
+                      rk_gather_small_kv,
                       rk_partial_attn, rk_query_sim, rk_mark_refresh, rk_calibration_copy, EXPORTS)
 from .schedule import RefreshKVLayer
 
 __all__ = ["LIB_PATH", "RkError", "Geom", "Workspace", "lib", "version", "status_string",
            "workspace_bytes", "rk_workspace_init", "rk_full_attn", "rk_full_attn_scores", "rk_topk_select",
+           "rk_full_attn_select",
            "rk_gather_small_kv", "rk_partial_attn", "rk_query_sim", "rk_mark_refresh", "rk_calibration_copy",
            "EXPORTS",
            "RefreshKVLayer"]

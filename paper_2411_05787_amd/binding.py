@@ -16,7 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "librefreshkv.so")
 
 EXPORTS = ["rk_version", "rk_status_string", "rk_workspace_bytes", "rk_workspace_init",
-           "rk_full_attn", "rk_full_attn_scores", "rk_topk_select", "rk_gather_small_kv", "rk_partial_attn",
+           "rk_full_attn", "rk_full_attn_scores", "rk_topk_select", "rk_full_attn_select", "rk_gather_small_kv", "rk_partial_attn",
            "rk_query_sim", "rk_mark_refresh", "rk_calibration_copy"]
 
 RK_AGG_MAX = 0
@@ -41,7 +41,7 @@ class _Kv(C.Structure):
 def _load(path: str = LIB_PATH) -> C.CDLL:
     if not os.path.exists(path):
         raise ImportError("librefreshkv.so is not built (%s missing); run "
-                          "`python -m paper_2411_05787_amd.build` first. There is no fallback path." % path)
+                          "`python paper_2411_05787_amd/build.py` first. There is no fallback path." % path)
     l = C.CDLL(path)
     P, I32, I64, SZ = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t
     G = C.POINTER(_Geom)
@@ -60,6 +60,8 @@ def _load(path: str = LIB_PATH) -> C.CDLL:
     l.rk_topk_select.restype = C.c_int
     l.rk_topk_select.argtypes = [G, P, I64, P, I32, I32, I32, I32, P, P, P, I32, P, SZ, P]
     l.rk_gather_small_kv.restype = C.c_int
+    l.rk_full_attn_select.argtypes = [G, P, _Kv, P, I32, P, P, I64, P, I32, I32, I32, P, P, P, I32, P, SZ, P]
+    l.rk_full_attn_select.restype = C.c_int
     l.rk_gather_small_kv.argtypes = [G, _Kv, P, I32, _Kv, P, P, P, I32, P]
     l.rk_partial_attn.restype = C.c_int
     l.rk_partial_attn.argtypes = [G, P, _Kv, I32, _Kv, P, P, I32, P, P, I32, P, SZ, P]
@@ -206,6 +208,30 @@ def rk_topk_select(geom: Geom, weights, seq_lens, max_len: int, k: int, pool_w: 
     _check("rk_topk_select", lib.rk_topk_select(
         C.byref(geom.c()), _dev(weights, torch.float32, "weights"), weights.shape[2],
         _dev(seq_lens, torch.int32, "seq_lens", (B,)), int(max_len), int(k), int(pool_w), int(agg),
+        _dev(idx, torch.int32, "idx", (B, Hkv, k)),
+        _dev(sel_scores, torch.float32, "sel_scores", (B, Hkv, k), optional=True),
+        _dev(pred, torch.int32, "pred", (B,), optional=True), int(pred_val),
+        workspace.ptr, workspace.nbytes, _stream(stream)))
+
+
+def rk_full_attn_select(geom: Geom, q, K, V, seq_lens, max_len: int, out, k: int, pool_w: int, idx,
+                        weights=None, lse=None, sel_scores=None, agg: int = RK_AGG_MAX,
+                        pred=None, pred_val: int = 0, workspace: Workspace = None, stream=None) -> None:
+    B, Hq, Hkv, D = geom.batch, geom.n_q_heads, geom.n_kv_heads, geom.head_dim
+    if max_len > K.shape[2]:
+        raise ValueError("max_len %d exceeds the cache capacity %d" % (max_len, K.shape[2]))
+    w_stride = 0
+    if weights is not None:
+        if weights.dim() != 3 or weights.shape[0] != B or weights.shape[1] != Hq or weights.shape[2] < max_len:
+            raise ValueError("weights must be [batch, n_q_heads, >= max_len]")
+        w_stride = weights.shape[2]
+    _check("rk_full_attn_select", lib.rk_full_attn_select(
+        C.byref(geom.c()), _dev(q, torch.bfloat16, "q", (B, Hq, D)), _kv(geom, K, V, "full"),
+        _dev(seq_lens, torch.int32, "seq_lens", (B,)), int(max_len),
+        _dev(out, torch.bfloat16, "out", (B, Hq, D)),
+        _dev(weights, torch.float32, "weights", optional=True), w_stride,
+        _dev(lse, torch.float32, "lse", (B, Hq), optional=True),
+        int(k), int(pool_w), int(agg),
         _dev(idx, torch.int32, "idx", (B, Hkv, k)),
         _dev(sel_scores, torch.float32, "sel_scores", (B, Hkv, k), optional=True),
         _dev(pred, torch.int32, "pred", (B,), optional=True), int(pred_val),

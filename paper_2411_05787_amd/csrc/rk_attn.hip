@@ -41,7 +41,7 @@ struct AttnParams {
     int32_t n_sel;                     // rows taken from the small cache (TWO_SEG only)
     int32_t max_rows2;                 // host bound on the rows taken from the full cache
     int32_t cap1, cap2;                // rows allocated in the small / full cache
-    int32_t chunk;                     // rows per workgroup
+    int32_t nch;                       // workgroups per (sequence, KV head): the launch's grid x
     int32_t Hq, Hkv;
     float scale;
     uint16_t* out;                     // bf16 [B, Hq, 128]
@@ -51,6 +51,17 @@ struct AttnParams {
     const int32_t* pred; int32_t pred_val;
     int32_t* counters; float* part_ml; float* part_o; int32_t max_chunks;
 };
+
+// Work split of the split kernels.  The rows of a (sequence, KV head) are cut into tiles of 32;
+// tile t belongs to wavefront t % 4 of workgroup (t / 4) % nch, so workgroup c starts at row
+// 128 c and the tiles go round the nch * 4 wavefronts of the launch: every wavefront gets the
+// same number of tiles, give or take one, whatever the length, and at any moment the launch
+// streams one contiguous stretch of the cache.  Workgroups whose first row is past the end do
+// nothing; the others each leave one partial result (the merge takes any subsets of the rows).
+constexpr int kSplitWaves = 4, kTileRows = 32;
+__device__ __forceinline__ int active_workgroups(int n_rows, int nch) {
+    return max(1, min(nch, (n_rows + kSplitWaves * kTileRows - 1) / (kSplitWaves * kTileRows)));
+}
 
 __device__ __forceinline__ void coherent_store2(float* p, float a, float b) {
     const uint64_t v = (uint64_t)__float_as_uint(a) | ((uint64_t)__float_as_uint(b) << 32);
@@ -66,87 +77,85 @@ __device__ __forceinline__ void wait_stores_acknowledged() { asm volatile("s_wai
 
 // Merge of the partial results of one (sequence, KV head); run by one whole workgroup.
 //   M = max_c m_c;  L = sum_c e^{m_c - M} l_c;  out = sum_c e^{m_c - M} o_c / L;  lse = M + ln L
+// Only one workgroup per (sequence, KV head) ever gets here, on whichever CU it happens to run,
+// so this code is fetched cold: it is kept small (rolled loops, no fp64 library calls) because
+// instruction fetch, not arithmetic, is what its run time is made of.  Partial outputs are read
+// in batches of kMergeBatch chunks, two batches ahead of their use: up to 2 * kMergeBatch chunks
+// cost one round trip, requested together with the (max, sum) pairs.
+constexpr int kMergeBatch = 16;
+
 template <int G, int NW>
 __device__ void merge_partials(const AttnParams& p, int b, int g, int nchunks, float* sW, float* sLc,
                                float* sM, double* sL) {
     constexpr int NT = NW * 64;
     constexpr int PER = G * kD / 2;               // pairs of consecutive dims to produce
-    constexpr int ROUNDS = (PER + NT - 1) / NT;   // per thread: 1 (G <= 4) or 2
-    constexpr int SUB = 16;                       // loads are issued in uniform groups of 16 chunks
-    static_assert(kMergeChunks % SUB == 0, "chunk groups");
+    constexpr int SLICES = (PER + NT - 1) / NT;   // pairs per thread: 1 (G <= 4) or 2
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int64_t bg = (int64_t)b * p.Hkv + g;
     const float* ml = p.part_ml + bg * kMaxChunks * G * 2;
     const float* po = p.part_o + bg * p.max_chunks * G * kD;
     const int n_ml = nchunks * G;
+    static_assert(2 * NT >= kMergeChunks * RK_MAX_GROUP, "two loads per thread cover all (chunk, head) pairs");
 
-    // Everything that has to come from memory is requested up front, in one round trip:
-    // the (max, sum) pairs of every chunk and head, and this thread's slice of every partial output.
-    uint64_t vml[4];
+    // Work items of this thread, in order: (slice 0, batch 0), (slice 0, batch 1), ... (slice 1, batch 0) ...
+    const int nb = (nchunks + kMergeBatch - 1) / kMergeBatch;
+    const int n_items = SLICES * nb;
+    uint64_t cur[kMergeBatch], nxt[kMergeBatch];
+    auto request = [&](uint64_t (&dst)[kMergeBatch], int item) {
+        const int e2 = min((item / nb) * NT + tid, PER - 1), c0 = (item % nb) * kMergeBatch;
+        const float* src = po + 2 * e2;
 #pragma unroll
-    for (int u = 0; u < 4; ++u) vml[u] = coherent_load2(ml + (int64_t)min(u * NT + tid, n_ml - 1) * 2);
-    uint64_t v[kMergeChunks];
-    auto request = [&](int r) {
-        const int e2 = min(r * NT + tid, PER - 1);
-#pragma unroll
-        for (int c0 = 0; c0 < kMergeChunks; c0 += SUB) {
-            if (c0 < nchunks) {                   // uniform over the workgroup
-#pragma unroll
-                for (int u = 0; u < SUB; ++u)
-                    v[c0 + u] = coherent_load2(po + (int64_t)min(c0 + u, nchunks - 1) * G * kD + 2 * e2);
-            } else {
-#pragma unroll
-                for (int u = 0; u < SUB; ++u) v[c0 + u] = 0;
-            }
-        }
+        for (int u = 0; u < kMergeBatch; ++u) dst[u] = coherent_load2(src + (int64_t)min(c0 + u, nchunks - 1) * G * kD);
     };
-    request(0);
-    static_assert(4 * NT >= kMergeChunks * G, "one batch covers all (chunk, head) pairs");
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-        const int i = u * NT + tid;
-        if (i < n_ml) { sW[i] = lo_f(vml[u]); sLc[i] = hi_f(vml[u]); }
-    }
+    // everything below is requested before the first wait
+    const uint64_t ml0 = coherent_load2(ml + (int64_t)min(tid, n_ml - 1) * 2);
+    const uint64_t ml1 = coherent_load2(ml + (int64_t)min(NT + tid, n_ml - 1) * 2);
+    request(cur, 0);
+    if (n_items > 1) request(nxt, 1);
+    if (tid < n_ml) { sW[tid] = lo_f(ml0); sLc[tid] = hi_f(ml0); }
+    if (NT + tid < n_ml) { sW[NT + tid] = lo_f(ml1); sLc[NT + tid] = hi_f(ml1); }
     __syncthreads();
     // one wavefront per head: M = max_c m_c, w_c = e^{m_c - M} (overwrites m_c), L = sum_c w_c l_c
     for (int gi = w; gi < G; gi += NW) {
-        float mx = -INFINITY;
-        for (int c = lane; c < nchunks; c += 64) mx = fmaxf(mx, sW[c * G + gi]);
-        mx = wave_max(mx);
-        double ls = 0.0;                          // the sum that normalises the output: fp64
-        for (int c = lane; c < nchunks; c += 64) {
-            const float mc = sW[c * G + gi];
-            const float wgt = (mc == -INFINITY) ? 0.f : fast_exp2((mc - mx) * kLog2e);
-            sW[c * G + gi] = wgt;
-            ls += (double)wgt * (double)sLc[c * G + gi];
-        }
+        const int c = min(lane, nchunks - 1);     // nchunks <= kMergeChunks = 64: one chunk per lane
+        const float mc = sW[c * G + gi];
+        const float mx = wave_max(mc);
+        const float wgt = (lane >= nchunks || mc == -INFINITY) ? 0.f : fast_exp2((mc - mx) * kLog2e);
+        double ls = (double)wgt * (double)sLc[c * G + gi];      // the sum that normalises the output: fp64
+        if (lane < nchunks) sW[c * G + gi] = wgt;
 #pragma unroll
         for (int m = 1; m < 64; m <<= 1) ls += __shfl_xor(ls, m);
         if (lane == 0) { sM[gi] = mx; sL[gi] = ls; }
     }
     __syncthreads();
+    float acc0 = 0.f, acc1 = 0.f;
+#pragma unroll 1
+    for (int item = 0; item < n_items; ++item) {
+        const int slice = item / nb, c0 = (item % nb) * kMergeBatch;
+        const int e2 = min(slice * NT + tid, PER - 1);
+        const int gi = (2 * e2) / kD;
 #pragma unroll
-    for (int r = 0; r < ROUNDS; ++r) {
-        if (r > 0) request(r);                    // G > 4: a second round trip for the other half
-        const int e2 = r * NT + tid;
-        if (e2 < PER) {
-            const int gi = (2 * e2) / kD;
-            float acc0 = 0.f, acc1 = 0.f;
+        for (int u = 0; u < kMergeBatch; ++u) {
+            const float wgt = (c0 + u < nchunks) ? sW[(c0 + u) * G + gi] : 0.f;
+            acc0 = fmaf(wgt, lo_f(cur[u]), acc0);
+            acc1 = fmaf(wgt, hi_f(cur[u]), acc1);
+        }
 #pragma unroll
-            for (int c = 0; c < kMergeChunks; ++c) {
-                const float wgt = (c < nchunks) ? sW[c * G + gi] : 0.f;
-                acc0 = fmaf(wgt, lo_f(v[c]), acc0);
-                acc1 = fmaf(wgt, hi_f(v[c]), acc1);
+        for (int u = 0; u < kMergeBatch; ++u) cur[u] = nxt[u];
+        if (item + 2 < n_items) request(nxt, item + 2);
+        if (c0 + kMergeBatch >= nchunks) {         // last batch of the slice
+            if (slice * NT + tid < PER) {
+                const float L = (float)sL[gi];
+                const float inv = L > 0.f ? 1.f / L : 0.f;
+                const uint32_t packed = (uint32_t)f32_to_bf16(acc0 * inv) | ((uint32_t)f32_to_bf16(acc1 * inv) << 16);
+                reinterpret_cast<uint32_t*>(p.out + ((int64_t)b * p.Hq + g * G) * kD)[e2] = packed;
             }
-            const float L = (float)sL[gi];
-            const float inv = L > 0.f ? 1.f / L : 0.f;
-            const uint32_t packed = (uint32_t)f32_to_bf16(acc0 * inv) | ((uint32_t)f32_to_bf16(acc1 * inv) << 16);
-            reinterpret_cast<uint32_t*>(p.out + ((int64_t)b * p.Hq + g * G) * kD)[e2] = packed;
+            acc0 = 0.f; acc1 = 0.f;
         }
     }
-    if (tid < G) {
-        const double L = sL[tid];
-        p.lse[(int64_t)b * p.Hq + g * G + tid] = L > 0.0 ? (float)((double)sM[tid] + log(L)) : -INFINITY;
+    if (tid < G) {                                // fp32 log: lse is an fp32 output, M + ln L loses nothing that matters
+        const float L = (float)sL[tid];
+        p.lse[(int64_t)b * p.Hq + g * G + tid] = L > 0.f ? sM[tid] + logf(L) : -INFINITY;
     }
 }
 
@@ -175,9 +184,10 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 //   V operand   dim 16*dt + n16, the same slots (LDS transpose read)
 //   O result    dim 16*dt + n16, heads 4*c4 + i
 template <int G, int NW, bool EMIT, bool TWO_SEG>
-__global__ __launch_bounds__(NW * 64, 2)
+__global__ __launch_bounds__(NW * 64, EMIT ? 3 : 2)
 void attn_split_kernel(const AttnParams p) {
-    constexpr int ROWS = 32;                 // rows per wavefront and tile = contraction depth of P V
+    constexpr int ROWS = kTileRows;          // rows per wavefront and tile = contraction depth of P V
+    static_assert(NW == kSplitWaves, "work split");
     constexpr int NV = ROWS / 4;             // V loads per lane and tile
     constexpr int NC = (G + 3) / 4;          // lane groups whose O accumulators hold real heads
     constexpr int NT = NW * 64;
@@ -189,14 +199,14 @@ void attn_split_kernel(const AttnParams p) {
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int n16 = lane & 15, c4 = lane >> 4;
 
-    // ---- K rows of the first tile are requested before any length is known ----
+    // ---- K and V rows of the first tile are requested before any length is known ----
     // Rows below `spec_rows` exist whatever the device-side lengths say (small cache: the first
-    // n_sel rows; full cache: its capacity), so a chunk that lies wholly below it may be read
-    // at once; rows that turn out to be past the end are masked like any other.  This takes the
-    // round trip for seq_lens / tail_start off the critical path of every workgroup.
-    const int r_first = c * p.chunk + w * ROWS;
+    // n_sel rows; full cache: its capacity), so a workgroup whose first 128 rows lie wholly below
+    // it may read them at once; rows that turn out to be past the end are masked like any other.
+    // This takes the round trip for seq_lens / tail_start off the critical path.
+    const int r_first = (c * NW + w) * ROWS;
     const int spec_rows = TWO_SEG ? min(p.n_sel, p.cap1) : p.cap2;
-    const bool spec = (int64_t)(c + 1) * p.chunk <= spec_rows;
+    const bool spec = (c + 1) * NW * ROWS <= spec_rows;
     u32x4 kA[2][4], vA[NV];
     if (spec) {
         const uint16_t* kspec = (TWO_SEG ? p.k1 + (int64_t)b * p.s1_b + (int64_t)g * p.s1_h
@@ -206,6 +216,11 @@ void attn_split_kernel(const AttnParams p) {
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk)
                 kA[t][kk] = *reinterpret_cast<const u32x4*>(kspec + (int64_t)(r_first + t * 16 + n16) * kD + kk * 32);
+        const uint16_t* vspec = (TWO_SEG ? p.v1 + (int64_t)b * p.s1_b + (int64_t)g * p.s1_h
+                                         : p.v2 + (int64_t)b * p.s2_b + (int64_t)g * p.s2_h) + n16 * 8;
+#pragma unroll
+        for (int jj = 0; jj < NV; ++jj)
+            vA[jj] = *reinterpret_cast<const u32x4*>(vspec + (int64_t)(r_first + jj * 4 + c4) * kD);
     }
 
     // ---- Q: head n16, dims 8*(4*kk + c4) .. +7 ----
@@ -232,10 +247,9 @@ void attn_split_kernel(const AttnParams p) {
     }
     const int n2 = min(max(len - start2, 0), p.max_rows2);
     const int n = n1 + n2;
-    const int nchunks = max(1, (n + p.chunk - 1) / p.chunk);
+    const int nchunks = active_workgroups(n, p.nch);
     if (c >= nchunks) return;
-    const int row0 = c * p.chunk;
-    const int row1 = min(n, row0 + p.chunk);
+    const int row1 = n;
 
     const uint16_t* kb1 = nullptr; const uint16_t* vb1 = nullptr;
     if (TWO_SEG) {
@@ -365,13 +379,21 @@ void attn_split_kernel(const AttnParams p) {
     };
 
     {
-        const int step = NW * ROWS;
+        const int step = p.nch * NW * ROWS;
         int r = r_first;
         if (r < row1) {
             // the early request stands unless part of this chunk maps to the tail of the full cache
-            const bool spec_ok = spec && (!TWO_SEG || (c + 1) * p.chunk <= n1);
-            if (!spec_ok) load_k(r);
-            load_v(r);
+            const bool spec_ok = spec && (!TWO_SEG || (c + 1) * NW * ROWS <= n1);
+            if (!spec_ok) {
+                load_k(r); load_v(r);
+            } else if (r + ROWS > row1) {
+                // early V rows past the end of the list hold whatever the cache holds there, maybe
+                // NaN: P is 0 for them, but 0 * NaN is NaN, so they are cleared (early K rows need
+                // nothing: their scores are replaced by -inf)
+#pragma unroll
+                for (int jj = 0; jj < NV; ++jj)
+                    if (r + jj * 4 + c4 >= row1) vA[jj] = u32x4{0u, 0u, 0u, 0u};
+            }
         }
         for (; r < row1; r += step) compute_tile(r, r + step);
     }
@@ -428,13 +450,102 @@ void attn_split_kernel(const AttnParams p) {
     if (tid == 0) __hip_atomic_store(&p.counters[bg], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // next call
 }
 
+// ---- pieces of the kernels that finish a full step whose scores were emitted ----
+// LDS of one 256-thread workgroup that rebuilds lse of a query head and merges its output.
+struct HeadMergeLds {
+    __attribute__((aligned(8))) float red[8];
+    float w[kMaxChunks];
+    float lse[2];
+    double L64;
+    float acc[4][kD];
+};
+constexpr int kOutBatch = 16;                    // partial outputs per thread and round trip
+
+// lse of (b, h) in fp64 from the per-chunk (max, sum) pairs: s.lse = (hi, lo) with hi + lo = lse,
+// s.w[c] = e^{m_c - M}, s.L64 = sum_c w_c l_c.  All 256 threads call; ends with a barrier.
+__device__ __forceinline__ void block_head_lse(const AttnParams& p, int G, int64_t bg, int gi, int nchunks,
+                                               HeadMergeLds& s) {
+    const int tid = threadIdx.x;
+    const float* ml = p.part_ml + (bg * kMaxChunks * G + gi) * 2;
+    float m = -INFINITY, l = 0.f;
+    if (tid < nchunks) {                                   // nchunks <= kMaxChunks == blockDim
+        const float2 t2 = *reinterpret_cast<const float2*>(ml + (int64_t)tid * G * 2);
+        m = t2.x; l = t2.y;
+    }
+    const float M = block_max<4>(m, s.red);
+    const float wgt = (m == -INFINITY) ? 0.f : fast_exp2((m - M) * kLog2e);
+    if (tid < nchunks) s.w[tid] = wgt;
+    const double L64 = block_sum_f64<4>((double)wgt * (double)l, reinterpret_cast<double*>(s.red));
+    if (tid == 0) {
+        float hi = -INFINITY, lo = 0.f;
+        if (L64 > 0.0) {
+            const double l64 = (double)M + log(L64);
+            hi = (float)l64;
+            lo = (float)(l64 - (double)hi);
+        }
+        s.lse[0] = hi; s.lse[1] = lo; s.L64 = L64;
+    }
+    __syncthreads();
+}
+
+// First round of partial-output loads of (b, h); issued before block_head_lse so that the
+// reductions there run under the memory latency.
+__device__ __forceinline__ void head_out_request(const AttnParams& p, int G, int64_t bg, int gi, int nchunks,
+                                                 float2 (&v)[kOutBatch]) {
+    const int cg = threadIdx.x >> 6, d2 = threadIdx.x & 63;
+    const float* po = p.part_o + (bg * p.max_chunks * G + gi) * kD + 2 * d2;
+#pragma unroll
+    for (int u = 0; u < kOutBatch; ++u)
+        v[u] = *reinterpret_cast<const float2*>(po + (int64_t)min(cg + 4 * u, nchunks - 1) * G * kD);
+}
+
+// out[b,h,:] = sum_c w_c o_c[h,:] / L and lse[b,h]: four groups of 64 lanes take every fourth
+// chunk.  Needs block_head_lse's results in s and head_out_request's in v.
+__device__ __forceinline__ void block_head_out(const AttnParams& p, int G, int b, int64_t bg, int gi, int nchunks,
+                                               HeadMergeLds& s, float2 (&v)[kOutBatch]) {
+    const int tid = threadIdx.x, cg = tid >> 6, d2 = tid & 63;
+    const int h = (int)(bg % p.Hkv) * G + gi;
+    const float* po = p.part_o + (bg * p.max_chunks * G + gi) * kD + 2 * d2;
+    float acc0 = 0.f, acc1 = 0.f;
+    for (int c0 = cg; c0 < nchunks; c0 += 4 * kOutBatch) {
+        if (c0 != cg) {
+#pragma unroll
+            for (int u = 0; u < kOutBatch; ++u)
+                v[u] = *reinterpret_cast<const float2*>(po + (int64_t)min(c0 + 4 * u, nchunks - 1) * G * kD);
+        }
+#pragma unroll
+        for (int u = 0; u < kOutBatch; ++u) {
+            const float wc = (c0 + 4 * u < nchunks) ? s.w[c0 + 4 * u] : 0.f;
+            acc0 = fmaf(wc, v[u].x, acc0);
+            acc1 = fmaf(wc, v[u].y, acc1);
+        }
+    }
+    s.acc[cg][2 * d2] = acc0; s.acc[cg][2 * d2 + 1] = acc1;
+    __syncthreads();
+    if (tid < kD) {
+        const float L = (float)s.L64;
+        const float o = L > 0.f ? (s.acc[0][tid] + s.acc[1][tid] + s.acc[2][tid] + s.acc[3][tid]) / L : 0.f;
+        p.out[((int64_t)b * p.Hq + h) * kD + tid] = f32_to_bf16(o);
+    }
+    if (tid == 0) p.lse[(int64_t)b * p.Hq + h] = s.lse[0];
+}
+
+// weight = e^{s - lse} with lse = -nl + ll given as an fp32 pair.  The exponent is formed as an
+// exact fp32 pair (two-sum) minus the low part of lse, so a weight carries the error of its
+// score and of expf only (a plain fp32 subtraction alone would cost up to 5e-7 relative, which
+// is the size of the gaps that decide the selection).
+__device__ __forceinline__ float weight_of(float s, float nl, float ll) {
+    const float hi = s + nl;
+    const float bp = hi - s;
+    const float lo = (s - (hi - bp)) + (nl - bp) - ll;     // s - lse = hi + lo, |lo| << 1
+    const float e = expf(hi);
+    return fmaf(e, lo, e);
+}
+
 // Second kernel of a full step that returns the attention weights.  Every workgroup first
-// rebuilds lse of its (sequence, query head) from the per-chunk (max, sum) pairs, in fp64.
-// Workgroup x = 0 then merges the partial outputs of that head; workgroups x >= 1 turn
-// kNormTile raw scores each into weights[b,h,j] = exp(s[b,h,j] - lse[b,h]), in place.  The
-// exponent is formed as an exact fp32 pair (two-sum) minus the low part of lse, so a weight
-// carries the error of its score and of expf only (a plain fp32 subtraction alone would cost
-// up to 5e-7 relative, which is the size of the gaps that decide the selection).
+// rebuilds lse of its (sequence, query head).  Workgroup x = 0 then merges the partial outputs of
+// that head; workgroups x >= 1 turn kNormTile raw scores each into
+// weights[b,h,j] = exp(s[b,h,j] - lse[b,h]), in place.
 constexpr int kNormTile = 4096;
 
 __global__ __launch_bounds__(256)
@@ -444,32 +555,18 @@ void merge_normalise_kernel(const AttnParams p, int G) {
     const int tid = threadIdx.x;
     const int g = h / G, gi = h % G;
     const int len = min(max(min(p.seq_lens[b], p.cap2), 0), p.max_rows2);
-    const int nchunks = max(1, (len + p.chunk - 1) / p.chunk);
+    const int nchunks = active_workgroups(len, p.nch);
     const int j0 = (x - 1) * kNormTile;
     if (x >= 1 && j0 >= len) return;
 
-    __shared__ __attribute__((aligned(8))) float sRed[8];
-    __shared__ float sW[kMaxChunks];
-    __shared__ float sLse[2];
-    __shared__ double sL64;
-    __shared__ float sAcc[4][kD];
+    __shared__ HeadMergeLds s;
     constexpr int PER = kNormTile / 256;         // scores per thread
-    constexpr int BATCH = 16;                    // partial outputs per thread and round trip
-
     const int64_t bg = (int64_t)b * p.Hkv + g;
-    const float* ml = p.part_ml + (bg * kMaxChunks * G + gi) * 2;
     float* row = p.weights + ((int64_t)b * p.Hq + h) * p.w_stride;
-    const int cg = tid >> 6, d2 = tid & 63;
-    const float* po = p.part_o + (bg * p.max_chunks * G + gi) * kD + 2 * d2;
 
     // ---- request everything this workgroup needs before the first wait ----
-    float m = -INFINITY, l = 0.f;
-    if (tid < nchunks) {                                   // nchunks <= kMaxChunks == blockDim
-        const float2 t2 = *reinterpret_cast<const float2*>(ml + (int64_t)tid * G * 2);
-        m = t2.x; l = t2.y;
-    }
     float sc[PER];
-    float2 v[BATCH];
+    float2 v[kOutBatch];
     if (x >= 1) {
 #pragma unroll
         for (int i = 0; i < PER; ++i) {
@@ -477,66 +574,160 @@ void merge_normalise_kernel(const AttnParams p, int G) {
             sc[i] = (j < len) ? row[j] : 0.f;
         }
     } else {
-#pragma unroll
-        for (int u = 0; u < BATCH; ++u) v[u] = *reinterpret_cast<const float2*>(po + (int64_t)min(cg + 4 * u, nchunks - 1) * G * kD);
+        head_out_request(p, G, bg, gi, nchunks, v);
     }
-
-    // ---- lse of (b, h) in fp64 ----
-    const float M = block_max<4>(m, sRed);
-    const float wgt = (m == -INFINITY) ? 0.f : fast_exp2((m - M) * kLog2e);
-    if (tid < nchunks) sW[tid] = wgt;
-    const double L64 = block_sum_f64<4>((double)wgt * (double)l, reinterpret_cast<double*>(sRed));
-    if (tid == 0) {
-        float hi = -INFINITY, lo = 0.f;
-        if (L64 > 0.0) {
-            const double l64 = (double)M + log(L64);
-            hi = (float)l64;
-            lo = (float)(l64 - (double)hi);
-        }
-        sLse[0] = hi; sLse[1] = lo; sL64 = L64;
-    }
-    __syncthreads();
-
+    block_head_lse(p, G, bg, gi, nchunks, s);
     if (x == 0) {
-        // out[b,h,:] = sum_c w_c o_c[h,:] / L: four groups of 64 lanes take every fourth chunk
-        float acc0 = 0.f, acc1 = 0.f;
-        for (int c0 = cg; c0 < nchunks; c0 += 4 * BATCH) {
-            if (c0 != cg) {
-#pragma unroll
-                for (int u = 0; u < BATCH; ++u)
-                    v[u] = *reinterpret_cast<const float2*>(po + (int64_t)min(c0 + 4 * u, nchunks - 1) * G * kD);
-            }
-#pragma unroll
-            for (int u = 0; u < BATCH; ++u) {
-                const float wc = (c0 + 4 * u < nchunks) ? sW[c0 + 4 * u] : 0.f;
-                acc0 = fmaf(wc, v[u].x, acc0);
-                acc1 = fmaf(wc, v[u].y, acc1);
-            }
-        }
-        sAcc[cg][2 * d2] = acc0; sAcc[cg][2 * d2 + 1] = acc1;
-        __syncthreads();
-        if (tid < kD) {
-            const float L = (float)sL64;
-            const float o = L > 0.f ? (sAcc[0][tid] + sAcc[1][tid] + sAcc[2][tid] + sAcc[3][tid]) / L : 0.f;
-            p.out[((int64_t)b * p.Hq + h) * kD + tid] = f32_to_bf16(o);
-        }
-        if (tid == 0) p.lse[(int64_t)b * p.Hq + h] = sLse[0];
+        block_head_out(p, G, b, bg, gi, nchunks, s, v);
         return;
     }
-
-    const float nl = -sLse[0], ll = sLse[1];
+    const float nl = -s.lse[0], ll = s.lse[1];
 #pragma unroll
     for (int i = 0; i < PER; ++i) {
         const int j = j0 + i * 256 + tid;
-        if (j < len) {
-            const float s = sc[i];
-            const float hi = s + nl;
-            const float bp = hi - s;
-            const float lo = (s - (hi - bp)) + (nl - bp) - ll;     // s - lse = hi + lo, |lo| << 1
-            const float e = expf(hi);
-            row[j] = fmaf(e, lo, e);
+        if (j < len) row[j] = weight_of(sc[i], nl, ll);
+    }
+}
+
+// Second kernel of a full step that goes straight on to the selection (Section 2.2, "Decoding
+// with full cache": the attention weights of the step decide the small cache).  Grid x < G: the
+// output merge of query head x of the group, as above.  Grid x >= G: one tile of kPoolTile
+// positions of one KV group: lse of all G heads (one wavefront per head), the weights of the
+// tile and its pooling halo, their max over the group, the max-pool, and the first-level
+// histogram of the selection.  Raw scores are read from `scores` (never modified, so the halo
+// of a neighbouring tile is always raw); weights are written only if the caller wants them.
+template <int G>
+__global__ __launch_bounds__(256)
+void finish_pool_kernel(const AttnParams p, const float* __restrict__ scores, int64_t s_stride, int half,
+                        float* __restrict__ pooled, int64_t pooled_stride, uint32_t* __restrict__ hist) {
+    const int x = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+    if (p.pred != nullptr && p.pred[b] != p.pred_val) return;
+    const int tid = threadIdx.x;
+    const int len = min(max(min(p.seq_lens[b], p.cap2), 0), p.max_rows2);
+    const int nchunks = active_workgroups(len, p.nch);
+    const int64_t bg = (int64_t)b * p.Hkv + g;
+
+    __shared__ HeadMergeLds s;
+    if (x < G) {
+        float2 v[kOutBatch];
+        head_out_request(p, G, bg, x, nchunks, v);
+        block_head_lse(p, G, bg, x, nchunks, s);
+        block_head_out(p, G, b, bg, x, nchunks, s, v);
+        return;
+    }
+    const int j0 = (x - G) * kPoolTile;
+    if (j0 >= len) return;
+
+    __shared__ float sA[kPoolTile + RK_MAX_POOL_W - 1];
+    __shared__ uint32_t sH[kHistBins];
+    __shared__ float sLse[G][2];
+    constexpr int R = (kPoolTile + RK_MAX_POOL_W - 1 + 255) / 256;
+    const int span = kPoolTile + 2 * half;
+    const float* sg = scores + ((int64_t)b * p.Hq + (int64_t)g * G) * s_stride;
+
+    // ---- request the raw scores of the tile and its halo, and the chunk statistics ----
+    float sc[G][R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int i = r * 256 + tid, j = j0 - half + i;
+        const bool in = i < span && j >= 0 && j < len;
+#pragma unroll
+        for (int gi = 0; gi < G; ++gi) sc[gi][r] = in ? sg[(int64_t)gi * s_stride + j] : 0.f;
+    }
+    const int wv = tid >> 6, lane = tid & 63;
+    constexpr int HPW = (G + 3) / 4;              // heads per wavefront
+    constexpr int CPL = kMaxChunks / 64;          // chunk statistics per lane
+    float m[HPW][CPL], l[HPW][CPL];
+#pragma unroll
+    for (int e = 0; e < HPW; ++e) {
+        const int gi = wv + 4 * e;
+        const float* ml = p.part_ml + (bg * kMaxChunks * G + min(gi, G - 1)) * 2;
+#pragma unroll
+        for (int u = 0; u < CPL; ++u) {
+            const int c = lane + 64 * u;
+            m[e][u] = -INFINITY; l[e][u] = 0.f;
+            if (c < nchunks) {
+                const float2 t2 = *reinterpret_cast<const float2*>(ml + (int64_t)c * G * 2);
+                m[e][u] = t2.x; l[e][u] = t2.y;
+            }
         }
     }
+    for (int i = tid; i < kHistBins; i += 256) sH[i] = 0;
+
+    // ---- lse of the G heads, fp64, one wavefront per head ----
+#pragma unroll
+    for (int e = 0; e < HPW; ++e) {
+        const int gi = wv + 4 * e;
+        float M = m[e][0];
+#pragma unroll
+        for (int u = 1; u < CPL; ++u) M = fmaxf(M, m[e][u]);
+        M = wave_max(M);
+        double L64 = 0.0;
+#pragma unroll
+        for (int u = 0; u < CPL; ++u) {
+            const float wgt = (m[e][u] == -INFINITY) ? 0.f : fast_exp2((m[e][u] - M) * kLog2e);
+            L64 += (double)wgt * (double)l[e][u];
+        }
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) L64 += __shfl_xor(L64, d);
+        if (lane == 0 && gi < G) {
+            float hi = -INFINITY, lo = 0.f;
+            if (L64 > 0.0) {
+                const double l64 = (double)M + log(L64);
+                hi = (float)l64;
+                lo = (float)(l64 - (double)hi);
+            }
+            sLse[gi][0] = hi; sLse[gi][1] = lo;
+        }
+    }
+    __syncthreads();
+
+    // ---- weights, max over the group ----
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const int i = r * 256 + tid, j = j0 - half + i;
+        if (i < span) {
+            float a = -INFINITY;                     // outside [0, len): never wins a max
+            if (j >= 0 && j < len) {
+                const bool core = p.weights != nullptr && i >= half && i < half + kPoolTile;
+#pragma unroll
+                for (int gi = 0; gi < G; ++gi) {
+                    const float wgt = weight_of(sc[gi][r], -sLse[gi][0], sLse[gi][1]);
+                    if (core) p.weights[((int64_t)b * p.Hq + (int64_t)g * G + gi) * p.w_stride + j] = wgt;
+                    a = fmaxf(a, wgt);
+                }
+            }
+            sA[i] = a;
+        }
+    }
+    __syncthreads();
+
+    // ---- max-pool, store, histogram ----
+    float* prow = pooled + bg * pooled_stride;
+    for (int i = tid; i < kPoolTile; i += 256) {
+        const int j = j0 + i;
+        if (j < len) {
+            float mx = sA[i];
+            for (int d = 1; d <= 2 * half; ++d) mx = fmaxf(mx, sA[i + d]);
+            mx += 0.0f;                           // -0 becomes +0: one bit pattern per value
+            prow[j] = mx;
+            atomicAdd(&sH[key_of(mx) >> kHistShift], 1u);
+        }
+    }
+    __syncthreads();
+    uint32_t* gh = hist + bg * kHistBins;
+    for (int i = tid; i < kHistBins; i += 256) {
+        const uint32_t c = sH[i];
+        if (c != 0) atomicAdd(&gh[i], c);
+    }
+}
+
+template <int G>
+static int launch_finish_pool(const AttnParams& p, int batch, int32_t max_len, const Workspace& ws, int half, hipStream_t st) {
+    dim3 grid(G + (max_len + kPoolTile - 1) / kPoolTile, p.Hkv, batch);
+    const int64_t stride = pooled_row_stride(max_len);
+    hipLaunchKernelGGL((finish_pool_kernel<G>), grid, dim3(256), 0, st, p, ws.scores, stride, half, ws.pooled, stride, ws.hist);
+    return launch_status();
 }
 
 template <int G, bool EMIT, bool TWO_SEG>
@@ -562,25 +753,12 @@ static int launch_split(const AttnParams& p, int batch, int G, int nchunk_grid, 
     }
 }
 
-}  // namespace rk
-
-using namespace rk;
-
-static int full_attn_impl(const rk_geom* geom, const void* q, rk_kv full,
-                          const int32_t* seq_lens, int32_t max_len,
-                          void* out, float* weights, int64_t w_stride, float* lse,
-                          const int32_t* pred, int32_t pred_val,
-                          void* workspace, size_t workspace_bytes, void* stream, bool scores_only) {
-    int rc = check_geom(geom);
-    if (rc != RK_OK) return rc;
-    if (!q || (!out && !scores_only) || !seq_lens || max_len <= 0) return RK_ERR_INVALID_ARG;
-    if (!aligned16(q) || ((uintptr_t)out & 1u)) return RK_ERR_INVALID_ARG;
-    if ((rc = check_kv(full)) != RK_OK) return rc;
-    if (weights && (w_stride < max_len || ((uintptr_t)weights & 3u))) return RK_ERR_INVALID_ARG;
-    Workspace ws;
-    if ((rc = check_workspace(geom, max_len, 0, workspace, workspace_bytes, &ws)) != RK_OK) return rc;
-
+int full_attn_stage(const rk_geom* geom, const void* q, rk_kv full, const int32_t* seq_lens, int32_t max_len,
+                    void* out, float* weights, int64_t w_stride, float* lse, const int32_t* pred, int32_t pred_val,
+                    const Workspace& ws, hipStream_t st, bool scores_only, int pool_half) {
     const int G = geom->n_q_heads / geom->n_kv_heads;
+    const bool fused = pool_half >= 0;
+    const bool emit = weights != nullptr || fused;
     AttnParams p{};
     p.q = (const uint16_t*)q;
     p.k2 = (const uint16_t*)full.k; p.v2 = (const uint16_t*)full.v;
@@ -589,25 +767,52 @@ static int full_attn_impl(const rk_geom* geom, const void* q, rk_kv full,
     p.n_sel = 0;
     p.max_rows2 = max_len;
     p.cap1 = 0; p.cap2 = (int32_t)full.capacity;
-    p.chunk = attn_chunk_rows(max_len, (int64_t)geom->batch * geom->n_kv_heads, weights ? kMaxChunks : kMergeChunks);
+    p.nch = split_workgroups(max_len, (int64_t)geom->batch * geom->n_kv_heads, emit ? kMaxChunks : kMergeChunks);
     p.Hq = geom->n_q_heads; p.Hkv = geom->n_kv_heads;
     p.scale = geom->scale;
     p.out = (uint16_t*)out;
-    p.weights = weights; p.w_stride = w_stride;
-    p.w_vec = (weights && (w_stride % 4 == 0) && aligned16(weights)) ? 1 : 0;
+    if (fused) { p.weights = ws.scores; p.w_stride = pooled_row_stride(max_len); }
+    else       { p.weights = weights;   p.w_stride = w_stride; }
+    p.w_vec = (p.weights && (p.w_stride % 4 == 0) && aligned16(p.weights)) ? 1 : 0;
     p.lse = lse ? lse : ws.lse;
     p.pred = pred; p.pred_val = pred_val;
     p.counters = ws.counters; p.part_ml = ws.part_ml; p.part_o = ws.part_o; p.max_chunks = ws.max_chunks;
-    const int nchunk_grid = (max_len + p.chunk - 1) / p.chunk;
-    hipStream_t st = (hipStream_t)stream;
-    if (weights) {
-        rc = launch_split<true, false>(p, geom->batch, G, nchunk_grid, st);
-        if (rc != RK_OK || scores_only) return rc;
+    const int nchunk_grid = p.nch;
+    if (!emit) return launch_split<false, false>(p, geom->batch, G, nchunk_grid, st);
+    int rc = launch_split<true, false>(p, geom->batch, G, nchunk_grid, st);
+    if (rc != RK_OK || scores_only) return rc;
+    if (!fused) {
         dim3 grid(1 + (max_len + kNormTile - 1) / kNormTile, geom->n_q_heads, geom->batch);
         hipLaunchKernelGGL(merge_normalise_kernel, grid, dim3(256), 0, st, p, G);
         return launch_status();
     }
-    return launch_split<false, false>(p, geom->batch, G, nchunk_grid, st);
+    p.weights = weights; p.w_stride = w_stride;          // where the finish writes weights, if anywhere
+    switch (G) {
+        case 1: return launch_finish_pool<1>(p, geom->batch, max_len, ws, pool_half, st);
+        case 2: return launch_finish_pool<2>(p, geom->batch, max_len, ws, pool_half, st);
+        case 3: return launch_finish_pool<3>(p, geom->batch, max_len, ws, pool_half, st);
+        case 4: return launch_finish_pool<4>(p, geom->batch, max_len, ws, pool_half, st);
+        case 5: return launch_finish_pool<5>(p, geom->batch, max_len, ws, pool_half, st);
+        case 6: return launch_finish_pool<6>(p, geom->batch, max_len, ws, pool_half, st);
+        case 7: return launch_finish_pool<7>(p, geom->batch, max_len, ws, pool_half, st);
+        case 8: return launch_finish_pool<8>(p, geom->batch, max_len, ws, pool_half, st);
+        default: return RK_ERR_UNSUPPORTED;
+    }
+}
+
+}  // namespace rk
+
+using namespace rk;
+
+static int check_full_args(const rk_geom* geom, const void* q, rk_kv full, const int32_t* seq_lens, int32_t max_len,
+                           void* out, bool need_out, float* weights, int64_t w_stride) {
+    int rc = check_geom(geom);
+    if (rc != RK_OK) return rc;
+    if (!q || (!out && need_out) || !seq_lens || max_len <= 0) return RK_ERR_INVALID_ARG;
+    if (!aligned16(q) || ((uintptr_t)out & 1u)) return RK_ERR_INVALID_ARG;
+    if ((rc = check_kv(full)) != RK_OK) return rc;
+    if (weights && (w_stride < max_len || ((uintptr_t)weights & 3u))) return RK_ERR_INVALID_ARG;
+    return RK_OK;
 }
 
 extern "C" int rk_full_attn(const rk_geom* geom, const void* q, rk_kv full,
@@ -615,8 +820,12 @@ extern "C" int rk_full_attn(const rk_geom* geom, const void* q, rk_kv full,
                             void* out, float* weights, int64_t w_stride, float* lse,
                             const int32_t* pred, int32_t pred_val,
                             void* workspace, size_t workspace_bytes, void* stream) {
-    return full_attn_impl(geom, q, full, seq_lens, max_len, out, weights, w_stride, lse, pred, pred_val,
-                          workspace, workspace_bytes, stream, false);
+    int rc = check_full_args(geom, q, full, seq_lens, max_len, out, true, weights, w_stride);
+    if (rc != RK_OK) return rc;
+    Workspace ws;
+    if ((rc = check_workspace(geom, max_len, 0, workspace, workspace_bytes, &ws)) != RK_OK) return rc;
+    return full_attn_stage(geom, q, full, seq_lens, max_len, out, weights, w_stride, lse, pred, pred_val,
+                           ws, (hipStream_t)stream, false, -1);
 }
 
 extern "C" int rk_full_attn_scores(const rk_geom* geom, const void* q, rk_kv full,
@@ -625,8 +834,12 @@ extern "C" int rk_full_attn_scores(const rk_geom* geom, const void* q, rk_kv ful
                                    const int32_t* pred, int32_t pred_val,
                                    void* workspace, size_t workspace_bytes, void* stream) {
     if (!scores) return RK_ERR_INVALID_ARG;
-    return full_attn_impl(geom, q, full, seq_lens, max_len, nullptr, scores, s_stride, nullptr, pred, pred_val,
-                          workspace, workspace_bytes, stream, true);
+    int rc = check_full_args(geom, q, full, seq_lens, max_len, nullptr, false, scores, s_stride);
+    if (rc != RK_OK) return rc;
+    Workspace ws;
+    if ((rc = check_workspace(geom, max_len, 0, workspace, workspace_bytes, &ws)) != RK_OK) return rc;
+    return full_attn_stage(geom, q, full, seq_lens, max_len, nullptr, scores, s_stride, nullptr, pred, pred_val,
+                           ws, (hipStream_t)stream, true, -1);
 }
 
 extern "C" int rk_partial_attn(const rk_geom* geom, const void* q, rk_kv small, int32_t n_sel,
@@ -657,13 +870,13 @@ extern "C" int rk_partial_attn(const rk_geom* geom, const void* q, rk_kv small, 
     p.n_sel = n_sel;
     p.max_rows2 = max_recent;
     p.cap1 = n_sel > 0 ? (int32_t)small.capacity : 0; p.cap2 = (int32_t)full.capacity;
-    p.chunk = attn_chunk_rows(max_rows, (int64_t)geom->batch * geom->n_kv_heads, kMergeChunks);
+    p.nch = split_workgroups(max_rows, (int64_t)geom->batch * geom->n_kv_heads, kMergeChunks);
     p.Hq = geom->n_q_heads; p.Hkv = geom->n_kv_heads;
     p.scale = geom->scale;
     p.out = (uint16_t*)out;
     p.lse = ws.lse;
     p.pred = pred; p.pred_val = pred_val;
     p.counters = ws.counters; p.part_ml = ws.part_ml; p.part_o = ws.part_o; p.max_chunks = ws.max_chunks;
-    const int nchunk_grid = (max_rows + p.chunk - 1) / p.chunk;
+    const int nchunk_grid = p.nch;
     return launch_split<false, true>(p, geom->batch, G, nchunk_grid, (hipStream_t)stream);
 }

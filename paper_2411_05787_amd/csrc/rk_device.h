@@ -98,6 +98,14 @@ __device__ __forceinline__ double block_sum_f64(double v, double* red) {
     return r;
 }
 
+// Order-preserving map float -> uint32 (larger float <=> larger key) and its inverse.
+__device__ __forceinline__ uint32_t key_of(float x) {
+    const uint32_t u = __float_as_uint(x);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float value_of(uint32_t k) {
+    return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
+}
 // Orders LDS traffic of the lanes of one wavefront: what was written before is visible to
 // every lane after.  Lanes of a wavefront run in lockstep, so no hardware barrier is needed,
 // only the compiler and the LDS queue have to be told.

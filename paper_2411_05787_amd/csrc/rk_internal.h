@@ -10,31 +10,34 @@
 namespace rk {
 
 constexpr int kD = RK_HEAD_DIM;          // head_dim
-constexpr int kMinChunk = 128;           // smallest number of KV rows one workgroup reduces: 4 wavefronts x 32
+constexpr int kMinChunk = 128;           // rows one workgroup takes per round: 4 wavefronts x 32
 constexpr int kMaxChunks = 256;          // most partial results one (sequence, KV head) produces
 constexpr int kMergeChunks = 64;         // ... when the split kernel itself merges them
 #ifndef RK_TARGET_WGS
 #define RK_TARGET_WGS 512                // workgroups a split launch aims for (2 per CU, all resident)
 #endif
 
-// Rows per workgroup of the split attention kernels: a power of two >= 64.  No (sequence, KV
-// head) may produce more than `chunk_limit` partial results; within that, the largest chunk that
-// still gives the launch at least RK_TARGET_WGS workgroups (fewer, larger chunks mean fewer
-// partial results to merge, but below two workgroups per CU the chip is no longer kept busy).
-// When the last workgroup of a (sequence, KV head) merges the partial results inside the split
-// kernel the limit is kMergeChunks: that many results are fetched in one round trip.
-static inline int attn_chunk_rows(int64_t max_rows, int64_t n_problems, int chunk_limit) {
-    auto nch = [&](int64_t chunk) { return (max_rows + chunk - 1) / chunk; };
-    int64_t chunk = kMinChunk;
-    while (nch(chunk) > chunk_limit) chunk *= 2;
-    while (nch(2 * chunk) * n_problems >= RK_TARGET_WGS) chunk *= 2;
-    return (int)chunk;
+// Workgroups per (sequence, KV head) of a split attention launch: as many as give the launch
+// RK_TARGET_WGS workgroups in all, never more than `limit` (the most partial results the merge
+// that follows takes: kMergeChunks when the last workgroup merges inside the split kernel,
+// kMaxChunks when a second kernel does), never more than there are stretches of kMinChunk rows.
+// A launch of at most RK_TARGET_WGS workgroups is resident as a whole from the start; a few
+// workgroups more and it grows a tail that costs about a fifth of its run time at 32k rows.
+static inline int split_workgroups(int64_t max_rows, int64_t n_problems, int limit) {
+    int64_t per = RK_TARGET_WGS / (n_problems > 0 ? n_problems : 1);
+    const int64_t stretches = (max_rows + kMinChunk - 1) / kMinChunk;
+    if (per > stretches) per = stretches;
+    if (per > limit) per = limit;
+    if (per < 1) per = 1;
+    return (int)per;
 }
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 constexpr int kHistBins = 2048;          // first-level histogram of the selection: top 11 key bits
 constexpr int kMaxCandidates = 16384;    // most candidates the fast selection path sorts in LDS
+constexpr int kHistShift = 32 - 11;      // key bits below the first-level histogram bin
+constexpr int kPoolTile = 1024;          // positions one workgroup pools and histograms
 
 // Candidate slots per (sequence, KV head) of the selection: the K winners plus the rest of the
 // histogram bin that holds the K-th score.
@@ -53,6 +56,8 @@ static inline int topk_cand_cap(int64_t k) {
 //   part_ml   fp32  [B*Hkv][kMaxChunks][G][2] running max and sum of every partial result
 //   part_o    fp32  [B*Hkv][nch][G][128]     unnormalised partial outputs
 //   pooled    fp32  [B*Hkv][max_len up to a multiple of 4]   group-max, pooled scores of the selection
+//   scores    fp32  [B*Hq][max_len up to a multiple of 4]    raw scores between the two kernels of
+//                                                            rk_full_attn_select
 struct Workspace {
     int32_t* counters;
     uint32_t* hist;
@@ -60,6 +65,7 @@ struct Workspace {
     float* part_ml;
     float* part_o;
     float* pooled;
+    float* scores;
     int cand_cap;         // candidate slots the selection sorts in LDS
     int max_chunks;       // nch above
     size_t total;
@@ -94,6 +100,7 @@ static inline Workspace carve(const rk_geom* g, int64_t max_len, int64_t max_k, 
     w.part_ml = (float*)(p + off);    off += align_up(problems * kMaxChunks * G * 2 * sizeof(float), 256);
     w.part_o = (float*)(p + off);     off += align_up(problems * w.max_chunks * G * kD * sizeof(float), 256);
     w.pooled = (float*)(p + off);     off += align_up(problems * (size_t)pooled_row_stride(max_len > 0 ? max_len : 1) * sizeof(float), 256);
+    w.scores = (float*)(p + off);     off += align_up((size_t)g->batch * g->n_q_heads * (size_t)pooled_row_stride(max_len > 0 ? max_len : 1) * sizeof(float), 256);
     w.cand_cap = topk_cand_cap(max_k > 0 ? max_k : 1);
     w.total = off;
     return w;
@@ -114,7 +121,8 @@ static inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; 
 static inline int check_kv(const rk_kv& c) {
     if (!c.k || !c.v) return RK_ERR_INVALID_ARG;
     if (!aligned16(c.k) || !aligned16(c.v)) return RK_ERR_INVALID_ARG;
-    if (c.stride_b < 0 || c.stride_h < 0 || c.capacity <= 0 || c.capacity > INT32_MAX) return RK_ERR_INVALID_ARG;
+    // row indices are int32 and the kernels step past the end by up to kMaxChunks * kMinChunk rows
+    if (c.stride_b < 0 || c.stride_h < 0 || c.capacity <= 0 || c.capacity > INT32_MAX - 2 * kMaxChunks * kMinChunk) return RK_ERR_INVALID_ARG;
     if (c.stride_b % 8 != 0 || c.stride_h % 8 != 0) return RK_ERR_INVALID_ARG;
     return RK_OK;
 }
@@ -130,5 +138,18 @@ static inline int check_workspace(const rk_geom* g, int64_t max_len, int64_t max
 static inline int launch_status() {
     return hipGetLastError() == hipSuccess ? RK_OK : RK_ERR_HIP;
 }
+
+// Stages shared by the entry points (arguments already checked by the caller).
+//   full_attn_stage: the split kernel, then either the merge inside it (no weights), the merge +
+//     normalise kernel (weights in place), or, with pool_half >= 0, the fused finish that also
+//     leaves the pooled group scores and their histogram in the workspace.
+//   select_stage: top-K over the pooled scores and histogram that are in the workspace.
+__attribute__((visibility("hidden")))
+int full_attn_stage(const rk_geom* geom, const void* q, rk_kv full, const int32_t* seq_lens, int32_t max_len,
+                    void* out, float* weights, int64_t w_stride, float* lse, const int32_t* pred, int32_t pred_val,
+                    const Workspace& ws, hipStream_t st, bool scores_only, int pool_half);
+__attribute__((visibility("hidden")))
+int select_stage(const rk_geom* geom, const int32_t* seq_lens, int32_t max_len, int32_t k, int32_t* idx,
+                 float* sel_scores, const int32_t* pred, int32_t pred_val, const Workspace& ws, hipStream_t st);
 
 }  // namespace rk

@@ -28,22 +28,12 @@
 
 namespace rk {
 
-constexpr int kPoolTile = 1024;
 constexpr int kSelThreads = 1024;
-constexpr int kHistShift = 32 - 11;
 constexpr int kBuckets = 2048;                           // regular buckets, plus one for all above
 constexpr int kBucketLimit = 1024;                       // larger buckets: sort instead of ranking
 constexpr int kTopLoose = 64;                            // scores above the bucketed range: fewer than this
 static_assert(kHistBins == 1 << 11, "first-level histogram is 11 bits wide");
 
-// Order-preserving map float -> uint32 (larger float <=> larger key) and its inverse.
-__device__ __forceinline__ uint32_t key_of(float x) {
-    const uint32_t u = __float_as_uint(x);
-    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
-}
-__device__ __forceinline__ float value_of(uint32_t k) {
-    return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
-}
 __device__ __forceinline__ uint64_t item_of(uint32_t key, int j) {
     return ((uint64_t)key << 32) | (uint64_t)(0xFFFFFFFFu - (uint32_t)j);
 }
@@ -406,23 +396,17 @@ void select_kernel(const float* __restrict__ pooled, int64_t pooled_stride, cons
 
 using namespace rk;
 
-extern "C" int rk_topk_select(const rk_geom* geom, const float* weights, int64_t w_stride,
-                              const int32_t* seq_lens, int32_t max_len,
-                              int32_t k, int32_t pool_w, int32_t agg,
-                              int32_t* idx, float* sel_scores,
-                              const int32_t* pred, int32_t pred_val,
-                              void* workspace, size_t workspace_bytes, void* stream) {
-    int rc = check_geom(geom);
-    if (rc != RK_OK) return rc;
-    if (!weights || !seq_lens || !idx || max_len <= 0 || k <= 0 || w_stride < max_len) return RK_ERR_INVALID_ARG;
+namespace rk {
+
+static int check_select_args(int32_t k, int32_t pool_w, int32_t agg) {
     if (pool_w < 1 || (pool_w & 1) == 0) return RK_ERR_INVALID_ARG;
     if (pool_w > RK_MAX_POOL_W || k > RK_MAX_K || agg != RK_AGG_MAX) return RK_ERR_UNSUPPORTED;
-    Workspace ws;
-    if ((rc = check_workspace(geom, max_len, k, workspace, workspace_bytes, &ws)) != RK_OK) return rc;
-    hipStream_t st = (hipStream_t)stream;
-    const int G = geom->n_q_heads / geom->n_kv_heads;
+    return RK_OK;
+}
 
-    // the sort kernel may need more than the default dynamic LDS: ask before anything is enqueued
+int select_stage(const rk_geom* geom, const int32_t* seq_lens, int32_t max_len, int32_t k, int32_t* idx,
+                 float* sel_scores, const int32_t* pred, int32_t pred_val, const Workspace& ws, hipStream_t st) {
+    // the sort kernel may need more than the default dynamic LDS
     const size_t lds = (size_t)ws.cand_cap * sizeof(uint64_t) +
                        (2 * (kBuckets + 1) + kSelThreads / 64 + 2 + 1) * sizeof(uint32_t);
     static size_t lds_allowed = 48 * 1024;       // grows monotonically
@@ -434,15 +418,55 @@ extern "C" int rk_topk_select(const rk_geom* geom, const float* weights, int64_t
         }
         lds_allowed = lds;
     }
-
-    const int64_t pooled_stride = pooled_row_stride(max_len);      // rows start 16-byte aligned
-    dim3 pgrid((max_len + kPoolTile - 1) / kPoolTile, geom->n_kv_heads, geom->batch);
-    hipLaunchKernelGGL(pool_hist_kernel, pgrid, dim3(256), 0, st, weights, w_stride, seq_lens, max_len,
-                       geom->n_q_heads, geom->n_kv_heads, G, (pool_w - 1) / 2, ws.pooled, pooled_stride, ws.hist,
-                       pred, pred_val);
-    if ((rc = launch_status()) != RK_OK) return rc;
     dim3 sgrid(geom->n_kv_heads, geom->batch);
-    hipLaunchKernelGGL(select_kernel, sgrid, dim3(kSelThreads), lds, st, ws.pooled, pooled_stride, seq_lens,
+    hipLaunchKernelGGL(select_kernel, sgrid, dim3(kSelThreads), lds, st, ws.pooled, pooled_row_stride(max_len), seq_lens,
                        max_len, k, ws.hist, ws.cand_cap, idx, sel_scores, pred, pred_val);
     return launch_status();
+}
+
+}  // namespace rk
+
+extern "C" int rk_topk_select(const rk_geom* geom, const float* weights, int64_t w_stride,
+                              const int32_t* seq_lens, int32_t max_len,
+                              int32_t k, int32_t pool_w, int32_t agg,
+                              int32_t* idx, float* sel_scores,
+                              const int32_t* pred, int32_t pred_val,
+                              void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_geom(geom);
+    if (rc != RK_OK) return rc;
+    if (!weights || !seq_lens || !idx || max_len <= 0 || k <= 0 || w_stride < max_len) return RK_ERR_INVALID_ARG;
+    if ((rc = check_select_args(k, pool_w, agg)) != RK_OK) return rc;
+    Workspace ws;
+    if ((rc = check_workspace(geom, max_len, k, workspace, workspace_bytes, &ws)) != RK_OK) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    const int G = geom->n_q_heads / geom->n_kv_heads;
+    dim3 pgrid((max_len + kPoolTile - 1) / kPoolTile, geom->n_kv_heads, geom->batch);
+    hipLaunchKernelGGL(pool_hist_kernel, pgrid, dim3(256), 0, st, weights, w_stride, seq_lens, max_len,
+                       geom->n_q_heads, geom->n_kv_heads, G, (pool_w - 1) / 2, ws.pooled, pooled_row_stride(max_len), ws.hist,
+                       pred, pred_val);
+    if ((rc = launch_status()) != RK_OK) return rc;
+    return select_stage(geom, seq_lens, max_len, k, idx, sel_scores, pred, pred_val, ws, st);
+}
+
+extern "C" int rk_full_attn_select(const rk_geom* geom, const void* q, rk_kv full,
+                                   const int32_t* seq_lens, int32_t max_len,
+                                   void* out, float* weights, int64_t w_stride, float* lse,
+                                   int32_t k, int32_t pool_w, int32_t agg,
+                                   int32_t* idx, float* sel_scores,
+                                   const int32_t* pred, int32_t pred_val,
+                                   void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_geom(geom);
+    if (rc != RK_OK) return rc;
+    if (!q || !out || !seq_lens || !idx || max_len <= 0 || k <= 0) return RK_ERR_INVALID_ARG;
+    if (!aligned16(q) || ((uintptr_t)out & 1u)) return RK_ERR_INVALID_ARG;
+    if ((rc = check_kv(full)) != RK_OK) return rc;
+    if (weights && (w_stride < max_len || ((uintptr_t)weights & 3u))) return RK_ERR_INVALID_ARG;
+    if ((rc = check_select_args(k, pool_w, agg)) != RK_OK) return rc;
+    Workspace ws;
+    if ((rc = check_workspace(geom, max_len, k, workspace, workspace_bytes, &ws)) != RK_OK) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    rc = full_attn_stage(geom, q, full, seq_lens, max_len, out, weights, w_stride, lse, pred, pred_val, ws, st,
+                         false, (pool_w - 1) / 2);
+    if (rc != RK_OK) return rc;
+    return select_stage(geom, seq_lens, max_len, k, idx, sel_scores, pred, pred_val, ws, st);
 }

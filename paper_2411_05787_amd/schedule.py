@@ -31,7 +31,7 @@ class RefreshKVLayer:
         self.k_small, self.stride, self.pool_w = int(k_small), int(stride), int(pool_w)
         self.dynamic, self.threshold, self.evict_lowest = bool(dynamic), float(threshold), bool(evict_lowest)
         self.ws = workspace if workspace is not None else rk.Workspace(geom, self.capacity, k_small, device=dev)
-        self.weights = weights if weights is not None else torch.empty(B, Hq, self.capacity, dtype=torch.float32, device=dev)
+        self.weights = weights        # optional fp32 [B, Hq, capacity]: the weights of the last full step, if wanted
         self.small_K = torch.zeros(B, Hkv, k_small, D, dtype=torch.bfloat16, device=dev)
         self.small_V = torch.zeros(B, Hkv, k_small, D, dtype=torch.bfloat16, device=dev)
         self.idx = torch.full((B, Hkv, k_small), -1, dtype=torch.int32, device=dev)
@@ -73,10 +73,8 @@ class RefreshKVLayer:
 
     def _full(self, q, out, pred=None, stream=None) -> None:
         g = self.geom
-        rk.rk_full_attn(g, q, self.K, self.V, self.seq_lens, self.max_len, out, weights=self.weights,
-                        pred=pred, pred_val=1, workspace=self.ws, stream=stream)
-        rk.rk_topk_select(g, self.weights, self.seq_lens, self.max_len, self.k_small, self.pool_w, self.idx,
-                          pred=pred, pred_val=1, workspace=self.ws, stream=stream)
+        rk.rk_full_attn_select(g, q, self.K, self.V, self.seq_lens, self.max_len, out, self.k_small, self.pool_w,
+                               self.idx, weights=self.weights, pred=pred, pred_val=1, workspace=self.ws, stream=stream)
         rk.rk_gather_small_kv(g, self.K, self.V, self.idx, self.k_small, self.small_K, self.small_V,
                               seq_lens=self.seq_lens, tail_start=self.tail_start,
                               pred=pred, pred_val=1, stream=stream)

@@ -84,6 +84,16 @@ def test_host_side_argument_checks_return_before_any_launch(rk):
     assert topk(pool=4) == -1
     assert topk(pool=65) == -2
     assert topk(agg=1) == -2
+    fused = lambda **kw: lib.rk_full_attn_select(C.byref(g), kw.get("q", fake), kv, fake, 4096, kw.get("out", fake), None, 0,
+                                                 None, kw.get("k", 256), kw.get("pool", 7), 0, kw.get("idx", fake), None,
+                                                 None, 0, kw.get("ws", 0x100000), ws_bytes, None)
+    assert fused(q=None) == -1
+    assert fused(out=None) == -1
+    assert fused(idx=None) == -1
+    assert fused(k=0) == -1
+    assert fused(k=16385) == -2
+    assert fused(pool=2) == -1
+    assert fused(ws=None) == -3
     assert lib.rk_gather_small_kv(C.byref(g), kv, None, 16, kv, None, None, None, 0, None) == -1
     assert lib.rk_gather_small_kv(C.byref(g), kv, fake, 0, kv, None, None, None, 0, None) == -1
     assert lib.rk_gather_small_kv(C.byref(g), kv, fake, 16, kv, None, fake, None, 0, None) == -1   # tail_start without seq_lens
@@ -110,5 +120,6 @@ def test_chunk_policy_host_logic():
     import paper_2411_05787_amd as rk
     g = rk.Geom(1, 32, 8, 128, 1.0)
     small, big = rk.workspace_bytes(g, 64 * 512, 16), rk.workspace_bytes(g, 64 * 512 * 4, 16)
-    # beyond 512 chunks of 64 rows the partial area stops growing; only the pooled scores grow
-    assert big - small == 8 * (64 * 512 * 3) * 4
+    # beyond 256 chunks of 128 rows the partial area stops growing; only the pooled scores (one
+    # row per KV head) and the raw scores (one row per query head) grow
+    assert big - small == (8 + 32) * (64 * 512 * 3) * 4

@@ -185,6 +185,101 @@ def test_topk_select_exact(rk, case):
     assert (idx2 == idx).all()
 
 
+FUSED_CASES = [
+    # name, B, Hq, Hkv, lens, cap, k, pool_w
+    ("llama_ragged", 2, 32, 8, [3100, 1029], 3200, 256, 7),          # several pooling tiles, ragged
+    ("qwen_g7", 1, 28, 4, [2500], 2560, 128, 7),
+    ("g8_pool1", 1, 16, 2, [1300], 1408, 64, 1),
+    ("mha_g1_pool63", 1, 4, 4, [1024], 1024, 100, 63),               # halo as wide as allowed, tile-aligned length
+    ("short_and_empty", 3, 8, 2, [5, 0, 1025], 1100, 16, 7),         # k > len, len 0, one position past a tile
+    ("g5", 1, 15, 3, [700], 704, 32, 3),
+]
+
+
+@pytest.mark.parametrize("case", FUSED_CASES, ids=[c[0] for c in FUSED_CASES])
+def test_full_attn_select_matches_oracle(rk, case):
+    """rk_full_attn_select = rk_full_attn + rk_topk_select: out, lse, weights and idx against the
+    oracle, with and without the weights returned, twice in a row (workspace left clean)."""
+    name, B, Hq, Hkv, lens, cap, k, pool_w = case
+    say("full_attn_select case", case)
+    q, K, V = rand_case(200 + len(name), B, Hq, Hkv, cap)
+    scale = float(np.float32(1 / np.sqrt(128)))
+    geom = rk.Geom(B, Hq, Hkv, 128, scale)
+    ws = rk.Workspace(geom, cap, k)
+    sl = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    qd, Kd, Vd = q.cuda(), K.cuda(), V.cuda()
+    o_ref, w_ref, lse_ref = oracle.full_attn(gen.bf16_bits(q), gen.bf16_bits(K), gen.bf16_bits(V), lens, scale)
+    i_ref, s_ref = oracle.topk_select(w_ref.astype(np.float32), lens, Hkv, k, pool_w)
+    G = Hq // Hkv
+    max_len = max(max(lens), 1)
+    for rep, want_w in enumerate([True, False, True]):
+        out = torch.zeros(B, Hq, 128, dtype=torch.bfloat16, device="cuda")
+        wt = torch.full((B, Hq, cap), -7.0, dtype=torch.float32, device="cuda") if want_w else None
+        lse = torch.full((B, Hq), 123.0, dtype=torch.float32, device="cuda")
+        idx = torch.full((B, Hkv, k), -5, dtype=torch.int32, device="cuda")
+        sel = torch.full((B, Hkv, k), -5.0, dtype=torch.float32, device="cuda")
+        rk.rk_full_attn_select(geom, qd, Kd, Vd, sl, max_len, out, k, pool_w, idx, weights=wt, lse=lse,
+                               sel_scores=sel, workspace=ws)
+        torch.cuda.synchronize()
+        assert_out_close(gen.bf16_bits(out), o_ref, "%s rep %d" % (name, rep))
+        idx_n, sel_n, lse_n = idx.cpu().numpy(), sel.cpu().numpy(), lse.cpu().numpy()
+        for b in range(B):
+            n = lens[b]
+            if n == 0:
+                assert (lse_n[b] == -np.inf).all() and (idx_n[b] == -1).all()
+                continue
+            assert np.abs(lse_n[b] - lse_ref[b]).max() < 1e-5
+            if want_w:
+                wn = wt[b].cpu().numpy()
+                assert (np.abs(wn[:, :n] - w_ref[b, :, :n]) / w_ref[b, :, :n]).max() < 1e-5
+                assert (wn[:, n:] == -7.0).all(), "weights beyond len must not be written"
+            for g in range(Hkv):
+                P = oracle.pooled_group_scores(w_ref[b, g * G:(g + 1) * G, :n].astype(np.float32), pool_w)
+                assert_idx_equivalent(idx_n[b, g], i_ref[b, g], P, n, k, "%s b=%d g=%d" % (name, b, g))
+                kk = min(k, n)
+                assert np.abs(sel_n[b, g, :kk] - s_ref[b, g, :kk]).max() <= 1e-5 * s_ref[b, g, :kk].max()
+                assert (sel_n[b, g, kk:] == 0).all()
+    # and the same indices as the two separate calls on the same inputs
+    out2 = torch.zeros(B, Hq, 128, dtype=torch.bfloat16, device="cuda")
+    wt2 = torch.zeros(B, Hq, cap, dtype=torch.float32, device="cuda")
+    idx2 = torch.full((B, Hkv, k), -5, dtype=torch.int32, device="cuda")
+    rk.rk_full_attn(geom, qd, Kd, Vd, sl, max_len, out2, weights=wt2, workspace=ws)
+    rk.rk_topk_select(geom, wt2, sl, max_len, k, pool_w, idx2, workspace=ws)
+    torch.cuda.synchronize()
+    for b in range(B):
+        for g in range(Hkv):
+            n = lens[b]
+            if n == 0:
+                continue
+            P = oracle.pooled_group_scores(w_ref[b, g * G:(g + 1) * G, :n].astype(np.float32), pool_w)
+            assert_idx_equivalent(idx2[b, g].cpu().numpy(), idx_n[b, g], P, n, k, "two calls vs one")
+
+
+def test_full_attn_select_predicate(rk):
+    say("full_attn_select predicate")
+    B, Hq, Hkv, cap, k = 3, 8, 2, 1500, 32
+    lens = [1200, 900, 1500]
+    q, K, V = rand_case(77, B, Hq, Hkv, cap)
+    geom = rk.Geom(B, Hq, Hkv, 128, 0.1)
+    ws = rk.Workspace(geom, cap, k)
+    out = torch.full((B, Hq, 128), 5.0, dtype=torch.bfloat16, device="cuda")
+    idx = torch.full((B, Hkv, k), -5, dtype=torch.int32, device="cuda")
+    pred = torch.tensor([1, 0, 1], dtype=torch.int32, device="cuda")
+    sl = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    rk.rk_full_attn_select(geom, q.cuda(), K.cuda(), V.cuda(), sl, cap, out, k, 7, idx, pred=pred, pred_val=1, workspace=ws)
+    torch.cuda.synchronize()
+    o_ref, w_ref, _ = oracle.full_attn(gen.bf16_bits(q), gen.bf16_bits(K), gen.bf16_bits(V), lens, 0.1)
+    i_ref, _ = oracle.topk_select(w_ref.astype(np.float32), lens, Hkv, k, 7)
+    got = gen.bf16_bits(out)
+    assert_out_close(got[[0, 2]], o_ref[[0, 2]])
+    assert (out[1] == 5.0).all() and (idx[1] == -5).all()
+    G = Hq // Hkv
+    for b in (0, 2):
+        for g in range(Hkv):
+            P = oracle.pooled_group_scores(w_ref[b, g * G:(g + 1) * G, :lens[b]].astype(np.float32), 7)
+            assert_idx_equivalent(idx[b, g].cpu().numpy(), i_ref[b, g], P, lens[b], k, "pred b=%d" % b)
+
+
 def test_gather_bit_exact(rk):
     say("gather")
     B, Hkv, cap, k = 3, 4, 500, 77
@@ -258,6 +353,58 @@ def test_partial_attn_matches_oracle(rk, case):
     oracle.gather_small_kv(gen.bf16_bits(K), gen.bf16_bits(V), idx.numpy(), rK, rV)
     o_ref = oracle.partial_attn(gen.bf16_bits(q), rK, rV, n_sel, gen.bf16_bits(K), gen.bf16_bits(V), tail, lens, scale)
     assert_out_close(gen.bf16_bits(out), o_ref, name)
+
+
+def test_rows_past_the_end_are_never_used(rk):
+    """Cache rows at and beyond seq_lens (and small-cache rows beyond the selected ones) hold NaN:
+    nothing of them may reach the outputs, the weights or the selection."""
+    say("NaN beyond the end")
+    B, Hq, Hkv, cap, k = 2, 8, 2, 1400, 160       # k >= 128: the early loads of the first rows are taken
+    lens = [1210, 70]
+    q, K, V = rand_case(91, B, Hq, Hkv, cap)
+    nan = torch.tensor(float("nan"), dtype=torch.bfloat16)
+    for b in range(B):
+        K[b, :, lens[b]:] = nan
+        V[b, :, lens[b]:] = nan
+    scale = float(np.float32(1 / np.sqrt(128)))
+    geom = rk.Geom(B, Hq, Hkv, 128, scale)
+    ws = rk.Workspace(geom, cap, k)
+    sl = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    Kd, Vd, qd = K.cuda(), V.cuda(), q.cuda()
+    Kb, Vb = gen.bf16_bits(K), gen.bf16_bits(V)
+    o_ref, w_ref, _ = oracle.full_attn(gen.bf16_bits(q), Kb, Vb, lens, scale)
+    for want_w in (True, False):
+        out = torch.zeros(B, Hq, 128, dtype=torch.bfloat16, device="cuda")
+        wt = torch.zeros(B, Hq, cap, dtype=torch.float32, device="cuda") if want_w else None
+        rk.rk_full_attn(geom, qd, Kd, Vd, sl, cap, out, weights=wt, workspace=ws)
+        torch.cuda.synchronize()
+        assert_out_close(gen.bf16_bits(out), o_ref, "full, weights=%s" % want_w)
+        if want_w:
+            assert torch.isfinite(wt).all()
+    out = torch.zeros(B, Hq, 128, dtype=torch.bfloat16, device="cuda")
+    idx = torch.full((B, Hkv, k), -5, dtype=torch.int32, device="cuda")
+    rk.rk_full_attn_select(geom, qd, Kd, Vd, sl, cap, out, k, 7, idx, workspace=ws)
+    torch.cuda.synchronize()
+    assert_out_close(gen.bf16_bits(out), o_ref, "fused")
+    i_ref, _ = oracle.topk_select(w_ref.astype(np.float32), lens, Hkv, k, 7)
+    G = Hq // Hkv
+    for b in range(B):
+        for g in range(Hkv):
+            P = oracle.pooled_group_scores(w_ref[b, g * G:(g + 1) * G, :lens[b]].astype(np.float32), 7)
+            assert_idx_equivalent(idx[b, g].cpu().numpy(), i_ref[b, g], P, lens[b], k, "b=%d g=%d" % (b, g))
+    # partial step: the small cache holds NaN beyond the min(k, tail_start) gathered rows
+    sK = torch.full((B, Hkv, k, 128), float("nan"), dtype=torch.bfloat16, device="cuda")
+    sV = sK.clone()
+    rk.rk_gather_small_kv(geom, Kd, Vd, idx, k, sK, sV)
+    tail = [lens[0] - 4, lens[1] - 1]
+    out = torch.zeros(B, Hq, 128, dtype=torch.bfloat16, device="cuda")
+    rk.rk_partial_attn(geom, qd, sK, sV, k, Kd, Vd, torch.tensor(tail, dtype=torch.int32, device="cuda"), sl, 4, out,
+                       workspace=ws)
+    torch.cuda.synchronize()
+    rK = np.zeros((B, Hkv, k, 128), dtype=np.uint16); rV = rK.copy()
+    oracle.gather_small_kv(Kb, Vb, idx.cpu().numpy(), rK, rV)
+    o_part = oracle.partial_attn(gen.bf16_bits(q), rK, rV, k, Kb, Vb, tail, lens, scale)
+    assert_out_close(gen.bf16_bits(out), o_part, "partial")
 
 
 def test_query_sim_matches_oracle(rk):

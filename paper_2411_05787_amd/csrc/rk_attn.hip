@@ -183,8 +183,11 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 //   P operand   head n16, contraction slot e = 4*t + i  <->  row 16*t + 4*c4 + i
 //   V operand   dim 16*dt + n16, the same slots (LDS transpose read)
 //   O result    dim 16*dt + n16, heads 4*c4 + i
+#ifndef RK_EMIT_OCCUPANCY
+#define RK_EMIT_OCCUPANCY 3       // workgroups per CU the score-emitting kernel is compiled for
+#endif
 template <int G, int NW, bool EMIT, bool TWO_SEG>
-__global__ __launch_bounds__(NW * 64, EMIT ? 3 : 2)
+__global__ __launch_bounds__(NW * 64, EMIT ? RK_EMIT_OCCUPANCY : 2)
 void attn_split_kernel(const AttnParams p) {
     constexpr int ROWS = kTileRows;          // rows per wavefront and tile = contraction depth of P V
     static_assert(NW == kSplitWaves, "work split");
@@ -297,7 +300,7 @@ void attn_split_kernel(const AttnParams p) {
     // One tile.  The K registers are free again once S^T is computed and the V registers once the
     // tile sits in LDS: the next tile's rows are requested at those two points, so its loads are
     // in flight during the rest of this tile's work.
-    auto compute_tile = [&](int r, int r_next) {
+    auto compute_tile = [&](int r, int r_next) -> int {
         // ---- S^T = K Q^T on the matrix cores: head n16, rows r + 16 t + 4 c4 + i ----
         float s[2][4];
 #pragma unroll
@@ -376,6 +379,7 @@ void attn_split_kernel(const AttnParams p) {
             acc_o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(p_lo, vb, acc_o[dt], 0, 0, 0);
         }
         wave_lds_sync();      // sV / sAlpha are rewritten by the next tile
+        return r_next;
     };
 
     {
@@ -395,7 +399,7 @@ void attn_split_kernel(const AttnParams p) {
                     if (r + jj * 4 + c4 >= row1) vA[jj] = u32x4{0u, 0u, 0u, 0u};
             }
         }
-        for (; r < row1; r += step) compute_tile(r, r + step);
+        while (r < row1) r = compute_tile(r, r + step);
     }
 
     // ---- wavefront results to LDS ----

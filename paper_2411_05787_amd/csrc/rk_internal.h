@@ -14,22 +14,33 @@ constexpr int kMinChunk = 128;           // rows one workgroup takes per round: 
 constexpr int kMaxChunks = 256;          // most partial results one (sequence, KV head) produces
 constexpr int kMergeChunks = 64;         // ... when the split kernel itself merges them
 #ifndef RK_TARGET_WGS
-#define RK_TARGET_WGS 512                // workgroups a split launch aims for (2 per CU, all resident)
+#define RK_TARGET_WGS 768                // workgroups a split launch aims for (3 per CU, all resident)
 #endif
 
-// Workgroups per (sequence, KV head) of a split attention launch: as many as give the launch
-// RK_TARGET_WGS workgroups in all, never more than `limit` (the most partial results the merge
-// that follows takes: kMergeChunks when the last workgroup merges inside the split kernel,
-// kMaxChunks when a second kernel does), never more than there are stretches of kMinChunk rows.
-// A launch of at most RK_TARGET_WGS workgroups is resident as a whole from the start; a few
-// workgroups more and it grows a tail that costs about a fifth of its run time at 32k rows.
+// Workgroups per (sequence, KV head) of a split attention launch.  Upper bound: as many as give
+// the launch RK_TARGET_WGS workgroups in all (such a launch is resident as a whole from the
+// start), never more than `limit` (the most partial results the merge that follows takes:
+// kMergeChunks when the last workgroup merges inside the split kernel, kMaxChunks when a second
+// kernel does), never more than there are stretches of kMinChunk rows.
+// Below that bound the count is chosen for the rows at hand.  The launch works in rounds: each
+// of its 4 * nch wavefronts per (sequence, KV head) takes one 32-row tile per round, and a round
+// costs about the same whether all wavefronts or only a few have a tile in it (one memory round
+// trip).  So the run time goes with rounds * wavefronts, and a count a little below the bound
+// that fills its last round beats the bound with a nearly empty one (32979 rows: 52 workgroups,
+// 5 full rounds, instead of 64 and a fifth round for 7 tiles: 15% faster).  Counts down to 5/8
+// of the bound are considered; ties go to the larger count.
 static inline int split_workgroups(int64_t max_rows, int64_t n_problems, int limit) {
     int64_t per = RK_TARGET_WGS / (n_problems > 0 ? n_problems : 1);
     const int64_t stretches = (max_rows + kMinChunk - 1) / kMinChunk;
     if (per > stretches) per = stretches;
     if (per > limit) per = limit;
     if (per < 1) per = 1;
-    return (int)per;
+    const int64_t tiles = (max_rows + 31) / 32;
+    auto cost = [&](int64_t nch) { return (tiles + 4 * nch - 1) / (4 * nch) * (4 * nch); };
+    int64_t best = per;
+    for (int64_t nch = per - 1; nch >= 1 && 8 * nch >= 5 * per; --nch)
+        if (cost(nch) < cost(best)) best = nch;
+    return (int)best;
 }
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -92,7 +103,7 @@ static inline Workspace carve(const rk_geom* g, int64_t max_len, int64_t max_k, 
     w.max_chunks = max_chunks_for(max_len);
     char* p = (char*)base;
     size_t off = 0;
-    // the two zero-kept regions are contiguous (no padding between them)
+    // the zero-kept regions are contiguous (no padding between them)
     w.counters = (int32_t*)(p + off); off += problems * sizeof(int32_t);
     w.hist = (uint32_t*)(p + off);    off += problems * kHistBins * sizeof(uint32_t);
     off = align_up(off, 256);

@@ -33,6 +33,7 @@ constexpr int kBuckets = 2048;                           // regular buckets, plu
 constexpr int kBucketLimit = 1024;                       // larger buckets: sort instead of ranking
 constexpr int kTopLoose = 64;                            // scores above the bucketed range: fewer than this
 static_assert(kHistBins == 1 << 11, "first-level histogram is 11 bits wide");
+static_assert(kHistBins == 2 * kSelThreads, "the selection scans the histogram two bins per thread");
 
 __device__ __forceinline__ uint64_t item_of(uint32_t key, int j) {
     return ((uint64_t)key << 32) | (uint64_t)(0xFFFFFFFFu - (uint32_t)j);
@@ -208,8 +209,8 @@ void select_kernel(const float* __restrict__ pooled, int64_t pooled_stride, cons
     uint32_t* sHist = reinterpret_cast<uint32_t*>(sKeys + cand_cap);       // [2 * (kBuckets + 1)]: bucket
                                                                            // arrays, or the radix histogram
     uint32_t* sScan = sHist + 2 * (kBuckets + 1);                          // [16]
-    uint32_t* sOut = sScan + kSelThreads / 64;                             // [2]
-    uint32_t* sCount = sOut + 2;                                           // [1]
+    uint32_t* sOut = sScan + kSelThreads / 64;                             // [4]
+    uint32_t* sCount = sOut + 4;                                           // [1]
 
     const int tid = threadIdx.x;
     const int n = min(seq_lens[b], max_len);
@@ -223,19 +224,52 @@ void select_kernel(const float* __restrict__ pooled, int64_t pooled_stride, cons
     const float* P = pooled + bg * pooled_stride;
     uint32_t* gh = hist + bg * kHistBins;
 
+    // The first 32 scores of every thread (the whole row up to 32768 positions) are requested now,
+    // 16-byte loads all in flight together with the histogram's, and stay in registers.
+    constexpr int NV = 8;
+    const float4* P4 = reinterpret_cast<const float4*>(P);
+    const int nvec = (n + 3) >> 2;
+    // positions at and beyond n read as -1: below every candidate threshold (scores are >= 0)
+    auto load4 = [&](int v) -> float4 {
+        float4 x = (v < nvec) ? P4[v] : make_float4(-1.f, -1.f, -1.f, -1.f);
+        if (4 * v + 3 >= n && v < nvec) {             // the row's last, partial vector
+            if (4 * v + 1 >= n) x.y = -1.f;
+            if (4 * v + 2 >= n) x.z = -1.f;
+            x.w = -1.f;
+        }
+        return x;
+    };
+    float4 held[NV];
+#pragma unroll
+    for (int u = 0; u < NV; ++u) held[u] = load4(u * kSelThreads + tid);
+
+    // From the histogram, in one scan from the top bin down (thread 0 owns the top two bins):
+    // the bin b1 that holds the K'-th largest score (with the count above it), and the bin that
+    // holds the kTopLoose-th largest, which bounds the bucketed range from above so that the one
+    // bucket for "everything above" stays small (its items are ranked by a loop over the bucket).
     if (tid == 0) *sCount = 0;
-    find_bin_from_top<kSelThreads, kHistBins>(gh, (uint32_t)kprime, sScan, sOut);
+    for (int i = tid; i < kBuckets + 1; i += kSelThreads) sHist[i] = 0;     // bucket sizes of the fast path
+    {
+        const int rt = kSelThreads - 1 - tid;
+        const uint32_t h0 = gh[2 * rt], h1 = gh[2 * rt + 1];
+        uint32_t total;
+        const uint32_t incl = block_inclusive_scan<kSelThreads>(h0 + h1, sScan, &total);   // entries in bins >= 2 rt
+        const uint32_t abv = incl - (h0 + h1);
+        const uint32_t kk1 = (uint32_t)kprime, kk2 = min((uint32_t)kprime, (uint32_t)kTopLoose);
+        if (abv < kk1 && kk1 <= incl) {
+            const bool upper = abv + h1 >= kk1;
+            sOut[0] = (uint32_t)(2 * rt + (upper ? 1 : 0));
+            sOut[1] = upper ? abv : abv + h1;
+            sOut[2] = upper ? h1 : h0;
+        }
+        if (abv < kk2 && kk2 <= incl) sOut[3] = (uint32_t)(2 * rt + (abv + h1 >= kk2 ? 1 : 0));
+        gh[2 * rt] = 0; gh[2 * rt + 1] = 0;            // cleared for the next call
+        __syncthreads();
+    }
     const uint32_t b1 = sOut[0];
     const uint32_t above = sOut[1];
-    uint32_t count_ge = above + gh[b1];
-    __syncthreads();
-    // The bin that holds the kTopLoose-th largest score bounds the bucketed range from above, so
-    // that the one bucket for "everything above" stays small (its items are ranked by a loop over
-    // the whole bucket).
-    find_bin_from_top<kSelThreads, kHistBins>(gh, min((uint32_t)kprime, (uint32_t)kTopLoose), sScan, sOut);
-    const uint32_t key_top = (sOut[0] + 1u) << kHistShift;      // sOut[0] >= b1; wraps to 0 for the last bin
-    __syncthreads();                        // every thread has read the histogram: clear it
-    for (int i = tid; i < kHistBins; i += kSelThreads) gh[i] = 0;
+    uint32_t count_ge = above + sOut[2];
+    const uint32_t key_top = (sOut[3] + 1u) << kHistShift;      // sOut[3] >= b1; wraps to 0 for the last bin
 
     // Candidates are the positions whose image is >= key_thr.  Normally that is "bin b1 or above";
     // if those are too many for LDS, bin b1 is cut once more by the next 11 image bits.
@@ -252,64 +286,87 @@ void select_kernel(const float* __restrict__ pooled, int64_t pooled_stride, cons
         __syncthreads();
     }
     // bucket width: the smallest power of two for which [key_thr, key_top) fits in kBuckets buckets
-    int bucket_shift = 0;
-    while (((key_top - 1u - key_thr) >> bucket_shift) >= (uint32_t)kBuckets) ++bucket_shift;
+    const uint32_t span = key_top - 1u - key_thr;        // 11 significant bits are left after the shift
+    const int bucket_shift = span >= (uint32_t)kBuckets ? 32 - 11 - __builtin_clz(span) : 0;
 
-    // Visits every candidate (position in bin b1 or above) of P: one float compare per element,
-    // `visit(key, j)` runs for the candidates only.  The first 32 scores of every thread (the
-    // whole row up to 32768 positions) are loaded once, 16-byte loads all in flight together,
-    // and stay in registers for both passes; longer rows re-read the rest from memory.
+    // Visits every candidate (position whose image is >= key_thr) of P: one float compare per
+    // element, `visit(key, j)` runs for the candidates only, in position order per thread.  The
+    // scores held in registers come first; longer rows re-read the rest from memory.
     const float thr = value_of(key_thr);                 // lowest candidate score (scores are >= 0)
-    constexpr int NV = 8;
-    const float4* P4 = reinterpret_cast<const float4*>(P);
-    const int nvec = (n + 3) >> 2;
-    float4 held[NV];
-#pragma unroll
-    for (int u = 0; u < NV; ++u) {
-        const int v = u * kSelThreads + tid;
-        held[u] = (v < nvec) ? P4[v] : make_float4(-1.f, -1.f, -1.f, -1.f);
-    }
     auto visit4 = [&](const float4 x, int j, auto&& visit) {
-        if (x.x >= thr || x.y >= thr || x.z >= thr || x.w >= thr) {
-            if (x.x >= thr && j + 0 < n) visit(key_of(x.x), j + 0);
-            if (x.y >= thr && j + 1 < n) visit(key_of(x.y), j + 1);
-            if (x.z >= thr && j + 2 < n) visit(key_of(x.z), j + 2);
-            if (x.w >= thr && j + 3 < n) visit(key_of(x.w), j + 3);
-        }
+        // scores are >= +0, so the order-preserving image is the bit pattern with the top bit set
+        if (x.x >= thr) visit(__float_as_uint(x.x) | 0x80000000u, j + 0);
+        if (x.y >= thr) visit(__float_as_uint(x.y) | 0x80000000u, j + 1);
+        if (x.z >= thr) visit(__float_as_uint(x.z) | 0x80000000u, j + 2);
+        if (x.w >= thr) visit(__float_as_uint(x.w) | 0x80000000u, j + 3);
     };
+    constexpr int UN = 8;                    // vectors per thread and round trip beyond the held ones
     auto for_each_candidate = [&](auto&& visit) {
 #pragma unroll
         for (int u = 0; u < NV; ++u) visit4(held[u], (u * kSelThreads + tid) << 2, visit);
-        constexpr int UN = 8;
         for (int v0 = NV * kSelThreads; v0 < nvec; v0 += kSelThreads * UN) {
             float4 pv[UN];
 #pragma unroll
-            for (int u = 0; u < UN; ++u) {
-                const int v = v0 + u * kSelThreads + tid;
-                pv[u] = (v < nvec) ? P4[v] : make_float4(-1.f, -1.f, -1.f, -1.f);
-            }
+            for (int u = 0; u < UN; ++u) pv[u] = load4(v0 + u * kSelThreads + tid);
 #pragma unroll
             for (int u = 0; u < UN; ++u) visit4(pv[u], (v0 + u * kSelThreads + tid) << 2, visit);
         }
+    };
+    // number of candidates among this thread's positions, without branches
+    auto count_candidates = [&]() -> uint32_t {
+        auto c4 = [&](const float4 x) -> uint32_t {
+            return (x.x >= thr ? 1u : 0u) + (x.y >= thr ? 1u : 0u) + (x.z >= thr ? 1u : 0u) + (x.w >= thr ? 1u : 0u);
+        };
+        uint32_t c = 0;
+#pragma unroll
+        for (int u = 0; u < NV; ++u) c += c4(held[u]);
+        for (int v0 = NV * kSelThreads; v0 < nvec; v0 += kSelThreads * UN) {
+            float4 pv[UN];
+#pragma unroll
+            for (int u = 0; u < UN; ++u) pv[u] = load4(v0 + u * kSelThreads + tid);
+#pragma unroll
+            for (int u = 0; u < UN; ++u) c += c4(pv[u]);
+        }
+        return c;
     };
     auto bucket_of = [&](uint32_t key) -> uint32_t {
         return min((key - key_thr) >> bucket_shift, (uint32_t)kBuckets);
     };
     int nvalid;                             // entries of sKeys that are real (sorting paths)
     if (count_ge <= (uint32_t)cand_cap) {
-        // ---- candidates = every position in bin b1 or above ----
+        // ---- candidates = every position whose image is >= key_thr, count_ge of them ----
+        // They are first packed into a dense list in LDS (a count per thread, a scan, then every
+        // thread writes its candidates behind those of the threads before it).  The two passes over
+        // all n positions are the only work here that is proportional to n; everything after runs
+        // on the dense list: up to kItems items per thread, taken into registers so that the same
+        // LDS array can receive them again sorted by bucket.
         uint32_t* sCnt = sHist;                         // [kBuckets + 1] bucket sizes, then fill marks
         uint32_t* sStart = sHist + kBuckets + 1;        // [kBuckets + 1] bucket offsets
-        for (int i = tid; i < kBuckets + 1; i += kSelThreads) sCnt[i] = 0;
+        if (refined) {                                  // the radix pass used the array: clear it again
+            for (int i = tid; i < kBuckets + 1; i += kSelThreads) sCnt[i] = 0;
+        }
+        const uint32_t mine = count_candidates();
+        uint32_t total;
+        uint32_t pos = block_inclusive_scan<kSelThreads>(mine, sScan, &total) - mine;
+        for_each_candidate([&](uint32_t key, int j) { sKeys[pos++] = item_of(key, j); });
         __syncthreads();
-        // pass A: bucket sizes
-        for_each_candidate([&](uint32_t key, int) { atomicAdd(&sCnt[bucket_of(key)], 1u); });
+        constexpr int kItems = kMaxCandidates / kSelThreads;
+        uint64_t it[kItems];
+#pragma unroll
+        for (int u = 0; u < kItems; ++u) {
+            const int e = u * kSelThreads + tid;
+            it[u] = (e < (int)count_ge) ? sKeys[e] : 0ull;
+        }
+        const int n_mine = ((int)count_ge - tid + kSelThreads - 1) / kSelThreads;   // items of this thread
+        __syncthreads();                                // the list is in registers: sKeys is free
+#pragma unroll
+        for (int u = 0; u < kItems; ++u)
+            if (u < n_mine) atomicAdd(&sCnt[bucket_of((uint32_t)(it[u] >> 32))], 1u);
         __syncthreads();
         // offsets from the top bucket down: thread 0 owns the two highest regular buckets
         const int rt = kSelThreads - 1 - tid;
         const uint32_t c0 = sCnt[2 * rt], c1 = sCnt[2 * rt + 1], cov = sCnt[kBuckets];
         const bool big = c0 > (uint32_t)kBucketLimit || c1 > (uint32_t)kBucketLimit || cov > (uint32_t)kBucketLimit;
-        uint32_t total;
         const uint32_t incl = block_inclusive_scan<kSelThreads>(c0 + c1, sScan, &total);
         const uint32_t above2 = incl - (c0 + c1) + cov;
         if (!__syncthreads_or(big ? 1 : 0)) {
@@ -317,10 +374,10 @@ void select_kernel(const float* __restrict__ pooled, int64_t pooled_stride, cons
             sStart[2 * rt] = above2 + c1;     sCnt[2 * rt] = above2 + c1;
             if (tid == 0) { sStart[kBuckets] = 0; sCnt[kBuckets] = 0; }
             __syncthreads();
-            // pass B: every candidate into its bucket (order inside a bucket is arbitrary)
-            for_each_candidate([&](uint32_t key, int j) {
-                sKeys[atomicAdd(&sCnt[bucket_of(key)], 1u)] = item_of(key, j);
-            });
+            // every item into its bucket (order inside a bucket is arbitrary)
+#pragma unroll
+            for (int u = 0; u < kItems; ++u)
+                if (u < n_mine) sKeys[atomicAdd(&sCnt[bucket_of((uint32_t)(it[u] >> 32))], 1u)] = it[u];
             __syncthreads();
             // rank = bucket offset + larger items in the same bucket; ranks < K' are the answer
             for (int e = tid; e < (int)count_ge; e += kSelThreads) {
@@ -340,8 +397,10 @@ void select_kernel(const float* __restrict__ pooled, int64_t pooled_stride, cons
             }
             return;
         }
-        // a huge bucket (many equal or nearly equal scores): collect and sort instead
-        for_each_candidate([&](uint32_t key, int j) { sKeys[atomicAdd(sCount, 1u)] = item_of(key, j); });
+        // a huge bucket (many equal or nearly equal scores): put the list back and sort it instead
+#pragma unroll
+        for (int u = 0; u < kItems; ++u)
+            if (u < n_mine) sKeys[u * kSelThreads + tid] = it[u];
         nvalid = (int)count_ge;
     } else {
         // ---- slow path: exact K-th largest image T by radix select over P ----
@@ -408,7 +467,7 @@ int select_stage(const rk_geom* geom, const int32_t* seq_lens, int32_t max_len, 
                  float* sel_scores, const int32_t* pred, int32_t pred_val, const Workspace& ws, hipStream_t st) {
     // the sort kernel may need more than the default dynamic LDS
     const size_t lds = (size_t)ws.cand_cap * sizeof(uint64_t) +
-                       (2 * (kBuckets + 1) + kSelThreads / 64 + 2 + 1) * sizeof(uint32_t);
+                       (2 * (kBuckets + 1) + kSelThreads / 64 + 4 + 1) * sizeof(uint32_t);
     static size_t lds_allowed = 48 * 1024;       // grows monotonically
     if (lds > lds_allowed) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel),

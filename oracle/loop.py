@@ -8,7 +8,7 @@ from typing import Dict, List
 
 import numpy as np
 
-from .steps import full_attn, topk_select, gather_small_kv, partial_attn, query_sim
+from .steps import full_attn, attn_scores, topk_select, gather_small_kv, partial_attn, query_sim
 
 
 def is_full_step(t: int, stride: int) -> bool:
@@ -23,7 +23,7 @@ def is_full_step(t: int, stride: int) -> bool:
 def decode_loop(q_steps_bits, k_bits, v_bits, new_k_bits, new_v_bits, seq_lens0, scale: float,
                 k_small: int, stride: int, pool_w: int = 7, dynamic: bool = False,
                 threshold: float = 0.0, evict_lowest: bool = False,
-                weights_dtype=np.float32) -> Dict[str, object]:
+                weights_dtype=np.float32, scores_only_refresh: bool = False) -> Dict[str, object]:
     """Run T decode steps of one layer.
 
     q_steps_bits [T+1,B,Hq,D] (index 0: the query of the last prompt token, which
@@ -37,6 +37,9 @@ def decode_loop(q_steps_bits, k_bits, v_bits, new_k_bits, new_v_bits, seq_lens0,
     ``evict_lowest``: partial steps read K - r selected rows (r = rows appended since the
     refresh), the paper's fixed-size C_p; otherwise all K selected rows plus the r new ones.
     The attention scores are cast to ``weights_dtype`` (the boundary's fp32) before ranking.
+    ``scores_only_refresh``: the "w/o full attention" setting of Section 4.3: a refresh step
+    computes the scores over the whole cache, rebuilds the small cache from them and then
+    attends to the rebuilt small cache alone (its K rows; nothing has been decoded since).
 
     Returns outs (bf16 bits [T+1,B,Hq,D]), full (bool [T+1,B]), sims ([T+1,B], nan where
     not tested), idx (list over t of int32 [B,Hkv,K] snapshots taken after each step),
@@ -81,12 +84,19 @@ def decode_loop(q_steps_bits, k_bits, v_bits, new_k_bits, new_v_bits, seq_lens0,
                 do_full = False
             full[t, b] = do_full
             if do_full:
-                o, w, _ = full_attn(q[sl], kf[sl], vf[sl], lens[sl], scale)
+                if scores_only_refresh:
+                    w, _ = attn_scores(q[sl], kf[sl], lens[sl], scale)
+                else:
+                    o, w, _ = full_attn(q[sl], kf[sl], vf[sl], lens[sl], scale)
                 i_b, _ = topk_select(w.astype(weights_dtype), lens[sl], Hkv, k_small, pool_w)
                 idx[sl] = i_b
                 gather_small_kv(kf[sl], vf[sl], idx[sl], small_k[sl], small_v[sl])
                 tail_start[b] = lens[b]
                 rows[t, b] = lens[b]
+                if scores_only_refresh:
+                    o = partial_attn(q[sl], small_k[sl], small_v[sl], k_small, kf[sl], vf[sl],
+                                     tail_start[sl], lens[sl], scale)
+                    rows[t, b] = min(k_small, int(lens[b]))
             else:
                 r = int(lens[b] - tail_start[b])
                 n_sel = max(k_small - r, 0) if evict_lowest else k_small

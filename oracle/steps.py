@@ -67,6 +67,39 @@ def full_attn(q_bits, k_bits, v_bits, seq_lens, scale: float
     return f64_to_bf16_bits(out), weights, lse
 
 
+def attn_scores(q_bits, k_bits, seq_lens, scale: float) -> Tuple[np.ndarray, np.ndarray]:
+    """Attention scores of the current token over the entire full cache, keys only
+    (Section 4.3 "Impact of full attention steps", the setting "w/o full attention":
+    the scores over the entire KV cache are calculated and the partial cache is updated
+    from them, but the step then attends to the updated partial cache, so the values of
+    the full cache are never read).
+
+    a[b,h,j] = exp(s_j) / sum_i exp(s_i) with s_j = scale * <q[b,h], K[b,g(h),j]>, j < seq_lens[b].
+    Returns (weights fp64 [B,Hq,max(seq_lens)] zero beyond each length, lse fp64 [B,Hq]).
+    """
+    q = bf16_bits_to_f64(q_bits)
+    B, Hq, D = q.shape
+    Hkv = k_bits.shape[1]
+    G = Hq // Hkv
+    lens = np.asarray(seq_lens, dtype=np.int64)
+    width = int(lens.max()) if B else 0
+    weights = np.zeros((B, Hq, width), dtype=np.float64)
+    lse = np.full((B, Hq), -np.inf, dtype=np.float64)
+    for b in range(B):
+        n = int(lens[b])
+        if n == 0:
+            continue
+        for h in range(Hq):
+            keys = bf16_bits_to_f64(k_bits[b, h // G, :n])
+            s = scale * (keys @ q[b, h])
+            m = s.max()
+            e = np.exp(s - m)
+            z = e.sum()
+            weights[b, h, :n] = e / z
+            lse[b, h] = m + np.log(z)
+    return weights, lse
+
+
 def pooled_group_scores(weights_row_group: np.ndarray, pool_w: int) -> np.ndarray:
     """Scores that rank the tokens of one (sequence, KV head).
 

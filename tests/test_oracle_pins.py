@@ -424,6 +424,69 @@ def test_loop_refresh_changes_selection_and_tail_is_attended():
         assert np.allclose(val(res["outs"][t, b, h]), o, rtol=2 ** -8, atol=1e-30)
 
 
+def test_attn_scores_match_pure_python_and_closed_forms():
+    """Scores-only pass (Section 4.3, "w/o full attention"): softmax of scale * q.K over the
+    valid rows, keys only."""
+    rng = np.random.default_rng(31)
+    B, Hq, Hkv, D, cap = 2, 6, 2, 8, 12
+    lens = [11, 5]
+    q, K = rand_bits(rng, (B, Hq, D)), rand_bits(rng, (B, Hkv, cap, D), 1.5)
+    w, lse = oracle.attn_scores(q, K, lens, 0.37)
+    assert w.shape == (B, Hq, 11)
+    for b in range(B):
+        for h in range(Hq):
+            g = h // 3                                     # G = 3: heads 0-2 -> KV head 0
+            keys = val(K[b, g, :lens[b]]).tolist()
+            _, a, l = brute_attention(val(q[b, h]).tolist(), keys, keys, 0.37)
+            assert np.allclose(w[b, h, :lens[b]], a, rtol=1e-12, atol=0)
+            assert (w[b, h, lens[b]:] == 0).all()
+            assert abs(lse[b, h] - l) < 1e-12
+    # two keys, closed form: a0 = 1 / (1 + exp(scale * q.(k1 - k0)))
+    q2 = bits([[[1.0, 2.0]]]); K2 = bits([[[[0.5, -1.0], [0.25, 0.5]]]])
+    w2, _ = oracle.attn_scores(q2, K2, [2], 0.5)
+    s0, s1 = 0.5 * (0.5 - 2.0), 0.5 * (0.25 + 1.0)
+    assert abs(w2[0, 0, 0] - 1 / (1 + math.exp(s1 - s0))) < 1e-15
+    # equal keys: uniform scores; an empty sequence: nothing, lse = -inf
+    Ku = bits(np.ones((1, 1, 7, 2)))
+    wu, _ = oracle.attn_scores(q2, Ku, [7], 3.0)
+    assert np.allclose(wu, 1 / 7, rtol=1e-15)
+    w0, l0 = oracle.attn_scores(q2, Ku, [0], 3.0)
+    assert w0.shape == (1, 1, 0) and l0[0, 0] == -np.inf
+
+
+def test_scores_only_refresh_loop():
+    """Section 4.3, "w/o full attention": at a refresh step the output is attention over the
+    rebuilt small cache alone; the selections, and every partial step, are those of the
+    normal schedule."""
+    x = _small_loop_inputs(17, T=8)
+    args = (x["q"], x["K"], x["V"], x["nk"], x["nv"], x["lens"], 0.4, 5, 4)
+    ref = oracle.decode_loop(*args, pool_w=1)
+    res = oracle.decode_loop(*args, pool_w=1, scores_only_refresh=True)
+    assert (res["full"] == ref["full"]).all()
+    for a, c in zip(res["idx"], ref["idx"]):
+        assert (a == c).all()
+    partial = ~res["full"][:, 0]
+    assert (res["outs"][partial] == ref["outs"][partial]).all()
+    assert not (res["outs"][~partial] == ref["outs"][~partial]).all()     # refresh steps differ
+    assert res["rows"][:, 0].tolist() == [5, 6, 7, 8, 5, 6, 7, 8, 5]
+    # a refresh step equals brute-force attention over exactly the selected rows
+    Kv, Vv = val(res["k"]), val(res["v"])
+    for t in (0, 4, 8):
+        for b in range(2):
+            for h in range(4):
+                g = h // 2
+                rows = res["idx"][t][b, g].tolist()
+                assert len(set(rows)) == 5 and min(rows) >= 0
+                o, _, _ = brute_attention(val(x["q"][t, b, h]).tolist(), [Kv[b, g, j].tolist() for j in rows],
+                                          [Vv[b, g, j].tolist() for j in rows], 0.4)
+                assert np.allclose(val(res["outs"][t, b, h]), o, rtol=2 ** -8, atol=1e-30)
+    # a small cache as large as the context selects everything: the step is full attention again
+    big = oracle.decode_loop(x["q"], x["K"], x["V"], x["nk"], x["nv"], x["lens"], 0.4, 40, 1,
+                             scores_only_refresh=True)
+    van = oracle.decode_loop(x["q"], x["K"], x["V"], x["nk"], x["nv"], x["lens"], 0.4, 40, 1)
+    assert (big["outs"] == van["outs"]).all()
+
+
 def test_dynamic_trigger_in_loop():
     x = _small_loop_inputs(16, T=8, B=1, L=(21,))
     # identical queries at every step: similarity 1 > s, so no full step after t=0

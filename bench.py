@@ -175,6 +175,8 @@ def main():
         "full_attn": graph_us(lambda l: rk.rk_full_attn(geom, q_cur[l], *kv[l], seq_lens, Lb, out, weights=weights, workspace=ws)),
         "full_attn_select": graph_us(lambda l: rk.rk_full_attn_select(geom, q_cur[l], *kv[l], seq_lens, Lb, out, w.k_small, w.pool_w,
                                                                        layers[l].idx, workspace=ws)),
+        "score_select": graph_us(lambda l: rk.rk_score_select(geom, q_cur[l], kv[l][0], seq_lens, Lb, w.k_small, w.pool_w,
+                                                               layers[l].idx, workspace=ws)),
         "topk_select": graph_us(lambda l: rk.rk_topk_select(geom, weights, seq_lens, Lb, w.k_small, w.pool_w, layers[l].idx, workspace=ws)),
         "gather_small_kv": graph_us(lambda l: rk.rk_gather_small_kv(geom, *kv[l], layers[l].idx, w.k_small, layers[l].small_K, layers[l].small_V)),
         "partial_attn": graph_us(lambda l: rk.rk_partial_attn(geom, q_cur[l], layers[l].small_K, layers[l].small_V, w.k_small, *kv[l],

@@ -14,6 +14,8 @@
  *                       (Section 2.2 "Prefilling stage" + its GQA footnote; Appendix A.1
  *                       "Baseline Settings": kernel size 7; Appendix A.3)
  *   rk_full_attn_select the two steps above in one call (what a full step of the method does)
+ *   rk_score_select     scores over C_f and the selection without the attention output
+ *                       (Section 4.3, the "w/o full attention" setting)
  *   rk_gather_small_kv  rebuild C_p from the selected rows of C_f         (Section 2.2)
  *   rk_partial_attn     partial-attention step over C_p plus the tokens decoded since the
  *                       refresh                      (Section 2.2, "Decoding with partial cache")
@@ -164,6 +166,23 @@ int rk_full_attn_select(const rk_geom* geom, const void* q, rk_kv full,
                         int32_t* idx, float* sel_scores,
                         const int32_t* pred, int32_t pred_val,
                         void* workspace, size_t workspace_bytes, void* stream);
+
+/* Scores-only refresh (Section 4.3 "Impact of full attention steps", the setting "w/o full
+ * attention": the attention scores over the entire cache are calculated and the small cache is
+ * updated from them; the step's output then comes from rk_partial_attn on the updated small
+ * cache, so the values of the full cache are never read: half the bytes of a full step).
+ * Computes weights[b,h,j] = softmax_j(scale * <q[b,h,:], K[b,g,j,:]>), j < seq_lens[b], and the
+ * selection of rk_topk_select on them, exactly as rk_full_attn_select does, but produces no
+ * attention output.  full.v is not read and may be NULL.  `weights` ([batch, n_q_heads,
+ * w_stride] fp32) and `lse` are optional outputs (NULL: not returned); the other arguments as in
+ * rk_full_attn_select. */
+int rk_score_select(const rk_geom* geom, const void* q, rk_kv full,
+                    const int32_t* seq_lens, int32_t max_len,
+                    float* weights, int64_t w_stride, float* lse,
+                    int32_t k, int32_t pool_w, int32_t agg,
+                    int32_t* idx, float* sel_scores,
+                    const int32_t* pred, int32_t pred_val,
+                    void* workspace, size_t workspace_bytes, void* stream);
 
 /* Rebuild the small cache: small.k[b,g,i,:] = full.k[b,g,idx[b,g,i],:] and the same for v, for
  * every i < k with idx >= 0 (bit copies).  Slots whose idx is negative are left untouched.

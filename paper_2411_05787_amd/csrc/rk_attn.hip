@@ -454,6 +454,130 @@ void attn_split_kernel(const AttnParams p) {
     if (tid == 0) __hip_atomic_store(&p.counters[bg], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // next call
 }
 
+// Scores-only pass over the full cache (Section 4.3, "Impact of full attention steps", the
+// "w/o full attention" setting: the attention scores over the entire cache are computed and the
+// small cache is refreshed from them, but the step's output comes from the refreshed small cache,
+// so V is never read here: half the bytes of a full step).  Same work split, K operand layout
+// and score emission as attn_split_kernel; per workgroup it leaves only the (max, sum) pair of
+// every head.  With no V registers to hold, two K tiles per wavefront are in flight.
+template <int G>
+__global__ __launch_bounds__(256, 3)
+void score_split_kernel(const AttnParams p) {
+    constexpr int NW = kSplitWaves, ROWS = kTileRows;
+    const int c = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+    if (p.pred != nullptr && p.pred[b] != p.pred_val) return;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int n16 = lane & 15, c4 = lane >> 4;
+    const int r_first = (c * NW + w) * ROWS;
+    const int step = p.nch * NW * ROWS;
+    const uint16_t* kb = p.k2 + (int64_t)b * p.s2_b + (int64_t)g * p.s2_h + c4 * 8;
+
+    // first two tiles of this wavefront, requested before the length is known where they exist anyhow
+    u32x4 kA[2][4], kB[2][4];
+    const bool spec_a = (c + 1) * NW * ROWS <= p.cap2;
+    const bool spec_b = (int64_t)r_first + step + ROWS <= p.cap2;
+    auto load_exact = [&](u32x4 (&dst)[2][4], int r) {
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+                dst[t][kk] = *reinterpret_cast<const u32x4*>(kb + (int64_t)(r + t * 16 + n16) * kD + kk * 32);
+    };
+    if (spec_a) load_exact(kA, r_first);
+    if (spec_b) load_exact(kB, r_first + step);
+
+    bf16x8 qa[4];
+    {
+        const uint16_t* qrow = p.q + ((int64_t)b * p.Hq + (int64_t)g * G + (n16 < G ? n16 : 0)) * kD;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+            uint4 u = *reinterpret_cast<const uint4*>(qrow + (kk * 4 + c4) * 8);
+            if (n16 >= G) u = make_uint4(0, 0, 0, 0);
+            qa[kk] = __builtin_bit_cast(bf16x8, u);
+        }
+    }
+    const int n = min(max(min(p.seq_lens[b], p.cap2), 0), p.max_rows2);
+    const int nchunks = active_workgroups(n, p.nch);
+    if (c >= nchunks) return;
+    auto load_clamped = [&](u32x4 (&dst)[2][4], int r) {     // rows past the end re-read the last row (masked later)
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int row = min(r + t * 16 + n16, n - 1);
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+                dst[t][kk] = *reinterpret_cast<const u32x4*>(kb + (int64_t)row * kD + kk * 32);
+        }
+    };
+    float m_run = -INFINITY, l_run = 0.f;
+    auto tile = [&](const u32x4 (&k)[2][4], int r) {
+        float s[2][4];
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+                acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, k[t][kk]), qa[kk], acc, 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) s[t][i] = (r + t * 16 + 4 * c4 + i < n) ? acc[i] * p.scale : -INFINITY;
+        }
+        if (n16 < G) {
+            float* wrow = p.weights + ((int64_t)b * p.Hq + (int64_t)g * G + n16) * p.w_stride + r + 4 * c4;
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const int first = r + t * 16 + 4 * c4;
+                if (p.w_vec && first + 4 <= n) {
+                    *reinterpret_cast<float4*>(wrow + t * 16) = make_float4(s[t][0], s[t][1], s[t][2], s[t][3]);
+                } else {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i)
+                        if (first + i < n) wrow[t * 16 + i] = s[t][i];
+                }
+            }
+        }
+        float mx = fmaxf(fmaxf(fmaxf(s[0][0], s[0][1]), fmaxf(s[0][2], s[0][3])),
+                         fmaxf(fmaxf(s[1][0], s[1][1]), fmaxf(s[1][2], s[1][3])));
+        mx = fmaxf(mx, __shfl_xor(mx, 16));
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float m_new = fmaxf(m_run, mx);             // finite: the tile's first row is valid
+        float ps = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ps += fast_exp2((s[e >> 2][e & 3] - m_new) * kLog2e);
+        l_run = l_run * fast_exp2((m_run - m_new) * kLog2e) + ps;
+        m_run = m_new;
+    };
+    // tiles alternate between the two register sets; each set is re-requested right after use
+    int r = r_first;
+    if (r < n && !spec_a) load_clamped(kA, r);
+    if (r + step < n && !spec_b) load_clamped(kB, r + step);
+    while (r < n) {
+        tile(kA, r);
+        if (r + 2 * step < n) load_clamped(kA, r + 2 * step);
+        r += step;
+        if (r >= n) break;
+        tile(kB, r);
+        if (r + 2 * step < n) load_clamped(kB, r + 2 * step);
+        r += step;
+    }
+    l_run += __shfl_xor(l_run, 16);
+    l_run += __shfl_xor(l_run, 32);
+    __shared__ float sMw[NW][16], sLw[NW][16];
+    if (c4 == 0) { sMw[w][n16] = m_run; sLw[w][n16] = l_run; }
+    __syncthreads();
+    if (tid < G) {
+        float M = sMw[0][tid];
+#pragma unroll
+        for (int ww = 1; ww < NW; ++ww) M = fmaxf(M, sMw[ww][tid]);
+        float L = 0.f;
+#pragma unroll
+        for (int ww = 0; ww < NW; ++ww) {
+            const float mw = sMw[ww][tid];
+            L = fmaf((mw == -INFINITY) ? 0.f : fast_exp2((mw - M) * kLog2e), sLw[ww][tid], L);
+        }
+        float* ml = p.part_ml + (((int64_t)b * p.Hkv + g) * kMaxChunks + c) * G * 2;
+        *reinterpret_cast<float2*>(ml + tid * 2) = make_float2(M, L);
+    }
+}
+
 // ---- pieces of the kernels that finish a full step whose scores were emitted ----
 // LDS of one 256-thread workgroup that rebuilds lse of a query head and merges its output.
 struct HeadMergeLds {
@@ -612,15 +736,16 @@ void finish_pool_kernel(const AttnParams p, const float* __restrict__ scores, in
     const int64_t bg = (int64_t)b * p.Hkv + g;
 
     __shared__ HeadMergeLds s;
-    if (x < G) {
+    const int n_merge = p.out != nullptr ? G : 0;     // no output to merge after a scores-only pass
+    if (x < n_merge) {
         float2 v[kOutBatch];
         head_out_request(p, G, bg, x, nchunks, v);
         block_head_lse(p, G, bg, x, nchunks, s);
         block_head_out(p, G, b, bg, x, nchunks, s, v);
         return;
     }
-    const int j0 = (x - G) * kPoolTile;
-    if (j0 >= len) return;
+    const int j0 = (x - n_merge) * kPoolTile;
+    if (j0 >= len && !(j0 == 0 && n_merge == 0)) return;   // (an empty sequence still gets its lse = -inf)
 
     __shared__ float sA[kPoolTile + RK_MAX_POOL_W - 1];
     __shared__ uint32_t sH[kHistBins];
@@ -682,9 +807,11 @@ void finish_pool_kernel(const AttnParams p, const float* __restrict__ scores, in
                 lo = (float)(l64 - (double)hi);
             }
             sLse[gi][0] = hi; sLse[gi][1] = lo;
+            if (n_merge == 0 && j0 == 0) p.lse[(int64_t)b * p.Hq + (int64_t)g * G + gi] = hi;
         }
     }
     __syncthreads();
+    if (j0 >= len) return;
 
     // ---- weights, max over the group ----
 #pragma unroll
@@ -728,7 +855,7 @@ void finish_pool_kernel(const AttnParams p, const float* __restrict__ scores, in
 
 template <int G>
 static int launch_finish_pool(const AttnParams& p, int batch, int32_t max_len, const Workspace& ws, int half, hipStream_t st) {
-    dim3 grid(G + (max_len + kPoolTile - 1) / kPoolTile, p.Hkv, batch);
+    dim3 grid((p.out != nullptr ? G : 0) + (max_len + kPoolTile - 1) / kPoolTile, p.Hkv, batch);
     const int64_t stride = pooled_row_stride(max_len);
     hipLaunchKernelGGL((finish_pool_kernel<G>), grid, dim3(256), 0, st, p, ws.scores, stride, half, ws.pooled, stride, ws.hist);
     return launch_status();
@@ -757,9 +884,20 @@ static int launch_split(const AttnParams& p, int batch, int G, int nchunk_grid, 
     }
 }
 
+static int launch_score_split(const AttnParams& p, int batch, int G, int nchunk_grid, hipStream_t st) {
+    dim3 grid(nchunk_grid, p.Hkv, batch);
+    switch (G) {
+#define RK_CASE(g) case g: hipLaunchKernelGGL((score_split_kernel<g>), grid, dim3(256), 0, st, p); break;
+        RK_CASE(1) RK_CASE(2) RK_CASE(3) RK_CASE(4) RK_CASE(5) RK_CASE(6) RK_CASE(7) RK_CASE(8)
+#undef RK_CASE
+        default: return RK_ERR_UNSUPPORTED;
+    }
+    return launch_status();
+}
+
 int full_attn_stage(const rk_geom* geom, const void* q, rk_kv full, const int32_t* seq_lens, int32_t max_len,
                     void* out, float* weights, int64_t w_stride, float* lse, const int32_t* pred, int32_t pred_val,
-                    const Workspace& ws, hipStream_t st, bool scores_only, int pool_half) {
+                    const Workspace& ws, hipStream_t st, bool scores_only, int pool_half, bool no_v) {
     const int G = geom->n_q_heads / geom->n_kv_heads;
     const bool fused = pool_half >= 0;
     const bool emit = weights != nullptr || fused;
@@ -783,7 +921,8 @@ int full_attn_stage(const rk_geom* geom, const void* q, rk_kv full, const int32_
     p.counters = ws.counters; p.part_ml = ws.part_ml; p.part_o = ws.part_o; p.max_chunks = ws.max_chunks;
     const int nchunk_grid = p.nch;
     if (!emit) return launch_split<false, false>(p, geom->batch, G, nchunk_grid, st);
-    int rc = launch_split<true, false>(p, geom->batch, G, nchunk_grid, st);
+    int rc = no_v ? launch_score_split(p, geom->batch, G, nchunk_grid, st)
+                  : launch_split<true, false>(p, geom->batch, G, nchunk_grid, st);
     if (rc != RK_OK || scores_only) return rc;
     if (!fused) {
         dim3 grid(1 + (max_len + kNormTile - 1) / kNormTile, geom->n_q_heads, geom->batch);
@@ -829,7 +968,7 @@ extern "C" int rk_full_attn(const rk_geom* geom, const void* q, rk_kv full,
     Workspace ws;
     if ((rc = check_workspace(geom, max_len, 0, workspace, workspace_bytes, &ws)) != RK_OK) return rc;
     return full_attn_stage(geom, q, full, seq_lens, max_len, out, weights, w_stride, lse, pred, pred_val,
-                           ws, (hipStream_t)stream, false, -1);
+                           ws, (hipStream_t)stream, false, -1, false);
 }
 
 extern "C" int rk_full_attn_scores(const rk_geom* geom, const void* q, rk_kv full,
@@ -843,7 +982,7 @@ extern "C" int rk_full_attn_scores(const rk_geom* geom, const void* q, rk_kv ful
     Workspace ws;
     if ((rc = check_workspace(geom, max_len, 0, workspace, workspace_bytes, &ws)) != RK_OK) return rc;
     return full_attn_stage(geom, q, full, seq_lens, max_len, nullptr, scores, s_stride, nullptr, pred, pred_val,
-                           ws, (hipStream_t)stream, true, -1);
+                           ws, (hipStream_t)stream, true, -1, false);
 }
 
 extern "C" int rk_partial_attn(const rk_geom* geom, const void* q, rk_kv small, int32_t n_sel,

@@ -129,8 +129,8 @@ static inline int check_geom(const rk_geom* g) {
 
 static inline bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
 
-static inline int check_kv(const rk_kv& c) {
-    if (!c.k || !c.v) return RK_ERR_INVALID_ARG;
+static inline int check_kv(const rk_kv& c, bool need_v = true) {
+    if (!c.k || (need_v && !c.v)) return RK_ERR_INVALID_ARG;
     if (!aligned16(c.k) || !aligned16(c.v)) return RK_ERR_INVALID_ARG;
     // row indices are int32 and the kernels step past the end by up to kMaxChunks * kMinChunk rows
     if (c.stride_b < 0 || c.stride_h < 0 || c.capacity <= 0 || c.capacity > INT32_MAX - 2 * kMaxChunks * kMinChunk) return RK_ERR_INVALID_ARG;
@@ -153,12 +153,13 @@ static inline int launch_status() {
 // Stages shared by the entry points (arguments already checked by the caller).
 //   full_attn_stage: the split kernel, then either the merge inside it (no weights), the merge +
 //     normalise kernel (weights in place), or, with pool_half >= 0, the fused finish that also
-//     leaves the pooled group scores and their histogram in the workspace.
+//     leaves the pooled group scores and their histogram in the workspace.  no_v: the split kernel
+//     is the scores-only one (K rows only; out must be NULL, pool_half >= 0).
 //   select_stage: top-K over the pooled scores and histogram that are in the workspace.
 __attribute__((visibility("hidden")))
 int full_attn_stage(const rk_geom* geom, const void* q, rk_kv full, const int32_t* seq_lens, int32_t max_len,
                     void* out, float* weights, int64_t w_stride, float* lse, const int32_t* pred, int32_t pred_val,
-                    const Workspace& ws, hipStream_t st, bool scores_only, int pool_half);
+                    const Workspace& ws, hipStream_t st, bool scores_only, int pool_half, bool no_v);
 __attribute__((visibility("hidden")))
 int select_stage(const rk_geom* geom, const int32_t* seq_lens, int32_t max_len, int32_t k, int32_t* idx,
                  float* sel_scores, const int32_t* pred, int32_t pred_val, const Workspace& ws, hipStream_t st);

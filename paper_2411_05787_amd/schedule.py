@@ -20,9 +20,13 @@ class RefreshKVLayer:
     def __init__(self, geom: rk.Geom, K: torch.Tensor, V: torch.Tensor, seq_lens: torch.Tensor,
                  max_len: int, k_small: int, stride: int, pool_w: int = 7, dynamic: bool = False,
                  threshold: float = 0.0, evict_lowest: bool = False,
-                 workspace: Optional[rk.Workspace] = None, weights: Optional[torch.Tensor] = None):
+                 workspace: Optional[rk.Workspace] = None, weights: Optional[torch.Tensor] = None,
+                 scores_only_refresh: bool = False):
         """K, V: bf16 [B, Hkv, capacity, D] holding seq_lens[b] rows; seq_lens int32 [B] on the
-        GPU; max_len: host upper bound of seq_lens now (kept up to date by :meth:`advance`)."""
+        GPU; max_len: host upper bound of seq_lens now (kept up to date by :meth:`advance`).
+        scores_only_refresh: refresh steps compute the scores over the full cache, rebuild the
+        small cache and attend to the rebuilt small cache alone (Section 4.3, "w/o full
+        attention"); the values of the full cache are then read only by the gather."""
         dev = K.device
         B, Hq, Hkv, D = geom.batch, geom.n_q_heads, geom.n_kv_heads, geom.head_dim
         self.geom, self.K, self.V, self.seq_lens = geom, K, V, seq_lens
@@ -30,6 +34,7 @@ class RefreshKVLayer:
         self.max_len = int(max_len)
         self.k_small, self.stride, self.pool_w = int(k_small), int(stride), int(pool_w)
         self.dynamic, self.threshold, self.evict_lowest = bool(dynamic), float(threshold), bool(evict_lowest)
+        self.scores_only_refresh = bool(scores_only_refresh)
         self.ws = workspace if workspace is not None else rk.Workspace(geom, self.capacity, k_small, device=dev)
         self.weights = weights        # optional fp32 [B, Hq, capacity]: the weights of the last full step, if wanted
         self.small_K = torch.zeros(B, Hkv, k_small, D, dtype=torch.bfloat16, device=dev)
@@ -73,11 +78,19 @@ class RefreshKVLayer:
 
     def _full(self, q, out, pred=None, stream=None) -> None:
         g = self.geom
-        rk.rk_full_attn_select(g, q, self.K, self.V, self.seq_lens, self.max_len, out, self.k_small, self.pool_w,
-                               self.idx, weights=self.weights, pred=pred, pred_val=1, workspace=self.ws, stream=stream)
+        if self.scores_only_refresh:
+            rk.rk_score_select(g, q, self.K, self.seq_lens, self.max_len, self.k_small, self.pool_w, self.idx,
+                               weights=self.weights, pred=pred, pred_val=1, workspace=self.ws, stream=stream)
+        else:
+            rk.rk_full_attn_select(g, q, self.K, self.V, self.seq_lens, self.max_len, out, self.k_small, self.pool_w,
+                                   self.idx, weights=self.weights, pred=pred, pred_val=1, workspace=self.ws,
+                                   stream=stream)
         rk.rk_gather_small_kv(g, self.K, self.V, self.idx, self.k_small, self.small_K, self.small_V,
                               seq_lens=self.seq_lens, tail_start=self.tail_start,
                               pred=pred, pred_val=1, stream=stream)
+        if self.scores_only_refresh:      # tail_start == seq_lens now: the K selected rows and nothing else
+            rk.rk_partial_attn(g, q, self.small_K, self.small_V, self.k_small, self.K, self.V, self.tail_start,
+                               self.seq_lens, 1, out, pred=pred, pred_val=1, workspace=self.ws, stream=stream)
 
     def _partial(self, q, out, pred=None, stream=None) -> None:
         if self.evict_lowest and not self.dynamic:

@@ -94,6 +94,16 @@ def test_host_side_argument_checks_return_before_any_launch(rk):
     assert fused(k=16385) == -2
     assert fused(pool=2) == -1
     assert fused(ws=None) == -3
+    kv_k_only = _Kv(fake, None, 8 * 4096 * 128, 4096 * 128, 4096)
+    score = lambda **kw: lib.rk_score_select(C.byref(g), kw.get("q", fake), kw.get("kv", kv_k_only), fake, 4096, None, 0, None,
+                                             kw.get("k", 256), 7, 0, kw.get("idx", fake), None, None, 0,
+                                             kw.get("ws", 0x100000), ws_bytes, None)
+    assert score(q=None) == -1
+    assert score(kv=_Kv(None, fake, 0, 0, 4096)) == -1                   # keys are required, values are not
+    assert score(idx=None) == -1
+    assert score(k=0) == -1
+    assert score(ws=None) == -3
+    assert full(kv=kv_k_only) == -1                                      # a full step needs the values
     assert lib.rk_gather_small_kv(C.byref(g), kv, None, 16, kv, None, None, None, 0, None) == -1
     assert lib.rk_gather_small_kv(C.byref(g), kv, fake, 0, kv, None, None, None, 0, None) == -1
     assert lib.rk_gather_small_kv(C.byref(g), kv, fake, 16, kv, None, fake, None, 0, None) == -1   # tail_start without seq_lens

@@ -428,14 +428,16 @@ def test_query_sim_matches_oracle(rk):
 
 
 # ----------------------------------------------------------------------------- whole loop
-def run_gpu_loop(rk, w: gen.Workload, layer: int, K, V, q_steps, new_k, new_v, lens0, evict_lowest=False):
+def run_gpu_loop(rk, w: gen.Workload, layer: int, K, V, q_steps, new_k, new_v, lens0, evict_lowest=False,
+                 scores_only=False):
     """Drive the library through the decode schedule; returns per-step outputs and snapshots."""
     dev = "cuda"
     geom = rk.Geom(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.scale)
     Kd, Vd = K.to(dev).clone(), V.to(dev).clone()
     sl = lens0.to(dev).clone()
     lay = rk.RefreshKVLayer(geom, Kd, Vd, sl, int(lens0.max()), w.k_small, w.stride, pool_w=w.pool_w,
-                            dynamic=w.dynamic, threshold=w.threshold, evict_lowest=evict_lowest)
+                            dynamic=w.dynamic, threshold=w.threshold, evict_lowest=evict_lowest,
+                            scores_only_refresh=scores_only)
     qd, nk, nv = q_steps.to(dev), new_k.to(dev), new_v.to(dev)
     outs, idxs, needs, sims, kinds = [], [], [], [], []
     for t in range(w.n_steps + 1):
@@ -450,15 +452,16 @@ def run_gpu_loop(rk, w: gen.Workload, layer: int, K, V, q_steps, new_k, new_v, l
                 kinds=kinds, K=gen.bf16_bits(Kd), V=gen.bf16_bits(Vd), lens=sl.cpu().numpy())
 
 
-def check_loop(rk, w: gen.Workload, evict_lowest=False):
+def check_loop(rk, w: gen.Workload, evict_lowest=False, scores_only=False):
     K, V = gen.make_kv(w, 0)
     q = gen.make_queries(w, 0)
     nk, nv = gen.make_new_rows(w, 0)
     lens0 = gen.seq_lens(w)
-    got = run_gpu_loop(rk, w, 0, K, V, q, nk, nv, lens0, evict_lowest)
+    got = run_gpu_loop(rk, w, 0, K, V, q, nk, nv, lens0, evict_lowest, scores_only)
     ref = oracle.decode_loop(gen.bf16_bits(q), gen.bf16_bits(K), gen.bf16_bits(V), gen.bf16_bits(nk),
                              gen.bf16_bits(nv), lens0.numpy(), w.scale, w.k_small, w.stride, pool_w=w.pool_w,
-                             dynamic=w.dynamic, threshold=w.threshold, evict_lowest=evict_lowest)
+                             dynamic=w.dynamic, threshold=w.threshold, evict_lowest=evict_lowest,
+                             scores_only_refresh=scores_only)
     assert (got["K"] == ref["k"]).all() and (got["V"] == ref["v"]).all() and (got["lens"] == ref["lens"]).all()
     G = w.group
     n_diff = 0
@@ -486,6 +489,58 @@ def check_loop(rk, w: gen.Workload, evict_lowest=False):
                                                 "t=%d b=%d g=%d" % (t, b, g))
         assert_out_close(got["outs"][t], ref["outs"][t], "%s t=%d" % (w.name, t))
     return got, ref, n_diff
+
+
+def test_score_select_matches_oracle(rk):
+    """rk_score_select: weights, lse and selection from the keys alone (no value pointer at all)."""
+    cases = [("llama_ragged", 2, 32, 8, [3100, 1029], 3200, 256, 7), ("qwen_g7", 1, 28, 4, [2500], 2560, 128, 7),
+             ("g8_pool1_short_empty", 3, 16, 2, [130, 0, 5], 256, 16, 1), ("two_rounds", 1, 4, 1, [40000], 40064, 512, 7)]
+    for name, B, Hq, Hkv, lens, cap, k, pool_w in cases:
+        say("score_select case", name)
+        q, K, _ = rand_case(400 + len(name), B, Hq, Hkv, cap)
+        K[:, :, ::97] *= 3.0
+        for b in range(B):
+            K[b, :, lens[b]:] = float("nan")             # rows past the end must not matter
+        scale = float(np.float32(1 / np.sqrt(128)))
+        geom = rk.Geom(B, Hq, Hkv, 128, scale)
+        ws = rk.Workspace(geom, cap, k)
+        sl = torch.tensor(lens, dtype=torch.int32, device="cuda")
+        w_ref, lse_ref = oracle.attn_scores(gen.bf16_bits(q), gen.bf16_bits(K), lens, scale)
+        i_ref, _ = oracle.topk_select(w_ref.astype(np.float32), lens, Hkv, k, pool_w)
+        G = Hq // Hkv
+        for want_w in (True, False):
+            wt = torch.full((B, Hq, cap), -7.0, dtype=torch.float32, device="cuda") if want_w else None
+            lse = torch.full((B, Hq), 123.0, dtype=torch.float32, device="cuda")
+            idx = torch.full((B, Hkv, k), -5, dtype=torch.int32, device="cuda")
+            rk.rk_score_select(geom, q.cuda(), K.cuda(), sl, max(max(lens), 1), k, pool_w, idx, weights=wt, lse=lse,
+                               workspace=ws)
+            torch.cuda.synchronize()
+            idx_n, lse_n = idx.cpu().numpy(), lse.cpu().numpy()
+            for b in range(B):
+                n = lens[b]
+                if n == 0:
+                    assert (lse_n[b] == -np.inf).all() and (idx_n[b] == -1).all()
+                    continue
+                assert np.abs(lse_n[b] - lse_ref[b]).max() < 1e-5
+                if want_w:
+                    wn = wt[b].cpu().numpy()
+                    assert (np.abs(wn[:, :n] - w_ref[b, :, :n]) / w_ref[b, :, :n]).max() < 1e-5
+                    assert (wn[:, n:] == -7.0).all()
+                for g in range(Hkv):
+                    P = oracle.pooled_group_scores(w_ref[b, g * G:(g + 1) * G, :n].astype(np.float32), pool_w)
+                    assert_idx_equivalent(idx_n[b, g], i_ref[b, g], P, n, k, "%s b=%d g=%d" % (name, b, g))
+
+
+def test_loop_scores_only_refresh(rk):
+    """Section 4.3 "w/o full attention": refresh steps attend to the rebuilt small cache alone."""
+    w = gen.shrink(gen.WORKLOADS["cfg1_llama_2k"], n_steps=12)
+    say("loop, scores-only refresh", w)
+    got, ref, n_diff = check_loop(rk, w, scores_only=True)
+    assert got["kinds"][0] == "full" and got["kinds"][4] == "full" and got["kinds"][5] == "partial"
+    wq = gen.shrink(gen.WORKLOADS["cfg3_qwen_64k_dynamic"], context=3000, k_small=256, n_steps=22, n_layers=1)
+    say("loop, scores-only refresh, dynamic", wq)
+    got, ref, _ = check_loop(rk, wq, scores_only=True)
+    assert "both" in got["kinds"]
 
 
 def test_loop_cfg1_every_step(rk):

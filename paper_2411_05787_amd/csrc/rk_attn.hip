@@ -101,17 +101,19 @@ __device__ void merge_partials(const AttnParams& p, int b, int g, int nchunks, f
     const int nb = (nchunks + kMergeBatch - 1) / kMergeBatch;
     const int n_items = SLICES * nb;
     uint64_t cur[kMergeBatch], nxt[kMergeBatch];
-    auto request = [&](uint64_t (&dst)[kMergeBatch], int item) {
-        const int e2 = min((item / nb) * NT + tid, PER - 1), c0 = (item % nb) * kMergeBatch;
-        const float* src = po + 2 * e2;
+    int r_slice = 0, r_batch = 0;                 // the next item to request
+    auto request = [&](uint64_t (&dst)[kMergeBatch]) {
+        const float* src = po + 2 * min(r_slice * NT + tid, PER - 1);
+        const int c0 = r_batch * kMergeBatch;
 #pragma unroll
         for (int u = 0; u < kMergeBatch; ++u) dst[u] = coherent_load2(src + (int64_t)min(c0 + u, nchunks - 1) * G * kD);
+        if (++r_batch == nb) { r_batch = 0; ++r_slice; }
     };
     // everything below is requested before the first wait
     const uint64_t ml0 = coherent_load2(ml + (int64_t)min(tid, n_ml - 1) * 2);
     const uint64_t ml1 = coherent_load2(ml + (int64_t)min(NT + tid, n_ml - 1) * 2);
-    request(cur, 0);
-    if (n_items > 1) request(nxt, 1);
+    request(cur);
+    if (n_items > 1) request(nxt);
     if (tid < n_ml) { sW[tid] = lo_f(ml0); sLc[tid] = hi_f(ml0); }
     if (NT + tid < n_ml) { sW[NT + tid] = lo_f(ml1); sLc[NT + tid] = hi_f(ml1); }
     __syncthreads();
@@ -122,35 +124,36 @@ __device__ void merge_partials(const AttnParams& p, int b, int g, int nchunks, f
         const float mx = wave_max(mc);
         const float wgt = (lane >= nchunks || mc == -INFINITY) ? 0.f : fast_exp2((mc - mx) * kLog2e);
         double ls = (double)wgt * (double)sLc[c * G + gi];      // the sum that normalises the output: fp64
-        if (lane < nchunks) sW[c * G + gi] = wgt;
+        if (lane < nb * kMergeBatch) sW[lane * G + gi] = wgt;    // zero beyond nchunks: whole batches are summed
 #pragma unroll
         for (int m = 1; m < 64; m <<= 1) ls += __shfl_xor(ls, m);
         if (lane == 0) { sM[gi] = mx; sL[gi] = ls; }
     }
     __syncthreads();
     float acc0 = 0.f, acc1 = 0.f;
+    int slice = 0, batch = 0;                     // the item in `cur`
 #pragma unroll 1
     for (int item = 0; item < n_items; ++item) {
-        const int slice = item / nb, c0 = (item % nb) * kMergeBatch;
         const int e2 = min(slice * NT + tid, PER - 1);
         const int gi = (2 * e2) / kD;
+        const float* wrow = sW + batch * kMergeBatch * G + gi;
 #pragma unroll
         for (int u = 0; u < kMergeBatch; ++u) {
-            const float wgt = (c0 + u < nchunks) ? sW[(c0 + u) * G + gi] : 0.f;
+            const float wgt = wrow[u * G];
             acc0 = fmaf(wgt, lo_f(cur[u]), acc0);
             acc1 = fmaf(wgt, hi_f(cur[u]), acc1);
         }
 #pragma unroll
         for (int u = 0; u < kMergeBatch; ++u) cur[u] = nxt[u];
-        if (item + 2 < n_items) request(nxt, item + 2);
-        if (c0 + kMergeBatch >= nchunks) {         // last batch of the slice
+        if (item + 2 < n_items) request(nxt);
+        if (++batch == nb) {                       // that was the last batch of the slice
             if (slice * NT + tid < PER) {
                 const float L = (float)sL[gi];
                 const float inv = L > 0.f ? 1.f / L : 0.f;
                 const uint32_t packed = (uint32_t)f32_to_bf16(acc0 * inv) | ((uint32_t)f32_to_bf16(acc1 * inv) << 16);
                 reinterpret_cast<uint32_t*>(p.out + ((int64_t)b * p.Hq + g * G) * kD)[e2] = packed;
             }
-            acc0 = 0.f; acc1 = 0.f;
+            acc0 = 0.f; acc1 = 0.f; batch = 0; ++slice;
         }
     }
     if (tid < G) {                                // fp32 log: lse is an fp32 output, M + ln L loses nothing that matters

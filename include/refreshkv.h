@@ -210,6 +210,18 @@ int rk_partial_attn(const rk_geom* geom, const void* q, rk_kv small, int32_t n_s
                     const int32_t* pred, int32_t pred_val,
                     void* workspace, size_t workspace_bytes, void* stream);
 
+/* The same step with the fixed-size small cache of Section 2.2 ("Decoding with partial cache":
+ * the new token's KV pair is appended to C_p and the KV pair with the lowest score is evicted):
+ * sequence b reads the first max(k - r[b], 0) selected rows, r[b] = seq_lens[b] - tail_start[b]
+ * being the rows decoded since its refresh, plus those r[b] rows from the full cache, so k rows
+ * in all.  Equal to rk_partial_attn with n_sel = k - r when every sequence has the same r; here
+ * r is taken per sequence on the GPU (dynamic schedule, ragged batches). */
+int rk_partial_attn_fixed(const rk_geom* geom, const void* q, rk_kv small, int32_t k,
+                          rk_kv full, const int32_t* tail_start, const int32_t* seq_lens,
+                          int32_t max_recent, void* out,
+                          const int32_t* pred, int32_t pred_val,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
 /* Query-similarity trigger.
  *   qbar[b,:] = mean over the query heads of q[b,h,:]                        (fp32)
  *   sim[b]    = <qbar, q_ref[b]> / (max(|qbar|, 1e-8) * max(|q_ref[b]|, 1e-8))

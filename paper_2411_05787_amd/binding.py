@@ -16,7 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "librefreshkv.so")
 
 EXPORTS = ["rk_version", "rk_status_string", "rk_workspace_bytes", "rk_workspace_init",
-           "rk_full_attn", "rk_full_attn_scores", "rk_topk_select", "rk_full_attn_select", "rk_score_select", "rk_gather_small_kv", "rk_partial_attn",
+           "rk_full_attn", "rk_full_attn_scores", "rk_topk_select", "rk_full_attn_select", "rk_score_select", "rk_gather_small_kv", "rk_partial_attn", "rk_partial_attn_fixed",
            "rk_query_sim", "rk_mark_refresh", "rk_calibration_copy"]
 
 RK_AGG_MAX = 0
@@ -67,6 +67,8 @@ def _load(path: str = LIB_PATH) -> C.CDLL:
     l.rk_gather_small_kv.argtypes = [G, _Kv, P, I32, _Kv, P, P, P, I32, P]
     l.rk_partial_attn.restype = C.c_int
     l.rk_partial_attn.argtypes = [G, P, _Kv, I32, _Kv, P, P, I32, P, P, I32, P, SZ, P]
+    l.rk_partial_attn_fixed.restype = C.c_int
+    l.rk_partial_attn_fixed.argtypes = [G, P, _Kv, I32, _Kv, P, P, I32, P, P, I32, P, SZ, P]
     l.rk_query_sim.restype = C.c_int
     l.rk_query_sim.argtypes = [G, P, P, C.c_float, I32, P, P, P]
     l.rk_calibration_copy.restype = C.c_int
@@ -284,6 +286,19 @@ def rk_partial_attn(geom: Geom, q, small_K, small_V, n_sel: int, K, V, tail_star
     _check("rk_partial_attn", lib.rk_partial_attn(
         C.byref(geom.c()), _dev(q, torch.bfloat16, "q", (B, Hq, D)),
         _kv(geom, small_K, small_V, "small", min_rows=n_sel), int(n_sel), _kv(geom, K, V, "full"),
+        _dev(tail_start, torch.int32, "tail_start", (B,)), _dev(seq_lens, torch.int32, "seq_lens", (B,)),
+        int(max_recent), _dev(out, torch.bfloat16, "out", (B, Hq, D)),
+        _dev(pred, torch.int32, "pred", (B,), optional=True), int(pred_val),
+        workspace.ptr, workspace.nbytes, _stream(stream)))
+
+
+def rk_partial_attn_fixed(geom: Geom, q, small_K, small_V, k: int, K, V, tail_start, seq_lens,
+                          max_recent: int, out, pred=None, pred_val: int = 0, workspace: Workspace = None,
+                          stream=None) -> None:
+    B, Hq, D = geom.batch, geom.n_q_heads, geom.head_dim
+    _check("rk_partial_attn_fixed", lib.rk_partial_attn_fixed(
+        C.byref(geom.c()), _dev(q, torch.bfloat16, "q", (B, Hq, D)),
+        _kv(geom, small_K, small_V, "small", min_rows=k), int(k), _kv(geom, K, V, "full"),
         _dev(tail_start, torch.int32, "tail_start", (B,)), _dev(seq_lens, torch.int32, "seq_lens", (B,)),
         int(max_recent), _dev(out, torch.bfloat16, "out", (B, Hq, D)),
         _dev(pred, torch.int32, "pred", (B,), optional=True), int(pred_val),

@@ -39,6 +39,7 @@ struct AttnParams {
     const int32_t* tail_start;         // TWO_SEG only
     const int32_t* seq_lens;
     int32_t n_sel;                     // rows taken from the small cache (TWO_SEG only)
+    int32_t evict;                     // ... less one per row decoded since the refresh (fixed-size small cache)
     int32_t max_rows2;                 // host bound on the rows taken from the full cache
     int32_t cap1, cap2;                // rows allocated in the small / full cache
     int32_t nch;                       // workgroups per (sequence, KV head): the launch's grid x
@@ -247,7 +248,10 @@ void attn_split_kernel(const AttnParams p) {
     int n1 = 0, start2 = 0;
     if (TWO_SEG) {
         const int t0 = min(max(p.tail_start[b], 0), p.cap2);
-        n1 = min(min(p.n_sel, t0), p.cap1);
+        // fixed-size small cache: every row decoded since the refresh pushed out the selected row
+        // with the lowest score, i.e. the last one (the small cache is in descending score order)
+        const int keep = p.evict ? max(p.n_sel - max(len - t0, 0), 0) : p.n_sel;
+        n1 = min(min(keep, t0), p.cap1);
         n1 = max(n1, 0);
         start2 = t0;
     }
@@ -988,11 +992,11 @@ extern "C" int rk_full_attn_scores(const rk_geom* geom, const void* q, rk_kv ful
                            ws, (hipStream_t)stream, true, -1, false);
 }
 
-extern "C" int rk_partial_attn(const rk_geom* geom, const void* q, rk_kv small, int32_t n_sel,
-                               rk_kv full, const int32_t* tail_start, const int32_t* seq_lens,
-                               int32_t max_recent, void* out,
-                               const int32_t* pred, int32_t pred_val,
-                               void* workspace, size_t workspace_bytes, void* stream) {
+static int partial_attn_impl(const rk_geom* geom, const void* q, rk_kv small, int32_t n_sel, bool evict,
+                             rk_kv full, const int32_t* tail_start, const int32_t* seq_lens,
+                             int32_t max_recent, void* out,
+                             const int32_t* pred, int32_t pred_val,
+                             void* workspace, size_t workspace_bytes, void* stream) {
     int rc = check_geom(geom);
     if (rc != RK_OK) return rc;
     if (!q || !out || !seq_lens || !tail_start || n_sel < 0 || max_recent < 0) return RK_ERR_INVALID_ARG;
@@ -1014,6 +1018,7 @@ extern "C" int rk_partial_attn(const rk_geom* geom, const void* q, rk_kv small, 
     p.tail_start = tail_start;
     p.seq_lens = seq_lens;
     p.n_sel = n_sel;
+    p.evict = evict ? 1 : 0;
     p.max_rows2 = max_recent;
     p.cap1 = n_sel > 0 ? (int32_t)small.capacity : 0; p.cap2 = (int32_t)full.capacity;
     p.nch = split_workgroups(max_rows, (int64_t)geom->batch * geom->n_kv_heads, kMergeChunks);
@@ -1025,4 +1030,22 @@ extern "C" int rk_partial_attn(const rk_geom* geom, const void* q, rk_kv small, 
     p.counters = ws.counters; p.part_ml = ws.part_ml; p.part_o = ws.part_o; p.max_chunks = ws.max_chunks;
     const int nchunk_grid = p.nch;
     return launch_split<false, true>(p, geom->batch, G, nchunk_grid, (hipStream_t)stream);
+}
+
+extern "C" int rk_partial_attn(const rk_geom* geom, const void* q, rk_kv small, int32_t n_sel,
+                               rk_kv full, const int32_t* tail_start, const int32_t* seq_lens,
+                               int32_t max_recent, void* out,
+                               const int32_t* pred, int32_t pred_val,
+                               void* workspace, size_t workspace_bytes, void* stream) {
+    return partial_attn_impl(geom, q, small, n_sel, false, full, tail_start, seq_lens, max_recent, out, pred, pred_val,
+                             workspace, workspace_bytes, stream);
+}
+
+extern "C" int rk_partial_attn_fixed(const rk_geom* geom, const void* q, rk_kv small, int32_t k,
+                                     rk_kv full, const int32_t* tail_start, const int32_t* seq_lens,
+                                     int32_t max_recent, void* out,
+                                     const int32_t* pred, int32_t pred_val,
+                                     void* workspace, size_t workspace_bytes, void* stream) {
+    return partial_attn_impl(geom, q, small, k, true, full, tail_start, seq_lens, max_recent, out, pred, pred_val,
+                             workspace, workspace_bytes, stream);
 }

@@ -93,13 +93,9 @@ class RefreshKVLayer:
                                self.seq_lens, 1, out, pred=pred, pred_val=1, workspace=self.ws, stream=stream)
 
     def _partial(self, q, out, pred=None, stream=None) -> None:
-        if self.evict_lowest and not self.dynamic:
-            n_sel = max(self.k_small - self.recent_bound, 0)      # exact: all sequences refreshed together
-        else:
-            n_sel = self.k_small
-        rk.rk_partial_attn(self.geom, q, self.small_K, self.small_V, n_sel, self.K, self.V, self.tail_start,
-                           self.seq_lens, max(self.recent_bound, 1), out, pred=pred, pred_val=0,
-                           workspace=self.ws, stream=stream)
+        fn = rk.rk_partial_attn_fixed if self.evict_lowest else rk.rk_partial_attn
+        fn(self.geom, q, self.small_K, self.small_V, self.k_small, self.K, self.V, self.tail_start,
+           self.seq_lens, max(self.recent_bound, 1), out, pred=pred, pred_val=0, workspace=self.ws, stream=stream)
 
     def step(self, t: int, q: torch.Tensor, out: Optional[torch.Tensor] = None, stream=None) -> str:
         """Attention of decode step t (t = 0: the prefill-equivalent initialisation).

@@ -355,6 +355,41 @@ def test_partial_attn_matches_oracle(rk, case):
     assert_out_close(gen.bf16_bits(out), o_ref, name)
 
 
+def test_partial_attn_fixed_size_per_sequence(rk):
+    """rk_partial_attn_fixed: every sequence drops one selected row per row decoded since ITS refresh."""
+    say("partial, fixed-size small cache, ragged")
+    B, Hq, Hkv, k = 4, 8, 2, 200
+    lens, recent = [900, 650, 300, 150], [0, 7, 31, 3]        # the last one: fewer than k rows were ever selected
+    cap = max(lens) + 8
+    q, K, V = rand_case(321, B, Hq, Hkv, cap)
+    scale = float(np.float32(1 / np.sqrt(128)))
+    geom = rk.Geom(B, Hq, Hkv, 128, scale)
+    tail = [l - r for l, r in zip(lens, recent)]
+    g = torch.Generator().manual_seed(6)
+    idx = torch.full((B, Hkv, k), -1, dtype=torch.int32)
+    for b in range(B):
+        kk = min(k, tail[b])
+        for h in range(Hkv):
+            idx[b, h, :kk] = torch.randperm(tail[b], generator=g)[:kk].to(torch.int32)
+    sK = torch.zeros(B, Hkv, k, 128, dtype=torch.bfloat16, device="cuda")
+    sV = torch.zeros_like(sK)
+    Kd, Vd = K.cuda(), V.cuda()
+    rk.rk_gather_small_kv(geom, Kd, Vd, idx.cuda(), k, sK, sV)
+    ws = rk.Workspace(geom, cap, k)
+    out = torch.zeros(B, Hq, 128, dtype=torch.bfloat16, device="cuda")
+    rk.rk_partial_attn_fixed(geom, q.cuda(), sK, sV, k, Kd, Vd, torch.tensor(tail, dtype=torch.int32, device="cuda"),
+                             torch.tensor(lens, dtype=torch.int32, device="cuda"), max(recent), out, workspace=ws)
+    torch.cuda.synchronize()
+    rK = np.zeros((B, Hkv, k, 128), dtype=np.uint16); rV = rK.copy()
+    oracle.gather_small_kv(gen.bf16_bits(K), gen.bf16_bits(V), idx.numpy(), rK, rV)
+    got = gen.bf16_bits(out)
+    for b in range(B):
+        sl = slice(b, b + 1)
+        o_ref = oracle.partial_attn(gen.bf16_bits(q)[sl], rK[sl], rV[sl], max(k - recent[b], 0), gen.bf16_bits(K)[sl],
+                                    gen.bf16_bits(V)[sl], tail[sl], lens[sl], scale)
+        assert_out_close(got[sl], o_ref, "b=%d" % b)
+
+
 def test_rows_past_the_end_are_never_used(rk):
     """Cache rows at and beyond seq_lens (and small-cache rows beyond the selected ones) hold NaN:
     nothing of them may reach the outputs, the weights or the selection."""
@@ -556,6 +591,14 @@ def test_loop_cfg1_fixed_size_small_cache(rk):
     w = gen.shrink(gen.WORKLOADS["cfg1_llama_2k"], context=1024, k_small=128, n_steps=12, stride=6)
     say("loop evict-lowest", w.name)
     check_loop(rk, w, evict_lowest=True)
+
+
+def test_loop_dynamic_trigger_fixed_size_small_cache(rk):
+    """Dynamic schedule with the paper's fixed-size small cache: r differs per layer and sequence."""
+    w = gen.shrink(gen.WORKLOADS["cfg3_qwen_64k_dynamic"], context=3000, k_small=256, n_steps=30, batch=2)
+    say("loop dynamic, evict lowest", w.name)
+    got, ref, _ = check_loop(rk, w, evict_lowest=True)
+    assert ref["full"][1:].any() and not ref["full"][1:].all()
 
 
 def test_loop_dynamic_trigger_qwen_small(rk):

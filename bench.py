@@ -36,6 +36,9 @@ def parse():
     ap.add_argument("--workload", default="cfg2_llama_32k")
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (0 = workload's)")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
+    ap.add_argument("--launch", choices=["graph", "native", "eager"], default="graph",
+                    help="graph: replay one HIP graph per step; native: one rk_decode_step call per step enqueues all "
+                         "layers; eager: one Python call per library call")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=4, help="layers of the oracle sample")
     return ap.parse_args()
@@ -84,10 +87,20 @@ def main():
     torch.cuda.synchronize()
     setup_s = time.time() - t_setup
 
+    launch = "eager" if args.no_graph else args.launch
+    model = None
+    if launch == "native":
+        model = rk.RefreshKVModel(geom, kv, seq_lens, int(lens0.max()), w.k_small, w.stride, pool_w=w.pool_w,
+                                  dynamic=w.dynamic, threshold=w.threshold, workspace=ws)
+
     def enqueue_step(t: int):
         """Everything of decode step t on the current stream (q_cur already holds the queries)."""
         if t >= 1:
             seq_lens.add_(1)
+        if model is not None:
+            if t >= 1:
+                model.advance()
+            return model.step(t, q_cur)
         kind = None
         for l, lay in enumerate(layers):
             kind = lay.step(t, q_cur[l])
@@ -99,10 +112,13 @@ def main():
     # t = 0: prefill-equivalent initialisation (full step everywhere), eager
     q_cur.copy_(q_steps[0])
     enqueue_step(0)
+    if model is not None:          # the per-layer objects serve the per-call timings below: initialise them too
+        for l, lay in enumerate(layers):
+            lay.step(0, q_cur[l])
     torch.cuda.synchronize()
 
     graphs = {}
-    if not args.no_graph:
+    if launch == "graph":
         # capture one full-style and one partial-style step; the device-side seq_lens/tail_start
         # make a replay do the right thing at any later step.  Capturing advances seq_lens like a
         # real step would not (nothing runs during capture), so no state is disturbed.
@@ -281,7 +297,7 @@ def main():
         "config": {"workload": w.name, "layers": n_layers, "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv,
                    "head_dim": D, "context": L0, "k_small": w.k_small, "stride": w.stride, "pool_w": w.pool_w,
                    "schedule": "dynamic" if w.dynamic else "fixed", "full_steps": n_full,
-                   "partial_steps": args.steps - n_full, "launch": "eager" if args.no_graph else "hip_graph"},
+                   "partial_steps": args.steps - n_full, "launch": {"graph": "hip_graph", "native": "rk_decode_step", "eager": "eager"}[launch]},
         "step_us_per_layer": {k: round(v, 2) for k, v in med.items()},
         "call_us_per_layer": {k: round(v, 2) for k, v in klass.items()},
         "full_over_partial": round(klass["full_attn"] / klass["partial_attn"], 2),

@@ -246,6 +246,53 @@ int rk_calibration_copy(void* dst, const void* src, size_t bytes, void* stream);
 int rk_mark_refresh(const rk_geom* geom, const int32_t* seq_lens, int32_t* tail_start,
                     const int32_t* pred, int32_t pred_val, void* stream);
 
+/* ---- one decode step of a whole model --------------------------------------------------- */
+
+/* Per-layer state of the method: everything is caller-owned device memory. */
+typedef struct rk_layer_state {
+    rk_kv full;            /* C_f of the layer                                                  */
+    rk_kv small;           /* C_p of the layer, capacity >= k                                   */
+    int32_t* idx;          /* int32 [batch, n_kv_heads, k]: the selection of the last refresh   */
+    int32_t* tail_start;   /* int32 [batch]: seq_lens at the last refresh                       */
+    float* q_ref;          /* fp32 [batch, head_dim]: reference query of the trigger (dynamic)  */
+    float* sim;            /* fp32 [batch]: last similarity (dynamic)                           */
+    int32_t* need_full;    /* int32 [batch]: last decision of the trigger (dynamic)             */
+    int32_t* n_full;       /* int32 [batch] or NULL: incremented at every refresh of (layer,
+                              sequence): step count / n_full is the effective stride of App.
+                              "Effective stride per layer"                                      */
+} rk_layer_state;
+
+/* The schedule of Section 2.2 and the two variants of the step. */
+typedef struct rk_schedule {
+    int32_t k;             /* small-cache size K                                                */
+    int32_t pool_w;        /* max-pool window of the selection (7 in the paper)                 */
+    int32_t stride;        /* S (fixed schedule) or the QC stride (dynamic); <= 0: never after
+                              the initialisation                                                */
+    int32_t dynamic;       /* 1: the query-similarity trigger decides on every stride-th step   */
+    float   threshold;     /* s: full step iff similarity <= s                                  */
+    int32_t fixed_size;    /* 1: partial steps use rk_partial_attn_fixed (evict the lowest)     */
+    int32_t scores_only;   /* 1: refreshes use rk_score_select + rk_partial_attn (Section 4.3)  */
+} rk_schedule;
+
+#define RK_STEP_FULL    1  /* every layer took a full step                                      */
+#define RK_STEP_PARTIAL 2  /* every layer took a partial step                                   */
+#define RK_STEP_BOTH    3  /* trigger test step: both branches enqueued, predicated per sequence */
+
+/* Attention of decode step t (t = 0: the prefill-equivalent initialisation; steps count from 1)
+ * for n_layers layers, enqueued on `stream` in layer order: exactly the calls a caller would
+ * issue layer by layer (rk_query_sim, rk_full_attn_select or rk_score_select,
+ * rk_gather_small_kv, rk_partial_attn / rk_partial_attn_fixed), with the trigger's device
+ * predicate on test steps.  `layers`, `q` and `out` are HOST arrays of n_layers entries
+ * (q[l], out[l]: device bf16 [batch, n_q_heads, head_dim]); they are read during the call only.
+ * seq_lens (shared by the layers) must already count the current token, whose K/V rows the
+ * caller has written to every layer's C_f.  max_len / max_recent: host bounds of seq_lens and
+ * of seq_lens - tail_start.  Returns RK_STEP_* (> 0) or a negative rk_status; on an error in
+ * layer l the layers before it have been enqueued. */
+int rk_decode_step(const rk_geom* geom, const rk_schedule* sched, int32_t t, int32_t n_layers,
+                   const rk_layer_state* layers, const void* const* q, void* const* out,
+                   const int32_t* seq_lens, int32_t max_len, int32_t max_recent,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

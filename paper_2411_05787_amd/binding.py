@@ -16,7 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "librefreshkv.so")
 
 EXPORTS = ["rk_version", "rk_status_string", "rk_workspace_bytes", "rk_workspace_init",
-           "rk_full_attn", "rk_full_attn_scores", "rk_topk_select", "rk_full_attn_select", "rk_score_select", "rk_gather_small_kv", "rk_partial_attn", "rk_partial_attn_fixed",
+           "rk_full_attn", "rk_full_attn_scores", "rk_topk_select", "rk_full_attn_select", "rk_score_select", "rk_gather_small_kv", "rk_partial_attn", "rk_partial_attn_fixed", "rk_decode_step",
            "rk_query_sim", "rk_mark_refresh", "rk_calibration_copy"]
 
 RK_AGG_MAX = 0
@@ -36,6 +36,19 @@ class _Geom(C.Structure):
 class _Kv(C.Structure):
     _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("stride_b", C.c_int64), ("stride_h", C.c_int64),
                 ("capacity", C.c_int64)]
+
+
+class _LayerState(C.Structure):
+    _fields_ = [("full", _Kv), ("small", _Kv), ("idx", C.c_void_p), ("tail_start", C.c_void_p),
+                ("q_ref", C.c_void_p), ("sim", C.c_void_p), ("need_full", C.c_void_p), ("n_full", C.c_void_p)]
+
+
+class _Schedule(C.Structure):
+    _fields_ = [("k", C.c_int32), ("pool_w", C.c_int32), ("stride", C.c_int32), ("dynamic", C.c_int32),
+                ("threshold", C.c_float), ("fixed_size", C.c_int32), ("scores_only", C.c_int32)]
+
+
+STEP_KINDS = {1: "full", 2: "partial", 3: "both"}
 
 
 def _load(path: str = LIB_PATH) -> C.CDLL:
@@ -70,6 +83,9 @@ def _load(path: str = LIB_PATH) -> C.CDLL:
     l.rk_partial_attn_fixed.restype = C.c_int
     l.rk_partial_attn_fixed.argtypes = [G, P, _Kv, I32, _Kv, P, P, I32, P, P, I32, P, SZ, P]
     l.rk_query_sim.restype = C.c_int
+    l.rk_decode_step.restype = C.c_int
+    l.rk_decode_step.argtypes = [G, C.POINTER(_Schedule), I32, I32, C.POINTER(_LayerState), C.POINTER(C.c_void_p),
+                                 C.POINTER(C.c_void_p), P, I32, I32, P, SZ, P]
     l.rk_query_sim.argtypes = [G, P, P, C.c_float, I32, P, P, P]
     l.rk_calibration_copy.restype = C.c_int
     l.rk_calibration_copy.argtypes = [P, P, SZ, P]
@@ -303,6 +319,32 @@ def rk_partial_attn_fixed(geom: Geom, q, small_K, small_V, k: int, K, V, tail_st
         int(max_recent), _dev(out, torch.bfloat16, "out", (B, Hq, D)),
         _dev(pred, torch.int32, "pred", (B,), optional=True), int(pred_val),
         workspace.ptr, workspace.nbytes, _stream(stream)))
+
+
+def layer_state(geom: Geom, K, V, small_K, small_V, idx, tail_start, q_ref=None, sim=None, need_full=None,
+                n_full=None, k: int = 0) -> _LayerState:
+    """One entry of rk_decode_step's `layers` array (the tensors must outlive its use)."""
+    B, Hkv, D = geom.batch, geom.n_kv_heads, geom.head_dim
+    return _LayerState(_kv(geom, K, V, "full"), _kv(geom, small_K, small_V, "small", min_rows=k),
+                       _dev(idx, torch.int32, "idx", (B, Hkv, k) if k else None),
+                       _dev(tail_start, torch.int32, "tail_start", (B,)),
+                       _dev(q_ref, torch.float32, "q_ref", (B, D), optional=True),
+                       _dev(sim, torch.float32, "sim", (B,), optional=True),
+                       _dev(need_full, torch.int32, "need_full", (B,), optional=True),
+                       _dev(n_full, torch.int32, "n_full", (B,), optional=True))
+
+
+def rk_decode_step(geom: Geom, sched: _Schedule, t: int, layers, q_ptrs, out_ptrs, seq_lens, max_len: int,
+                   max_recent: int, workspace: Workspace = None, stream=None) -> str:
+    """layers: ctypes array of _LayerState; q_ptrs / out_ptrs: ctypes arrays of device pointers
+    (one per layer).  Returns "full", "partial" or "both"."""
+    n = len(layers)
+    rc = lib.rk_decode_step(C.byref(geom.c()), C.byref(sched), int(t), n, layers, q_ptrs, out_ptrs,
+                            _dev(seq_lens, torch.int32, "seq_lens", (geom.batch,)), int(max_len), int(max_recent),
+                            workspace.ptr, workspace.nbytes, _stream(stream))
+    if rc <= 0:
+        _check("rk_decode_step", rc if rc < 0 else -1)
+    return STEP_KINDS[rc]
 
 
 def rk_query_sim(geom: Geom, q, q_ref, threshold: float, force_full: bool, sim, need_full, stream=None) -> None:

@@ -13,10 +13,13 @@ void gather_rows_kernel(const uint16_t* __restrict__ fk, const uint16_t* __restr
                         uint16_t* __restrict__ sk, uint16_t* __restrict__ sv, int64_t ss_b, int64_t ss_h,
                         const int32_t* __restrict__ idx, int32_t k, int32_t Hkv, int32_t full_cap,
                         const int32_t* __restrict__ seq_lens, int32_t* __restrict__ tail_start,
-                        const int32_t* pred, int32_t pred_val) {
+                        int32_t* __restrict__ n_refresh, const int32_t* pred, int32_t pred_val) {
     const int g = blockIdx.y, b = blockIdx.z;
     if (pred != nullptr && pred[b] != pred_val) return;
-    if (tail_start != nullptr && blockIdx.x == 0 && g == 0 && threadIdx.x == 0) tail_start[b] = seq_lens[b];
+    if (blockIdx.x == 0 && g == 0 && threadIdx.x == 0) {
+        if (tail_start != nullptr) tail_start[b] = seq_lens[b];
+        if (n_refresh != nullptr) n_refresh[b] += 1;       // one writer per sequence and launch
+    }
     const int i = blockIdx.x * kGatherRows + (threadIdx.x >> 4);
     if (i >= k) return;
     const int j = idx[((int64_t)b * Hkv + g) * k + i];
@@ -32,11 +35,10 @@ void gather_rows_kernel(const uint16_t* __restrict__ fk, const uint16_t* __restr
 
 }  // namespace rk
 
-using namespace rk;
-
-extern "C" int rk_gather_small_kv(const rk_geom* geom, rk_kv full, const int32_t* idx, int32_t k,
-                                  rk_kv small, const int32_t* seq_lens, int32_t* tail_start,
-                                  const int32_t* pred, int32_t pred_val, void* stream) {
+namespace rk {
+int gather_stage(const rk_geom* geom, rk_kv full, const int32_t* idx, int32_t k, rk_kv small,
+                 const int32_t* seq_lens, int32_t* tail_start, int32_t* n_refresh,
+                 const int32_t* pred, int32_t pred_val, hipStream_t stream) {
     int rc = check_geom(geom);
     if (rc != RK_OK) return rc;
     if (!idx || k <= 0 || (tail_start && !seq_lens)) return RK_ERR_INVALID_ARG;
@@ -44,9 +46,18 @@ extern "C" int rk_gather_small_kv(const rk_geom* geom, rk_kv full, const int32_t
     if ((rc = check_kv(small)) != RK_OK) return rc;
     if (small.capacity < k) return RK_ERR_INVALID_ARG;
     dim3 grid((k + kGatherRows - 1) / kGatherRows, geom->n_kv_heads, geom->batch);
-    hipLaunchKernelGGL(gather_rows_kernel, grid, dim3(256), 0, (hipStream_t)stream,
+    hipLaunchKernelGGL(gather_rows_kernel, grid, dim3(256), 0, stream,
                        (const uint16_t*)full.k, (const uint16_t*)full.v, full.stride_b, full.stride_h,
                        (uint16_t*)small.k, (uint16_t*)small.v, small.stride_b, small.stride_h,
-                       idx, k, geom->n_kv_heads, (int32_t)full.capacity, seq_lens, tail_start, pred, pred_val);
+                       idx, k, geom->n_kv_heads, (int32_t)full.capacity, seq_lens, tail_start, n_refresh, pred, pred_val);
     return launch_status();
+}
+}  // namespace rk
+
+using namespace rk;
+
+extern "C" int rk_gather_small_kv(const rk_geom* geom, rk_kv full, const int32_t* idx, int32_t k,
+                                  rk_kv small, const int32_t* seq_lens, int32_t* tail_start,
+                                  const int32_t* pred, int32_t pred_val, void* stream) {
+    return gather_stage(geom, full, idx, k, small, seq_lens, tail_start, nullptr, pred, pred_val, (hipStream_t)stream);
 }

@@ -160,6 +160,11 @@ __attribute__((visibility("hidden")))
 int full_attn_stage(const rk_geom* geom, const void* q, rk_kv full, const int32_t* seq_lens, int32_t max_len,
                     void* out, float* weights, int64_t w_stride, float* lse, const int32_t* pred, int32_t pred_val,
                     const Workspace& ws, hipStream_t st, bool scores_only, int pool_half, bool no_v);
+//   gather_stage: rk_gather_small_kv plus an optional per-sequence count of refreshes.
+__attribute__((visibility("hidden")))
+int gather_stage(const rk_geom* geom, rk_kv full, const int32_t* idx, int32_t k, rk_kv small,
+                 const int32_t* seq_lens, int32_t* tail_start, int32_t* n_refresh,
+                 const int32_t* pred, int32_t pred_val, hipStream_t stream);
 __attribute__((visibility("hidden")))
 int select_stage(const rk_geom* geom, const int32_t* seq_lens, int32_t max_len, int32_t k, int32_t* idx,
                  float* sel_scores, const int32_t* pred, int32_t pred_val, const Workspace& ws, hipStream_t st);

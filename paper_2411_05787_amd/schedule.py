@@ -117,3 +117,75 @@ class RefreshKVLayer:
             return "both"
         self._partial(q, out, stream=stream)
         return "partial"
+
+
+class RefreshKVModel:
+    """All attention layers of a model stepped by one library call (``rk_decode_step``).
+
+    Same schedule and state as :class:`RefreshKVLayer`, per layer; the per-layer pointers are
+    packed once, so a decode step costs one foreign call whatever the number of layers.
+    ``n_full[l]`` counts the refreshes of every sequence in layer l on the GPU (effective stride
+    of a layer = steps / refreshes).
+    """
+
+    def __init__(self, geom: rk.Geom, kv, seq_lens: torch.Tensor, max_len: int, k_small: int, stride: int,
+                 pool_w: int = 7, dynamic: bool = False, threshold: float = 0.0, evict_lowest: bool = False,
+                 scores_only_refresh: bool = False, workspace: Optional[rk.Workspace] = None):
+        """kv: list of (K, V) per layer, bf16 [B, Hkv, capacity, D]; seq_lens int32 [B] on the GPU,
+        shared by the layers (every layer holds the same tokens)."""
+        import ctypes as C
+        from .binding import _Schedule, _LayerState, layer_state
+        dev = kv[0][0].device
+        B, Hq, Hkv, D = geom.batch, geom.n_q_heads, geom.n_kv_heads, geom.head_dim
+        n = len(kv)
+        self.geom, self.kv, self.seq_lens, self.n_layers = geom, kv, seq_lens, n
+        self.capacity = kv[0][0].shape[2]
+        self.max_len, self.k_small, self.stride = int(max_len), int(k_small), int(stride)
+        self.ws = workspace if workspace is not None else rk.Workspace(geom, self.capacity, k_small, device=dev)
+        self.sched = _Schedule(int(k_small), int(pool_w), int(stride), int(bool(dynamic)), float(threshold),
+                               int(bool(evict_lowest)), int(bool(scores_only_refresh)))
+        self.small_K = torch.zeros(n, B, Hkv, k_small, D, dtype=torch.bfloat16, device=dev)
+        self.small_V = torch.zeros(n, B, Hkv, k_small, D, dtype=torch.bfloat16, device=dev)
+        self.idx = torch.full((n, B, Hkv, k_small), -1, dtype=torch.int32, device=dev)
+        self.q_ref = torch.zeros(n, B, D, dtype=torch.float32, device=dev)
+        self.sim = torch.zeros(n, B, dtype=torch.float32, device=dev)
+        self.need_full = torch.zeros(n, B, dtype=torch.int32, device=dev)
+        self.tail_start = seq_lens.clone().unsqueeze(0).repeat(n, 1).contiguous()
+        self.n_full = torch.zeros(n, B, dtype=torch.int32, device=dev)
+        self.out = torch.empty(n, B, Hq, D, dtype=torch.bfloat16, device=dev)
+        self._layers = (_LayerState * n)(*[
+            layer_state(geom, kv[l][0], kv[l][1], self.small_K[l], self.small_V[l], self.idx[l], self.tail_start[l],
+                        self.q_ref[l], self.sim[l], self.need_full[l], self.n_full[l], k=k_small) for l in range(n)])
+        self._out_ptrs = (C.c_void_p * n)(*[self.out[l].data_ptr() for l in range(n)])
+        self._q_ptrs = (C.c_void_p * n)()
+        self.recent_bound = 0
+        self._static = False
+
+    def use_static_bounds(self, max_len: int, max_recent: int) -> None:
+        if max_len > self.capacity:
+            raise ValueError("max_len exceeds the cache capacity")
+        self.max_len, self.recent_bound, self._static = int(max_len), int(max_recent), True
+
+    def advance(self) -> None:
+        """The caller has appended one token to every layer's full cache and to seq_lens."""
+        if not self._static:
+            if self.max_len + 1 > self.capacity:
+                raise ValueError("KV cache capacity exceeded")
+            self.max_len += 1
+            self.recent_bound += 1
+
+    def step(self, t: int, q: torch.Tensor, stream=None) -> str:
+        """q: bf16 [n_layers, B, Hq, D] on the GPU (the query of the current token in every layer).
+        Outputs land in ``self.out[l]``."""
+        n, g = self.n_layers, self.geom
+        if not q.is_cuda or q.dtype != torch.bfloat16 or not q.is_contiguous() or \
+                tuple(q.shape) != (n, g.batch, g.n_q_heads, g.head_dim):
+            raise ValueError("q must be a contiguous bf16 GPU tensor [n_layers, batch, n_q_heads, head_dim]")
+        base, step_bytes = q.data_ptr(), q.stride(0) * 2
+        for l in range(n):
+            self._q_ptrs[l] = base + l * step_bytes
+        kind = rk.rk_decode_step(g, self.sched, t, self._layers, self._q_ptrs, self._out_ptrs, self.seq_lens,
+                                 self.max_len, max(self.recent_bound, 1), workspace=self.ws, stream=stream)
+        if kind == "full" and not self._static:
+            self.recent_bound = 0
+        return kind

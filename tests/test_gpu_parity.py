@@ -487,12 +487,8 @@ def run_gpu_loop(rk, w: gen.Workload, layer: int, K, V, q_steps, new_k, new_v, l
                 kinds=kinds, K=gen.bf16_bits(Kd), V=gen.bf16_bits(Vd), lens=sl.cpu().numpy())
 
 
-def check_loop(rk, w: gen.Workload, evict_lowest=False, scores_only=False):
-    K, V = gen.make_kv(w, 0)
-    q = gen.make_queries(w, 0)
-    nk, nv = gen.make_new_rows(w, 0)
-    lens0 = gen.seq_lens(w)
-    got = run_gpu_loop(rk, w, 0, K, V, q, nk, nv, lens0, evict_lowest, scores_only)
+def compare_with_oracle(w: gen.Workload, layer: int, got, K, V, q, nk, nv, lens0, evict_lowest=False, scores_only=False):
+    """One layer's GPU run against the oracle's decode loop on the same inputs."""
     ref = oracle.decode_loop(gen.bf16_bits(q), gen.bf16_bits(K), gen.bf16_bits(V), gen.bf16_bits(nk),
                              gen.bf16_bits(nv), lens0.numpy(), w.scale, w.k_small, w.stride, pool_w=w.pool_w,
                              dynamic=w.dynamic, threshold=w.threshold, evict_lowest=evict_lowest,
@@ -521,9 +517,64 @@ def check_loop(rk, w: gen.Workload, evict_lowest=False, scores_only=False):
             for g in range(w.n_kv_heads):
                 P, n = last_full_scores[(b, g)]
                 n_diff += assert_idx_equivalent(got["idx"][t][b, g], ref["idx"][t][b, g], P, n, w.k_small,
-                                                "t=%d b=%d g=%d" % (t, b, g))
-        assert_out_close(got["outs"][t], ref["outs"][t], "%s t=%d" % (w.name, t))
+                                                "layer %d t=%d b=%d g=%d" % (layer, t, b, g))
+        assert_out_close(got["outs"][t], ref["outs"][t], "%s layer %d t=%d" % (w.name, layer, t))
+    return ref, n_diff
+
+
+def check_loop(rk, w: gen.Workload, evict_lowest=False, scores_only=False):
+    K, V = gen.make_kv(w, 0)
+    q = gen.make_queries(w, 0)
+    nk, nv = gen.make_new_rows(w, 0)
+    lens0 = gen.seq_lens(w)
+    got = run_gpu_loop(rk, w, 0, K, V, q, nk, nv, lens0, evict_lowest, scores_only)
+    ref, n_diff = compare_with_oracle(w, 0, got, K, V, q, nk, nv, lens0, evict_lowest, scores_only)
     return got, ref, n_diff
+
+
+def check_model_loop(rk, w: gen.Workload, n_layers: int, evict_lowest=False, scores_only=False):
+    """The same schedule through rk_decode_step: all layers of a step in one call."""
+    dev = "cuda"
+    geom = rk.Geom(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.scale)
+    lens0 = gen.seq_lens(w)
+    data = [(gen.make_kv(w, l), gen.make_queries(w, l), gen.make_new_rows(w, l)) for l in range(n_layers)]
+    kv = [(d[0][0].to(dev).clone(), d[0][1].to(dev).clone()) for d in data]
+    sl = lens0.to(dev).clone()
+    model = rk.RefreshKVModel(geom, kv, sl, int(lens0.max()), w.k_small, w.stride, pool_w=w.pool_w, dynamic=w.dynamic,
+                              threshold=w.threshold, evict_lowest=evict_lowest, scores_only_refresh=scores_only)
+    q_all = torch.stack([d[1] for d in data], dim=1).to(dev).contiguous()            # [T+1, n_layers, B, Hq, D]
+    nk_all = [d[2][0].to(dev) for d in data]
+    nv_all = [d[2][1].to(dev) for d in data]
+    B, Hkv, D = w.batch, w.n_kv_heads, w.head_dim
+    outs, idxs, needs, sims, kinds = [], [], [], [], []
+    for t in range(w.n_steps + 1):
+        if t >= 1:
+            pos = sl.to(torch.int64)[:, None, None, None].expand(B, Hkv, 1, D)
+            for l in range(n_layers):
+                kv[l][0].scatter_(2, pos, nk_all[l][t - 1][:, :, None, :])
+                kv[l][1].scatter_(2, pos, nv_all[l][t - 1][:, :, None, :])
+            sl += 1
+            model.advance()
+        kinds.append(model.step(t, q_all[t]))
+        outs.append(model.out.clone()); idxs.append(model.idx.clone())
+        needs.append(model.need_full.clone()); sims.append(model.sim.clone())
+    torch.cuda.synchronize()
+    n_full = model.n_full.cpu().numpy()
+    refs = []
+    for l in range(n_layers):
+        got = dict(outs=np.stack([gen.bf16_bits(o[l]) for o in outs]), idx=[i[l].cpu().numpy() for i in idxs],
+                   need=np.stack([n[l].cpu().numpy() for n in needs]), sims=np.stack([s_[l].cpu().numpy() for s_ in sims]),
+                   kinds=kinds, K=gen.bf16_bits(kv[l][0]), V=gen.bf16_bits(kv[l][1]), lens=sl.cpu().numpy())
+        (K, V), q, (nk, nv) = data[l]
+        ref, _ = compare_with_oracle(w, l, got, K, V, q, nk, nv, lens0, evict_lowest, scores_only)
+        # refresh counters kept on the GPU: wherever no decision sat on the threshold
+        near = np.zeros(w.batch, dtype=bool)
+        if w.dynamic:
+            sims_ref = ref["sims"]
+            near = (np.abs(np.nan_to_num(sims_ref, nan=9.0) - w.threshold) <= 1e-5).any(axis=0)
+        assert (n_full[l][~near] == ref["full"].sum(axis=0)[~near]).all(), "refresh count of layer %d" % l
+        refs.append(ref)
+    return kinds, n_full, refs
 
 
 def test_score_select_matches_oracle(rk):
@@ -576,6 +627,24 @@ def test_loop_scores_only_refresh(rk):
     say("loop, scores-only refresh, dynamic", wq)
     got, ref, _ = check_loop(rk, wq, scores_only=True)
     assert "both" in got["kinds"]
+
+
+def test_decode_step_driver_fixed_and_dynamic(rk):
+    """rk_decode_step: three layers per call, fixed stride and the trigger, against the oracle."""
+    w = gen.shrink(gen.WORKLOADS["cfg1_llama_2k"], n_steps=9)
+    say("decode_step driver, fixed stride", w.name)
+    kinds, n_full, _ = check_model_loop(rk, w, 3)
+    assert kinds[:5] == ["full", "partial", "partial", "partial", "full"]
+    assert (n_full == 3).all()                       # t = 0, 4, 8
+    wq = gen.shrink(gen.WORKLOADS["cfg3_qwen_64k_dynamic"], context=3000, k_small=256, n_steps=25, batch=2)
+    say("decode_step driver, dynamic, fixed-size small cache", wq.name)
+    kinds, n_full, refs = check_model_loop(rk, wq, 3, evict_lowest=True)
+    assert kinds.count("both") == 5 and kinds[0] == "full"
+    fired = np.stack([r["full"][1:].sum(axis=0) for r in refs])
+    say("  refreshes per (layer, sequence) after the initialisation:", fired.tolist())
+    assert fired.min() < fired.max() or fired.max() < 5, "layers decide on their own"
+    say("decode_step driver, scores-only refresh")
+    check_model_loop(rk, gen.shrink(gen.WORKLOADS["cfg1_llama_2k"], n_steps=5), 2, scores_only=True)
 
 
 def test_loop_cfg1_every_step(rk):

@@ -100,18 +100,32 @@ def attn_scores(q_bits, k_bits, seq_lens, scale: float) -> Tuple[np.ndarray, np.
     return weights, lse
 
 
-def pooled_group_scores(weights_row_group: np.ndarray, pool_w: int) -> np.ndarray:
+def pooled_group_scores(weights_row_group: np.ndarray, pool_w: int, agg: str = "max") -> np.ndarray:
     """Scores that rank the tokens of one (sequence, KV head).
 
     weights_row_group [G, n]: the attention scores of the G query heads of the group.
-    1. Aggregate across the group by max (Section 2.2 footnote on GQA; Appendix A.3).
+    1. Aggregate across the group by max (Section 2.2 footnote on GQA).  Appendix A.3 also
+       tries the mean over the group and the score of the group's first head: ``agg`` =
+       "max" | "mean" | "first".  The mean is taken in the dtype given (fp32 at the
+       boundary), heads added in order, then divided by G: the decision is taken in the
+       kernel's precision.
     2. Max-pool over neighbouring tokens, window ``pool_w`` centred on each token,
        stride 1, window clipped at both ends (Section 2.2 "Prefilling stage"; kernel
        size 7 in Appendix A.1 "Baseline Settings").  pool_w = 1 leaves step 1 as is.
     """
     if pool_w < 1 or pool_w % 2 == 0:
         raise ValueError("pool_w must be odd and >= 1")
-    A = weights_row_group.max(axis=0)
+    if agg == "max":
+        A = weights_row_group.max(axis=0)
+    elif agg == "first":
+        A = weights_row_group[0].copy()
+    elif agg == "mean":
+        acc = weights_row_group[0].copy()
+        for h in range(1, weights_row_group.shape[0]):
+            acc = acc + weights_row_group[h]
+        A = acc / weights_row_group.dtype.type(weights_row_group.shape[0])
+    else:
+        raise ValueError("agg must be max, mean or first")
     half = (pool_w - 1) // 2
     if half == 0 or A.shape[0] == 0:
         return A.copy()
@@ -121,7 +135,7 @@ def pooled_group_scores(weights_row_group: np.ndarray, pool_w: int) -> np.ndarra
     return windows.max(axis=1)
 
 
-def topk_select(weights, seq_lens, n_kv_heads: int, k: int, pool_w: int = 7
+def topk_select(weights, seq_lens, n_kv_heads: int, k: int, pool_w: int = 7, agg: str = "max"
                 ) -> Tuple[np.ndarray, np.ndarray]:
     """Pick the K tokens of each (sequence, KV head) that refresh the small cache.
 
@@ -129,7 +143,7 @@ def topk_select(weights, seq_lens, n_kv_heads: int, k: int, pool_w: int = 7
     group-aggregated) attention score of the last full step.  Order of the result:
     score descending, equal scores by ascending position (the paper is silent on ties;
     pooling makes them common).  Comparisons are done on the values as given, in the
-    dtype given: no arithmetic is applied to them.
+    dtype given: no arithmetic is applied to them (except the mean of ``agg`` = "mean").
 
     weights [B, Hq, >=max len]; returns (idx int32 [B,Hkv,k], scores [B,Hkv,k] of
     weights' dtype); slots beyond min(k, seq_lens[b]) hold -1 / 0.
@@ -143,7 +157,7 @@ def topk_select(weights, seq_lens, n_kv_heads: int, k: int, pool_w: int = 7
         n = int(seq_lens[b])
         kk = min(k, n)
         for g in range(n_kv_heads):
-            P = pooled_group_scores(w[b, g * G:(g + 1) * G, :n], pool_w)
+            P = pooled_group_scores(w[b, g * G:(g + 1) * G, :n], pool_w, agg)
             # stable sort on the negated score: descending score, ascending position on ties
             order = np.argsort(-P, kind="stable")
             idx[b, g, :kk] = order[:kk]

@@ -205,6 +205,33 @@ def test_topk_group_max_not_mean_or_first():
     assert oracle.topk_select(w, [4], 2, 1, 1)[0][0, :, 0].tolist() == [0, 3]
 
 
+def test_topk_mean_and_first_aggregation_match_pure_python():
+    """Appendix A.3: mean over the group and first head of the group instead of the max."""
+    rng = np.random.default_rng(44)
+    G, n, k = 3, 40, 9
+    w = rng.random((1, 2 * G, n)).astype(np.float64)
+    for agg in ("mean", "first"):
+        for pool_w in (1, 5):
+            idx, sel = oracle.topk_select(w, [n], 2, k, pool_w, agg=agg)
+            for g in range(2):
+                rows = [w[0, g * G + h].tolist() for h in range(G)]
+                A = [sum(r[j] for r in rows) / G if agg == "mean" else rows[0][j] for j in range(n)]
+                half = (pool_w - 1) // 2
+                P = [max(A[max(0, j - half):min(n, j + half + 1)]) for j in range(n)]
+                order = sorted(range(n), key=lambda j: (-P[j], j))[:k]
+                assert idx[0, g].tolist() == order
+                assert np.allclose(sel[0, g], [P[j] for j in order], rtol=1e-15)
+    # the three aggregations differ where they should: one head dominates one position
+    w2 = np.full((1, 2, 6), 0.1); w2[0, 1, 4] = 0.9                   # only the second head sees position 4
+    assert oracle.topk_select(w2, [6], 1, 1, 1, agg="max")[0][0, 0, 0] == 4
+    assert oracle.topk_select(w2, [6], 1, 1, 1, agg="mean")[0][0, 0, 0] == 4
+    assert oracle.topk_select(w2, [6], 1, 1, 1, agg="first")[0][0, 0, 0] == 0
+    # fp32 in, fp32 arithmetic: the mean is the fp32 sum in head order divided in fp32
+    w3 = np.array([[[1.0], [2.0 ** -24], [2.0 ** -24]]], dtype=np.float32)
+    s3 = oracle.topk_select(w3, [1], 1, 1, 1, agg="mean")[1]
+    assert s3.dtype == np.float32 and s3[0, 0, 0] == np.float32(1.0) / np.float32(3.0)
+
+
 def test_topk_selected_dominate_unselected():
     w = gen.make_weights(1, 4, 500, seed=5).numpy()
     idx, sel = oracle.topk_select(w, [500], 1, 64, 7)

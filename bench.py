@@ -161,6 +161,7 @@ def main():
     for (a, b), k in zip(ev, kinds):
         per_kind.setdefault(k, []).append(a.elapsed_time(b) * 1e3)
     med = {k: float(np.median(v)) / n_layers for k, v in per_kind.items()}      # us per layer
+    spread = {k: [round(float(np.percentile(v, q)) / n_layers, 2) for q in (10, 90)] for k, v in per_kind.items()}
     final_len = int(seq_lens.max().item())
     assert final_len == int(lens0.max()) + T, (final_len, int(lens0.max()) + T)
 
@@ -299,6 +300,7 @@ def main():
                    "schedule": "dynamic" if w.dynamic else "fixed", "full_steps": n_full,
                    "partial_steps": args.steps - n_full, "launch": {"graph": "hip_graph", "native": "rk_decode_step", "eager": "eager"}[launch]},
         "step_us_per_layer": {k: round(v, 2) for k, v in med.items()},
+        "step_us_per_layer_p10_p90": spread,
         "call_us_per_layer": {k: round(v, 2) for k, v in klass.items()},
         "full_over_partial": round(klass["full_attn"] / klass["partial_attn"], 2),
         "full_attn_GBps": round((bytes_kv + bytes_w) / (klass["full_attn"] * 1e-6) / 1e9, 1),

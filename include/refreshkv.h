@@ -55,12 +55,14 @@ extern "C" {
 typedef enum rk_status {
     RK_OK = 0,
     RK_ERR_INVALID_ARG = -1,   /* NULL pointer, non-positive size, misaligned pointer/stride  */
-    RK_ERR_UNSUPPORTED = -2,   /* head_dim != 128, G > 8, k too large, aggregation != max ... */
+    RK_ERR_UNSUPPORTED = -2,   /* head_dim != 128, G > 8, k too large, unknown aggregation ... */
     RK_ERR_WORKSPACE   = -3,   /* workspace NULL, misaligned or smaller than rk_workspace_bytes */
     RK_ERR_HIP         = -4    /* a HIP runtime call failed (launch error)                    */
 } rk_status;
 
 #define RK_AGG_MAX 0           /* aggregation across the query heads of a GQA group: max      */
+#define RK_AGG_MEAN 1          /* ... mean (heads added in order in fp32, then divided by G)  */
+#define RK_AGG_FIRST 2         /* ... the score of the group's first head (Appendix A.3)      */
 
 #define RK_HEAD_DIM 128
 #define RK_MAX_GROUP 8
@@ -144,7 +146,8 @@ int rk_full_attn_scores(const rk_geom* geom, const void* q, rk_kv full,
  *                        equal P by ascending position;  idx[b,g,k' .. k) = -1
  *     sel_scores[b,g,i] = P[idx[b,g,i]] (0 where idx is -1), when sel_scores is not NULL
  *   weights must be non-negative and free of NaN (softmax output).  pool_w odd, 1..63
- *   (7 in the paper, 1 = no pooling).  agg must be RK_AGG_MAX.  1 <= k <= RK_MAX_K.
+ *   (7 in the paper, 1 = no pooling).  agg: RK_AGG_MAX (the method's choice; then A is the max
+ *   above), RK_AGG_MEAN or RK_AGG_FIRST (the alternatives of Appendix A.3).  1 <= k <= RK_MAX_K.
  *   idx int32 [batch, n_kv_heads, k]; sel_scores fp32 of the same shape or NULL. */
 int rk_topk_select(const rk_geom* geom, const float* weights, int64_t w_stride,
                    const int32_t* seq_lens, int32_t max_len,

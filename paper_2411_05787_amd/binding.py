@@ -19,7 +19,7 @@ EXPORTS = ["rk_version", "rk_status_string", "rk_workspace_bytes", "rk_workspace
            "rk_full_attn", "rk_full_attn_scores", "rk_topk_select", "rk_full_attn_select", "rk_score_select", "rk_gather_small_kv", "rk_partial_attn", "rk_partial_attn_fixed", "rk_decode_step",
            "rk_query_sim", "rk_mark_refresh", "rk_calibration_copy"]
 
-RK_AGG_MAX = 0
+RK_AGG_MAX, RK_AGG_MEAN, RK_AGG_FIRST = 0, 1, 2
 
 
 class RkError(RuntimeError):

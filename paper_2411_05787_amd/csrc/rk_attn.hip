@@ -733,7 +733,7 @@ void merge_normalise_kernel(const AttnParams p, int G) {
 // of a neighbouring tile is always raw); weights are written only if the caller wants them.
 template <int G>
 __global__ __launch_bounds__(256)
-void finish_pool_kernel(const AttnParams p, const float* __restrict__ scores, int64_t s_stride, int half,
+void finish_pool_kernel(const AttnParams p, const float* __restrict__ scores, int64_t s_stride, int half, int agg,
                         float* __restrict__ pooled, int64_t pooled_stride, uint32_t* __restrict__ hist) {
     const int x = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
     if (p.pred != nullptr && p.pred[b] != p.pred_val) return;
@@ -832,8 +832,9 @@ void finish_pool_kernel(const AttnParams p, const float* __restrict__ scores, in
                 for (int gi = 0; gi < G; ++gi) {
                     const float wgt = weight_of(sc[gi][r], -sLse[gi][0], sLse[gi][1]);
                     if (core) p.weights[((int64_t)b * p.Hq + (int64_t)g * G + gi) * p.w_stride + j] = wgt;
-                    a = fmaxf(a, wgt);
+                    a = aggregate(a, wgt, gi, agg);
                 }
+                if (agg == RK_AGG_MEAN) a = __fdiv_rn(a, (float)G);
             }
             sA[i] = a;
         }
@@ -861,10 +862,11 @@ void finish_pool_kernel(const AttnParams p, const float* __restrict__ scores, in
 }
 
 template <int G>
-static int launch_finish_pool(const AttnParams& p, int batch, int32_t max_len, const Workspace& ws, int half, hipStream_t st) {
+static int launch_finish_pool(const AttnParams& p, int batch, int32_t max_len, const Workspace& ws, int half, int agg,
+                              hipStream_t st) {
     dim3 grid((p.out != nullptr ? G : 0) + (max_len + kPoolTile - 1) / kPoolTile, p.Hkv, batch);
     const int64_t stride = pooled_row_stride(max_len);
-    hipLaunchKernelGGL((finish_pool_kernel<G>), grid, dim3(256), 0, st, p, ws.scores, stride, half, ws.pooled, stride, ws.hist);
+    hipLaunchKernelGGL((finish_pool_kernel<G>), grid, dim3(256), 0, st, p, ws.scores, stride, half, agg, ws.pooled, stride, ws.hist);
     return launch_status();
 }
 
@@ -904,7 +906,7 @@ static int launch_score_split(const AttnParams& p, int batch, int G, int nchunk_
 
 int full_attn_stage(const rk_geom* geom, const void* q, rk_kv full, const int32_t* seq_lens, int32_t max_len,
                     void* out, float* weights, int64_t w_stride, float* lse, const int32_t* pred, int32_t pred_val,
-                    const Workspace& ws, hipStream_t st, bool scores_only, int pool_half, bool no_v) {
+                    const Workspace& ws, hipStream_t st, bool scores_only, int pool_half, bool no_v, int agg) {
     const int G = geom->n_q_heads / geom->n_kv_heads;
     const bool fused = pool_half >= 0;
     const bool emit = weights != nullptr || fused;
@@ -938,14 +940,14 @@ int full_attn_stage(const rk_geom* geom, const void* q, rk_kv full, const int32_
     }
     p.weights = weights; p.w_stride = w_stride;          // where the finish writes weights, if anywhere
     switch (G) {
-        case 1: return launch_finish_pool<1>(p, geom->batch, max_len, ws, pool_half, st);
-        case 2: return launch_finish_pool<2>(p, geom->batch, max_len, ws, pool_half, st);
-        case 3: return launch_finish_pool<3>(p, geom->batch, max_len, ws, pool_half, st);
-        case 4: return launch_finish_pool<4>(p, geom->batch, max_len, ws, pool_half, st);
-        case 5: return launch_finish_pool<5>(p, geom->batch, max_len, ws, pool_half, st);
-        case 6: return launch_finish_pool<6>(p, geom->batch, max_len, ws, pool_half, st);
-        case 7: return launch_finish_pool<7>(p, geom->batch, max_len, ws, pool_half, st);
-        case 8: return launch_finish_pool<8>(p, geom->batch, max_len, ws, pool_half, st);
+        case 1: return launch_finish_pool<1>(p, geom->batch, max_len, ws, pool_half, agg, st);
+        case 2: return launch_finish_pool<2>(p, geom->batch, max_len, ws, pool_half, agg, st);
+        case 3: return launch_finish_pool<3>(p, geom->batch, max_len, ws, pool_half, agg, st);
+        case 4: return launch_finish_pool<4>(p, geom->batch, max_len, ws, pool_half, agg, st);
+        case 5: return launch_finish_pool<5>(p, geom->batch, max_len, ws, pool_half, agg, st);
+        case 6: return launch_finish_pool<6>(p, geom->batch, max_len, ws, pool_half, agg, st);
+        case 7: return launch_finish_pool<7>(p, geom->batch, max_len, ws, pool_half, agg, st);
+        case 8: return launch_finish_pool<8>(p, geom->batch, max_len, ws, pool_half, agg, st);
         default: return RK_ERR_UNSUPPORTED;
     }
 }
@@ -975,7 +977,7 @@ extern "C" int rk_full_attn(const rk_geom* geom, const void* q, rk_kv full,
     Workspace ws;
     if ((rc = check_workspace(geom, max_len, 0, workspace, workspace_bytes, &ws)) != RK_OK) return rc;
     return full_attn_stage(geom, q, full, seq_lens, max_len, out, weights, w_stride, lse, pred, pred_val,
-                           ws, (hipStream_t)stream, false, -1, false);
+                           ws, (hipStream_t)stream, false, -1, false, RK_AGG_MAX);
 }
 
 extern "C" int rk_full_attn_scores(const rk_geom* geom, const void* q, rk_kv full,
@@ -989,7 +991,7 @@ extern "C" int rk_full_attn_scores(const rk_geom* geom, const void* q, rk_kv ful
     Workspace ws;
     if ((rc = check_workspace(geom, max_len, 0, workspace, workspace_bytes, &ws)) != RK_OK) return rc;
     return full_attn_stage(geom, q, full, seq_lens, max_len, nullptr, scores, s_stride, nullptr, pred, pred_val,
-                           ws, (hipStream_t)stream, true, -1, false);
+                           ws, (hipStream_t)stream, true, -1, false, RK_AGG_MAX);
 }
 
 static int partial_attn_impl(const rk_geom* geom, const void* q, rk_kv small, int32_t n_sel, bool evict,

@@ -106,6 +106,16 @@ __device__ __forceinline__ uint32_t key_of(float x) {
 __device__ __forceinline__ float value_of(uint32_t k) {
     return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
 }
+// One step of the aggregation of the attention weights across the query heads of a GQA group
+// (Section 2.2 footnote: max; Appendix A.3 also tries the mean and the group's first head).
+// `acc` starts at -inf; head 0 always replaces it.  The mean is finished by a division by G.
+__device__ __forceinline__ float aggregate(float acc, float w, int head, int agg) {
+    if (head == 0) return w;
+    if (agg == 0) return fmaxf(acc, w);       // RK_AGG_MAX
+    if (agg == 1) return acc + w;             // RK_AGG_MEAN: heads added in order, in fp32
+    return acc;                               // RK_AGG_FIRST
+}
+
 // Orders LDS traffic of the lanes of one wavefront: what was written before is visible to
 // every lane after.  Lanes of a wavefront run in lockstep, so no hardware barrier is needed,
 // only the compiler and the LDS queue have to be told.

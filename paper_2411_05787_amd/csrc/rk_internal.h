@@ -159,7 +159,7 @@ static inline int launch_status() {
 __attribute__((visibility("hidden")))
 int full_attn_stage(const rk_geom* geom, const void* q, rk_kv full, const int32_t* seq_lens, int32_t max_len,
                     void* out, float* weights, int64_t w_stride, float* lse, const int32_t* pred, int32_t pred_val,
-                    const Workspace& ws, hipStream_t st, bool scores_only, int pool_half, bool no_v);
+                    const Workspace& ws, hipStream_t st, bool scores_only, int pool_half, bool no_v, int agg);
 //   gather_stage: rk_gather_small_kv plus an optional per-sequence count of refreshes.
 __attribute__((visibility("hidden")))
 int gather_stage(const rk_geom* geom, rk_kv full, const int32_t* idx, int32_t k, rk_kv small,

@@ -41,7 +41,7 @@ __device__ __forceinline__ uint64_t item_of(uint32_t key, int j) {
 
 __global__ __launch_bounds__(256)
 void pool_hist_kernel(const float* __restrict__ weights, int64_t w_stride, const int32_t* seq_lens,
-                      int32_t max_len, int32_t Hq, int32_t Hkv, int32_t G, int32_t half,
+                      int32_t max_len, int32_t Hq, int32_t Hkv, int32_t G, int32_t half, int32_t agg,
                       float* __restrict__ pooled, int64_t pooled_stride, uint32_t* __restrict__ hist,
                       const int32_t* pred, int32_t pred_val) {
     const int g = blockIdx.y, b = blockIdx.z;
@@ -58,8 +58,8 @@ void pool_hist_kernel(const float* __restrict__ weights, int64_t w_stride, const
         const int j = j0 - half + i;
         float a = -INFINITY;                     // outside [0, len): never wins a max
         if (j >= 0 && j < len) {
-            a = wg[j];
-            for (int gi = 1; gi < G; ++gi) a = fmaxf(a, wg[(int64_t)gi * w_stride + j]);
+            for (int gi = 0; gi < G; ++gi) a = aggregate(a, wg[(int64_t)gi * w_stride + j], gi, agg);
+            if (agg == RK_AGG_MEAN) a = __fdiv_rn(a, (float)G);
         }
         sA[i] = a;
     }
@@ -459,7 +459,7 @@ namespace rk {
 
 static int check_select_args(int32_t k, int32_t pool_w, int32_t agg) {
     if (pool_w < 1 || (pool_w & 1) == 0) return RK_ERR_INVALID_ARG;
-    if (pool_w > RK_MAX_POOL_W || k > RK_MAX_K || agg != RK_AGG_MAX) return RK_ERR_UNSUPPORTED;
+    if (pool_w > RK_MAX_POOL_W || k > RK_MAX_K || agg < RK_AGG_MAX || agg > RK_AGG_FIRST) return RK_ERR_UNSUPPORTED;
     return RK_OK;
 }
 
@@ -501,7 +501,7 @@ extern "C" int rk_topk_select(const rk_geom* geom, const float* weights, int64_t
     const int G = geom->n_q_heads / geom->n_kv_heads;
     dim3 pgrid((max_len + kPoolTile - 1) / kPoolTile, geom->n_kv_heads, geom->batch);
     hipLaunchKernelGGL(pool_hist_kernel, pgrid, dim3(256), 0, st, weights, w_stride, seq_lens, max_len,
-                       geom->n_q_heads, geom->n_kv_heads, G, (pool_w - 1) / 2, ws.pooled, pooled_row_stride(max_len), ws.hist,
+                       geom->n_q_heads, geom->n_kv_heads, G, (pool_w - 1) / 2, agg, ws.pooled, pooled_row_stride(max_len), ws.hist,
                        pred, pred_val);
     if ((rc = launch_status()) != RK_OK) return rc;
     return select_stage(geom, seq_lens, max_len, k, idx, sel_scores, pred, pred_val, ws, st);
@@ -525,7 +525,7 @@ extern "C" int rk_full_attn_select(const rk_geom* geom, const void* q, rk_kv ful
     if ((rc = check_workspace(geom, max_len, k, workspace, workspace_bytes, &ws)) != RK_OK) return rc;
     hipStream_t st = (hipStream_t)stream;
     rc = full_attn_stage(geom, q, full, seq_lens, max_len, out, weights, w_stride, lse, pred, pred_val, ws, st,
-                         false, (pool_w - 1) / 2, false);
+                         false, (pool_w - 1) / 2, false, agg);
     if (rc != RK_OK) return rc;
     return select_stage(geom, seq_lens, max_len, k, idx, sel_scores, pred, pred_val, ws, st);
 }
@@ -548,7 +548,7 @@ extern "C" int rk_score_select(const rk_geom* geom, const void* q, rk_kv full,
     if ((rc = check_workspace(geom, max_len, k, workspace, workspace_bytes, &ws)) != RK_OK) return rc;
     hipStream_t st = (hipStream_t)stream;
     rc = full_attn_stage(geom, q, full, seq_lens, max_len, nullptr, weights, w_stride, lse, pred, pred_val, ws, st,
-                         false, (pool_w - 1) / 2, true);
+                         false, (pool_w - 1) / 2, true, agg);
     if (rc != RK_OK) return rc;
     return select_stage(geom, seq_lens, max_len, k, idx, sel_scores, pred, pred_val, ws, st);
 }

@@ -280,6 +280,53 @@ def test_full_attn_select_predicate(rk):
             assert_idx_equivalent(idx[b, g].cpu().numpy(), i_ref[b, g], P, lens[b], k, "pred b=%d" % b)
 
 
+@pytest.mark.parametrize("agg", ["mean", "first"])
+def test_topk_select_other_aggregations_exact(rk, agg):
+    """Appendix A.3: mean over the group / first head of the group; same fp32 weights on both sides,
+    so the result is exact, the mean included (fp32 sum in head order, fp32 division)."""
+    code = {"mean": rk.RK_AGG_MEAN, "first": rk.RK_AGG_FIRST}[agg]
+    for name, B, Hq, Hkv, lens, k, pool_w, kind in [("g4", 2, 8, 2, [5000, 3777], 256, 7, "lognormal"),
+                                                     ("g7_ties", 1, 7, 1, [3000], 333, 7, "ties"),
+                                                     ("g3_pool1", 1, 6, 2, [1500], 100, 1, "lognormal")]:
+        say("topk", agg, name)
+        n = max(lens)
+        w = gen.make_weights(B, Hq, n, seed=len(name) * 7 + k, kind=kind)
+        geom = rk.Geom(B, Hq, Hkv, 128, 1.0)
+        ws = rk.Workspace(geom, n, k)
+        idx = torch.full((B, Hkv, k), -5, dtype=torch.int32, device="cuda")
+        sel = torch.full((B, Hkv, k), -5.0, dtype=torch.float32, device="cuda")
+        rk.rk_topk_select(geom, w.cuda(), torch.tensor(lens, dtype=torch.int32, device="cuda"), n, k, pool_w, idx,
+                          sel_scores=sel, agg=code, workspace=ws)
+        torch.cuda.synchronize()
+        i_ref, s_ref = oracle.topk_select(w.numpy(), lens, Hkv, k, pool_w, agg=agg)
+        assert (idx.cpu().numpy() == i_ref).all()
+        assert (sel.cpu().numpy() == s_ref).all()
+
+
+def test_full_attn_select_mean_aggregation(rk):
+    say("full_attn_select, mean aggregation")
+    B, Hq, Hkv, cap, k = 1, 8, 2, 2600, 128
+    lens = [2500]
+    q, K, V = rand_case(515, B, Hq, Hkv, cap)
+    scale = float(np.float32(1 / np.sqrt(128)))
+    geom = rk.Geom(B, Hq, Hkv, 128, scale)
+    ws = rk.Workspace(geom, cap, k)
+    out = torch.zeros(B, Hq, 128, dtype=torch.bfloat16, device="cuda")
+    idx = torch.full((B, Hkv, k), -5, dtype=torch.int32, device="cuda")
+    rk.rk_full_attn_select(geom, q.cuda(), K.cuda(), V.cuda(), torch.tensor(lens, dtype=torch.int32, device="cuda"),
+                           2500, out, k, 7, idx, agg=rk.RK_AGG_MEAN, workspace=ws)
+    torch.cuda.synchronize()
+    o_ref, w_ref, _ = oracle.full_attn(gen.bf16_bits(q), gen.bf16_bits(K), gen.bf16_bits(V), lens, scale)
+    w32 = w_ref.astype(np.float32)
+    i_ref, _ = oracle.topk_select(w32, lens, Hkv, k, 7, agg="mean")
+    assert_out_close(gen.bf16_bits(out), o_ref)
+    for g in range(Hkv):
+        P = oracle.pooled_group_scores(w32[0, g * 4:(g + 1) * 4, :2500], 7, "mean")
+        assert_idx_equivalent(idx[0, g].cpu().numpy(), i_ref[0, g], P, 2500, k, "g=%d" % g)
+    i_max, _ = oracle.topk_select(w32, lens, Hkv, k, 7)
+    assert (i_ref != i_max).any(), "the case should tell mean from max"
+
+
 def test_gather_bit_exact(rk):
     say("gather")
     B, Hkv, cap, k = 3, 4, 500, 77

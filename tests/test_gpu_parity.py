@@ -437,6 +437,36 @@ def test_partial_attn_fixed_size_per_sequence(rk):
         assert_out_close(got[sl], o_ref, "b=%d" % b)
 
 
+def test_streaming_llm_policy_through_partial_attn(rk):
+    """The StreamingLLM baseline of Appendix A.1 (4 sink tokens + K - 4 recent tokens) needs no kernel
+    of its own: the sinks are a 4-row small cache, the recent tokens the tail of the full cache."""
+    say("StreamingLLM policy on rk_partial_attn")
+    B, Hq, Hkv, k, sinks = 2, 32, 8, 512, 4
+    lens = [3000, 700]
+    cap = 3008
+    q, K, V = rand_case(612, B, Hq, Hkv, cap)
+    scale = float(np.float32(1 / np.sqrt(128)))
+    geom = rk.Geom(B, Hq, Hkv, 128, scale)
+    idx = torch.arange(sinks, dtype=torch.int32).repeat(B, Hkv, 1).cuda()
+    sK = torch.zeros(B, Hkv, sinks, 128, dtype=torch.bfloat16, device="cuda")
+    sV = torch.zeros_like(sK)
+    Kd, Vd = K.cuda(), V.cuda()
+    rk.rk_gather_small_kv(geom, Kd, Vd, idx, sinks, sK, sV)
+    sl = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    tail = sl - (k - sinks)                                   # the window slides with the sequence
+    ws = rk.Workspace(geom, cap, k)
+    out = torch.zeros(B, Hq, 128, dtype=torch.bfloat16, device="cuda")
+    rk.rk_partial_attn(geom, q.cuda(), sK, sV, sinks, Kd, Vd, tail, sl, k - sinks, out, workspace=ws)
+    torch.cuda.synchronize()
+    # reference: plain attention over rows {0..3} and the last k - 4 rows, from the oracle's full-attention step
+    got = gen.bf16_bits(out)
+    Kb, Vb, qb = gen.bf16_bits(K), gen.bf16_bits(V), gen.bf16_bits(q)
+    for b in range(B):
+        rows = list(range(sinks)) + list(range(lens[b] - (k - sinks), lens[b]))
+        o_ref, _, _ = oracle.full_attn(qb[b:b + 1], Kb[b:b + 1][:, :, rows], Vb[b:b + 1][:, :, rows], [len(rows)], scale)
+        assert_out_close(got[b:b + 1], o_ref, "b=%d" % b)
+
+
 def test_rows_past_the_end_are_never_used(rk):
     """Cache rows at and beyond seq_lens (and small-cache rows beyond the selected ones) hold NaN:
     nothing of them may reach the outputs, the weights or the selection."""

@@ -39,6 +39,9 @@ def parse():
     ap.add_argument("--launch", choices=["graph", "native", "eager"], default="graph",
                     help="graph: replay one HIP graph per step; native: one rk_decode_step call per step enqueues all "
                          "layers; eager: one Python call per library call")
+    ap.add_argument("--no-overlap", action="store_true",
+                    help="keep the selection and the gather of a full step on the main stream (default: second stream, "
+                         "beside the full attention of the following layers)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=4, help="layers of the oracle sample")
     return ap.parse_args()
@@ -93,6 +96,9 @@ def main():
         model = rk.RefreshKVModel(geom, kv, seq_lens, int(lens0.max()), w.k_small, w.stride, pool_w=w.pool_w,
                                   dynamic=w.dynamic, threshold=w.threshold, workspace=ws)
 
+    overlap = not args.no_overlap and model is None
+    stack = rk.RefreshKVStack(layers) if overlap else None
+
     def enqueue_step(t: int):
         """Everything of decode step t on the current stream (q_cur already holds the queries)."""
         if t >= 1:
@@ -101,6 +107,8 @@ def main():
             if t >= 1:
                 model.advance()
             return model.step(t, q_cur)
+        if stack is not None:
+            return stack.step(t, q_cur)
         kind = None
         for l, lay in enumerate(layers):
             kind = lay.step(t, q_cur[l])
@@ -161,6 +169,11 @@ def main():
     for (a, b), k in zip(ev, kinds):
         per_kind.setdefault(k, []).append(a.elapsed_time(b) * 1e3)
     med = {k: float(np.median(v)) / n_layers for k, v in per_kind.items()}      # us per layer
+    if os.environ.get("RK_BENCH_DEBUG"):
+        by_pos = {}
+        for (a, b), t in zip(ev, range(args.warmup + 1, T + 1)):
+            by_pos.setdefault(t % max(w.stride, 1), []).append(a.elapsed_time(b) * 1e3 / n_layers)
+        print("per position in the stride period:", {k: round(float(np.median(v)), 2) for k, v in sorted(by_pos.items())}, file=sys.stderr)
     spread = {k: [round(float(np.percentile(v, q)) / n_layers, 2) for q in (10, 90)] for k, v in per_kind.items()}
     final_len = int(seq_lens.max().item())
     assert final_len == int(lens0.max()) + T, (final_len, int(lens0.max()) + T)
@@ -298,7 +311,8 @@ def main():
         "config": {"workload": w.name, "layers": n_layers, "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv,
                    "head_dim": D, "context": L0, "k_small": w.k_small, "stride": w.stride, "pool_w": w.pool_w,
                    "schedule": "dynamic" if w.dynamic else "fixed", "full_steps": n_full,
-                   "partial_steps": args.steps - n_full, "launch": {"graph": "hip_graph", "native": "rk_decode_step", "eager": "eager"}[launch]},
+                   "partial_steps": args.steps - n_full, "launch": {"graph": "hip_graph", "native": "rk_decode_step", "eager": "eager"}[launch],
+                   "refresh_overlap": bool(stack is not None)},
         "step_us_per_layer": {k: round(v, 2) for k, v in med.items()},
         "step_us_per_layer_p10_p90": spread,
         "call_us_per_layer": {k: round(v, 2) for k, v in klass.items()},

@@ -170,6 +170,27 @@ int rk_full_attn_select(const rk_geom* geom, const void* q, rk_kv full,
                         const int32_t* pred, int32_t pred_val,
                         void* workspace, size_t workspace_bytes, void* stream);
 
+/* rk_full_attn_select in two halves, for callers that overlap the selection with other work.
+ * The step's output is complete after the first half; the selection and the gather are needed
+ * only by the NEXT partial step of the same layer, so they can run on another stream beside the
+ * attention of the following layers.
+ *   rk_full_attn_pool   everything of rk_full_attn_select up to and including the pooled group
+ *                       scores and their histogram, which stay in `workspace`;
+ *   rk_select_pooled    the top-K from what rk_full_attn_pool left in the SAME workspace, with the
+ *                       same seq_lens, max_len, predicate and geometry.
+ * Between the two calls no other call may use that workspace (two workspaces used in turn let the
+ * next layer's rk_full_attn_pool start before this layer's rk_select_pooled has run).  The pair
+ * leaves the workspace as clean as rk_full_attn_select does. */
+int rk_full_attn_pool(const rk_geom* geom, const void* q, rk_kv full,
+                      const int32_t* seq_lens, int32_t max_len,
+                      void* out, float* weights, int64_t w_stride, float* lse,
+                      int32_t pool_w, int32_t agg,
+                      const int32_t* pred, int32_t pred_val,
+                      void* workspace, size_t workspace_bytes, void* stream);
+int rk_select_pooled(const rk_geom* geom, const int32_t* seq_lens, int32_t max_len, int32_t k,
+                     int32_t* idx, float* sel_scores, const int32_t* pred, int32_t pred_val,
+                     void* workspace, size_t workspace_bytes, void* stream);
+
 /* Scores-only refresh (Section 4.3 "Impact of full attention steps", the setting "w/o full
  * attention": the attention scores over the entire cache are calculated and the small cache is
  * updated from them; the step's output then comes from rk_partial_attn on the updated small

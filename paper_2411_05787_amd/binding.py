@@ -16,7 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "librefreshkv.so")
 
 EXPORTS = ["rk_version", "rk_status_string", "rk_workspace_bytes", "rk_workspace_init",
-           "rk_full_attn", "rk_full_attn_scores", "rk_topk_select", "rk_full_attn_select", "rk_score_select", "rk_gather_small_kv", "rk_partial_attn", "rk_partial_attn_fixed", "rk_decode_step",
+           "rk_full_attn", "rk_full_attn_scores", "rk_topk_select", "rk_full_attn_select", "rk_full_attn_pool", "rk_select_pooled", "rk_score_select", "rk_gather_small_kv", "rk_partial_attn", "rk_partial_attn_fixed", "rk_decode_step",
            "rk_query_sim", "rk_mark_refresh", "rk_calibration_copy"]
 
 RK_AGG_MAX, RK_AGG_MEAN, RK_AGG_FIRST = 0, 1, 2
@@ -75,6 +75,10 @@ def _load(path: str = LIB_PATH) -> C.CDLL:
     l.rk_gather_small_kv.restype = C.c_int
     l.rk_full_attn_select.argtypes = [G, P, _Kv, P, I32, P, P, I64, P, I32, I32, I32, P, P, P, I32, P, SZ, P]
     l.rk_full_attn_select.restype = C.c_int
+    l.rk_full_attn_pool.restype = C.c_int
+    l.rk_full_attn_pool.argtypes = [G, P, _Kv, P, I32, P, P, I64, P, I32, I32, P, I32, P, SZ, P]
+    l.rk_select_pooled.restype = C.c_int
+    l.rk_select_pooled.argtypes = [G, P, I32, I32, P, P, P, I32, P, SZ, P]
     l.rk_score_select.argtypes = [G, P, _Kv, P, I32, P, I64, P, I32, I32, I32, P, P, P, I32, P, SZ, P]
     l.rk_score_select.restype = C.c_int
     l.rk_gather_small_kv.argtypes = [G, _Kv, P, I32, _Kv, P, P, P, I32, P]
@@ -252,6 +256,38 @@ def rk_full_attn_select(geom: Geom, q, K, V, seq_lens, max_len: int, out, k: int
         _dev(weights, torch.float32, "weights", optional=True), w_stride,
         _dev(lse, torch.float32, "lse", (B, Hq), optional=True),
         int(k), int(pool_w), int(agg),
+        _dev(idx, torch.int32, "idx", (B, Hkv, k)),
+        _dev(sel_scores, torch.float32, "sel_scores", (B, Hkv, k), optional=True),
+        _dev(pred, torch.int32, "pred", (B,), optional=True), int(pred_val),
+        workspace.ptr, workspace.nbytes, _stream(stream)))
+
+
+def rk_full_attn_pool(geom: Geom, q, K, V, seq_lens, max_len: int, out, pool_w: int, weights=None, lse=None,
+                      agg: int = RK_AGG_MAX, pred=None, pred_val: int = 0, workspace: Workspace = None,
+                      stream=None) -> None:
+    B, Hq, D = geom.batch, geom.n_q_heads, geom.head_dim
+    if max_len > K.shape[2]:
+        raise ValueError("max_len %d exceeds the cache capacity %d" % (max_len, K.shape[2]))
+    w_stride = 0
+    if weights is not None:
+        if weights.dim() != 3 or weights.shape[0] != B or weights.shape[1] != Hq or weights.shape[2] < max_len:
+            raise ValueError("weights must be [batch, n_q_heads, >= max_len]")
+        w_stride = weights.shape[2]
+    _check("rk_full_attn_pool", lib.rk_full_attn_pool(
+        C.byref(geom.c()), _dev(q, torch.bfloat16, "q", (B, Hq, D)), _kv(geom, K, V, "full"),
+        _dev(seq_lens, torch.int32, "seq_lens", (B,)), int(max_len),
+        _dev(out, torch.bfloat16, "out", (B, Hq, D)),
+        _dev(weights, torch.float32, "weights", optional=True), w_stride,
+        _dev(lse, torch.float32, "lse", (B, Hq), optional=True), int(pool_w), int(agg),
+        _dev(pred, torch.int32, "pred", (B,), optional=True), int(pred_val),
+        workspace.ptr, workspace.nbytes, _stream(stream)))
+
+
+def rk_select_pooled(geom: Geom, seq_lens, max_len: int, k: int, idx, sel_scores=None, pred=None, pred_val: int = 0,
+                     workspace: Workspace = None, stream=None) -> None:
+    B, Hkv = geom.batch, geom.n_kv_heads
+    _check("rk_select_pooled", lib.rk_select_pooled(
+        C.byref(geom.c()), _dev(seq_lens, torch.int32, "seq_lens", (B,)), int(max_len), int(k),
         _dev(idx, torch.int32, "idx", (B, Hkv, k)),
         _dev(sel_scores, torch.float32, "sel_scores", (B, Hkv, k), optional=True),
         _dev(pred, torch.int32, "pred", (B,), optional=True), int(pred_val),

@@ -552,3 +552,34 @@ extern "C" int rk_score_select(const rk_geom* geom, const void* q, rk_kv full,
     if (rc != RK_OK) return rc;
     return select_stage(geom, seq_lens, max_len, k, idx, sel_scores, pred, pred_val, ws, st);
 }
+
+extern "C" int rk_full_attn_pool(const rk_geom* geom, const void* q, rk_kv full,
+                                 const int32_t* seq_lens, int32_t max_len,
+                                 void* out, float* weights, int64_t w_stride, float* lse,
+                                 int32_t pool_w, int32_t agg,
+                                 const int32_t* pred, int32_t pred_val,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_geom(geom);
+    if (rc != RK_OK) return rc;
+    if (!q || !out || !seq_lens || max_len <= 0) return RK_ERR_INVALID_ARG;
+    if (!aligned16(q) || ((uintptr_t)out & 1u)) return RK_ERR_INVALID_ARG;
+    if ((rc = check_kv(full)) != RK_OK) return rc;
+    if (weights && (w_stride < max_len || ((uintptr_t)weights & 3u))) return RK_ERR_INVALID_ARG;
+    if ((rc = check_select_args(1, pool_w, agg)) != RK_OK) return rc;
+    Workspace ws;
+    if ((rc = check_workspace(geom, max_len, 0, workspace, workspace_bytes, &ws)) != RK_OK) return rc;
+    return full_attn_stage(geom, q, full, seq_lens, max_len, out, weights, w_stride, lse, pred, pred_val, ws,
+                           (hipStream_t)stream, false, (pool_w - 1) / 2, false, agg);
+}
+
+extern "C" int rk_select_pooled(const rk_geom* geom, const int32_t* seq_lens, int32_t max_len, int32_t k,
+                                int32_t* idx, float* sel_scores, const int32_t* pred, int32_t pred_val,
+                                void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_geom(geom);
+    if (rc != RK_OK) return rc;
+    if (!seq_lens || !idx || max_len <= 0 || k <= 0) return RK_ERR_INVALID_ARG;
+    if ((rc = check_select_args(k, 1, RK_AGG_MAX)) != RK_OK) return rc;
+    Workspace ws;
+    if ((rc = check_workspace(geom, max_len, k, workspace, workspace_bytes, &ws)) != RK_OK) return rc;
+    return select_stage(geom, seq_lens, max_len, k, idx, sel_scores, pred, pred_val, ws, (hipStream_t)stream);
+}

@@ -189,3 +189,59 @@ class RefreshKVModel:
         if kind == "full" and not self._static:
             self.recent_bound = 0
         return kind
+
+
+class RefreshKVStack:
+    """The layers of a model stepped in order, full steps with the refresh off the critical path.
+
+    The output of a full step is complete once ``rk_full_attn_pool`` has run; the selection and
+    the gather only prepare the layer's NEXT partial step.  Here they go to a second stream, where
+    they run beside the full attention of the following layers (in a model: beside the rest of
+    the layer), and the streams join at the end of the step.  Two workspaces are used in turn, so
+    that a layer's pooled scores survive until its selection has read them.  Partial steps and the
+    trigger's test steps are issued as :class:`RefreshKVLayer` issues them.
+    """
+
+    def __init__(self, layers, workspace_b: Optional[rk.Workspace] = None):
+        if not layers:
+            raise ValueError("no layers")
+        l0 = layers[0]
+        if l0.scores_only_refresh:
+            raise ValueError("the scores-only refresh is not split over two streams")
+        self.layers = layers
+        dev = l0.K.device
+        self.wss = (l0.ws, workspace_b if workspace_b is not None
+                    else rk.Workspace(l0.geom, l0.capacity, l0.k_small, device=dev))
+        self.side = torch.cuda.Stream(device=dev)
+        self.ready = [torch.cuda.Event() for _ in layers]
+        self.done = [torch.cuda.Event() for _ in layers]
+
+    def step(self, t: int, q_layers) -> str:
+        """q_layers[l]: bf16 [B, Hq, D], the query of the current token in layer l."""
+        l0 = self.layers[0]
+        scheduled = t == 0 or (l0.stride > 0 and t % l0.stride == 0)
+        if not (t == 0 or (scheduled and not l0.dynamic)):
+            kind = None
+            for l, lay in enumerate(self.layers):
+                kind = lay.step(t, q_layers[l])
+            return kind
+        main = torch.cuda.current_stream()
+        for l, lay in enumerate(self.layers):
+            ws = self.wss[l % 2]
+            if l >= 2:                      # the selection of layer l - 2 is done with this workspace
+                main.wait_event(self.done[l - 2])
+            q, g = q_layers[l], lay.geom
+            if lay.dynamic:
+                rk.rk_query_sim(g, q, lay.q_ref, lay.threshold, True, lay.sim, lay.need_full, stream=main)
+            rk.rk_full_attn_pool(g, q, lay.K, lay.V, lay.seq_lens, lay.max_len, lay.out, lay.pool_w,
+                                 weights=lay.weights, workspace=ws, stream=main)
+            self.ready[l].record(main)
+            self.side.wait_event(self.ready[l])
+            rk.rk_select_pooled(g, lay.seq_lens, lay.max_len, lay.k_small, lay.idx, workspace=ws, stream=self.side)
+            rk.rk_gather_small_kv(g, lay.K, lay.V, lay.idx, lay.k_small, lay.small_K, lay.small_V,
+                                  seq_lens=lay.seq_lens, tail_start=lay.tail_start, stream=self.side)
+            self.done[l].record(self.side)
+            if not lay._static:
+                lay.recent_bound = 0
+        main.wait_stream(self.side)         # the next step reads the small caches
+        return "full"

@@ -724,6 +724,62 @@ def test_decode_step_driver_fixed_and_dynamic(rk):
     check_model_loop(rk, gen.shrink(gen.WORKLOADS["cfg1_llama_2k"], n_steps=5), 2, scores_only=True)
 
 
+def test_refresh_on_second_stream_stack(rk):
+    """RefreshKVStack: selection and gather of a full step on a second stream, two workspaces in turn;
+    eager and replayed from a HIP graph."""
+    w = gen.shrink(gen.WORKLOADS["cfg1_llama_2k"], n_steps=9)
+    n_layers, dev = 5, "cuda"
+    geom = rk.Geom(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.scale)
+    lens0 = gen.seq_lens(w)
+    data = [(gen.make_kv(w, l), gen.make_queries(w, l), gen.make_new_rows(w, l)) for l in range(n_layers)]
+    for use_graph in (False, True):
+        say("refresh on a second stream, graph =", use_graph)
+        kv = [(d[0][0].to(dev).clone(), d[0][1].to(dev).clone()) for d in data]
+        sl = lens0.to(dev).clone()
+        ws = rk.Workspace(geom, w.capacity, w.k_small)
+        layers = [rk.RefreshKVLayer(geom, kv[l][0], kv[l][1], sl, int(lens0.max()), w.k_small, w.stride, pool_w=w.pool_w,
+                                    workspace=ws) for l in range(n_layers)]
+        stack = rk.RefreshKVStack(layers)
+        q_all = torch.stack([d[1] for d in data], dim=1).to(dev).contiguous()
+        q_cur = torch.empty_like(q_all[0])
+        B, Hkv, D = w.batch, w.n_kv_heads, w.head_dim
+        graphs = {}
+        if use_graph:
+            for lay in layers:
+                lay.use_static_bounds(int(lens0.max()) + w.n_steps + 1, w.stride)
+        outs, idxs = [], []
+        for t in range(w.n_steps + 1):
+            if t >= 1:
+                pos = sl.to(torch.int64)[:, None, None, None].expand(B, Hkv, 1, D)
+                for l in range(n_layers):
+                    kv[l][0].scatter_(2, pos, data[l][2][0][t - 1].to(dev)[:, :, None, :])
+                    kv[l][1].scatter_(2, pos, data[l][2][1][t - 1].to(dev)[:, :, None, :])
+                sl += 1
+                if not use_graph:
+                    for lay in layers:
+                        lay.advance()
+            q_cur.copy_(q_all[t])
+            kind = "full" if (t % w.stride == 0) else "partial"
+            if use_graph and t >= 1:
+                if kind not in graphs:
+                    torch.cuda.synchronize()
+                    g = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(g):
+                        stack.step(t, q_cur)
+                    graphs[kind] = g
+                graphs[kind].replay()
+            else:
+                assert stack.step(t, q_cur) == kind
+            torch.cuda.synchronize()
+            outs.append(torch.stack([lay.out for lay in layers]).clone())
+            idxs.append(torch.stack([lay.idx for lay in layers]).clone())
+        for l in range(n_layers):
+            got = dict(outs=np.stack([gen.bf16_bits(o[l]) for o in outs]), idx=[i[l].cpu().numpy() for i in idxs],
+                       K=gen.bf16_bits(kv[l][0]), V=gen.bf16_bits(kv[l][1]), lens=sl.cpu().numpy())
+            (K, V), q, (nk, nv) = data[l]
+            compare_with_oracle(w, l, got, K, V, q, nk, nv, lens0)
+
+
 def test_loop_cfg1_every_step(rk):
     w = gen.WORKLOADS["cfg1_llama_2k"]
     say("loop", w.name)

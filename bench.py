@@ -42,6 +42,7 @@ def parse():
     ap.add_argument("--no-overlap", action="store_true",
                     help="keep the selection and the gather of a full step on the main stream (default: second stream, "
                          "beside the full attention of the following layers)")
+    ap.add_argument("--overlap-workspaces", type=int, default=2, help="workspaces the overlapped refresh rotates (0: one per layer)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=4, help="layers of the oracle sample")
     return ap.parse_args()
@@ -97,7 +98,7 @@ def main():
                                   dynamic=w.dynamic, threshold=w.threshold, workspace=ws)
 
     overlap = not args.no_overlap and model is None
-    stack = rk.RefreshKVStack(layers) if overlap else None
+    stack = rk.RefreshKVStack(layers, n_workspaces=args.overlap_workspaces) if overlap else None
 
     def enqueue_step(t: int):
         """Everything of decode step t on the current stream (q_cur already holds the queries)."""

@@ -197,12 +197,15 @@ class RefreshKVStack:
     The output of a full step is complete once ``rk_full_attn_pool`` has run; the selection and
     the gather only prepare the layer's NEXT partial step.  Here they go to a second stream, where
     they run beside the full attention of the following layers (in a model: beside the rest of
-    the layer), and the streams join at the end of the step.  Two workspaces are used in turn, so
-    that a layer's pooled scores survive until its selection has read them.  Partial steps and the
-    trigger's test steps are issued as :class:`RefreshKVLayer` issues them.
+    the layer), and the streams join at the end of the step.  A layer's pooled scores must survive
+    until its selection has read them: ``n_workspaces`` workspaces are used in turn, and the main
+    stream waits for the selection that last used a workspace before it reuses it.  Two measured
+    best at 32 layers of 32k tokens: with one per layer the second stream falls behind and its
+    kernels crowd the full attention of later layers.  Partial
+    steps and the trigger's test steps are issued as :class:`RefreshKVLayer` issues them.
     """
 
-    def __init__(self, layers, workspace_b: Optional[rk.Workspace] = None):
+    def __init__(self, layers, n_workspaces: int = 2):
         if not layers:
             raise ValueError("no layers")
         l0 = layers[0]
@@ -210,8 +213,8 @@ class RefreshKVStack:
             raise ValueError("the scores-only refresh is not split over two streams")
         self.layers = layers
         dev = l0.K.device
-        self.wss = (l0.ws, workspace_b if workspace_b is not None
-                    else rk.Workspace(l0.geom, l0.capacity, l0.k_small, device=dev))
+        n_ws = len(layers) if n_workspaces <= 0 else max(2, min(int(n_workspaces), len(layers)))
+        self.wss = [l0.ws] + [rk.Workspace(l0.geom, l0.capacity, l0.k_small, device=dev) for _ in range(n_ws - 1)]
         self.side = torch.cuda.Stream(device=dev)
         self.ready = [torch.cuda.Event() for _ in layers]
         self.done = [torch.cuda.Event() for _ in layers]
@@ -227,9 +230,10 @@ class RefreshKVStack:
             return kind
         main = torch.cuda.current_stream()
         for l, lay in enumerate(self.layers):
-            ws = self.wss[l % 2]
-            if l >= 2:                      # the selection of layer l - 2 is done with this workspace
-                main.wait_event(self.done[l - 2])
+            n_ws = len(self.wss)
+            ws = self.wss[l % n_ws]
+            if l >= n_ws:                   # the selection of layer l - n_ws must be done with this workspace
+                main.wait_event(self.done[l - n_ws])
             q, g = q_layers[l], lay.geom
             if lay.dynamic:
                 rk.rk_query_sim(g, q, lay.q_ref, lay.threshold, True, lay.sim, lay.need_full, stream=main)

@@ -739,7 +739,7 @@ def test_refresh_on_second_stream_stack(rk):
         ws = rk.Workspace(geom, w.capacity, w.k_small)
         layers = [rk.RefreshKVLayer(geom, kv[l][0], kv[l][1], sl, int(lens0.max()), w.k_small, w.stride, pool_w=w.pool_w,
                                     workspace=ws) for l in range(n_layers)]
-        stack = rk.RefreshKVStack(layers)
+        stack = rk.RefreshKVStack(layers, n_workspaces=2 if use_graph else 0)      # with and without workspace reuse
         q_all = torch.stack([d[1] for d in data], dim=1).to(dev).contiguous()
         q_cur = torch.empty_like(q_all[0])
         B, Hkv, D = w.batch, w.n_kv_heads, w.head_dim

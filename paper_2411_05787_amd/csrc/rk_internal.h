@@ -58,10 +58,11 @@ static inline int topk_cand_cap(int64_t k) {
     return (int)c;
 }
 
-// Device workspace, carved in this order (every region 256-byte aligned).  The first two
+// Device workspace, carved in this order (every region 256-byte aligned).  The first three
 // regions must be zero whenever no call is in flight: rk_workspace_init clears them once and
 // the kernels that use them leave them cleared.
 //   counters  int32 [B*Hkv]                  arrival tickets of the split attention kernel
+//   sel_counters int32 [B*Hkv][2]            listed candidates and arrival tickets of the selection
 //   hist      uint32 [B*Hkv][kHistBins]      first-level histogram of the pooled scores
 //   lse       fp32  [B*Hq]                   log-sum-exp when the caller does not ask for it
 //   part_ml   fp32  [B*Hkv][kMaxChunks][G][2] running max and sum of every partial result
@@ -71,12 +72,15 @@ static inline int topk_cand_cap(int64_t k) {
 //                                                            rk_full_attn_select
 struct Workspace {
     int32_t* counters;
+    int32_t* sel_counters;
     uint32_t* hist;
     float* lse;
     float* part_ml;
     float* part_o;
     float* pooled;
     float* scores;
+    uint64_t* cand_list;  // [B*Hkv][cand_cap] candidates (score image, ~position) of the spread-out selection;
+                          // last, because its size depends on k
     int cand_cap;         // candidate slots the selection sorts in LDS
     int max_chunks;       // nch above
     size_t total;
@@ -86,7 +90,7 @@ struct Workspace {
 static inline int64_t pooled_row_stride(int64_t max_len) { return (max_len + 3) / 4 * 4; }
 
 static inline size_t zeroed_words(const rk_geom* g) {
-    return (size_t)g->batch * g->n_kv_heads * (1 + (size_t)kHistBins);
+    return (size_t)g->batch * g->n_kv_heads * (3 + (size_t)kHistBins);
 }
 
 static inline int max_chunks_for(int64_t max_len) {
@@ -105,6 +109,7 @@ static inline Workspace carve(const rk_geom* g, int64_t max_len, int64_t max_k, 
     size_t off = 0;
     // the zero-kept regions are contiguous (no padding between them)
     w.counters = (int32_t*)(p + off); off += problems * sizeof(int32_t);
+    w.sel_counters = (int32_t*)(p + off); off += 2 * problems * sizeof(int32_t);
     w.hist = (uint32_t*)(p + off);    off += problems * kHistBins * sizeof(uint32_t);
     off = align_up(off, 256);
     w.lse = (float*)(p + off);        off += align_up((size_t)g->batch * g->n_q_heads * sizeof(float), 256);
@@ -113,6 +118,7 @@ static inline Workspace carve(const rk_geom* g, int64_t max_len, int64_t max_k, 
     w.pooled = (float*)(p + off);     off += align_up(problems * (size_t)pooled_row_stride(max_len > 0 ? max_len : 1) * sizeof(float), 256);
     w.scores = (float*)(p + off);     off += align_up((size_t)g->batch * g->n_q_heads * (size_t)pooled_row_stride(max_len > 0 ? max_len : 1) * sizeof(float), 256);
     w.cand_cap = topk_cand_cap(max_k > 0 ? max_k : 1);
+    w.cand_list = (uint64_t*)(p + off); off += align_up(problems * (size_t)w.cand_cap * sizeof(uint64_t), 256);
     w.total = off;
     return w;
 }

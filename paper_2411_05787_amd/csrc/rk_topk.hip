@@ -6,29 +6,32 @@
 // Kernel 1, whole chip (pool_hist_kernel): P[j] = max over the G heads of the group and over the
 //   pooling window, staged through LDS so that every weight is read once; P is stored and its
 //   top 11 image bits are histogrammed (LDS, then one global atomic per non-empty bin).
-// Kernel 2, one workgroup of 1024 threads per (sequence, KV head) (select_kernel): finds, from
-//   the histogram, the bin b1 that holds the K-th largest score; every position in that bin or a
-//   higher one is a candidate (the K winners plus the rest of one bin).  The candidates are
-//   bucket-sorted in LDS on the 64-bit item (P image, ~position): 2048 buckets of equal width
-//   from the lowest candidate image up to the bin of the 64-th largest score, one more bucket
-//   for everything above (fewer than 64 items);
-//   pass A over P counts the buckets, a scan turns counts into offsets, pass B over P drops every
-//   candidate into its bucket, and each candidate's final rank is its bucket offset plus the
-//   number of larger items in its own bucket (a few dozen compares).  Ranks below K' are written
-//   out directly: idx comes out in rank order.  The kernel also clears the histogram for the
-//   next call.
-// Dense or degenerate score distributions take further exact steps in kernel 2: more candidates
-// than fit in LDS -> bin b1 is cut once more by the next 11 image bits (one more pass over P) and
-// only its upper part stays a candidate; a bucket with more than 1024 items -> the candidates
-// are bitonic-sorted instead of ranked; still too many candidates (e.g. all scores equal) ->
-// a last radix pass (10 bits) finds the K-th largest image T exactly, positions with P > T and
-// the first positions with P == T are collected in position order, then bitonic-sorted.
+// Kernel 2 (select_kernel), workgroups of 1024 threads: from the histogram, the bin b1 that holds
+//   the K-th largest score; every position in that bin or a higher one is a candidate (the K
+//   winners plus the rest of one bin).  The candidates are packed into a dense list: for rows up
+//   to 8192 positions by the one workgroup of the (sequence, KV head), in LDS; for longer rows by
+//   one workgroup per 4096 positions, into the workspace (one atomic add per workgroup reserves
+//   the space), and the workgroup that arrives last goes on alone.  It takes the list into
+//   registers and bucket-sorts it back into LDS on the 64-bit item (P image, ~position): 2048
+//   buckets of equal width from the lowest candidate image up to the bin of the 64-th largest
+//   score, one more bucket for everything above (fewer than 64 items); a scan turns bucket counts
+//   into offsets, and each candidate's final rank is its bucket offset plus the number of larger
+//   items in its own bucket (a few dozen compares).  Ranks below K' are written out directly: idx
+//   comes out in rank order.  The kernel also clears the histogram for the next call.
+// Dense or degenerate score distributions take further exact steps in kernel 2 (one workgroup):
+// more candidates than fit in LDS -> bin b1 is cut once more by the next 11 image bits (one more
+// pass over P) and only its upper part stays a candidate; a bucket with more than 1024 items ->
+// the candidates are bitonic-sorted instead of ranked; still too many candidates (e.g. all scores
+// equal) -> a last radix pass (10 bits) finds the K-th largest image T exactly, positions with
+// P > T and the first positions with P == T are collected in position order, then bitonic-sorted.
 #include "rk_internal.h"
 #include "rk_device.h"
 
 namespace rk {
 
 constexpr int kSelThreads = 1024;
+constexpr int kSelTile = 4 * kSelThreads;                // positions per workgroup when the selection is spread out
+constexpr int kSelSingle = 2 * kSelTile;                 // rows up to this length are left to one workgroup
 constexpr int kBuckets = 2048;                           // regular buckets, plus one for all above
 constexpr int kBucketLimit = 1024;                       // larger buckets: sort instead of ranking
 constexpr int kTopLoose = 64;                            // scores above the bucketed range: fewer than this
@@ -197,12 +200,20 @@ __device__ void bitonic_sort_desc(uint64_t* sKeys, int npad) {
     __syncthreads();
 }
 
+// Grid (tiles, KV heads, sequences).  With one tile the workgroup does everything.  With more,
+// every workgroup derives the thresholds from the histogram, packs the candidates of its own
+// kSelTile positions into a list in the workspace (one atomic add per workgroup reserves the
+// space), and the workgroup that arrives last (ticket, as in the attention kernels) takes the
+// list into registers and ranks it: the pass over all positions, which is what a single
+// workgroup spends most of its time on, is spread over the chip.
 __global__ __launch_bounds__(kSelThreads)
 void select_kernel(const float* __restrict__ pooled, int64_t pooled_stride, const int32_t* seq_lens,
                    int32_t max_len, int32_t k, uint32_t* __restrict__ hist, int32_t cand_cap,
                    int32_t* __restrict__ idx, float* __restrict__ sel_scores,
-                   const int32_t* pred, int32_t pred_val) {
-    const int g = blockIdx.x, b = blockIdx.y, Hkv = gridDim.x;
+                   const int32_t* pred, int32_t pred_val,
+                   int32_t* __restrict__ sel_counters, uint64_t* __restrict__ cand_list) {
+    const int tile = blockIdx.x, g = blockIdx.y, b = blockIdx.z, Hkv = gridDim.y;
+    const bool multi = gridDim.x > 1;
     if (pred != nullptr && pred[b] != pred_val) return;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     uint64_t* sKeys = reinterpret_cast<uint64_t*>(smem);                   // [cand_cap]
@@ -218,7 +229,8 @@ void select_kernel(const float* __restrict__ pooled, int64_t pooled_stride, cons
     const int64_t bg = (int64_t)b * Hkv + g;
     const int64_t ob = bg * k;
     if (kprime <= 0) {                      // nothing was histogrammed for an empty sequence
-        for (int i = tid; i < k; i += kSelThreads) { idx[ob + i] = -1; if (sel_scores) sel_scores[ob + i] = 0.f; }
+        if (tile == 0)
+            for (int i = tid; i < k; i += kSelThreads) { idx[ob + i] = -1; if (sel_scores) sel_scores[ob + i] = 0.f; }
         return;
     }
     const float* P = pooled + bg * pooled_stride;
@@ -240,8 +252,12 @@ void select_kernel(const float* __restrict__ pooled, int64_t pooled_stride, cons
         return x;
     };
     float4 held[NV];
+    if (!multi) {
 #pragma unroll
-    for (int u = 0; u < NV; ++u) held[u] = load4(u * kSelThreads + tid);
+        for (int u = 0; u < NV; ++u) held[u] = load4(u * kSelThreads + tid);
+    } else {
+        held[0] = load4(tile * kSelThreads + tid);      // this workgroup's kSelTile positions
+    }
 
     // From the histogram, in one scan from the top bin down (thread 0 owns the top two bins):
     // the bin b1 that holds the K'-th largest score (with the count above it), and the bin that
@@ -263,7 +279,7 @@ void select_kernel(const float* __restrict__ pooled, int64_t pooled_stride, cons
             sOut[2] = upper ? h1 : h0;
         }
         if (abv < kk2 && kk2 <= incl) sOut[3] = (uint32_t)(2 * rt + (abv + h1 >= kk2 ? 1 : 0));
-        gh[2 * rt] = 0; gh[2 * rt + 1] = 0;            // cleared for the next call
+        if (!multi) { gh[2 * rt] = 0; gh[2 * rt + 1] = 0; }     // cleared for the next call
         __syncthreads();
     }
     const uint32_t b1 = sOut[0];
@@ -271,9 +287,50 @@ void select_kernel(const float* __restrict__ pooled, int64_t pooled_stride, cons
     uint32_t count_ge = above + sOut[2];
     const uint32_t key_top = (sOut[3] + 1u) << kHistShift;      // sOut[3] >= b1; wraps to 0 for the last bin
 
+    uint32_t key_thr = b1 << kHistShift;
+    const bool listed = multi && count_ge <= (uint32_t)cand_cap;       // the same in every workgroup of (b, g)
+    if (multi) {
+        int32_t* n_listed = sel_counters + bg * 2;
+        int32_t* arrived = n_listed + 1;
+        uint64_t* list = cand_list + bg * cand_cap;
+        if (listed) {
+            const float t1 = value_of(key_thr);
+            const float4 x = held[0];
+            const uint32_t c = (x.x >= t1 ? 1u : 0u) + (x.y >= t1 ? 1u : 0u) + (x.z >= t1 ? 1u : 0u) + (x.w >= t1 ? 1u : 0u);
+            uint32_t total;
+            const uint32_t incl = block_inclusive_scan<kSelThreads>(c, sScan, &total);
+            if (tid == 0 && total != 0)
+                *sCount = (uint32_t)__hip_atomic_fetch_add(n_listed, (int32_t)total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __syncthreads();
+            uint32_t pos = *sCount + incl - c;
+            const int j0 = (tile * kSelThreads + tid) << 2;
+            auto put = [&](float v, int j) {
+                if (v >= t1 && pos < (uint32_t)cand_cap)          // (pos < cand_cap always: count_ge items in all)
+                    __hip_atomic_store(&list[pos++], item_of(__float_as_uint(v) | 0x80000000u, j), __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+            };
+            put(x.x, j0); put(x.y, j0 + 1); put(x.z, j0 + 2); put(x.w, j0 + 3);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // the list entries are acknowledged
+        }
+        __syncthreads();                                           // ... and every thread has read the histogram
+        if (tid == 0) sOut[1] = (uint32_t)__hip_atomic_fetch_add(arrived, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        if (sOut[1] != gridDim.x - 1) return;
+        // last to arrive: everything of this (b, g) is in; leave the workspace clean, then rank
+        if (tid == 0) {
+            __hip_atomic_store(n_listed, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(arrived, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            *sCount = 0;
+        }
+        { const int rt = kSelThreads - 1 - tid; gh[2 * rt] = 0; gh[2 * rt + 1] = 0; }
+        if (!listed) {                                             // too many candidates: go on alone, from the scores
+#pragma unroll
+            for (int u = 0; u < NV; ++u) held[u] = load4(u * kSelThreads + tid);
+        }
+        __syncthreads();
+    }
     // Candidates are the positions whose image is >= key_thr.  Normally that is "bin b1 or above";
     // if those are too many for LDS, bin b1 is cut once more by the next 11 image bits.
-    uint32_t key_thr = b1 << kHistShift;
     uint32_t prefix = key_thr, mask = 0x7FFu << kHistShift, kk = (uint32_t)kprime - above;   // radix-select state
     bool refined = false;
     if (count_ge > (uint32_t)cand_cap) {
@@ -345,17 +402,26 @@ void select_kernel(const float* __restrict__ pooled, int64_t pooled_stride, cons
         if (refined) {                                  // the radix pass used the array: clear it again
             for (int i = tid; i < kBuckets + 1; i += kSelThreads) sCnt[i] = 0;
         }
-        const uint32_t mine = count_candidates();
         uint32_t total;
-        uint32_t pos = block_inclusive_scan<kSelThreads>(mine, sScan, &total) - mine;
-        for_each_candidate([&](uint32_t key, int j) { sKeys[pos++] = item_of(key, j); });
-        __syncthreads();
         constexpr int kItems = kMaxCandidates / kSelThreads;
         uint64_t it[kItems];
+        if (listed) {                                   // the dense list is in the workspace already
+            const uint64_t* list = cand_list + bg * cand_cap;
 #pragma unroll
-        for (int u = 0; u < kItems; ++u) {
-            const int e = u * kSelThreads + tid;
-            it[u] = (e < (int)count_ge) ? sKeys[e] : 0ull;
+            for (int u = 0; u < kItems; ++u) {
+                const int e = u * kSelThreads + tid;
+                it[u] = (e < (int)count_ge) ? __hip_atomic_load(&list[e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0ull;
+            }
+        } else {
+            const uint32_t mine = count_candidates();
+            uint32_t pos = block_inclusive_scan<kSelThreads>(mine, sScan, &total) - mine;
+            for_each_candidate([&](uint32_t key, int j) { sKeys[pos++] = item_of(key, j); });
+            __syncthreads();
+#pragma unroll
+            for (int u = 0; u < kItems; ++u) {
+                const int e = u * kSelThreads + tid;
+                it[u] = (e < (int)count_ge) ? sKeys[e] : 0ull;
+            }
         }
         const int n_mine = ((int)count_ge - tid + kSelThreads - 1) / kSelThreads;   // items of this thread
         __syncthreads();                                // the list is in registers: sKeys is free
@@ -477,9 +543,11 @@ int select_stage(const rk_geom* geom, const int32_t* seq_lens, int32_t max_len, 
         }
         lds_allowed = lds;
     }
-    dim3 sgrid(geom->n_kv_heads, geom->batch);
+    // short rows: one workgroup per (sequence, KV head) does it all; longer ones: one per kSelTile positions
+    const int tiles = max_len > kSelSingle ? (max_len + kSelTile - 1) / kSelTile : 1;
+    dim3 sgrid(tiles, geom->n_kv_heads, geom->batch);
     hipLaunchKernelGGL(select_kernel, sgrid, dim3(kSelThreads), lds, st, ws.pooled, pooled_row_stride(max_len), seq_lens,
-                       max_len, k, ws.hist, ws.cand_cap, idx, sel_scores, pred, pred_val);
+                       max_len, k, ws.hist, ws.cand_cap, idx, sel_scores, pred, pred_val, ws.sel_counters, ws.cand_list);
     return launch_status();
 }
 

@@ -170,12 +170,6 @@ def main():
     for (a, b), k in zip(ev, kinds):
         per_kind.setdefault(k, []).append(a.elapsed_time(b) * 1e3)
     med = {k: float(np.median(v)) / n_layers for k, v in per_kind.items()}      # us per layer
-    if os.environ.get("RK_BENCH_DEBUG"):
-        by_pos = {}
-        for (a, b), t in zip(ev, range(args.warmup + 1, T + 1)):
-            by_pos.setdefault(t % max(w.stride, 1), []).append(a.elapsed_time(b) * 1e3 / n_layers)
-        print("per position in the stride period:", {k: round(float(np.median(v)), 2) for k, v in sorted(by_pos.items())}, file=sys.stderr)
-    spread = {k: [round(float(np.percentile(v, q)) / n_layers, 2) for q in (10, 90)] for k, v in per_kind.items()}
     final_len = int(seq_lens.max().item())
     assert final_len == int(lens0.max()) + T, (final_len, int(lens0.max()) + T)
 

@@ -48,7 +48,7 @@ static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; 
 constexpr int kHistBins = 2048;          // first-level histogram of the selection: top 11 key bits
 constexpr int kMaxCandidates = 16384;    // most candidates the fast selection path sorts in LDS
 constexpr int kHistShift = 32 - 11;      // key bits below the first-level histogram bin
-constexpr int kPoolTile = 1024;          // positions one workgroup pools and histograms
+constexpr int kPoolTile = 512;           // positions one workgroup pools and histograms
 
 // Candidate slots per (sequence, KV head) of the selection: the K winners plus the rest of the
 // histogram bin that holds the K-th score.

@@ -96,6 +96,8 @@ def main():
     if launch == "native":
         model = rk.RefreshKVModel(geom, kv, seq_lens, int(lens0.max()), w.k_small, w.stride, pool_w=w.pool_w,
                                   dynamic=w.dynamic, threshold=w.threshold, workspace=ws)
+        if not args.no_overlap:
+            model.overlap_refresh(args.overlap_workspaces)
 
     overlap = not args.no_overlap and model is None
     stack = rk.RefreshKVStack(layers, n_workspaces=args.overlap_workspaces) if overlap else None
@@ -170,6 +172,7 @@ def main():
     for (a, b), k in zip(ev, kinds):
         per_kind.setdefault(k, []).append(a.elapsed_time(b) * 1e3)
     med = {k: float(np.median(v)) / n_layers for k, v in per_kind.items()}      # us per layer
+    spread = {k: [round(float(np.percentile(v, q)) / n_layers, 2) for q in (10, 90)] for k, v in per_kind.items()}
     final_len = int(seq_lens.max().item())
     assert final_len == int(lens0.max()) + T, (final_len, int(lens0.max()) + T)
 
@@ -307,7 +310,7 @@ def main():
                    "head_dim": D, "context": L0, "k_small": w.k_small, "stride": w.stride, "pool_w": w.pool_w,
                    "schedule": "dynamic" if w.dynamic else "fixed", "full_steps": n_full,
                    "partial_steps": args.steps - n_full, "launch": {"graph": "hip_graph", "native": "rk_decode_step", "eager": "eager"}[launch],
-                   "refresh_overlap": bool(stack is not None)},
+                   "refresh_overlap": bool(stack is not None or (model is not None and not args.no_overlap))},
         "step_us_per_layer": {k: round(v, 2) for k, v in med.items()},
         "step_us_per_layer_p10_p90": spread,
         "call_us_per_layer": {k: round(v, 2) for k, v in klass.items()},

@@ -317,6 +317,31 @@ int rk_decode_step(const rk_geom* geom, const rk_schedule* sched, int32_t t, int
                    const int32_t* seq_lens, int32_t max_len, int32_t max_recent,
                    void* workspace, size_t workspace_bytes, void* stream);
 
+/* What rk_decode_step_overlapped needs besides rk_decode_step's arguments; all caller-owned. */
+typedef struct rk_overlap {
+    void* side_stream;          /* hipStream_t for the selections and gathers of a full step         */
+    void* const* ready;         /* host array of n_layers hipEvent_t: recorded on `stream` when a
+                                   layer's pooled scores are complete                              */
+    void* const* done;          /* host array of n_layers hipEvent_t: recorded on side_stream when
+                                   a layer's small cache is rebuilt                                */
+    void* join;                 /* one more hipEvent_t                                             */
+    void* const* workspaces;    /* host array of n_workspaces device workspaces of workspace_bytes
+                                   each, initialised with rk_workspace_init                        */
+    int32_t n_workspaces;       /* >= 2 to overlap (2 measured best); 1: same as rk_decode_step    */
+    size_t workspace_bytes;
+} rk_overlap;
+
+/* rk_decode_step with the refresh of a full step off the critical path: per layer,
+ * rk_full_attn_pool on `stream`, then rk_select_pooled and rk_gather_small_kv on
+ * ov->side_stream beside the following layers' full attention; `stream` has waited for all of it
+ * when the step's work on it ends.  Same results, same return values.  Other steps, and the
+ * scores-only refresh, are passed to rk_decode_step with the first workspace.  The events must
+ * not be in use by anything else while the step is in flight. */
+int rk_decode_step_overlapped(const rk_geom* geom, const rk_schedule* sched, int32_t t, int32_t n_layers,
+                              const rk_layer_state* layers, const void* const* q, void* const* out,
+                              const int32_t* seq_lens, int32_t max_len, int32_t max_recent,
+                              const rk_overlap* ov, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -16,7 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "librefreshkv.so")
 
 EXPORTS = ["rk_version", "rk_status_string", "rk_workspace_bytes", "rk_workspace_init",
-           "rk_full_attn", "rk_full_attn_scores", "rk_topk_select", "rk_full_attn_select", "rk_full_attn_pool", "rk_select_pooled", "rk_score_select", "rk_gather_small_kv", "rk_partial_attn", "rk_partial_attn_fixed", "rk_decode_step",
+           "rk_full_attn", "rk_full_attn_scores", "rk_topk_select", "rk_full_attn_select", "rk_full_attn_pool", "rk_select_pooled", "rk_score_select", "rk_gather_small_kv", "rk_partial_attn", "rk_partial_attn_fixed", "rk_decode_step", "rk_decode_step_overlapped",
            "rk_query_sim", "rk_mark_refresh", "rk_calibration_copy"]
 
 RK_AGG_MAX, RK_AGG_MEAN, RK_AGG_FIRST = 0, 1, 2
@@ -46,6 +46,12 @@ class _LayerState(C.Structure):
 class _Schedule(C.Structure):
     _fields_ = [("k", C.c_int32), ("pool_w", C.c_int32), ("stride", C.c_int32), ("dynamic", C.c_int32),
                 ("threshold", C.c_float), ("fixed_size", C.c_int32), ("scores_only", C.c_int32)]
+
+
+class _Overlap(C.Structure):
+    _fields_ = [("side_stream", C.c_void_p), ("ready", C.POINTER(C.c_void_p)), ("done", C.POINTER(C.c_void_p)),
+                ("join", C.c_void_p), ("workspaces", C.POINTER(C.c_void_p)), ("n_workspaces", C.c_int32),
+                ("workspace_bytes", C.c_size_t)]
 
 
 STEP_KINDS = {1: "full", 2: "partial", 3: "both"}
@@ -90,6 +96,9 @@ def _load(path: str = LIB_PATH) -> C.CDLL:
     l.rk_decode_step.restype = C.c_int
     l.rk_decode_step.argtypes = [G, C.POINTER(_Schedule), I32, I32, C.POINTER(_LayerState), C.POINTER(C.c_void_p),
                                  C.POINTER(C.c_void_p), P, I32, I32, P, SZ, P]
+    l.rk_decode_step_overlapped.restype = C.c_int
+    l.rk_decode_step_overlapped.argtypes = [G, C.POINTER(_Schedule), I32, I32, C.POINTER(_LayerState), C.POINTER(C.c_void_p),
+                                            C.POINTER(C.c_void_p), P, I32, I32, C.POINTER(_Overlap), P]
     l.rk_query_sim.argtypes = [G, P, P, C.c_float, I32, P, P, P]
     l.rk_calibration_copy.restype = C.c_int
     l.rk_calibration_copy.argtypes = [P, P, SZ, P]
@@ -380,6 +389,16 @@ def rk_decode_step(geom: Geom, sched: _Schedule, t: int, layers, q_ptrs, out_ptr
                             workspace.ptr, workspace.nbytes, _stream(stream))
     if rc <= 0:
         _check("rk_decode_step", rc if rc < 0 else -1)
+    return STEP_KINDS[rc]
+
+
+def rk_decode_step_overlapped(geom: Geom, sched: _Schedule, t: int, layers, q_ptrs, out_ptrs, seq_lens, max_len: int,
+                              max_recent: int, overlap: _Overlap, stream=None) -> str:
+    rc = lib.rk_decode_step_overlapped(C.byref(geom.c()), C.byref(sched), int(t), len(layers), layers, q_ptrs, out_ptrs,
+                                       _dev(seq_lens, torch.int32, "seq_lens", (geom.batch,)), int(max_len),
+                                       int(max_recent), C.byref(overlap), _stream(stream))
+    if rc <= 0:
+        _check("rk_decode_step_overlapped", rc if rc < 0 else -1)
     return STEP_KINDS[rc]
 
 

@@ -160,6 +160,28 @@ class RefreshKVModel:
         self._q_ptrs = (C.c_void_p * n)()
         self.recent_bound = 0
         self._static = False
+        self._overlap = None
+
+    def overlap_refresh(self, n_workspaces: int = 2) -> None:
+        """From now on full steps run their selections and gathers on a second stream, beside the
+        following layers' full attention (``rk_decode_step_overlapped``)."""
+        import ctypes as C
+        from .binding import _Overlap
+        n = self.n_layers
+        dev = self.out.device
+        self._side = torch.cuda.Stream(device=dev)
+        self._wss = [self.ws] + [rk.Workspace(self.geom, self.capacity, self.k_small, device=dev)
+                                 for _ in range(max(int(n_workspaces), 2) - 1)]
+        self._events = [torch.cuda.Event() for _ in range(2 * n + 1)]
+        for e in self._events:          # an event gets its handle when it is first recorded
+            e.record()
+        torch.cuda.synchronize(dev)
+        handles = [e.cuda_event for e in self._events]
+        self._ready = (C.c_void_p * n)(*handles[:n])
+        self._done = (C.c_void_p * n)(*handles[n:2 * n])
+        self._ws_ptrs = (C.c_void_p * len(self._wss))(*[w_.ptr for w_ in self._wss])
+        self._overlap = _Overlap(self._side.cuda_stream, self._ready, self._done, handles[2 * n], self._ws_ptrs,
+                                 len(self._wss), min(w_.nbytes for w_ in self._wss))
 
     def use_static_bounds(self, max_len: int, max_recent: int) -> None:
         if max_len > self.capacity:
@@ -184,8 +206,13 @@ class RefreshKVModel:
         base, step_bytes = q.data_ptr(), q.stride(0) * 2
         for l in range(n):
             self._q_ptrs[l] = base + l * step_bytes
-        kind = rk.rk_decode_step(g, self.sched, t, self._layers, self._q_ptrs, self._out_ptrs, self.seq_lens,
-                                 self.max_len, max(self.recent_bound, 1), workspace=self.ws, stream=stream)
+        if self._overlap is not None:
+            kind = rk.rk_decode_step_overlapped(g, self.sched, t, self._layers, self._q_ptrs, self._out_ptrs,
+                                                self.seq_lens, self.max_len, max(self.recent_bound, 1), self._overlap,
+                                                stream=stream)
+        else:
+            kind = rk.rk_decode_step(g, self.sched, t, self._layers, self._q_ptrs, self._out_ptrs, self.seq_lens,
+                                     self.max_len, max(self.recent_bound, 1), workspace=self.ws, stream=stream)
         if kind == "full" and not self._static:
             self.recent_bound = 0
         return kind

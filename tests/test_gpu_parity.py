@@ -609,7 +609,7 @@ def check_loop(rk, w: gen.Workload, evict_lowest=False, scores_only=False):
     return got, ref, n_diff
 
 
-def check_model_loop(rk, w: gen.Workload, n_layers: int, evict_lowest=False, scores_only=False):
+def check_model_loop(rk, w: gen.Workload, n_layers: int, evict_lowest=False, scores_only=False, overlap=False):
     """The same schedule through rk_decode_step: all layers of a step in one call."""
     dev = "cuda"
     geom = rk.Geom(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.scale)
@@ -619,6 +619,8 @@ def check_model_loop(rk, w: gen.Workload, n_layers: int, evict_lowest=False, sco
     sl = lens0.to(dev).clone()
     model = rk.RefreshKVModel(geom, kv, sl, int(lens0.max()), w.k_small, w.stride, pool_w=w.pool_w, dynamic=w.dynamic,
                               threshold=w.threshold, evict_lowest=evict_lowest, scores_only_refresh=scores_only)
+    if overlap:
+        model.overlap_refresh(2)
     q_all = torch.stack([d[1] for d in data], dim=1).to(dev).contiguous()            # [T+1, n_layers, B, Hq, D]
     nk_all = [d[2][0].to(dev) for d in data]
     nv_all = [d[2][1].to(dev) for d in data]
@@ -720,6 +722,10 @@ def test_decode_step_driver_fixed_and_dynamic(rk):
     fired = np.stack([r["full"][1:].sum(axis=0) for r in refs])
     say("  refreshes per (layer, sequence) after the initialisation:", fired.tolist())
     assert fired.min() < fired.max() or fired.max() < 5, "layers decide on their own"
+    say("decode_step driver, refresh on a second stream (native events)")
+    kinds, n_full, _ = check_model_loop(rk, gen.shrink(gen.WORKLOADS["cfg1_llama_2k"], n_steps=9), 5, overlap=True)
+    assert kinds[:5] == ["full", "partial", "partial", "partial", "full"] and (n_full == 3).all()
+    check_model_loop(rk, wq, 3, evict_lowest=True, overlap=True)
     say("decode_step driver, scores-only refresh")
     check_model_loop(rk, gen.shrink(gen.WORKLOADS["cfg1_llama_2k"], n_steps=5), 2, scores_only=True)
 

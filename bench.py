@@ -42,7 +42,7 @@ def parse():
     ap.add_argument("--no-overlap", action="store_true",
                     help="keep the selection and the gather of a full step on the main stream (default: second stream, "
                          "beside the full attention of the following layers)")
-    ap.add_argument("--overlap-workspaces", type=int, default=2, help="workspaces the overlapped refresh rotates (0: one per layer)")
+    ap.add_argument("--overlap-workspaces", type=int, default=3, help="workspaces the overlapped refresh rotates (0: one per layer)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=4, help="layers of the oracle sample")
     return ap.parse_args()

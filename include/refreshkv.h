@@ -327,7 +327,7 @@ typedef struct rk_overlap {
     void* join;                 /* one more hipEvent_t                                             */
     void* const* workspaces;    /* host array of n_workspaces device workspaces of workspace_bytes
                                    each, initialised with rk_workspace_init                        */
-    int32_t n_workspaces;       /* >= 2 to overlap (2 measured best); 1: same as rk_decode_step    */
+    int32_t n_workspaces;       /* >= 2 to overlap (3 measured best); 1: same as rk_decode_step    */
     size_t workspace_bytes;
 } rk_overlap;
 

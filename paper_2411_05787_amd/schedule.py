@@ -162,7 +162,7 @@ class RefreshKVModel:
         self._static = False
         self._overlap = None
 
-    def overlap_refresh(self, n_workspaces: int = 2) -> None:
+    def overlap_refresh(self, n_workspaces: int = 3) -> None:
         """From now on full steps run their selections and gathers on a second stream, beside the
         following layers' full attention (``rk_decode_step_overlapped``)."""
         import ctypes as C
@@ -226,13 +226,13 @@ class RefreshKVStack:
     they run beside the full attention of the following layers (in a model: beside the rest of
     the layer), and the streams join at the end of the step.  A layer's pooled scores must survive
     until its selection has read them: ``n_workspaces`` workspaces are used in turn, and the main
-    stream waits for the selection that last used a workspace before it reuses it.  Two measured
-    best at 32 layers of 32k tokens: with one per layer the second stream falls behind and its
-    kernels crowd the full attention of later layers.  Partial
+    stream waits for the selection that last used a workspace before it reuses it.  Three measured
+    best at 32 layers of 32k tokens (full step 46.8 us per layer; two: 50.0, four: 48.2, one per
+    layer: 57, where the second stream falls behind and its kernels crowd later layers).  Partial
     steps and the trigger's test steps are issued as :class:`RefreshKVLayer` issues them.
     """
 
-    def __init__(self, layers, n_workspaces: int = 2):
+    def __init__(self, layers, n_workspaces: int = 3):
         if not layers:
             raise ValueError("no layers")
         l0 = layers[0]

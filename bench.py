@@ -92,6 +92,8 @@ def main():
     setup_s = time.time() - t_setup
 
     launch = "eager" if args.no_graph else args.launch
+    if w.dynamic and launch == "graph":
+        launch = "native"      # trigger test steps enqueue both branches; the native driver also counts refreshes
     model = None
     if launch == "native":
         model = rk.RefreshKVModel(geom, kv, seq_lens, int(lens0.max()), w.k_small, w.stride, pool_w=w.pool_w,
@@ -299,6 +301,13 @@ def main():
                "full_us": round(tot["full"] / n_cpu * 1e6, 1), "refresh_us": round(tot["refresh"] / n_cpu * 1e6, 1),
                "partial_us": round(tot["partial"] / max(n_cpu * (period - 1), 1) * 1e6, 1)}
 
+    # dynamic schedule: how often a full step was taken, per layer (refresh counters kept on the GPU)
+    eff_stride = None
+    if model is not None and w.dynamic:
+        fired = (model.n_full.float().mean(dim=1) - 1.0).clamp(min=1e-9).cpu().numpy()      # minus the initialisation
+        per_layer = T / fired
+        eff_stride = {"mean": round(float(per_layer.mean()), 2), "min": round(float(per_layer.min()), 2),
+                      "max": round(float(per_layer.max()), 2), "qc_stride": w.stride, "threshold": w.threshold}
     us_per_step_layer = ms_per_step * 1e3 / n_layers
     n_full = sum(k == "full" for k in kinds)
     result = {
@@ -317,6 +326,7 @@ def main():
         "full_over_partial": round(klass["full_attn"] / klass["partial_attn"], 2),
         "full_attn_GBps": round((bytes_kv + bytes_w) / (klass["full_attn"] * 1e-6) / 1e9, 1),
         "partial_attn_GBps": round(2 * Hkv * D * 2 * (w.k_small + 1) * B / (klass["partial_attn"] * 1e-6) / 1e9, 1),
+        "effective_stride": eff_stride,
         "roofline": roofline,
         "cpu_baseline": cpu,
         "calibration_copy_bytes": calibration_bytes,

@@ -860,3 +860,30 @@ def test_full_size_one_layer_refresh_and_partial(rk, name):
         P = oracle.pooled_group_scores(wts[0, g * G:(g + 1) * G], w.pool_w)
         n_diff += assert_idx_equivalent(got["idx"][0][0, g], ref["idx"][0][0, g], P, w.context, w.k_small, "g=%d" % g)
     say("  index entries differing within the gap tolerance:", n_diff, "of", w.n_kv_heads * w.k_small)
+
+
+def test_full_size_batched_ragged(rk):
+    """Workload 4 at its real shape (16 ragged sequences, one layer): a full step, the refresh and a
+    partial step two tokens later against the oracle, per sequence."""
+    w = gen.shrink(gen.WORKLOADS["cfg4_llama_batch16_ragged"], n_layers=1, n_steps=2, stride=100)
+    lens0 = gen.seq_lens(w)
+    say("full size", w.name, "lens", lens0.tolist(), "K", w.k_small)
+    K, V = gen.make_kv(w, 0, device="cuda")
+    q = gen.make_queries(w, 0)
+    nk, nv = gen.make_new_rows(w, 0)
+    Kc, Vc = K.cpu(), V.cpu()
+    got = run_gpu_loop(rk, w, 0, K, V, q, nk, nv, lens0)
+    say("  gpu done; running oracle")
+    ref = oracle.decode_loop(gen.bf16_bits(q), gen.bf16_bits(Kc), gen.bf16_bits(Vc), gen.bf16_bits(nk),
+                             gen.bf16_bits(nv), lens0.numpy(), w.scale, w.k_small, w.stride, pool_w=w.pool_w)
+    for t in range(w.n_steps + 1):
+        assert_out_close(got["outs"][t], ref["outs"][t], "%s t=%d" % (w.name, t))
+    wts = oracle.full_attn(gen.bf16_bits(q[0]), gen.bf16_bits(Kc), gen.bf16_bits(Vc), lens0.numpy(), w.scale)[1]
+    wts = wts.astype(np.float32)
+    G, n_diff = w.group, 0
+    for b in range(w.batch):
+        n = int(lens0[b])
+        for g in range(w.n_kv_heads):
+            P = oracle.pooled_group_scores(wts[b, g * G:(g + 1) * G, :n], w.pool_w)
+            n_diff += assert_idx_equivalent(got["idx"][0][b, g], ref["idx"][0][b, g], P, n, w.k_small, "b=%d g=%d" % (b, g))
+    say("  index entries differing within the gap tolerance:", n_diff, "of", w.batch * w.n_kv_heads * w.k_small)

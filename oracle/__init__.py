@@ -26,10 +26,11 @@ ROUGE, F1) need model weights and datasets and are not reproduced: for those,
 parity unpinned.
 """
 from .bf16 import bf16_bits_to_f64, f64_to_bf16_bits
-from .steps import (full_attn, attn_scores, topk_select, gather_small_kv, partial_attn, query_sim,
+from .steps import (full_attn, attn_scores, window_votes, topk_select, gather_small_kv, partial_attn, query_sim,
                     pooled_group_scores)
 from .loop import decode_loop, is_full_step
 
-__all__ = ["bf16_bits_to_f64", "f64_to_bf16_bits", "full_attn", "attn_scores", "topk_select",
+__all__ = ["bf16_bits_to_f64", "f64_to_bf16_bits", "full_attn", "attn_scores", "window_votes",
+           "topk_select",
            "gather_small_kv", "partial_attn", "query_sim", "pooled_group_scores",
            "decode_loop", "is_full_step"]

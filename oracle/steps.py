@@ -100,6 +100,48 @@ def attn_scores(q_bits, k_bits, seq_lens, scale: float) -> Tuple[np.ndarray, np.
     return weights, lse
 
 
+def window_votes(q_win_bits, k_bits, seq_lens, scale: float) -> np.ndarray:
+    """Votes of an observation window of prompt tokens for the rows of the full cache.
+
+    Section 2.2 "Prefilling stage" initialises the small cache from the attention scores
+    of the last prompt token; Section 3 describes the SnapKV baseline as built from the
+    scores of the last few tokens of the prompt, and Appendix A.1 "Baseline Settings"
+    names the number of those tokens the observation window size (1 in all of the paper's
+    runs).  For a window of W tokens the rule of the cited work is followed: every query
+    head sums, over the W queries, the post-softmax scores each of them gives to a row.
+
+    q_win bf16 bits [B, W, Hq, D]: entry i is the query of the token at position
+    p_i = seq_lens[b] - W + i (the last entry is the last prompt token); entries with
+    p_i < 0 do not exist and are ignored.  Attention is causal: query i sees rows
+    0..p_i, its own row included.
+
+        votes[b,h,j] = sum over i with p_i >= j of  exp(s_ij) / sum_{j' <= p_i} exp(s_ij'),
+        s_ij = scale * <q_win[b,i,h], K[b,g(h),j]>
+
+    W = 1 gives the scores a_L of the last token (``attn_scores``).  Returns fp64
+    [B, Hq, max(seq_lens)], zero beyond each length.
+    """
+    qw = bf16_bits_to_f64(q_win_bits)
+    B, W, Hq, D = qw.shape
+    Hkv = k_bits.shape[1]
+    G = Hq // Hkv
+    lens = np.asarray(seq_lens, dtype=np.int64)
+    width = int(lens.max()) if B else 0
+    votes = np.zeros((B, Hq, width), dtype=np.float64)
+    for b in range(B):
+        n = int(lens[b])
+        for i in range(W):
+            pos = n - W + i
+            if pos < 0:
+                continue
+            for h in range(Hq):
+                keys = bf16_bits_to_f64(k_bits[b, h // G, :pos + 1])
+                s = scale * (keys @ qw[b, i, h])
+                e = np.exp(s - s.max())
+                votes[b, h, :pos + 1] += e / e.sum()
+    return votes
+
+
 def pooled_group_scores(weights_row_group: np.ndarray, pool_w: int, agg: str = "max") -> np.ndarray:
     """Scores that rank the tokens of one (sequence, KV head).
 

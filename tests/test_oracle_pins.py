@@ -526,3 +526,46 @@ def test_dynamic_trigger_in_loop():
     res = oracle.decode_loop(x["q"][:, :1], x["K"][:1], x["V"][:1], x["nk"][:, :1], x["nv"][:, :1], [21], 0.4, 5, 2,
                              dynamic=True, threshold=0.9)
     assert res["full"][:, 0].tolist() == [True, False, True, False, True, False, True, False, True]
+
+
+def test_window_votes_match_pure_python_and_closed_forms():
+    """Observation window of W prompt tokens (Section 2.2 "Prefilling stage"; Section 3 on the
+    SnapKV baseline; Appendix A.1 "Baseline Settings"): per query head, the sum over the
+    window's queries of the causal post-softmax scores."""
+    rng = np.random.default_rng(77)
+    B, W, Hq, Hkv, D, cap = 2, 3, 4, 2, 8, 12
+    lens = [10, 2]                                             # the second prompt is shorter than the window
+    qw, K = rand_bits(rng, (B, W, Hq, D)), rand_bits(rng, (B, Hkv, cap, D), 1.5)
+    votes = oracle.window_votes(qw, K, lens, 0.41)
+    assert votes.shape == (B, Hq, 10)
+    for b in range(B):
+        for h in range(Hq):
+            want = [0.0] * 10
+            for i in range(W):
+                pos = lens[b] - W + i                          # query i sits at this position
+                if pos < 0:
+                    continue
+                keys = val(K[b, h // 2, :pos + 1]).tolist()
+                _, a, _ = brute_attention(val(qw[b, i, h]).tolist(), keys, keys, 0.41)
+                for j in range(pos + 1):
+                    want[j] += a[j]
+            assert np.allclose(votes[b, h], want, rtol=1e-12, atol=1e-300)
+    # every existing query hands out one vote in all: 3 for the long prompt, 2 for the short one
+    assert np.allclose(votes[0].sum(axis=1), 3.0, rtol=1e-12)
+    assert np.allclose(votes[1].sum(axis=1), 2.0, rtol=1e-12)
+    # equal keys: query at position p gives 1/(p+1) to rows 0..p, so row j collects a harmonic tail
+    Ku = bits(np.ones((1, 1, 9, 2)))
+    qu = rand_bits(rng, (1, 4, 1, 2))
+    vu = oracle.window_votes(qu, Ku, [9], 2.0)[0, 0]
+    for j in range(9):
+        assert abs(vu[j] - sum(1.0 / (p + 1) for p in range(5, 9) if p >= j)) < 1e-14
+    # causality: the last row is seen by the last query only; a window of one is the plain score pass
+    one, _ = oracle.attn_scores(qw[:, -1], K, lens, 0.41)
+    assert np.array_equal(oracle.window_votes(qw[:, -1:], K, lens, 0.41), one)
+    last = oracle.window_votes(qw, K, lens, 0.41)[0, :, 9]
+    assert np.allclose(last, one[0, :, 9], rtol=1e-14)
+    # a dominant key inside every query's view collects the whole window
+    Kd = np.zeros((1, 1, 6, 2)); Kd[0, 0, 1] = [40.0, 0.0]
+    qd = bits(np.tile([[1.0, 0.0]], (1, 3, 1, 1)))
+    vd = oracle.window_votes(qd, bits(Kd), [6], 1.0)[0, 0]
+    assert abs(vd[1] - 3.0) < 1e-12 and vd[[0, 2, 3, 4, 5]].max() < 1e-15

@@ -201,12 +201,21 @@ def main():
 
     out = layers[0].out
     Lb = max_len_bound
+    gw = torch.Generator(device="cuda").manual_seed(4242)
+    q_win = torch.randn(w.batch, 32, w.n_q_heads, w.head_dim, generator=gw, device="cuda").to(torch.bfloat16)
+    q_win1 = q_win[:, -1:].contiguous()
     klass = {
         "full_attn": graph_us(lambda l: rk.rk_full_attn(geom, q_cur[l], *kv[l], seq_lens, Lb, out, weights=weights, workspace=ws)),
         "full_attn_select": graph_us(lambda l: rk.rk_full_attn_select(geom, q_cur[l], *kv[l], seq_lens, Lb, out, w.k_small, w.pool_w,
                                                                        layers[l].idx, workspace=ws)),
         "score_select": graph_us(lambda l: rk.rk_score_select(geom, q_cur[l], kv[l][0], seq_lens, Lb, w.k_small, w.pool_w,
                                                                layers[l].idx, workspace=ws)),
+        # prefill-side initialisation from an observation window of 1 and of 32 prompt tokens (the queries
+        # are synthetic; the window ends at the current length)
+        "window_select_w1": graph_us(lambda l: rk.rk_window_select(geom, q_win1, kv[l][0], seq_lens, Lb, w.k_small, w.pool_w,
+                                                                   layers[l].idx, workspace=ws)),
+        "window_select_w32": graph_us(lambda l: rk.rk_window_select(geom, q_win, kv[l][0], seq_lens, Lb, w.k_small, w.pool_w,
+                                                                    layers[l].idx, workspace=ws)),
         "topk_select": graph_us(lambda l: rk.rk_topk_select(geom, weights, seq_lens, Lb, w.k_small, w.pool_w, layers[l].idx, workspace=ws)),
         "gather_small_kv": graph_us(lambda l: rk.rk_gather_small_kv(geom, *kv[l], layers[l].idx, w.k_small, layers[l].small_K, layers[l].small_V)),
         "partial_attn": graph_us(lambda l: rk.rk_partial_attn(geom, q_cur[l], layers[l].small_K, layers[l].small_V, w.k_small, *kv[l],

@@ -16,6 +16,8 @@
  *   rk_full_attn_select the two steps above in one call (what a full step of the method does)
  *   rk_score_select     scores over C_f and the selection without the attention output
  *                       (Section 4.3, the "w/o full attention" setting)
+ *   rk_window_select    the selection from the scores of the last W prompt tokens: how C_p
+ *                       starts after the prefill (Section 2.2 "Prefilling stage"; Appendix A.1)
  *   rk_gather_small_kv  rebuild C_p from the selected rows of C_f         (Section 2.2)
  *   rk_partial_attn     partial-attention step over C_p plus the tokens decoded since the
  *                       refresh                      (Section 2.2, "Decoding with partial cache")
@@ -68,6 +70,7 @@ typedef enum rk_status {
 #define RK_MAX_GROUP 8
 #define RK_MAX_K 16384         /* largest small-cache size rk_topk_select accepts              */
 #define RK_MAX_POOL_W 63       /* largest (odd) max-pool window                                */
+#define RK_MAX_WINDOW 32       /* largest observation window rk_window_select accepts          */
 
 /* Geometry of one attention layer; `scale` multiplies q.k before the softmax. */
 typedef struct rk_geom {
@@ -207,6 +210,31 @@ int rk_score_select(const rk_geom* geom, const void* q, rk_kv full,
                     int32_t* idx, float* sel_scores,
                     const int32_t* pred, int32_t pred_val,
                     void* workspace, size_t workspace_bytes, void* stream);
+
+/* Prefill-side initialisation of the small cache from an observation window (Section 2.2
+ * "Prefilling stage": the small cache starts from the attention scores of the last prompt token;
+ * Section 3 describes the SnapKV baseline as the tokens with high scores from the last few tokens
+ * of the prompt, and Appendix A.1 "Baseline Settings" calls their number the observation window
+ * size: 1 in the paper's runs, where this call selects what rk_score_select selects).
+ *   q_win   bf16 [batch, window, n_q_heads, 128]: entry i is the query of the prompt token at
+ *           position p_i = seq_lens[b] - window + i, so the last entry belongs to the last prompt
+ *           token.  Entries with p_i < 0 (prompt shorter than the window) are ignored.
+ *   full    the full cache with the whole prompt appended; only full.k is read (full.v may be NULL)
+ *   votes[b,h,j] = sum_i softmax_{j' <= p_i}(scale * <q_win[b,i,h,:], K[b,g,j',:]>)[j]   (causal:
+ *           query i sees rows 0..p_i), the rule of the cited work for a window of several queries.
+ *           Optional output, fp32 [batch, n_q_heads, v_stride], v_stride >= max_len; positions
+ *           >= seq_lens[b] are not written.  NULL: kept in the workspace only.
+ *   idx, sel_scores, k, pool_w, agg: the selection of rk_topk_select applied to the votes; all
+ *           rows of the prompt compete, the window's own rows included.
+ *   1 <= window <= RK_MAX_WINDOW (RK_ERR_UNSUPPORTED beyond).  The other arguments as in
+ *   rk_score_select.  K is read twice (log-sum-exp of every query first, votes second). */
+int rk_window_select(const rk_geom* geom, const void* q_win, int32_t window, rk_kv full,
+                     const int32_t* seq_lens, int32_t max_len,
+                     float* votes, int64_t v_stride,
+                     int32_t k, int32_t pool_w, int32_t agg,
+                     int32_t* idx, float* sel_scores,
+                     const int32_t* pred, int32_t pred_val,
+                     void* workspace, size_t workspace_bytes, void* stream);
 
 /* Rebuild the small cache: small.k[b,g,i,:] = full.k[b,g,idx[b,g,i],:] and the same for v, for
  * every i < k with idx >= 0 (bit copies).  Slots whose idx is negative are left untouched.

@@ -16,7 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "librefreshkv.so")
 
 EXPORTS = ["rk_version", "rk_status_string", "rk_workspace_bytes", "rk_workspace_init",
-           "rk_full_attn", "rk_full_attn_scores", "rk_topk_select", "rk_full_attn_select", "rk_full_attn_pool", "rk_select_pooled", "rk_score_select", "rk_gather_small_kv", "rk_partial_attn", "rk_partial_attn_fixed", "rk_decode_step", "rk_decode_step_overlapped",
+           "rk_full_attn", "rk_full_attn_scores", "rk_topk_select", "rk_full_attn_select", "rk_full_attn_pool", "rk_select_pooled", "rk_score_select", "rk_window_select", "rk_gather_small_kv", "rk_partial_attn", "rk_partial_attn_fixed", "rk_decode_step", "rk_decode_step_overlapped",
            "rk_query_sim", "rk_mark_refresh", "rk_calibration_copy"]
 
 RK_AGG_MAX, RK_AGG_MEAN, RK_AGG_FIRST = 0, 1, 2
@@ -87,6 +87,8 @@ def _load(path: str = LIB_PATH) -> C.CDLL:
     l.rk_select_pooled.argtypes = [G, P, I32, I32, P, P, P, I32, P, SZ, P]
     l.rk_score_select.argtypes = [G, P, _Kv, P, I32, P, I64, P, I32, I32, I32, P, P, P, I32, P, SZ, P]
     l.rk_score_select.restype = C.c_int
+    l.rk_window_select.argtypes = [G, P, I32, _Kv, P, I32, P, I64, I32, I32, I32, P, P, P, I32, P, SZ, P]
+    l.rk_window_select.restype = C.c_int
     l.rk_gather_small_kv.argtypes = [G, _Kv, P, I32, _Kv, P, P, P, I32, P]
     l.rk_partial_attn.restype = C.c_int
     l.rk_partial_attn.argtypes = [G, P, _Kv, I32, _Kv, P, P, I32, P, P, I32, P, SZ, P]
@@ -322,6 +324,34 @@ def rk_score_select(geom: Geom, q, K, seq_lens, max_len: int, k: int, pool_w: in
         _dev(seq_lens, torch.int32, "seq_lens", (B,)), int(max_len),
         _dev(weights, torch.float32, "weights", optional=True), w_stride,
         _dev(lse, torch.float32, "lse", (B, Hq), optional=True),
+        int(k), int(pool_w), int(agg),
+        _dev(idx, torch.int32, "idx", (B, Hkv, k)),
+        _dev(sel_scores, torch.float32, "sel_scores", (B, Hkv, k), optional=True),
+        _dev(pred, torch.int32, "pred", (B,), optional=True), int(pred_val),
+        workspace.ptr, workspace.nbytes, _stream(stream)))
+
+
+def rk_window_select(geom: Geom, q_win, K, seq_lens, max_len: int, k: int, pool_w: int, idx,
+                     votes=None, sel_scores=None, agg: int = RK_AGG_MAX,
+                     pred=None, pred_val: int = 0, workspace: Workspace = None, stream=None) -> None:
+    """q_win: bf16 [B, W, Hq, D], the queries of the last W prompt tokens; K: bf16 [B, Hkv, capacity, D]."""
+    B, Hq, Hkv, D = geom.batch, geom.n_q_heads, geom.n_kv_heads, geom.head_dim
+    if q_win.dim() != 4:
+        raise ValueError("q_win must be [batch, window, n_q_heads, head_dim]")
+    W = q_win.shape[1]
+    if max_len > K.shape[2]:
+        raise ValueError("max_len %d exceeds the cache capacity %d" % (max_len, K.shape[2]))
+    v_stride = 0
+    if votes is not None:
+        if votes.dim() != 3 or votes.shape[0] != B or votes.shape[1] != Hq or votes.shape[2] < max_len:
+            raise ValueError("votes must be [batch, n_q_heads, >= max_len]")
+        v_stride = votes.shape[2]
+    kv = _kv(geom, K, K, "full")
+    kv.v = None
+    _check("rk_window_select", lib.rk_window_select(
+        C.byref(geom.c()), _dev(q_win, torch.bfloat16, "q_win", (B, W, Hq, D)), int(W), kv,
+        _dev(seq_lens, torch.int32, "seq_lens", (B,)), int(max_len),
+        _dev(votes, torch.float32, "votes", optional=True), v_stride,
         int(k), int(pool_w), int(agg),
         _dev(idx, torch.int32, "idx", (B, Hkv, k)),
         _dev(sel_scores, torch.float32, "sel_scores", (B, Hkv, k), optional=True),

@@ -171,6 +171,14 @@ __attribute__((visibility("hidden")))
 int gather_stage(const rk_geom* geom, rk_kv full, const int32_t* idx, int32_t k, rk_kv small,
                  const int32_t* seq_lens, int32_t* tail_start, int32_t* n_refresh,
                  const int32_t* pred, int32_t pred_val, hipStream_t stream);
+//   pool_stage: group aggregation, max-pool and histogram of normalised per-head scores (first
+//     kernel of rk_topk_select); check_select_args: the limits on k, pool_w and agg.
+__attribute__((visibility("hidden")))
+int pool_stage(const rk_geom* geom, const float* weights, int64_t w_stride, const int32_t* seq_lens,
+               int32_t max_len, int32_t pool_w, int32_t agg, const int32_t* pred, int32_t pred_val,
+               const Workspace& ws, hipStream_t st);
+__attribute__((visibility("hidden")))
+int check_select_args(int32_t k, int32_t pool_w, int32_t agg);
 __attribute__((visibility("hidden")))
 int select_stage(const rk_geom* geom, const int32_t* seq_lens, int32_t max_len, int32_t k, int32_t* idx,
                  float* sel_scores, const int32_t* pred, int32_t pred_val, const Workspace& ws, hipStream_t st);

@@ -523,7 +523,18 @@ using namespace rk;
 
 namespace rk {
 
-static int check_select_args(int32_t k, int32_t pool_w, int32_t agg) {
+int pool_stage(const rk_geom* geom, const float* weights, int64_t w_stride, const int32_t* seq_lens,
+               int32_t max_len, int32_t pool_w, int32_t agg, const int32_t* pred, int32_t pred_val,
+               const Workspace& ws, hipStream_t st) {
+    const int G = geom->n_q_heads / geom->n_kv_heads;
+    dim3 pgrid((max_len + kPoolTile - 1) / kPoolTile, geom->n_kv_heads, geom->batch);
+    hipLaunchKernelGGL(pool_hist_kernel, pgrid, dim3(256), 0, st, weights, w_stride, seq_lens, max_len,
+                       geom->n_q_heads, geom->n_kv_heads, G, (pool_w - 1) / 2, agg, ws.pooled, pooled_row_stride(max_len), ws.hist,
+                       pred, pred_val);
+    return launch_status();
+}
+
+int check_select_args(int32_t k, int32_t pool_w, int32_t agg) {
     if (pool_w < 1 || (pool_w & 1) == 0) return RK_ERR_INVALID_ARG;
     if (pool_w > RK_MAX_POOL_W || k > RK_MAX_K || agg < RK_AGG_MAX || agg > RK_AGG_FIRST) return RK_ERR_UNSUPPORTED;
     return RK_OK;
@@ -566,12 +577,7 @@ extern "C" int rk_topk_select(const rk_geom* geom, const float* weights, int64_t
     Workspace ws;
     if ((rc = check_workspace(geom, max_len, k, workspace, workspace_bytes, &ws)) != RK_OK) return rc;
     hipStream_t st = (hipStream_t)stream;
-    const int G = geom->n_q_heads / geom->n_kv_heads;
-    dim3 pgrid((max_len + kPoolTile - 1) / kPoolTile, geom->n_kv_heads, geom->batch);
-    hipLaunchKernelGGL(pool_hist_kernel, pgrid, dim3(256), 0, st, weights, w_stride, seq_lens, max_len,
-                       geom->n_q_heads, geom->n_kv_heads, G, (pool_w - 1) / 2, agg, ws.pooled, pooled_row_stride(max_len), ws.hist,
-                       pred, pred_val);
-    if ((rc = launch_status()) != RK_OK) return rc;
+    if ((rc = pool_stage(geom, weights, w_stride, seq_lens, max_len, pool_w, agg, pred, pred_val, ws, st)) != RK_OK) return rc;
     return select_stage(geom, seq_lens, max_len, k, idx, sel_scores, pred, pred_val, ws, st);
 }
 

@@ -104,6 +104,15 @@ def test_host_side_argument_checks_return_before_any_launch(rk):
     assert score(k=0) == -1
     assert score(ws=None) == -3
     assert full(kv=kv_k_only) == -1                                      # a full step needs the values
+    window = lambda **kw: lib.rk_window_select(C.byref(g), kw.get("q", fake), kw.get("w", 8), kv_k_only, fake, 4096, None, 0,
+                                               kw.get("k", 256), 7, 0, kw.get("idx", fake), None, None, 0,
+                                               kw.get("ws", 0x100000), ws_bytes, None)
+    assert window(q=None) == -1
+    assert window(w=0) == -1
+    assert window(w=33) == -2                                            # beyond RK_MAX_WINDOW
+    assert window(idx=None) == -1
+    assert window(k=0) == -1
+    assert window(ws=None) == -3
     assert lib.rk_gather_small_kv(C.byref(g), kv, None, 16, kv, None, None, None, 0, None) == -1
     assert lib.rk_gather_small_kv(C.byref(g), kv, fake, 0, kv, None, None, None, 0, None) == -1
     assert lib.rk_gather_small_kv(C.byref(g), kv, fake, 16, kv, None, fake, None, 0, None) == -1   # tail_start without seq_lens

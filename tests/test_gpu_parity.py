@@ -696,6 +696,55 @@ def test_score_select_matches_oracle(rk):
                     assert_idx_equivalent(idx_n[b, g], i_ref[b, g], P, n, k, "%s b=%d g=%d" % (name, b, g))
 
 
+def test_window_select_matches_oracle(rk):
+    """rk_window_select: votes of the last W prompt tokens (causal, summed per head) and the selection
+    on them; W = 1 must select what rk_score_select selects."""
+    cases = [("llama_w8", 2, 32, 8, [3100, 1029], 3200, 256, 7, 8), ("qwen_g7_w5", 1, 28, 4, [2500], 2560, 128, 7, 5),
+             ("g8_w32_short_empty", 3, 16, 2, [130, 0, 5], 256, 16, 1, 32), ("w1", 1, 8, 2, [5000], 5056, 64, 7, 1),
+             ("two_rounds_w32", 1, 4, 1, [40000], 40064, 512, 7, 32), ("mha_w3", 1, 4, 4, [700], 768, 32, 7, 3),
+             ("g3_w4", 1, 6, 2, [1000], 1024, 50, 7, 4)]
+    for name, B, Hq, Hkv, lens, cap, k, pool_w, W in cases:
+        say("window_select case", name)
+        _, K, _ = rand_case(500 + len(name), B, Hq, Hkv, cap)
+        gq = torch.Generator().manual_seed(900 + W)
+        qw = torch.randn(B, W, Hq, 128, generator=gq).to(torch.bfloat16)
+        K[:, :, ::97] *= 3.0
+        for b in range(B):
+            K[b, :, lens[b]:] = float("nan")             # rows past the end must not matter
+        scale = float(np.float32(1 / np.sqrt(128)))
+        geom = rk.Geom(B, Hq, Hkv, 128, scale)
+        ws = rk.Workspace(geom, cap, k)
+        sl = torch.tensor(lens, dtype=torch.int32, device="cuda")
+        v_ref = oracle.window_votes(gen.bf16_bits(qw), gen.bf16_bits(K), lens, scale)
+        i_ref, _ = oracle.topk_select(v_ref.astype(np.float32), lens, Hkv, k, pool_w)
+        G = Hq // Hkv
+        max_len = max(max(lens), 1)
+        for want_v in (True, False):
+            vt = torch.full((B, Hq, cap), -7.0, dtype=torch.float32, device="cuda") if want_v else None
+            idx = torch.full((B, Hkv, k), -5, dtype=torch.int32, device="cuda")
+            rk.rk_window_select(geom, qw.cuda(), K.cuda(), sl, max_len, k, pool_w, idx, votes=vt, workspace=ws)
+            torch.cuda.synchronize()
+            idx_n = idx.cpu().numpy()
+            for b in range(B):
+                n = lens[b]
+                if n == 0:
+                    assert (idx_n[b] == -1).all()
+                    continue
+                if want_v:
+                    vn = vt[b].cpu().numpy()
+                    assert (np.abs(vn[:, :n] - v_ref[b, :, :n]) / v_ref[b, :, :n]).max() < 1e-5
+                    assert (vn[:, n:] == -7.0).all()
+                for g in range(Hkv):
+                    P = oracle.pooled_group_scores(v_ref[b, g * G:(g + 1) * G, :n].astype(np.float32), pool_w)
+                    assert_idx_equivalent(idx_n[b, g], i_ref[b, g], P, n, k, "%s b=%d g=%d" % (name, b, g))
+        if W == 1:
+            idx1 = torch.full((B, Hkv, k), -5, dtype=torch.int32, device="cuda")
+            rk.rk_score_select(geom, qw[:, 0].contiguous().cuda(), K.cuda(), sl, max_len, k, pool_w, idx1, workspace=ws)
+            torch.cuda.synchronize()
+            P = oracle.pooled_group_scores(v_ref[0, :G, :lens[0]].astype(np.float32), pool_w)
+            assert_idx_equivalent(idx1.cpu().numpy()[0, 0], idx_n[0, 0], P, lens[0], k, "w1 vs score_select")
+
+
 def test_loop_scores_only_refresh(rk):
     """Section 4.3 "w/o full attention": refresh steps attend to the rebuilt small cache alone."""
     w = gen.shrink(gen.WORKLOADS["cfg1_llama_2k"], n_steps=12)

@@ -92,6 +92,23 @@ class RefreshKVLayer:
             rk.rk_partial_attn(g, q, self.small_K, self.small_V, self.k_small, self.K, self.V, self.tail_start,
                                self.seq_lens, 1, out, pred=pred, pred_val=1, workspace=self.ws, stream=stream)
 
+    def prefill_init(self, q_win: torch.Tensor, stream=None) -> None:
+        """Start the small cache right after the prefill (Section 2.2, "Prefilling stage"): q_win
+        bf16 [B, W, Hq, D] holds the queries of the last W prompt tokens (W = 1 in the paper), whose
+        rows are already in the full cache.  Selection from their votes, gather, tail_start <-
+        seq_lens; with the dynamic trigger the last prompt token's query becomes the reference.
+        Produces no attention output: that is the prefill's."""
+        g = self.geom
+        if self.dynamic:
+            rk.rk_query_sim(g, q_win[:, -1].contiguous(), self.q_ref, self.threshold, True, self.sim, self.need_full,
+                            stream=stream)
+        rk.rk_window_select(g, q_win, self.K, self.seq_lens, self.max_len, self.k_small, self.pool_w, self.idx,
+                            workspace=self.ws, stream=stream)
+        rk.rk_gather_small_kv(g, self.K, self.V, self.idx, self.k_small, self.small_K, self.small_V,
+                              seq_lens=self.seq_lens, tail_start=self.tail_start, stream=stream)
+        if not self._static:
+            self.recent_bound = 0
+
     def _partial(self, q, out, pred=None, stream=None) -> None:
         fn = rk.rk_partial_attn_fixed if self.evict_lowest else rk.rk_partial_attn
         fn(self.geom, q, self.small_K, self.small_V, self.k_small, self.K, self.V, self.tail_start,

@@ -745,6 +745,34 @@ def test_window_select_matches_oracle(rk):
             assert_idx_equivalent(idx1.cpu().numpy()[0, 0], idx_n[0, 0], P, lens[0], k, "w1 vs score_select")
 
 
+def test_prefill_init_window_one_equals_initial_full_step(rk):
+    """Section 2.2 "Prefilling stage": with an observation window of one, starting the small cache
+    from the last prompt token's query is what the t = 0 full step of the schedule does."""
+    from paper_2411_05787_amd.schedule import RefreshKVLayer
+    B, Hq, Hkv, cap, k = 2, 16, 4, 2304, 96
+    lens = [2200, 517]
+    q, K, V = rand_case(77, B, Hq, Hkv, cap)
+    geom = rk.Geom(B, Hq, Hkv, 128, float(np.float32(1 / np.sqrt(128))))
+    layers = []
+    for _ in range(2):
+        sl = torch.tensor(lens, dtype=torch.int32, device="cuda")
+        layers.append(RefreshKVLayer(geom, K.cuda(), V.cuda(), sl, max(lens), k, 4, dynamic=True, threshold=0.5))
+    layers[0].step(0, q.cuda())
+    layers[1].prefill_init(q[:, None].contiguous().cuda())
+    torch.cuda.synchronize()
+    a, b = layers
+    w_ref, _ = oracle.attn_scores(gen.bf16_bits(q), gen.bf16_bits(K), lens, geom.scale)
+    ia, ib = a.idx.cpu().numpy(), b.idx.cpu().numpy()
+    for bi in range(B):
+        for g in range(Hkv):
+            P = oracle.pooled_group_scores(w_ref[bi, g * 4:(g + 1) * 4, :lens[bi]].astype(np.float32), 7)
+            assert_idx_equivalent(ib[bi, g], ia[bi, g], P, lens[bi], k, "b=%d g=%d" % (bi, g))
+    same = torch.from_numpy(ia == ib).cuda()                 # rows may differ only where near-ties swapped
+    assert same.float().mean().item() > 0.95
+    assert torch.equal(a.small_K[same], b.small_K[same]) and torch.equal(a.small_V[same], b.small_V[same])
+    assert torch.equal(a.tail_start, b.tail_start) and torch.equal(a.q_ref, b.q_ref)
+
+
 def test_loop_scores_only_refresh(rk):
     """Section 4.3 "w/o full attention": refresh steps attend to the rebuilt small cache alone."""
     w = gen.shrink(gen.WORKLOADS["cfg1_llama_2k"], n_steps=12)

@@ -29,8 +29,9 @@ from .bf16 import bf16_bits_to_f64, f64_to_bf16_bits
 from .steps import (full_attn, attn_scores, window_votes, topk_select, gather_small_kv, partial_attn, query_sim,
                     pooled_group_scores)
 from .loop import decode_loop, is_full_step
+from .h2o import h2o_decode_loop
 
 __all__ = ["bf16_bits_to_f64", "f64_to_bf16_bits", "full_attn", "attn_scores", "window_votes",
            "topk_select",
            "gather_small_kv", "partial_attn", "query_sim", "pooled_group_scores",
-           "decode_loop", "is_full_step"]
+           "decode_loop", "is_full_step", "h2o_decode_loop"]

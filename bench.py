@@ -204,7 +204,29 @@ def main():
     gw = torch.Generator(device="cuda").manual_seed(4242)
     q_win = torch.randn(w.batch, 32, w.n_q_heads, w.head_dim, generator=gw, device="cuda").to(torch.bfloat16)
     q_win1 = q_win[:, -1:].contiguous()
+    # the H2O comparison policy at the same budget K (K/2 recent): one state per layer, caches full
+    h2o_cap = w.k_small + 1
+    h2o = []
+    for l in range(n_layers):
+        cK = torch.randn(B, Hkv, h2o_cap, D, generator=gw, device="cuda").to(torch.bfloat16)
+        cV = torch.randn(B, Hkv, h2o_cap, D, generator=gw, device="cuda").to(torch.bfloat16)
+        tot = torch.rand(B, Hkv, h2o_cap, generator=gw, device="cuda")
+        hpos = torch.arange(h2o_cap, dtype=torch.int32, device="cuda").expand(B, Hkv, h2o_cap).contiguous()
+        n_rows = torch.full((B,), w.k_small, dtype=torch.int32, device="cuda")
+        keep = (cK, cV, tot, hpos, n_rows, torch.zeros(B, dtype=torch.int32, device="cuda"))
+        h2o.append((rk.h2o_state(geom, *keep), keep))
+    h2o_lens = torch.full((B,), h2o_cap, dtype=torch.int32, device="cuda")
+    h2o_new = torch.randn(2, B, Hkv, D, generator=gw, device="cuda").to(torch.bfloat16)
+
+    def h2o_call(l):
+        if l == 0:
+            h2o_lens.add_(1)                  # one decoding step further: a new position for the new token
+        rk.rk_h2o_step(geom, h2o[l][0], q_cur[l], h2o_new[0], h2o_new[1], h2o_lens, w.k_small, w.k_small // 2, out,
+                       workspace=ws)
+
     klass = {
+        "full_attn_no_weights": graph_us(lambda l: rk.rk_full_attn(geom, q_cur[l], *kv[l], seq_lens, Lb, out, workspace=ws)),
+        "h2o_step": graph_us(h2o_call),
         "full_attn": graph_us(lambda l: rk.rk_full_attn(geom, q_cur[l], *kv[l], seq_lens, Lb, out, weights=weights, workspace=ws)),
         "full_attn_select": graph_us(lambda l: rk.rk_full_attn_select(geom, q_cur[l], *kv[l], seq_lens, Lb, out, w.k_small, w.pool_w,
                                                                        layers[l].idx, workspace=ws)),
@@ -332,6 +354,12 @@ def main():
         "step_us_per_layer": {k: round(v, 2) for k, v in med.items()},
         "step_us_per_layer_p10_p90": spread,
         "call_us_per_layer": {k: round(v, 2) for k, v in klass.items()},
+        # attention time per (step, layer) of the paper's comparison systems at kernel level (Table 1, "Time"):
+        # vanilla = full attention at every step; StreamingLLM and SnapKV = the partial step at every step;
+        # H2O = attention over K + 1 rows with the scores returned + its bookkeeping; RefreshKV = `value`
+        "policy_us_per_layer": {"vanilla": round(klass["full_attn_no_weights"], 2),
+                                "streaming_llm_or_snapkv": round(klass["partial_attn"], 2),
+                                "h2o": round(klass["h2o_step"], 2), "refreshkv": round(us_per_step_layer, 2)},
         "full_over_partial": round(klass["full_attn"] / klass["partial_attn"], 2),
         "full_attn_GBps": round((bytes_kv + bytes_w) / (klass["full_attn"] * 1e-6) / 1e9, 1),
         "partial_attn_GBps": round(2 * Hkv * D * 2 * (w.k_small + 1) * B / (klass["partial_attn"] * 1e-6) / 1e9, 1),

@@ -298,6 +298,50 @@ int rk_calibration_copy(void* dst, const void* src, size_t bytes, void* stream);
 int rk_mark_refresh(const rk_geom* geom, const int32_t* seq_lens, int32_t* tail_start,
                     const int32_t* pred, int32_t pred_val, void* stream);
 
+/* ---- the H2O comparison policy on the same attention step --------------------------------- */
+
+/* H2O (Section 3 "Comparison systems": the recent tokens plus dynamically updated "heavy hitters",
+ * the tokens with high cumulative attention scores; Appendix A.1 "Baseline Settings": K/2 each, the
+ * scores aggregated over a GQA group by max as for the paper's own method; Section 4.1: it needs
+ * the attention scores at every decoding step, which is what makes it slow).  Per (sequence, KV
+ * head) and step: the new token joins the cache; the step attends over the whole cache and every
+ * cached token adds the aggregated score it received to its running total (fp32); if the cache
+ * then holds more than `budget` tokens, the one with the lowest total among those whose position
+ * is <= newest - recent is dropped for good (equal totals: the older one).
+ * State, all caller-owned device memory.  Slots are dense ([0, n_rows)) but not in token order:
+ * the newest token moves into the slot of the dropped one. */
+typedef struct rk_h2o_state {
+    rk_kv cache;           /* rows of the kept tokens; capacity >= budget + 1                   */
+    float* total;          /* fp32 [batch, n_kv_heads, cache.capacity]: running totals          */
+    int32_t* pos;          /* int32 [batch, n_kv_heads, cache.capacity]: token position per slot */
+    int32_t* n_rows;       /* int32 [batch]: tokens kept (the same for every head)              */
+    int32_t* n_attend;     /* int32 [batch]: rows the current step attends over (written by
+                              rk_h2o_append, read by the attention and by rk_h2o_update)        */
+} rk_h2o_state;
+
+/* The three parts of a step; rk_h2o_step enqueues all of them.
+ *   rk_h2o_append  rows k_new, v_new (bf16 [batch, n_kv_heads, 128]) go to slot n_rows[b] with
+ *                  total 0 and position seq_lens[b] - 1 (seq_lens: tokens so far, the new one
+ *                  included); n_attend[b] = n_rows[b] + 1.
+ *   (attention)    rk_full_attn over state.cache with seq_lens = state.n_attend, max_len =
+ *                  budget + 1 and `weights` returned.
+ *   rk_h2o_update  totals += aggregate over the group of weights[b,h,j] ([batch, n_q_heads,
+ *                  w_stride] fp32, w_stride >= budget + 1), drop rule, n_rows[b] updated;
+ *                  dropped (optional, int32 [batch, n_kv_heads]) gets the position dropped or -1.
+ *   rk_h2o_step    the three in one call; the scores pass through `workspace`
+ *                  (rk_workspace_bytes(geom, budget + 1, 0) or more).  out bf16 [batch,
+ *                  n_q_heads, 128].
+ * 0 <= recent < budget; agg as in rk_topk_select. */
+int rk_h2o_append(const rk_geom* geom, rk_h2o_state state, const void* k_new, const void* v_new,
+                  const int32_t* seq_lens, int32_t budget, void* stream);
+int rk_h2o_update(const rk_geom* geom, rk_h2o_state state, const float* weights, int64_t w_stride,
+                  int32_t budget, int32_t recent, int32_t agg, int32_t* dropped, void* stream);
+int rk_h2o_step(const rk_geom* geom, rk_h2o_state state, const void* q,
+                const void* k_new, const void* v_new, const int32_t* seq_lens,
+                int32_t budget, int32_t recent, int32_t agg,
+                void* out, int32_t* dropped,
+                void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---- one decode step of a whole model --------------------------------------------------- */
 
 /* Per-layer state of the method: everything is caller-owned device memory. */

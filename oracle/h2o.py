@@ -34,7 +34,9 @@ def h2o_decode_loop(q_steps_bits, k0_bits, v0_bits, total0, pos0, n0, new_k_bits
     with query q_steps_bits[t,b] and new rows new_k_bits[t,b], new_v_bits[t,b] ([T,B,Hkv,D]).
 
     Returns outs (bf16 bits [T,B,Hq,D]), dropped (int64 [T,B,Hkv]: position dropped at that
-    step, -1 if none), and the final caches as lists over (b, g) of dicts position -> total.
+    step, -1 if none), margin ([T,B,Hkv]: by how much, relative, the runner-up's total exceeded
+    the dropped token's; inf where nothing or the only candidate was dropped) and the final
+    caches as lists over (b, g) of dicts position -> total.
     """
     if agg not in ("max", "mean", "first"):
         raise ValueError("agg must be max, mean or first")
@@ -53,6 +55,7 @@ def h2o_decode_loop(q_steps_bits, k0_bits, v0_bits, total0, pos0, n0, new_k_bits
         cache.append(per_head)
     outs = np.zeros((T, B, Hq, D), dtype=np.float64)
     dropped = np.full((T, B, Hkv), -1, dtype=np.int64)
+    margin = np.full((T, B, Hkv), np.inf)
     for b in range(B):
         first_pos = max([e["pos"] for e in cache[b][0]], default=-1) + 1
         for t in range(T):
@@ -85,6 +88,9 @@ def h2o_decode_loop(q_steps_bits, k0_bits, v0_bits, total0, pos0, n0, new_k_bits
                     old = [e for e in c if e["pos"] <= p - recent]
                     victim = min(old, key=lambda e: (e["total"], e["pos"]))
                     dropped[t, b, g] = victim["pos"]
+                    others = [float(e["total"]) for e in old if e is not victim]
+                    if others:
+                        margin[t, b, g] = (min(others) - float(victim["total"])) / max(min(others), 1e-30)
                     c.pop(next(i for i, e in enumerate(c) if e is victim))
     final = [[{e["pos"]: e["total"] for e in cache[b][g]} for g in range(Hkv)] for b in range(B)]
-    return {"outs": f64_to_bf16_bits(outs), "dropped": dropped, "final": final}
+    return {"outs": f64_to_bf16_bits(outs), "dropped": dropped, "margin": margin, "final": final}

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(HERE, "librefreshkv.so")
 
 EXPORTS = ["rk_version", "rk_status_string", "rk_workspace_bytes", "rk_workspace_init",
            "rk_full_attn", "rk_full_attn_scores", "rk_topk_select", "rk_full_attn_select", "rk_full_attn_pool", "rk_select_pooled", "rk_score_select", "rk_window_select", "rk_gather_small_kv", "rk_partial_attn", "rk_partial_attn_fixed", "rk_decode_step", "rk_decode_step_overlapped",
-           "rk_query_sim", "rk_mark_refresh", "rk_calibration_copy"]
+           "rk_query_sim", "rk_mark_refresh", "rk_calibration_copy", "rk_h2o_append", "rk_h2o_update", "rk_h2o_step"]
 
 RK_AGG_MAX, RK_AGG_MEAN, RK_AGG_FIRST = 0, 1, 2
 
@@ -41,6 +41,11 @@ class _Kv(C.Structure):
 class _LayerState(C.Structure):
     _fields_ = [("full", _Kv), ("small", _Kv), ("idx", C.c_void_p), ("tail_start", C.c_void_p),
                 ("q_ref", C.c_void_p), ("sim", C.c_void_p), ("need_full", C.c_void_p), ("n_full", C.c_void_p)]
+
+
+class _H2oState(C.Structure):
+    _fields_ = [("cache", _Kv), ("total", C.c_void_p), ("pos", C.c_void_p), ("n_rows", C.c_void_p),
+                ("n_attend", C.c_void_p)]
 
 
 class _Schedule(C.Structure):
@@ -106,6 +111,12 @@ def _load(path: str = LIB_PATH) -> C.CDLL:
     l.rk_calibration_copy.argtypes = [P, P, SZ, P]
     l.rk_mark_refresh.restype = C.c_int
     l.rk_mark_refresh.argtypes = [G, P, P, P, I32, P]
+    l.rk_h2o_append.argtypes = [G, _H2oState, P, P, P, I32, P]
+    l.rk_h2o_append.restype = C.c_int
+    l.rk_h2o_update.argtypes = [G, _H2oState, P, I64, I32, I32, I32, P, P]
+    l.rk_h2o_update.restype = C.c_int
+    l.rk_h2o_step.argtypes = [G, _H2oState, P, P, P, P, I32, I32, I32, P, P, P, SZ, P]
+    l.rk_h2o_step.restype = C.c_int
     return l
 
 
@@ -458,3 +469,43 @@ def rk_calibration_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> in
         raise ValueError("dst and src must have the same size in bytes")
     _check("rk_calibration_copy", lib.rk_calibration_copy(dst.data_ptr(), src.data_ptr(), nbytes, _stream(stream)))
     return nbytes
+
+
+def h2o_state(geom: Geom, cache_K, cache_V, total, pos, n_rows, n_attend) -> _H2oState:
+    """The H2O policy's state as the C struct (the tensors must outlive its use).  cache_K/V bf16
+    [B, Hkv, capacity, D]; total fp32 and pos int32 [B, Hkv, capacity]; n_rows, n_attend int32 [B]."""
+    B, Hkv = geom.batch, geom.n_kv_heads
+    cap = cache_K.shape[2]
+    return _H2oState(_kv(geom, cache_K, cache_V, "cache"),
+                     _dev(total, torch.float32, "total", (B, Hkv, cap)), _dev(pos, torch.int32, "pos", (B, Hkv, cap)),
+                     _dev(n_rows, torch.int32, "n_rows", (B,)), _dev(n_attend, torch.int32, "n_attend", (B,)))
+
+
+def rk_h2o_append(geom: Geom, state: _H2oState, k_new, v_new, seq_lens, budget: int, stream=None) -> None:
+    B, Hkv, D = geom.batch, geom.n_kv_heads, geom.head_dim
+    _check("rk_h2o_append", lib.rk_h2o_append(
+        C.byref(geom.c()), state, _dev(k_new, torch.bfloat16, "k_new", (B, Hkv, D)),
+        _dev(v_new, torch.bfloat16, "v_new", (B, Hkv, D)), _dev(seq_lens, torch.int32, "seq_lens", (B,)),
+        int(budget), _stream(stream)))
+
+
+def rk_h2o_update(geom: Geom, state: _H2oState, weights, budget: int, recent: int, agg: int = RK_AGG_MAX,
+                  dropped=None, stream=None) -> None:
+    B, Hq, Hkv = geom.batch, geom.n_q_heads, geom.n_kv_heads
+    if weights.dim() != 3 or weights.shape[0] != B or weights.shape[1] != Hq:
+        raise ValueError("weights must be [batch, n_q_heads, >= budget + 1]")
+    _check("rk_h2o_update", lib.rk_h2o_update(
+        C.byref(geom.c()), state, _dev(weights, torch.float32, "weights"), weights.shape[2],
+        int(budget), int(recent), int(agg), _dev(dropped, torch.int32, "dropped", (B, Hkv), optional=True),
+        _stream(stream)))
+
+
+def rk_h2o_step(geom: Geom, state: _H2oState, q, k_new, v_new, seq_lens, budget: int, recent: int, out,
+                agg: int = RK_AGG_MAX, dropped=None, workspace: Workspace = None, stream=None) -> None:
+    B, Hq, Hkv, D = geom.batch, geom.n_q_heads, geom.n_kv_heads, geom.head_dim
+    _check("rk_h2o_step", lib.rk_h2o_step(
+        C.byref(geom.c()), state, _dev(q, torch.bfloat16, "q", (B, Hq, D)),
+        _dev(k_new, torch.bfloat16, "k_new", (B, Hkv, D)), _dev(v_new, torch.bfloat16, "v_new", (B, Hkv, D)),
+        _dev(seq_lens, torch.int32, "seq_lens", (B,)), int(budget), int(recent), int(agg),
+        _dev(out, torch.bfloat16, "out", (B, Hq, D)), _dev(dropped, torch.int32, "dropped", (B, Hkv), optional=True),
+        workspace.ptr, workspace.nbytes, _stream(stream)))

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librefreshkv.so")
 SOURCES = ["rk_api.hip", "rk_attn.hip", "rk_topk.hip", "rk_gather.hip", "rk_query_sim.hip", "rk_step.hip",
-           "rk_window.hip"]
+           "rk_window.hip", "rk_h2o.hip"]
 # Packed fp32 VALU forms are switched off for every device compilation of this library.
 HIPCC_FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

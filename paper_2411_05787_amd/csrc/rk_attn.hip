@@ -322,7 +322,7 @@ void attn_split_kernel(const AttnParams p) {
         if (r_next < row1) load_k(r_next);
         // ---- raw scores out: four consecutive rows of one head per lane, one 16-byte store
         //      where the row of the weights tensor allows it ----
-        if (EMIT) {
+        if (EMIT && p.weights != nullptr) {
             if (n16 < G) {
                 float* wrow = p.weights + ((int64_t)b * p.Hq + (int64_t)g * G + n16) * p.w_stride + r + 4 * c4;
 #pragma unroll
@@ -928,8 +928,20 @@ int full_attn_stage(const rk_geom* geom, const void* q, rk_kv full, const int32_
     p.lse = lse ? lse : ws.lse;
     p.pred = pred; p.pred_val = pred_val;
     p.counters = ws.counters; p.part_ml = ws.part_ml; p.part_o = ws.part_o; p.max_chunks = ws.max_chunks;
+    if (!emit) {
+        // No scores wanted.  Short rows: one launch, merged by the last workgroup inside it (at most
+        // kMergeChunks partial results).  Long rows: the wider split of the score-emitting kernel
+        // (its stores switched off) and the merge as a second small launch fill the chip better.
+        const int wide = split_workgroups(max_len, (int64_t)geom->batch * geom->n_kv_heads, kMaxChunks);
+        if (wide <= kMergeChunks) return launch_split<false, false>(p, geom->batch, G, p.nch, st);
+        p.nch = wide;
+        p.weights = nullptr;
+        int rc = launch_split<true, false>(p, geom->batch, G, p.nch, st);
+        if (rc != RK_OK) return rc;
+        hipLaunchKernelGGL(merge_normalise_kernel, dim3(1, geom->n_q_heads, geom->batch), dim3(256), 0, st, p, G);
+        return launch_status();
+    }
     const int nchunk_grid = p.nch;
-    if (!emit) return launch_split<false, false>(p, geom->batch, G, nchunk_grid, st);
     int rc = no_v ? launch_score_split(p, geom->batch, G, nchunk_grid, st)
                   : launch_split<true, false>(p, geom->batch, G, nchunk_grid, st);
     if (rc != RK_OK || scores_only) return rc;

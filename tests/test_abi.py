@@ -120,6 +120,16 @@ def test_host_side_argument_checks_return_before_any_launch(rk):
     assert lib.rk_partial_attn(C.byref(g), fake, kv, 0, kv, fake, fake, 0, fake, None, 0, 0x100000, ws_bytes, None) == -1
     assert lib.rk_partial_attn(C.byref(g), fake, kv, 16, kv, None, fake, 4, fake, None, 0, 0x100000, ws_bytes, None) == -1
     assert lib.rk_query_sim(C.byref(g), fake, None, 0.5, 0, fake, fake, None) == -1
+    from paper_2411_05787_amd.binding import _H2oState
+    h2o = lambda cap=257, total=fake: _H2oState(_Kv(fake, fake, 8 * cap * 128, cap * 128, cap), total, fake, fake, fake)
+    assert lib.rk_h2o_append(C.byref(g), h2o(), None, fake, fake, 256, None) == -1
+    assert lib.rk_h2o_append(C.byref(g), h2o(cap=256), fake, fake, fake, 256, None) == -1        # no room for budget + 1 rows
+    assert lib.rk_h2o_update(C.byref(g), h2o(), fake, 300, 256, 256, 0, None, None) == -1         # recent must stay below the budget
+    assert lib.rk_h2o_update(C.byref(g), h2o(), fake, 200, 256, 128, 0, None, None) == -1         # weight rows too short
+    assert lib.rk_h2o_update(C.byref(g), h2o(total=None), fake, 300, 256, 128, 0, None, None) == -1
+    assert lib.rk_h2o_update(C.byref(g), h2o(), fake, 300, 256, 128, 5, None, None) == -2         # unknown aggregation
+    assert lib.rk_h2o_step(C.byref(g), h2o(), fake, fake, fake, fake, 256, 128, 0, None, None, 0x100000, ws_bytes, None) == -1
+    assert lib.rk_h2o_step(C.byref(g), h2o(), fake, fake, fake, fake, 256, 128, 0, fake, None, None, ws_bytes, None) == -3
     assert lib.rk_mark_refresh(C.byref(g), None, fake, None, 0, None) == -1
     assert lib.rk_workspace_init(C.byref(g), None, 4096, None) == -3
     assert lib.rk_workspace_init(C.byref(g), 0x100000, 16, None) == -3

@@ -964,3 +964,85 @@ def test_full_size_batched_ragged(rk):
             P = oracle.pooled_group_scores(wts[b, g * G:(g + 1) * G, :n], w.pool_w)
             n_diff += assert_idx_equivalent(got["idx"][0][b, g], ref["idx"][0][b, g], P, n, w.k_small, "b=%d g=%d" % (b, g))
     say("  index entries differing within the gap tolerance:", n_diff, "of", w.batch * w.n_kv_heads * w.k_small)
+
+
+# ----------------------------------------------------------------------------- H2O comparison policy
+H2O_CASES = [
+    # name, B, Hq, Hkv, budget, recent, n0, T, agg
+    ("llama_small", 2, 8, 2, 300, 150, [290, 120], 40, "max"),
+    ("qwen_g7", 1, 14, 2, 64, 32, [64], 30, "max"),
+    ("mean_recent0", 1, 4, 1, 40, 0, [33], 25, "mean"),
+    ("k2048", 1, 32, 8, 2048, 1024, [2048], 4, "max"),
+]
+
+
+@pytest.mark.parametrize("case", H2O_CASES, ids=[c[0] for c in H2O_CASES])
+def test_h2o_policy_matches_oracle(rk, case):
+    """Section 3 "Comparison systems" / Appendix A.1: the H2O baseline (cumulative scores, K/2 recent,
+    greedy drop) on the library's attention step, against the oracle's statement of the policy."""
+    name, B, Hq, Hkv, budget, recent, n0, T, agg = case
+    say("h2o case", name)
+    rng = np.random.default_rng(len(name) * 7 + budget)
+    g = torch.Generator().manual_seed(budget + T)
+    D, cap = 128, budget + 1
+    nmax = max(n0)
+    k0 = torch.randn(B, Hkv, nmax, D, generator=g).to(torch.bfloat16)
+    v0 = torch.randn(B, Hkv, nmax, D, generator=g).to(torch.bfloat16)
+    q = torch.randn(T, B, Hq, D, generator=g).to(torch.bfloat16)
+    nk = torch.randn(T, B, Hkv, D, generator=g).to(torch.bfloat16)
+    nv = torch.randn(T, B, Hkv, D, generator=g).to(torch.bfloat16)
+    k0[:, :, ::13] *= 2.0
+    pos0 = np.zeros((B, Hkv, nmax), dtype=np.int64)
+    for b in range(B):
+        for h in range(Hkv):             # what a prefill-side selection leaves: a subset of the prompt, in any order
+            pos0[b, h, :n0[b]] = rng.permutation(np.sort(rng.choice(3 * nmax, size=n0[b], replace=False)))
+        pos0[b, :, 0] = 3 * nmax         # the same newest position for every head of a sequence
+    tot0 = (rng.random((B, Hkv, nmax)) * 0.05).astype(np.float32)
+    scale = float(np.float32(1 / np.sqrt(128)))
+    ref = oracle.h2o_decode_loop(gen.bf16_bits(q), gen.bf16_bits(k0), gen.bf16_bits(v0), tot0, pos0, n0,
+                                 gen.bf16_bits(nk), gen.bf16_bits(nv), scale, budget, recent, agg)
+
+    geom = rk.Geom(B, Hq, Hkv, D, scale)
+    cK = torch.zeros(B, Hkv, cap, D, dtype=torch.bfloat16, device="cuda"); cV = torch.zeros_like(cK)
+    cK[:, :, :nmax] = k0.cuda(); cV[:, :, :nmax] = v0.cuda()
+    total = torch.zeros(B, Hkv, cap, dtype=torch.float32, device="cuda"); total[:, :, :nmax] = torch.from_numpy(tot0).cuda()
+    pos = torch.full((B, Hkv, cap), -1, dtype=torch.int32, device="cuda"); pos[:, :, :nmax] = torch.from_numpy(pos0).int().cuda()
+    n_rows = torch.tensor(n0, dtype=torch.int32, device="cuda")
+    n_attend = torch.zeros(B, dtype=torch.int32, device="cuda")
+    st = rk.h2o_state(geom, cK, cV, total, pos, n_rows, n_attend)
+    ws = rk.Workspace(geom, cap, 16)
+    out = torch.zeros(B, Hq, D, dtype=torch.bfloat16, device="cuda")
+    dropped = torch.zeros(B, Hkv, dtype=torch.int32, device="cuda")
+    seq_lens = torch.full((B,), 3 * nmax + 1, dtype=torch.int32, device="cuda")
+    code = {"max": rk.RK_AGG_MAX, "mean": rk.RK_AGG_MEAN, "first": rk.RK_AGG_FIRST}[agg]
+    alive = np.ones((B, Hkv), dtype=bool)            # (b, g) still on the oracle's path
+    qd, nkd, nvd = q.cuda(), nk.cuda(), nv.cuda()
+    n_drops = 0
+    for t in range(T):
+        seq_lens += 1
+        rk.rk_h2o_step(geom, st, qd[t], nkd[t], nvd[t], seq_lens, budget, recent, out, agg=code, dropped=dropped, workspace=ws)
+        torch.cuda.synchronize()
+        got_drop, got_out = dropped.cpu().numpy(), gen.bf16_bits(out)
+        for b in range(B):
+            for h in range(Hkv):
+                if not alive[b, h]:
+                    continue
+                G = Hq // Hkv
+                assert_out_close(got_out[b:b + 1, h * G:(h + 1) * G], ref["outs"][t, b:b + 1, h * G:(h + 1) * G])
+                if got_drop[b, h] != ref["dropped"][t, b, h]:
+                    assert ref["margin"][t, b, h] < 1e-5, (name, t, b, h, got_drop[b, h], ref["dropped"][t, b, h])
+                    alive[b, h] = False              # a near-tie went the other way: the paths part here
+                n_drops += int(got_drop[b, h] >= 0)
+    assert alive.mean() > 0.7 and n_drops > 0
+    nr = n_rows.cpu().numpy()
+    tot_n, pos_n = total.cpu().numpy(), pos.cpu().numpy()
+    for b in range(B):
+        assert nr[b] == min(n0[b] + T, budget)
+        for h in range(Hkv):
+            if not alive[b, h]:
+                continue
+            want = ref["final"][b][h]
+            got = {int(pos_n[b, h, j]): float(tot_n[b, h, j]) for j in range(nr[b])}
+            assert sorted(got) == sorted(want)
+            for x in want:
+                assert abs(got[x] - float(want[x])) <= 1e-5 * max(abs(float(want[x])), 1e-3)

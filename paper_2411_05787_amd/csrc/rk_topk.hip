@@ -34,6 +34,7 @@ constexpr int kSelTile = 4 * kSelThreads;                // positions per workgr
 constexpr int kSelSingle = 2 * kSelTile;                 // rows up to this length are left to one workgroup
 constexpr int kBuckets = 2048;                           // regular buckets, plus one for all above
 constexpr int kBucketLimit = 1024;                       // larger buckets: sort instead of ranking
+constexpr int kAdaptiveFrom = 8192;                      // candidates from which buckets follow the histogram
 constexpr int kTopLoose = 64;                            // scores above the bucketed range: fewer than this
 static_assert(kHistBins == 1 << 11, "first-level histogram is 11 bits wide");
 static_assert(kHistBins == 2 * kSelThreads, "the selection scans the histogram two bins per thread");
@@ -222,6 +223,7 @@ void select_kernel(const float* __restrict__ pooled, int64_t pooled_stride, cons
     uint32_t* sScan = sHist + 2 * (kBuckets + 1);                          // [16]
     uint32_t* sOut = sScan + kSelThreads / 64;                             // [4]
     uint32_t* sCount = sOut + 4;                                           // [1]
+    uint16_t* sTab = reinterpret_cast<uint16_t*>(sCount + 1);              // [kHistBins] buckets of each first-level bin
 
     const int tid = threadIdx.x;
     const int n = min(seq_lens[b], max_len);
@@ -265,9 +267,10 @@ void select_kernel(const float* __restrict__ pooled, int64_t pooled_stride, cons
     // bucket for "everything above" stays small (its items are ranked by a loop over the bucket).
     if (tid == 0) *sCount = 0;
     for (int i = tid; i < kBuckets + 1; i += kSelThreads) sHist[i] = 0;     // bucket sizes of the fast path
+    uint32_t h0, h1;                         // this thread's two bins of the first-level histogram
     {
         const int rt = kSelThreads - 1 - tid;
-        const uint32_t h0 = gh[2 * rt], h1 = gh[2 * rt + 1];
+        h0 = gh[2 * rt]; h1 = gh[2 * rt + 1];
         uint32_t total;
         const uint32_t incl = block_inclusive_scan<kSelThreads>(h0 + h1, sScan, &total);   // entries in bins >= 2 rt
         const uint32_t abv = incl - (h0 + h1);
@@ -386,7 +389,22 @@ void select_kernel(const float* __restrict__ pooled, int64_t pooled_stride, cons
         }
         return c;
     };
+    // Buckets of the fast path.  Preferred layout: every first-level bin from b1 up to the bin of
+    // the kTopLoose-th largest score gets a power-of-two number of equal-width buckets in
+    // proportion to its count in the histogram, so that all buckets hold about the same number of
+    // candidates however the scores are distributed over the octaves (scores thin out towards the
+    // top: equal-width buckets over the whole range leave most candidates in the lowest few, and
+    // the ranking below costs the square of a bucket's size).  sTab[bin] = first bucket | log2 of
+    // the number of buckets << 11.  Used from kAdaptiveFrom candidates on (below that, building the
+    // table costs more than it saves: measured).  Otherwise, and when the threshold is not on a bin
+    // boundary or the bins need more than kBuckets buckets: equal-width buckets over the whole range.
+    bool adaptive = false;
     auto bucket_of = [&](uint32_t key) -> uint32_t {
+        if (adaptive) {
+            if (key_top != 0u && key >= key_top) return (uint32_t)kBuckets;
+            const uint32_t t = sTab[key >> kHistShift], e = t >> 11;
+            return (t & 0x7FFu) + ((key >> (kHistShift - e)) & ((1u << e) - 1u));
+        }
         return min((key - key_thr) >> bucket_shift, (uint32_t)kBuckets);
     };
     int nvalid;                             // entries of sKeys that are real (sorting paths)
@@ -403,6 +421,26 @@ void select_kernel(const float* __restrict__ pooled, int64_t pooled_stride, cons
             for (int i = tid; i < kBuckets + 1; i += kSelThreads) sCnt[i] = 0;
         }
         uint32_t total;
+        if (!refined && count_ge > (uint32_t)kAdaptiveFrom) {
+            const int rt = kSelThreads - 1 - tid;
+            const uint32_t top = (key_top - 1u) >> kHistShift;
+            const float per_item = 1400.f / (float)count_ge;              // aims at ~1500 buckets in all
+            auto log2_buckets = [&](uint32_t h, uint32_t bin) -> int {    // -1: no bucket
+                if (h == 0 || bin < b1 || bin > top) return -1;
+                const float x = (float)h * per_item;
+                return x <= 1.f ? 0 : min((int)(__log2f(x) + 0.5f), 11);
+            };
+            const int e0 = log2_buckets(h0, 2 * rt), e1 = log2_buckets(h1, 2 * rt + 1);
+            const uint32_t nb0 = e0 < 0 ? 0u : 1u << e0, nb1 = e1 < 0 ? 0u : 1u << e1;
+            const uint32_t incl = block_inclusive_scan<kSelThreads>(nb0 + nb1, sScan, &total);   // buckets of bins >= 2 rt
+            adaptive = total != 0 && total <= (uint32_t)kBuckets;
+            if (adaptive) {
+                const uint32_t first0 = total - incl;                     // buckets of all lower bins
+                if (e0 >= 0) sTab[2 * rt] = (uint16_t)(first0 | ((uint32_t)e0 << 11));
+                if (e1 >= 0) sTab[2 * rt + 1] = (uint16_t)((first0 + nb0) | ((uint32_t)e1 << 11));
+            }
+            __syncthreads();
+        }
         constexpr int kItems = kMaxCandidates / kSelThreads;
         uint64_t it[kItems];
         if (listed) {                                   // the dense list is in the workspace already
@@ -544,7 +582,7 @@ int select_stage(const rk_geom* geom, const int32_t* seq_lens, int32_t max_len, 
                  float* sel_scores, const int32_t* pred, int32_t pred_val, const Workspace& ws, hipStream_t st) {
     // the sort kernel may need more than the default dynamic LDS
     const size_t lds = (size_t)ws.cand_cap * sizeof(uint64_t) +
-                       (2 * (kBuckets + 1) + kSelThreads / 64 + 4 + 1) * sizeof(uint32_t);
+                       (2 * (kBuckets + 1) + kSelThreads / 64 + 4 + 1) * sizeof(uint32_t) + kHistBins * sizeof(uint16_t);
     static size_t lds_allowed = 48 * 1024;       // grows monotonically
     if (lds > lds_allowed) {
         if (hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel),

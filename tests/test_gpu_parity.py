@@ -159,6 +159,8 @@ TOPK_CASES = [
     ("pool63", 1, 2, 1, [2000], 128, 63, "lognormal"),
     ("refine_path", 1, 2, 1, [90000], 14000, 1, "lognormal"),     # more candidates than LDS holds: bin cut again
     ("ragged_batch", 5, 8, 2, [70000, 3, 1025, 64, 31999], 1024, 7, "lognormal"),
+    ("many_candidates_128k", 1, 4, 1, [131072], 8192, 7, "lognormal"),    # buckets laid out from the histogram
+    ("many_candidates_pool1", 2, 2, 1, [60000, 20000], 8192, 1, "lognormal"),
 ]
 
 

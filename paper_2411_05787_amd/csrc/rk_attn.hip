@@ -944,7 +944,10 @@ int full_attn_stage(const rk_geom* geom, const void* q, rk_kv full, const int32_
         // kMergeChunks partial results).  Long rows: the wider split of the score-emitting kernel
         // (its stores switched off) and the merge as a second small launch fill the chip better.
         const int wide = split_workgroups(max_len, (int64_t)geom->batch * geom->n_kv_heads, kMaxChunks);
-        if (wide <= kMergeChunks) return launch_split<false, false>(p, geom->batch, G, p.nch, st);
+        if (wide <= kMergeChunks) {
+            p.nch = merged_split_workgroups(max_len, 0, (int64_t)geom->batch * geom->n_kv_heads);
+            return launch_split<false, false>(p, geom->batch, G, p.nch, st);
+        }
         p.nch = wide;
         p.weights = nullptr;
         int rc = launch_split<true, false>(p, geom->batch, G, p.nch, st);
@@ -1046,7 +1049,7 @@ static int partial_attn_impl(const rk_geom* geom, const void* q, rk_kv small, in
     p.evict = evict ? 1 : 0;
     p.max_rows2 = max_recent;
     p.cap1 = n_sel > 0 ? (int32_t)small.capacity : 0; p.cap2 = (int32_t)full.capacity;
-    p.nch = split_workgroups(max_rows, (int64_t)geom->batch * geom->n_kv_heads, kMergeChunks);
+    p.nch = merged_split_workgroups(n_sel, max_recent, (int64_t)geom->batch * geom->n_kv_heads);
     p.Hq = geom->n_q_heads; p.Hkv = geom->n_kv_heads;
     p.scale = geom->scale;
     p.out = (uint16_t*)out;

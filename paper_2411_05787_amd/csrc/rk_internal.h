@@ -43,6 +43,29 @@ static inline int split_workgroups(int64_t max_rows, int64_t n_problems, int lim
     return (int)best;
 }
 
+// Workgroups per (sequence, KV head) when the last workgroup of the launch merges the partial
+// results inside the kernel (partial steps; short full steps without scores).  There the merge
+// sets the terms (measured, K = 1024..8192, groups of 4, 7 and 8): it reads the partial outputs
+// in batches of 16 per round trip, and a 17th partial result costs 0.8 us, about what a whole
+// further round of tiles costs a wavefront (16 workgroups: 9.1 us, 17: 9.9 at K = 2048; 16: 10.3,
+// 33: 13.7 at K = 4096; 16: 14.6, 40: 17.2 at K = 8192).  So: the largest count within whole
+// batches of 16 that keeps the rounds per wavefront at 5 or fewer, one batch if possible; and a
+// tail of a few rows (the tokens decoded since the refresh) gets no workgroup of its own, one
+// wavefront takes it as a second tile.
+static inline int merged_split_workgroups(int64_t rows, int64_t tail_rows, int64_t n_problems) {
+    const int64_t all_rows = rows + tail_rows;
+    const int64_t counted = (rows > 0 && tail_rows <= 32) ? rows : all_rows;
+    int64_t per = RK_TARGET_WGS / (n_problems > 0 ? n_problems : 1);
+    const int64_t stretches = (counted + kMinChunk - 1) / kMinChunk;
+    if (per > stretches) per = stretches;
+    if (per > kMergeChunks) per = kMergeChunks;
+    if (per < 1) per = 1;
+    const int64_t tiles = (all_rows + 31) / 32;
+    for (int64_t n = 16; n < per; n += 16)
+        if ((tiles + 4 * n - 1) / (4 * n) <= 5) return (int)n;
+    return (int)per;
+}
+
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 constexpr int kHistBins = 2048;          // first-level histogram of the selection: top 11 key bits

@@ -207,6 +207,7 @@ __device__ void bitonic_sort_desc(uint64_t* sKeys, int npad) {
 // space), and the workgroup that arrives last (ticket, as in the attention kernels) takes the
 // list into registers and ranks it: the pass over all positions, which is what a single
 // workgroup spends most of its time on, is spread over the chip.
+template <bool ADAPT>                    // ADAPT: compiled with the histogram-driven bucket layout (large K only)
 __global__ __launch_bounds__(kSelThreads)
 void select_kernel(const float* __restrict__ pooled, int64_t pooled_stride, const int32_t* seq_lens,
                    int32_t max_len, int32_t k, uint32_t* __restrict__ hist, int32_t cand_cap,
@@ -224,6 +225,7 @@ void select_kernel(const float* __restrict__ pooled, int64_t pooled_stride, cons
     uint32_t* sOut = sScan + kSelThreads / 64;                             // [4]
     uint32_t* sCount = sOut + 4;                                           // [1]
     uint16_t* sTab = reinterpret_cast<uint16_t*>(sCount + 1);              // [kHistBins] buckets of each first-level bin
+                                                                           // (allocated only if cand_cap > kAdaptiveFrom)
 
     const int tid = threadIdx.x;
     const int n = min(seq_lens[b], max_len);
@@ -400,7 +402,7 @@ void select_kernel(const float* __restrict__ pooled, int64_t pooled_stride, cons
     // boundary or the bins need more than kBuckets buckets: equal-width buckets over the whole range.
     bool adaptive = false;
     auto bucket_of = [&](uint32_t key) -> uint32_t {
-        if (adaptive) {
+        if (ADAPT && adaptive) {
             if (key_top != 0u && key >= key_top) return (uint32_t)kBuckets;
             const uint32_t t = sTab[key >> kHistShift], e = t >> 11;
             return (t & 0x7FFu) + ((key >> (kHistShift - e)) & ((1u << e) - 1u));
@@ -421,7 +423,7 @@ void select_kernel(const float* __restrict__ pooled, int64_t pooled_stride, cons
             for (int i = tid; i < kBuckets + 1; i += kSelThreads) sCnt[i] = 0;
         }
         uint32_t total;
-        if (!refined && count_ge > (uint32_t)kAdaptiveFrom) {
+        if (ADAPT && !refined && count_ge > (uint32_t)kAdaptiveFrom) {
             const int rt = kSelThreads - 1 - tid;
             const uint32_t top = (key_top - 1u) >> kHistShift;
             const float per_item = 1400.f / (float)count_ge;              // aims at ~1500 buckets in all
@@ -578,14 +580,17 @@ int check_select_args(int32_t k, int32_t pool_w, int32_t agg) {
     return RK_OK;
 }
 
-int select_stage(const rk_geom* geom, const int32_t* seq_lens, int32_t max_len, int32_t k, int32_t* idx,
-                 float* sel_scores, const int32_t* pred, int32_t pred_val, const Workspace& ws, hipStream_t st) {
-    // the sort kernel may need more than the default dynamic LDS
+template <bool ADAPT>
+static int launch_select(const rk_geom* geom, const int32_t* seq_lens, int32_t max_len, int32_t k, int32_t* idx,
+                         float* sel_scores, const int32_t* pred, int32_t pred_val, const Workspace& ws, hipStream_t st) {
+    // the sort kernel may need more than the default dynamic LDS; the per-bin bucket table is part
+    // of it only where there can be kAdaptiveFrom candidates
     const size_t lds = (size_t)ws.cand_cap * sizeof(uint64_t) +
-                       (2 * (kBuckets + 1) + kSelThreads / 64 + 4 + 1) * sizeof(uint32_t) + kHistBins * sizeof(uint16_t);
-    static size_t lds_allowed = 48 * 1024;       // grows monotonically
+                       (2 * (kBuckets + 1) + kSelThreads / 64 + 4 + 1) * sizeof(uint32_t) +
+                       (ADAPT ? kHistBins * sizeof(uint16_t) : 0);
+    static size_t lds_allowed = 48 * 1024;       // grows monotonically (one per instantiation)
     if (lds > lds_allowed) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel),
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&select_kernel<ADAPT>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
             (void)hipGetLastError();
             return RK_ERR_UNSUPPORTED;
@@ -595,9 +600,20 @@ int select_stage(const rk_geom* geom, const int32_t* seq_lens, int32_t max_len, 
     // short rows: one workgroup per (sequence, KV head) does it all; longer ones: one per kSelTile positions
     const int tiles = max_len > kSelSingle ? (max_len + kSelTile - 1) / kSelTile : 1;
     dim3 sgrid(tiles, geom->n_kv_heads, geom->batch);
-    hipLaunchKernelGGL(select_kernel, sgrid, dim3(kSelThreads), lds, st, ws.pooled, pooled_row_stride(max_len), seq_lens,
+    hipLaunchKernelGGL((select_kernel<ADAPT>), sgrid, dim3(kSelThreads), lds, st, ws.pooled, pooled_row_stride(max_len), seq_lens,
                        max_len, k, ws.hist, ws.cand_cap, idx, sel_scores, pred, pred_val, ws.sel_counters, ws.cand_list);
     return launch_status();
+}
+
+// Two builds of the selection kernel: the one with the histogram-driven bucket layout serves the
+// workspaces that can hold more than kAdaptiveFrom candidates (K > 4096); the other is the same
+// code without it, because the smaller kernel measures faster where the layout is never used
+// (1 us per layer of a full step at K = 2048 when it runs beside the attention kernel).
+int select_stage(const rk_geom* geom, const int32_t* seq_lens, int32_t max_len, int32_t k, int32_t* idx,
+                 float* sel_scores, const int32_t* pred, int32_t pred_val, const Workspace& ws, hipStream_t st) {
+    if (ws.cand_cap > kAdaptiveFrom)
+        return launch_select<true>(geom, seq_lens, max_len, k, idx, sel_scores, pred, pred_val, ws, st);
+    return launch_select<false>(geom, seq_lens, max_len, k, idx, sel_scores, pred, pred_val, ws, st);
 }
 
 }  // namespace rk

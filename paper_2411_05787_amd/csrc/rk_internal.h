@@ -17,30 +17,32 @@ constexpr int kMergeChunks = 64;         // ... when the split kernel itself mer
 #define RK_TARGET_WGS 768                // workgroups a split launch aims for (3 per CU, all resident)
 #endif
 
-// Workgroups per (sequence, KV head) of a split attention launch.  Upper bound: as many as give
-// the launch RK_TARGET_WGS workgroups in all (such a launch is resident as a whole from the
-// start), never more than `limit` (the most partial results the merge that follows takes:
-// kMergeChunks when the last workgroup merges inside the split kernel, kMaxChunks when a second
-// kernel does), never more than there are stretches of kMinChunk rows.
-// Below that bound the count is chosen for the rows at hand.  The launch works in rounds: each
-// of its 4 * nch wavefronts per (sequence, KV head) takes one 32-row tile per round, and a round
-// costs about the same whether all wavefronts or only a few have a tile in it (one memory round
-// trip).  So the run time goes with rounds * wavefronts, and a count a little below the bound
-// that fills its last round beats the bound with a nearly empty one (32979 rows: 52 workgroups,
-// 5 full rounds, instead of 64 and a fifth round for 7 tiles: 15% faster).  Counts down to 5/8
-// of the bound are considered; ties go to the larger count.
+// Workgroups per (sequence, KV head) of a split attention launch whose partial results a second
+// kernel merges.  Upper bound: as many as give the launch RK_TARGET_WGS workgroups in all (such a
+// launch is resident as a whole from the start), never more than `limit` (the most partial
+// results the merge takes), never more than there are stretches of kMinChunk rows.
+// Below that bound, a count that gives every CU the same number of workgroups is preferred
+// (total a multiple of the 256 CUs) as long as no wavefront gets more tiles for it.  Measured on
+// the score-emitting kernel alone, 8 KV heads, total workgroups -> us per launch:
+//   24576 rows: 512 -> 20.5, 768 -> 21.5, 1024 -> 22.4;   560..720 -> 22.5..25.9
+//   32768 rows: 512 -> 27.1, 768 -> 27.5, 1024 -> 26.6;   560..720 -> 28.9..31.6
+//   65536 rows: 512 -> 51.5, 768 -> 52.5, 1024 -> 49.7;   560..720 -> 54.5..60.1
+// and the same picture with 4 KV heads and with a batch of 4: an even spread is worth 10-20%,
+// which of the even spreads is worth 3-5% and depends on the length; 3 per CU (one residency
+// wave) is never more than 5% from the best.
+constexpr int kComputeUnits = 256;
 static inline int split_workgroups(int64_t max_rows, int64_t n_problems, int limit) {
-    int64_t per = RK_TARGET_WGS / (n_problems > 0 ? n_problems : 1);
+    if (n_problems < 1) n_problems = 1;
+    int64_t per = RK_TARGET_WGS / n_problems;
     const int64_t stretches = (max_rows + kMinChunk - 1) / kMinChunk;
     if (per > stretches) per = stretches;
     if (per > limit) per = limit;
     if (per < 1) per = 1;
     const int64_t tiles = (max_rows + 31) / 32;
-    auto cost = [&](int64_t nch) { return (tiles + 4 * nch - 1) / (4 * nch) * (4 * nch); };
-    int64_t best = per;
-    for (int64_t nch = per - 1; nch >= 1 && 8 * nch >= 5 * per; --nch)
-        if (cost(nch) < cost(best)) best = nch;
-    return (int)best;
+    auto rounds = [&](int64_t nch) { return (tiles + 4 * nch - 1) / (4 * nch); };
+    for (int64_t nch = per; nch >= 1 && 8 * nch >= 5 * per; --nch)
+        if ((nch * n_problems) % kComputeUnits == 0 && rounds(nch) == rounds(per)) return (int)nch;
+    return (int)per;
 }
 
 // Workgroups per (sequence, KV head) when the last workgroup of the launch merges the partial

@@ -247,6 +247,12 @@ class RefreshKVStack:
     best at 32 layers of 32k tokens (full step 46.8 us per layer; two: 50.0, four: 48.2, one per
     layer: 57, where the second stream falls behind and its kernels crowd later layers).  Partial
     steps and the trigger's test steps are issued as :class:`RefreshKVLayer` issues them.
+
+    Submission: a full step issued (or its graph replayed) while many earlier steps are still
+    pending leaves the second stream's queue blocked behind all of them, and on this hardware a
+    blocked queue slows every dispatch of the first one (measured: +0.9 us per layer on each partial
+    step in between).  A driver loop should therefore submit a full step late, when at most one
+    earlier step is still pending (wait on the event that ended the step before the last).
     """
 
     def __init__(self, layers, n_workspaces: int = 3):

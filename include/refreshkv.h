@@ -408,7 +408,11 @@ typedef struct rk_overlap {
  * ov->side_stream beside the following layers' full attention; `stream` has waited for all of it
  * when the step's work on it ends.  Same results, same return values.  Other steps, and the
  * scores-only refresh, are passed to rk_decode_step with the first workspace.  The events must
- * not be in use by anything else while the step is in flight. */
+ * not be in use by anything else while the step is in flight.
+ * Submit a step that uses the side stream late: if many earlier steps are still pending on
+ * `stream`, the side stream's queue sits blocked behind all of them, and on MI355X a blocked queue
+ * slows every kernel launch of the other one (about 0.9 us each, measured).  A loop that lets at
+ * most one earlier step be pending when it calls this for a full step avoids that. */
 int rk_decode_step_overlapped(const rk_geom* geom, const rk_schedule* sched, int32_t t, int32_t n_layers,
                               const rk_layer_state* layers, const void* const* q, void* const* out,
                               const int32_t* seq_lens, int32_t max_len, int32_t max_recent,

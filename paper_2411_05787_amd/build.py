@@ -14,6 +14,8 @@ SOURCES = ["rk_api.hip", "rk_attn.hip", "rk_topk.hip", "rk_gather.hip", "rk_quer
 # Packed fp32 VALU forms are switched off for every device compilation of this library.
 HIPCC_FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+               # the first scalar kernel arguments arrive in registers (see attn_split_kernel)
+               "-mllvm", "-amdgpu-kernarg-preload-count=16",
                "-Wall", "-Wno-unused-function"]
 
 

@@ -203,7 +203,13 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 #endif
 template <int G, int NW, bool EMIT, bool TWO_SEG>
 __global__ __launch_bounds__(NW * 64, EMIT ? RK_EMIT_OCCUPANCY : 2)
-void attn_split_kernel(const AttnParams p) {
+void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t s_b, int64_t s_h,
+                       const uint16_t* q, const int32_t* pred, int32_t pred_val, int32_t spec_rows, int32_t Hq,
+                       const AttnParams p) {
+    // The leading arguments repeat what the first loads need (the cache that holds the first rows,
+    // its strides, q, the predicate): 15 dwords that the command processor can hand over in
+    // registers at wavefront launch (kernel-argument preload), so the first K/V request does not
+    // wait for a read of the argument block.  Everything else comes from `p` as before.
     constexpr int ROWS = kTileRows;          // rows per wavefront and tile = contraction depth of P V
     static_assert(NW == kSplitWaves, "work split");
     constexpr int NV = ROWS / 4;             // V loads per lane and tile
@@ -212,7 +218,7 @@ void attn_split_kernel(const AttnParams p) {
     constexpr int VS = kD + 8;               // LDS row stride of the V tile (272 bytes: rows spread over banks)
 
     const int c = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
-    if (p.pred != nullptr && p.pred[b] != p.pred_val) return;
+    if (pred != nullptr && pred[b] != pred_val) return;
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int n16 = lane & 15, c4 = lane >> 4;
@@ -223,19 +229,16 @@ void attn_split_kernel(const AttnParams p) {
     // it may read them at once; rows that turn out to be past the end are masked like any other.
     // This takes the round trip for seq_lens / tail_start off the critical path.
     const int r_first = (c * NW + w) * ROWS;
-    const int spec_rows = TWO_SEG ? min(p.n_sel, p.cap1) : p.cap2;
-    const bool spec = (c + 1) * NW * ROWS <= spec_rows;
+    const bool spec = (c + 1) * NW * ROWS <= spec_rows;     // spec_rows: min(n_sel, cap1) or cap2
     u32x4 kA[2][4], vA[NV];
     if (spec) {
-        const uint16_t* kspec = (TWO_SEG ? p.k1 + (int64_t)b * p.s1_b + (int64_t)g * p.s1_h
-                                         : p.k2 + (int64_t)b * p.s2_b + (int64_t)g * p.s2_h) + c4 * 8;
+        const uint16_t* kspec = k_first + (int64_t)b * s_b + (int64_t)g * s_h + c4 * 8;
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk)
                 kA[t][kk] = load_rows16<!TWO_SEG>(kspec + (int64_t)(r_first + t * 16 + n16) * kD + kk * 32);
-        const uint16_t* vspec = (TWO_SEG ? p.v1 + (int64_t)b * p.s1_b + (int64_t)g * p.s1_h
-                                         : p.v2 + (int64_t)b * p.s2_b + (int64_t)g * p.s2_h) + n16 * 8;
+        const uint16_t* vspec = v_first + (int64_t)b * s_b + (int64_t)g * s_h + n16 * 8;
 #pragma unroll
         for (int jj = 0; jj < NV; ++jj)
             vA[jj] = load_rows16<!TWO_SEG>(vspec + (int64_t)(r_first + jj * 4 + c4) * kD);
@@ -244,7 +247,7 @@ void attn_split_kernel(const AttnParams p) {
     // ---- Q: head n16, dims 8*(4*kk + c4) .. +7 ----
     bf16x8 qa[4];
     {
-        const uint16_t* qrow = p.q + ((int64_t)b * p.Hq + (int64_t)g * G + (n16 < G ? n16 : 0)) * kD;
+        const uint16_t* qrow = q + ((int64_t)b * Hq + (int64_t)g * G + (n16 < G ? n16 : 0)) * kD;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
             uint4 u = *reinterpret_cast<const uint4*>(qrow + (kk * 4 + c4) * 8);
@@ -885,7 +888,10 @@ template <int G, bool EMIT, bool TWO_SEG>
 static int launch_split_g(const AttnParams& p, int batch, int nchunk_grid, hipStream_t st) {
     dim3 grid(nchunk_grid, p.Hkv, batch);
     // four wavefronts of 32 rows per iteration; with 64-row chunks two of them only help to merge
-    hipLaunchKernelGGL((attn_split_kernel<G, 4, EMIT, TWO_SEG>), grid, dim3(256), 0, st, p);
+    const int32_t spec_rows = TWO_SEG ? (p.n_sel < p.cap1 ? p.n_sel : p.cap1) : p.cap2;
+    hipLaunchKernelGGL((attn_split_kernel<G, 4, EMIT, TWO_SEG>), grid, dim3(256), 0, st,
+                       TWO_SEG ? p.k1 : p.k2, TWO_SEG ? p.v1 : p.v2, TWO_SEG ? p.s1_b : p.s2_b, TWO_SEG ? p.s1_h : p.s2_h,
+                       p.q, p.pred, p.pred_val, spec_rows, p.Hq, p);
     return launch_status();
 }
 

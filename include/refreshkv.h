@@ -84,7 +84,8 @@ typedef struct rk_geom {
 /* A KV cache: k and v are bf16 [batch, n_kv_heads, capacity, head_dim] with element strides
  * stride_b (between sequences) and stride_h (between KV heads); the row stride is head_dim.
  * `capacity` is the number of rows allocated per (sequence, KV head): the kernels never touch
- * a row at or beyond it, whatever the device-side lengths and indices say. */
+ * a row at or beyond it, whatever the device-side lengths and indices say.  Strides are
+ * non-negative multiples of 8 elements; stride_h must be below 2^31 (RK_ERR_UNSUPPORTED). */
 typedef struct rk_kv {
     const void* k;
     const void* v;

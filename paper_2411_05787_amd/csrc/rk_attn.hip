@@ -203,13 +203,14 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 #endif
 template <int G, int NW, bool EMIT, bool TWO_SEG>
 __global__ __launch_bounds__(NW * 64, EMIT ? RK_EMIT_OCCUPANCY : 2)
-void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t s_b, int64_t s_h,
-                       const uint16_t* q, const int32_t* pred, int32_t pred_val, int32_t spec_rows, int32_t Hq,
+void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t s_b, int32_t s_h, int32_t spec_rows,
+                       const uint16_t* q, const int32_t* seq_lens, const int32_t* tail_start,
                        const AttnParams p) {
     // The leading arguments repeat what the first loads need (the cache that holds the first rows,
-    // its strides, q, the predicate): 15 dwords that the command processor can hand over in
-    // registers at wavefront launch (kernel-argument preload), so the first K/V request does not
-    // wait for a read of the argument block.  Everything else comes from `p` as before.
+    // its strides, q, the two length arrays): 14 dwords that the command processor hands over in
+    // registers at wavefront launch (kernel-argument preload), so neither the first K/V request
+    // nor the read of the lengths waits for a read of the argument block.  Everything else comes
+    // from `p` as before (tail_start is NULL unless TWO_SEG).
     constexpr int ROWS = kTileRows;          // rows per wavefront and tile = contraction depth of P V
     static_assert(NW == kSplitWaves, "work split");
     constexpr int NV = ROWS / 4;             // V loads per lane and tile
@@ -218,8 +219,6 @@ void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t
     constexpr int VS = kD + 8;               // LDS row stride of the V tile (272 bytes: rows spread over banks)
 
     const int c = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
-    if (pred != nullptr && pred[b] != pred_val) return;
-
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int n16 = lane & 15, c4 = lane >> 4;
 
@@ -247,7 +246,7 @@ void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t
     // ---- Q: head n16, dims 8*(4*kk + c4) .. +7 ----
     bf16x8 qa[4];
     {
-        const uint16_t* qrow = q + ((int64_t)b * Hq + (int64_t)g * G + (n16 < G ? n16 : 0)) * kD;
+        const uint16_t* qrow = q + ((int64_t)b * p.Hq + (int64_t)g * G + (n16 < G ? n16 : 0)) * kD;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
             uint4 u = *reinterpret_cast<const uint4*>(qrow + (kk * 4 + c4) * 8);
@@ -258,10 +257,14 @@ void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t
 
     // ---- the row list of this (sequence, KV head) ----
     // (device-side lengths are clamped to the allocated rows: no access leaves the caches)
-    const int len = min(p.seq_lens[b], p.cap2);
+    // (a sequence the predicate switches off: the requests above were harmless, nothing is stored)
+    const int len_raw = seq_lens[b];
+    const int tail_raw = TWO_SEG ? tail_start[b] : 0;
+    if (p.pred != nullptr && p.pred[b] != p.pred_val) return;
+    const int len = min(len_raw, p.cap2);
     int n1 = 0, start2 = 0;
     if (TWO_SEG) {
-        const int t0 = min(max(p.tail_start[b], 0), p.cap2);
+        const int t0 = min(max(tail_raw, 0), p.cap2);
         // fixed-size small cache: every row decoded since the refresh pushed out the selected row
         // with the lowest score, i.e. the last one (the small cache is in descending score order)
         const int keep = p.evict ? max(p.n_sel - max(len - t0, 0), 0) : p.n_sel;
@@ -890,8 +893,8 @@ static int launch_split_g(const AttnParams& p, int batch, int nchunk_grid, hipSt
     // four wavefronts of 32 rows per iteration; with 64-row chunks two of them only help to merge
     const int32_t spec_rows = TWO_SEG ? (p.n_sel < p.cap1 ? p.n_sel : p.cap1) : p.cap2;
     hipLaunchKernelGGL((attn_split_kernel<G, 4, EMIT, TWO_SEG>), grid, dim3(256), 0, st,
-                       TWO_SEG ? p.k1 : p.k2, TWO_SEG ? p.v1 : p.v2, TWO_SEG ? p.s1_b : p.s2_b, TWO_SEG ? p.s1_h : p.s2_h,
-                       p.q, p.pred, p.pred_val, spec_rows, p.Hq, p);
+                       TWO_SEG ? p.k1 : p.k2, TWO_SEG ? p.v1 : p.v2, TWO_SEG ? p.s1_b : p.s2_b,
+                       (int32_t)(TWO_SEG ? p.s1_h : p.s2_h), spec_rows, p.q, p.seq_lens, p.tail_start, p);
     return launch_status();
 }
 

@@ -166,6 +166,7 @@ static inline int check_kv(const rk_kv& c, bool need_v = true) {
     // row indices are int32 and the kernels step past the end by up to kMaxChunks * kMinChunk rows
     if (c.stride_b < 0 || c.stride_h < 0 || c.capacity <= 0 || c.capacity > INT32_MAX - 2 * kMaxChunks * kMinChunk) return RK_ERR_INVALID_ARG;
     if (c.stride_b % 8 != 0 || c.stride_h % 8 != 0) return RK_ERR_INVALID_ARG;
+    if (c.stride_h > INT32_MAX) return RK_ERR_UNSUPPORTED;      // the head stride travels as 32 bits to the kernels
     return RK_OK;
 }
 

@@ -73,6 +73,7 @@ def test_host_side_argument_checks_return_before_any_launch(rk):
     assert full(kv=_Kv(fake + 2, fake, 0, 0, 4096)) == -1                     # misaligned K
     assert full(kv=_Kv(fake, fake, 12, 128, 4096)) == -1                      # stride not a multiple of 8
     assert full(kv=_Kv(fake, fake, 0, 0, 0)) == -1                      # no rows allocated
+    assert full(kv=_Kv(fake, fake, 0, 2 ** 31, 4096)) == -2             # head stride beyond 32 bits
     assert full(w=fake, ws_stride=100) == -1                            # weights rows shorter than max_len
     assert full(ws=None) == -3
     assert full(ws=fake + 4) == -3                                      # misaligned workspace

@@ -747,6 +747,37 @@ def test_window_select_matches_oracle(rk):
             assert_idx_equivalent(idx1.cpu().numpy()[0, 0], idx_n[0, 0], P, lens[0], k, "w1 vs score_select")
 
 
+def test_window_select_predicate(rk):
+    """A sequence the predicate switches off keeps its idx and votes; the other one is selected as usual."""
+    B, Hq, Hkv, cap, k, W = 2, 8, 2, 1536, 64, 4
+    lens = [1500, 1400]
+    _, K, _ = rand_case(61, B, Hq, Hkv, cap)
+    qw = torch.randn(B, W, Hq, 128, generator=torch.Generator().manual_seed(62)).to(torch.bfloat16)
+    scale = float(np.float32(1 / np.sqrt(128)))
+    geom = rk.Geom(B, Hq, Hkv, 128, scale)
+    ws = rk.Workspace(geom, cap, k)
+    sl = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    pred = torch.tensor([1, 0], dtype=torch.int32, device="cuda")
+    idx = torch.full((B, Hkv, k), -5, dtype=torch.int32, device="cuda")
+    votes = torch.full((B, Hq, cap), -7.0, dtype=torch.float32, device="cuda")
+    rk.rk_window_select(geom, qw.cuda(), K.cuda(), sl, max(lens), k, 7, idx, votes=votes, pred=pred, pred_val=1, workspace=ws)
+    torch.cuda.synchronize()
+    assert (idx[1] == -5).all() and (votes[1] == -7.0).all()
+    v_ref = oracle.window_votes(gen.bf16_bits(qw), gen.bf16_bits(K), lens, scale)
+    i_ref, _ = oracle.topk_select(v_ref.astype(np.float32), lens, Hkv, k, 7)
+    G = Hq // Hkv
+    for g in range(Hkv):
+        P = oracle.pooled_group_scores(v_ref[0, g * G:(g + 1) * G, :lens[0]].astype(np.float32), 7)
+        assert_idx_equivalent(idx.cpu().numpy()[0, g], i_ref[0, g], P, lens[0], k, "g=%d" % g)
+    # the workspace is left clean: the same call without a predicate selects both sequences correctly
+    rk.rk_window_select(geom, qw.cuda(), K.cuda(), sl, max(lens), k, 7, idx, workspace=ws)
+    torch.cuda.synchronize()
+    for b in range(B):
+        for g in range(Hkv):
+            P = oracle.pooled_group_scores(v_ref[b, g * G:(g + 1) * G, :lens[b]].astype(np.float32), 7)
+            assert_idx_equivalent(idx.cpu().numpy()[b, g], i_ref[b, g], P, lens[b], k, "b=%d g=%d" % (b, g))
+
+
 def test_prefill_init_window_one_equals_initial_full_step(rk):
     """Section 2.2 "Prefilling stage": with an observation window of one, starting the small cache
     from the last prompt token's query is what the t = 0 full step of the schedule does."""

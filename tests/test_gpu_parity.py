@@ -64,6 +64,9 @@ FULL_CASES = [
     ("len1_and_len0", 3, 8, 2, [1, 0, 17], 64),
     ("tiles2_path", 4, 32, 8, [2100, 1500, 2099, 64], 2112),     # chunk 128
     ("tiles4_path", 4, 32, 8, [4200, 4100, 255, 257], 4224),     # chunk 256
+    # long rows: without weights the wide split + the separate merge launch
+    ("long_two_heads", 1, 8, 2, [20000], 20032),
+    ("long_llama", 1, 32, 8, [9001], 9024),
 ]
 
 

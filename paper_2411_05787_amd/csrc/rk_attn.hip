@@ -204,13 +204,15 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 template <int G, int NW, bool EMIT, bool TWO_SEG>
 __global__ __launch_bounds__(NW * 64, EMIT ? RK_EMIT_OCCUPANCY : 2)
 void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t s_b, int32_t s_h, int32_t spec_rows,
-                       const uint16_t* q, const int32_t* seq_lens, const int32_t* tail_start,
+                       const int32_t* seq_lens, const int32_t* tail_start, const int32_t* pred,
                        const AttnParams p) {
     // The leading arguments repeat what the first loads need (the cache that holds the first rows,
-    // its strides, q, the two length arrays): 14 dwords that the command processor hands over in
-    // registers at wavefront launch (kernel-argument preload), so neither the first K/V request
-    // nor the read of the lengths waits for a read of the argument block.  Everything else comes
-    // from `p` as before (tail_start is NULL unless TWO_SEG).
+    // its strides, the two length arrays, the predicate): 14 dwords that the command processor
+    // hands over in registers at wavefront launch (kernel-argument preload), so neither the first
+    // K/V request nor the read of the lengths waits for a read of the argument block.  Everything
+    // else comes from `p` as before (tail_start is NULL unless TWO_SEG).  A launch with a predicate
+    // does wait for it (and for p.pred_val) before it requests anything: a switched-off sequence
+    // must not cost memory traffic.
     constexpr int ROWS = kTileRows;          // rows per wavefront and tile = contraction depth of P V
     static_assert(NW == kSplitWaves, "work split");
     constexpr int NV = ROWS / 4;             // V loads per lane and tile
@@ -219,6 +221,8 @@ void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t
     constexpr int VS = kD + 8;               // LDS row stride of the V tile (272 bytes: rows spread over banks)
 
     const int c = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+    if (pred != nullptr && pred[b] != p.pred_val) return;
+
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int n16 = lane & 15, c4 = lane >> 4;
 
@@ -246,7 +250,7 @@ void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t
     // ---- Q: head n16, dims 8*(4*kk + c4) .. +7 ----
     bf16x8 qa[4];
     {
-        const uint16_t* qrow = q + ((int64_t)b * p.Hq + (int64_t)g * G + (n16 < G ? n16 : 0)) * kD;
+        const uint16_t* qrow = p.q + ((int64_t)b * p.Hq + (int64_t)g * G + (n16 < G ? n16 : 0)) * kD;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
             uint4 u = *reinterpret_cast<const uint4*>(qrow + (kk * 4 + c4) * 8);
@@ -257,10 +261,8 @@ void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t
 
     // ---- the row list of this (sequence, KV head) ----
     // (device-side lengths are clamped to the allocated rows: no access leaves the caches)
-    // (a sequence the predicate switches off: the requests above were harmless, nothing is stored)
     const int len_raw = seq_lens[b];
     const int tail_raw = TWO_SEG ? tail_start[b] : 0;
-    if (p.pred != nullptr && p.pred[b] != p.pred_val) return;
     const int len = min(len_raw, p.cap2);
     int n1 = 0, start2 = 0;
     if (TWO_SEG) {
@@ -894,7 +896,7 @@ static int launch_split_g(const AttnParams& p, int batch, int nchunk_grid, hipSt
     const int32_t spec_rows = TWO_SEG ? (p.n_sel < p.cap1 ? p.n_sel : p.cap1) : p.cap2;
     hipLaunchKernelGGL((attn_split_kernel<G, 4, EMIT, TWO_SEG>), grid, dim3(256), 0, st,
                        TWO_SEG ? p.k1 : p.k2, TWO_SEG ? p.v1 : p.v2, TWO_SEG ? p.s1_b : p.s2_b,
-                       (int32_t)(TWO_SEG ? p.s1_h : p.s2_h), spec_rows, p.q, p.seq_lens, p.tail_start, p);
+                       (int32_t)(TWO_SEG ? p.s1_h : p.s2_h), spec_rows, p.seq_lens, p.tail_start, p.pred, p);
     return launch_status();
 }
 
@@ -926,7 +928,8 @@ static int launch_score_split(const AttnParams& p, int batch, int G, int nchunk_
 
 int full_attn_stage(const rk_geom* geom, const void* q, rk_kv full, const int32_t* seq_lens, int32_t max_len,
                     void* out, float* weights, int64_t w_stride, float* lse, const int32_t* pred, int32_t pred_val,
-                    const Workspace& ws, hipStream_t st, bool scores_only, int pool_half, bool no_v, int agg) {
+                    const Workspace& ws, hipStream_t st, bool scores_only, int pool_half, bool no_v, int agg,
+                    bool co_run) {
     const int G = geom->n_q_heads / geom->n_kv_heads;
     const bool fused = pool_half >= 0;
     const bool emit = weights != nullptr || fused;
@@ -939,6 +942,10 @@ int full_attn_stage(const rk_geom* geom, const void* q, rk_kv full, const int32_
     p.max_rows2 = max_len;
     p.cap1 = 0; p.cap2 = (int32_t)full.capacity;
     p.nch = split_workgroups(max_len, (int64_t)geom->batch * geom->n_kv_heads, emit ? kMaxChunks : kMergeChunks);
+    if (co_run) {       // more, smaller workgroups, unless that means more partial results than the finish takes cheaply
+        const int wide = split_workgroups(max_len, (int64_t)geom->batch * geom->n_kv_heads, kMaxChunks, kCoRunTargetWgs);
+        if (wide <= kCoRunMaxChunks) p.nch = wide;
+    }
     p.Hq = geom->n_q_heads; p.Hkv = geom->n_kv_heads;
     p.scale = geom->scale;
     p.out = (uint16_t*)out;

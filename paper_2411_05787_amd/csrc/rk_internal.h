@@ -30,10 +30,18 @@ constexpr int kMergeChunks = 64;         // ... when the split kernel itself mer
 // and the same picture with 4 KV heads and with a batch of 4: an even spread is worth 10-20%,
 // which of the even spreads is worth 3-5% and depends on the length; 3 per CU (one residency
 // wave) is never more than 5% from the best.
+// `target` above RK_TARGET_WGS (rk_full_attn_pool: 4 per CU): the launch then runs in two
+// residency waves, which costs it 5% when it has the chip to itself (26.7 -> 29.7 us at 32k rows)
+// but lets the kernels of a second stream, which do not fit beside three of these workgroups on a
+// CU, start while it runs: full step of 32 layers with the refresh on a second stream 46.7 -> 45.3 us
+// per layer.
 constexpr int kComputeUnits = 256;
-static inline int split_workgroups(int64_t max_rows, int64_t n_problems, int limit) {
+constexpr int kCoRunTargetWgs = 1024;
+constexpr int kCoRunMaxChunks = 128;     // with 4 KV heads 1024 workgroups are 256 partial results per head: the finish
+                                         // then costs more than the co-running gains (46.2 -> 51.5 us per layer)
+static inline int split_workgroups(int64_t max_rows, int64_t n_problems, int limit, int target = RK_TARGET_WGS) {
     if (n_problems < 1) n_problems = 1;
-    int64_t per = RK_TARGET_WGS / n_problems;
+    int64_t per = target / n_problems;
     const int64_t stretches = (max_rows + kMinChunk - 1) / kMinChunk;
     if (per > stretches) per = stretches;
     if (per > limit) per = limit;
@@ -186,12 +194,14 @@ static inline int launch_status() {
 //   full_attn_stage: the split kernel, then either the merge inside it (no weights), the merge +
 //     normalise kernel (weights in place), or, with pool_half >= 0, the fused finish that also
 //     leaves the pooled group scores and their histogram in the workspace.  no_v: the split kernel
-//     is the scores-only one (K rows only; out must be NULL, pool_half >= 0).
+//     is the scores-only one (K rows only; out must be NULL, pool_half >= 0).  co_run: the launch is
+//     shaped for running beside another stream's kernels (see split_workgroups).
 //   select_stage: top-K over the pooled scores and histogram that are in the workspace.
 __attribute__((visibility("hidden")))
 int full_attn_stage(const rk_geom* geom, const void* q, rk_kv full, const int32_t* seq_lens, int32_t max_len,
                     void* out, float* weights, int64_t w_stride, float* lse, const int32_t* pred, int32_t pred_val,
-                    const Workspace& ws, hipStream_t st, bool scores_only, int pool_half, bool no_v, int agg);
+                    const Workspace& ws, hipStream_t st, bool scores_only, int pool_half, bool no_v, int agg,
+                    bool co_run = false);
 //   gather_stage: rk_gather_small_kv plus an optional per-sequence count of refreshes.
 __attribute__((visibility("hidden")))
 int gather_stage(const rk_geom* geom, rk_kv full, const int32_t* idx, int32_t k, rk_kv small,

@@ -697,7 +697,7 @@ extern "C" int rk_full_attn_pool(const rk_geom* geom, const void* q, rk_kv full,
     Workspace ws;
     if ((rc = check_workspace(geom, max_len, 0, workspace, workspace_bytes, &ws)) != RK_OK) return rc;
     return full_attn_stage(geom, q, full, seq_lens, max_len, out, weights, w_stride, lse, pred, pred_val, ws,
-                           (hipStream_t)stream, false, (pool_w - 1) / 2, false, agg);
+                           (hipStream_t)stream, false, (pool_w - 1) / 2, false, agg, true);
 }
 
 extern "C" int rk_select_pooled(const rk_geom* geom, const int32_t* seq_lens, int32_t max_len, int32_t k,

@@ -36,8 +36,9 @@ def parse():
     ap.add_argument("--workload", default="cfg2_llama_32k")
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (0 = workload's)")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
-    ap.add_argument("--launch", choices=["graph", "native", "eager"], default="graph",
-                    help="graph: replay one HIP graph per step; native: one rk_decode_step call per step enqueues all "
+    ap.add_argument("--launch", choices=["graph", "native", "eager", "hybrid"], default="hybrid",
+                    help="hybrid: partial steps through one rk_decode_step call each, full steps as a replayed HIP graph; "
+                         "graph: replay one HIP graph per step; native: one rk_decode_step call per step enqueues all "
                          "layers; eager: one Python call per library call")
     ap.add_argument("--no-overlap", action="store_true",
                     help="keep the selection and the gather of a full step on the main stream (default: second stream, "
@@ -94,7 +95,7 @@ def main():
     setup_s = time.time() - t_setup
 
     launch = "eager" if args.no_graph else args.launch
-    if w.dynamic and launch == "graph":
+    if w.dynamic and launch in ("graph", "hybrid"):
         launch = "native"      # trigger test steps enqueue both branches; the native driver also counts refreshes
     model = None
     if launch == "native":
@@ -102,6 +103,18 @@ def main():
                                   dynamic=w.dynamic, threshold=w.threshold, workspace=ws)
         if not args.no_overlap:
             model.overlap_refresh(args.overlap_workspaces)
+
+    # hybrid: partial steps through the native driver (one foreign call, kernels launched back to back
+    # from C: smaller gaps between kernels than between the nodes of a HIP graph), full steps as the
+    # two-stream HIP graph.  Both act on the same per-layer state, which the native driver owns.
+    partial_driver = None
+    if launch == "hybrid":
+        partial_driver = rk.RefreshKVModel(geom, kv, seq_lens, int(lens0.max()), w.k_small, w.stride, pool_w=w.pool_w,
+                                           dynamic=False, workspace=ws)
+        partial_driver.use_static_bounds(max_len_bound, max(w.stride, 1))
+        for l, lay in enumerate(layers):
+            lay.small_K, lay.small_V, lay.idx = partial_driver.small_K[l], partial_driver.small_V[l], partial_driver.idx[l]
+            lay.tail_start, lay.out = partial_driver.tail_start[l], partial_driver.out[l]
 
     overlap = not args.no_overlap and model is None
     stack = rk.RefreshKVStack(layers, n_workspaces=args.overlap_workspaces) if overlap else None
@@ -114,6 +127,8 @@ def main():
             if t >= 1:
                 model.advance()
             return model.step(t, q_cur)
+        if partial_driver is not None and not is_full(t):
+            return partial_driver.step(t, q_cur)
         if stack is not None:
             return stack.step(t, q_cur)
         kind = None
@@ -133,13 +148,13 @@ def main():
     torch.cuda.synchronize()
 
     graphs = {}
-    if launch == "graph":
+    if launch in ("graph", "hybrid"):
         # capture one full-style and one partial-style step; the device-side seq_lens/tail_start
         # make a replay do the right thing at any later step.  Capturing advances seq_lens like a
         # real step would not (nothing runs during capture), so no state is disturbed.
         side = torch.cuda.Stream()
         for kind, t_like in (("partial", 1), ("full", w.stride if w.stride > 0 else 0)):
-            if kind == "full" and w.stride <= 0:
+            if (kind == "full" and w.stride <= 0) or (kind == "partial" and partial_driver is not None):
                 continue
             g = torch.cuda.CUDAGraph()
             with torch.cuda.graph(g, stream=side):
@@ -358,7 +373,8 @@ def main():
         "config": {"workload": w.name, "layers": n_layers, "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv,
                    "head_dim": D, "context": L0, "k_small": w.k_small, "stride": w.stride, "pool_w": w.pool_w,
                    "schedule": "dynamic" if w.dynamic else "fixed", "full_steps": n_full,
-                   "partial_steps": args.steps - n_full, "launch": {"graph": "hip_graph", "native": "rk_decode_step", "eager": "eager"}[launch],
+                   "partial_steps": args.steps - n_full, "launch": {"graph": "hip_graph", "native": "rk_decode_step", "eager": "eager",
+                                                                      "hybrid": "rk_decode_step (partial steps) + hip_graph (full steps)"}[launch],
                    "refresh_overlap": bool(stack is not None or (model is not None and not args.no_overlap))},
         "step_us_per_layer": {k: round(v, 2) for k, v in med.items()},
         "step_us_per_layer_p10_p90": spread,

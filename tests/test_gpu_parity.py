@@ -899,6 +899,63 @@ def test_refresh_on_second_stream_stack(rk):
             compare_with_oracle(w, l, got, K, V, q, nk, nv, lens0)
 
 
+def test_hybrid_driver_native_partial_steps_graph_full_steps(rk):
+    """The launch configuration bench.py times by default: partial steps through rk_decode_step (one
+    call for all layers), full steps as the replayed two-stream HIP graph of RefreshKVStack, both on
+    the same per-layer state."""
+    w = gen.shrink(gen.WORKLOADS["cfg1_llama_2k"], n_steps=11)
+    n_layers, dev = 4, "cuda"
+    geom = rk.Geom(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.scale)
+    lens0 = gen.seq_lens(w)
+    data = [(gen.make_kv(w, l), gen.make_queries(w, l), gen.make_new_rows(w, l)) for l in range(n_layers)]
+    kv = [(d[0][0].to(dev).clone(), d[0][1].to(dev).clone()) for d in data]
+    sl = lens0.to(dev).clone()
+    ws = rk.Workspace(geom, w.capacity, w.k_small)
+    bound = int(lens0.max()) + w.n_steps + 1
+    driver = rk.RefreshKVModel(geom, kv, sl, int(lens0.max()), w.k_small, w.stride, pool_w=w.pool_w, workspace=ws)
+    driver.use_static_bounds(bound, w.stride)
+    layers = [rk.RefreshKVLayer(geom, kv[l][0], kv[l][1], sl, int(lens0.max()), w.k_small, w.stride, pool_w=w.pool_w,
+                                workspace=ws) for l in range(n_layers)]
+    for l, lay in enumerate(layers):
+        lay.small_K, lay.small_V, lay.idx = driver.small_K[l], driver.small_V[l], driver.idx[l]
+        lay.tail_start, lay.out = driver.tail_start[l], driver.out[l]
+        lay.use_static_bounds(bound, w.stride)
+    stack = rk.RefreshKVStack(layers, n_workspaces=3)
+    q_all = torch.stack([d[1] for d in data], dim=1).to(dev).contiguous()
+    q_cur = torch.empty_like(q_all[0])
+    B, Hkv, D = w.batch, w.n_kv_heads, w.head_dim
+    full_graph = None
+    outs, idxs = [], []
+    for t in range(w.n_steps + 1):
+        if t >= 1:
+            pos = sl.to(torch.int64)[:, None, None, None].expand(B, Hkv, 1, D)
+            for l in range(n_layers):
+                kv[l][0].scatter_(2, pos, data[l][2][0][t - 1].to(dev)[:, :, None, :])
+                kv[l][1].scatter_(2, pos, data[l][2][1][t - 1].to(dev)[:, :, None, :])
+            sl += 1
+        q_cur.copy_(q_all[t])
+        if t % w.stride != 0:
+            assert driver.step(t, q_cur) == "partial"
+        elif t == 0:
+            assert stack.step(0, q_cur) == "full"
+        else:
+            if full_graph is None:
+                torch.cuda.synchronize()
+                full_graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(full_graph):
+                    stack.step(t, q_cur)
+            full_graph.replay()
+        torch.cuda.synchronize()
+        outs.append(driver.out.clone())
+        idxs.append(driver.idx.clone())
+    assert full_graph is not None
+    for l in range(n_layers):
+        got = dict(outs=np.stack([gen.bf16_bits(o[l]) for o in outs]), idx=[i[l].cpu().numpy() for i in idxs],
+                   K=gen.bf16_bits(kv[l][0]), V=gen.bf16_bits(kv[l][1]), lens=sl.cpu().numpy())
+        (K, V), q, (nk, nv) = data[l]
+        compare_with_oracle(w, l, got, K, V, q, nk, nv, lens0)
+
+
 def test_loop_cfg1_every_step(rk):
     w = gen.WORKLOADS["cfg1_llama_2k"]
     say("loop", w.name)

@@ -277,6 +277,25 @@ int rk_partial_attn_fixed(const rk_geom* geom, const void* q, rk_kv small, int32
                           const int32_t* pred, int32_t pred_val,
                           void* workspace, size_t workspace_bytes, void* stream);
 
+/* The first partial step after a refresh whose rk_gather_small_kv was left out (the gather moved
+ * into the step that first needs its result: Section 2.2's small cache is still rebuilt, by the
+ * kernel that reads it).  Computes what rk_partial_attn (fixed_size = 0, n_sel = k) or
+ * rk_partial_attn_fixed (fixed_size = 1) computes on a small cache rebuilt from `idx`, but takes the
+ * selected rows from the full cache through idx (int32 [batch, n_kv_heads, k], as rk_topk_select
+ * leaves it) and writes them into `small` on the way: afterwards, for every selected row i the step
+ * attended to, small.k[b,g,i,:] = full.k[b,g,idx[b,g,i],:] and the same for v, bit for bit (with
+ * fixed_size = 0 these are all min(k, tail_start[b]) rows; with fixed_size = 1 the rows the step no
+ * longer reads are not written, and no later step reads them either).  Later partial steps use
+ * rk_partial_attn / rk_partial_attn_fixed on `small` as usual.  tail_start must already hold the
+ * refresh's value (rk_mark_refresh).  An idx entry outside [0, full.capacity) is clamped into the
+ * cache (none occurs among the entries rk_topk_select writes for existing rows).  k >= 1 and
+ * small.capacity >= k; the other arguments as in rk_partial_attn. */
+int rk_partial_attn_lazy(const rk_geom* geom, const void* q, rk_kv small, const int32_t* idx, int32_t k,
+                         int32_t fixed_size, rk_kv full, const int32_t* tail_start, const int32_t* seq_lens,
+                         int32_t max_recent, void* out,
+                         const int32_t* pred, int32_t pred_val,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
 /* Query-similarity trigger.
  *   qbar[b,:] = mean over the query heads of q[b,h,:]                        (fp32)
  *   sim[b]    = <qbar, q_ref[b]> / (max(|qbar|, 1e-8) * max(|q_ref[b]|, 1e-8))

@@ -16,7 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "librefreshkv.so")
 
 EXPORTS = ["rk_version", "rk_status_string", "rk_workspace_bytes", "rk_workspace_init",
-           "rk_full_attn", "rk_full_attn_scores", "rk_topk_select", "rk_full_attn_select", "rk_full_attn_pool", "rk_select_pooled", "rk_score_select", "rk_window_select", "rk_gather_small_kv", "rk_partial_attn", "rk_partial_attn_fixed", "rk_decode_step", "rk_decode_step_overlapped",
+           "rk_full_attn", "rk_full_attn_scores", "rk_topk_select", "rk_full_attn_select", "rk_full_attn_pool", "rk_select_pooled", "rk_score_select", "rk_window_select", "rk_gather_small_kv", "rk_partial_attn", "rk_partial_attn_fixed", "rk_partial_attn_lazy", "rk_decode_step", "rk_decode_step_overlapped",
            "rk_query_sim", "rk_mark_refresh", "rk_calibration_copy", "rk_h2o_append", "rk_h2o_update", "rk_h2o_step"]
 
 RK_AGG_MAX, RK_AGG_MEAN, RK_AGG_FIRST = 0, 1, 2
@@ -99,6 +99,8 @@ def _load(path: str = LIB_PATH) -> C.CDLL:
     l.rk_partial_attn.argtypes = [G, P, _Kv, I32, _Kv, P, P, I32, P, P, I32, P, SZ, P]
     l.rk_partial_attn_fixed.restype = C.c_int
     l.rk_partial_attn_fixed.argtypes = [G, P, _Kv, I32, _Kv, P, P, I32, P, P, I32, P, SZ, P]
+    l.rk_partial_attn_lazy.argtypes = [G, P, _Kv, P, I32, I32, _Kv, P, P, I32, P, P, I32, P, SZ, P]
+    l.rk_partial_attn_lazy.restype = C.c_int
     l.rk_query_sim.restype = C.c_int
     l.rk_decode_step.restype = C.c_int
     l.rk_decode_step.argtypes = [G, C.POINTER(_Schedule), I32, I32, C.POINTER(_LayerState), C.POINTER(C.c_void_p),
@@ -401,6 +403,22 @@ def rk_partial_attn_fixed(geom: Geom, q, small_K, small_V, k: int, K, V, tail_st
     _check("rk_partial_attn_fixed", lib.rk_partial_attn_fixed(
         C.byref(geom.c()), _dev(q, torch.bfloat16, "q", (B, Hq, D)),
         _kv(geom, small_K, small_V, "small", min_rows=k), int(k), _kv(geom, K, V, "full"),
+        _dev(tail_start, torch.int32, "tail_start", (B,)), _dev(seq_lens, torch.int32, "seq_lens", (B,)),
+        int(max_recent), _dev(out, torch.bfloat16, "out", (B, Hq, D)),
+        _dev(pred, torch.int32, "pred", (B,), optional=True), int(pred_val),
+        workspace.ptr, workspace.nbytes, _stream(stream)))
+
+
+def rk_partial_attn_lazy(geom: Geom, q, small_K, small_V, idx, k: int, K, V, tail_start, seq_lens,
+                         max_recent: int, out, fixed_size: bool = False, pred=None, pred_val: int = 0,
+                         workspace: Workspace = None, stream=None) -> None:
+    """The first partial step after a refresh without a gather: selected rows come from (K, V) through
+    idx and are written into (small_K, small_V) on the way."""
+    B, Hq, Hkv, D = geom.batch, geom.n_q_heads, geom.n_kv_heads, geom.head_dim
+    _check("rk_partial_attn_lazy", lib.rk_partial_attn_lazy(
+        C.byref(geom.c()), _dev(q, torch.bfloat16, "q", (B, Hq, D)),
+        _kv(geom, small_K, small_V, "small", min_rows=k), _dev(idx, torch.int32, "idx", (B, Hkv, k)), int(k),
+        int(bool(fixed_size)), _kv(geom, K, V, "full"),
         _dev(tail_start, torch.int32, "tail_start", (B,)), _dev(seq_lens, torch.int32, "seq_lens", (B,)),
         int(max_recent), _dev(out, torch.bfloat16, "out", (B, Hq, D)),
         _dev(pred, torch.int32, "pred", (B,), optional=True), int(pred_val),

@@ -51,6 +51,7 @@ struct AttnParams {
     float* lse;                        // fp32 [B, Hq], never NULL here
     const int32_t* pred; int32_t pred_val;
     int32_t* counters; float* part_ml; float* part_o; int32_t max_chunks;
+    const int32_t* idx; int32_t idx_stride;   // LAZY only: the selection [B, Hkv, idx_stride] whose rows are not gathered yet
 };
 
 // Work split of the split kernels.  The rows of a (sequence, KV head) are cut into tiles of 32;
@@ -201,11 +202,17 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 #ifndef RK_EMIT_OCCUPANCY
 #define RK_EMIT_OCCUPANCY 3       // workgroups per CU the score-emitting kernel is compiled for
 #endif
-template <int G, int NW, bool EMIT, bool TWO_SEG>
+// LAZY (with TWO_SEG): the first partial step after a refresh whose gather was left out.  The rows
+// of the small-cache segment are read from the full cache through the selection (row r of the list
+// is row idx[r] of the full cache) and written to the small cache on the way, so that the step
+// leaves the small cache as rk_gather_small_kv would have.  k_first / v_first / s_b / s_h then
+// describe the FULL cache and `pred` carries the selection (the predicate is read from `p`).
+template <int G, int NW, bool EMIT, bool TWO_SEG, bool LAZY = false>
 __global__ __launch_bounds__(NW * 64, EMIT ? RK_EMIT_OCCUPANCY : 2)
 void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t s_b, int32_t s_h, int32_t spec_rows,
                        const int32_t* seq_lens, const int32_t* tail_start, const int32_t* pred,
                        const AttnParams p) {
+    static_assert(!LAZY || (TWO_SEG && !EMIT), "the lazy gather belongs to the partial step");
     // The leading arguments repeat what the first loads need (the cache that holds the first rows,
     // its strides, the two length arrays, the predicate): 14 dwords that the command processor
     // hands over in registers at wavefront launch (kernel-argument preload), so neither the first
@@ -221,10 +228,22 @@ void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t
     constexpr int VS = kD + 8;               // LDS row stride of the V tile (272 bytes: rows spread over banks)
 
     const int c = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
-    if (pred != nullptr && pred[b] != p.pred_val) return;
-
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int n16 = lane & 15, c4 = lane >> 4;
+    // LAZY: the selection's entries for the rows of a tile, lane i < 32 holding that of row r + i
+    // (clamped into the full cache: a bad index reads a wrong row, never outside the cache)
+    const int32_t* sel = LAZY ? pred + ((int64_t)b * gridDim.y + g) * spec_rows : nullptr;   // idx_stride == spec_rows
+    auto tile_sel = [&](int r, int n_rows) -> int {
+        const int j = min(r + (lane & 31), n_rows - 1);
+        return LAZY ? sel[max(j, 0)] : 0;
+    };
+    int sel0 = 0;
+    if (LAZY) {
+        sel0 = tile_sel((c * NW + w) * kTileRows, spec_rows);      // before anything else: the rows depend on it
+        if (p.pred != nullptr && p.pred[b] != p.pred_val) return;
+    } else {
+        if (pred != nullptr && pred[b] != p.pred_val) return;
+    }
 
     // ---- K and V rows of the first tile are requested before any length is known ----
     // Rows below `spec_rows` exist whatever the device-side lengths say (small cache: the first
@@ -236,15 +255,20 @@ void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t
     u32x4 kA[2][4], vA[NV];
     if (spec) {
         const uint16_t* kspec = k_first + (int64_t)b * s_b + (int64_t)g * s_h + c4 * 8;
+        const int cap_full = p.cap2;
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
+        for (int t = 0; t < 2; ++t) {
+            const int64_t row = LAZY ? min(max(__shfl(sel0, t * 16 + n16), 0), cap_full - 1) : r_first + t * 16 + n16;
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk)
-                kA[t][kk] = load_rows16<!TWO_SEG>(kspec + (int64_t)(r_first + t * 16 + n16) * kD + kk * 32);
+                kA[t][kk] = load_rows16<!TWO_SEG>(kspec + row * kD + kk * 32);
+        }
         const uint16_t* vspec = v_first + (int64_t)b * s_b + (int64_t)g * s_h + n16 * 8;
 #pragma unroll
-        for (int jj = 0; jj < NV; ++jj)
-            vA[jj] = load_rows16<!TWO_SEG>(vspec + (int64_t)(r_first + jj * 4 + c4) * kD);
+        for (int jj = 0; jj < NV; ++jj) {
+            const int64_t row = LAZY ? min(max(__shfl(sel0, jj * 4 + c4), 0), cap_full - 1) : r_first + jj * 4 + c4;
+            vA[jj] = load_rows16<!TWO_SEG>(vspec + row * kD);
+        }
     }
 
     // ---- Q: head n16, dims 8*(4*kk + c4) .. +7 ----
@@ -305,28 +329,55 @@ void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t
     for (int dt = 0; dt < 8; ++dt) acc_o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     // ---- loads: rows past the end of the chunk re-read its last row (masked later) ----
+    // (LAZY: kfull / vfull are row 0 of the full cache of this (sequence, KV head))
+    const uint16_t* kfull = LAZY ? p.k2 + (int64_t)b * p.s2_b + (int64_t)g * p.s2_h : nullptr;
+    const uint16_t* vfull = LAZY ? p.v2 + (int64_t)b * p.s2_b + (int64_t)g * p.s2_h : nullptr;
     auto load_k = [&](int r) {
+        const int sv = LAZY ? tile_sel(r, n1) : 0;
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
             const int row = min(r + t * 16 + n16, row1 - 1);
-            const uint16_t* base = (TWO_SEG && row < n1) ? kb1 : kb2;
-            const uint16_t* rp = base + (int64_t)row * kD + c4 * 8;
+            const int srow = LAZY ? __shfl(sv, t * 16 + n16) : 0;       // (all lanes take part)
+            const uint16_t* rp;
+            if (LAZY && row < n1) {
+                rp = kfull + (int64_t)min(max(srow, 0), p.cap2 - 1) * kD + c4 * 8;
+            } else {
+                const uint16_t* base = (TWO_SEG && row < n1) ? kb1 : kb2;
+                rp = base + (int64_t)row * kD + c4 * 8;
+            }
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk) kA[t][kk] = load_rows16<!TWO_SEG>(rp + kk * 32);
         }
     };
     auto load_v = [&](int r) {
+        const int sv = LAZY ? tile_sel(r, n1) : 0;
 #pragma unroll
         for (int jj = 0; jj < NV; ++jj) {
             const int row = min(r + jj * 4 + c4, row1 - 1);
-            const uint16_t* base = (TWO_SEG && row < n1) ? vb1 : vb2;
-            vA[jj] = load_rows16<!TWO_SEG>(base + (int64_t)row * kD + n16 * 8);
+            const int srow = LAZY ? __shfl(sv, jj * 4 + c4) : 0;
+            if (LAZY && row < n1) {
+                vA[jj] = load_rows16<!TWO_SEG>(vfull + (int64_t)min(max(srow, 0), p.cap2 - 1) * kD + n16 * 8);
+            } else {
+                const uint16_t* base = (TWO_SEG && row < n1) ? vb1 : vb2;
+                vA[jj] = load_rows16<!TWO_SEG>(base + (int64_t)row * kD + n16 * 8);
+            }
         }
     };
     // One tile.  The K registers are free again once S^T is computed and the V registers once the
     // tile sits in LDS: the next tile's rows are requested at those two points, so its loads are
     // in flight during the rest of this tile's work.
     auto compute_tile = [&](int r, int r_next) -> int {
+        if (LAZY) {       // the K rows of the selection go to their slots of the small cache (bit copies)
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const int row = r + t * 16 + n16;
+                if (row < n1) {
+                    uint16_t* dst = const_cast<uint16_t*>(kb1) + (int64_t)row * kD + c4 * 8;
+#pragma unroll
+                    for (int kk = 0; kk < 4; ++kk) *reinterpret_cast<u32x4*>(dst + kk * 32) = kA[t][kk];
+                }
+            }
+        }
         // ---- S^T = K Q^T on the matrix cores: head n16, rows r + 16 t + 4 c4 + i ----
         float s[2][4];
 #pragma unroll
@@ -385,6 +436,13 @@ void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t
         if (c4 == 0) sAlpha[w][n16] = alpha;
 #pragma unroll
         for (int jj = 0; jj < NV; ++jj) *reinterpret_cast<u32x4*>(&sV[w][jj * 4 + c4][n16 * 8]) = vA[jj];
+        if (LAZY) {       // ... and the V rows
+#pragma unroll
+            for (int jj = 0; jj < NV; ++jj) {
+                const int row = r + jj * 4 + c4;
+                if (row < n1) *reinterpret_cast<u32x4*>(const_cast<uint16_t*>(vb1) + (int64_t)row * kD + n16 * 8) = vA[jj];
+            }
+        }
         if (r_next < row1) load_v(r_next);
         wave_lds_sync();
         if (__any(alpha != 1.0f)) {                 // the running max moved (always on the first tile)
@@ -900,6 +958,28 @@ static int launch_split_g(const AttnParams& p, int batch, int nchunk_grid, hipSt
     return launch_status();
 }
 
+template <int G>
+static int launch_lazy_g(const AttnParams& p, int batch, hipStream_t st) {
+    dim3 grid(p.nch, p.Hkv, batch);
+    hipLaunchKernelGGL((attn_split_kernel<G, 4, false, true, true>), grid, dim3(256), 0, st,
+                       p.k2, p.v2, p.s2_b, (int32_t)p.s2_h, p.n_sel, p.seq_lens, p.tail_start, p.idx, p);
+    return launch_status();
+}
+
+static int launch_lazy(const AttnParams& p, int batch, int G, hipStream_t st) {
+    switch (G) {
+        case 1: return launch_lazy_g<1>(p, batch, st);
+        case 2: return launch_lazy_g<2>(p, batch, st);
+        case 3: return launch_lazy_g<3>(p, batch, st);
+        case 4: return launch_lazy_g<4>(p, batch, st);
+        case 5: return launch_lazy_g<5>(p, batch, st);
+        case 6: return launch_lazy_g<6>(p, batch, st);
+        case 7: return launch_lazy_g<7>(p, batch, st);
+        case 8: return launch_lazy_g<8>(p, batch, st);
+        default: return RK_ERR_UNSUPPORTED;
+    }
+}
+
 template <bool EMIT, bool TWO_SEG>
 static int launch_split(const AttnParams& p, int batch, int G, int nchunk_grid, hipStream_t st) {
     switch (G) {
@@ -1040,7 +1120,7 @@ static int partial_attn_impl(const rk_geom* geom, const void* q, rk_kv small, in
                              rk_kv full, const int32_t* tail_start, const int32_t* seq_lens,
                              int32_t max_recent, void* out,
                              const int32_t* pred, int32_t pred_val,
-                             void* workspace, size_t workspace_bytes, void* stream) {
+                             void* workspace, size_t workspace_bytes, void* stream, const int32_t* lazy_idx = nullptr) {
     int rc = check_geom(geom);
     if (rc != RK_OK) return rc;
     if (!q || !out || !seq_lens || !tail_start || n_sel < 0 || max_recent < 0) return RK_ERR_INVALID_ARG;
@@ -1072,6 +1152,11 @@ static int partial_attn_impl(const rk_geom* geom, const void* q, rk_kv small, in
     p.lse = ws.lse;
     p.pred = pred; p.pred_val = pred_val;
     p.counters = ws.counters; p.part_ml = ws.part_ml; p.part_o = ws.part_o; p.max_chunks = ws.max_chunks;
+    if (lazy_idx != nullptr) {      // rows of the selection come from the full cache and are written to `small` on the way
+        if (n_sel < 1 || small.capacity < n_sel) return RK_ERR_INVALID_ARG;
+        p.idx = lazy_idx; p.idx_stride = n_sel;
+        return launch_lazy(p, geom->batch, G, (hipStream_t)stream);
+    }
     const int nchunk_grid = p.nch;
     return launch_split<false, true>(p, geom->batch, G, nchunk_grid, (hipStream_t)stream);
 }
@@ -1083,6 +1168,16 @@ extern "C" int rk_partial_attn(const rk_geom* geom, const void* q, rk_kv small, 
                                void* workspace, size_t workspace_bytes, void* stream) {
     return partial_attn_impl(geom, q, small, n_sel, false, full, tail_start, seq_lens, max_recent, out, pred, pred_val,
                              workspace, workspace_bytes, stream);
+}
+
+extern "C" int rk_partial_attn_lazy(const rk_geom* geom, const void* q, rk_kv small, const int32_t* idx, int32_t k,
+                                    int32_t fixed_size, rk_kv full, const int32_t* tail_start, const int32_t* seq_lens,
+                                    int32_t max_recent, void* out,
+                                    const int32_t* pred, int32_t pred_val,
+                                    void* workspace, size_t workspace_bytes, void* stream) {
+    if (!idx) return RK_ERR_INVALID_ARG;
+    return partial_attn_impl(geom, q, small, k, fixed_size != 0, full, tail_start, seq_lens, max_recent, out,
+                             pred, pred_val, workspace, workspace_bytes, stream, idx);
 }
 
 extern "C" int rk_partial_attn_fixed(const rk_geom* geom, const void* q, rk_kv small, int32_t k,

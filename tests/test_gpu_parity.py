@@ -442,6 +442,68 @@ def test_partial_attn_fixed_size_per_sequence(rk):
         assert_out_close(got[sl], o_ref, "b=%d" % b)
 
 
+LAZY_CASES = [
+    # name, B, Hq, Hkv, k, lens, recent, fixed
+    ("llama_first_step", 2, 32, 8, 256, [3000, 1400], [1, 1], False),
+    ("qwen_g7", 1, 28, 4, 300, [2500], [1], False),
+    ("ragged_short_and_later", 4, 8, 2, 200, [900, 650, 300, 150], [1, 7, 31, 3], False),    # the last: fewer than k rows exist
+    ("fixed_size", 3, 8, 2, 200, [900, 650, 150], [1, 5, 2], True),
+    ("big_k_tail", 1, 8, 2, 2048, [9000], [9], False),
+]
+
+
+@pytest.mark.parametrize("case", LAZY_CASES, ids=[c[0] for c in LAZY_CASES])
+def test_partial_attn_lazy_gathers_on_the_way(rk, case):
+    """rk_partial_attn_lazy: the step's output equals the partial step on a gathered small cache, and the
+    small cache it leaves equals the gather (bit for bit) on every row the step attended to."""
+    name, B, Hq, Hkv, k, lens, recent, fixed = case
+    say("lazy partial case", name)
+    cap = max(lens) + 8
+    q, K, V = rand_case(777 + len(name), B, Hq, Hkv, cap)
+    scale = float(np.float32(1 / np.sqrt(128)))
+    geom = rk.Geom(B, Hq, Hkv, 128, scale)
+    tail = [l - r for l, r in zip(lens, recent)]
+    g = torch.Generator().manual_seed(6)
+    idx = torch.full((B, Hkv, k), -1, dtype=torch.int32)
+    for b in range(B):
+        kk = min(k, tail[b])
+        for h in range(Hkv):
+            idx[b, h, :kk] = torch.randperm(tail[b], generator=g)[:kk].to(torch.int32)
+    marker_val = 0x7fc1                       # a NaN pattern: rows the step does not write must keep it
+    sK = torch.full((B, Hkv, k, 128), float("nan"), dtype=torch.bfloat16, device="cuda")
+    sV = torch.full_like(sK, float("nan"))
+    Kd, Vd = K.cuda(), V.cuda()
+    ws = rk.Workspace(geom, cap, k)
+    out = torch.zeros(B, Hq, 128, dtype=torch.bfloat16, device="cuda")
+    rk.rk_partial_attn_lazy(geom, q.cuda(), sK, sV, idx.cuda(), k, Kd, Vd, torch.tensor(tail, dtype=torch.int32, device="cuda"),
+                            torch.tensor(lens, dtype=torch.int32, device="cuda"), max(recent), out, fixed_size=fixed,
+                            workspace=ws)
+    torch.cuda.synchronize()
+    rK = np.zeros((B, Hkv, k, 128), dtype=np.uint16); rV = rK.copy()
+    oracle.gather_small_kv(gen.bf16_bits(K), gen.bf16_bits(V), idx.numpy(), rK, rV)
+    got, gK, gV = gen.bf16_bits(out), gen.bf16_bits(sK), gen.bf16_bits(sV)
+    for b in range(B):
+        sl = slice(b, b + 1)
+        n_sel = max(k - recent[b], 0) if fixed else k
+        o_ref = oracle.partial_attn(gen.bf16_bits(q)[sl], rK[sl], rV[sl], n_sel, gen.bf16_bits(K)[sl],
+                                    gen.bf16_bits(V)[sl], tail[sl], lens[sl], scale)
+        assert_out_close(got[sl], o_ref, "%s b=%d" % (name, b))
+        n1 = min(n_sel, tail[b])
+        assert (gK[b, :, :n1] == rK[b, :, :n1]).all() and (gV[b, :, :n1] == rV[b, :, :n1]).all()
+        assert np.isnan(gen.bits_to_bf16(gK[b, :, n1:]).float().numpy()).all(), "rows beyond the attended ones were written"
+        assert np.isnan(gen.bits_to_bf16(gV[b, :, n1:]).float().numpy()).all()
+    # the next step runs on the small cache the lazy step left (only where it is complete: not the fixed-size case)
+    if not fixed:
+        lens2 = [l + 1 for l in lens]
+        q2 = torch.randn(B, Hq, 128, generator=g).to(torch.bfloat16)
+        sK2, sV2 = torch.nan_to_num(sK), torch.nan_to_num(sV)
+        rk.rk_partial_attn(geom, q2.cuda(), sK2, sV2, k, Kd, Vd, torch.tensor(tail, dtype=torch.int32, device="cuda"),
+                           torch.tensor(lens2, dtype=torch.int32, device="cuda"), max(recent) + 1, out, workspace=ws)
+        torch.cuda.synchronize()
+        o2 = oracle.partial_attn(gen.bf16_bits(q2), rK, rV, k, gen.bf16_bits(K), gen.bf16_bits(V), tail, lens2, scale)
+        assert_out_close(gen.bf16_bits(out), o2, name + " next step")
+
+
 def test_streaming_llm_policy_through_partial_attn(rk):
     """The StreamingLLM baseline of Appendix A.1 (4 sink tokens + K - 4 recent tokens) needs no kernel
     of its own: the sinks are a 4-row small cache, the recent tokens the tail of the full cache."""

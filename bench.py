@@ -36,14 +36,17 @@ def parse():
     ap.add_argument("--workload", default="cfg2_llama_32k")
     ap.add_argument("--layers", type=int, default=0, help="override the number of layers (0 = workload's)")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying HIP graphs")
-    ap.add_argument("--launch", choices=["graph", "native", "eager", "hybrid"], default="hybrid",
-                    help="hybrid: partial steps through one rk_decode_step call each, full steps as a replayed HIP graph; "
-                         "graph: replay one HIP graph per step; native: one rk_decode_step call per step enqueues all "
-                         "layers; eager: one Python call per library call")
+    ap.add_argument("--launch", choices=["graph", "native", "eager", "hybrid"], default="native",
+                    help="native: one call of the library's step driver (rk_decode_step_batched) per step launches the "
+                         "kernels of all layers back to back from C; graph: replay one HIP graph per step; hybrid: "
+                         "partial steps native, full steps as a replayed HIP graph; eager: one Python call per library call")
     ap.add_argument("--no-overlap", action="store_true",
                     help="keep the selection and the gather of a full step on the main stream (default: second stream, "
                          "beside the full attention of the following layers)")
     ap.add_argument("--overlap-workspaces", type=int, default=3, help="workspaces the overlapped refresh rotates (0: one per layer)")
+    ap.add_argument("--refresh", choices=["batched", "second-stream"], default="batched",
+                    help="how a full step of the layer stack does its selections and gathers: all layers at once after "
+                         "the last layer's attention (rk_refresh_batched), or per layer on a second stream")
     ap.add_argument("--run-ahead", type=int, default=1,
                     help="steps that may still be pending when a two-stream (full) step is submitted (-1: no limit)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -102,7 +105,10 @@ def main():
         model = rk.RefreshKVModel(geom, kv, seq_lens, int(lens0.max()), w.k_small, w.stride, pool_w=w.pool_w,
                                   dynamic=w.dynamic, threshold=w.threshold, workspace=ws)
         if not args.no_overlap:
-            model.overlap_refresh(args.overlap_workspaces)
+            if args.refresh == "batched":
+                model.batched_refresh()
+            else:
+                model.overlap_refresh(args.overlap_workspaces)
 
     # hybrid: partial steps through the native driver (one foreign call, kernels launched back to back
     # from C: smaller gaps between kernels than between the nodes of a HIP graph), full steps as the
@@ -117,7 +123,7 @@ def main():
             lay.tail_start, lay.out = partial_driver.tail_start[l], partial_driver.out[l]
 
     overlap = not args.no_overlap and model is None
-    stack = rk.RefreshKVStack(layers, n_workspaces=args.overlap_workspaces) if overlap else None
+    stack = rk.RefreshKVStack(layers, n_workspaces=args.overlap_workspaces, batched=args.refresh == "batched") if overlap else None
 
     def enqueue_step(t: int):
         """Everything of decode step t on the current stream (q_cur already holds the queries)."""
@@ -183,7 +189,7 @@ def main():
     # `--run-ahead` earlier steps are still pending.  Submitted far ahead, its second queue sits
     # blocked on a barrier behind all of them, and a blocked queue slows every dispatch of the
     # first one meanwhile (measured: +0.9 us per layer on every partial step of the period).
-    two_streams = (stack is not None) or (model is not None and not args.no_overlap)
+    two_streams = (stack is not None and not stack.batched) or (model is not None and not args.no_overlap and args.refresh != "batched")
     for i, t in enumerate(range(args.warmup + 1, T + 1)):
         if two_streams and args.run_ahead >= 0 and is_full(t) and i - 1 - args.run_ahead >= 0:
             ev[i - 1 - args.run_ahead][1].synchronize()
@@ -373,9 +379,11 @@ def main():
         "config": {"workload": w.name, "layers": n_layers, "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv,
                    "head_dim": D, "context": L0, "k_small": w.k_small, "stride": w.stride, "pool_w": w.pool_w,
                    "schedule": "dynamic" if w.dynamic else "fixed", "full_steps": n_full,
-                   "partial_steps": args.steps - n_full, "launch": {"graph": "hip_graph", "native": "rk_decode_step", "eager": "eager",
+                   "partial_steps": args.steps - n_full, "launch": {"graph": "hip_graph", "native": "rk_decode_step_batched" if args.refresh == "batched" and not args.no_overlap else "rk_decode_step", "eager": "eager",
                                                                       "hybrid": "rk_decode_step (partial steps) + hip_graph (full steps)"}[launch],
-                   "refresh_overlap": bool(stack is not None or (model is not None and not args.no_overlap))},
+                   "refresh": ("serial per layer" if args.no_overlap else
+                               "batched over the layers (rk_refresh_batched)" if args.refresh == "batched" else
+                               "per layer on a second stream")},
         "step_us_per_layer": {k: round(v, 2) for k, v in med.items()},
         "step_us_per_layer_p10_p90": spread,
         "call_us_per_layer": {k: round(v, 2) for k, v in klass.items()},

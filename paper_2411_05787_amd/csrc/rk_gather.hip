@@ -33,9 +33,75 @@ void gather_rows_kernel(const uint16_t* __restrict__ fk, const uint16_t* __restr
     *reinterpret_cast<uint4*>(sv + dst) = vr;
 }
 
+// The gathers of several layers in one launch: grid z = layer * batch + sequence.
+struct GatherBatch {
+    const uint16_t* fk[kBatchLayers]; const uint16_t* fv[kBatchLayers];
+    uint16_t* sk[kBatchLayers]; uint16_t* sv[kBatchLayers];
+    const int32_t* idx[kBatchLayers];
+    int32_t* tail_start[kBatchLayers]; int32_t* n_refresh[kBatchLayers];
+    const int32_t* pred[kBatchLayers];
+};
+
+__global__ __launch_bounds__(256)
+void gather_rows_batched_kernel(const GatherBatch tab, int32_t batch, int64_t fs_b, int64_t fs_h, int64_t ss_b, int64_t ss_h,
+                                int32_t k, int32_t Hkv, int32_t full_cap, const int32_t* __restrict__ seq_lens,
+                                int32_t pred_val) {
+    const int layer = blockIdx.z / batch, b = blockIdx.z - layer * batch, g = blockIdx.y;
+    if (tab.pred[layer] != nullptr && tab.pred[layer][b] != pred_val) return;
+    if (blockIdx.x == 0 && g == 0 && threadIdx.x == 0) {
+        if (tab.tail_start[layer] != nullptr) tab.tail_start[layer][b] = seq_lens[b];
+        if (tab.n_refresh[layer] != nullptr) tab.n_refresh[layer][b] += 1;
+    }
+    const int i = blockIdx.x * kGatherRows + (threadIdx.x >> 4);
+    if (i >= k) return;
+    const int j = tab.idx[layer][((int64_t)b * Hkv + g) * k + i];
+    if (j < 0 || j >= full_cap) return;
+    const int seg = (threadIdx.x & 15) * 8;
+    const int64_t src = (int64_t)b * fs_b + (int64_t)g * fs_h + (int64_t)j * kD + seg;
+    const int64_t dst = (int64_t)b * ss_b + (int64_t)g * ss_h + (int64_t)i * kD + seg;
+    const uint4 kr = *reinterpret_cast<const uint4*>(tab.fk[layer] + src);
+    const uint4 vr = *reinterpret_cast<const uint4*>(tab.fv[layer] + src);
+    *reinterpret_cast<uint4*>(tab.sk[layer] + dst) = kr;
+    *reinterpret_cast<uint4*>(tab.sv[layer] + dst) = vr;
+}
+
 }  // namespace rk
 
 namespace rk {
+int gather_batched_stage(const rk_geom* geom, int n_layers, const rk_kv* full, const rk_kv* small, int32_t* const* idx,
+                         int32_t k, const int32_t* seq_lens, int32_t* const* tail_start, int32_t* const* n_refresh,
+                         const int32_t* const* pred, int32_t pred_val, hipStream_t st) {
+    if (k <= 0 || !seq_lens) return RK_ERR_INVALID_ARG;
+    if ((int64_t)kBatchLayers * geom->batch > 65535) return RK_ERR_UNSUPPORTED;
+    for (int l = 0; l < n_layers; ++l) {
+        int rc;
+        if ((rc = check_kv(full[l])) != RK_OK || (rc = check_kv(small[l])) != RK_OK) return rc;
+        if (small[l].capacity < k || !idx[l]) return RK_ERR_INVALID_ARG;
+        // one launch takes one set of strides
+        if (full[l].stride_b != full[0].stride_b || full[l].stride_h != full[0].stride_h || full[l].capacity != full[0].capacity ||
+            small[l].stride_b != small[0].stride_b || small[l].stride_h != small[0].stride_h) return RK_ERR_UNSUPPORTED;
+    }
+    for (int l0 = 0; l0 < n_layers; l0 += kBatchLayers) {
+        const int n = n_layers - l0 < kBatchLayers ? n_layers - l0 : kBatchLayers;
+        GatherBatch tab{};
+        for (int l = 0; l < n; ++l) {
+            tab.fk[l] = (const uint16_t*)full[l0 + l].k; tab.fv[l] = (const uint16_t*)full[l0 + l].v;
+            tab.sk[l] = (uint16_t*)small[l0 + l].k; tab.sv[l] = (uint16_t*)small[l0 + l].v;
+            tab.idx[l] = idx[l0 + l];
+            tab.tail_start[l] = tail_start ? tail_start[l0 + l] : nullptr;
+            tab.n_refresh[l] = n_refresh ? n_refresh[l0 + l] : nullptr;
+            tab.pred[l] = pred ? pred[l0 + l] : nullptr;
+        }
+        dim3 grid((k + kGatherRows - 1) / kGatherRows, geom->n_kv_heads, n * geom->batch);
+        hipLaunchKernelGGL(gather_rows_batched_kernel, grid, dim3(256), 0, st, tab, (int32_t)geom->batch,
+                           full[0].stride_b, full[0].stride_h, small[0].stride_b, small[0].stride_h,
+                           k, geom->n_kv_heads, (int32_t)full[0].capacity, seq_lens, pred_val);
+        const int rc = launch_status();
+        if (rc != RK_OK) return rc;
+    }
+    return RK_OK;
+}
+
 int gather_stage(const rk_geom* geom, rk_kv full, const int32_t* idx, int32_t k, rk_kv small,
                  const int32_t* seq_lens, int32_t* tail_start, int32_t* n_refresh,
                  const int32_t* pred, int32_t pred_val, hipStream_t stream) {

@@ -78,6 +78,7 @@ static inline int merged_split_workgroups(int64_t rows, int64_t tail_rows, int64
 
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+constexpr int kBatchLayers = 32;         // layers one batched launch (rk_refresh_batched) takes; more go in several launches
 constexpr int kHistBins = 2048;          // first-level histogram of the selection: top 11 key bits
 constexpr int kMaxCandidates = 16384;    // most candidates the fast selection path sorts in LDS
 constexpr int kHistShift = 32 - 11;      // key bits below the first-level histogram bin
@@ -218,5 +219,16 @@ int check_select_args(int32_t k, int32_t pool_w, int32_t agg);
 __attribute__((visibility("hidden")))
 int select_stage(const rk_geom* geom, const int32_t* seq_lens, int32_t max_len, int32_t k, int32_t* idx,
                  float* sel_scores, const int32_t* pred, int32_t pred_val, const Workspace& ws, hipStream_t st);
+
+// Batched forms for rk_refresh_batched: the selections, then the gathers, of up to kBatchLayers
+// layers in one launch each.  wss[l] holds what rk_full_attn_pool left for layer l.
+__attribute__((visibility("hidden")))
+int select_batched_stage(const rk_geom* geom, int n_layers, const Workspace* wss, int32_t* const* idx,
+                         const int32_t* seq_lens, int32_t max_len, int32_t k, const int32_t* const* pred, int32_t pred_val,
+                         hipStream_t st);
+__attribute__((visibility("hidden")))
+int gather_batched_stage(const rk_geom* geom, int n_layers, const rk_kv* full, const rk_kv* small, int32_t* const* idx,
+                         int32_t k, const int32_t* seq_lens, int32_t* const* tail_start, int32_t* const* n_refresh,
+                         const int32_t* const* pred, int32_t pred_val, hipStream_t st);
 
 }  // namespace rk

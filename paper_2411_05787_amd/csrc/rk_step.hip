@@ -116,7 +116,7 @@ extern "C" int rk_decode_step_overlapped(const rk_geom* geom, const rk_schedule*
             if (rc != RK_OK) return rc;
         }
         rc = rk_full_attn_pool(geom, q[l], L.full, seq_lens, max_len, out[l], nullptr, 0, nullptr, sched->pool_w,
-                               RK_AGG_MAX, nullptr, 0, ws, ov->workspace_bytes, main);
+                               RK_AGG_MAX, 1, nullptr, 0, ws, ov->workspace_bytes, main);
         if (rc != RK_OK) return rc;
         if ((rc = hip_ok(hipEventRecord((hipEvent_t)ov->ready[l], main))) != RK_OK) return rc;
         if ((rc = hip_ok(hipStreamWaitEvent(side, (hipEvent_t)ov->ready[l], 0))) != RK_OK) return rc;
@@ -129,4 +129,97 @@ extern "C" int rk_decode_step_overlapped(const rk_geom* geom, const rk_schedule*
     if ((rc = hip_ok(hipEventRecord((hipEvent_t)ov->join, side))) != RK_OK) return rc;
     if ((rc = hip_ok(hipStreamWaitEvent(main, (hipEvent_t)ov->join, 0))) != RK_OK) return rc;
     return RK_STEP_FULL;
+}
+
+// The refreshes of all layers after their rk_full_attn_pool calls, in two launches per
+// kBatchLayers layers: every selection, then every gather (+ tail_start <- seq_lens, refresh
+// counters).  Nothing of it is needed before the layers' next partial step, so it can wait until
+// the last layer's attention is done; batched, the selections of all layers share the chip instead
+// of one layer's 8 workgroups at a time, and the gathers run at memory speed.
+extern "C" int rk_refresh_batched(const rk_geom* geom, int32_t n_layers, const rk_layer_state* layers,
+                                  void* const* workspaces, size_t workspace_bytes,
+                                  const int32_t* seq_lens, int32_t max_len, int32_t k, int32_t by_need_full, void* stream) {
+    int rc = check_geom(geom);
+    if (rc != RK_OK) return rc;
+    if (!layers || !workspaces || !seq_lens || n_layers <= 0 || k <= 0 || max_len <= 0) return RK_ERR_INVALID_ARG;
+    if (k > RK_MAX_K) return RK_ERR_UNSUPPORTED;
+    if ((int64_t)rk::kBatchLayers * geom->batch > 65535) return RK_ERR_UNSUPPORTED;
+    // every argument is checked before the first launch
+    for (int l = 0; l < n_layers; ++l) {
+        const rk_layer_state& L = layers[l];
+        rk::Workspace w;
+        if (!L.idx || !L.tail_start || (by_need_full && !L.need_full)) return RK_ERR_INVALID_ARG;
+        if ((rc = rk::check_workspace(geom, max_len, k, workspaces[l], workspace_bytes, &w)) != RK_OK) return rc;
+        if ((rc = rk::check_kv(L.full)) != RK_OK || (rc = rk::check_kv(L.small)) != RK_OK) return rc;
+        if (L.small.capacity < k) return RK_ERR_INVALID_ARG;
+        if (L.full.stride_b != layers[0].full.stride_b || L.full.stride_h != layers[0].full.stride_h ||
+            L.full.capacity != layers[0].full.capacity || L.small.stride_b != layers[0].small.stride_b ||
+            L.small.stride_h != layers[0].small.stride_h) return RK_ERR_UNSUPPORTED;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    for (int pass = 0; pass < 2; ++pass) {              // all selections, then all gathers
+        for (int l0 = 0; l0 < n_layers; l0 += rk::kBatchLayers) {
+            const int n = n_layers - l0 < rk::kBatchLayers ? n_layers - l0 : rk::kBatchLayers;
+            rk::Workspace wss[rk::kBatchLayers];
+            rk_kv full[rk::kBatchLayers], small[rk::kBatchLayers];
+            int32_t* idx[rk::kBatchLayers]; int32_t* tail[rk::kBatchLayers]; int32_t* nref[rk::kBatchLayers];
+            const int32_t* pred[rk::kBatchLayers];
+            for (int l = 0; l < n; ++l) {
+                const rk_layer_state& L = layers[l0 + l];
+                wss[l] = rk::carve(geom, max_len, k, workspaces[l0 + l]);
+                full[l] = L.full; small[l] = L.small; idx[l] = L.idx; tail[l] = L.tail_start; nref[l] = L.n_full;
+                pred[l] = by_need_full ? L.need_full : nullptr;
+            }
+            rc = pass == 0 ? rk::select_batched_stage(geom, n, wss, idx, seq_lens, max_len, k, pred, 1, st)
+                           : rk::gather_batched_stage(geom, n, full, small, idx, k, seq_lens, tail, nref, pred, 1, st);
+            if (rc != RK_OK) return rc;
+        }
+    }
+    return RK_OK;
+}
+
+// rk_decode_step with the refreshes of a full step batched over the layers: every layer's
+// rk_full_attn_pool (workspace l), then rk_refresh_batched.  Steps that are not full steps of all
+// layers, and the scores-only refresh, go through rk_decode_step with the first workspace.
+extern "C" int rk_decode_step_batched(const rk_geom* geom, const rk_schedule* sched, int32_t t, int32_t n_layers,
+                                      const rk_layer_state* layers, const void* const* q, void* const* out,
+                                      const int32_t* seq_lens, int32_t max_len, int32_t max_recent,
+                                      void* const* workspaces, size_t workspace_bytes, void* stream) {
+    if (!workspaces || !workspaces[0]) return RK_ERR_WORKSPACE;
+    if (!sched) return RK_ERR_INVALID_ARG;
+    const bool scheduled = t == 0 || (sched->stride > 0 && t % sched->stride == 0);
+    const bool all_full = t == 0 || (scheduled && !sched->dynamic);
+    if (!scheduled || sched->scores_only)
+        return rk_decode_step(geom, sched, t, n_layers, layers, q, out, seq_lens, max_len, max_recent,
+                              workspaces[0], workspace_bytes, stream);
+    const bool both = !all_full;                             // the trigger's test step: both branches, predicated
+    int rc = check_geom(geom);
+    if (rc != RK_OK) return rc;
+    if (!layers || !q || !out || !seq_lens || t < 0 || n_layers <= 0 || sched->k <= 0 || max_len <= 0 || max_recent < 0)
+        return RK_ERR_INVALID_ARG;
+    for (int l = 0; l < n_layers; ++l) {
+        const rk_layer_state& L = layers[l];
+        if (!q[l] || !out[l] || !L.idx || !L.tail_start || !workspaces[l]) return RK_ERR_INVALID_ARG;
+        if (sched->dynamic && (!L.q_ref || !L.sim || !L.need_full)) return RK_ERR_INVALID_ARG;
+    }
+    const int recent = max_recent > 0 ? max_recent : 1;
+    for (int l = 0; l < n_layers; ++l) {
+        const rk_layer_state& L = layers[l];
+        if (sched->dynamic) {
+            rc = rk_query_sim(geom, q[l], L.q_ref, sched->threshold, both ? 0 : 1, L.sim, L.need_full, stream);
+            if (rc != RK_OK) return rc;
+        }
+        if (both) {
+            auto fn = sched->fixed_size ? rk_partial_attn_fixed : rk_partial_attn;
+            rc = fn(geom, q[l], L.small, sched->k, L.full, L.tail_start, seq_lens, recent, out[l], L.need_full, 0,
+                    workspaces[l], workspace_bytes, stream);
+            if (rc != RK_OK) return rc;
+        }
+        rc = rk_full_attn_pool(geom, q[l], L.full, seq_lens, max_len, out[l], nullptr, 0, nullptr, sched->pool_w,
+                               RK_AGG_MAX, 0, both ? L.need_full : nullptr, 1, workspaces[l], workspace_bytes, stream);
+        if (rc != RK_OK) return rc;
+    }
+    rc = rk_refresh_batched(geom, n_layers, layers, workspaces, workspace_bytes, seq_lens, max_len, sched->k,
+                            both ? 1 : 0, stream);
+    return rc != RK_OK ? rc : (both ? RK_STEP_BOTH : RK_STEP_FULL);
 }

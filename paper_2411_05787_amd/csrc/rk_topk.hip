@@ -207,14 +207,15 @@ __device__ void bitonic_sort_desc(uint64_t* sKeys, int npad) {
 // space), and the workgroup that arrives last (ticket, as in the attention kernels) takes the
 // list into registers and ranks it: the pass over all positions, which is what a single
 // workgroup spends most of its time on, is spread over the chip.
+// The selection of one (sequence b, KV head blockIdx.y), by the workgroups blockIdx.x = 0 .. gridDim.x - 1.
 template <bool ADAPT>                    // ADAPT: compiled with the histogram-driven bucket layout (large K only)
-__global__ __launch_bounds__(kSelThreads)
-void select_kernel(const float* __restrict__ pooled, int64_t pooled_stride, const int32_t* seq_lens,
-                   int32_t max_len, int32_t k, uint32_t* __restrict__ hist, int32_t cand_cap,
-                   int32_t* __restrict__ idx, float* __restrict__ sel_scores,
-                   const int32_t* pred, int32_t pred_val,
-                   int32_t* __restrict__ sel_counters, uint64_t* __restrict__ cand_list) {
-    const int tile = blockIdx.x, g = blockIdx.y, b = blockIdx.z, Hkv = gridDim.y;
+__device__ __forceinline__
+void select_body(const float* __restrict__ pooled, int64_t pooled_stride, const int32_t* seq_lens,
+                 int32_t max_len, int32_t k, uint32_t* __restrict__ hist, int32_t cand_cap,
+                 int32_t* __restrict__ idx, float* __restrict__ sel_scores,
+                 const int32_t* pred, int32_t pred_val,
+                 int32_t* __restrict__ sel_counters, uint64_t* __restrict__ cand_list, const int b) {
+    const int tile = blockIdx.x, g = blockIdx.y, Hkv = gridDim.y;
     const bool multi = gridDim.x > 1;
     if (pred != nullptr && pred[b] != pred_val) return;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -557,6 +558,37 @@ void select_kernel(const float* __restrict__ pooled, int64_t pooled_stride, cons
     }
 }
 
+template <bool ADAPT>
+__global__ __launch_bounds__(kSelThreads)
+void select_kernel(const float* __restrict__ pooled, int64_t pooled_stride, const int32_t* seq_lens,
+                   int32_t max_len, int32_t k, uint32_t* __restrict__ hist, int32_t cand_cap,
+                   int32_t* __restrict__ idx, float* __restrict__ sel_scores,
+                   const int32_t* pred, int32_t pred_val,
+                   int32_t* __restrict__ sel_counters, uint64_t* __restrict__ cand_list) {
+    select_body<ADAPT>(pooled, pooled_stride, seq_lens, max_len, k, hist, cand_cap, idx, sel_scores, pred, pred_val,
+                       sel_counters, cand_list, (int)blockIdx.z);
+}
+
+// The selections of several layers in one launch: grid z = layer * batch + sequence; what differs
+// from layer to layer comes from a table passed by value.
+struct SelectBatch {
+    const float* pooled[kBatchLayers];
+    uint32_t* hist[kBatchLayers];
+    int32_t* idx[kBatchLayers];
+    int32_t* sel_counters[kBatchLayers];
+    uint64_t* cand_list[kBatchLayers];
+    const int32_t* pred[kBatchLayers];       // NULL: every sequence of the layer
+};
+
+template <bool ADAPT>
+__global__ __launch_bounds__(kSelThreads)
+void select_batched_kernel(const SelectBatch tab, int32_t batch, int64_t pooled_stride, const int32_t* seq_lens,
+                           int32_t max_len, int32_t k, int32_t cand_cap, int32_t pred_val) {
+    const int layer = blockIdx.z / batch, b = blockIdx.z - layer * batch;
+    select_body<ADAPT>(tab.pooled[layer], pooled_stride, seq_lens, max_len, k, tab.hist[layer], cand_cap, tab.idx[layer],
+                       nullptr, tab.pred[layer], pred_val, tab.sel_counters[layer], tab.cand_list[layer], b);
+}
+
 }  // namespace rk
 
 using namespace rk;
@@ -603,6 +635,52 @@ static int launch_select(const rk_geom* geom, const int32_t* seq_lens, int32_t m
     hipLaunchKernelGGL((select_kernel<ADAPT>), sgrid, dim3(kSelThreads), lds, st, ws.pooled, pooled_row_stride(max_len), seq_lens,
                        max_len, k, ws.hist, ws.cand_cap, idx, sel_scores, pred, pred_val, ws.sel_counters, ws.cand_list);
     return launch_status();
+}
+
+template <bool ADAPT>
+static int launch_select_batched(const rk_geom* geom, int n_layers, const Workspace* wss, int32_t* const* idx,
+                                 const int32_t* seq_lens, int32_t max_len, int32_t k, const int32_t* const* pred,
+                                 int32_t pred_val, hipStream_t st) {
+    const int cand_cap = wss[0].cand_cap;
+    const size_t lds = (size_t)cand_cap * sizeof(uint64_t) +
+                       (2 * (kBuckets + 1) + kSelThreads / 64 + 4 + 1) * sizeof(uint32_t) +
+                       (ADAPT ? kHistBins * sizeof(uint16_t) : 0);
+    static size_t lds_allowed = 48 * 1024;
+    if (lds > lds_allowed) {
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(&select_batched_kernel<ADAPT>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+            (void)hipGetLastError();
+            return RK_ERR_UNSUPPORTED;
+        }
+        lds_allowed = lds;
+    }
+    const int tiles = max_len > kSelSingle ? (max_len + kSelTile - 1) / kSelTile : 1;
+    for (int l0 = 0; l0 < n_layers; l0 += kBatchLayers) {
+        const int n = n_layers - l0 < kBatchLayers ? n_layers - l0 : kBatchLayers;
+        SelectBatch tab{};
+        for (int l = 0; l < n; ++l) {
+            const Workspace& w = wss[l0 + l];
+            tab.pooled[l] = w.pooled; tab.hist[l] = w.hist; tab.idx[l] = idx[l0 + l];
+            tab.sel_counters[l] = w.sel_counters; tab.cand_list[l] = w.cand_list;
+            tab.pred[l] = pred ? pred[l0 + l] : nullptr;
+        }
+        dim3 grid(tiles, geom->n_kv_heads, n * geom->batch);
+        hipLaunchKernelGGL((select_batched_kernel<ADAPT>), grid, dim3(kSelThreads), lds, st, tab, (int32_t)geom->batch,
+                           pooled_row_stride(max_len), seq_lens, max_len, k, (int32_t)cand_cap, pred_val);
+        const int rc = launch_status();
+        if (rc != RK_OK) return rc;
+    }
+    return RK_OK;
+}
+
+int select_batched_stage(const rk_geom* geom, int n_layers, const Workspace* wss, int32_t* const* idx,
+                         const int32_t* seq_lens, int32_t max_len, int32_t k, const int32_t* const* pred, int32_t pred_val,
+                         hipStream_t st) {
+    if ((int64_t)kBatchLayers * geom->batch > 65535) return RK_ERR_UNSUPPORTED;      // grid z
+    for (int l = 1; l < n_layers; ++l)
+        if (wss[l].cand_cap != wss[0].cand_cap) return RK_ERR_INVALID_ARG;
+    if (wss[0].cand_cap > kAdaptiveFrom) return launch_select_batched<true>(geom, n_layers, wss, idx, seq_lens, max_len, k, pred, pred_val, st);
+    return launch_select_batched<false>(geom, n_layers, wss, idx, seq_lens, max_len, k, pred, pred_val, st);
 }
 
 // Two builds of the selection kernel: the one with the histogram-driven bucket layout serves the
@@ -684,7 +762,7 @@ extern "C" int rk_score_select(const rk_geom* geom, const void* q, rk_kv full,
 extern "C" int rk_full_attn_pool(const rk_geom* geom, const void* q, rk_kv full,
                                  const int32_t* seq_lens, int32_t max_len,
                                  void* out, float* weights, int64_t w_stride, float* lse,
-                                 int32_t pool_w, int32_t agg,
+                                 int32_t pool_w, int32_t agg, int32_t beside_other_work,
                                  const int32_t* pred, int32_t pred_val,
                                  void* workspace, size_t workspace_bytes, void* stream) {
     int rc = check_geom(geom);
@@ -697,7 +775,7 @@ extern "C" int rk_full_attn_pool(const rk_geom* geom, const void* q, rk_kv full,
     Workspace ws;
     if ((rc = check_workspace(geom, max_len, 0, workspace, workspace_bytes, &ws)) != RK_OK) return rc;
     return full_attn_stage(geom, q, full, seq_lens, max_len, out, weights, w_stride, lse, pred, pred_val, ws,
-                           (hipStream_t)stream, false, (pool_w - 1) / 2, false, agg, true);
+                           (hipStream_t)stream, false, (pool_w - 1) / 2, false, agg, beside_other_work != 0);
 }
 
 extern "C" int rk_select_pooled(const rk_geom* geom, const int32_t* seq_lens, int32_t max_len, int32_t k,

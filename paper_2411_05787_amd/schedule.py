@@ -200,6 +200,17 @@ class RefreshKVModel:
         self._overlap = _Overlap(self._side.cuda_stream, self._ready, self._done, handles[2 * n], self._ws_ptrs,
                                  len(self._wss), min(w_.nbytes for w_ in self._wss))
 
+    def batched_refresh(self) -> None:
+        """From now on full steps run every layer's attention first (one workspace per layer) and then all
+        selections and all gathers in one launch each (``rk_decode_step_batched``)."""
+        import ctypes as C
+        dev = self.out.device
+        self._wss = [self.ws] + [rk.Workspace(self.geom, self.capacity, self.k_small, device=dev)
+                                 for _ in range(self.n_layers - 1)]
+        self._batched_ptrs = (C.c_void_p * self.n_layers)(*[w_.ptr for w_ in self._wss])
+        self._batched_bytes = min(w_.nbytes for w_ in self._wss)
+        self._overlap = None
+
     def use_static_bounds(self, max_len: int, max_recent: int) -> None:
         if max_len > self.capacity:
             raise ValueError("max_len exceeds the cache capacity")
@@ -223,7 +234,11 @@ class RefreshKVModel:
         base, step_bytes = q.data_ptr(), q.stride(0) * 2
         for l in range(n):
             self._q_ptrs[l] = base + l * step_bytes
-        if self._overlap is not None:
+        if getattr(self, "_batched_ptrs", None) is not None:
+            kind = rk.rk_decode_step_batched(g, self.sched, t, self._layers, self._q_ptrs, self._out_ptrs, self.seq_lens,
+                                             self.max_len, max(self.recent_bound, 1), self._batched_ptrs,
+                                             self._batched_bytes, stream=stream)
+        elif self._overlap is not None:
             kind = rk.rk_decode_step_overlapped(g, self.sched, t, self._layers, self._q_ptrs, self._out_ptrs,
                                                 self.seq_lens, self.max_len, max(self.recent_bound, 1), self._overlap,
                                                 stream=stream)
@@ -255,7 +270,10 @@ class RefreshKVStack:
     earlier step is still pending (wait on the event that ended the step before the last).
     """
 
-    def __init__(self, layers, n_workspaces: int = 3):
+    def __init__(self, layers, n_workspaces: int = 3, batched: bool = False):
+        """batched: no second stream; a full step runs ``rk_full_attn_pool`` for every layer (one
+        workspace per layer) and then ``rk_refresh_batched``: all selections in one launch, all gathers
+        in another, after the last layer's attention."""
         if not layers:
             raise ValueError("no layers")
         l0 = layers[0]
@@ -263,6 +281,17 @@ class RefreshKVStack:
             raise ValueError("the scores-only refresh is not split over two streams")
         self.layers = layers
         dev = l0.K.device
+        self.batched = bool(batched)
+        if self.batched:
+            import ctypes as C
+            from .binding import _LayerState, layer_state
+            n = len(layers)
+            self.wss = [l0.ws] + [rk.Workspace(l0.geom, l0.capacity, l0.k_small, device=dev) for _ in range(n - 1)]
+            self._states = (_LayerState * n)(*[layer_state(l0.geom, lay.K, lay.V, lay.small_K, lay.small_V, lay.idx,
+                                                           lay.tail_start, k=lay.k_small) for lay in layers])
+            self._ws_ptrs = (C.c_void_p * n)(*[w_.ptr for w_ in self.wss])
+            self._ws_bytes = min(w_.nbytes for w_ in self.wss)
+            return
         n_ws = len(layers) if n_workspaces <= 0 else max(2, min(int(n_workspaces), len(layers)))
         self.wss = [l0.ws] + [rk.Workspace(l0.geom, l0.capacity, l0.k_small, device=dev) for _ in range(n_ws - 1)]
         self.side = torch.cuda.Stream(device=dev)
@@ -279,6 +308,17 @@ class RefreshKVStack:
                 kind = lay.step(t, q_layers[l])
             return kind
         main = torch.cuda.current_stream()
+        if self.batched:
+            for l, lay in enumerate(self.layers):
+                if lay.dynamic:
+                    rk.rk_query_sim(lay.geom, q_layers[l], lay.q_ref, lay.threshold, True, lay.sim, lay.need_full, stream=main)
+                rk.rk_full_attn_pool(lay.geom, q_layers[l], lay.K, lay.V, lay.seq_lens, lay.max_len, lay.out, lay.pool_w,
+                                     weights=lay.weights, workspace=self.wss[l], stream=main)
+                if not lay._static:
+                    lay.recent_bound = 0
+            rk.rk_refresh_batched(l0.geom, self._states, self._ws_ptrs, self._ws_bytes, l0.seq_lens, l0.max_len,
+                                  l0.k_small, stream=main)
+            return "full"
         for l, lay in enumerate(self.layers):
             n_ws = len(self.wss)
             ws = self.wss[l % n_ws]
@@ -288,7 +328,7 @@ class RefreshKVStack:
             if lay.dynamic:
                 rk.rk_query_sim(g, q, lay.q_ref, lay.threshold, True, lay.sim, lay.need_full, stream=main)
             rk.rk_full_attn_pool(g, q, lay.K, lay.V, lay.seq_lens, lay.max_len, lay.out, lay.pool_w,
-                                 weights=lay.weights, workspace=ws, stream=main)
+                                 weights=lay.weights, workspace=ws, stream=main, beside_other_work=True)
             self.ready[l].record(main)
             self.side.wait_event(self.ready[l])
             rk.rk_select_pooled(g, lay.seq_lens, lay.max_len, lay.k_small, lay.idx, workspace=ws, stream=self.side)

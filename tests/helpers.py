@@ -16,14 +16,20 @@ def assert_out_close(gpu_bits: np.ndarray, ref_bits: np.ndarray, what: str = "ou
     """Outputs agree within 2e-2 absolute and within one bf16 step of the larger magnitude.
 
     Both sides round an (almost) equal real number to bf16, so they may differ by one unit in
-    the last place (2^-8 relative to the binade, 2^-7 at worst) when it lies near a tie.
+    the last place (2^-8 relative to the binade, 2^-7 at worst) when it lies near a tie.  On top
+    of that comes an absolute term: an output element is sum_j p_j v_j with sum_j p_j = 1 and
+    |v_j| = O(1), the kernel carries p_j to 2^-17 (two bf16 operands) and accumulates in fp32, so
+    its error is a few 1e-6 whatever the element's own size (an element of 9e-5 was seen 2.4e-6
+    off); 4e-6 covers that and is 5000 times below the 2e-2 the path is held to.
     """
     a, b = bf16_val(gpu_bits), bf16_val(ref_bits)
     assert np.isfinite(a).all(), what + ": non-finite GPU output"
     d = np.abs(a - b)
     assert d.max(initial=0.0) <= OUT_MAX_ABS, "%s: max abs diff %.3g" % (what, d.max())
-    ulp = np.maximum(np.abs(a), np.abs(b)) * 2.0 ** -7 + 1e-6
-    assert (d <= ulp).all(), "%s: differs by more than one bf16 step (max %.3g)" % (what, (d / ulp).max())
+    ulp = np.maximum(np.abs(a), np.abs(b)) * 2.0 ** -7 + 4e-6
+    worst = np.unravel_index(np.argmax(d / ulp), d.shape)
+    assert (d <= ulp).all(), "%s: differs by more than one bf16 step (max %.3g at %s: gpu %.6g, oracle %.6g)" % (
+        what, (d / ulp).max(), worst, a[worst], b[worst])
     return float(d.max(initial=0.0))
 
 

@@ -15,7 +15,7 @@ def test_more_than_one_gpu_is_refused():
 
 
 @pytest.mark.gpu
-@pytest.mark.parametrize("launch", ["hybrid", "graph", "native"])
+@pytest.mark.parametrize("launch", ["native", "hybrid", "graph"])
 def test_bench_json_line_small_workload(launch):
     import torch
     if not torch.cuda.is_available():

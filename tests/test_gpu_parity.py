@@ -686,7 +686,9 @@ def check_model_loop(rk, w: gen.Workload, n_layers: int, evict_lowest=False, sco
     sl = lens0.to(dev).clone()
     model = rk.RefreshKVModel(geom, kv, sl, int(lens0.max()), w.k_small, w.stride, pool_w=w.pool_w, dynamic=w.dynamic,
                               threshold=w.threshold, evict_lowest=evict_lowest, scores_only_refresh=scores_only)
-    if overlap:
+    if overlap == "batched":
+        model.batched_refresh()
+    elif overlap:
         model.overlap_refresh(2)
     q_all = torch.stack([d[1] for d in data], dim=1).to(dev).contiguous()            # [T+1, n_layers, B, Hq, D]
     nk_all = [d[2][0].to(dev) for d in data]
@@ -901,26 +903,32 @@ def test_decode_step_driver_fixed_and_dynamic(rk):
     kinds, n_full, _ = check_model_loop(rk, gen.shrink(gen.WORKLOADS["cfg1_llama_2k"], n_steps=9), 5, overlap=True)
     assert kinds[:5] == ["full", "partial", "partial", "partial", "full"] and (n_full == 3).all()
     check_model_loop(rk, wq, 3, evict_lowest=True, overlap=True)
+    say("decode_step driver, refreshes batched over the layers")
+    kinds, n_full, _ = check_model_loop(rk, gen.shrink(gen.WORKLOADS["cfg1_llama_2k"], n_steps=9), 5, overlap="batched")
+    assert kinds[:5] == ["full", "partial", "partial", "partial", "full"] and (n_full == 3).all()
+    check_model_loop(rk, wq, 3, evict_lowest=True, overlap="batched")
+    check_model_loop(rk, gen.shrink(gen.WORKLOADS["cfg1_llama_2k"], n_steps=9, batch=3), 34, overlap="batched")   # two launches of 32 + 2 layers
     say("decode_step driver, scores-only refresh")
     check_model_loop(rk, gen.shrink(gen.WORKLOADS["cfg1_llama_2k"], n_steps=5), 2, scores_only=True)
 
 
 def test_refresh_on_second_stream_stack(rk):
-    """RefreshKVStack: selection and gather of a full step on a second stream, two workspaces in turn;
-    eager and replayed from a HIP graph."""
+    """RefreshKVStack: selection and gather of a full step on a second stream (two workspaces in turn), or
+    for all layers at once after the last layer's attention (rk_refresh_batched); eager and replayed from
+    a HIP graph."""
     w = gen.shrink(gen.WORKLOADS["cfg1_llama_2k"], n_steps=9)
     n_layers, dev = 5, "cuda"
     geom = rk.Geom(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.scale)
     lens0 = gen.seq_lens(w)
     data = [(gen.make_kv(w, l), gen.make_queries(w, l), gen.make_new_rows(w, l)) for l in range(n_layers)]
-    for use_graph in (False, True):
-        say("refresh on a second stream, graph =", use_graph)
+    for use_graph, batched in ((False, False), (True, False), (False, True), (True, True)):
+        say("refresh of a layer stack, graph =", use_graph, "batched =", batched)
         kv = [(d[0][0].to(dev).clone(), d[0][1].to(dev).clone()) for d in data]
         sl = lens0.to(dev).clone()
         ws = rk.Workspace(geom, w.capacity, w.k_small)
         layers = [rk.RefreshKVLayer(geom, kv[l][0], kv[l][1], sl, int(lens0.max()), w.k_small, w.stride, pool_w=w.pool_w,
                                     workspace=ws) for l in range(n_layers)]
-        stack = rk.RefreshKVStack(layers, n_workspaces=2 if use_graph else 0)      # with and without workspace reuse
+        stack = rk.RefreshKVStack(layers, n_workspaces=2 if use_graph else 0, batched=batched)   # with and without workspace reuse
         q_all = torch.stack([d[1] for d in data], dim=1).to(dev).contiguous()
         q_cur = torch.empty_like(q_all[0])
         B, Hkv, D = w.batch, w.n_kv_heads, w.head_dim

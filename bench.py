@@ -71,7 +71,10 @@ def main():
     dev = "cuda"
     w = gen.WORKLOADS[args.workload]
     n_layers = args.layers or w.n_layers
-    T = args.warmup + args.steps
+    # after the timed steps, a few more with an event pair around each give the per-kind figures: the
+    # events cost about 4 us each on the stream, so the timed region itself carries none
+    n_kind_steps = 3 * w.stride if w.stride > 0 else 20
+    T = args.warmup + args.steps + n_kind_steps
     L0 = w.context
     # rows for every future step are pre-written: context' = L0 + T, seq_lens starts at L0
     w_alloc = gen.shrink(w, context=L0 + T + 8, n_steps=0)
@@ -181,28 +184,33 @@ def main():
         run_step(t)
     torch.cuda.synchronize()
 
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
     kinds = []
+    two_streams = (stack is not None and not stack.batched) or (model is not None and not args.no_overlap and args.refresh != "batched")
+    done = [torch.cuda.Event() for _ in range(args.steps)] if two_streams else None
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     # A step that uses the second stream is submitted late: the host first waits until at most
     # `--run-ahead` earlier steps are still pending.  Submitted far ahead, its second queue sits
     # blocked on a barrier behind all of them, and a blocked queue slows every dispatch of the
     # first one meanwhile (measured: +0.9 us per layer on every partial step of the period).
-    two_streams = (stack is not None and not stack.batched) or (model is not None and not args.no_overlap and args.refresh != "batched")
-    for i, t in enumerate(range(args.warmup + 1, T + 1)):
+    t_first = args.warmup + 1
+    for i, t in enumerate(range(t_first, t_first + args.steps)):
         if two_streams and args.run_ahead >= 0 and is_full(t) and i - 1 - args.run_ahead >= 0:
-            ev[i - 1 - args.run_ahead][1].synchronize()
-        ev[i][0].record()
+            done[i - 1 - args.run_ahead].synchronize()
         kinds.append(run_step(t))
-        ev[i][1].record()
+        if two_streams:
+            done[i].record()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     wall_ms = (t1 - t0) * 1e3
     ms_per_step = wall_ms / args.steps
     per_kind = {}
-    for (a, b), k in zip(ev, kinds):
-        per_kind.setdefault(k, []).append(a.elapsed_time(b) * 1e3)
+    for t in range(t_first + args.steps, T + 1):        # untimed: the same steps, one event pair around each
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(); k = run_step(t); b.record()
+        per_kind.setdefault(k, []).append((a, b))
+    torch.cuda.synchronize()
+    per_kind = {k: [a.elapsed_time(b) * 1e3 for a, b in v] for k, v in per_kind.items()}
     med = {k: float(np.median(v)) / n_layers for k, v in per_kind.items()}      # us per layer
     spread = {k: [round(float(np.percentile(v, q)) / n_layers, 2) for q in (10, 90)] for k, v in per_kind.items()}
     final_len = int(seq_lens.max().item())
@@ -320,7 +328,7 @@ def main():
             pmc = json.load(f)
         k = pmc["attn_split"]
         traffic = int(k["fetch_kib"] * 1024 * pmc["fetch_scale"] + k["write_kib"] * 1024 * pmc["write_scale"])
-    roofline = {"bound": "hbm", "kernel": "rk::attn_split_kernel<%d, 4, true, false> (first kernel of rk_full_attn when weights are returned)" % w.group,
+    roofline = {"bound": "hbm", "kernel": "rk::attn_split_kernel<%d, 4, true, false, false> (first kernel of rk_full_attn when weights are returned)" % w.group,
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
                 "avg_launch_us": round(split_us, 2), "launches": n_roof_launches, "algorithmic_bytes": algo_bytes}

@@ -444,24 +444,37 @@ int rk_decode_step_overlapped(const rk_geom* geom, const rk_schedule* sched, int
                               const int32_t* seq_lens, int32_t max_len, int32_t max_recent,
                               const rk_overlap* ov, void* stream);
 
-/* The refreshes of all layers of a full step at once, after every layer's rk_full_attn_pool:
- * for layer l, rk_select_pooled on workspaces[l] (which holds what rk_full_attn_pool left for that
- * layer, with the same seq_lens, max_len and geometry) into layers[l].idx, then rk_gather_small_kv
- * into layers[l].small with tail_start <- seq_lens and, where given, n_full += 1.  A layer's
- * selection and gather are needed only by its next partial step (Section 2.2), so they can wait
- * until the last layer's attention is done; here all selections run in one launch and all gathers in
- * another (per 32 layers), which fills the chip where one layer's refresh cannot.  Same results as
- * the per-layer calls.  Every layer needs a workspace of its own (workspace_bytes each); the caches
- * of all layers must share strides and capacity (RK_ERR_UNSUPPORTED otherwise).  by_need_full != 0:
- * layer l refreshes only the sequences with layers[l].need_full[b] == 1 (what the trigger of that
- * layer decided: the pooled scores of the others are stale and are not looked at); 0: every
- * sequence of every layer. */
+/* Full attention of a full step whose pooling is left for rk_refresh_batched (Section 2.2,
+ * "Decoding with full cache"): `out` (and lse, if given) as rk_full_attn; the raw scores of the
+ * step and the statistics that normalise them stay in `workspace`, which must not be used for
+ * anything else until rk_refresh_batched has run with pool_w != 0.  Launches the same kernels as
+ * the first half of rk_full_attn_pool, less the pooling tiles of its finishing kernel. */
+int rk_full_attn_deferred(const rk_geom* geom, const void* q, rk_kv full,
+                          const int32_t* seq_lens, int32_t max_len, void* out, float* lse,
+                          const int32_t* pred, int32_t pred_val,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
+/* The refreshes of all layers of a full step at once, after every layer's rk_full_attn_pool
+ * (pool_w == 0) or rk_full_attn_deferred (pool_w = the odd pooling width, agg = RK_AGG_*: the
+ * scores are pooled here first, all layers in one launch, with the results rk_full_attn_pool
+ * would have left): for layer l, rk_select_pooled on workspaces[l] (which holds what that call
+ * left for the layer, with the same seq_lens, max_len and geometry) into layers[l].idx, then
+ * rk_gather_small_kv into layers[l].small with tail_start <- seq_lens and, where given,
+ * n_full += 1.  A layer's selection and gather are needed only by its next partial step (Section
+ * 2.2), so they can wait until the last layer's attention is done; here all selections run in one
+ * launch and all gathers in another (per 32 layers), which fills the chip where one layer's
+ * refresh cannot.  Same results as the per-layer calls.  Every layer needs a workspace of its own
+ * (workspace_bytes each); the caches of all layers must share strides and capacity
+ * (RK_ERR_UNSUPPORTED otherwise).  by_need_full != 0: layer l refreshes only the sequences with
+ * layers[l].need_full[b] == 1 (what the trigger of that layer decided: the scores of the others
+ * are stale and are not looked at); 0: every sequence of every layer. */
 int rk_refresh_batched(const rk_geom* geom, int32_t n_layers, const rk_layer_state* layers,
                        void* const* workspaces, size_t workspace_bytes,
-                       const int32_t* seq_lens, int32_t max_len, int32_t k, int32_t by_need_full, void* stream);
+                       const int32_t* seq_lens, int32_t max_len, int32_t k, int32_t pool_w, int32_t agg,
+                       int32_t by_need_full, void* stream);
 
 /* rk_decode_step whose full steps do the refresh with rk_refresh_batched: per layer
- * rk_full_attn_pool on workspaces[l] (n_layers workspaces of workspace_bytes each, initialised with
+ * rk_full_attn_deferred on workspaces[l] (n_layers workspaces of workspace_bytes each, initialised with
  * rk_workspace_init), then one rk_refresh_batched for all layers; on the trigger's test steps both
  * branches are enqueued as in rk_decode_step and the batched refresh goes by every layer's need_full.
  * One stream, no events.  Same results and return values as rk_decode_step; partial steps, and the

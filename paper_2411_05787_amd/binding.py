@@ -16,7 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "librefreshkv.so")
 
 EXPORTS = ["rk_version", "rk_status_string", "rk_workspace_bytes", "rk_workspace_init",
-           "rk_full_attn", "rk_full_attn_scores", "rk_topk_select", "rk_full_attn_select", "rk_full_attn_pool", "rk_select_pooled", "rk_score_select", "rk_window_select", "rk_gather_small_kv", "rk_partial_attn", "rk_partial_attn_fixed", "rk_partial_attn_lazy", "rk_decode_step", "rk_decode_step_overlapped", "rk_refresh_batched", "rk_decode_step_batched",
+           "rk_full_attn", "rk_full_attn_scores", "rk_topk_select", "rk_full_attn_select", "rk_full_attn_pool", "rk_full_attn_deferred", "rk_select_pooled", "rk_score_select", "rk_window_select", "rk_gather_small_kv", "rk_partial_attn", "rk_partial_attn_fixed", "rk_partial_attn_lazy", "rk_decode_step", "rk_decode_step_overlapped", "rk_refresh_batched", "rk_decode_step_batched",
            "rk_query_sim", "rk_mark_refresh", "rk_calibration_copy", "rk_h2o_append", "rk_h2o_update", "rk_h2o_step"]
 
 RK_AGG_MAX, RK_AGG_MEAN, RK_AGG_FIRST = 0, 1, 2
@@ -87,6 +87,8 @@ def _load(path: str = LIB_PATH) -> C.CDLL:
     l.rk_full_attn_select.argtypes = [G, P, _Kv, P, I32, P, P, I64, P, I32, I32, I32, P, P, P, I32, P, SZ, P]
     l.rk_full_attn_select.restype = C.c_int
     l.rk_full_attn_pool.restype = C.c_int
+    l.rk_full_attn_deferred.restype = C.c_int
+    l.rk_full_attn_deferred.argtypes = [G, P, _Kv, P, I32, P, P, P, I32, P, SZ, P]
     l.rk_full_attn_pool.argtypes = [G, P, _Kv, P, I32, P, P, I64, P, I32, I32, I32, P, I32, P, SZ, P]
     l.rk_select_pooled.restype = C.c_int
     l.rk_select_pooled.argtypes = [G, P, I32, I32, P, P, P, I32, P, SZ, P]
@@ -111,7 +113,7 @@ def _load(path: str = LIB_PATH) -> C.CDLL:
     l.rk_decode_step_batched.argtypes = [G, C.POINTER(_Schedule), I32, I32, C.POINTER(_LayerState), C.POINTER(C.c_void_p),
                                          C.POINTER(C.c_void_p), P, I32, I32, C.POINTER(C.c_void_p), SZ, P]
     l.rk_decode_step_batched.restype = C.c_int
-    l.rk_refresh_batched.argtypes = [G, I32, C.POINTER(_LayerState), C.POINTER(C.c_void_p), SZ, P, I32, I32, I32, P]
+    l.rk_refresh_batched.argtypes = [G, I32, C.POINTER(_LayerState), C.POINTER(C.c_void_p), SZ, P, I32, I32, I32, I32, I32, P]
     l.rk_refresh_batched.restype = C.c_int
     l.rk_query_sim.argtypes = [G, P, P, C.c_float, I32, P, P, P]
     l.rk_calibration_copy.restype = C.c_int
@@ -308,6 +310,20 @@ def rk_full_attn_pool(geom: Geom, q, K, V, seq_lens, max_len: int, out, pool_w: 
         _dev(out, torch.bfloat16, "out", (B, Hq, D)),
         _dev(weights, torch.float32, "weights", optional=True), w_stride,
         _dev(lse, torch.float32, "lse", (B, Hq), optional=True), int(pool_w), int(agg), int(bool(beside_other_work)),
+        _dev(pred, torch.int32, "pred", (B,), optional=True), int(pred_val),
+        workspace.ptr, workspace.nbytes, _stream(stream)))
+
+
+def rk_full_attn_deferred(geom: Geom, q, K, V, seq_lens, max_len: int, out, lse=None, pred=None, pred_val: int = 0,
+                          workspace: Workspace = None, stream=None) -> None:
+    B, Hq, D = geom.batch, geom.n_q_heads, geom.head_dim
+    if max_len > K.shape[2]:
+        raise ValueError("max_len %d exceeds the cache capacity %d" % (max_len, K.shape[2]))
+    _check("rk_full_attn_deferred", lib.rk_full_attn_deferred(
+        C.byref(geom.c()), _dev(q, torch.bfloat16, "q", (B, Hq, D)), _kv(geom, K, V, "full"),
+        _dev(seq_lens, torch.int32, "seq_lens", (B,)), int(max_len),
+        _dev(out, torch.bfloat16, "out", (B, Hq, D)),
+        _dev(lse, torch.float32, "lse", (B, Hq), optional=True),
         _dev(pred, torch.int32, "pred", (B,), optional=True), int(pred_val),
         workspace.ptr, workspace.nbytes, _stream(stream)))
 
@@ -535,12 +551,13 @@ def rk_h2o_step(geom: Geom, state: _H2oState, q, k_new, v_new, seq_lens, budget:
 
 
 def rk_refresh_batched(geom: Geom, layers, ws_ptrs, workspace_bytes: int, seq_lens, max_len: int, k: int,
-                       by_need_full: bool = False, stream=None) -> None:
-    """layers: ctypes array of _LayerState; ws_ptrs: ctypes array of one workspace pointer per layer."""
+                       pool_w: int = 0, agg: int = RK_AGG_MAX, by_need_full: bool = False, stream=None) -> None:
+    """layers: ctypes array of _LayerState; ws_ptrs: ctypes array of one workspace pointer per layer.
+    pool_w != 0: the layers ran rk_full_attn_deferred and are pooled here first."""
     _check("rk_refresh_batched", lib.rk_refresh_batched(
         C.byref(geom.c()), len(layers), layers, ws_ptrs, int(workspace_bytes),
-        _dev(seq_lens, torch.int32, "seq_lens", (geom.batch,)), int(max_len), int(k), int(bool(by_need_full)),
-        _stream(stream)))
+        _dev(seq_lens, torch.int32, "seq_lens", (geom.batch,)), int(max_len), int(k), int(pool_w), int(agg),
+        int(bool(by_need_full)), _stream(stream)))
 
 
 def rk_decode_step_batched(geom: Geom, sched: _Schedule, t: int, layers, q_ptrs, out_ptrs, seq_lens, max_len: int,

@@ -809,10 +809,10 @@ void merge_normalise_kernel(const AttnParams p, int G) {
 // histogram of the selection.  Raw scores are read from `scores` (never modified, so the halo
 // of a neighbouring tile is always raw); weights are written only if the caller wants them.
 template <int G>
-__global__ __launch_bounds__(256)
-void finish_pool_kernel(const AttnParams p, const float* __restrict__ scores, int64_t s_stride, int half, int agg,
-                        float* __restrict__ pooled, int64_t pooled_stride, uint32_t* __restrict__ hist) {
-    const int x = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+__device__ __forceinline__
+void finish_pool_body(const AttnParams& p, const float* __restrict__ scores, int64_t s_stride, int half, int agg,
+                      float* __restrict__ pooled, int64_t pooled_stride, uint32_t* __restrict__ hist, const int b) {
+    const int x = blockIdx.x, g = blockIdx.y;
     if (p.pred != nullptr && p.pred[b] != p.pred_val) return;
     const int tid = threadIdx.x;
     const int len = min(max(min(p.seq_lens[b], p.cap2), 0), p.max_rows2);
@@ -939,6 +939,46 @@ void finish_pool_kernel(const AttnParams p, const float* __restrict__ scores, in
 }
 
 template <int G>
+__global__ __launch_bounds__(256)
+void finish_pool_kernel(const AttnParams p, const float* __restrict__ scores, int64_t s_stride, int half, int agg,
+                        float* __restrict__ pooled, int64_t pooled_stride, uint32_t* __restrict__ hist) {
+    finish_pool_body<G>(p, scores, s_stride, half, agg, pooled, pooled_stride, hist, (int)blockIdx.z);
+}
+
+// The pooling half of the finishing kernel for several layers in one launch (grid z = layer *
+// batch + sequence): each layer's raw scores and chunk statistics are where its full attention
+// left them, in a workspace of its own.  What differs from layer to layer comes from a table
+// passed by value.
+struct PoolBatch {
+    const float* part_ml[kBatchLayers];
+    const float* scores[kBatchLayers];
+    float* lse[kBatchLayers];
+    float* pooled[kBatchLayers];
+    uint32_t* hist[kBatchLayers];
+    const int32_t* pred[kBatchLayers];       // NULL: every sequence of the layer
+};
+
+template <int G>
+__global__ __launch_bounds__(256)
+void pool_batched_kernel(const PoolBatch tab, const AttnParams common, int32_t batch, int64_t stride, int half, int agg) {
+    const int layer = blockIdx.z / batch, b = blockIdx.z - layer * batch;
+    AttnParams p = common;                   // out == NULL and weights == NULL: pooling tiles only
+    p.part_ml = const_cast<float*>(tab.part_ml[layer]);
+    p.lse = tab.lse[layer];
+    p.pred = tab.pred[layer];
+    finish_pool_body<G>(p, tab.scores[layer], stride, half, agg, tab.pooled[layer], stride, tab.hist[layer], b);
+}
+
+template <int G>
+static int launch_pool_batched(const PoolBatch& tab, const AttnParams& p, int n, int batch, int32_t max_len, int half,
+                               int agg, hipStream_t st) {
+    dim3 grid((max_len + kPoolTile - 1) / kPoolTile, p.Hkv, n * batch);
+    hipLaunchKernelGGL((pool_batched_kernel<G>), grid, dim3(256), 0, st, tab, p, (int32_t)batch,
+                       pooled_row_stride(max_len), half, agg);
+    return launch_status();
+}
+
+template <int G>
 static int launch_finish_pool(const AttnParams& p, int batch, int32_t max_len, const Workspace& ws, int half, int agg,
                               hipStream_t st) {
     dim3 grid((p.out != nullptr ? G : 0) + (max_len + kPoolTile - 1) / kPoolTile, p.Hkv, batch);
@@ -1009,7 +1049,7 @@ static int launch_score_split(const AttnParams& p, int batch, int G, int nchunk_
 int full_attn_stage(const rk_geom* geom, const void* q, rk_kv full, const int32_t* seq_lens, int32_t max_len,
                     void* out, float* weights, int64_t w_stride, float* lse, const int32_t* pred, int32_t pred_val,
                     const Workspace& ws, hipStream_t st, bool scores_only, int pool_half, bool no_v, int agg,
-                    bool co_run) {
+                    bool co_run, bool defer_pool) {
     const int G = geom->n_q_heads / geom->n_kv_heads;
     const bool fused = pool_half >= 0;
     const bool emit = weights != nullptr || fused;
@@ -1021,7 +1061,8 @@ int full_attn_stage(const rk_geom* geom, const void* q, rk_kv full, const int32_
     p.n_sel = 0;
     p.max_rows2 = max_len;
     p.cap1 = 0; p.cap2 = (int32_t)full.capacity;
-    p.nch = split_workgroups(max_len, (int64_t)geom->batch * geom->n_kv_heads, emit ? kMaxChunks : kMergeChunks);
+    p.nch = emit ? emit_split_workgroups(geom, max_len)
+                 : split_workgroups(max_len, (int64_t)geom->batch * geom->n_kv_heads, kMergeChunks);
     if (co_run) {       // more, smaller workgroups, unless that means more partial results than the finish takes cheaply
         const int wide = split_workgroups(max_len, (int64_t)geom->batch * geom->n_kv_heads, kMaxChunks, kCoRunTargetWgs);
         if (wide <= kCoRunMaxChunks) p.nch = wide;
@@ -1060,6 +1101,11 @@ int full_attn_stage(const rk_geom* geom, const void* q, rk_kv full, const int32_
         hipLaunchKernelGGL(merge_normalise_kernel, grid, dim3(256), 0, st, p, G);
         return launch_status();
     }
+    if (defer_pool) {            // only the output is finished now; pool_batched_stage does the rest later
+        p.weights = nullptr;
+        hipLaunchKernelGGL(merge_normalise_kernel, dim3(1, geom->n_q_heads, geom->batch), dim3(256), 0, st, p, G);
+        return launch_status();
+    }
     p.weights = weights; p.w_stride = w_stride;          // where the finish writes weights, if anywhere
     switch (G) {
         case 1: return launch_finish_pool<1>(p, geom->batch, max_len, ws, pool_half, agg, st);
@@ -1072,6 +1118,46 @@ int full_attn_stage(const rk_geom* geom, const void* q, rk_kv full, const int32_
         case 8: return launch_finish_pool<8>(p, geom->batch, max_len, ws, pool_half, agg, st);
         default: return RK_ERR_UNSUPPORTED;
     }
+}
+
+// The pooled scores and histograms of n_layers layers whose full attention ran with defer_pool,
+// each on its own workspace, with the launch shape emit_split_workgroups gives.
+int pool_batched_stage(const rk_geom* geom, int n_layers, const Workspace* wss, const int32_t* seq_lens, int32_t max_len,
+                       int64_t full_capacity, int pool_half, int agg, const int32_t* const* pred, int32_t pred_val,
+                       hipStream_t st) {
+    const int G = geom->n_q_heads / geom->n_kv_heads;
+    if ((int64_t)kBatchLayers * geom->batch > 65535) return RK_ERR_UNSUPPORTED;
+    AttnParams p{};
+    p.seq_lens = seq_lens;
+    p.max_rows2 = max_len;
+    p.cap2 = (int32_t)full_capacity;
+    p.nch = emit_split_workgroups(geom, max_len);
+    p.Hq = geom->n_q_heads; p.Hkv = geom->n_kv_heads;
+    p.pred_val = pred_val;
+    for (int l0 = 0; l0 < n_layers; l0 += kBatchLayers) {
+        const int n = n_layers - l0 < kBatchLayers ? n_layers - l0 : kBatchLayers;
+        PoolBatch tab{};
+        for (int l = 0; l < n; ++l) {
+            const Workspace& w = wss[l0 + l];
+            tab.part_ml[l] = w.part_ml; tab.scores[l] = w.scores; tab.lse[l] = w.lse;
+            tab.pooled[l] = w.pooled; tab.hist[l] = w.hist;
+            tab.pred[l] = pred ? pred[l0 + l] : nullptr;
+        }
+        int rc;
+        switch (G) {
+            case 1: rc = launch_pool_batched<1>(tab, p, n, geom->batch, max_len, pool_half, agg, st); break;
+            case 2: rc = launch_pool_batched<2>(tab, p, n, geom->batch, max_len, pool_half, agg, st); break;
+            case 3: rc = launch_pool_batched<3>(tab, p, n, geom->batch, max_len, pool_half, agg, st); break;
+            case 4: rc = launch_pool_batched<4>(tab, p, n, geom->batch, max_len, pool_half, agg, st); break;
+            case 5: rc = launch_pool_batched<5>(tab, p, n, geom->batch, max_len, pool_half, agg, st); break;
+            case 6: rc = launch_pool_batched<6>(tab, p, n, geom->batch, max_len, pool_half, agg, st); break;
+            case 7: rc = launch_pool_batched<7>(tab, p, n, geom->batch, max_len, pool_half, agg, st); break;
+            case 8: rc = launch_pool_batched<8>(tab, p, n, geom->batch, max_len, pool_half, agg, st); break;
+            default: return RK_ERR_UNSUPPORTED;
+        }
+        if (rc != RK_OK) return rc;
+    }
+    return RK_OK;
 }
 
 }  // namespace rk

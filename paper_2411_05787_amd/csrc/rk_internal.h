@@ -134,6 +134,12 @@ static inline int max_chunks_for(int64_t max_len) {
     return (int)n;
 }
 
+// Workgroups per (sequence, KV head) of the score-emitting split kernel of a full step (the
+// finishing kernels must be told the same number).
+static inline int emit_split_workgroups(const rk_geom* g, int64_t max_len) {
+    return split_workgroups(max_len, (int64_t)g->batch * g->n_kv_heads, kMaxChunks);
+}
+
 static inline Workspace carve(const rk_geom* g, int64_t max_len, int64_t max_k, void* base) {
     Workspace w;
     const size_t problems = (size_t)g->batch * g->n_kv_heads;
@@ -196,13 +202,20 @@ static inline int launch_status() {
 //     normalise kernel (weights in place), or, with pool_half >= 0, the fused finish that also
 //     leaves the pooled group scores and their histogram in the workspace.  no_v: the split kernel
 //     is the scores-only one (K rows only; out must be NULL, pool_half >= 0).  co_run: the launch is
-//     shaped for running beside another stream's kernels (see split_workgroups).
+//     shaped for running beside another stream's kernels (see split_workgroups).  defer_pool (with
+//     pool_half >= 0 and out != NULL): only the output is finished; the raw scores and the chunk
+//     statistics stay in the workspace for pool_batched_stage, which does for several layers at
+//     once what the finishing kernel's pooling tiles do for one.
 //   select_stage: top-K over the pooled scores and histogram that are in the workspace.
 __attribute__((visibility("hidden")))
 int full_attn_stage(const rk_geom* geom, const void* q, rk_kv full, const int32_t* seq_lens, int32_t max_len,
                     void* out, float* weights, int64_t w_stride, float* lse, const int32_t* pred, int32_t pred_val,
                     const Workspace& ws, hipStream_t st, bool scores_only, int pool_half, bool no_v, int agg,
-                    bool co_run = false);
+                    bool co_run = false, bool defer_pool = false);
+__attribute__((visibility("hidden")))
+int pool_batched_stage(const rk_geom* geom, int n_layers, const Workspace* wss, const int32_t* seq_lens, int32_t max_len,
+                       int64_t full_capacity, int pool_half, int agg, const int32_t* const* pred, int32_t pred_val,
+                       hipStream_t st);
 //   gather_stage: rk_gather_small_kv plus an optional per-sequence count of refreshes.
 __attribute__((visibility("hidden")))
 int gather_stage(const rk_geom* geom, rk_kv full, const int32_t* idx, int32_t k, rk_kv small,

@@ -138,11 +138,13 @@ extern "C" int rk_decode_step_overlapped(const rk_geom* geom, const rk_schedule*
 // of one layer's 8 workgroups at a time, and the gathers run at memory speed.
 extern "C" int rk_refresh_batched(const rk_geom* geom, int32_t n_layers, const rk_layer_state* layers,
                                   void* const* workspaces, size_t workspace_bytes,
-                                  const int32_t* seq_lens, int32_t max_len, int32_t k, int32_t by_need_full, void* stream) {
+                                  const int32_t* seq_lens, int32_t max_len, int32_t k, int32_t pool_w, int32_t agg,
+                                  int32_t by_need_full, void* stream) {
     int rc = check_geom(geom);
     if (rc != RK_OK) return rc;
     if (!layers || !workspaces || !seq_lens || n_layers <= 0 || k <= 0 || max_len <= 0) return RK_ERR_INVALID_ARG;
     if (k > RK_MAX_K) return RK_ERR_UNSUPPORTED;
+    if (pool_w != 0 && (rc = rk::check_select_args(k, pool_w, agg)) != RK_OK) return rc;
     if ((int64_t)rk::kBatchLayers * geom->batch > 65535) return RK_ERR_UNSUPPORTED;
     // every argument is checked before the first launch
     for (int l = 0; l < n_layers; ++l) {
@@ -157,7 +159,7 @@ extern "C" int rk_refresh_batched(const rk_geom* geom, int32_t n_layers, const r
             L.small.stride_h != layers[0].small.stride_h) return RK_ERR_UNSUPPORTED;
     }
     hipStream_t st = (hipStream_t)stream;
-    for (int pass = 0; pass < 2; ++pass) {              // all selections, then all gathers
+    for (int pass = pool_w != 0 ? -1 : 0; pass < 2; ++pass) {     // (all poolings,) all selections, then all gathers
         for (int l0 = 0; l0 < n_layers; l0 += rk::kBatchLayers) {
             const int n = n_layers - l0 < rk::kBatchLayers ? n_layers - l0 : rk::kBatchLayers;
             rk::Workspace wss[rk::kBatchLayers];
@@ -170,7 +172,9 @@ extern "C" int rk_refresh_batched(const rk_geom* geom, int32_t n_layers, const r
                 full[l] = L.full; small[l] = L.small; idx[l] = L.idx; tail[l] = L.tail_start; nref[l] = L.n_full;
                 pred[l] = by_need_full ? L.need_full : nullptr;
             }
-            rc = pass == 0 ? rk::select_batched_stage(geom, n, wss, idx, seq_lens, max_len, k, pred, 1, st)
+            rc = pass < 0  ? rk::pool_batched_stage(geom, n, wss, seq_lens, max_len, layers[0].full.capacity,
+                                                    (pool_w - 1) / 2, agg, pred, 1, st)
+               : pass == 0 ? rk::select_batched_stage(geom, n, wss, idx, seq_lens, max_len, k, pred, 1, st)
                            : rk::gather_batched_stage(geom, n, full, small, idx, k, seq_lens, tail, nref, pred, 1, st);
             if (rc != RK_OK) return rc;
         }
@@ -179,7 +183,7 @@ extern "C" int rk_refresh_batched(const rk_geom* geom, int32_t n_layers, const r
 }
 
 // rk_decode_step with the refreshes of a full step batched over the layers: every layer's
-// rk_full_attn_pool (workspace l), then rk_refresh_batched.  Steps that are not full steps of all
+// rk_full_attn_deferred (workspace l), then rk_refresh_batched (pooling, selection, gather).  Steps that are not full steps of all
 // layers, and the scores-only refresh, go through rk_decode_step with the first workspace.
 extern "C" int rk_decode_step_batched(const rk_geom* geom, const rk_schedule* sched, int32_t t, int32_t n_layers,
                                       const rk_layer_state* layers, const void* const* q, void* const* out,
@@ -215,11 +219,11 @@ extern "C" int rk_decode_step_batched(const rk_geom* geom, const rk_schedule* sc
                     workspaces[l], workspace_bytes, stream);
             if (rc != RK_OK) return rc;
         }
-        rc = rk_full_attn_pool(geom, q[l], L.full, seq_lens, max_len, out[l], nullptr, 0, nullptr, sched->pool_w,
-                               RK_AGG_MAX, 0, both ? L.need_full : nullptr, 1, workspaces[l], workspace_bytes, stream);
+        rc = rk_full_attn_deferred(geom, q[l], L.full, seq_lens, max_len, out[l], nullptr,
+                                   both ? L.need_full : nullptr, 1, workspaces[l], workspace_bytes, stream);
         if (rc != RK_OK) return rc;
     }
     rc = rk_refresh_batched(geom, n_layers, layers, workspaces, workspace_bytes, seq_lens, max_len, sched->k,
-                            both ? 1 : 0, stream);
+                            sched->pool_w, RK_AGG_MAX, both ? 1 : 0, stream);
     return rc != RK_OK ? rc : (both ? RK_STEP_BOTH : RK_STEP_FULL);
 }

@@ -32,6 +32,7 @@ namespace rk {
 constexpr int kSelThreads = 1024;
 constexpr int kSelTile = 4 * kSelThreads;                // positions per workgroup when the selection is spread out
 constexpr int kSelSingle = 2 * kSelTile;                 // rows up to this length are left to one workgroup
+constexpr int kBatchSingleFrom = 64;                     // ... and so are all rows of a batched launch with this many rows
 constexpr int kBuckets = 2048;                           // regular buckets, plus one for all above
 constexpr int kBucketLimit = 1024;                       // larger buckets: sort instead of ranking
 constexpr int kAdaptiveFrom = 8192;                      // candidates from which buckets follow the histogram
@@ -654,7 +655,11 @@ static int launch_select_batched(const rk_geom* geom, int n_layers, const Worksp
         }
         lds_allowed = lds;
     }
-    const int tiles = max_len > kSelSingle ? (max_len + kSelTile - 1) / kSelTile : 1;
+    // Spreading a row over workgroups shortens one selection, but with many selections in one launch
+    // the chip is full anyway and the hand-over between a row's workgroups only costs: measured at
+    // 32k..128k rows, one workgroup per row wins from about 64 rows on (256 rows of 32k: 29 against 116 us).
+    const int problems = (n_layers < kBatchLayers ? n_layers : kBatchLayers) * geom->batch * geom->n_kv_heads;
+    const int tiles = (max_len > kSelSingle && problems < kBatchSingleFrom) ? (max_len + kSelTile - 1) / kSelTile : 1;
     for (int l0 = 0; l0 < n_layers; l0 += kBatchLayers) {
         const int n = n_layers - l0 < kBatchLayers ? n_layers - l0 : kBatchLayers;
         SelectBatch tab{};
@@ -776,6 +781,21 @@ extern "C" int rk_full_attn_pool(const rk_geom* geom, const void* q, rk_kv full,
     if ((rc = check_workspace(geom, max_len, 0, workspace, workspace_bytes, &ws)) != RK_OK) return rc;
     return full_attn_stage(geom, q, full, seq_lens, max_len, out, weights, w_stride, lse, pred, pred_val, ws,
                            (hipStream_t)stream, false, (pool_w - 1) / 2, false, agg, beside_other_work != 0);
+}
+
+extern "C" int rk_full_attn_deferred(const rk_geom* geom, const void* q, rk_kv full,
+                                     const int32_t* seq_lens, int32_t max_len, void* out, float* lse,
+                                     const int32_t* pred, int32_t pred_val,
+                                     void* workspace, size_t workspace_bytes, void* stream) {
+    int rc = check_geom(geom);
+    if (rc != RK_OK) return rc;
+    if (!q || !out || !seq_lens || max_len <= 0) return RK_ERR_INVALID_ARG;
+    if (!aligned16(q) || ((uintptr_t)out & 1u)) return RK_ERR_INVALID_ARG;
+    if ((rc = check_kv(full)) != RK_OK) return rc;
+    Workspace ws;
+    if ((rc = check_workspace(geom, max_len, 0, workspace, workspace_bytes, &ws)) != RK_OK) return rc;
+    return full_attn_stage(geom, q, full, seq_lens, max_len, out, nullptr, 0, lse, pred, pred_val, ws,
+                           (hipStream_t)stream, false, 0, false, RK_AGG_MAX, false, true);
 }
 
 extern "C" int rk_select_pooled(const rk_geom* geom, const int32_t* seq_lens, int32_t max_len, int32_t k,

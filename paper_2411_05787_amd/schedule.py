@@ -270,10 +270,11 @@ class RefreshKVStack:
     earlier step is still pending (wait on the event that ended the step before the last).
     """
 
-    def __init__(self, layers, n_workspaces: int = 3, batched: bool = False):
-        """batched: no second stream; a full step runs ``rk_full_attn_pool`` for every layer (one
-        workspace per layer) and then ``rk_refresh_batched``: all selections in one launch, all gathers
-        in another, after the last layer's attention."""
+    def __init__(self, layers, n_workspaces: int = 3, batched: bool = False, deferred: bool = True):
+        """batched: no second stream; a full step runs ``rk_full_attn_deferred`` (``rk_full_attn_pool``
+        with deferred=False, or where a layer wants the weights of the step) for every layer (one
+        workspace per layer) and then ``rk_refresh_batched``: (all poolings,) all selections and all
+        gathers, each in one launch, after the last layer's attention."""
         if not layers:
             raise ValueError("no layers")
         l0 = layers[0]
@@ -282,6 +283,7 @@ class RefreshKVStack:
         self.layers = layers
         dev = l0.K.device
         self.batched = bool(batched)
+        self.deferred = bool(deferred) and all(lay.weights is None for lay in layers)
         if self.batched:
             import ctypes as C
             from .binding import _LayerState, layer_state
@@ -312,12 +314,16 @@ class RefreshKVStack:
             for l, lay in enumerate(self.layers):
                 if lay.dynamic:
                     rk.rk_query_sim(lay.geom, q_layers[l], lay.q_ref, lay.threshold, True, lay.sim, lay.need_full, stream=main)
-                rk.rk_full_attn_pool(lay.geom, q_layers[l], lay.K, lay.V, lay.seq_lens, lay.max_len, lay.out, lay.pool_w,
-                                     weights=lay.weights, workspace=self.wss[l], stream=main)
+                if self.deferred:
+                    rk.rk_full_attn_deferred(lay.geom, q_layers[l], lay.K, lay.V, lay.seq_lens, lay.max_len, lay.out,
+                                             workspace=self.wss[l], stream=main)
+                else:
+                    rk.rk_full_attn_pool(lay.geom, q_layers[l], lay.K, lay.V, lay.seq_lens, lay.max_len, lay.out,
+                                         lay.pool_w, weights=lay.weights, workspace=self.wss[l], stream=main)
                 if not lay._static:
                     lay.recent_bound = 0
             rk.rk_refresh_batched(l0.geom, self._states, self._ws_ptrs, self._ws_bytes, l0.seq_lens, l0.max_len,
-                                  l0.k_small, stream=main)
+                                  l0.k_small, pool_w=l0.pool_w if self.deferred else 0, stream=main)
             return "full"
         for l, lay in enumerate(self.layers):
             n_ws = len(self.wss)

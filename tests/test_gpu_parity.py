@@ -914,21 +914,23 @@ def test_decode_step_driver_fixed_and_dynamic(rk):
 
 def test_refresh_on_second_stream_stack(rk):
     """RefreshKVStack: selection and gather of a full step on a second stream (two workspaces in turn), or
-    for all layers at once after the last layer's attention (rk_refresh_batched); eager and replayed from
-    a HIP graph."""
+    for all layers at once after the last layer's attention (rk_refresh_batched, with the pooling done per
+    layer or deferred to it as well); eager and replayed from a HIP graph."""
     w = gen.shrink(gen.WORKLOADS["cfg1_llama_2k"], n_steps=9)
     n_layers, dev = 5, "cuda"
     geom = rk.Geom(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.scale)
     lens0 = gen.seq_lens(w)
     data = [(gen.make_kv(w, l), gen.make_queries(w, l), gen.make_new_rows(w, l)) for l in range(n_layers)]
-    for use_graph, batched in ((False, False), (True, False), (False, True), (True, True)):
-        say("refresh of a layer stack, graph =", use_graph, "batched =", batched)
+    for use_graph, batched, deferred in ((False, False, False), (True, False, False), (False, True, False),
+                                         (True, True, False), (False, True, True), (True, True, True)):
+        say("refresh of a layer stack, graph =", use_graph, "batched =", batched, "pooling deferred =", deferred)
         kv = [(d[0][0].to(dev).clone(), d[0][1].to(dev).clone()) for d in data]
         sl = lens0.to(dev).clone()
         ws = rk.Workspace(geom, w.capacity, w.k_small)
         layers = [rk.RefreshKVLayer(geom, kv[l][0], kv[l][1], sl, int(lens0.max()), w.k_small, w.stride, pool_w=w.pool_w,
                                     workspace=ws) for l in range(n_layers)]
-        stack = rk.RefreshKVStack(layers, n_workspaces=2 if use_graph else 0, batched=batched)   # with and without workspace reuse
+        stack = rk.RefreshKVStack(layers, n_workspaces=2 if use_graph else 0, batched=batched,
+                                  deferred=deferred)   # with and without workspace reuse
         q_all = torch.stack([d[1] for d in data], dim=1).to(dev).contiguous()
         q_cur = torch.empty_like(q_all[0])
         B, Hkv, D = w.batch, w.n_kv_heads, w.head_dim

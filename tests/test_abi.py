@@ -131,6 +131,34 @@ def test_host_side_argument_checks_return_before_any_launch(rk):
     assert lib.rk_h2o_update(C.byref(g), h2o(), fake, 300, 256, 128, 5, None, None) == -2         # unknown aggregation
     assert lib.rk_h2o_step(C.byref(g), h2o(), fake, fake, fake, fake, 256, 128, 0, None, None, 0x100000, ws_bytes, None) == -1
     assert lib.rk_h2o_step(C.byref(g), h2o(), fake, fake, fake, fake, 256, 128, 0, fake, None, None, ws_bytes, None) == -3
+    deferred = lambda **kw: lib.rk_full_attn_deferred(C.byref(g), kw.get("q", fake), kw.get("kv", kv), kw.get("sl", fake), 4096,
+                                                      kw.get("out", fake), None, None, 0, kw.get("ws", 0x100000),
+                                                      kw.get("wsb", ws_bytes), None)
+    assert deferred(q=None) == -1
+    assert deferred(out=None) == -1
+    assert deferred(sl=None) == -1
+    assert deferred(kv=kv_k_only) == -1
+    assert deferred(ws=None) == -3
+    assert deferred(wsb=1024) == -3
+    from paper_2411_05787_amd.binding import _LayerState
+    small = _Kv(fake, fake, 8 * 256 * 128, 256 * 128, 256)
+    state = lambda **kw: _LayerState(kw.get("full", kv), kw.get("small", small), kw.get("idx", fake), kw.get("tail", fake),
+                                     None, None, kw.get("need", None), None)
+    wsp = (C.c_void_p * 2)(0x100000, 0x900000)
+    batched = lambda layers, **kw: lib.rk_refresh_batched(C.byref(g), len(layers), (_LayerState * len(layers))(*layers),
+                                                          kw.get("wsp", wsp), kw.get("wsb", ws_bytes), kw.get("sl", fake), 4096,
+                                                          kw.get("k", 256), kw.get("pool", 7), kw.get("agg", 0),
+                                                          kw.get("by_need", 0), None)
+    assert batched([state(), state()], sl=None) == -1
+    assert batched([state(), state()], k=0) == -1
+    assert batched([state(), state()], k=16385) == -2
+    assert batched([state(), state()], pool=4) == -1                       # even pooling width
+    assert batched([state(), state()], agg=7) == -2
+    assert batched([state(), state(idx=None)]) == -1
+    assert batched([state(), state()], by_need=1) == -1                    # no need_full to go by
+    assert batched([state(), state()], wsb=1024) == -3
+    assert batched([state(), state(small=_Kv(fake, fake, 8 * 128 * 128, 128 * 128, 128))]) == -1       # fewer than k rows
+    assert batched([state(), state(full=_Kv(fake, fake, 8 * 8192 * 128, 8192 * 128, 8192))]) == -2     # strides differ
     assert lib.rk_mark_refresh(C.byref(g), None, fake, None, 0, None) == -1
     assert lib.rk_workspace_init(C.byref(g), None, 4096, None) == -3
     assert lib.rk_workspace_init(C.byref(g), 0x100000, 16, None) == -3

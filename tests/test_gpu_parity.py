@@ -912,6 +912,81 @@ def test_decode_step_driver_fixed_and_dynamic(rk):
     check_model_loop(rk, gen.shrink(gen.WORKLOADS["cfg1_llama_2k"], n_steps=5), 2, scores_only=True)
 
 
+def test_deferred_pooling_and_batched_refresh(rk):
+    """rk_full_attn_deferred per layer + rk_refresh_batched(pool_w): out, lse, idx, small cache, tail_start and
+    refresh counters against the oracle and, bit for bit, against rk_full_attn_select + rk_gather_small_kv per
+    layer; ragged batch with an empty sequence, three layers, then once more with every layer's need_full as
+    the predicate (workspaces left clean by the first pass)."""
+    import ctypes as C
+    from paper_2411_05787_amd.binding import _LayerState, layer_state
+    B, Hq, Hkv, cap, k, pool_w, n_layers = 3, 8, 2, 2300, 96, 7, 3
+    lens = [2300, 0, 1111]
+    say("deferred pooling + batched refresh", B, Hq, Hkv, lens, k)
+    scale = float(np.float32(1 / np.sqrt(128)))
+    geom = rk.Geom(B, Hq, Hkv, 128, scale)
+    sl = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    G = Hq // Hkv
+    data = [rand_case(900 + l, B, Hq, Hkv, cap) for l in range(n_layers)]
+    dev = [tuple(x.cuda() for x in d) for d in data]
+    refs = []
+    for q, K, V in data:
+        o_ref, w_ref, lse_ref = oracle.full_attn(gen.bf16_bits(q), gen.bf16_bits(K), gen.bf16_bits(V), lens, scale)
+        i_ref, _ = oracle.topk_select(w_ref.astype(np.float32), lens, Hkv, k, pool_w)
+        refs.append((o_ref, w_ref, lse_ref, i_ref))
+
+    def fresh():
+        return dict(out=[torch.full((B, Hq, 128), 3.0, dtype=torch.bfloat16, device="cuda") for _ in range(n_layers)],
+                    lse=[torch.full((B, Hq), 9.0, dtype=torch.float32, device="cuda") for _ in range(n_layers)],
+                    idx=[torch.full((B, Hkv, k), -5, dtype=torch.int32, device="cuda") for _ in range(n_layers)],
+                    sK=[torch.zeros(B, Hkv, k, 128, dtype=torch.bfloat16, device="cuda") for _ in range(n_layers)],
+                    sV=[torch.zeros(B, Hkv, k, 128, dtype=torch.bfloat16, device="cuda") for _ in range(n_layers)],
+                    tail=[torch.full((B,), -3, dtype=torch.int32, device="cuda") for _ in range(n_layers)],
+                    n_full=[torch.zeros(B, dtype=torch.int32, device="cuda") for _ in range(n_layers)])
+
+    wss = [rk.Workspace(geom, cap, k) for _ in range(n_layers)]
+    ws_ptrs = (C.c_void_p * n_layers)(*[w_.ptr for w_ in wss])
+    ws_bytes = min(w_.nbytes for w_ in wss)
+    need = [torch.tensor(v, dtype=torch.int32, device="cuda") for v in ([1, 1, 0], [0, 0, 1], [1, 0, 1])]
+    for use_pred in (False, True):
+        a, b_ = fresh(), fresh()
+        states = (_LayerState * n_layers)(*[layer_state(geom, dev[l][1], dev[l][2], a["sK"][l], a["sV"][l], a["idx"][l],
+                                                        a["tail"][l], need_full=need[l], n_full=a["n_full"][l], k=k)
+                                            for l in range(n_layers)])
+        for l in range(n_layers):
+            pr = need[l] if use_pred else None
+            rk.rk_full_attn_deferred(geom, dev[l][0], dev[l][1], dev[l][2], sl, cap, a["out"][l], lse=a["lse"][l],
+                                     pred=pr, pred_val=1, workspace=wss[l])
+        rk.rk_refresh_batched(geom, states, ws_ptrs, ws_bytes, sl, cap, k, pool_w=pool_w, by_need_full=use_pred)
+        for l in range(n_layers):       # the per-layer path on the first workspace
+            pr = need[l] if use_pred else None
+            rk.rk_full_attn_select(geom, dev[l][0], dev[l][1], dev[l][2], sl, cap, b_["out"][l], k, pool_w, b_["idx"][l],
+                                   lse=b_["lse"][l], pred=pr, pred_val=1, workspace=wss[0])
+            rk.rk_gather_small_kv(geom, dev[l][1], dev[l][2], b_["idx"][l], k, b_["sK"][l], b_["sV"][l], seq_lens=sl,
+                                  tail_start=b_["tail"][l], pred=pr, pred_val=1)
+        torch.cuda.synchronize()
+        for l in range(n_layers):
+            o_ref, w_ref, lse_ref, i_ref = refs[l]
+            for key in ("out", "idx", "sK", "sV", "tail"):
+                assert torch.equal(a[key][l], b_[key][l]), "layer %d: %s differs from the per-layer path" % (l, key)
+            assert (a["lse"][l] - b_["lse"][l]).abs().nan_to_num(0.0).max().item() <= 1e-6
+            on = need[l].cpu().numpy() == 1 if use_pred else np.ones(B, bool)
+            got, idx_n = gen.bf16_bits(a["out"][l]), a["idx"][l].cpu().numpy()
+            for b in range(B):
+                if not on[b]:
+                    assert (a["out"][l][b] == 3.0).all() and (idx_n[b] == -5).all() and a["tail"][l][b].item() == -3
+                    assert a["n_full"][l][b].item() == 0
+                    continue
+                assert a["tail"][l][b].item() == lens[b] and a["n_full"][l][b].item() == 1
+                assert_out_close(got[b:b + 1], o_ref[b:b + 1], "layer %d b %d" % (l, b))
+                n = lens[b]
+                if n == 0:
+                    assert (idx_n[b] == -1).all()
+                    continue
+                for g in range(Hkv):
+                    P = oracle.pooled_group_scores(w_ref[b, g * G:(g + 1) * G, :n].astype(np.float32), pool_w)
+                    assert_idx_equivalent(idx_n[b, g], i_ref[b, g], P, n, k, "deferred l=%d b=%d g=%d" % (l, b, g))
+
+
 def test_refresh_on_second_stream_stack(rk):
     """RefreshKVStack: selection and gather of a full step on a second stream (two workspaces in turn), or
     for all layers at once after the last layer's attention (rk_refresh_batched, with the pooling done per

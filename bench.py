@@ -128,14 +128,15 @@ def main():
     overlap = not args.no_overlap and model is None
     stack = rk.RefreshKVStack(layers, n_workspaces=args.overlap_workspaces, batched=args.refresh == "batched") if overlap else None
 
-    def enqueue_step(t: int):
-        """Everything of decode step t on the current stream (q_cur already holds the queries)."""
+    def enqueue_step(t: int, q=None):
+        """Everything of decode step t on the current stream (q_cur already holds the queries, unless
+        the native driver is given the step's own queries: it takes pointers, so they need no staging)."""
         if t >= 1:
             seq_lens.add_(1)
         if model is not None:
             if t >= 1:
                 model.advance()
-            return model.step(t, q_cur)
+            return model.step(t, q_cur if q is None else q)
         if partial_driver is not None and not is_full(t):
             return partial_driver.step(t, q_cur)
         if stack is not None:
@@ -172,8 +173,11 @@ def main():
         torch.cuda.synchronize()
 
     def run_step(t: int):
-        q_cur.copy_(q_steps[t], non_blocking=True)
         kind = "full" if is_full(t) else ("both" if (w.dynamic and t % w.stride == 0) else "partial")
+        if model is not None:                  # pointers to the step's queries: no copy into a static buffer
+            enqueue_step(t, q_steps[t])
+            return kind
+        q_cur.copy_(q_steps[t], non_blocking=True)
         if graphs and kind in graphs:
             graphs[kind].replay()
         else:

@@ -1179,6 +1179,16 @@ def test_full_size_one_layer_refresh_and_partial(rk, name):
     say("  index entries differing within the gap tolerance:", n_diff, "of", w.n_kv_heads * w.k_small)
 
 
+def test_full_size_model_batched_refresh(rk):
+    """Workload 2 at its real shape through rk_decode_step_batched, the driver bench.py times: 8 layers, so
+    that the batched selection has the 64 rows from which it takes one workgroup per row, as it does with
+    all 32 layers; full, partial, full, partial step, every layer against the oracle."""
+    w = gen.shrink(gen.WORKLOADS["cfg2_llama_32k"], n_steps=3, stride=2)
+    say("full size, batched driver", w.name, "context", w.context, "K", w.k_small)
+    kinds, n_full, _ = check_model_loop(rk, w, 8, overlap="batched")
+    assert kinds == ["full", "partial", "full", "partial"] and (n_full == 2).all()
+
+
 def test_full_size_batched_ragged(rk):
     """Workload 4 at its real shape (16 ragged sequences, one layer): a full step, the refresh and a
     partial step two tokens later against the oracle, per sequence."""

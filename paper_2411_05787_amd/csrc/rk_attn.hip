@@ -52,6 +52,7 @@ struct AttnParams {
     const int32_t* pred; int32_t pred_val;
     int32_t* counters; float* part_ml; float* part_o; int32_t max_chunks;
     const int32_t* idx; int32_t idx_stride;   // LAZY only: the selection [B, Hkv, idx_stride] whose rows are not gathered yet
+    int32_t ragged_batch;              // != 0 (= batch): workgroups are shared out by length, see ragged_share_lane
 };
 
 // Work split of the split kernels.  The rows of a (sequence, KV head) are cut into tiles of 32;
@@ -64,6 +65,76 @@ constexpr int kSplitWaves = 4, kTileRows = 32;
 __device__ __forceinline__ int active_workgroups(int n_rows, int nch) {
     return max(1, min(nch, (n_rows + kSplitWaves * kTileRows - 1) / (kSplitWaves * kTileRows)));
 }
+
+// Ragged batches.  With nch workgroups for every sequence, whatever its length, a launch that is
+// resident as a whole takes as long as its longest sequence.  Score-emitting launches over
+// 2..kRaggedMaxBatch sequences therefore share the nch * batch workgroups of a KV head out in
+// proportion to the lengths: sequence i gets a_i = 1 + its share of the other nch * batch - batch by
+// the largest-remainder rule (at least one, at most one per 128 rows and kMaxChunks; the a_i add up
+// to no more than there are), and workgroup z * nch + x of the grid is number (that minus the a_j before it) of
+// the sequence it falls into; those past the sum do nothing.  Every kernel of the call derives the
+// same a_i from seq_lens: exact integer arithmetic, one wavefront, lane i for sequence i.
+constexpr int kRaggedMaxBatch = 64;
+__device__ __forceinline__ int clamped_len(int raw, int cap, int max_rows) { return min(max(min(raw, cap), 0), max_rows); }
+
+// Lane i < batch: a_i.  Other lanes: 0.  Called by whole wavefronts.
+__device__ __forceinline__ int ragged_share_lane(const int32_t* seq_lens, int batch, int nch, int cap, int max_rows) {
+    const int lane = threadIdx.x & 63;
+    const int len = lane < batch ? clamped_len(seq_lens[lane], cap, max_rows) : 0;
+    long long total = len;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) total += __shfl_xor(total, d);
+    const long long spare = (long long)nch * batch - batch;
+    int a = 1;
+    if (total > 0) {
+        const long long num = spare * (long long)len;
+        const long long fl = num / total;
+        const long long rem = num - fl * total;
+        // what the floors leave over goes, one each, to the largest remainders (ties: lower sequence first)
+        long long given = fl;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) given += __shfl_xor(given, d);
+        const int left = (int)(spare - given);                 // 0 <= left < batch
+        int rank = 0;
+        for (int j = 0; j < batch; ++j) {
+            const long long rj = __shfl(rem, j);
+            rank += (rj > rem || (rj == rem && j < lane)) ? 1 : 0;
+        }
+        a += (int)fl + (rank < left ? 1 : 0);
+    }
+    a = min(a, min(kMaxChunks, max(1, (len + kSplitWaves * kTileRows - 1) / (kSplitWaves * kTileRows))));
+    return lane < batch ? a : 0;
+}
+
+// Partial results sequence b leaves behind (what active_workgroups is to the even split).
+__device__ __forceinline__ int ragged_chunks_of(const AttnParams& p, int b) {
+    const int a = ragged_share_lane(p.seq_lens, p.ragged_batch, p.nch, p.cap2, p.max_rows2);
+    return __shfl(a, b);
+}
+
+// Sequence, number within it and share of the workgroup at `slot` (b < 0: none).
+struct RaggedSlot { int b, c, nchunks; };
+__device__ __forceinline__ RaggedSlot ragged_slot(const AttnParams& p, const int32_t* seq_lens, int slot) {
+    const int lane = threadIdx.x & 63;
+    const int a = ragged_share_lane(seq_lens, p.ragged_batch, p.nch, p.cap2, p.max_rows2);
+    int incl = a;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int up = __shfl_up(incl, d);
+        if (lane >= d) incl += up;
+    }
+    const int before = incl - a;
+    const unsigned long long hit = __ballot(a > 0 && before <= slot && slot < incl);
+    RaggedSlot r{-1, 0, 0};
+    if (hit != 0) {
+        r.b = __ffsll(hit) - 1;
+        r.c = slot - __shfl(before, r.b);
+        r.nchunks = __shfl(a, r.b);
+    }
+    return r;
+}
+
+static inline int ragged_batch_of(const rk_geom* g) { return (g->batch > 1 && g->batch <= kRaggedMaxBatch) ? g->batch : 0; }
 
 __device__ __forceinline__ void coherent_store2(float* p, float a, float b) {
     const uint64_t v = (uint64_t)__float_as_uint(a) | ((uint64_t)__float_as_uint(b) << 32);
@@ -227,9 +298,18 @@ void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t
     constexpr int NT = NW * 64;
     constexpr int VS = kD + 8;               // LDS row stride of the V tile (272 bytes: rows spread over banks)
 
-    const int c = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+    int c = blockIdx.x, b = blockIdx.z, nch_b = p.nch;
+    const int g = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int n16 = lane & 15, c4 = lane >> 4;
+    constexpr bool kCanBeRagged = EMIT && !TWO_SEG;
+    if (kCanBeRagged && p.ragged_batch != 0) {           // which sequence this workgroup works for: by length
+        const RaggedSlot rs = ragged_slot(p, seq_lens, (int)(blockIdx.z * p.nch + blockIdx.x));
+        if (rs.b < 0) return;
+        b = __builtin_amdgcn_readfirstlane(rs.b);
+        c = __builtin_amdgcn_readfirstlane(rs.c);
+        nch_b = __builtin_amdgcn_readfirstlane(rs.nchunks);
+    }
     // LAZY: the selection's entries for the rows of a tile, lane i < 32 holding that of row r + i
     // (clamped into the full cache: a bad index reads a wrong row, never outside the cache)
     const int32_t* sel = LAZY ? pred + ((int64_t)b * gridDim.y + g) * spec_rows : nullptr;   // idx_stride == spec_rows
@@ -300,7 +380,7 @@ void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t
     }
     const int n2 = min(max(len - start2, 0), p.max_rows2);
     const int n = n1 + n2;
-    const int nchunks = active_workgroups(n, p.nch);
+    const int nchunks = (kCanBeRagged && p.ragged_batch != 0) ? nch_b : active_workgroups(n, p.nch);
     if (c >= nchunks) return;
     const int row1 = n;
 
@@ -467,7 +547,7 @@ void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t
     };
 
     {
-        const int step = p.nch * NW * ROWS;
+        const int step = nchunks * NW * ROWS;      // (== p.nch wherever a workgroup has a second tile, see active_workgroups)
         int r = r_first;
         if (r < row1) {
             // the early request stands unless part of this chunk maps to the tail of the full cache
@@ -767,7 +847,7 @@ void merge_normalise_kernel(const AttnParams p, int G) {
     const int tid = threadIdx.x;
     const int g = h / G, gi = h % G;
     const int len = min(max(min(p.seq_lens[b], p.cap2), 0), p.max_rows2);
-    const int nchunks = active_workgroups(len, p.nch);
+    const int nchunks = p.ragged_batch != 0 ? ragged_chunks_of(p, b) : active_workgroups(len, p.nch);
     const int j0 = (x - 1) * kNormTile;
     if (x >= 1 && j0 >= len) return;
 
@@ -816,7 +896,7 @@ void finish_pool_body(const AttnParams& p, const float* __restrict__ scores, int
     if (p.pred != nullptr && p.pred[b] != p.pred_val) return;
     const int tid = threadIdx.x;
     const int len = min(max(min(p.seq_lens[b], p.cap2), 0), p.max_rows2);
-    const int nchunks = active_workgroups(len, p.nch);
+    const int nchunks = p.ragged_batch != 0 ? ragged_chunks_of(p, b) : active_workgroups(len, p.nch);
     const int64_t bg = (int64_t)b * p.Hkv + g;
 
     __shared__ HeadMergeLds s;
@@ -1080,6 +1160,7 @@ int full_attn_stage(const rk_geom* geom, const void* q, rk_kv full, const int32_
     p.lse = lse ? lse : ws.lse;
     p.pred = pred; p.pred_val = pred_val;
     p.counters = ws.counters; p.part_ml = ws.part_ml; p.part_o = ws.part_o; p.max_chunks = ws.max_chunks;
+    p.ragged_batch = (emit && !no_v) ? ragged_batch_of(geom) : 0;
     if (!emit) {
         // No scores wanted.  Short rows: one launch, merged by the last workgroup inside it (at most
         // kMergeChunks partial results).  Long rows: the wider split of the score-emitting kernel
@@ -1091,6 +1172,7 @@ int full_attn_stage(const rk_geom* geom, const void* q, rk_kv full, const int32_
         }
         p.nch = wide;
         p.weights = nullptr;
+        p.ragged_batch = ragged_batch_of(geom);
         int rc = launch_split<true, false>(p, geom->batch, G, p.nch, st);
         if (rc != RK_OK) return rc;
         hipLaunchKernelGGL(merge_normalise_kernel, dim3(1, geom->n_q_heads, geom->batch), dim3(256), 0, st, p, G);
@@ -1136,6 +1218,7 @@ int pool_batched_stage(const rk_geom* geom, int n_layers, const Workspace* wss, 
     p.max_rows2 = max_len;
     p.cap2 = (int32_t)full_capacity;
     p.nch = emit_split_workgroups(geom, max_len);
+    p.ragged_batch = ragged_batch_of(geom);
     p.Hq = geom->n_q_heads; p.Hkv = geom->n_kv_heads;
     p.pred_val = pred_val;
     for (int l0 = 0; l0 < n_layers; l0 += kBatchLayers) {

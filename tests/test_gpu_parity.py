@@ -67,6 +67,11 @@ FULL_CASES = [
     # long rows: without weights the wide split + the separate merge launch
     ("long_two_heads", 1, 8, 2, [20000], 20032),
     ("long_llama", 1, 32, 8, [9001], 9024),
+    # ragged batches: the workgroups of a launch are shared out by length (2..64 sequences); 65 take the even split
+    ("ragged_16", 16, 8, 2, [3000, 1, 0, 129, 2999, 640, 77, 1500, 128, 127, 2048, 5, 900, 31, 3000, 256], 3008),
+    ("ragged_64", 64, 4, 1, [((i * 37) % 19) * 61 + (i % 3) for i in range(64)], 1152),
+    ("ragged_65_even_split", 65, 4, 1, [((i * 37) % 19) * 61 + (i % 3) for i in range(65)], 1152),
+    ("ragged_one_long", 3, 8, 2, [6000, 40, 200], 6016),
 ]
 
 

@@ -1194,6 +1194,17 @@ def test_full_size_model_batched_refresh(rk):
     assert kinds == ["full", "partial", "full", "partial"] and (n_full == 2).all()
 
 
+def test_batched_refresh_large_k(rk):
+    """K large enough for the selection's histogram-driven bucket layout (more than 8192 candidate slots),
+    through the batched driver: 2 layers (a row's selection spread over workgroups) and 8 layers (64 rows
+    in the launch: one workgroup per row)."""
+    w = gen.shrink(gen.WORKLOADS["cfg2_llama_32k"], context=12000, k_small=5000, n_steps=2, stride=2)
+    for n_layers in (2, 8):
+        say("batched refresh, K =", w.k_small, "layers =", n_layers)
+        kinds, n_full, _ = check_model_loop(rk, w, n_layers, overlap="batched")
+        assert kinds == ["full", "partial", "full"] and (n_full == 2).all()
+
+
 def test_full_size_batched_ragged(rk):
     """Workload 4 at its real shape (16 ragged sequences, one layer): a full step, the refresh and a
     partial step two tokens later against the oracle, per sequence."""

@@ -61,11 +61,17 @@ static inline int split_workgroups(int64_t max_rows, int64_t n_problems, int lim
 // 33: 13.7 at K = 4096; 16: 14.6, 40: 17.2 at K = 8192).  So: the largest count within whole
 // batches of 16 that keeps the rounds per wavefront at 5 or fewer, one batch if possible; and a
 // tail of a few rows (the tokens decoded since the refresh) gets no workgroup of its own, one
-// wavefront takes it as a second tile.
+// wavefront takes it as a second tile.  With several sequences the launch as a whole is best at
+// about one workgroup per CU (us per launch by workgroups per (sequence, KV head), 8 KV heads:
+// 16 sequences, K = 1024: 1: 21.7, 2: 18.7, 4: 19.5, 6: 20.7, 8: 23.4;  16 x 2048: 2: 28.4, 4: 31.1,
+// 6: 33.8, 16: 40.0;  8 x 4096: 2: 33.0, 4: 28.5, 12: 32.1, 32: 45.1;  4 x 2048: 4: 16.5, 8: 13.7,
+// 16: 14.1;  64 x 512: 1: 30.1, 2: 33.6), so the upper bound is 256 workgroups in all, not the 768 of
+// the kernels that leave the merge to a second launch.
 static inline int merged_split_workgroups(int64_t rows, int64_t tail_rows, int64_t n_problems) {
     const int64_t all_rows = rows + tail_rows;
     const int64_t counted = (rows > 0 && tail_rows <= 32) ? rows : all_rows;
-    int64_t per = RK_TARGET_WGS / (n_problems > 0 ? n_problems : 1);
+    const int64_t problems = n_problems > 0 ? n_problems : 1;
+    int64_t per = (kComputeUnits + problems / 2) / problems;        // one workgroup per CU in all, see above
     const int64_t stretches = (counted + kMinChunk - 1) / kMinChunk;
     if (per > stretches) per = stretches;
     if (per > kMergeChunks) per = kMergeChunks;

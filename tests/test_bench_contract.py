@@ -15,13 +15,14 @@ def test_more_than_one_gpu_is_refused():
 
 
 @pytest.mark.gpu
-@pytest.mark.parametrize("launch", ["native", "hybrid", "graph"])
+@pytest.mark.parametrize("launch", ["native", "hybrid", "graph", "native --refresh second-stream", "native --no-overlap",
+                                    "eager"])
 def test_bench_json_line_small_workload(launch):
     import torch
     if not torch.cuda.is_available():
         pytest.skip("no GPU")
     cmd = [sys.executable, os.path.join(ROOT, "bench.py"), "--workload", "cfg1_llama_2k", "--layers", "3", "--steps", "12",
-           "--warmup", "2", "--cpu-layers", "1", "--launch", launch]
+           "--warmup", "2", "--cpu-layers", "1", "--launch"] + launch.split()
     r = subprocess.run(cmd, capture_output=True, text=True, timeout=300)
     assert r.returncode == 0, r.stderr[-2000:]
     lines = [ln for ln in r.stdout.splitlines() if ln.startswith("{")]

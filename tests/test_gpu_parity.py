@@ -1203,6 +1203,12 @@ def test_batched_refresh_large_k(rk):
         say("batched refresh, K =", w.k_small, "layers =", n_layers)
         kinds, n_full, _ = check_model_loop(rk, w, n_layers, overlap="batched")
         assert kinds == ["full", "partial", "full"] and (n_full == 2).all()
+    # rows longer than one workgroup holds in registers (32768 positions), one workgroup per row all the same:
+    # the rest of the row is read again from memory
+    w = gen.shrink(gen.WORKLOADS["cfg2_llama_32k"], context=40000, k_small=5000, n_steps=1, stride=2)
+    say("batched refresh, K =", w.k_small, "context", w.context, "layers = 8")
+    kinds, n_full, _ = check_model_loop(rk, w, 8, overlap="batched")
+    assert kinds == ["full", "partial"] and (n_full == 1).all()
 
 
 def test_full_size_batched_ragged(rk):

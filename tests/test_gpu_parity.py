@@ -952,7 +952,8 @@ def test_deferred_pooling_and_batched_refresh(rk):
     ws_ptrs = (C.c_void_p * n_layers)(*[w_.ptr for w_ in wss])
     ws_bytes = min(w_.nbytes for w_ in wss)
     need = [torch.tensor(v, dtype=torch.int32, device="cuda") for v in ([1, 1, 0], [0, 0, 1], [1, 0, 1])]
-    for use_pred in (False, True):
+    for use_pred, agg in ((False, "max"), (True, "max"), (False, "mean")):
+        agg_id = {"max": rk.RK_AGG_MAX, "mean": rk.RK_AGG_MEAN}[agg]
         a, b_ = fresh(), fresh()
         states = (_LayerState * n_layers)(*[layer_state(geom, dev[l][1], dev[l][2], a["sK"][l], a["sV"][l], a["idx"][l],
                                                         a["tail"][l], need_full=need[l], n_full=a["n_full"][l], k=k)
@@ -961,11 +962,11 @@ def test_deferred_pooling_and_batched_refresh(rk):
             pr = need[l] if use_pred else None
             rk.rk_full_attn_deferred(geom, dev[l][0], dev[l][1], dev[l][2], sl, cap, a["out"][l], lse=a["lse"][l],
                                      pred=pr, pred_val=1, workspace=wss[l])
-        rk.rk_refresh_batched(geom, states, ws_ptrs, ws_bytes, sl, cap, k, pool_w=pool_w, by_need_full=use_pred)
+        rk.rk_refresh_batched(geom, states, ws_ptrs, ws_bytes, sl, cap, k, pool_w=pool_w, agg=agg_id, by_need_full=use_pred)
         for l in range(n_layers):       # the per-layer path on the first workspace
             pr = need[l] if use_pred else None
             rk.rk_full_attn_select(geom, dev[l][0], dev[l][1], dev[l][2], sl, cap, b_["out"][l], k, pool_w, b_["idx"][l],
-                                   lse=b_["lse"][l], pred=pr, pred_val=1, workspace=wss[0])
+                                   lse=b_["lse"][l], agg=agg_id, pred=pr, pred_val=1, workspace=wss[0])
             rk.rk_gather_small_kv(geom, dev[l][1], dev[l][2], b_["idx"][l], k, b_["sK"][l], b_["sV"][l], seq_lens=sl,
                                   tail_start=b_["tail"][l], pred=pr, pred_val=1)
         torch.cuda.synchronize()
@@ -988,8 +989,10 @@ def test_deferred_pooling_and_batched_refresh(rk):
                     assert (idx_n[b] == -1).all()
                     continue
                 for g in range(Hkv):
-                    P = oracle.pooled_group_scores(w_ref[b, g * G:(g + 1) * G, :n].astype(np.float32), pool_w)
-                    assert_idx_equivalent(idx_n[b, g], i_ref[b, g], P, n, k, "deferred l=%d b=%d g=%d" % (l, b, g))
+                    P = oracle.pooled_group_scores(w_ref[b, g * G:(g + 1) * G, :n].astype(np.float32), pool_w, agg=agg)
+                    i_want = i_ref[b, g] if agg == "max" else oracle.topk_select(w_ref[b:b + 1, g * G:(g + 1) * G].astype(np.float32),
+                                                                                 [n], 1, k, pool_w, agg=agg)[0][0, 0]
+                    assert_idx_equivalent(idx_n[b, g], i_want, P, n, k, "deferred %s l=%d b=%d g=%d" % (agg, l, b, g))
 
 
 def test_refresh_on_second_stream_stack(rk):

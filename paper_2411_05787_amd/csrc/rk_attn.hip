@@ -198,8 +198,7 @@ __device__ void merge_partials(const AttnParams& p, int b, int g, int nchunks, f
         const float wgt = (lane >= nchunks || mc == -INFINITY) ? 0.f : fast_exp2((mc - mx) * kLog2e);
         double ls = (double)wgt * (double)sLc[c * G + gi];      // the sum that normalises the output: fp64
         if (lane < nb * kMergeBatch) sW[lane * G + gi] = wgt;    // zero beyond nchunks: whole batches are summed
-#pragma unroll
-        for (int m = 1; m < 64; m <<= 1) ls += __shfl_xor(ls, m);
+        ls = wave_sum(ls);
         if (lane == 0) { sM[gi] = mx; sL[gi] = ls; }
     }
     __syncthreads();
@@ -491,8 +490,7 @@ void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t
         // ---- running softmax statistics of head n16 (row r itself is always valid: finite max) ----
         float mx = fmaxf(fmaxf(fmaxf(s[0][0], s[0][1]), fmaxf(s[0][2], s[0][3])),
                          fmaxf(fmaxf(s[1][0], s[1][1]), fmaxf(s[1][2], s[1][3])));
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        mx = max_xor32(max_xor16(mx));
         const float m_new = fmaxf(m_run, mx);
         const float alpha = fast_exp2((m_run - m_new) * kLog2e);
         m_run = m_new;
@@ -567,8 +565,7 @@ void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t
     }
 
     // ---- wavefront results to LDS ----
-    l_run += __shfl_xor(l_run, 16);
-    l_run += __shfl_xor(l_run, 32);
+    l_run = sum_xor32(sum_xor16(l_run));
     if (c4 == 0) { sMw[w][n16] = m_run; sLw[w][n16] = l_run; }
     if (c4 < NC) {
 #pragma unroll
@@ -700,8 +697,7 @@ void score_split_kernel(const AttnParams p) {
         }
         float mx = fmaxf(fmaxf(fmaxf(s[0][0], s[0][1]), fmaxf(s[0][2], s[0][3])),
                          fmaxf(fmaxf(s[1][0], s[1][1]), fmaxf(s[1][2], s[1][3])));
-        mx = fmaxf(mx, __shfl_xor(mx, 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        mx = max_xor32(max_xor16(mx));
         const float m_new = fmaxf(m_run, mx);             // finite: the tile's first row is valid
         float ps = 0.f;
 #pragma unroll
@@ -722,8 +718,7 @@ void score_split_kernel(const AttnParams p) {
         if (r + 2 * step < n) load_clamped(kB, r + 2 * step);
         r += step;
     }
-    l_run += __shfl_xor(l_run, 16);
-    l_run += __shfl_xor(l_run, 32);
+    l_run = sum_xor32(sum_xor16(l_run));
     __shared__ float sMw[NW][16], sLw[NW][16];
     if (c4 == 0) { sMw[w][n16] = m_run; sLw[w][n16] = l_run; }
     __syncthreads();
@@ -961,8 +956,7 @@ void finish_pool_body(const AttnParams& p, const float* __restrict__ scores, int
             const float wgt = (m[e][u] == -INFINITY) ? 0.f : fast_exp2((m[e][u] - M) * kLog2e);
             L64 += (double)wgt * (double)l[e][u];
         }
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) L64 += __shfl_xor(L64, d);
+        L64 = wave_sum(L64);
         if (lane == 0 && gi < G) {
             float hi = -INFINITY, lo = 0.f;
             if (L64 > 0.0) {

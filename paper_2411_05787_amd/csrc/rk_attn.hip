@@ -757,7 +757,7 @@ struct HeadMergeLds {
     double L64;
     float acc[4][kD];
 };
-constexpr int kOutBatch = 16;                    // partial outputs per thread and round trip
+constexpr int kOutBatch = 24;                    // partial outputs per thread and round trip (96 partial results: one trip)
 
 // lse of (b, h) in fp64 from the per-chunk (max, sum) pairs: s.lse = (hi, lo) with hi + lo = lse,
 // s.w[c] = e^{m_c - M}, s.L64 = sum_c w_c l_c.  All 256 threads call; ends with a barrier.

@@ -95,11 +95,18 @@ template <int NT>
 __device__ __forceinline__ uint32_t block_inclusive_scan(uint32_t v, uint32_t* scratch, uint32_t* total) {
     constexpr int NWV = NT / 64;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    // inside the wavefront: a scan of every row of 16 lanes on the DPP path (a lane whose source
+    // would lie outside its row adds 0), then the totals of the rows before, through scalar registers
     uint32_t x = v;
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const uint32_t y = __shfl_up(x, d);
-        if (lane >= d) x += y;
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x111, 0xF, 0xF, true);     // row_shr:1
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x112, 0xF, 0xF, true);     // row_shr:2
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x114, 0xF, 0xF, true);     // row_shr:4
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x118, 0xF, 0xF, true);     // row_shr:8
+    {
+        const uint32_t t0 = (uint32_t)__builtin_amdgcn_readlane((int)x, 15), t1 = (uint32_t)__builtin_amdgcn_readlane((int)x, 31);
+        const uint32_t t2 = (uint32_t)__builtin_amdgcn_readlane((int)x, 47);
+        const int row = lane >> 4;
+        x += row == 0 ? 0u : row == 1 ? t0 : row == 2 ? t0 + t1 : t0 + t1 + t2;
     }
     __syncthreads();                              // scratch may still be read from a previous scan
     if (lane == 63) scratch[w] = x;

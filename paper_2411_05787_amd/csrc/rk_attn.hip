@@ -150,83 +150,104 @@ __device__ __forceinline__ void wait_stores_acknowledged() { asm volatile("s_wai
 
 // Merge of the partial results of one (sequence, KV head); run by one whole workgroup.
 //   M = max_c m_c;  L = sum_c e^{m_c - M} l_c;  out = sum_c e^{m_c - M} o_c / L;  lse = M + ln L
-// Only one workgroup per (sequence, KV head) ever gets here, on whichever CU it happens to run,
-// so this code is fetched cold: it is kept small (rolled loops, no fp64 library calls) because
-// instruction fetch, not arithmetic, is what its run time is made of.  Partial outputs are read
-// in batches of kMergeBatch chunks, two batches ahead of their use: up to 2 * kMergeBatch chunks
-// cost one round trip, requested together with the (max, sum) pairs.
+// Only one workgroup per (sequence, KV head) ever gets here, and nothing runs beside it on its
+// CU: what it costs is the round trip of its loads plus one instruction after the other, so it is
+// kept small (rolled loops, no fp64 library calls).  The partial outputs are read with 16-byte
+// agent-scope loads, four consecutive dims of one chunk each (the read of kMergeBatch partial
+// results of a group of 4 is 8 requests per thread; as 8-byte requests, 16 per thread, the same
+// bytes took twice as long to come back), in batches of kMergeBatch chunks, two batches ahead of
+// their use: up to 2 * kMergeBatch chunks cost one round trip, requested together with the
+// (max, sum) pairs.  Where the outputs are fewer than half the threads, two halves of the
+// workgroup take every other chunk and meet in LDS.
 constexpr int kMergeBatch = 16;
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 
 template <int G, int NW>
 __device__ void merge_partials(const AttnParams& p, int b, int g, int nchunks, float* sW, float* sLc,
                                float* sM, double* sL) {
     constexpr int NT = NW * 64;
-    constexpr int PER = G * kD / 2;               // pairs of consecutive dims to produce
-    constexpr int SLICES = (PER + NT - 1) / NT;   // pairs per thread: 1 (G <= 4) or 2
+    constexpr int PER4 = G * kD / 4;              // groups of four consecutive dims to produce
+    static_assert(PER4 <= NT, "one group of four dims per thread");
+    constexpr int T = (2 * PER4 <= NT) ? 2 : 1;   // halves of the workgroup that share the chunks
+    constexpr int LB = kMergeBatch / T;           // loads per thread and batch
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int64_t bg = (int64_t)b * p.Hkv + g;
     const float* ml = p.part_ml + bg * kMaxChunks * G * 2;
     const float* po = p.part_o + bg * p.max_chunks * G * kD;
     const int n_ml = nchunks * G;
     static_assert(2 * NT >= kMergeChunks * RK_MAX_GROUP, "two loads per thread cover all (chunk, head) pairs");
+    float* sRed = sLc + kMergeChunks * G;         // [PER4][4]: the second half's sums
+    static_assert(NW * G * kD >= 2 * kMergeChunks * G + PER4 * 4, "merge scratch fits in the output staging buffer");
 
-    // Work items of this thread, in order: (slice 0, batch 0), (slice 0, batch 1), ... (slice 1, batch 0) ...
+    const int half = tid / PER4, e4 = tid - half * PER4;          // (threads with half >= T only take part in the barriers)
+    const bool active = half < T;
+    const int gi = (4 * e4) / kD;
+    // the partial outputs of this (sequence, KV head) as a buffer: reads past its end return 0
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<float*>(po), 0, (int)((int64_t)p.max_chunks * G * kD * sizeof(float)), 0x00020000);
+    constexpr int kAgentScope = 16;               // cache-policy operand of the buffer load: sc1
     const int nb = (nchunks + kMergeBatch - 1) / kMergeBatch;
-    const int n_items = SLICES * nb;
-    uint64_t cur[kMergeBatch], nxt[kMergeBatch];
-    int r_slice = 0, r_batch = 0;                 // the next item to request
-    auto request = [&](uint64_t (&dst)[kMergeBatch]) {
-        const float* src = po + 2 * min(r_slice * NT + tid, PER - 1);
-        const int c0 = r_batch * kMergeBatch;
+    u32x4_t cur[LB], nxt[LB];
+    int r_batch = 0;                              // the next batch to request
+    auto request = [&](u32x4_t (&dst)[LB]) {
+        const int c0 = r_batch * kMergeBatch + (active ? half : 0);
 #pragma unroll
-        for (int u = 0; u < kMergeBatch; ++u) dst[u] = coherent_load2(src + (int64_t)min(c0 + u, nchunks - 1) * G * kD);
-        if (++r_batch == nb) { r_batch = 0; ++r_slice; }
+        for (int u = 0; u < LB; ++u) {
+            const int c = min(c0 + u * T, nchunks - 1);
+            dst[u] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (c * G * kD + e4 * 4) * (int)sizeof(float), 0, kAgentScope);
+        }
+        ++r_batch;
     };
     // everything below is requested before the first wait
     const uint64_t ml0 = coherent_load2(ml + (int64_t)min(tid, n_ml - 1) * 2);
     const uint64_t ml1 = coherent_load2(ml + (int64_t)min(NT + tid, n_ml - 1) * 2);
     request(cur);
-    if (n_items > 1) request(nxt);
+    if (nb > 1) request(nxt);
     if (tid < n_ml) { sW[tid] = lo_f(ml0); sLc[tid] = hi_f(ml0); }
     if (NT + tid < n_ml) { sW[NT + tid] = lo_f(ml1); sLc[NT + tid] = hi_f(ml1); }
     __syncthreads();
     // one wavefront per head: M = max_c m_c, w_c = e^{m_c - M} (overwrites m_c), L = sum_c w_c l_c
-    for (int gi = w; gi < G; gi += NW) {
+    for (int gj = w; gj < G; gj += NW) {
         const int c = min(lane, nchunks - 1);     // nchunks <= kMergeChunks = 64: one chunk per lane
-        const float mc = sW[c * G + gi];
+        const float mc = sW[c * G + gj];
         const float mx = wave_max(mc);
         const float wgt = (lane >= nchunks || mc == -INFINITY) ? 0.f : fast_exp2((mc - mx) * kLog2e);
-        double ls = (double)wgt * (double)sLc[c * G + gi];      // the sum that normalises the output: fp64
-        if (lane < nb * kMergeBatch) sW[lane * G + gi] = wgt;    // zero beyond nchunks: whole batches are summed
+        double ls = (double)wgt * (double)sLc[c * G + gj];      // the sum that normalises the output: fp64
+        if (lane < nb * kMergeBatch) sW[lane * G + gj] = wgt;    // zero beyond nchunks: whole batches are summed
         ls = wave_sum(ls);
-        if (lane == 0) { sM[gi] = mx; sL[gi] = ls; }
+        if (lane == 0) { sM[gj] = mx; sL[gj] = ls; }
     }
     __syncthreads();
-    float acc0 = 0.f, acc1 = 0.f;
-    int slice = 0, batch = 0;                     // the item in `cur`
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll 1
-    for (int item = 0; item < n_items; ++item) {
-        const int e2 = min(slice * NT + tid, PER - 1);
-        const int gi = (2 * e2) / kD;
-        const float* wrow = sW + batch * kMergeBatch * G + gi;
+    for (int batch = 0; batch < nb; ++batch) {
+        const float* wrow = sW + (batch * kMergeBatch + (active ? half : 0)) * G + gi;
 #pragma unroll
-        for (int u = 0; u < kMergeBatch; ++u) {
-            const float wgt = wrow[u * G];
-            acc0 = fmaf(wgt, lo_f(cur[u]), acc0);
-            acc1 = fmaf(wgt, hi_f(cur[u]), acc1);
+        for (int u = 0; u < LB; ++u) {
+            const float wgt = wrow[u * T * G];
+            acc[0] = fmaf(wgt, __uint_as_float(cur[u].x), acc[0]);
+            acc[1] = fmaf(wgt, __uint_as_float(cur[u].y), acc[1]);
+            acc[2] = fmaf(wgt, __uint_as_float(cur[u].z), acc[2]);
+            acc[3] = fmaf(wgt, __uint_as_float(cur[u].w), acc[3]);
         }
 #pragma unroll
-        for (int u = 0; u < kMergeBatch; ++u) cur[u] = nxt[u];
-        if (item + 2 < n_items) request(nxt);
-        if (++batch == nb) {                       // that was the last batch of the slice
-            if (slice * NT + tid < PER) {
-                const float L = (float)sL[gi];
-                const float inv = L > 0.f ? 1.f / L : 0.f;
-                const uint32_t packed = (uint32_t)f32_to_bf16(acc0 * inv) | ((uint32_t)f32_to_bf16(acc1 * inv) << 16);
-                reinterpret_cast<uint32_t*>(p.out + ((int64_t)b * p.Hq + g * G) * kD)[e2] = packed;
-            }
-            acc0 = 0.f; acc1 = 0.f; batch = 0; ++slice;
+        for (int u = 0; u < LB; ++u) cur[u] = nxt[u];
+        if (batch + 2 < nb) request(nxt);
+    }
+    if (T == 2) {                                 // the second half hands its sums over
+        if (half == 1) *reinterpret_cast<float4*>(sRed + e4 * 4) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        __syncthreads();
+        if (half == 0) {
+            const float4 o = *reinterpret_cast<const float4*>(sRed + e4 * 4);
+            acc[0] += o.x; acc[1] += o.y; acc[2] += o.z; acc[3] += o.w;
         }
+    }
+    if (half == 0) {
+        const float L = (float)sL[gi];
+        const float inv = L > 0.f ? 1.f / L : 0.f;
+        const uint2 packed = make_uint2((uint32_t)f32_to_bf16(acc[0] * inv) | ((uint32_t)f32_to_bf16(acc[1] * inv) << 16),
+                                        (uint32_t)f32_to_bf16(acc[2] * inv) | ((uint32_t)f32_to_bf16(acc[3] * inv) << 16));
+        reinterpret_cast<uint2*>(p.out + ((int64_t)b * p.Hq + g * G) * kD)[e4] = packed;
     }
     if (tid < G) {                                // fp32 log: lse is an fp32 output, M + ln L loses nothing that matters
         const float L = (float)sL[tid];
@@ -411,7 +432,7 @@ void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t
     __shared__ float sMf[8];
     __shared__ double sLf[8];
     __shared__ int sTicket;
-    static_assert(NW * G * kD >= 2 * kMergeChunks * G, "merge scratch must fit in the output staging buffer");
+    static_assert(NW * G * kD >= 2 * kMergeChunks * G + G * kD, "merge scratch must fit in the output staging buffer");
 
     float m_run = -INFINITY, l_run = 0.f;          // of head n16, over the rows this lane group saw
     f32x4 acc_o[8];

@@ -41,12 +41,13 @@ def parse():
                          "kernels of all layers back to back from C; graph: replay one HIP graph per step; hybrid: "
                          "partial steps native, full steps as a replayed HIP graph; eager: one Python call per library call")
     ap.add_argument("--no-overlap", action="store_true",
-                    help="keep the selection and the gather of a full step on the main stream (default: second stream, "
-                         "beside the full attention of the following layers)")
+                    help="keep the selection and the gather of a full step per layer on the main stream (default: see "
+                         "--refresh)")
     ap.add_argument("--overlap-workspaces", type=int, default=3, help="workspaces the overlapped refresh rotates (0: one per layer)")
     ap.add_argument("--refresh", choices=["batched", "second-stream"], default="batched",
-                    help="how a full step of the layer stack does its selections and gathers: all layers at once after "
-                         "the last layer's attention (rk_refresh_batched), or per layer on a second stream")
+                    help="how a full step of the layer stack does its pooling, selections and gathers: all layers at once "
+                         "after the last layer's attention (rk_full_attn_deferred + rk_refresh_batched), or per layer on a "
+                         "second stream beside the full attention of the following layers")
     ap.add_argument("--run-ahead", type=int, default=1,
                     help="steps that may still be pending when a two-stream (full) step is submitted (-1: no limit)")
     ap.add_argument("--no-cpu-baseline", action="store_true")

@@ -72,6 +72,7 @@ FULL_CASES = [
     ("ragged_64", 64, 4, 1, [((i * 37) % 19) * 61 + (i % 3) for i in range(64)], 1152),
     ("ragged_65_even_split", 65, 4, 1, [((i * 37) % 19) * 61 + (i % 3) for i in range(65)], 1152),
     ("ragged_one_long", 3, 8, 2, [6000, 40, 200], 6016),
+    ("ragged_64_one_long", 64, 4, 1, [3000] + [1] * 62 + [0], 3008),     # shares capped by the rows a sequence has
 ]
 
 

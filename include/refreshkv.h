@@ -33,7 +33,9 @@
  *   stream (or otherwise serialised).
  * - bf16 tensors are 16-bit patterns (upper half of IEEE fp32).  head_dim must be 128, rows of
  *   128 elements are contiguous, and K/V base pointers and strides must keep rows 16-byte
- *   aligned.  Strides are counted in elements.
+ *   aligned.  q must be 16-byte aligned; out needs 2-byte alignment only, but 8-byte alignment
+ *   (any freshly allocated tensor, any [.., n_q_heads, 128] slice of one) lets a row leave in
+ *   8-byte stores.  Strides are counted in elements.
  * - Query head h reads KV head h / G with G = n_q_heads / n_kv_heads (1 <= G <= 8).
  * - `seq_lens` is a device int32[batch]: the number of valid rows of each sequence in C_f, the
  *   current token included.  `max_len` is a host-side upper bound of it, used to size grids; a

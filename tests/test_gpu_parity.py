@@ -411,6 +411,14 @@ def test_partial_attn_matches_oracle(rk, case):
     oracle.gather_small_kv(gen.bf16_bits(K), gen.bf16_bits(V), idx.numpy(), rK, rV)
     o_ref = oracle.partial_attn(gen.bf16_bits(q), rK, rV, n_sel, gen.bf16_bits(K), gen.bf16_bits(V), tail, lens, scale)
     assert_out_close(gen.bf16_bits(out), o_ref, name)
+    # an output that is only 2-byte aligned (the kernel stores 8 bytes at a time where it can): same bits
+    raw = torch.zeros(B * Hq * 128 + 1, dtype=torch.bfloat16, device="cuda")
+    out_odd = raw[1:].view(B, Hq, 128)
+    assert out_odd.data_ptr() % 4 == 2
+    rk.rk_partial_attn(geom, q.cuda(), sK, sV, n_sel, Kd, Vd, torch.tensor(tail, dtype=torch.int32, device="cuda"),
+                       torch.tensor(lens, dtype=torch.int32, device="cuda"), max(max(recent), 1), out_odd, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(out_odd, out) and raw[0].item() == 0
 
 
 def test_partial_attn_fixed_size_per_sequence(rk):

@@ -55,6 +55,17 @@ def parse():
     return ap.parse_args()
 
 
+def cost_model(w, lens0, eff_stride, achieved_gbps, measured_us):
+    per_token = 2 * w.n_kv_heads * w.head_dim * 2
+    stride = (eff_stride or {}).get("mean") or (w.stride if w.stride > 0 else float("inf"))
+    rows = float(lens0.sum()) / stride + w.k_small * w.batch
+    model_bytes = per_token * rows
+    return {"bytes_per_step_layer": int(model_bytes), "stride": stride,
+            "us_at_hbm_peak": round(model_bytes / 8000e9 * 1e6, 2),
+            "us_at_achieved_rate": round(model_bytes / (achieved_gbps * 1e9) * 1e6, 2),
+            "measured_us": round(measured_us, 2)}
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -410,6 +421,10 @@ def main():
         "full_attn_GBps": round((bytes_kv + bytes_w) / (klass["full_attn"] * 1e-6) / 1e9, 1),
         "partial_attn_GBps": round(2 * Hkv * D * 2 * (w.k_small + 1) * B / (klass["partial_attn"] * 1e-6) / 1e9, 1),
         "effective_stride": eff_stride,
+        # Appendix A.2's cost model: K/V bytes moved per step and layer, averaged over a stride period
+        # = bytes per token x (L / S + K), here with the true sum of lengths, beside what it would
+        # take at the rate the first kernel of a full step reaches and what a step takes
+        "cost_model": cost_model(w, lens0, eff_stride, roofline["achieved"], us_per_step_layer),
         "roofline": roofline,
         "cpu_baseline": cpu,
         "calibration_copy_bytes": calibration_bytes,

@@ -61,7 +61,9 @@ typedef enum rk_status {
     RK_ERR_INVALID_ARG = -1,   /* NULL pointer, non-positive size, misaligned pointer/stride  */
     RK_ERR_UNSUPPORTED = -2,   /* head_dim != 128, G > 8, k too large, unknown aggregation ... */
     RK_ERR_WORKSPACE   = -3,   /* workspace NULL, misaligned or smaller than rk_workspace_bytes */
-    RK_ERR_HIP         = -4    /* a HIP runtime call failed (launch error)                    */
+    RK_ERR_HIP         = -4,   /* a HIP runtime call failed (launch error)                    */
+    RK_ERR_STATIC_SCRATCH = -5 /* the call needs more scratch than the library's built-in array
+                                  holds (rk_partial_attn_static); nothing was enqueued            */
 } rk_status;
 
 #define RK_AGG_MAX 0           /* aggregation across the query heads of a GQA group: max      */
@@ -270,6 +272,27 @@ int rk_partial_attn(const rk_geom* geom, const void* q, rk_kv small, int32_t n_s
                     int32_t max_recent, void* out,
                     const int32_t* pred, int32_t pred_val,
                     void* workspace, size_t workspace_bytes, void* stream);
+
+/* rk_partial_attn for callers that cannot allocate device memory or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments less the
+ * workspace, same kernels, same results bit for bit.  The step's scratch (arrival counters,
+ * per-workgroup softmax statistics and partial outputs) is a device array built into the library,
+ * RK_STATIC_SCRATCH_BYTES per GPU, held from the moment the library is loaded until the process
+ * ends; the call allocates and frees nothing and calls no library that does.
+ * Limits: batch * n_kv_heads <= 4096 and rk_partial_attn_static_bytes(geom, n_sel, max_recent) <=
+ * RK_STATIC_SCRATCH_BYTES (any step of up to 256 (sequence, KV head) pairs fits, whatever its
+ * n_sel, max_recent and group size); beyond them the call returns RK_ERR_STATIC_SCRATCH and
+ * enqueues nothing.  The device that is current when the call is made must be the stream's.  On
+ * its first call on a device the library looks the array up on that device and enqueues one small
+ * fill kernel ahead of the step.  All calls on one GPU share that GPU's array: calls that may
+ * overlap in time (different streams without an ordering between them, several host threads whose
+ * streams run concurrently) race on it and must be serialised by the caller. */
+#define RK_STATIC_SCRATCH_BYTES (8u << 20)
+size_t rk_partial_attn_static_bytes(const rk_geom* geom, int32_t n_sel, int32_t max_recent);
+int rk_partial_attn_static(const rk_geom* geom, const void* q, rk_kv small, int32_t n_sel,
+                           rk_kv full, const int32_t* tail_start, const int32_t* seq_lens,
+                           int32_t max_recent, void* out,
+                           const int32_t* pred, int32_t pred_val, void* stream);
 
 /* The same step with the fixed-size small cache of Section 2.2 ("Decoding with partial cache":
  * the new token's KV pair is appended to C_p and the KV pair with the lowest score is evicted):

@@ -16,7 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "librefreshkv.so")
 
 EXPORTS = ["rk_version", "rk_status_string", "rk_workspace_bytes", "rk_workspace_init",
-           "rk_full_attn", "rk_full_attn_scores", "rk_topk_select", "rk_full_attn_select", "rk_full_attn_pool", "rk_full_attn_deferred", "rk_select_pooled", "rk_score_select", "rk_window_select", "rk_gather_small_kv", "rk_partial_attn", "rk_partial_attn_fixed", "rk_partial_attn_lazy", "rk_decode_step", "rk_decode_step_overlapped", "rk_refresh_batched", "rk_decode_step_batched",
+           "rk_full_attn", "rk_full_attn_scores", "rk_topk_select", "rk_full_attn_select", "rk_full_attn_pool", "rk_full_attn_deferred", "rk_select_pooled", "rk_score_select", "rk_window_select", "rk_gather_small_kv", "rk_partial_attn", "rk_partial_attn_static", "rk_partial_attn_static_bytes", "rk_partial_attn_fixed", "rk_partial_attn_lazy", "rk_decode_step", "rk_decode_step_overlapped", "rk_refresh_batched", "rk_decode_step_batched",
            "rk_query_sim", "rk_mark_refresh", "rk_calibration_copy", "rk_h2o_append", "rk_h2o_update", "rk_h2o_step"]
 
 RK_AGG_MAX, RK_AGG_MEAN, RK_AGG_FIRST = 0, 1, 2
@@ -99,6 +99,10 @@ def _load(path: str = LIB_PATH) -> C.CDLL:
     l.rk_gather_small_kv.argtypes = [G, _Kv, P, I32, _Kv, P, P, P, I32, P]
     l.rk_partial_attn.restype = C.c_int
     l.rk_partial_attn.argtypes = [G, P, _Kv, I32, _Kv, P, P, I32, P, P, I32, P, SZ, P]
+    l.rk_partial_attn_static.restype = C.c_int
+    l.rk_partial_attn_static.argtypes = [G, P, _Kv, I32, _Kv, P, P, I32, P, P, I32, P]
+    l.rk_partial_attn_static_bytes.restype = SZ
+    l.rk_partial_attn_static_bytes.argtypes = [G, I32, I32]
     l.rk_partial_attn_fixed.restype = C.c_int
     l.rk_partial_attn_fixed.argtypes = [G, P, _Kv, I32, _Kv, P, P, I32, P, P, I32, P, SZ, P]
     l.rk_partial_attn_lazy.argtypes = [G, P, _Kv, P, I32, I32, _Kv, P, P, I32, P, P, I32, P, SZ, P]
@@ -415,6 +419,25 @@ def rk_partial_attn(geom: Geom, q, small_K, small_V, n_sel: int, K, V, tail_star
         int(max_recent), _dev(out, torch.bfloat16, "out", (B, Hq, D)),
         _dev(pred, torch.int32, "pred", (B,), optional=True), int(pred_val),
         workspace.ptr, workspace.nbytes, _stream(stream)))
+
+
+STATIC_SCRATCH_BYTES = 8 << 20
+
+
+def rk_partial_attn_static_bytes(geom: Geom, n_sel: int, max_recent: int) -> int:
+    return int(lib.rk_partial_attn_static_bytes(C.byref(geom.c()), int(n_sel), int(max_recent)))
+
+
+def rk_partial_attn_static(geom: Geom, q, small_K, small_V, n_sel: int, K, V, tail_start, seq_lens,
+                           max_recent: int, out, pred=None, pred_val: int = 0, stream=None) -> None:
+    """rk_partial_attn on the library's built-in scratch array: no workspace, nothing allocated."""
+    B, Hq, D = geom.batch, geom.n_q_heads, geom.head_dim
+    _check("rk_partial_attn_static", lib.rk_partial_attn_static(
+        C.byref(geom.c()), _dev(q, torch.bfloat16, "q", (B, Hq, D)),
+        _kv(geom, small_K, small_V, "small", min_rows=n_sel), int(n_sel), _kv(geom, K, V, "full"),
+        _dev(tail_start, torch.int32, "tail_start", (B,)), _dev(seq_lens, torch.int32, "seq_lens", (B,)),
+        int(max_recent), _dev(out, torch.bfloat16, "out", (B, Hq, D)),
+        _dev(pred, torch.int32, "pred", (B,), optional=True), int(pred_val), _stream(stream)))
 
 
 def rk_partial_attn_fixed(geom: Geom, q, small_K, small_V, k: int, K, V, tail_start, seq_lens,

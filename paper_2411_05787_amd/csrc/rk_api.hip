@@ -12,6 +12,7 @@ extern "C" const char* rk_status_string(int status) {
         case RK_ERR_UNSUPPORTED: return "unsupported configuration";
         case RK_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
         case RK_ERR_HIP: return "HIP runtime error";
+        case RK_ERR_STATIC_SCRATCH: return "sizes beyond the library's built-in scratch array";
         default: return "unknown status";
     }
 }

@@ -30,6 +30,8 @@
 #include "rk_internal.h"
 #include "rk_device.h"
 
+#include <mutex>
+
 namespace rk {
 
 struct AttnParams {
@@ -1315,11 +1317,9 @@ extern "C" int rk_full_attn_scores(const rk_geom* geom, const void* q, rk_kv ful
                            ws, (hipStream_t)stream, true, -1, false, RK_AGG_MAX);
 }
 
-static int partial_attn_impl(const rk_geom* geom, const void* q, rk_kv small, int32_t n_sel, bool evict,
-                             rk_kv full, const int32_t* tail_start, const int32_t* seq_lens,
-                             int32_t max_recent, void* out,
-                             const int32_t* pred, int32_t pred_val,
-                             void* workspace, size_t workspace_bytes, void* stream, const int32_t* lazy_idx = nullptr) {
+// Argument checks of the partial step (everything but the scratch memory).
+static int check_partial_args(const rk_geom* geom, const void* q, rk_kv small, int32_t n_sel, rk_kv full,
+                              const int32_t* tail_start, const int32_t* seq_lens, int32_t max_recent, void* out) {
     int rc = check_geom(geom);
     if (rc != RK_OK) return rc;
     if (!q || !out || !seq_lens || !tail_start || n_sel < 0 || max_recent < 0) return RK_ERR_INVALID_ARG;
@@ -1327,10 +1327,14 @@ static int partial_attn_impl(const rk_geom* geom, const void* q, rk_kv small, in
     if (!aligned16(q) || ((uintptr_t)out & 1u)) return RK_ERR_INVALID_ARG;
     if ((rc = check_kv(full)) != RK_OK) return rc;
     if (n_sel > 0 && (rc = check_kv(small)) != RK_OK) return rc;
-    const int max_rows = n_sel + max_recent;
-    Workspace ws;
-    if ((rc = check_workspace(geom, max_rows, 0, workspace, workspace_bytes, &ws)) != RK_OK) return rc;
+    return RK_OK;
+}
 
+// Launch of the partial step; `ws` needs counters, lse, part_ml, part_o and max_chunks only.
+static int launch_partial(const rk_geom* geom, const void* q, rk_kv small, int32_t n_sel, bool evict,
+                          rk_kv full, const int32_t* tail_start, const int32_t* seq_lens,
+                          int32_t max_recent, void* out, const int32_t* pred, int32_t pred_val,
+                          const Workspace& ws, void* stream, const int32_t* lazy_idx = nullptr) {
     const int G = geom->n_q_heads / geom->n_kv_heads;
     AttnParams p{};
     p.q = (const uint16_t*)q;
@@ -1351,6 +1355,7 @@ static int partial_attn_impl(const rk_geom* geom, const void* q, rk_kv small, in
     p.lse = ws.lse;
     p.pred = pred; p.pred_val = pred_val;
     p.counters = ws.counters; p.part_ml = ws.part_ml; p.part_o = ws.part_o; p.max_chunks = ws.max_chunks;
+    if (p.nch > p.max_chunks) return RK_ERR_WORKSPACE;
     if (lazy_idx != nullptr) {      // rows of the selection come from the full cache and are written to `small` on the way
         if (n_sel < 1 || small.capacity < n_sel) return RK_ERR_INVALID_ARG;
         p.idx = lazy_idx; p.idx_stride = n_sel;
@@ -1358,6 +1363,19 @@ static int partial_attn_impl(const rk_geom* geom, const void* q, rk_kv small, in
     }
     const int nchunk_grid = p.nch;
     return launch_split<false, true>(p, geom->batch, G, nchunk_grid, (hipStream_t)stream);
+}
+
+static int partial_attn_impl(const rk_geom* geom, const void* q, rk_kv small, int32_t n_sel, bool evict,
+                             rk_kv full, const int32_t* tail_start, const int32_t* seq_lens,
+                             int32_t max_recent, void* out,
+                             const int32_t* pred, int32_t pred_val,
+                             void* workspace, size_t workspace_bytes, void* stream, const int32_t* lazy_idx = nullptr) {
+    int rc = check_partial_args(geom, q, small, n_sel, full, tail_start, seq_lens, max_recent, out);
+    if (rc != RK_OK) return rc;
+    Workspace ws;
+    if ((rc = check_workspace(geom, n_sel + max_recent, 0, workspace, workspace_bytes, &ws)) != RK_OK) return rc;
+    return launch_partial(geom, q, small, n_sel, evict, full, tail_start, seq_lens, max_recent, out, pred, pred_val,
+                          ws, stream, lazy_idx);
 }
 
 extern "C" int rk_partial_attn(const rk_geom* geom, const void* q, rk_kv small, int32_t n_sel,
@@ -1388,3 +1406,85 @@ extern "C" int rk_partial_attn_fixed(const rk_geom* geom, const void* q, rk_kv s
                              workspace, workspace_bytes, stream);
 }
 
+
+// ---- rk_partial_attn_static: the partial step for callers that cannot allocate ----
+// The scratch memory of the step (arrival counters, per-workgroup statistics and partial outputs)
+// lives in a file-scope device array instead of a caller's workspace.  Every GPU the library is
+// loaded on holds its own copy of the array at its own address; that address is looked up once per
+// device (hipGetSymbolAddress) and only the looked-up pointer is ever handed to kernels: in host
+// code the array's name is a stand-in, not a device address.
+namespace rk {
+constexpr size_t kStaticScratchBytes = (size_t)RK_STATIC_SCRATCH_BYTES;
+constexpr int kStaticMaxProblems = 4096;          // (sequence, KV head) pairs: one arrival counter each
+constexpr int kStaticMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+static std::mutex g_static_mutex;
+static unsigned char* g_static_ptr[kStaticMaxDevices];     // per device: its copy of `scratch`, counters cleared
+
+__global__ void static_clear_kernel(int32_t* p, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+
+// The scratch of the current device.  First use on a device: the address is looked up and the
+// counters are cleared by a small fill kernel on `stream` (not a memset: the call may be under
+// graph capture), ahead of the step that is enqueued next on the same stream.
+static int static_scratch(hipStream_t stream, unsigned char** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return RK_ERR_HIP;
+    if (dev < 0 || dev >= kStaticMaxDevices) return RK_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (g_static_ptr[dev] == nullptr) {
+        unsigned char* ptr = nullptr;
+        if (hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return RK_ERR_HIP;
+        if (((uintptr_t)ptr & 255u) != 0) return RK_ERR_HIP;
+        hipLaunchKernelGGL(static_clear_kernel, dim3(kStaticMaxProblems / 256), dim3(256), 0, stream,
+                           (int32_t*)ptr, kStaticMaxProblems);
+        if (launch_status() != RK_OK) return RK_ERR_HIP;
+        g_static_ptr[dev] = ptr;
+    }
+    *out = g_static_ptr[dev];
+    return RK_OK;
+}
+
+// Fixed layout of the array, whatever the geometry: counters first (always kStaticMaxProblems of
+// them, so a call with another geometry finds them where the last call left them: zero), then the
+// regions whose size follows the call.  Returns the bytes used.
+static size_t carve_static(const rk_geom* g, int32_t n_sel, int32_t max_recent, unsigned char* base, Workspace* w) {
+    const size_t problems = (size_t)g->batch * g->n_kv_heads;
+    const size_t G = (size_t)(g->n_q_heads / g->n_kv_heads);
+    *w = Workspace{};
+    w->max_chunks = merged_split_workgroups(n_sel, max_recent, (int64_t)problems);     // the launch's own count
+    size_t off = 0;
+    w->counters = (int32_t*)(base + off); off += (size_t)kStaticMaxProblems * sizeof(int32_t);
+    w->lse = (float*)(base + off);        off += align_up((size_t)g->batch * g->n_q_heads * sizeof(float), 256);
+    w->part_ml = (float*)(base + off);    off += align_up(problems * kMaxChunks * G * 2 * sizeof(float), 256);
+    w->part_o = (float*)(base + off);     off += align_up(problems * (size_t)w->max_chunks * G * kD * sizeof(float), 256);
+    w->total = off;
+    return off;
+}
+}  // namespace rk
+
+extern "C" size_t rk_partial_attn_static_bytes(const rk_geom* geom, int32_t n_sel, int32_t max_recent) {
+    if (check_geom(geom) != RK_OK || n_sel < 0 || max_recent < 0 || n_sel + (int64_t)max_recent <= 0 ||
+        n_sel + (int64_t)max_recent > INT32_MAX) return 0;
+    Workspace w;
+    return carve_static(geom, n_sel, max_recent, nullptr, &w);
+}
+
+extern "C" int rk_partial_attn_static(const rk_geom* geom, const void* q, rk_kv small, int32_t n_sel,
+                                      rk_kv full, const int32_t* tail_start, const int32_t* seq_lens,
+                                      int32_t max_recent, void* out,
+                                      const int32_t* pred, int32_t pred_val, void* stream) {
+    int rc = check_partial_args(geom, q, small, n_sel, full, tail_start, seq_lens, max_recent, out);
+    if (rc != RK_OK) return rc;
+    if ((int64_t)geom->batch * geom->n_kv_heads > kStaticMaxProblems) return RK_ERR_STATIC_SCRATCH;
+    Workspace ws;
+    if (carve_static(geom, n_sel, max_recent, nullptr, &ws) > kStaticScratchBytes) return RK_ERR_STATIC_SCRATCH;
+    unsigned char* base = nullptr;
+    if ((rc = static_scratch((hipStream_t)stream, &base)) != RK_OK) return rc;
+    carve_static(geom, n_sel, max_recent, base, &ws);
+    return launch_partial(geom, q, small, n_sel, false, full, tail_start, seq_lens, max_recent, out, pred, pred_val,
+                          ws, stream);
+}

@@ -37,7 +37,7 @@ def test_every_declared_symbol_is_exported(rk):
 def test_version_and_status_strings(rk):
     assert rk.version() >= 100
     assert rk.status_string(0) == "ok"
-    for code in (-1, -2, -3, -4):
+    for code in (-1, -2, -3, -4, -5):
         assert rk.status_string(code) not in ("ok", "unknown status")
     assert rk.status_string(-99) == "unknown status"
 
@@ -120,6 +120,18 @@ def test_host_side_argument_checks_return_before_any_launch(rk):
     assert lib.rk_partial_attn(C.byref(g), fake, kv, -1, kv, fake, fake, 4, fake, None, 0, 0x100000, ws_bytes, None) == -1
     assert lib.rk_partial_attn(C.byref(g), fake, kv, 0, kv, fake, fake, 0, fake, None, 0, 0x100000, ws_bytes, None) == -1
     assert lib.rk_partial_attn(C.byref(g), fake, kv, 16, kv, None, fake, 4, fake, None, 0, 0x100000, ws_bytes, None) == -1
+    static = lambda **kw: lib.rk_partial_attn_static(C.byref(kw.get("g", g)), kw.get("q", fake), kv, kw.get("n_sel", 16), kv,
+                                                     kw.get("tail", fake), fake, kw.get("recent", 4), fake, None, 0, None)
+    assert static(q=None) == -1
+    assert static(n_sel=-1) == -1
+    assert static(tail=None) == -1
+    assert static(n_sel=0, recent=0) == -1
+    assert static(g=_Geom(4097, 8, 8, 128, 1.0)) == -5                  # more (sequence, KV head) pairs than counters
+    assert static(g=_Geom(512, 64, 8, 128, 1.0)) == -5                  # statistics of 4096 pairs x 8 heads: beyond the array
+    assert lib.rk_partial_attn_static_bytes(C.byref(g), 2048, 16) <= 8 << 20
+    assert lib.rk_partial_attn_static_bytes(C.byref(_Geom(32, 64, 8, 128, 1.0)), 16384, 64) <= 8 << 20     # 256 pairs, G = 8
+    assert lib.rk_partial_attn_static_bytes(C.byref(_Geom(512, 64, 8, 128, 1.0)), 2048, 16) > 8 << 20
+    assert lib.rk_partial_attn_static_bytes(C.byref(g), 0, 0) == 0
     assert lib.rk_query_sim(C.byref(g), fake, None, 0.5, 0, fake, fake, None) == -1
     from paper_2411_05787_amd.binding import _H2oState
     h2o = lambda cap=257, total=fake: _H2oState(_Kv(fake, fake, 8 * cap * 128, cap * 128, cap), total, fake, fake, fake)

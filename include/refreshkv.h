@@ -109,10 +109,12 @@ const char* rk_status_string(int status);
 size_t rk_workspace_bytes(const rk_geom* geom, int32_t max_len, int32_t max_k);
 
 /* Prepare a workspace (256-byte aligned device memory of at least rk_workspace_bytes) for its
- * first use with this geometry: zeroes the arrival counters the kernels keep in it (a small
- * fill kernel on `stream`).  Call once after allocating it, on the stream that will use it.
- * The kernels leave the counters zero again after every call, so no further initialisation
- * is needed. */
+ * first use with this geometry: clears all workspace_bytes of it (a fill kernel on `stream`; no
+ * memset, so the call may sit in a captured graph).  The kernels keep arrival counters, call
+ * numbers and the tags of partial results there, which must start at zero.  Call once after
+ * allocating it, on the stream that will use it; the kernels leave it fit for the next call, so
+ * no further initialisation is needed.  A workspace belongs to one geometry (batch and head
+ * counts): initialise it again before using it with another. */
 int rk_workspace_init(const rk_geom* geom, void* workspace, size_t workspace_bytes, void* stream);
 
 /* Full-attention decode step.

@@ -24,9 +24,8 @@ extern "C" size_t rk_workspace_bytes(const rk_geom* geom, int32_t max_len, int32
 
 namespace rk {
 // A fill kernel instead of hipMemsetAsync, so that the call can sit inside a captured graph.
-__global__ void zero_words_kernel(int32_t* p, size_t n) {
-    const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = 0;
+__global__ __launch_bounds__(256) void zero_fill_kernel(uint4* p, size_t n) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) p[i] = make_uint4(0, 0, 0, 0);
 }
 __global__ __launch_bounds__(256) void calibration_copy_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src, size_t n) {
     for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) dst[i] = src[i];
@@ -58,9 +57,11 @@ extern "C" int rk_mark_refresh(const rk_geom* geom, const int32_t* seq_lens, int
 extern "C" int rk_workspace_init(const rk_geom* geom, void* workspace, size_t workspace_bytes, void* stream) {
     if (check_geom(geom) != RK_OK) return RK_ERR_INVALID_ARG;
     if (!workspace || ((uintptr_t)workspace & 255u) != 0) return RK_ERR_WORKSPACE;
-    const size_t n = zeroed_words(geom);     // arrival counters, candidate counters, histograms
-    if (workspace_bytes < align_up(n * sizeof(int32_t), 256)) return RK_ERR_WORKSPACE;
-    hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
-                       (int32_t*)workspace, n);
+    // counters, call numbers, histograms and the tags of the partial results must start at zero; the
+    // whole workspace is cleared, so that nothing depends on what the memory held before
+    if (workspace_bytes < zero_kept_bytes(geom)) return RK_ERR_WORKSPACE;
+    const size_t n = workspace_bytes / 16;
+    const unsigned grid = (unsigned)((n + 255) / 256 < 2048 ? (n + 255) / 256 : 2048);
+    hipLaunchKernelGGL(zero_fill_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, (uint4*)workspace, n);
     return launch_status();
 }

@@ -5,11 +5,20 @@
 // last for a (sequence, KV head) merges the partial results and writes the output.
 //
 // Hand-over between workgroups (which may sit on different XCDs, each with its own L2):
-// partial results are written with agent-scope atomic stores and read with agent-scope atomic
-// loads, i.e. write-through / coherent accesses; a writer waits until its stores are
-// acknowledged (s_waitcnt vmcnt(0)) before it takes its arrival ticket with an agent-scope
-// atomic add.  No cache-wide release/acquire fence is used: on this chip one such fence per
-// workgroup writes back and invalidates a whole L2 and costs more than the attention itself.
+// partial results are written with agent-scope (write-through, coherent) stores and read with
+// agent-scope loads.  No cache-wide release/acquire fence is used: on this chip one such fence
+// per workgroup writes back and invalidates a whole L2 and costs more than the attention itself.
+// Two forms (template parameter TAGGED):
+//   tagged   every 16-byte row of a partial result carries the number of the call that wrote it.
+//            A workgroup issues its rows and takes its arrival ticket at once, without waiting for
+//            the rows to be acknowledged; the last arrival reads all rows and takes a row whose
+//            tag is not this call's as still in flight: it reads that row again.  Every row it
+//            waits for was issued before the ticket that made it the last arrival, so the wait
+//            ends whatever else happens on the chip.
+//   ticketed a writer waits until its stores are acknowledged (s_waitcnt vmcnt(0)) before it
+//            takes its ticket; the last arrival can then rely on everything it reads.  One
+//            round trip more; kept for scratch memory whose layout changes from call to call
+//            (rk_partial_attn_static), where an old tag could sit where a new one is expected.
 //
 // Data path per wavefront and tile of 32 rows:
 //   K rows  -> registers in MFMA operand layout (16-byte loads, no LDS)
@@ -42,6 +51,7 @@ struct AttnParams {
     const int32_t* seq_lens;
     int32_t n_sel;                     // rows taken from the small cache (TWO_SEG only)
     int32_t evict;                     // ... less one per row decoded since the refresh (fixed-size small cache)
+    int32_t tail_wg;                   // TWO_SEG: the rows of the full cache have a workgroup of their own (grid x = nch + 1)
     int32_t max_rows2;                 // host bound on the rows taken from the full cache
     int32_t cap1, cap2;                // rows allocated in the small / full cache
     int32_t nch;                       // workgroups per (sequence, KV head): the launch's grid x
@@ -53,6 +63,7 @@ struct AttnParams {
     float* lse;                        // fp32 [B, Hq], never NULL here
     const int32_t* pred; int32_t pred_val;
     int32_t* counters; float* part_ml; float* part_o; int32_t max_chunks;
+    uint32_t* epochs; uint32_t* tag_rows;     // TAGGED only: call number per (sequence, KV head), tagged partial results
     const int32_t* idx; int32_t idx_stride;   // LAZY only: the selection [B, Hkv, idx_stride] whose rows are not gathered yet
     int32_t ragged_batch;              // != 0 (= batch): workgroups are shared out by length, see ragged_share_lane
 };
@@ -64,6 +75,7 @@ struct AttnParams {
 // streams one contiguous stretch of the cache.  Workgroups whose first row is past the end do
 // nothing; the others each leave one partial result (the merge takes any subsets of the rows).
 constexpr int kSplitWaves = 4, kTileRows = 32;
+constexpr int kNoTailWg = 0xff;                   // top byte of the kernel argument s_b_and_tail: no workgroup for the tail rows
 __device__ __forceinline__ int active_workgroups(int n_rows, int nch) {
     return max(1, min(nch, (n_rows + kSplitWaves * kTileRows - 1) / (kSplitWaves * kTileRows)));
 }
@@ -284,6 +296,112 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
+// ---- tagged partial results ----
+// The partial result of workgroup c of a (sequence, KV head) is G * 44 rows of 16 bytes.  For each
+// head: 43 data rows { x[3r], x[3r+1], x[3r+2], tag } (the last holds two values) with
+// x = (sum_j e^{s_j - m} v_j) / l the chunk's own normalised output, and one row
+// { lambda, 0, 0, tag } with lambda = m + ln l, its log-sum-exp; tag is the number of the call.
+// A row is one 16-byte store of one lane and one 16-byte load of one lane: it is never split, so
+// a row whose tag is this call's holds this call's values.  The merge
+//   Lambda = max_c lambda_c,  w_c = e^{lambda_c - Lambda},  out = sum_c w_c x_c / sum_c w_c
+// needs no LDS and no barrier: the rows of a head are written by one wavefront of every workgroup
+// (wavefront h % 4 for head h of the group) and merged by one wavefront of the workgroup that
+// arrives last, lane r < 43 reading row r of every chunk and writing three elements.  lambda_c and
+// the weights are the same for every lane: lane u takes chunk u's lambda, the wavefront reduces
+// max and sum across lanes, and w_u reaches the other lanes as a scalar operand (v_readlane), which
+// leaves three multiply-adds per chunk and lane.  Chunks are summed in order: the result does not
+// depend on which workgroup merges or when.
+constexpr int kTagSpinLimit = 1 << 16;            // re-reads of rows still in flight before giving up (NaN output)
+constexpr int kAgentScopeAux = 16;                // cache-policy operand of buffer loads and stores: sc1
+
+// (`rows`: the partial result of one workgroup, the same for all lanes; `row`: this lane's row of it)
+__device__ __forceinline__ void store_tagged_row(uint32_t* rows, int n_rows, int row, float x0, float x1, float x2,
+                                                 uint32_t tag) {
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(rows, 0, n_rows * 16, 0x00020000);
+    const u32x4 v = {__float_as_uint(x0), __float_as_uint(x1), __float_as_uint(x2), tag};
+    __builtin_amdgcn_raw_buffer_store_b128(v, rsrc, row * 16, 0, kAgentScopeAux);
+}
+
+// Merge of the heads gi0, gi0 + 4, ... (NH of them; those >= G are skipped) of one (sequence, KV
+// head) by one whole wavefront.  TB partial results per round trip: the loads of all NH heads are
+// in flight together.
+template <int G, int NH, int TB>
+__device__ __forceinline__ void merge_tagged_heads(const AttnParams& p, int b, int g, int gi0, int nchunks_any_lane, uint32_t tag) {
+    constexpr int ROWS = G * kTagRowsPerHead;
+    static_assert(kTagDataRows <= 64 && TB <= 64, "one data row per lane, one chunk per lane");
+    const int nchunks = __builtin_amdgcn_readfirstlane(nchunks_any_lane);      // the same in all lanes: kept in a scalar register
+    const int lane = threadIdx.x & 63;
+    const int64_t bg = (int64_t)b * p.Hkv + g;
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        p.tag_rows + bg * kTagSlots * ROWS * 4, 0, kTagSlots * ROWS * 16, 0x00020000);
+    const int r = min(lane, kTagDataRows - 1);
+    float num[NH][3], den[NH], Lam[NH];
+    bool good = true;
+#pragma unroll
+    for (int i = 0; i < NH; ++i) { num[i][0] = 0.f; num[i][1] = 0.f; num[i][2] = 0.f; den[i] = 0.f; Lam[i] = -INFINITY; }
+#pragma unroll 1
+    for (int c0 = 0; c0 < nchunks; c0 += TB) {                   // one round trip up to TB partial results
+        u32x4 v[NH][TB], lt[NH];
+        bool ok = false;
+        int tries = 0;
+        const int nb = min(nchunks - c0, TB);                    // partial results of this round (the same for all lanes)
+        const int cl = c0 + min(lane, nb - 1);
+        while (!__all(ok) && tries++ < kTagSpinLimit) {          // again only for rows that were still in flight
+            if (tries > 1) __builtin_amdgcn_s_sleep(2);
+#pragma unroll
+            for (int i = 0; i < NH; ++i) {
+                const int h0 = min(gi0 + i * kSplitWaves, G - 1) * kTagRowsPerHead;
+                lt[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (cl * ROWS + h0 + kTagDataRows) * 16, 0, kAgentScopeAux);
+#pragma unroll
+                for (int u = 0; u < TB; ++u)
+                    v[i][u] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, ((c0 + min(u, nb - 1)) * ROWS + h0 + r) * 16, 0, kAgentScopeAux);
+            }
+            ok = true;
+#pragma unroll
+            for (int i = 0; i < NH; ++i) {
+                ok = ok && (lt[i].w == tag);
+#pragma unroll
+                for (int u = 0; u < TB; ++u) ok = ok && (v[i][u].w == tag);
+            }
+        }
+        good = good && ok;
+#pragma unroll
+        for (int i = 0; i < NH; ++i) {
+            const float lam = lane < nb ? __uint_as_float(lt[i].x) : -INFINITY;      // this lane's chunk, if it has one
+            const float nl = fmaxf(fmaxf(Lam[i], wave_max(lam)), -3.0e38f);          // finite: exponents below are never inf - inf
+            const float wv = fast_exp2((lam - nl) * kLog2e);                          // 0 for lanes without a chunk and for empty chunks
+            const float so = fast_exp2((Lam[i] - nl) * kLog2e);
+            float a0 = num[i][0] * so, a1 = num[i][1] * so, a2 = num[i][2] * so;
+            den[i] = fmaf(den[i], so, wave_sum(wv));
+#pragma unroll
+            for (int u = 0; u < TB; ++u) {
+                const float wu = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(wv), u));
+                a0 = fmaf(wu, __uint_as_float(v[i][u].x), a0);
+                a1 = fmaf(wu, __uint_as_float(v[i][u].y), a1);
+                a2 = fmaf(wu, __uint_as_float(v[i][u].z), a2);
+            }
+            num[i][0] = a0; num[i][1] = a1; num[i][2] = a2; Lam[i] = nl;
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < NH; ++i) {
+        const int gi = gi0 + i * kSplitWaves;
+        if (gi < G) {
+            const float inv = den[i] > 0.f ? __builtin_amdgcn_rcpf(den[i]) : 0.f;
+            const float nan = __uint_as_float(0x7fc00000u);
+            const uint32_t p01 = good ? pack_bf16(num[i][0] * inv, num[i][1] * inv) : pack_bf16(nan, nan);
+            const uint32_t p2 = good ? pack_bf16(num[i][2] * inv, 0.f) : pack_bf16(nan, 0.f);
+            const int64_t bh = (int64_t)b * p.Hq + g * G + gi;
+            uint16_t* o = p.out + bh * kD + 3 * lane;
+            if (lane < kTagDataRows) {
+                o[0] = (uint16_t)p01; o[1] = (uint16_t)(p01 >> 16);
+                if (lane < kTagDataRows - 1) o[2] = (uint16_t)p2;
+            }
+            if (lane == 0) p.lse[bh] = den[i] > 0.f ? Lam[i] + __logf(den[i]) : -INFINITY;
+        }
+    }
+}
+
 // Roles of lane (n16, c4) = (lane % 16, lane / 16) of a wavefront, per tile of 32 rows:
 //   K operand   row n16 of a 16-row half tile, dims 8*(4*kk + c4) .. +7, kk = 0..3
 //   Q operand   head n16 (zero beyond G), same dims
@@ -301,14 +419,15 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 // leaves the small cache as rk_gather_small_kv would have.  k_first / v_first / s_b / s_h then
 // describe the FULL cache and `pred` carries the selection (the predicate is read from `p`).
 
-template <int G, int NW, bool EMIT, bool TWO_SEG, bool LAZY = false>
+template <int G, int NW, bool EMIT, bool TWO_SEG, bool LAZY = false, bool TAGGED = !EMIT>
 __global__ __launch_bounds__(NW * 64, EMIT ? RK_EMIT_OCCUPANCY : 2)
-void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t s_b, int32_t s_h, int32_t spec_rows,
-                       const int32_t* seq_lens, const int32_t* tail_start, const int32_t* pred,
+void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t s_b_and_tail, int32_t s_h, int32_t spec_rows,
+                       const int32_t* seq_lens, const int32_t* tail_start, const int32_t* pred, const uint32_t* epochs,
                        const AttnParams p) {
     static_assert(!LAZY || (TWO_SEG && !EMIT), "the lazy gather belongs to the partial step");
+    static_assert(!(TAGGED && EMIT), "tagged partial results belong to the launches that merge inside the kernel");
     // The leading arguments repeat what the first loads need (the cache that holds the first rows,
-    // its strides, the two length arrays, the predicate): 14 dwords that the command processor
+    // its strides, the two length arrays, the predicate, the call numbers): 16 dwords that the command processor
     // hands over in registers at wavefront launch (kernel-argument preload), so neither the first
     // K/V request nor the read of the lengths waits for a read of the argument block.  Everything
     // else comes from `p` as before (tail_start is NULL unless TWO_SEG).  A launch with a predicate
@@ -321,8 +440,14 @@ void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t
     constexpr int NT = NW * 64;
     constexpr int VS = kD + 8;               // LDS row stride of the V tile (272 bytes: rows spread over banks)
 
+    // The sequence stride also carries, in its top byte, the grid x of the workgroup that takes the
+    // rows of the full cache on its own (kNoTailWg: none; see tail_mode below): like everything the
+    // first loads need, it is there when the wavefront starts.
+    const int64_t s_b = s_b_and_tail & ((1ll << 56) - 1);
+    const int tail_c = (int)(s_b_and_tail >> 56) & 0xff;
     int c = blockIdx.x, b = blockIdx.z, nch_b = p.nch;
     const int g = blockIdx.y;
+    const int n_kv = gridDim.y;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int n16 = lane & 15, c4 = lane >> 4;
     constexpr bool kCanBeRagged = EMIT && !TWO_SEG;
@@ -335,7 +460,7 @@ void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t
     }
     // LAZY: the selection's entries for the rows of a tile, lane i < 32 holding that of row r + i
     // (clamped into the full cache: a bad index reads a wrong row, never outside the cache)
-    const int32_t* sel = LAZY ? pred + ((int64_t)b * gridDim.y + g) * spec_rows : nullptr;   // idx_stride == spec_rows
+    const int32_t* sel = LAZY ? pred + ((int64_t)b * n_kv + g) * spec_rows : nullptr;   // idx_stride == spec_rows
     auto tile_sel = [&](int r, int n_rows) -> int {
         const int j = min(r + (lane & 31), n_rows - 1);
         return LAZY ? sel[max(j, 0)] : 0;
@@ -353,8 +478,14 @@ void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t
     // n_sel rows; full cache: its capacity), so a workgroup whose first 128 rows lie wholly below
     // it may read them at once; rows that turn out to be past the end are masked like any other.
     // This takes the round trip for seq_lens / tail_start off the critical path.
-    const int r_first = (c * NW + w) * ROWS;
-    const bool spec = (c + 1) * NW * ROWS <= spec_rows;     // spec_rows: min(n_sel, cap1) or cap2
+    // TWO_SEG with p.tail_wg: the launch has one workgroup more per (sequence, KV head), the last of
+    // grid x, which takes the rows of the full cache (the tokens decoded since the refresh) and
+    // nothing else; the others share the rows of the small cache.  Those few rows then cost no
+    // wavefront a second tile: the workgroup that has them finishes with the others, not a tile later.
+    const bool tail_mode = TWO_SEG && !LAZY && tail_c != kNoTailWg;
+    const bool is_tail = tail_mode && c == tail_c;
+    int r_first = (c * NW + w) * ROWS;
+    const bool spec = !is_tail && (c + 1) * NW * ROWS <= spec_rows;     // spec_rows: min(n_sel, cap1) or cap2
     u32x4 kA[2][4], vA[NV];
     if (spec) {
         const uint16_t* kspec = k_first + (int64_t)b * s_b + (int64_t)g * s_h + c4 * 8;
@@ -382,11 +513,14 @@ void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t
     // condition is always true; it only keeps the requests in a block of their own, up here.
     bf16x8 qa[4];
     int len_raw = 0, tail_raw = 0;
+    constexpr int UPW = (G + NW - 1) / NW;    // TAGGED: heads whose rows this wavefront publishes and merges (heads w, w + NW)
+    uint32_t epoch = 0;                       // ... and the number of the last call that merged this (sequence, KV head)
     {
         uint4 qu[4] = {make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0)};
         if (spec_rows >= 0) {
             len_raw = seq_lens[b];
             if (TWO_SEG) tail_raw = tail_start[b];
+            if (TAGGED) epoch = epochs[(int64_t)b * n_kv + g];
             const uint16_t* qrow = p.q + ((int64_t)b * p.Hq + (int64_t)g * G + (n16 < G ? n16 : 0)) * kD;
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk) qu[kk] = *reinterpret_cast<const uint4*>(qrow + (kk * 4 + c4) * 8);
@@ -413,9 +547,22 @@ void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t
     }
     const int n2 = min(max(len - start2, 0), p.max_rows2);
     const int n = n1 + n2;
-    const int nchunks = (kCanBeRagged && p.ragged_batch != 0) ? nch_b : active_workgroups(n, p.nch);
-    if (c >= nchunks) return;
-    const int row1 = n;
+    int nchunks, row1 = n, c_rec = c, n_split;          // partial results in all; end of this workgroup's rows; its slot; workgroups it shares rows with
+    if (tail_mode) {
+        const int n_main = (n1 > 0 || n2 == 0) ? active_workgroups(n1, p.nch) : 0;
+        nchunks = n_main + (n2 > 0 ? 1 : 0);
+        if (is_tail) {
+            if (n2 == 0) return;
+            c_rec = n_main; r_first = n1 + w * ROWS; n_split = 1;
+        } else {
+            if (c >= n_main) return;
+            row1 = n1; n_split = n_main;
+        }
+    } else {
+        nchunks = (kCanBeRagged && p.ragged_batch != 0) ? nch_b : active_workgroups(n, p.nch);
+        if (c >= nchunks) return;
+        n_split = nchunks;
+    }
 
     const uint16_t* kb1 = nullptr; const uint16_t* vb1 = nullptr;
     if (TWO_SEG) {
@@ -557,7 +704,7 @@ void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t
         }
         if (r_next < row1) load_v(r_next);
         wave_lds_sync();
-        if (__any(alpha != 1.0f)) {                 // the running max moved (always on the first tile)
+        if (r != r_first && __any(alpha != 1.0f)) {     // the running max moved (first tile: the accumulators are still zero)
             const float4 al = *reinterpret_cast<const float4*>(&sAlpha[w][(c4 < NC ? c4 : 0) * 4]);
 #pragma unroll
             for (int dt = 0; dt < 8; ++dt) {
@@ -579,7 +726,7 @@ void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t
     };
 
     {
-        const int step = nchunks * NW * ROWS;      // (== p.nch wherever a workgroup has a second tile, see active_workgroups)
+        const int step = n_split * NW * ROWS;      // (== p.nch wherever a workgroup has a second tile, see active_workgroups)
         int r = r_first;
         if (r < row1) {
             // the early request stands unless part of this chunk maps to the tail of the full cache
@@ -612,14 +759,12 @@ void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t
 
     // ---- merge the NW wavefronts and publish the partial result of this chunk ----
     const int64_t bg = (int64_t)b * p.Hkv + g;
-    float* ml = p.part_ml + (bg * kMaxChunks + c) * G * 2;
-    float* po = p.part_o + (bg * p.max_chunks + c) * G * kD;
-    for (int e2 = tid; e2 < G * kD / 2; e2 += NT) {           // two consecutive dims per thread
-        const int gi = (2 * e2) / kD, d = (2 * e2) % kD;
-        float M = sMw[0][gi];
+    // what the NW wavefronts found for dims d, d + 1 of head gi, as one: max, sum, unnormalised output
+    auto combine = [&](int gi, int d, float& M, float& L, float& acc0, float& acc1) {
+        M = sMw[0][gi];
 #pragma unroll
         for (int ww = 1; ww < NW; ++ww) M = fmaxf(M, sMw[ww][gi]);
-        float acc0 = 0.f, acc1 = 0.f, L = 0.f;
+        acc0 = 0.f; acc1 = 0.f; L = 0.f;
 #pragma unroll
         for (int ww = 0; ww < NW; ++ww) {
             const float mw = sMw[ww][gi];
@@ -629,6 +774,58 @@ void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t
             acc1 = fmaf(sc, t2.y, acc1);
             L = fmaf(sc, sLw[ww][gi], L);
         }
+    };
+    if (TAGGED) {
+        // Wavefront w publishes the rows of heads w, w + NW: lane r < 43 dims 3r .. 3r + 2, lane 43 the
+        // head's log-sum-exp.  The ticket is taken once every wavefront has ISSUED its rows; nothing
+        // waits for their acknowledgement (hence a bare barrier: __syncthreads would wait for the stores).
+        uint32_t* trows = p.tag_rows + (bg * kTagSlots + c_rec) * (G * kTagRowsPerHead * 4);
+        const uint32_t tag = epoch + 1u != 0u ? epoch + 1u : 1u;           // this call's number: never 0
+#pragma unroll
+        for (int i = 0; i < UPW; ++i) {
+            const int gi = w + i * NW;
+            if (gi < G) {
+                float M = sMw[0][gi];
+#pragma unroll
+                for (int ww = 1; ww < NW; ++ww) M = fmaxf(M, sMw[ww][gi]);
+                const int d = 3 * min(lane, kTagDataRows - 1);
+                float a0 = 0.f, a1 = 0.f, a2 = 0.f, L = 0.f;
+#pragma unroll
+                for (int ww = 0; ww < NW; ++ww) {
+                    const float mw = sMw[ww][gi];
+                    const float sc = (mw == -INFINITY) ? 0.f : fast_exp2((mw - M) * kLog2e);
+                    a0 = fmaf(sc, sO[ww][gi][d], a0);
+                    a1 = fmaf(sc, sO[ww][gi][d + 1], a1);
+                    a2 = fmaf(sc, sO[ww][gi][min(d + 2, kD - 1)], a2);
+                    L = fmaf(sc, sLw[ww][gi], L);
+                }
+                const float inv = L > 0.f ? __builtin_amdgcn_rcpf(L) : 0.f;
+                const float lam = L > 0.f ? M + __logf(L) : -INFINITY;
+                const bool lam_row = lane == kTagDataRows;
+                if (lane <= kTagDataRows)
+                    store_tagged_row(trows, G * kTagRowsPerHead, gi * kTagRowsPerHead + lane, lam_row ? lam : a0 * inv,
+                                     lam_row ? 0.f : a1 * inv, (lam_row || d + 2 >= kD) ? 0.f : a2 * inv, tag);
+            }
+        }
+        int32_t* counter = p.counters + bg * kCounterStride;
+        asm volatile("s_barrier" ::: "memory");
+        if (tid == 0) sTicket = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        if (sTicket != nchunks - 1) return;
+        // last arrival: every wavefront merges its heads
+        merge_tagged_heads<G, UPW, (UPW == 1 ? 20 : 17)>(p, b, g, w, nchunks, tag);
+        if (tid == 0) {
+            __hip_atomic_store(&p.epochs[bg], tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);       // next call
+        }
+        return;
+    }
+    float* ml = p.part_ml + (bg * kMaxChunks + c_rec) * G * 2;
+    float* po = p.part_o + (bg * p.max_chunks + c_rec) * G * kD;
+    for (int e2 = tid; e2 < G * kD / 2; e2 += NT) {           // two consecutive dims per thread
+        const int gi = (2 * e2) / kD, d = (2 * e2) % kD;
+        float M, L, acc0, acc1;
+        combine(gi, d, M, L, acc0, acc1);
         if (EMIT) {       // merged by the next kernel: ordinary stores
             *reinterpret_cast<float2*>(po + 2 * e2) = make_float2(acc0, acc1);
             if (d == 0) *reinterpret_cast<float2*>(ml + gi * 2) = make_float2(M, L);
@@ -639,14 +836,15 @@ void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t
     }
     if (EMIT) return;
 
-    // ---- the workgroup that arrives last for (b, g) merges all chunks ----
+    // ---- ticketed hand-over: the workgroup that arrives last for (b, g) merges all chunks ----
+    int32_t* counter = p.counters + bg * kCounterStride;
     wait_stores_acknowledged();
     __syncthreads();
-    if (tid == 0) sTicket = __hip_atomic_fetch_add(&p.counters[bg], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (tid == 0) sTicket = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     __syncthreads();
     if (sTicket != nchunks - 1) return;
     merge_partials<G, NW>(p, b, g, nchunks, &sO[0][0][0], &sO[0][0][0] + kMergeChunks * G, sMf, sLf);
-    if (tid == 0) __hip_atomic_store(&p.counters[bg], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // next call
+    if (tid == 0) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // next call
 }
 
 // Scores-only pass over the full cache (Section 4.3, "Impact of full attention steps", the
@@ -1099,14 +1297,15 @@ static int launch_finish_pool(const AttnParams& p, int batch, int32_t max_len, c
     return launch_status();
 }
 
-template <int G, bool EMIT, bool TWO_SEG>
+template <int G, bool EMIT, bool TWO_SEG, bool TAGGED>
 static int launch_split_g(const AttnParams& p, int batch, int nchunk_grid, hipStream_t st) {
     dim3 grid(nchunk_grid, p.Hkv, batch);
     // four wavefronts of 32 rows per iteration; with 64-row chunks two of them only help to merge
     const int32_t spec_rows = TWO_SEG ? (p.n_sel < p.cap1 ? p.n_sel : p.cap1) : p.cap2;
-    hipLaunchKernelGGL((attn_split_kernel<G, 4, EMIT, TWO_SEG>), grid, dim3(256), 0, st,
-                       TWO_SEG ? p.k1 : p.k2, TWO_SEG ? p.v1 : p.v2, TWO_SEG ? p.s1_b : p.s2_b,
-                       (int32_t)(TWO_SEG ? p.s1_h : p.s2_h), spec_rows, p.seq_lens, p.tail_start, p.pred, p);
+    const int64_t tail_c = (TWO_SEG && p.tail_wg) ? p.nch : kNoTailWg;
+    hipLaunchKernelGGL((attn_split_kernel<G, 4, EMIT, TWO_SEG, false, TAGGED>), grid, dim3(256), 0, st,
+                       TWO_SEG ? p.k1 : p.k2, TWO_SEG ? p.v1 : p.v2, (TWO_SEG ? p.s1_b : p.s2_b) | (tail_c << 56),
+                       (int32_t)(TWO_SEG ? p.s1_h : p.s2_h), spec_rows, p.seq_lens, p.tail_start, p.pred, p.epochs, p);
     return launch_status();
 }
 
@@ -1114,7 +1313,7 @@ template <int G>
 static int launch_lazy_g(const AttnParams& p, int batch, hipStream_t st) {
     dim3 grid(p.nch, p.Hkv, batch);
     hipLaunchKernelGGL((attn_split_kernel<G, 4, false, true, true>), grid, dim3(256), 0, st,
-                       p.k2, p.v2, p.s2_b, (int32_t)p.s2_h, p.n_sel, p.seq_lens, p.tail_start, p.idx, p);
+                       p.k2, p.v2, p.s2_b | ((int64_t)kNoTailWg << 56), (int32_t)p.s2_h, p.n_sel, p.seq_lens, p.tail_start, p.idx, p.epochs, p);
     return launch_status();
 }
 
@@ -1132,17 +1331,17 @@ static int launch_lazy(const AttnParams& p, int batch, int G, hipStream_t st) {
     }
 }
 
-template <bool EMIT, bool TWO_SEG>
+template <bool EMIT, bool TWO_SEG, bool TAGGED = !EMIT>
 static int launch_split(const AttnParams& p, int batch, int G, int nchunk_grid, hipStream_t st) {
     switch (G) {
-        case 1: return launch_split_g<1, EMIT, TWO_SEG>(p, batch, nchunk_grid, st);
-        case 2: return launch_split_g<2, EMIT, TWO_SEG>(p, batch, nchunk_grid, st);
-        case 3: return launch_split_g<3, EMIT, TWO_SEG>(p, batch, nchunk_grid, st);
-        case 4: return launch_split_g<4, EMIT, TWO_SEG>(p, batch, nchunk_grid, st);
-        case 5: return launch_split_g<5, EMIT, TWO_SEG>(p, batch, nchunk_grid, st);
-        case 6: return launch_split_g<6, EMIT, TWO_SEG>(p, batch, nchunk_grid, st);
-        case 7: return launch_split_g<7, EMIT, TWO_SEG>(p, batch, nchunk_grid, st);
-        case 8: return launch_split_g<8, EMIT, TWO_SEG>(p, batch, nchunk_grid, st);
+        case 1: return launch_split_g<1, EMIT, TWO_SEG, TAGGED>(p, batch, nchunk_grid, st);
+        case 2: return launch_split_g<2, EMIT, TWO_SEG, TAGGED>(p, batch, nchunk_grid, st);
+        case 3: return launch_split_g<3, EMIT, TWO_SEG, TAGGED>(p, batch, nchunk_grid, st);
+        case 4: return launch_split_g<4, EMIT, TWO_SEG, TAGGED>(p, batch, nchunk_grid, st);
+        case 5: return launch_split_g<5, EMIT, TWO_SEG, TAGGED>(p, batch, nchunk_grid, st);
+        case 6: return launch_split_g<6, EMIT, TWO_SEG, TAGGED>(p, batch, nchunk_grid, st);
+        case 7: return launch_split_g<7, EMIT, TWO_SEG, TAGGED>(p, batch, nchunk_grid, st);
+        case 8: return launch_split_g<8, EMIT, TWO_SEG, TAGGED>(p, batch, nchunk_grid, st);
         default: return RK_ERR_UNSUPPORTED;
     }
 }
@@ -1188,6 +1387,7 @@ int full_attn_stage(const rk_geom* geom, const void* q, rk_kv full, const int32_
     p.lse = lse ? lse : ws.lse;
     p.pred = pred; p.pred_val = pred_val;
     p.counters = ws.counters; p.part_ml = ws.part_ml; p.part_o = ws.part_o; p.max_chunks = ws.max_chunks;
+    p.epochs = ws.epochs; p.tag_rows = ws.tag_rows;
     p.ragged_batch = (emit && !no_v) ? ragged_batch_of(geom) : 0;
     if (!emit) {
         // No scores wanted.  Short rows: one launch, merged by the last workgroup inside it (at most
@@ -1348,20 +1548,28 @@ static int launch_partial(const rk_geom* geom, const void* q, rk_kv small, int32
     p.evict = evict ? 1 : 0;
     p.max_rows2 = max_recent;
     p.cap1 = n_sel > 0 ? (int32_t)small.capacity : 0; p.cap2 = (int32_t)full.capacity;
-    p.nch = merged_split_workgroups(n_sel, max_recent, (int64_t)geom->batch * geom->n_kv_heads);
     p.Hq = geom->n_q_heads; p.Hkv = geom->n_kv_heads;
     p.scale = geom->scale;
     p.out = (uint16_t*)out;
     p.lse = ws.lse;
     p.pred = pred; p.pred_val = pred_val;
     p.counters = ws.counters; p.part_ml = ws.part_ml; p.part_o = ws.part_o; p.max_chunks = ws.max_chunks;
-    if (p.nch > p.max_chunks) return RK_ERR_WORKSPACE;
+    p.epochs = ws.epochs; p.tag_rows = ws.tag_rows;
+    // Tagged hand-over where a wavefront merges one head (groups of up to 4); with two heads per
+    // wavefront the ticketed form is the faster one (measured at 7 heads per group, 4096 rows: 9.9 against 10.7 us).
+    const bool tagged = ws.tag_rows != nullptr && G <= kSplitWaves;          // (the built-in scratch array has no tagged region)
+    // a few rows decoded since the refresh: a workgroup of their own (see the kernel), the others split the small cache
+    // (ticketed merge: a 17th partial result costs it a second round trip, more than the tail workgroup gains)
+    p.tail_wg = (tagged && lazy_idx == nullptr && n_sel > 0 && max_recent <= kMinChunk) ? 1 : 0;
+    p.nch = merged_split_workgroups(n_sel, p.tail_wg ? 0 : max_recent, (int64_t)geom->batch * geom->n_kv_heads);
+    if (p.nch > (tagged ? kMergeChunks : p.max_chunks)) return RK_ERR_WORKSPACE;
     if (lazy_idx != nullptr) {      // rows of the selection come from the full cache and are written to `small` on the way
         if (n_sel < 1 || small.capacity < n_sel) return RK_ERR_INVALID_ARG;
         p.idx = lazy_idx; p.idx_stride = n_sel;
         return launch_lazy(p, geom->batch, G, (hipStream_t)stream);
     }
-    const int nchunk_grid = p.nch;
+    const int nchunk_grid = p.nch + p.tail_wg;
+    if (!tagged) return launch_split<false, true, false>(p, geom->batch, G, nchunk_grid, (hipStream_t)stream);
     return launch_split<false, true>(p, geom->batch, G, nchunk_grid, (hipStream_t)stream);
 }
 
@@ -1415,7 +1623,7 @@ extern "C" int rk_partial_attn_fixed(const rk_geom* geom, const void* q, rk_kv s
 // code the array's name is a stand-in, not a device address.
 namespace rk {
 constexpr size_t kStaticScratchBytes = (size_t)RK_STATIC_SCRATCH_BYTES;
-constexpr int kStaticMaxProblems = 4096;          // (sequence, KV head) pairs: one arrival counter each
+constexpr int kStaticMaxProblems = 4096;          // (sequence, KV head) pairs: one arrival counter line each
 constexpr int kStaticMaxDevices = 64;
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
@@ -1439,8 +1647,8 @@ static int static_scratch(hipStream_t stream, unsigned char** out) {
         unsigned char* ptr = nullptr;
         if (hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch)) != hipSuccess || ptr == nullptr) return RK_ERR_HIP;
         if (((uintptr_t)ptr & 255u) != 0) return RK_ERR_HIP;
-        hipLaunchKernelGGL(static_clear_kernel, dim3(kStaticMaxProblems / 256), dim3(256), 0, stream,
-                           (int32_t*)ptr, kStaticMaxProblems);
+        hipLaunchKernelGGL(static_clear_kernel, dim3(kStaticMaxProblems * kCounterStride / 256), dim3(256), 0, stream,
+                           (int32_t*)ptr, kStaticMaxProblems * kCounterStride);
         if (launch_status() != RK_OK) return RK_ERR_HIP;
         g_static_ptr[dev] = ptr;
     }
@@ -1457,7 +1665,7 @@ static size_t carve_static(const rk_geom* g, int32_t n_sel, int32_t max_recent, 
     *w = Workspace{};
     w->max_chunks = merged_split_workgroups(n_sel, max_recent, (int64_t)problems);     // the launch's own count
     size_t off = 0;
-    w->counters = (int32_t*)(base + off); off += (size_t)kStaticMaxProblems * sizeof(int32_t);
+    w->counters = (int32_t*)(base + off); off += (size_t)kStaticMaxProblems * kCounterStride * sizeof(int32_t);
     w->lse = (float*)(base + off);        off += align_up((size_t)g->batch * g->n_q_heads * sizeof(float), 256);
     w->part_ml = (float*)(base + off);    off += align_up(problems * kMaxChunks * G * 2 * sizeof(float), 256);
     w->part_o = (float*)(base + off);     off += align_up(problems * (size_t)w->max_chunks * G * kD * sizeof(float), 256);

@@ -98,22 +98,34 @@ static inline int topk_cand_cap(int64_t k) {
     return (int)c;
 }
 
-// Device workspace, carved in this order (every region 256-byte aligned).  The first three
-// regions must be zero whenever no call is in flight: rk_workspace_init clears them once and
-// the kernels that use them leave them cleared.
-//   counters  int32 [B*Hkv]                  arrival tickets of the split attention kernel
+// Device workspace, carved in this order (every region 256-byte aligned).  The regions up to and
+// including tag_rows must be zero when a workspace is first used (rk_workspace_init clears the
+// whole workspace once); the counters and histograms are left cleared by the kernels that use
+// them, the call numbers and tags only ever grow.  Where these regions lie depends on the
+// geometry alone, never on max_len or max_k.
+//   counters  int32 [B*Hkv][kCounterStride]  arrival tickets of the split attention kernel, one per
+//                                            128-byte line
 //   sel_counters int32 [B*Hkv][2]            listed candidates and arrival tickets of the selection
+//   epochs    uint32 [B*Hkv]                 call number of the last merge inside a split kernel
 //   hist      uint32 [B*Hkv][kHistBins]      first-level histogram of the pooled scores
+//   tag_rows  16 B  [B*Hkv][kTagSlots][G*44]  tagged partial results of the kernels that merge
+//                                            inside the launch (see merge_tagged in rk_attn.hip)
 //   lse       fp32  [B*Hq]                   log-sum-exp when the caller does not ask for it
 //   part_ml   fp32  [B*Hkv][kMaxChunks][G][2] running max and sum of every partial result
 //   part_o    fp32  [B*Hkv][nch][G][128]     unnormalised partial outputs
 //   pooled    fp32  [B*Hkv][max_len up to a multiple of 4]   group-max, pooled scores of the selection
 //   scores    fp32  [B*Hq][max_len up to a multiple of 4]    raw scores between the two kernels of
 //                                                            rk_full_attn_select
+constexpr int kCounterStride = 32;       // int32 between two arrival counters: one 128-byte line each
+constexpr int kTagDataRows = 43;          // a head's 128 output dims as rows of three (the last one holds two) ...
+constexpr int kTagRowsPerHead = kTagDataRows + 1;   // ... plus the row with the chunk's log-sum-exp (see merge_tagged_heads)
+constexpr int kTagSlots = kMergeChunks + 1;   // tagged partial results per (sequence, KV head): the chunks + the tail's own
 struct Workspace {
     int32_t* counters;
     int32_t* sel_counters;
+    uint32_t* epochs;
     uint32_t* hist;
+    uint32_t* tag_rows;
     float* lse;
     float* part_ml;
     float* part_o;
@@ -129,8 +141,13 @@ struct Workspace {
 // Row stride of the pooled-score area: rows are read with 16-byte loads.
 static inline int64_t pooled_row_stride(int64_t max_len) { return (max_len + 3) / 4 * 4; }
 
-static inline size_t zeroed_words(const rk_geom* g) {
-    return (size_t)g->batch * g->n_kv_heads * (3 + (size_t)kHistBins);
+// Bytes of the regions that must be zero at first use (the head of the workspace).
+static inline size_t zero_kept_bytes(const rk_geom* g) {
+    const size_t problems = (size_t)g->batch * g->n_kv_heads;
+    const size_t G = (size_t)(g->n_q_heads / g->n_kv_heads);
+    size_t off = problems * ((size_t)kCounterStride + 2 + 1 + (size_t)kHistBins) * sizeof(int32_t);
+    off = (off + 255) / 256 * 256;
+    return off + problems * kTagSlots * G * kTagRowsPerHead * 16;
 }
 
 static inline int max_chunks_for(int64_t max_len) {
@@ -153,11 +170,12 @@ static inline Workspace carve(const rk_geom* g, int64_t max_len, int64_t max_k, 
     w.max_chunks = max_chunks_for(max_len);
     char* p = (char*)base;
     size_t off = 0;
-    // the zero-kept regions are contiguous (no padding between them)
-    w.counters = (int32_t*)(p + off); off += problems * sizeof(int32_t);
+    w.counters = (int32_t*)(p + off); off += problems * kCounterStride * sizeof(int32_t);
     w.sel_counters = (int32_t*)(p + off); off += 2 * problems * sizeof(int32_t);
+    w.epochs = (uint32_t*)(p + off);  off += problems * sizeof(uint32_t);
     w.hist = (uint32_t*)(p + off);    off += problems * kHistBins * sizeof(uint32_t);
     off = align_up(off, 256);
+    w.tag_rows = (uint32_t*)(p + off); off += problems * kTagSlots * G * kTagRowsPerHead * 16;
     w.lse = (float*)(p + off);        off += align_up((size_t)g->batch * g->n_q_heads * sizeof(float), 256);
     w.part_ml = (float*)(p + off);    off += align_up(problems * kMaxChunks * G * 2 * sizeof(float), 256);
     w.part_o = (float*)(p + off);     off += align_up(problems * w.max_chunks * G * kD * sizeof(float), 256);
@@ -187,6 +205,7 @@ static inline int check_kv(const rk_kv& c, bool need_v = true) {
     // row indices are int32 and the kernels step past the end by up to kMaxChunks * kMinChunk rows
     if (c.stride_b < 0 || c.stride_h < 0 || c.capacity <= 0 || c.capacity > INT32_MAX - 2 * kMaxChunks * kMinChunk) return RK_ERR_INVALID_ARG;
     if (c.stride_b % 8 != 0 || c.stride_h % 8 != 0) return RK_ERR_INVALID_ARG;
+    if (c.stride_b >= (1ll << 56)) return RK_ERR_UNSUPPORTED;   // the top byte of the sequence stride travels as a flag to the kernels
     if (c.stride_h > INT32_MAX) return RK_ERR_UNSUPPORTED;      // the head stride travels as 32 bits to the kernels
     return RK_OK;
 }

@@ -2,7 +2,8 @@
 
 Its scratch is a device array built into the library, so consecutive calls share memory whatever
 their shapes: two calls in a row, the second with a smaller input, each compared with
-rk_partial_attn on a caller's workspace (same kernels: equal bit for bit) and with the oracle.
+rk_partial_attn on a caller's workspace (same kernels, another hand-over between the workgroups:
+equal to within the bar the outputs are held to) and with the oracle.
 """
 import ctypes as C
 import sys
@@ -81,8 +82,9 @@ def run_both(rk, c, what):
                              None, 0, ws.ptr, ws.nbytes, stream)
     assert rc == 0, rk.status_string(rc)
     torch.cuda.synchronize()
-    assert torch.equal(out_st, out_ws), what + ": static scratch and workspace disagree"
-    assert_out_close(gen.bf16_bits(out_st), c["o_ref"], what)
+    assert_out_close(gen.bf16_bits(out_st), gen.bf16_bits(out_ws), what + ": static scratch against workspace")
+    assert_out_close(gen.bf16_bits(out_st), c["o_ref"], what + ": static scratch against the oracle")
+    assert_out_close(gen.bf16_bits(out_ws), c["o_ref"], what + ": workspace against the oracle")
 
 
 def test_static_entry_two_calls_second_smaller(rk):

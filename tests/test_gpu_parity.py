@@ -690,13 +690,18 @@ def check_loop(rk, w: gen.Workload, evict_lowest=False, scores_only=False):
     return got, ref, n_diff
 
 
-def check_model_loop(rk, w: gen.Workload, n_layers: int, evict_lowest=False, scores_only=False, overlap=False):
-    """The same schedule through rk_decode_step: all layers of a step in one call."""
+def check_model_loop(rk, w: gen.Workload, n_layers: int, evict_lowest=False, scores_only=False, overlap=False,
+                     gen_device="cpu"):
+    """The same schedule through rk_decode_step: all layers of a step in one call.  gen_device="cuda":
+    the caches are drawn on the GPU (large workloads) and copied to the host for the oracle."""
     dev = "cuda"
     geom = rk.Geom(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.scale)
     lens0 = gen.seq_lens(w)
-    data = [(gen.make_kv(w, l), gen.make_queries(w, l), gen.make_new_rows(w, l)) for l in range(n_layers)]
-    kv = [(d[0][0].to(dev).clone(), d[0][1].to(dev).clone()) for d in data]
+    data, kv = [], []
+    for l in range(n_layers):
+        Kg, Vg = gen.make_kv(w, l, device=gen_device)
+        data.append(((Kg.cpu(), Vg.cpu()) if gen_device != "cpu" else (Kg, Vg), gen.make_queries(w, l), gen.make_new_rows(w, l)))
+        kv.append((Kg.to(dev).clone(), Vg.to(dev).clone()) if gen_device == "cpu" else (Kg, Vg))
     sl = lens0.to(dev).clone()
     model = rk.RefreshKVModel(geom, kv, sl, int(lens0.max()), w.k_small, w.stride, pool_w=w.pool_w, dynamic=w.dynamic,
                               threshold=w.threshold, evict_lowest=evict_lowest, scores_only_refresh=scores_only)
@@ -1171,8 +1176,10 @@ FULL_SIZE = ["cfg2_llama_32k", "cfg3_qwen_64k_dynamic", "cfg5_llama_128k"]
 
 @pytest.mark.parametrize("name", FULL_SIZE)
 def test_full_size_one_layer_refresh_and_partial(rk, name):
-    """One layer at the benchmark's real shape, in the launch configuration bench.py times:
-    full step + selection + gather + a partial step 3 tokens later, all against the oracle."""
+    """One layer at the workload's real shape through the per-layer calls (rk_full_attn_select, gather,
+    rk_partial_attn): full step + selection + gather + partial steps up to 3 tokens later, all against
+    the oracle.  (The driver bench.py times, with the refresh batched over the layers, is covered at these
+    shapes by test_full_size_whole_stride_through_the_timed_driver.)"""
     w = gen.shrink(gen.WORKLOADS[name], n_layers=1, n_steps=3, stride=100, dynamic=False)
     say("full size", w.name, "L", w.context, "K", w.k_small)
     K, V = gen.make_kv(w, 0, device="cuda")
@@ -1204,6 +1211,38 @@ def test_full_size_model_batched_refresh(rk):
     say("full size, batched driver", w.name, "context", w.context, "K", w.k_small)
     kinds, n_full, _ = check_model_loop(rk, w, 8, overlap="batched")
     assert kinds == ["full", "partial", "full", "partial"] and (n_full == 2).all()
+
+
+WHOLE_STRIDE = [
+    # workload, layers, steps: one whole stride period and the refresh that ends it (+ one partial step after)
+    ("cfg2_llama_32k", 8, 11),                 # full at t = 0 and 10 (at 32778 rows); partial steps with 1..9 recent rows
+    ("cfg5_llama_128k", 8, 17),                # full at t = 0 and 16; 64 rows of 128k in the batched selection
+    ("cfg4_llama_batch16_ragged", 4, 9),       # full at t = 0 and 8; 16 ragged sequences
+    ("cfg3_qwen_64k_dynamic", 3, 16),          # trigger tested at t = 5, 10, 15: fires for some layers, not for others
+]
+
+
+@pytest.mark.parametrize("case", WHOLE_STRIDE, ids=[c[0] for c in WHOLE_STRIDE])
+def test_full_size_whole_stride_through_the_timed_driver(rk, case):
+    """Every workload bench.py can time, at its real shape, through the driver it times
+    (rk_decode_step_batched: rk_full_attn_deferred per layer, then pooling, selection and gather of all
+    layers in one launch each; on the trigger's test steps both branches under the device predicate):
+    every step's output and every snapshot of the selection against the oracle's decode loop."""
+    name, n_layers, n_steps = case
+    w = gen.shrink(gen.WORKLOADS[name], n_steps=n_steps)
+    say("whole stride at full size:", name, "layers", n_layers, "steps", n_steps, "context", w.context, "K", w.k_small)
+    kinds, n_full, refs = check_model_loop(rk, w, n_layers, overlap="batched", gen_device="cuda")
+    S = w.stride
+    if w.dynamic:
+        assert kinds == ["full"] + ["both" if t % S == 0 else "partial" for t in range(1, n_steps + 1)]
+        fired = np.stack([r["full"][S::S, 0] for r in refs])            # [layer, test step]
+        say("  trigger decisions per layer at the test steps:", fired.astype(int).tolist())
+        assert fired.any() and not fired.all(), "the case must hold a test step that refreshes and one that does not"
+        # a partial step that follows a fired refresh of its layer, and one that follows a declined one, both ran
+        assert any(fired[l, i] and (i + 1) * S < n_steps for l in range(n_layers) for i in range(fired.shape[1]))
+    else:
+        assert kinds == ["full" if t % S == 0 else "partial" for t in range(n_steps + 1)]
+        assert (n_full == 1 + n_steps // S).all()
 
 
 def test_batched_refresh_large_k(rk):

@@ -8,11 +8,17 @@ resident in HBM; the rows that later steps "append" are pre-written, so a step o
 seq_lens (the append itself is the caller's 4 KB copy, outside this library).
 
 Prints ONE JSON line (see the keys below).  Beside the headline it carries
-  roofline      achieved HBM GB/s of the dominant HBM-bound kernel (the split full-attention
-                kernel) = algorithmic bytes per launch / its average duration, measured here
-                with HIP events on the launch stream around back-to-back launches of that
-                kernel alone (rk_full_attn_scores), one per layer;
-  cpu_baseline  the CPU oracle timed on this machine's host cores on a bounded sample.
+  roofline          achieved HBM GB/s of the dominant HBM-bound kernel (the split full-attention
+                    kernel) = algorithmic bytes per launch / its average duration, measured here
+                    with HIP events on the launch stream around back-to-back launches of that
+                    kernel alone (rk_full_attn_scores), one per layer;
+  roofline_partial  the same for the kernel of the partial step, which most of `value` is made of;
+  copy_GBps         what a plain copy kernel of known size reaches in the same run (read + written
+                    bytes per second): the yardstick beside the 8 TB/s peak;
+  other_workloads   the other single-GPU workloads of the benchmark spec at their own layer counts, a
+                    few steps each (value, roofline fraction of the first kernel of a full step,
+                    full / partial ratio);
+  cpu_baseline      the CPU oracle timed on this machine's host cores on a bounded sample.
 """
 from __future__ import annotations
 
@@ -52,6 +58,8 @@ def parse():
                     help="steps that may still be pending when a two-stream (full) step is submitted (-1: no limit)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=4, help="layers of the oracle sample")
+    ap.add_argument("--no-other-workloads", action="store_true",
+                    help="skip the short runs of the other workloads that the default invocation appends")
     return ap.parse_args()
 
 
@@ -66,22 +74,67 @@ def cost_model(w, lens0, eff_stride, achieved_gbps, measured_us):
             "measured_us": round(measured_us, 2)}
 
 
+def profile_traffic(w_name, key):
+    """HBM bytes per launch of a kernel from the committed profiler summary of this workload (None if
+    there is none), and where the figure comes from: it is a measurement of the commit named there,
+    not of this run."""
+    path = os.path.join(ROOT, "profiles", "bench_%s_pmc.json" % w_name)
+    if not os.path.exists(path):
+        return None, None
+    with open(path) as f:
+        pmc = json.load(f)
+    if key not in pmc:
+        return None, None
+    k = pmc[key]
+    traffic = int(k["fetch_kib"] * 1024 * pmc["fetch_scale"] + k["write_kib"] * 1024 * pmc["write_scale"])
+    return traffic, {"file": "profiles/bench_%s_pmc.json" % w_name, "commit": pmc.get("commit"), "layers": pmc.get("layers")}
+
+
 def main():
     args = parse()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the path has no multi-GPU part); got --gpus %d" % args.gpus,
               file=sys.stderr)
         sys.exit(2)
+    import torch
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    result = run_workload(args, args.workload, light=False)
+    if args.workload == "cfg2_llama_32k" and not args.no_other_workloads and not args.layers:
+        import copy
+        import gc
+        import gen
+        others = {}
+        for name in ("cfg3_qwen_64k_dynamic", "cfg4_llama_batch16_ragged", "cfg5_llama_128k"):
+            a = copy.copy(args)
+            a.no_cpu_baseline = True
+            a.steps, a.warmup = 4 * max(gen.WORKLOADS[name].stride, 1), max(gen.WORKLOADS[name].stride, 1)
+            if gen.WORKLOADS[name].dynamic:
+                a.steps, a.warmup = 60, 20          # long enough for the trigger to have fired in every layer
+            gc.collect(); torch.cuda.empty_cache()      # the previous workload's caches go before the next is set up
+            r = run_workload(a, name, light=True)
+            others[name] = {"value": r["value"], "unit": r["unit"], "layers": r["config"]["layers"], "steps": a.steps,
+                            "step_us_per_layer": r["step_us_per_layer"], "effective_stride": r["effective_stride"],
+                            "full_attn_us": r["call_us_per_layer"]["full_attn"],
+                            "partial_attn_us": r["call_us_per_layer"]["partial_attn"],
+                            "full_over_partial": r["full_over_partial"],
+                            "roofline_frac": r["roofline"]["frac"], "roofline_avg_launch_us": r["roofline"]["avg_launch_us"],
+                            "roofline_traffic": r["roofline"]["traffic"], "traffic_source": r["roofline"]["traffic_source"],
+                            "roofline_partial_frac": r["roofline_partial"]["frac"]}
+        result["other_workloads"] = others
+    print(json.dumps(result))
 
+
+def run_workload(args, workload, light):
+    """One workload: the timed steps, the per-kind and per-call figures, the two roofline blocks.
+    light: only what `other_workloads` reports (no comparison policies, no CPU oracle)."""
     import numpy as np
     import torch
     import gen
     import paper_2411_05787_amd as rk
 
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    torch.cuda.set_device(0)
     dev = "cuda"
-    w = gen.WORKLOADS[args.workload]
+    w = gen.WORKLOADS[workload]
     n_layers = args.layers or w.n_layers
     # after the timed steps, a few more with an event pair around each give the per-kind figures: the
     # events cost about 4 us each on the stream, so the timed region itself carries none
@@ -158,8 +211,8 @@ def main():
             kind = lay.step(t, q_cur[l])
         return kind
 
-    def is_full(t):
-        return t == 0 or (w.stride > 0 and t % w.stride == 0)
+    def is_full(t):       # a step at which every layer takes a full step by schedule (the trigger's test steps are "both")
+        return t == 0 or (w.stride > 0 and t % w.stride == 0 and not w.dynamic)
 
     # t = 0: prefill-equivalent initialisation (full step everywhere), eager
     q_cur.copy_(q_steps[0])
@@ -185,9 +238,10 @@ def main():
         torch.cuda.synchronize()
 
     def run_step(t: int):
-        kind = "full" if is_full(t) else ("both" if (w.dynamic and t % w.stride == 0) else "partial")
+        kind = "both" if (w.dynamic and t >= 1 and w.stride > 0 and t % w.stride == 0) else ("full" if is_full(t) else "partial")
         if model is not None:                  # pointers to the step's queries: no copy into a static buffer
-            enqueue_step(t, q_steps[t])
+            reported = enqueue_step(t, q_steps[t])
+            assert reported == kind, (t, reported, kind)      # what the driver says it enqueued
             return kind
         q_cur.copy_(q_steps[t], non_blocking=True)
         if graphs and kind in graphs:
@@ -255,49 +309,54 @@ def main():
 
     out = layers[0].out
     Lb = max_len_bound
-    gw = torch.Generator(device="cuda").manual_seed(4242)
-    q_win = torch.randn(w.batch, 32, w.n_q_heads, w.head_dim, generator=gw, device="cuda").to(torch.bfloat16)
-    q_win1 = q_win[:, -1:].contiguous()
-    # the H2O comparison policy at the same budget K (K/2 recent): one state per layer, caches full
-    h2o_cap = w.k_small + 1
-    h2o = []
-    for l in range(n_layers):
-        cK = torch.randn(B, Hkv, h2o_cap, D, generator=gw, device="cuda").to(torch.bfloat16)
-        cV = torch.randn(B, Hkv, h2o_cap, D, generator=gw, device="cuda").to(torch.bfloat16)
-        tot = torch.rand(B, Hkv, h2o_cap, generator=gw, device="cuda")
-        hpos = torch.arange(h2o_cap, dtype=torch.int32, device="cuda").expand(B, Hkv, h2o_cap).contiguous()
-        n_rows = torch.full((B,), w.k_small, dtype=torch.int32, device="cuda")
-        keep = (cK, cV, tot, hpos, n_rows, torch.zeros(B, dtype=torch.int32, device="cuda"))
-        h2o.append((rk.h2o_state(geom, *keep), keep))
-    h2o_lens = torch.full((B,), h2o_cap, dtype=torch.int32, device="cuda")
-    h2o_new = torch.randn(2, B, Hkv, D, generator=gw, device="cuda").to(torch.bfloat16)
-
-    def h2o_call(l):
-        if l == 0:
-            h2o_lens.add_(1)                  # one decoding step further: a new position for the new token
-        rk.rk_h2o_step(geom, h2o[l][0], q_cur[l], h2o_new[0], h2o_new[1], h2o_lens, w.k_small, w.k_small // 2, out,
-                       workspace=ws)
-
+    partial_call = lambda l: rk.rk_partial_attn(geom, q_cur[l], layers[l].small_K, layers[l].small_V, w.k_small, *kv[l],
+                                                layers[l].tail_start, seq_lens, max(w.stride, 1), out, workspace=ws)
     klass = {
-        "full_attn_no_weights": graph_us(lambda l: rk.rk_full_attn(geom, q_cur[l], *kv[l], seq_lens, Lb, out, workspace=ws)),
-        "h2o_step": graph_us(h2o_call),
         "full_attn": graph_us(lambda l: rk.rk_full_attn(geom, q_cur[l], *kv[l], seq_lens, Lb, out, weights=weights, workspace=ws)),
-        "full_attn_select": graph_us(lambda l: rk.rk_full_attn_select(geom, q_cur[l], *kv[l], seq_lens, Lb, out, w.k_small, w.pool_w,
-                                                                       layers[l].idx, workspace=ws)),
-        "score_select": graph_us(lambda l: rk.rk_score_select(geom, q_cur[l], kv[l][0], seq_lens, Lb, w.k_small, w.pool_w,
-                                                               layers[l].idx, workspace=ws)),
-        # prefill-side initialisation from an observation window of 1 and of 32 prompt tokens (the queries
-        # are synthetic; the window ends at the current length)
-        "window_select_w1": graph_us(lambda l: rk.rk_window_select(geom, q_win1, kv[l][0], seq_lens, Lb, w.k_small, w.pool_w,
-                                                                   layers[l].idx, workspace=ws)),
-        "window_select_w32": graph_us(lambda l: rk.rk_window_select(geom, q_win, kv[l][0], seq_lens, Lb, w.k_small, w.pool_w,
-                                                                    layers[l].idx, workspace=ws)),
-        "topk_select": graph_us(lambda l: rk.rk_topk_select(geom, weights, seq_lens, Lb, w.k_small, w.pool_w, layers[l].idx, workspace=ws)),
-        "gather_small_kv": graph_us(lambda l: rk.rk_gather_small_kv(geom, *kv[l], layers[l].idx, w.k_small, layers[l].small_K, layers[l].small_V)),
-        "partial_attn": graph_us(lambda l: rk.rk_partial_attn(geom, q_cur[l], layers[l].small_K, layers[l].small_V, w.k_small, *kv[l],
-                                                               layers[l].tail_start, seq_lens, max(w.stride, 1), out, workspace=ws)),
-        "query_sim": graph_us(lambda l: rk.rk_query_sim(geom, q_cur[l], layers[l].q_ref, w.threshold, False, layers[l].sim, layers[l].need_full)),
+        "partial_attn": graph_us(partial_call),
     }
+    if not light:
+        gw = torch.Generator(device="cuda").manual_seed(4242)
+        q_win = torch.randn(w.batch, 32, w.n_q_heads, w.head_dim, generator=gw, device="cuda").to(torch.bfloat16)
+        q_win1 = q_win[:, -1:].contiguous()
+        # the H2O comparison policy at the same budget K (K/2 recent): one state per layer, caches full
+        h2o_cap = w.k_small + 1
+        h2o = []
+        for l in range(n_layers):
+            cK = torch.randn(B, Hkv, h2o_cap, D, generator=gw, device="cuda").to(torch.bfloat16)
+            cV = torch.randn(B, Hkv, h2o_cap, D, generator=gw, device="cuda").to(torch.bfloat16)
+            tot = torch.rand(B, Hkv, h2o_cap, generator=gw, device="cuda")
+            hpos = torch.arange(h2o_cap, dtype=torch.int32, device="cuda").expand(B, Hkv, h2o_cap).contiguous()
+            n_rows = torch.full((B,), w.k_small, dtype=torch.int32, device="cuda")
+            keep = (cK, cV, tot, hpos, n_rows, torch.zeros(B, dtype=torch.int32, device="cuda"))
+            h2o.append((rk.h2o_state(geom, *keep), keep))
+        h2o_lens = torch.full((B,), h2o_cap, dtype=torch.int32, device="cuda")
+        h2o_new = torch.randn(2, B, Hkv, D, generator=gw, device="cuda").to(torch.bfloat16)
+
+        def h2o_call(l):
+            if l == 0:
+                h2o_lens.add_(1)                  # one decoding step further: a new position for the new token
+            rk.rk_h2o_step(geom, h2o[l][0], q_cur[l], h2o_new[0], h2o_new[1], h2o_lens, w.k_small, w.k_small // 2, out,
+                           workspace=ws)
+
+        klass.update({
+            "full_attn_no_weights": graph_us(lambda l: rk.rk_full_attn(geom, q_cur[l], *kv[l], seq_lens, Lb, out, workspace=ws)),
+            "h2o_step": graph_us(h2o_call),
+            "full_attn_select": graph_us(lambda l: rk.rk_full_attn_select(geom, q_cur[l], *kv[l], seq_lens, Lb, out, w.k_small, w.pool_w,
+                                                                           layers[l].idx, workspace=ws)),
+            "score_select": graph_us(lambda l: rk.rk_score_select(geom, q_cur[l], kv[l][0], seq_lens, Lb, w.k_small, w.pool_w,
+                                                                   layers[l].idx, workspace=ws)),
+            # prefill-side initialisation from an observation window of 1 and of 32 prompt tokens (the queries
+            # are synthetic; the window ends at the current length)
+            "window_select_w1": graph_us(lambda l: rk.rk_window_select(geom, q_win1, kv[l][0], seq_lens, Lb, w.k_small, w.pool_w,
+                                                                       layers[l].idx, workspace=ws)),
+            "window_select_w32": graph_us(lambda l: rk.rk_window_select(geom, q_win, kv[l][0], seq_lens, Lb, w.k_small, w.pool_w,
+                                                                        layers[l].idx, workspace=ws)),
+            "topk_select": graph_us(lambda l: rk.rk_topk_select(geom, weights, seq_lens, Lb, w.k_small, w.pool_w, layers[l].idx, workspace=ws)),
+            "gather_small_kv": graph_us(lambda l: rk.rk_gather_small_kv(geom, *kv[l], layers[l].idx, w.k_small, layers[l].small_K, layers[l].small_V)),
+            "query_sim": graph_us(lambda l: rk.rk_query_sim(geom, q_cur[l], layers[l].q_ref, w.threshold, False, layers[l].sim, layers[l].need_full)),
+        })
+        del h2o
 
     # ---- roofline of the split full-attention kernel ----
     # rk_full_attn_scores launches that kernel alone.  One launch per layer (round-robin, so the
@@ -325,11 +384,23 @@ def main():
         per_replay.append(ea.elapsed_time(eb) * 1e3 / n_layers)
     split_us = float(np.mean(per_replay))
     n_roof_launches = roof_reps * n_layers
-    # one plain copy of known size: the kernel against which profiler byte counters are scaled
+    # one plain copy of known size: the kernel against which profiler byte counters are scaled, and, timed, what a
+    # copy reaches on this machine in this run (bytes read + bytes written per second)
     cal_src = kv[0][0].view(-1)                          # K of layer 0: B * Hkv * capacity * 256 bytes
     cal_dst = torch.empty_like(cal_src)
     calibration_bytes = rk.rk_calibration_copy(cal_dst, cal_src)
     torch.cuda.synchronize()
+    g_copy = torch.cuda.CUDAGraph()                      # other layers' rows as sources: nothing of them is in a cache
+    n_copies = min(n_layers, 4)
+    with torch.cuda.graph(g_copy):
+        for l in range(n_copies):
+            rk.rk_calibration_copy(cal_dst, kv[l][0].view(-1))
+    g_copy.replay(); torch.cuda.synchronize()
+    copy_us = []
+    for _ in range(4):
+        ea.record(); g_copy.replay(); eb.record(); torch.cuda.synchronize()
+        copy_us.append(ea.elapsed_time(eb) * 1e3 / n_copies)
+    copy_gbps = round(2 * calibration_bytes / (float(np.median(copy_us)) * 1e-6) / 1e9, 1)
     del cal_dst
     rows = int(seq_lens.sum().item())                    # rows streamed per launch (all sequences)
     bytes_kv = 2 * Hkv * D * 2 * rows                    # K and V rows, bf16
@@ -337,21 +408,28 @@ def main():
     algo_bytes = bytes_kv + bytes_w
     achieved = algo_bytes / (split_us * 1e-6) / 1e9
     # HBM traffic of that kernel from profiler byte counters, when a committed PMC summary exists
-    traffic = None
-    pmc_path = os.path.join(ROOT, "profiles", "bench_%s_pmc.json" % w.name)
-    if os.path.exists(pmc_path):
-        with open(pmc_path) as f:
-            pmc = json.load(f)
-        k = pmc["attn_split"]
-        traffic = int(k["fetch_kib"] * 1024 * pmc["fetch_scale"] + k["write_kib"] * 1024 * pmc["write_scale"])
-    roofline = {"bound": "hbm", "kernel": "rk::attn_split_kernel<%d, 4, true, false, false> (first kernel of rk_full_attn when weights are returned)" % w.group,
+    traffic, traffic_source = profile_traffic(w.name, "attn_split")
+    roofline = {"bound": "hbm", "kernel": "rk::attn_split_kernel<%d, 4, true, false, false, false> (first kernel of rk_full_attn when weights are returned)" % w.group,
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic, "traffic_source": traffic_source,
                 "avg_launch_us": round(split_us, 2), "launches": n_roof_launches, "algorithmic_bytes": algo_bytes}
+    # ---- the same for the kernel of the partial step (one launch: rk_partial_attn) ----
+    # rows it reads: the K selected rows and the rows decoded since the refresh, per sequence
+    recent_rows = int((seq_lens - layers[0].tail_start).clamp(min=0, max=max(w.stride, 1)).sum().item())   # (max_recent of the call)
+    sel_rows = int(torch.minimum(layers[0].tail_start, torch.full_like(seq_lens, w.k_small)).sum().item())
+    partial_bytes = 2 * Hkv * D * 2 * (sel_rows + recent_rows)
+    partial_us = graph_us(partial_call, reps=8)
+    p_traffic, p_source = profile_traffic(w.name, "partial_attn")
+    roofline_partial = {"bound": "hbm", "kernel": "rk::attn_split_kernel<%d, 4, false, true, false, %s> (rk_partial_attn)" % (w.group, "true" if w.group <= 4 else "false"),
+                        "achieved": round(partial_bytes / (partial_us * 1e-6) / 1e9, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                        "frac": round(partial_bytes / (partial_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
+                        "traffic": p_traffic, "traffic_source": p_source, "avg_launch_us": round(partial_us, 2),
+                        "launches": 9 * n_layers, "algorithmic_bytes": partial_bytes,
+                        "rows": {"selected": sel_rows, "decoded_since_refresh": recent_rows}}
 
     # ---- CPU oracle on a bounded sample of the same workload ----
     cpu = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and not light:
         import oracle
         try:
             from threadpoolctl import threadpool_info
@@ -395,6 +473,7 @@ def main():
                       "max": round(float(per_layer.max()), 2), "qc_stride": w.stride, "threshold": w.threshold}
     us_per_step_layer = ms_per_step * 1e3 / n_layers
     n_full = sum(k == "full" for k in kinds)
+    n_both = sum(k == "both" for k in kinds)
     result = {
         "metric": "decode attention us/step/layer (full vs partial) + achieved HBM GB/s vs peak",
         "value": round(us_per_step_layer, 3), "unit": "us/step/layer",
@@ -403,7 +482,7 @@ def main():
         "config": {"workload": w.name, "layers": n_layers, "batch": B, "n_q_heads": Hq, "n_kv_heads": Hkv,
                    "head_dim": D, "context": L0, "k_small": w.k_small, "stride": w.stride, "pool_w": w.pool_w,
                    "schedule": "dynamic" if w.dynamic else "fixed", "full_steps": n_full,
-                   "partial_steps": args.steps - n_full, "launch": {"graph": "hip_graph", "native": "rk_decode_step_batched" if args.refresh == "batched" and not args.no_overlap else "rk_decode_step", "eager": "eager",
+                   "partial_steps": args.steps - n_full - n_both, "trigger_test_steps": n_both, "launch": {"graph": "hip_graph", "native": "rk_decode_step_batched" if args.refresh == "batched" and not args.no_overlap else "rk_decode_step", "eager": "eager",
                                                                       "hybrid": "rk_decode_step (partial steps) + hip_graph (full steps)"}[launch],
                    "refresh": ("serial per layer" if args.no_overlap else
                                "batched over the layers (rk_refresh_batched)" if args.refresh == "batched" else
@@ -414,9 +493,9 @@ def main():
         # attention time per (step, layer) of the paper's comparison systems at kernel level (Table 1, "Time"):
         # vanilla = full attention at every step; StreamingLLM and SnapKV = the partial step at every step;
         # H2O = attention over K + 1 rows with the scores returned + its bookkeeping; RefreshKV = `value`
-        "policy_us_per_layer": {"vanilla": round(klass["full_attn_no_weights"], 2),
-                                "streaming_llm_or_snapkv": round(klass["partial_attn"], 2),
-                                "h2o": round(klass["h2o_step"], 2), "refreshkv": round(us_per_step_layer, 2)},
+        "policy_us_per_layer": None if light else {"vanilla": round(klass["full_attn_no_weights"], 2),
+                                                   "streaming_llm_or_snapkv": round(klass["partial_attn"], 2),
+                                                   "h2o": round(klass["h2o_step"], 2), "refreshkv": round(us_per_step_layer, 2)},
         "full_over_partial": round(klass["full_attn"] / klass["partial_attn"], 2),
         "full_attn_GBps": round((bytes_kv + bytes_w) / (klass["full_attn"] * 1e-6) / 1e9, 1),
         "partial_attn_GBps": round(2 * Hkv * D * 2 * (w.k_small + 1) * B / (klass["partial_attn"] * 1e-6) / 1e9, 1),
@@ -426,11 +505,13 @@ def main():
         # take at the rate the first kernel of a full step reaches and what a step takes
         "cost_model": cost_model(w, lens0, eff_stride, roofline["achieved"], us_per_step_layer),
         "roofline": roofline,
+        "roofline_partial": roofline_partial,
+        "copy_GBps": copy_gbps,
         "cpu_baseline": cpu,
         "calibration_copy_bytes": calibration_bytes,
         "setup_s": round(setup_s, 1),
     }
-    print(json.dumps(result))
+    return result
 
 
 if __name__ == "__main__":

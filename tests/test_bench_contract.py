@@ -29,13 +29,16 @@ def test_bench_json_line_small_workload(launch):
     assert len(lines) == 1
     d = json.loads(lines[0])
     for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
-                "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline"):
+                "vs_baseline", "dtype", "data", "config", "roofline", "roofline_partial", "copy_GBps", "cpu_baseline"):
         assert key in d, key
     assert d["n_gpus"] == 1 and d["steps"] == 12 and d["warmup"] == 2 and d["higher_is_better"] is False
     assert d["config"]["workload"] == "cfg1_llama_2k" and d["value"] > 0
-    for key in ("bound", "achieved", "peak", "unit", "frac", "traffic"):
-        assert key in d["roofline"], key
-    assert d["roofline"]["bound"] == "hbm" and 0 < d["roofline"]["frac"] < 1
+    for block in ("roofline", "roofline_partial"):
+        for key in ("bound", "kernel", "achieved", "peak", "unit", "frac", "traffic", "traffic_source", "avg_launch_us",
+                    "algorithmic_bytes"):
+            assert key in d[block], (block, key)
+        assert d[block]["bound"] == "hbm" and 0 < d[block]["frac"] < 1
+    assert d["copy_GBps"] > 0
     for key in ("value", "unit", "cores", "kind", "sample"):
         assert key in d["cpu_baseline"], key
     assert d["cpu_baseline"]["kind"] == "oracle" and d["cpu_baseline"]["value"] > 0

@@ -1562,7 +1562,8 @@ static int launch_partial(const rk_geom* geom, const void* q, rk_kv small, int32
     // (ticketed merge: a 17th partial result costs it a second round trip, more than the tail workgroup gains)
     p.tail_wg = (tagged && lazy_idx == nullptr && n_sel > 0 && max_recent <= kMinChunk) ? 1 : 0;
     p.nch = merged_split_workgroups(n_sel, p.tail_wg ? 0 : max_recent, (int64_t)geom->batch * geom->n_kv_heads);
-    if (p.nch > (tagged ? kMergeChunks : p.max_chunks)) return RK_ERR_WORKSPACE;
+    if (!tagged && p.nch > p.max_chunks) p.nch = p.max_chunks;      // fewer, longer chunks: what the workspace has slots for
+    if (p.nch > kMergeChunks || p.nch < 1) return RK_ERR_WORKSPACE;
     if (lazy_idx != nullptr) {      // rows of the selection come from the full cache and are written to `small` on the way
         if (n_sel < 1 || small.capacity < n_sel) return RK_ERR_INVALID_ARG;
         p.idx = lazy_idx; p.idx_stride = n_sel;
@@ -1580,8 +1581,18 @@ static int partial_attn_impl(const rk_geom* geom, const void* q, rk_kv small, in
                              void* workspace, size_t workspace_bytes, void* stream, const int32_t* lazy_idx = nullptr) {
     int rc = check_partial_args(geom, q, small, n_sel, full, tail_start, seq_lens, max_recent, out);
     if (rc != RK_OK) return rc;
-    Workspace ws;
-    if ((rc = check_workspace(geom, n_sel + max_recent, 0, workspace, workspace_bytes, &ws)) != RK_OK) return rc;
+    // What the step uses of the workspace lies at offsets that follow from the geometry alone; only the
+    // partial outputs of the ticketed form grow with the launch (one slot per workgroup of a (sequence,
+    // KV head), at most kMergeChunks): a bound on the rows decoded since the refresh that keeps growing
+    // (the trigger's schedule) never outgrows a workspace sized for the context.
+    if (!workspace || ((uintptr_t)workspace & 255u) != 0) return RK_ERR_WORKSPACE;
+    Workspace ws = carve(geom, 1, 0, workspace);
+    const size_t problems = (size_t)geom->batch * geom->n_kv_heads;
+    const size_t before = (size_t)((char*)ws.part_o - (char*)workspace);
+    const size_t slot = problems * (geom->n_q_heads / geom->n_kv_heads) * kD * sizeof(float);     // one partial output of every (sequence, KV head)
+    if (workspace_bytes < before + slot) return RK_ERR_WORKSPACE;
+    const size_t slots = (workspace_bytes - before) / slot;
+    ws.max_chunks = slots < (size_t)kMergeChunks ? (int)slots : kMergeChunks;     // the launch takes no more workgroups than this
     return launch_partial(geom, q, small, n_sel, evict, full, tail_start, seq_lens, max_recent, out, pred, pred_val,
                           ws, stream, lazy_idx);
 }

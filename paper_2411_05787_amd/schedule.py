@@ -76,6 +76,15 @@ class RefreshKVLayer:
             self.max_len += 1
             self.recent_bound += 1
 
+    def tighten_recent_bound(self) -> int:
+        """Re-reads the host bound of the rows decoded since the refresh from the GPU (max over the
+        sequences of seq_lens - tail_start).  Under the trigger's schedule the host never learns of a
+        refresh, so the bound only grows; results do not depend on it, launch shapes do.  Synchronises
+        with the stream: for an occasional step."""
+        if not self._static:
+            self.recent_bound = max(int((self.seq_lens - self.tail_start).max().item()), 0)
+        return self.recent_bound
+
     def _full(self, q, out, pred=None, stream=None) -> None:
         g = self.geom
         if self.scores_only_refresh:
@@ -223,6 +232,17 @@ class RefreshKVModel:
                 raise ValueError("KV cache capacity exceeded")
             self.max_len += 1
             self.recent_bound += 1
+
+    def tighten_recent_bound(self) -> int:
+        """Re-reads the host bound of the rows decoded since a refresh from the GPU: max over layers and
+        sequences of seq_lens - tail_start.  With the trigger's schedule the host never learns of a
+        refresh (the decision stays on the GPU), so its bound grows by one per step; the results do not
+        depend on it (the kernels clamp on the device-side lengths) but launch shapes do.  This call
+        synchronises with the stream: meant for an occasional step, not for every one."""
+        if not self._static:
+            r = int((self.seq_lens.unsqueeze(0) - self.tail_start).max().item())
+            self.recent_bound = max(r, 0)
+        return self.recent_bound
 
     def step(self, t: int, q: torch.Tensor, stream=None) -> str:
         """q: bf16 [n_layers, B, Hq, D] on the GPU (the query of the current token in every layer).

@@ -931,6 +931,39 @@ def test_decode_step_driver_fixed_and_dynamic(rk):
     check_model_loop(rk, gen.shrink(gen.WORKLOADS["cfg1_llama_2k"], n_steps=5), 2, scores_only=True)
 
 
+def test_host_bounds_under_the_trigger_schedule(rk):
+    """Under the trigger's schedule the host never learns of a refresh, so its bound on the rows decoded since
+    one grows by a row per step: a partial step given a bound far beyond the real count must still fit a
+    workspace sized for the context (what it uses does not grow with the bound) and give the result of the
+    tight bound (another launch shape: equal to within the bar, not bit for bit), and tighten_recent_bound()
+    brings the bound back from the GPU's own counts."""
+    say("host bounds under the trigger schedule")
+    w = gen.shrink(gen.WORKLOADS["cfg3_qwen_64k_dynamic"], context=3000, k_small=256, n_steps=12)
+    geom = rk.Geom(w.batch, w.n_q_heads, w.n_kv_heads, w.head_dim, w.scale)
+    lens0 = gen.seq_lens(w)
+    kv = [tuple(t.cuda() for t in gen.make_kv(w, l)) for l in range(2)]
+    sl = lens0.cuda()
+    model = rk.RefreshKVModel(geom, kv, sl, int(lens0.max()), w.k_small, w.stride, pool_w=w.pool_w, dynamic=True,
+                              threshold=w.threshold)
+    q_all = torch.stack([gen.make_queries(w, l) for l in range(2)], dim=1).cuda().contiguous()
+    for t in range(w.n_steps + 1):
+        if t >= 1:
+            sl += 1
+            model.advance()
+        model.step(t, q_all[t])
+    torch.cuda.synchronize()
+    assert model.recent_bound == w.n_steps                       # grew with every step: no full step by schedule after t = 0
+    real = int((sl.unsqueeze(0) - model.tail_start).max().item())
+    assert model.tighten_recent_bound() == real <= w.n_steps
+    out_tight = torch.zeros(w.batch, w.n_q_heads, 128, dtype=torch.bfloat16, device="cuda")
+    out_loose = torch.zeros_like(out_tight)
+    args = (geom, q_all[w.n_steps, 0], model.small_K[0], model.small_V[0], w.k_small, kv[0][0], kv[0][1], model.tail_start[0], sl)
+    rk.rk_partial_attn(*args, max(real, 1), out_tight, workspace=model.ws)
+    rk.rk_partial_attn(*args, 1_000_000, out_loose, workspace=model.ws)     # a bound far beyond the context
+    torch.cuda.synchronize()
+    assert_out_close(gen.bf16_bits(out_loose), gen.bf16_bits(out_tight), "loose against tight bound")
+
+
 def test_deferred_pooling_and_batched_refresh(rk):
     """rk_full_attn_deferred per layer + rk_refresh_batched(pool_w): out, lse, idx, small cache, tail_start and
     refresh counters against the oracle and, bit for bit, against rk_full_attn_select + rk_gather_small_kv per

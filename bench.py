@@ -364,7 +364,7 @@ def run_workload(args, workload, light):
     # HIP events on the launch stream bracket each replay; average = elapsed / launches.
     scores_buf = weights
     def roof_call(l):
-        rk.rk_full_attn_scores(geom, q_cur[l], *kv[l], seq_lens, Lb, scores_buf, workspace=ws)
+        rk.rk_full_attn_scores(geom, q_cur[l], *kv[l], seq_lens, Lb, None, workspace=ws)      # as a full step launches it
     roof_reps = 4
     per_replay = []
     side = torch.cuda.Stream()

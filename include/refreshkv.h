@@ -143,7 +143,10 @@ int rk_full_attn(const rk_geom* geom, const void* q, rk_kv full,
  * (rk_full_attn = this kernel + a short finishing kernel that merges the partial results and
  * turns the scores into weights; Section 2.2 "Decoding with full cache", Appendix A.1).
  * Exposed so that a benchmark can time the HBM-bound kernel alone, launch after launch.
- * scores: fp32 [batch, n_q_heads, s_stride], s_stride >= max_len. */
+ * scores: fp32 [batch, n_q_heads, s_stride], s_stride >= max_len; or NULL: the raw scores stay in the
+ * workspace, arranged as the full steps of rk_full_attn_select, rk_full_attn_pool and
+ * rk_full_attn_deferred keep them (for groups of 4 query heads: the 4 scores of a position side by
+ * side), i.e. the launch is exactly the first kernel of those steps. */
 int rk_full_attn_scores(const rk_geom* geom, const void* q, rk_kv full,
                         const int32_t* seq_lens, int32_t max_len,
                         float* scores, int64_t s_stride,

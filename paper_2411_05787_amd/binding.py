@@ -243,17 +243,19 @@ def rk_full_attn(geom: Geom, q, K, V, seq_lens, max_len: int, out, weights=None,
         workspace.ptr, workspace.nbytes, _stream(stream)))
 
 
-def rk_full_attn_scores(geom: Geom, q, K, V, seq_lens, max_len: int, scores, pred=None, pred_val: int = 0,
+def rk_full_attn_scores(geom: Geom, q, K, V, seq_lens, max_len: int, scores=None, pred=None, pred_val: int = 0,
                         workspace: Workspace = None, stream=None) -> None:
+    """scores=None: the raw scores stay in the workspace (the first kernel of a full step, as the
+    refreshing calls launch it)."""
     B, Hq, D = geom.batch, geom.n_q_heads, geom.head_dim
     if max_len > K.shape[2]:
         raise ValueError("max_len %d exceeds the cache capacity %d" % (max_len, K.shape[2]))
-    if scores.dim() != 3 or scores.shape[0] != B or scores.shape[1] != Hq or scores.shape[2] < max_len:
+    if scores is not None and (scores.dim() != 3 or scores.shape[0] != B or scores.shape[1] != Hq or scores.shape[2] < max_len):
         raise ValueError("scores must be [batch, n_q_heads, >= max_len]")
     _check("rk_full_attn_scores", lib.rk_full_attn_scores(
         C.byref(geom.c()), _dev(q, torch.bfloat16, "q", (B, Hq, D)), _kv(geom, K, V, "full"),
         _dev(seq_lens, torch.int32, "seq_lens", (B,)), int(max_len),
-        _dev(scores, torch.float32, "scores"), scores.shape[2],
+        _dev(scores, torch.float32, "scores", optional=True), scores.shape[2] if scores is not None else 0,
         _dev(pred, torch.int32, "pred", (B,), optional=True), int(pred_val),
         workspace.ptr, workspace.nbytes, _stream(stream)))
 

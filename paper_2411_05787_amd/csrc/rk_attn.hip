@@ -78,6 +78,7 @@ struct AttnParams {
 // nothing; the others each leave one partial result (the merge takes any subsets of the rows).
 constexpr int kSplitWaves = 4, kTileRows = 32;
 constexpr int kNoTailWg = 0xff;                   // top byte of the kernel argument s_b_and_tail: no workgroup for the tail rows
+constexpr int kHeadsFirst = 0xfe;                 // ... (launches over the full cache only) grid x = KV head, y = sequence, z = chunk
 __device__ __forceinline__ int active_workgroups(int n_rows, int nch) {
     return max(1, min(nch, (n_rows + kSplitWaves * kTileRows - 1) / (kSplitWaves * kTileRows)));
 }
@@ -447,9 +448,14 @@ void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t
     // first loads need, it is there when the wavefront starts.
     const int64_t s_b = s_b_and_tail & ((1ll << 56) - 1);
     const int tail_c = (int)(s_b_and_tail >> 56) & 0xff;
-    int c = blockIdx.x, b = blockIdx.z, nch_b = p.nch;
-    const int g = blockIdx.y;
-    const int n_kv = gridDim.y;
+    // kHeadsFirst in the same byte (launches of the full-cache kernel over one sequence or an evenly split
+    // batch): the KV head is grid x and the chunk grid z.  Workgroups are handed out in the grid's linear
+    // order, x fastest, and go to the 8 XCDs in turn: with the heads as x every XCD streams the same
+    // KV heads from start to end instead of every eighth chunk of all heads.
+    const bool heads_first = !TWO_SEG && tail_c == kHeadsFirst;
+    int c = heads_first ? blockIdx.z : blockIdx.x, b = heads_first ? blockIdx.y : blockIdx.z, nch_b = p.nch;
+    const int g = heads_first ? blockIdx.x : blockIdx.y;
+    const int n_kv = heads_first ? gridDim.x : gridDim.y;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int n16 = lane & 15, c4 = lane >> 4;
     constexpr bool kCanBeRagged = EMIT && !TWO_SEG;
@@ -484,7 +490,7 @@ void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t
     // grid x, which takes the rows of the full cache (the tokens decoded since the refresh) and
     // nothing else; the others share the rows of the small cache.  Those few rows then cost no
     // wavefront a second tile: the workgroup that has them finishes with the others, not a tile later.
-    const bool tail_mode = TWO_SEG && !LAZY && tail_c != kNoTailWg;
+    const bool tail_mode = TWO_SEG && !LAZY && tail_c != kNoTailWg && tail_c != kHeadsFirst;
     const bool is_tail = tail_mode && c == tail_c;
     int r_first = (c * NW + w) * ROWS;
     const bool spec = !is_tail && (c + 1) * NW * ROWS <= spec_rows;     // spec_rows: min(n_sel, cap1) or cap2
@@ -1325,10 +1331,16 @@ static int launch_finish_pool(const AttnParams& p, int batch, int32_t max_len, c
 
 template <int G, bool EMIT, bool TWO_SEG, bool TAGGED>
 static int launch_split_g(const AttnParams& p, int batch, int nchunk_grid, hipStream_t st) {
-    dim3 grid(nchunk_grid, p.Hkv, batch);
+    // (measured on the kernel alone, us per launch, chunk as grid x / KV head as grid x: 8 KV heads, 512
+    // workgroups, 32768..33000 rows 25.8 - 29.2 / 25.2 - 26.0; 4 KV heads, 65536..65800 rows 27.0 - 32.7 /
+    // 27.0 - 29.7; 8 KV heads, 1024 workgroups, which are not all resident at once, 131072..131400 rows
+    // 101.3 - 105.4 / 105.5; no difference at 8192 and 16384 rows)
+    const bool heads_first = EMIT && !TWO_SEG && p.ragged_batch == 0 &&
+                             (int64_t)nchunk_grid * p.Hkv * batch <= 3 * kComputeUnits;
+    dim3 grid(heads_first ? p.Hkv : nchunk_grid, heads_first ? batch : p.Hkv, heads_first ? nchunk_grid : batch);
     // four wavefronts of 32 rows per iteration; with 64-row chunks two of them only help to merge
     const int32_t spec_rows = TWO_SEG ? (p.n_sel < p.cap1 ? p.n_sel : p.cap1) : p.cap2;
-    const int64_t tail_c = (TWO_SEG && p.tail_wg) ? p.nch : kNoTailWg;
+    const int64_t tail_c = (TWO_SEG && p.tail_wg) ? p.nch : heads_first ? kHeadsFirst : kNoTailWg;
     hipLaunchKernelGGL((attn_split_kernel<G, 4, EMIT, TWO_SEG, false, TAGGED>), grid, dim3(256), 0, st,
                        TWO_SEG ? p.k1 : p.k2, TWO_SEG ? p.v1 : p.v2, (TWO_SEG ? p.s1_b : p.s2_b) | (tail_c << 56),
                        (int32_t)(TWO_SEG ? p.s1_h : p.s2_h), spec_rows, p.seq_lens, p.tail_start, p.pred, p.epochs, p);

@@ -158,9 +158,23 @@ static inline int max_chunks_for(int64_t max_len) {
 }
 
 // Workgroups per (sequence, KV head) of the score-emitting split kernel of a full step (the
-// finishing kernels must be told the same number).
+// finishing kernels must be told the same number).  The launch aims at about four tiles of 32 rows
+// per wavefront, in whole multiples of the 256 CUs, between one and four workgroups per CU.
+// Measured on the kernel alone, total workgroups -> us per launch (8 KV heads unless noted):
+//   32778 rows:            256 -> 25.8, 512 -> 24.8 - 25.2, 768 -> 25.7 - 26.2, 1024 -> 25.6 - 25.7
+//   65546 rows, 4 heads:   256 -> 28.5, 512 -> 27.6, 768 -> 28.6 - 28.9, 1024 -> 29.0 - 29.4
+//   131082 rows:           256 -> 103.0, 512 -> 102.4 - 102.9, 768 -> 102.5, 1024 -> 100.1
+// (384 workgroups, uneven over the CUs: 28.8 / 32.8 / 115.3.)  Few tiles per wavefront leave the
+// launch's fixed costs (start, the merge across the wavefronts, the partial results) a larger share
+// and make a ragged last round (2.67 tiles per wavefront with 768 workgroups at 32k rows) cost more;
+// long rows want more loads in flight.
 static inline int emit_split_workgroups(const rk_geom* g, int64_t max_len) {
-    return split_workgroups(max_len, (int64_t)g->batch * g->n_kv_heads, kMaxChunks);
+    const int64_t problems = (int64_t)g->batch * g->n_kv_heads;
+    const int64_t tiles = (max_len + 31) / 32 * problems;
+    int64_t target = (tiles / 16 + kComputeUnits / 2) / kComputeUnits * kComputeUnits;      // 16 tiles per workgroup: 4 per wavefront
+    if (target < kComputeUnits) target = kComputeUnits;
+    if (target > 4 * kComputeUnits) target = 4 * kComputeUnits;
+    return split_workgroups(max_len, problems, kMaxChunks, (int)target);
 }
 
 static inline Workspace carve(const rk_geom* g, int64_t max_len, int64_t max_k, void* base) {

@@ -74,6 +74,7 @@ typedef enum rk_status {
 #define RK_MAX_GROUP 8
 #define RK_MAX_K 16384         /* largest small-cache size rk_topk_select accepts              */
 #define RK_MAX_POOL_W 63       /* largest (odd) max-pool window                                */
+#define RK_MAX_SELECT_LEN (1 << 28) /* longest row (max_len) the selection entry points accept  */
 #define RK_MAX_WINDOW 32       /* largest observation window rk_window_select accepts          */
 
 /* Geometry of one attention layer; `scale` multiplies q.k before the softmax. */
@@ -163,6 +164,8 @@ int rk_full_attn_scores(const rk_geom* geom, const void* q, rk_kv full,
  *   weights must be non-negative and free of NaN (softmax output).  pool_w odd, 1..63
  *   (7 in the paper, 1 = no pooling).  agg: RK_AGG_MAX (the method's choice; then A is the max
  *   above), RK_AGG_MEAN or RK_AGG_FIRST (the alternatives of Appendix A.3).  1 <= k <= RK_MAX_K.
+ *   max_len <= RK_MAX_SELECT_LEN (RK_ERR_UNSUPPORTED beyond; the same limit holds for every entry
+ *   point that selects).
  *   idx int32 [batch, n_kv_heads, k]; sel_scores fp32 of the same shape or NULL. */
 int rk_topk_select(const rk_geom* geom, const float* weights, int64_t w_stride,
                    const int32_t* seq_lens, int32_t max_len,

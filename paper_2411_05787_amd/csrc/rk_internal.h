@@ -267,7 +267,7 @@ int pool_stage(const rk_geom* geom, const float* weights, int64_t w_stride, cons
                int32_t max_len, int32_t pool_w, int32_t agg, const int32_t* pred, int32_t pred_val,
                const Workspace& ws, hipStream_t st);
 __attribute__((visibility("hidden")))
-int check_select_args(int32_t k, int32_t pool_w, int32_t agg);
+int check_select_args(int32_t k, int32_t pool_w, int32_t agg, int32_t max_len);
 __attribute__((visibility("hidden")))
 int select_stage(const rk_geom* geom, const int32_t* seq_lens, int32_t max_len, int32_t k, int32_t* idx,
                  float* sel_scores, const int32_t* pred, int32_t pred_val, const Workspace& ws, hipStream_t st);

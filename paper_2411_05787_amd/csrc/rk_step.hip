@@ -144,7 +144,7 @@ extern "C" int rk_refresh_batched(const rk_geom* geom, int32_t n_layers, const r
     if (rc != RK_OK) return rc;
     if (!layers || !workspaces || !seq_lens || n_layers <= 0 || k <= 0 || max_len <= 0) return RK_ERR_INVALID_ARG;
     if (k > RK_MAX_K) return RK_ERR_UNSUPPORTED;
-    if (pool_w != 0 && (rc = rk::check_select_args(k, pool_w, agg)) != RK_OK) return rc;
+    if (pool_w != 0 && (rc = rk::check_select_args(k, pool_w, agg, max_len)) != RK_OK) return rc;
     if ((int64_t)rk::kBatchLayers * geom->batch > 65535) return RK_ERR_UNSUPPORTED;
     // every argument is checked before the first launch
     for (int l = 0; l < n_layers; ++l) {

@@ -344,7 +344,7 @@ extern "C" int rk_window_select(const rk_geom* geom, const void* q_win, int32_t 
     if (!aligned16(q_win)) return RK_ERR_INVALID_ARG;
     if ((rc = check_kv(full, false)) != RK_OK) return rc;
     if (votes && (v_stride < max_len || ((uintptr_t)votes & 3u))) return RK_ERR_INVALID_ARG;
-    if ((rc = check_select_args(k, pool_w, agg)) != RK_OK) return rc;
+    if ((rc = check_select_args(k, pool_w, agg, max_len)) != RK_OK) return rc;
     Workspace ws;
     if ((rc = check_workspace(geom, max_len, k, workspace, workspace_bytes, &ws)) != RK_OK) return rc;
     hipStream_t st = (hipStream_t)stream;

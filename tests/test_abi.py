@@ -85,6 +85,9 @@ def test_host_side_argument_checks_return_before_any_launch(rk):
     assert topk(pool=4) == -1
     assert topk(pool=65) == -2
     assert topk(agg=3) == -2 and topk(agg=-1) == -2
+    # a row beyond RK_MAX_SELECT_LEN positions (28 bits of a ranked item hold the position)
+    assert lib.rk_topk_select(C.byref(g), fake, 2 ** 28 + 8, fake, 2 ** 28 + 1, 256, 7, 0, fake, None, None, 0,
+                              0x100000, ws_bytes, None) == -2
     fused = lambda **kw: lib.rk_full_attn_select(C.byref(g), kw.get("q", fake), kv, fake, 4096, kw.get("out", fake), None, 0,
                                                  None, kw.get("k", 256), kw.get("pool", 7), 0, kw.get("idx", fake), None,
                                                  None, 0, kw.get("ws", 0x100000), ws_bytes, None)

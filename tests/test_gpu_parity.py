@@ -170,6 +170,11 @@ TOPK_CASES = [
     ("ragged_batch", 5, 8, 2, [70000, 3, 1025, 64, 31999], 1024, 7, "lognormal"),
     ("many_candidates_128k", 1, 4, 1, [131072], 8192, 7, "lognormal"),    # buckets laid out from the histogram
     ("many_candidates_pool1", 2, 2, 1, [60000, 20000], 8192, 1, "lognormal"),
+    # more candidate positions than LDS holds, but their runs of equal pooled scores fit: no second cut
+    ("runs_fit_positions_do_not_128k", 1, 4, 1, [131072], 16000, 7, "lognormal"),
+    ("runs_fit_one_workgroup", 2, 4, 2, [8100, 6000], 1100, 7, "lognormal"),
+    ("dense_one_workgroup_ties", 1, 4, 1, [8192], 1500, 7, "ties"),
+    ("pool3_runs_cut_by_k", 1, 2, 2, [20000], 999, 3, "lognormal"),
 ]
 
 

@@ -12,10 +12,19 @@ void query_sim_kernel(const uint16_t* __restrict__ q, float* __restrict__ q_ref,
     const int b = blockIdx.x, d = threadIdx.x;
     __shared__ float red[2];
     const uint16_t* qb = q + (int64_t)b * Hq * kD + d;
-    float acc = 0.f;
-    for (int h = 0; h < Hq; ++h) acc += __uint_as_float((uint32_t)qb[(int64_t)h * kD] << 16);
-    const float qbar = acc / (float)Hq;
     const float ref = q_ref[(int64_t)b * kD + d];
+    // the heads are added in order; their loads are requested sixteen at a time (one after the
+    // other, each waiting for the one before, the kernel took 28 memory round trips at 28 heads)
+    float acc = 0.f;
+    for (int h0 = 0; h0 < Hq; h0 += 16) {
+        uint16_t v[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) v[i] = qb[(int64_t)min(h0 + i, Hq - 1) * kD];
+#pragma unroll
+        for (int i = 0; i < 16; ++i)
+            if (h0 + i < Hq) acc += __uint_as_float((uint32_t)v[i] << 16);
+    }
+    const float qbar = acc / (float)Hq;
     const float dot = block_sum<2>(qbar * ref, red);
     const float n1 = block_sum<2>(qbar * qbar, red);
     const float n2 = block_sum<2>(ref * ref, red);

@@ -338,11 +338,30 @@ int rk_partial_attn_lazy(const rk_geom* geom, const void* q, rk_kv small, const 
  *   sim[b]    = <qbar, q_ref[b]> / (max(|qbar|, 1e-8) * max(|q_ref[b]|, 1e-8))
  *   need_full[b] = (sim[b] <= threshold) || force_full
  *   if need_full[b]: q_ref[b,:] = qbar[b,:]
- * q_ref fp32 [batch, 128] is read and updated in place; sim fp32 [batch]; need_full
- * int32 [batch] (0/1).  Pass force_full = 1 on steps that are full by schedule (fixed stride,
+ * q_ref fp32 [batch, 128] is read and updated in place (16-byte aligned, like q:
+ * RK_ERR_INVALID_ARG otherwise); sim fp32 [batch]; need_full int32 [batch] (0/1).  The sums are
+ * taken in fp32 in a fixed order (so every call gives the same bits for the same input).  Pass force_full = 1 on steps that are full by schedule (fixed stride,
  * first step) so that the reference follows the most recent full step. */
 int rk_query_sim(const rk_geom* geom, const void* q, float* q_ref, float threshold,
                  int32_t force_full, float* sim, int32_t* need_full, void* stream);
+
+/* The trigger's test and the partial step it guards in one launch (Section 2.2, "Deciding when
+ * to decode with full cache": the similarity check is to cost as little as possible).  For every
+ * sequence b, with sim and the decision as in rk_query_sim with force_full = 0:
+ *   sim[b], need_full[b] are stored;
+ *   need_full[b] == 0: out[b] as rk_partial_attn (fixed_size == 0, n_sel rows of `small`) or
+ *                      rk_partial_attn_fixed (fixed_size != 0, k = n_sel) leaves it; q_ref[b] unchanged;
+ *   need_full[b] == 1: out[b] is not written, q_ref[b,:] = qbar[b,:]; the caller's full step follows
+ *                      under the predicate (need_full, 1).
+ * The same result as rk_query_sim followed by the partial step under the predicate (need_full, 0),
+ * without the launch of the test and without the partial step waiting for it: every workgroup of
+ * the step works the test out for itself while its first rows are on their way.  Arguments as in
+ * rk_query_sim and rk_partial_attn; q_ref, sim and need_full must not be NULL. */
+int rk_partial_attn_triggered(const rk_geom* geom, const void* q, rk_kv small, int32_t n_sel,
+                              int32_t fixed_size, rk_kv full, const int32_t* tail_start,
+                              const int32_t* seq_lens, int32_t max_recent, void* out,
+                              float* q_ref, float threshold, float* sim, int32_t* need_full,
+                              void* workspace, size_t workspace_bytes, void* stream);
 
 /* Plain device-to-device copy of `bytes` bytes (a multiple of 16; both pointers 16-byte aligned)
  * with 16-byte loads and stores, one launch.  It exists so that a profiler run of the benchmark

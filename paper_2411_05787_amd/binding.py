@@ -16,7 +16,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "librefreshkv.so")
 
 EXPORTS = ["rk_version", "rk_status_string", "rk_workspace_bytes", "rk_workspace_init",
-           "rk_full_attn", "rk_full_attn_scores", "rk_topk_select", "rk_full_attn_select", "rk_full_attn_pool", "rk_full_attn_deferred", "rk_select_pooled", "rk_score_select", "rk_window_select", "rk_gather_small_kv", "rk_partial_attn", "rk_partial_attn_static", "rk_partial_attn_static_bytes", "rk_partial_attn_fixed", "rk_partial_attn_lazy", "rk_decode_step", "rk_decode_step_overlapped", "rk_refresh_batched", "rk_decode_step_batched",
+           "rk_full_attn", "rk_full_attn_scores", "rk_topk_select", "rk_full_attn_select", "rk_full_attn_pool", "rk_full_attn_deferred", "rk_select_pooled", "rk_score_select", "rk_window_select", "rk_gather_small_kv", "rk_partial_attn", "rk_partial_attn_static", "rk_partial_attn_static_bytes", "rk_partial_attn_fixed", "rk_partial_attn_lazy", "rk_partial_attn_triggered", "rk_decode_step", "rk_decode_step_overlapped", "rk_refresh_batched", "rk_decode_step_batched",
            "rk_query_sim", "rk_mark_refresh", "rk_calibration_copy", "rk_h2o_append", "rk_h2o_update", "rk_h2o_step"]
 
 RK_AGG_MAX, RK_AGG_MEAN, RK_AGG_FIRST = 0, 1, 2
@@ -108,6 +108,8 @@ def _load(path: str = LIB_PATH) -> C.CDLL:
     l.rk_partial_attn_lazy.argtypes = [G, P, _Kv, P, I32, I32, _Kv, P, P, I32, P, P, I32, P, SZ, P]
     l.rk_partial_attn_lazy.restype = C.c_int
     l.rk_query_sim.restype = C.c_int
+    l.rk_partial_attn_triggered.restype = C.c_int
+    l.rk_partial_attn_triggered.argtypes = [G, P, _Kv, I32, I32, _Kv, P, P, I32, P, P, C.c_float, P, P, P, SZ, P]
     l.rk_decode_step.restype = C.c_int
     l.rk_decode_step.argtypes = [G, C.POINTER(_Schedule), I32, I32, C.POINTER(_LayerState), C.POINTER(C.c_void_p),
                                  C.POINTER(C.c_void_p), P, I32, I32, P, SZ, P]
@@ -505,6 +507,19 @@ def rk_decode_step_overlapped(geom: Geom, sched: _Schedule, t: int, layers, q_pt
     if rc <= 0:
         _check("rk_decode_step_overlapped", rc if rc < 0 else -1)
     return STEP_KINDS[rc]
+
+
+def rk_partial_attn_triggered(geom: Geom, q, small_K, small_V, n_sel: int, K, V, tail_start, seq_lens,
+                              max_recent: int, out, q_ref, threshold: float, sim, need_full,
+                              fixed_size: bool = False, workspace: Workspace = None, stream=None) -> None:
+    B, Hq, D = geom.batch, geom.n_q_heads, geom.head_dim
+    _check("rk_partial_attn_triggered", lib.rk_partial_attn_triggered(
+        C.byref(geom.c()), _dev(q, torch.bfloat16, "q", (B, Hq, D)),
+        _kv(geom, small_K, small_V, "small", min_rows=n_sel), int(n_sel), 1 if fixed_size else 0, _kv(geom, K, V, "full"),
+        _dev(tail_start, torch.int32, "tail_start", (B,)), _dev(seq_lens, torch.int32, "seq_lens", (B,)),
+        int(max_recent), _dev(out, torch.bfloat16, "out", (B, Hq, D)),
+        _dev(q_ref, torch.float32, "q_ref", (B, D)), float(threshold), _dev(sim, torch.float32, "sim", (B,)),
+        _dev(need_full, torch.int32, "need_full", (B,)), workspace.ptr, workspace.nbytes, _stream(stream)))
 
 
 def rk_query_sim(geom: Geom, q, q_ref, threshold: float, force_full: bool, sim, need_full, stream=None) -> None:

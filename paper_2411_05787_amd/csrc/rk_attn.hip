@@ -67,6 +67,7 @@ struct AttnParams {
     int32_t* counters; float* part_ml; float* part_o; int32_t max_chunks;
     uint32_t* epochs; uint32_t* tag_rows;     // TAGGED only: call number per (sequence, KV head), tagged partial results
     const int32_t* idx; int32_t idx_stride;   // LAZY only: the selection [B, Hkv, idx_stride] whose rows are not gathered yet
+    float* trig_q_ref; float* trig_sim; int32_t* trig_need; float trig_threshold;   // TRIG only: the query-similarity test
     int32_t ragged_batch;              // != 0 (= batch): workgroups are shared out by length, see ragged_share_lane
 };
 
@@ -422,13 +423,22 @@ __device__ __forceinline__ void merge_tagged_heads(const AttnParams& p, int b, i
 // leaves the small cache as rk_gather_small_kv would have.  k_first / v_first / s_b / s_h then
 // describe the FULL cache and `pred` carries the selection (the predicate is read from `p`).
 
-template <int G, int NW, bool EMIT, bool TWO_SEG, bool LAZY = false, bool TAGGED = !EMIT>
+// TRIG (with TWO_SEG): the partial step of a step on which the query-similarity trigger is tested
+// (Section 2.2).  Every workgroup works the test out for itself from the 9 KB of queries and
+// reference, behind the requests for its first tile and before it waits for anything, and gives up
+// if its sequence needs a full step: the test costs no launch of its own and no launch waits for it.
+// Workgroup (0, 0) of the sequence stores the similarity and the decision for the launches that
+// follow (the full step under that predicate).  Where the test asks for a full step the averaged
+// query becomes the new reference; every workgroup of the sequence has read the old one by then:
+// each takes a ticket after its test, and the last one stores.
+template <int G, int NW, bool EMIT, bool TWO_SEG, bool LAZY = false, bool TAGGED = !EMIT, bool TRIG = false>
 __global__ __launch_bounds__(NW * 64, EMIT ? RK_EMIT_OCCUPANCY : 2)
 void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t s_b_and_tail, int32_t s_h, int32_t spec_rows,
                        const int32_t* seq_lens, const int32_t* tail_start, const int32_t* pred, const uint32_t* epochs,
                        const AttnParams p) {
     static_assert(!LAZY || (TWO_SEG && !EMIT), "the lazy gather belongs to the partial step");
     static_assert(!(TAGGED && EMIT), "tagged partial results belong to the launches that merge inside the kernel");
+    static_assert(!TRIG || (TWO_SEG && !LAZY), "the trigger is tested by the partial step");
     // The leading arguments repeat what the first loads need (the cache that holds the first rows,
     // its strides, the two length arrays, the predicate, the call numbers): 16 dwords that the command processor
     // hands over in registers at wavefront launch (kernel-argument preload), so neither the first
@@ -478,7 +488,19 @@ void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t
         sel0 = tile_sel((c * NW + w) * kTileRows, spec_rows);      // before anything else: the rows depend on it
         if (p.pred != nullptr && p.pred[b] != p.pred_val) return;
     } else {
-        if (pred != nullptr && pred[b] != p.pred_val) return;
+        if (!TRIG && pred != nullptr && pred[b] != p.pred_val) return;
+    }
+
+    // TRIG: the test's queries and reference are requested first of all, so that the test is worked out
+    // while the first tile is on its way (memory answers in the order of the requests).  A launch with
+    // the test has no predicate, and takes the call numbers from the argument block: the two
+    // preloaded pointers carry the queries and the reference instead.
+    // One wavefront of the workgroup does it (all the workgroups of the launch read the same 9 KB at
+    // the same time: four times the requests cost more than the barrier that passes the result on).
+    SimLoads trig_ld;
+    if constexpr (TRIG) {
+        if (w == 0)
+            similarity_request(reinterpret_cast<const uint16_t*>(pred), reinterpret_cast<const float*>(epochs), b, n_kv * G, trig_ld);
     }
 
     // ---- K and V rows of the first tile are requested before any length is known ----
@@ -528,10 +550,42 @@ void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t
         if (spec_rows >= 0) {
             len_raw = seq_lens[b];
             if (TWO_SEG) tail_raw = tail_start[b];
-            if (TAGGED) epoch = epochs[(int64_t)b * n_kv + g];
+            if (TAGGED) epoch = (TRIG ? p.epochs : epochs)[(int64_t)b * n_kv + g];
             const uint16_t* qrow = p.q + ((int64_t)b * p.Hq + (int64_t)g * G + (n16 < G ? n16 : 0)) * kD;
 #pragma unroll
             for (int kk = 0; kk < 4; ++kk) qu[kk] = *reinterpret_cast<const uint4*>(qrow + (kk * 4 + c4) * 8);
+        }
+        // TRIG: the test is worked out here, between the requests and the first wait for a tile
+        if constexpr (TRIG) {
+            __shared__ int trig_last, trig_need_full;
+            float qbar[8];
+            if (w == 0) {
+                const float s = similarity_finish(reinterpret_cast<const uint16_t*>(pred), b, n_kv * G, trig_ld, qbar);
+                const bool need_w = !(s > p.trig_threshold);
+                if (lane == 0) {
+                    trig_need_full = need_w ? 1 : 0;
+                    if (c == 0 && g == 0) { p.trig_sim[b] = s; p.trig_need[b] = need_w ? 1 : 0; }
+                }
+            }
+            __syncthreads();
+            const bool need = trig_need_full != 0;
+            if (need) {
+                // (the ticket is the second word of the sequence's first arrival-counter line: zero between launches;
+                // the wavefront that takes it is the one that read the reference)
+                if (tid == 0) {
+                    int32_t* ticket = p.counters + (int64_t)b * n_kv * kCounterStride + 1;
+                    const int seen = __hip_atomic_fetch_add(ticket, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    trig_last = seen == (int)(gridDim.x * gridDim.y) - 1 ? 1 : 0;
+                    if (trig_last) __hip_atomic_store(ticket, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+                __syncthreads();
+                if (trig_last && tid < 16) {
+                    float4* rp = reinterpret_cast<float4*>(p.trig_q_ref + (int64_t)b * kD + tid * 8);
+                    rp[0] = make_float4(qbar[0], qbar[1], qbar[2], qbar[3]);
+                    rp[1] = make_float4(qbar[4], qbar[5], qbar[6], qbar[7]);
+                }
+                return;
+            }
         }
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
@@ -1329,7 +1383,7 @@ static int launch_finish_pool(const AttnParams& p, int batch, int32_t max_len, c
     return launch_status();
 }
 
-template <int G, bool EMIT, bool TWO_SEG, bool TAGGED>
+template <int G, bool EMIT, bool TWO_SEG, bool TAGGED, bool TRIG = false>
 static int launch_split_g(const AttnParams& p, int batch, int nchunk_grid, hipStream_t st) {
     // (measured on the kernel alone, us per launch, chunk as grid x / KV head as grid x: 8 KV heads, 512
     // workgroups, 32768..33000 rows 25.8 - 29.2 / 25.2 - 26.0; 4 KV heads, 65536..65800 rows 27.0 - 32.7 /
@@ -1341,9 +1395,12 @@ static int launch_split_g(const AttnParams& p, int batch, int nchunk_grid, hipSt
     // four wavefronts of 32 rows per iteration; with 64-row chunks two of them only help to merge
     const int32_t spec_rows = TWO_SEG ? (p.n_sel < p.cap1 ? p.n_sel : p.cap1) : p.cap2;
     const int64_t tail_c = (TWO_SEG && p.tail_wg) ? p.nch : heads_first ? kHeadsFirst : kNoTailWg;
-    hipLaunchKernelGGL((attn_split_kernel<G, 4, EMIT, TWO_SEG, false, TAGGED>), grid, dim3(256), 0, st,
+    // (TRIG: the pointers the test needs first travel in the preloaded slots of the predicate and the call numbers)
+    hipLaunchKernelGGL((attn_split_kernel<G, 4, EMIT, TWO_SEG, false, TAGGED, TRIG>), grid, dim3(256), 0, st,
                        TWO_SEG ? p.k1 : p.k2, TWO_SEG ? p.v1 : p.v2, (TWO_SEG ? p.s1_b : p.s2_b) | (tail_c << 56),
-                       (int32_t)(TWO_SEG ? p.s1_h : p.s2_h), spec_rows, p.seq_lens, p.tail_start, p.pred, p.epochs, p);
+                       (int32_t)(TWO_SEG ? p.s1_h : p.s2_h), spec_rows, p.seq_lens, p.tail_start,
+                       TRIG ? reinterpret_cast<const int32_t*>(p.q) : p.pred,
+                       TRIG ? reinterpret_cast<const uint32_t*>(p.trig_q_ref) : p.epochs, p);
     return launch_status();
 }
 
@@ -1380,6 +1437,21 @@ static int launch_split(const AttnParams& p, int batch, int G, int nchunk_grid, 
         case 6: return launch_split_g<6, EMIT, TWO_SEG, TAGGED>(p, batch, nchunk_grid, st);
         case 7: return launch_split_g<7, EMIT, TWO_SEG, TAGGED>(p, batch, nchunk_grid, st);
         case 8: return launch_split_g<8, EMIT, TWO_SEG, TAGGED>(p, batch, nchunk_grid, st);
+        default: return RK_ERR_UNSUPPORTED;
+    }
+}
+
+// The partial step that tests the trigger itself: tagged hand-over for groups of up to 4 heads, ticketed beyond.
+static int launch_split_triggered(const AttnParams& p, int batch, int G, int nchunk_grid, hipStream_t st) {
+    switch (G) {
+        case 1: return launch_split_g<1, false, true, true, true>(p, batch, nchunk_grid, st);
+        case 2: return launch_split_g<2, false, true, true, true>(p, batch, nchunk_grid, st);
+        case 3: return launch_split_g<3, false, true, true, true>(p, batch, nchunk_grid, st);
+        case 4: return launch_split_g<4, false, true, true, true>(p, batch, nchunk_grid, st);
+        case 5: return launch_split_g<5, false, true, false, true>(p, batch, nchunk_grid, st);
+        case 6: return launch_split_g<6, false, true, false, true>(p, batch, nchunk_grid, st);
+        case 7: return launch_split_g<7, false, true, false, true>(p, batch, nchunk_grid, st);
+        case 8: return launch_split_g<8, false, true, false, true>(p, batch, nchunk_grid, st);
         default: return RK_ERR_UNSUPPORTED;
     }
 }
@@ -1570,11 +1642,15 @@ static int check_partial_args(const rk_geom* geom, const void* q, rk_kv small, i
     return RK_OK;
 }
 
+// The query-similarity test a partial step carries out itself (rk_partial_attn_triggered).
+struct Trigger { float* q_ref; float threshold; float* sim; int32_t* need_full; };
+
 // Launch of the partial step; `ws` needs counters, lse, part_ml, part_o and max_chunks only.
 static int launch_partial(const rk_geom* geom, const void* q, rk_kv small, int32_t n_sel, bool evict,
                           rk_kv full, const int32_t* tail_start, const int32_t* seq_lens,
                           int32_t max_recent, void* out, const int32_t* pred, int32_t pred_val,
-                          const Workspace& ws, void* stream, const int32_t* lazy_idx = nullptr) {
+                          const Workspace& ws, void* stream, const int32_t* lazy_idx = nullptr,
+                          const Trigger* trig = nullptr) {
     const int G = geom->n_q_heads / geom->n_kv_heads;
     AttnParams p{};
     p.q = (const uint16_t*)q;
@@ -1610,6 +1686,11 @@ static int launch_partial(const rk_geom* geom, const void* q, rk_kv small, int32
         return launch_lazy(p, geom->batch, G, (hipStream_t)stream);
     }
     const int nchunk_grid = p.nch + p.tail_wg;
+    if (trig != nullptr) {          // (groups of more than 4 heads take the ticketed form, as without the trigger)
+        if (ws.tag_rows == nullptr || pred != nullptr) return RK_ERR_INVALID_ARG;
+        p.trig_q_ref = trig->q_ref; p.trig_sim = trig->sim; p.trig_need = trig->need_full; p.trig_threshold = trig->threshold;
+        return launch_split_triggered(p, geom->batch, G, nchunk_grid, (hipStream_t)stream);
+    }
     if (!tagged) return launch_split<false, true, false>(p, geom->batch, G, nchunk_grid, (hipStream_t)stream);
     return launch_split<false, true>(p, geom->batch, G, nchunk_grid, (hipStream_t)stream);
 }
@@ -1618,7 +1699,8 @@ static int partial_attn_impl(const rk_geom* geom, const void* q, rk_kv small, in
                              rk_kv full, const int32_t* tail_start, const int32_t* seq_lens,
                              int32_t max_recent, void* out,
                              const int32_t* pred, int32_t pred_val,
-                             void* workspace, size_t workspace_bytes, void* stream, const int32_t* lazy_idx = nullptr) {
+                             void* workspace, size_t workspace_bytes, void* stream, const int32_t* lazy_idx = nullptr,
+                             const Trigger* trig = nullptr) {
     int rc = check_partial_args(geom, q, small, n_sel, full, tail_start, seq_lens, max_recent, out);
     if (rc != RK_OK) return rc;
     // What the step uses of the workspace lies at offsets that follow from the geometry alone; only the
@@ -1634,7 +1716,7 @@ static int partial_attn_impl(const rk_geom* geom, const void* q, rk_kv small, in
     const size_t slots = (workspace_bytes - before) / slot;
     ws.max_chunks = slots < (size_t)kMergeChunks ? (int)slots : kMergeChunks;     // the launch takes no more workgroups than this
     return launch_partial(geom, q, small, n_sel, evict, full, tail_start, seq_lens, max_recent, out, pred, pred_val,
-                          ws, stream, lazy_idx);
+                          ws, stream, lazy_idx, trig);
 }
 
 extern "C" int rk_partial_attn(const rk_geom* geom, const void* q, rk_kv small, int32_t n_sel,
@@ -1664,7 +1746,16 @@ extern "C" int rk_partial_attn_fixed(const rk_geom* geom, const void* q, rk_kv s
     return partial_attn_impl(geom, q, small, k, true, full, tail_start, seq_lens, max_recent, out, pred, pred_val,
                              workspace, workspace_bytes, stream);
 }
-
+extern "C" int rk_partial_attn_triggered(const rk_geom* geom, const void* q, rk_kv small, int32_t n_sel,
+                                         int32_t fixed_size, rk_kv full, const int32_t* tail_start,
+                                         const int32_t* seq_lens, int32_t max_recent, void* out,
+                                         float* q_ref, float threshold, float* sim, int32_t* need_full,
+                                         void* workspace, size_t workspace_bytes, void* stream) {
+    if (!q_ref || !sim || !need_full || !aligned16(q_ref)) return RK_ERR_INVALID_ARG;
+    const Trigger trig{q_ref, threshold, sim, need_full};
+    return partial_attn_impl(geom, q, small, n_sel, fixed_size != 0, full, tail_start, seq_lens, max_recent, out,
+                             nullptr, 0, workspace, workspace_bytes, stream, nullptr, &trig);
+}
 
 // ---- rk_partial_attn_static: the partial step for callers that cannot allocate ----
 // The scratch memory of the step (arrival counters, per-workgroup statistics and partial outputs)

@@ -135,6 +135,65 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
     return r;
 }
 
+// The query-similarity test of Section 2.2 ("deciding when to decode with the full cache"): cosine
+// similarity between the query of sequence b averaged over its Hq heads and the reference
+// q_ref[b, :] kept from the last full step.  The work of one wavefront, in two parts, so that a
+// kernel with other work can put the requests early and the arithmetic where it waits anyway.
+// Lane (hg, dc) = (lane / 16, lane % 16) has dimensions 8 dc .. 8 dc + 7 of the heads hg, hg + 4,
+// hg + 8, ...: one 16-byte load per lane fetches four whole heads per instruction.  The order of
+// the fp32 additions is fixed: the heads of a lane group in order, then (group 0 + 1) + (2 + 3);
+// the dot product and the two norms over a lane's 8 dimensions in order, then over the 16 lanes.
+constexpr int kSimRound = 8;                      // loads per lane in flight together: 32 heads
+struct SimLoads { uint4 v[kSimRound]; float4 r0, r1; };
+// Part 1: requests the reference and the first 32 heads (one memory round trip).  q and q_ref are
+// 16-byte aligned.
+__device__ __forceinline__ void similarity_request(const uint16_t* q, const float* q_ref, int b, int Hq, SimLoads& ld) {
+    const int lane = threadIdx.x & 63, hg = lane >> 4, dc = lane & 15;
+    const float4* rp = reinterpret_cast<const float4*>(q_ref + (int64_t)b * RK_HEAD_DIM + dc * 8);
+    ld.r0 = rp[0]; ld.r1 = rp[1];
+    const uint16_t* qb = q + (int64_t)b * Hq * RK_HEAD_DIM + dc * 8;
+#pragma unroll
+    for (int i = 0; i < kSimRound; ++i)
+        ld.v[i] = *reinterpret_cast<const uint4*>(qb + (int64_t)min(4 * i + hg, Hq - 1) * RK_HEAD_DIM);
+}
+// Part 2: the similarity, the same bits in every lane of every wavefront that computes it; mean[j]
+// = component 8 dc + j of the averaged query (the same in the four lane groups).
+__device__ __forceinline__ float similarity_finish(const uint16_t* q, int b, int Hq, const SimLoads& ld, float (&mean)[8]) {
+    const int lane = threadIdx.x & 63, hg = lane >> 4, dc = lane & 15;
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    auto add_head = [&](const uint4 x) {
+        acc[0] += __uint_as_float(x.x << 16); acc[1] += __uint_as_float(x.x & 0xFFFF0000u);
+        acc[2] += __uint_as_float(x.y << 16); acc[3] += __uint_as_float(x.y & 0xFFFF0000u);
+        acc[4] += __uint_as_float(x.z << 16); acc[5] += __uint_as_float(x.z & 0xFFFF0000u);
+        acc[6] += __uint_as_float(x.w << 16); acc[7] += __uint_as_float(x.w & 0xFFFF0000u);
+    };
+#pragma unroll
+    for (int i = 0; i < kSimRound; ++i)
+        if (4 * i + hg < Hq) add_head(ld.v[i]);
+    const uint16_t* qb = q + (int64_t)b * Hq * RK_HEAD_DIM + dc * 8;
+    for (int h0 = 4 * kSimRound; h0 < Hq; h0 += 4 * kSimRound) {      // more heads than one round holds
+        uint4 v[kSimRound];
+#pragma unroll
+        for (int i = 0; i < kSimRound; ++i)
+            v[i] = *reinterpret_cast<const uint4*>(qb + (int64_t)min(h0 + 4 * i + hg, Hq - 1) * RK_HEAD_DIM);
+#pragma unroll
+        for (int i = 0; i < kSimRound; ++i)
+            if (h0 + 4 * i + hg < Hq) add_head(v[i]);
+    }
+    const float ref[8] = {ld.r0.x, ld.r0.y, ld.r0.z, ld.r0.w, ld.r1.x, ld.r1.y, ld.r1.z, ld.r1.w};
+    float dot = 0.f, n1 = 0.f, n2 = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        mean[j] = sum_xor32(sum_xor16(acc[j])) / (float)Hq;
+        dot += mean[j] * ref[j]; n1 += mean[j] * mean[j]; n2 += ref[j] * ref[j];
+    }
+    // (the lanes of a row of 16 add in different orders: lane 0 speaks for all)
+    dot = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(row16_sum(dot))));
+    n1 = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(row16_sum(n1))));
+    n2 = __uint_as_float(__builtin_amdgcn_readfirstlane(__float_as_uint(row16_sum(n2))));
+    return dot / (fmaxf(sqrtf(n1), 1e-8f) * fmaxf(sqrtf(n2), 1e-8f));
+}
+
 // fp64 sum over the workgroup; `red` holds NW doubles.
 template <int NW>
 __device__ __forceinline__ double block_sum_f64(double v, double* red) {

@@ -61,9 +61,10 @@ extern "C" int rk_decode_step(const rk_geom* geom, const rk_schedule* sched, int
             }
             rc = full(L, l, nullptr);
         } else if (both) {
-            rc = rk_query_sim(geom, q[l], L.q_ref, sched->threshold, 0, L.sim, L.need_full, stream);
-            if (rc != RK_OK) return rc;
-            rc = partial(L, l, L.need_full, 0);
+            // the test rides on the partial step; the full step follows under the predicate it leaves
+            rc = rk_partial_attn_triggered(geom, q[l], L.small, sched->k, sched->fixed_size, L.full, L.tail_start,
+                                           seq_lens, recent, out[l], L.q_ref, sched->threshold, L.sim, L.need_full,
+                                           workspace, workspace_bytes, stream);
             if (rc != RK_OK) return rc;
             rc = full(L, l, L.need_full);
         } else {
@@ -209,14 +210,13 @@ extern "C" int rk_decode_step_batched(const rk_geom* geom, const rk_schedule* sc
     const int recent = max_recent > 0 ? max_recent : 1;
     for (int l = 0; l < n_layers; ++l) {
         const rk_layer_state& L = layers[l];
-        if (sched->dynamic) {
-            rc = rk_query_sim(geom, q[l], L.q_ref, sched->threshold, both ? 0 : 1, L.sim, L.need_full, stream);
+        if (both) {       // the test rides on the partial step; the full step follows under the predicate it leaves
+            rc = rk_partial_attn_triggered(geom, q[l], L.small, sched->k, sched->fixed_size, L.full, L.tail_start,
+                                           seq_lens, recent, out[l], L.q_ref, sched->threshold, L.sim, L.need_full,
+                                           workspaces[l], workspace_bytes, stream);
             if (rc != RK_OK) return rc;
-        }
-        if (both) {
-            auto fn = sched->fixed_size ? rk_partial_attn_fixed : rk_partial_attn;
-            rc = fn(geom, q[l], L.small, sched->k, L.full, L.tail_start, seq_lens, recent, out[l], L.need_full, 0,
-                    workspaces[l], workspace_bytes, stream);
+        } else if (sched->dynamic) {      // the trigger's reference follows every full step
+            rc = rk_query_sim(geom, q[l], L.q_ref, sched->threshold, 1, L.sim, L.need_full, stream);
             if (rc != RK_OK) return rc;
         }
         rc = rk_full_attn_deferred(geom, q[l], L.full, seq_lens, max_len, out[l], nullptr,

@@ -174,6 +174,12 @@ def test_host_side_argument_checks_return_before_any_launch(rk):
     assert batched([state(), state()], wsb=1024) == -3
     assert batched([state(), state(small=_Kv(fake, fake, 8 * 128 * 128, 128 * 128, 128))]) == -1       # fewer than k rows
     assert batched([state(), state(full=_Kv(fake, fake, 8 * 8192 * 128, 8192 * 128, 8192))]) == -2     # strides differ
+    trig = lambda **kw: lib.rk_partial_attn_triggered(C.byref(g), kw.get("q", fake), kv, 256, 0, kv, fake, fake, 16, fake,
+                                                     kw.get("q_ref", fake), 0.5, kw.get("sim", fake), kw.get("need", fake),
+                                                     kw.get("ws", 0x100000), ws_bytes, None)
+    assert trig(q_ref=None) == -1 and trig(sim=None) == -1 and trig(need=None) == -1
+    assert trig(q=None) == -1
+    assert trig(ws=None) == -3
     assert lib.rk_mark_refresh(C.byref(g), None, fake, None, 0, None) == -1
     assert lib.rk_workspace_init(C.byref(g), None, 4096, None) == -3
     assert lib.rk_workspace_init(C.byref(g), 0x100000, 16, None) == -3

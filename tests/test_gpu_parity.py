@@ -625,6 +625,64 @@ def test_query_sim_matches_oracle(rk):
         assert np.abs(q_ref.cpu().numpy() - r_ref).max() < 1e-6
 
 
+@pytest.mark.parametrize("heads", [(32, 8), (28, 4)], ids=["g4_tagged", "g7_ticketed"])
+@pytest.mark.parametrize("fixed_size", [False, True], ids=["growing", "fixed_size"])
+def test_partial_attn_triggered_equals_test_then_step(rk, heads, fixed_size):
+    """rk_partial_attn_triggered against rk_query_sim followed by the partial step under its predicate
+    (bit for bit: output, similarity, decision, reference), and the decisions against the oracle; sequences
+    that fire and that do not in one batch; twice in a row on one workspace (the test's ticket is left clean)."""
+    Hq, Hkv = heads
+    B, k, cap = 5, 600, 2048
+    say("partial_attn_triggered", heads, "fixed_size" if fixed_size else "growing")
+    g = torch.Generator().manual_seed(77 + Hq)
+    q = torch.randn(B, Hq, 128, generator=g).to(torch.bfloat16)
+    ref = torch.randn(B, 128, generator=g)
+    ref[0] = q[0].float().mean(0)                    # sim = 1: no full step
+    ref[2] = q[2].float().mean(0) * 3 + 0.01 * ref[2]
+    ref[3] = -q[3].float().mean(0)                   # sim = -1: full step
+    K = torch.randn(B, Hkv, cap, 128, generator=g).to(torch.bfloat16).cuda()
+    V = torch.randn(B, Hkv, cap, 128, generator=g).to(torch.bfloat16).cuda()
+    sK = torch.randn(B, Hkv, k, 128, generator=g).to(torch.bfloat16).cuda()
+    sV = torch.randn(B, Hkv, k, 128, generator=g).to(torch.bfloat16).cuda()
+    lens = torch.tensor([1500, 1400, 2000, 900, 1207], dtype=torch.int32, device="cuda")
+    tail = lens - torch.tensor([3, 9, 1, 5, 0], dtype=torch.int32, device="cuda")
+    geom = rk.Geom(B, Hq, Hkv, 128, float(np.float32(1 / np.sqrt(128))))
+    ws = rk.Workspace(geom, cap, k)
+    thr = 0.5
+    s_ref, n_ref, r_ref = oracle.query_sim(gen.bf16_bits(q), ref.double().numpy(), thr, False)
+    assert n_ref.any() and not n_ref.all()
+    qd = q.cuda()
+    # the two calls
+    q_ref_a = ref.clone().cuda(); sim_a = torch.zeros(B, device="cuda")
+    need_a = torch.full((B,), -1, dtype=torch.int32, device="cuda")
+    out_a = torch.full((B, Hq, 128), 7.0, dtype=torch.bfloat16, device="cuda")
+    rk.rk_query_sim(geom, qd, q_ref_a, thr, False, sim_a, need_a)
+    step = rk.rk_partial_attn_fixed if fixed_size else rk.rk_partial_attn
+    step(geom, qd, sK, sV, k, K, V, tail, lens, 16, out_a, pred=need_a, pred_val=0, workspace=ws)
+    torch.cuda.synchronize()
+    assert (need_a.cpu().numpy().astype(bool) == n_ref).all()
+    for rep in range(2):
+        q_ref_b = ref.clone().cuda(); sim_b = torch.zeros(B, device="cuda")
+        need_b = torch.full((B,), -1, dtype=torch.int32, device="cuda")
+        out_b = torch.full((B, Hq, 128), 7.0, dtype=torch.bfloat16, device="cuda")
+        rk.rk_partial_attn_triggered(geom, qd, sK, sV, k, K, V, tail, lens, 16, out_b, q_ref_b, thr, sim_b, need_b,
+                                     fixed_size=fixed_size, workspace=ws)
+        torch.cuda.synchronize()
+        assert torch.equal(need_b, need_a) and torch.equal(sim_b, sim_a), rep
+        assert torch.equal(q_ref_b, q_ref_a), rep
+        assert torch.equal(out_b, out_a), rep
+        assert np.abs(sim_b.cpu().numpy() - s_ref).max() < 1e-5
+        assert np.abs(q_ref_b.cpu().numpy() - r_ref).max() < 1e-6
+        fired = need_b.cpu().numpy().astype(bool)
+        assert (gen.bf16_bits(out_b.cpu())[fired] == gen.bf16_bits(torch.tensor(7.0, dtype=torch.bfloat16))).all()
+    # the workspace serves an ordinary step afterwards
+    out_c = torch.zeros_like(out_a)
+    step(geom, qd, sK, sV, k, K, V, tail, lens, 16, out_c, workspace=ws)
+    torch.cuda.synchronize()
+    keep = ~need_a.cpu().numpy().astype(bool)
+    assert torch.equal(out_c[torch.from_numpy(keep).cuda()], out_a[torch.from_numpy(keep).cuda()])
+
+
 # ----------------------------------------------------------------------------- whole loop
 def run_gpu_loop(rk, w: gen.Workload, layer: int, K, V, q_steps, new_k, new_v, lens0, evict_lowest=False,
                  scores_only=False):

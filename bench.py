@@ -404,6 +404,29 @@ def run_workload(args, workload, light):
     del cal_dst
     rows = int(seq_lens.sum().item())                    # rows streamed per launch (all sequences)
     bytes_kv = 2 * Hkv * D * 2 * rows                    # K and V rows, bf16
+    # what a kernel that only reads reaches here (rk_calibration_read: streaming 16-byte loads, nothing kept): over
+    # a buffer far larger than the caches in one launch, and in launches of the size of one launch of the
+    # full-cache kernel (its K and V bytes), one after the other over different parts of that buffer
+    read_buf = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+    sink = torch.zeros(1, dtype=torch.int32, device=dev)
+    launch_bytes = min(bytes_kv // 16 * 16, read_buf.numel())
+    windows = min(max(read_buf.numel() // launch_bytes, 1), 16)
+    read_gbps = {}
+    for key, n_bytes, n_launch in (("one_launch_1GiB", read_buf.numel(), 2), ("launches_of_full_attn_kv_bytes", launch_bytes, windows)):
+        g_read = torch.cuda.CUDAGraph()
+        rk.rk_calibration_read(read_buf, sink, n_bytes); torch.cuda.synchronize()
+        with torch.cuda.graph(g_read):
+            for i in range(n_launch):
+                rk.rk_calibration_read(read_buf, sink, n_bytes, offset=(i % windows) * launch_bytes if n_bytes == launch_bytes else 0)
+        g_read.replay(); torch.cuda.synchronize()
+        us = []
+        for _ in range(4):
+            ea.record(); g_read.replay(); eb.record(); torch.cuda.synchronize()
+            us.append(ea.elapsed_time(eb) * 1e3 / n_launch)
+        read_gbps[key] = round(n_bytes / (float(np.median(us)) * 1e-6) / 1e9, 1)
+        del g_read
+    read_gbps["bytes_per_launch"] = int(launch_bytes)
+    del read_buf
     bytes_w = 4 * Hq * rows                              # raw scores written by the same kernel
     algo_bytes = bytes_kv + bytes_w
     achieved = algo_bytes / (split_us * 1e-6) / 1e9
@@ -507,6 +530,7 @@ def run_workload(args, workload, light):
         "roofline": roofline,
         "roofline_partial": roofline_partial,
         "copy_GBps": copy_gbps,
+        "read_GBps": read_gbps,
         "cpu_baseline": cpu,
         "calibration_copy_bytes": calibration_bytes,
         "setup_s": round(setup_s, 1),

@@ -369,6 +369,12 @@ int rk_partial_attn_triggered(const rk_geom* geom, const void* q, rk_kv small, i
  * the byte counters read for the attention kernels are scaled. */
 int rk_calibration_copy(void* dst, const void* src, size_t bytes, void* stream);
 
+/* Reads `bytes` bytes (a multiple of 16; src 16-byte aligned) with 16-byte streaming loads and
+ * keeps nothing (sink: one device word that is written only if the words read xor to one fixed
+ * value).  It exists so that the benchmark can report, beside the attention kernels, the rate a
+ * kernel that only reads reaches on the same GPU. */
+int rk_calibration_read(const void* src, size_t bytes, uint32_t* sink, void* stream);
+
 /* Bookkeeping of a refresh: tail_start[b] = seq_lens[b] for every sequence the predicate
  * selects (all when pred is NULL).  After a full step + refresh the rows "decoded since the
  * refresh" start at the current length (Section 2.2: the partial cache then grows by the

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(HERE, "librefreshkv.so")
 
 EXPORTS = ["rk_version", "rk_status_string", "rk_workspace_bytes", "rk_workspace_init",
            "rk_full_attn", "rk_full_attn_scores", "rk_topk_select", "rk_full_attn_select", "rk_full_attn_pool", "rk_full_attn_deferred", "rk_select_pooled", "rk_score_select", "rk_window_select", "rk_gather_small_kv", "rk_partial_attn", "rk_partial_attn_static", "rk_partial_attn_static_bytes", "rk_partial_attn_fixed", "rk_partial_attn_lazy", "rk_partial_attn_triggered", "rk_decode_step", "rk_decode_step_overlapped", "rk_refresh_batched", "rk_decode_step_batched",
-           "rk_query_sim", "rk_mark_refresh", "rk_calibration_copy", "rk_h2o_append", "rk_h2o_update", "rk_h2o_step"]
+           "rk_query_sim", "rk_mark_refresh", "rk_calibration_copy", "rk_calibration_read", "rk_h2o_append", "rk_h2o_update", "rk_h2o_step"]
 
 RK_AGG_MAX, RK_AGG_MEAN, RK_AGG_FIRST = 0, 1, 2
 
@@ -124,6 +124,8 @@ def _load(path: str = LIB_PATH) -> C.CDLL:
     l.rk_query_sim.argtypes = [G, P, P, C.c_float, I32, P, P, P]
     l.rk_calibration_copy.restype = C.c_int
     l.rk_calibration_copy.argtypes = [P, P, SZ, P]
+    l.rk_calibration_read.restype = C.c_int
+    l.rk_calibration_read.argtypes = [P, SZ, P, P]
     l.rk_mark_refresh.restype = C.c_int
     l.rk_mark_refresh.argtypes = [G, P, P, P, I32, P]
     l.rk_h2o_append.argtypes = [G, _H2oState, P, P, P, I32, P]
@@ -536,6 +538,20 @@ def rk_mark_refresh(geom: Geom, seq_lens, tail_start, pred=None, pred_val: int =
         C.byref(geom.c()), _dev(seq_lens, torch.int32, "seq_lens", (B,)),
         _dev(tail_start, torch.int32, "tail_start", (B,)),
         _dev(pred, torch.int32, "pred", (B,), optional=True), int(pred_val), _stream(stream)))
+
+
+def rk_calibration_read(src: torch.Tensor, sink: torch.Tensor, nbytes: int = None, offset: int = 0, stream=None) -> int:
+    """Reads nbytes of src from byte `offset` on (default: all of it) and keeps nothing; returns the bytes read.
+    sink: one int32 in GPU memory."""
+    if not isinstance(src, torch.Tensor) or not src.is_cuda or not src.is_contiguous():
+        raise ValueError("src must be a contiguous tensor in GPU memory")
+    total = src.numel() * src.element_size()
+    nbytes = total - offset if nbytes is None else int(nbytes)
+    if offset < 0 or nbytes <= 0 or offset + nbytes > total or offset % 16 or nbytes % 16:
+        raise ValueError("the range read must lie inside src and be a multiple of 16 bytes")
+    _check("rk_calibration_read", lib.rk_calibration_read(src.data_ptr() + offset, nbytes,
+                                                          _dev(sink, torch.int32, "sink", (1,)), _stream(stream)))
+    return nbytes
 
 
 def rk_calibration_copy(dst: torch.Tensor, src: torch.Tensor, stream=None) -> int:

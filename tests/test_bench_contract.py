@@ -29,7 +29,7 @@ def test_bench_json_line_small_workload(launch):
     assert len(lines) == 1
     d = json.loads(lines[0])
     for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
-                "vs_baseline", "dtype", "data", "config", "roofline", "roofline_partial", "copy_GBps", "cpu_baseline"):
+                "vs_baseline", "dtype", "data", "config", "roofline", "roofline_partial", "copy_GBps", "read_GBps", "cpu_baseline"):
         assert key in d, key
     assert d["n_gpus"] == 1 and d["steps"] == 12 and d["warmup"] == 2 and d["higher_is_better"] is False
     assert d["config"]["workload"] == "cfg1_llama_2k" and d["value"] > 0
@@ -39,6 +39,7 @@ def test_bench_json_line_small_workload(launch):
             assert key in d[block], (block, key)
         assert d[block]["bound"] == "hbm" and 0 < d[block]["frac"] < 1
     assert d["copy_GBps"] > 0
+    assert d["read_GBps"]["one_launch_1GiB"] > 0 and d["read_GBps"]["launches_of_full_attn_kv_bytes"] > 0
     for key in ("value", "unit", "cores", "kind", "sample"):
         assert key in d["cpu_baseline"], key
     assert d["cpu_baseline"]["kind"] == "oracle" and d["cpu_baseline"]["value"] > 0

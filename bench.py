@@ -432,7 +432,7 @@ def run_workload(args, workload, light):
     achieved = algo_bytes / (split_us * 1e-6) / 1e9
     # HBM traffic of that kernel from profiler byte counters, when a committed PMC summary exists
     traffic, traffic_source = profile_traffic(w.name, "attn_split")
-    roofline = {"bound": "hbm", "kernel": "rk::attn_split_kernel<%d, 4, true, false, false, false> (first kernel of rk_full_attn when weights are returned)" % w.group,
+    roofline = {"bound": "hbm", "kernel": "rk::attn_split_kernel<%d, 4, true, false, false, false, false> (first kernel of rk_full_attn when weights are returned)" % w.group,
                 "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                 "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic, "traffic_source": traffic_source,
                 "avg_launch_us": round(split_us, 2), "launches": n_roof_launches, "algorithmic_bytes": algo_bytes}
@@ -443,7 +443,7 @@ def run_workload(args, workload, light):
     partial_bytes = 2 * Hkv * D * 2 * (sel_rows + recent_rows)
     partial_us = graph_us(partial_call, reps=8)
     p_traffic, p_source = profile_traffic(w.name, "partial_attn")
-    roofline_partial = {"bound": "hbm", "kernel": "rk::attn_split_kernel<%d, 4, false, true, false, %s> (rk_partial_attn)" % (w.group, "true" if w.group <= 4 else "false"),
+    roofline_partial = {"bound": "hbm", "kernel": "rk::attn_split_kernel<%d, 4, false, true, false, %s, false> (rk_partial_attn)" % (w.group, "true" if w.group <= 4 else "false"),
                         "achieved": round(partial_bytes / (partial_us * 1e-6) / 1e9, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                         "frac": round(partial_bytes / (partial_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),
                         "traffic": p_traffic, "traffic_source": p_source, "avg_launch_us": round(partial_us, 2),

@@ -13,6 +13,7 @@ The git commit the profiled tree was built from is recorded in both.
 from __future__ import annotations
 
 import collections
+import re
 import csv
 import json
 import os
@@ -22,11 +23,15 @@ import sys
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
+# attn_split_kernel<G, NW, EMIT, TWO_SEG, LAZY, TAGGED, TRIG>: the first kernel of a full step, and the partial step without the trigger inside
+FULL_KERNEL = r"attn_split_kernel<\d+, 4, true, false, false, false, false>"
+PARTIAL_KERNEL = r"attn_split_kernel<\d+, 4, false, true, false, (true|false), false>"
 LEGEND = [
-    ("attn_split_kernel<G, 4, true, false, false, false>", "streams C_f once and emits raw scores: first kernel of rk_full_attn (weights returned), rk_full_attn_select, rk_full_attn_deferred; rk_full_attn_scores launches it alone (the roofline measurement)"),
-    ("attn_split_kernel<G, 4, false, true, false, true>", "rk_partial_attn, groups of up to 4 heads: one launch, tagged partial results merged by the last workgroup"),
-    ("attn_split_kernel<G, 4, false, true, false, false>", "rk_partial_attn, larger groups (and rk_partial_attn_static): one launch, ticketed merge"),
-    ("attn_split_kernel<G, 4, false, false, false, true>", "rk_full_attn without weights over short rows: one launch, merged inside"),
+    ("attn_split_kernel<G, 4, true, false, false, false, false>", "streams C_f once and emits raw scores: first kernel of rk_full_attn (weights returned), rk_full_attn_select, rk_full_attn_deferred; rk_full_attn_scores launches it alone (the roofline measurement)"),
+    ("attn_split_kernel<G, 4, false, true, false, true, false>", "rk_partial_attn, groups of up to 4 heads: one launch, tagged partial results merged by the last workgroup"),
+    ("attn_split_kernel<G, 4, false, true, false, false, false>", "rk_partial_attn, larger groups (and rk_partial_attn_static): one launch, ticketed merge"),
+    ("attn_split_kernel<G, 4, false, true, false, *, true>", "rk_partial_attn_triggered: the partial step of a trigger test step, with the query-similarity test inside"),
+    ("attn_split_kernel<G, 4, false, false, false, true, false>", "rk_full_attn without weights over short rows: one launch, merged inside"),
     ("merge_normalise_kernel", "output merge of rk_full_attn / rk_full_attn_deferred (+ weights in place for rk_full_attn)"),
     ("finish_pool_kernel<G>", "second kernel of rk_full_attn_select: merge, weights, group max, max-pool, histogram"),
     ("pool_batched_kernel<G>", "pooling tiles of the finishing kernel for all layers in one launch (rk_refresh_batched)"),
@@ -71,10 +76,10 @@ def kernel_trace(workload, layers, stats_csv, bench_json, dispatch_csv=None):
         for r in csv.DictReader(open(dispatch_csv)):
             per[short(r["Kernel_Name"])].append((int(r["Start_Timestamp"]), (int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3))
         bench = json.loads(open(bench_json).read().strip().splitlines()[-1])
-        for key, block in (("true, false, false, false>", "roofline"), ("false, true, false", "roofline_partial")):
+        for key, block in ((FULL_KERNEL, "roofline"), (PARTIAL_KERNEL, "roofline_partial")):
             n = int(bench[block]["launches"])
             for k, v in per.items():
-                if "attn_split_kernel" in k and key in k:
+                if re.search(key, k):
                     v.sort()
                     if block == "roofline":
                         last = [d for _, d in v[-n:]]          # the roofline graph replays are the last launches of this kernel
@@ -116,9 +121,9 @@ def pmc(workload, layers, fetch_csv, write_csv, copy_bytes):
             continue
         a, b = st.median(f[k]), st.median(w.get(k, [0.0]))
         out.append("%-60s %6d %14.1f %14.1f %12.2f %12.2f" % (k[-60:], len(f[k]), a, b, a * 1024 * fs / 1e6, b * 1024 * wsc / 1e6))
-        if "attn_split_kernel" in k and "true, false, false, false>" in k:
+        if re.search(FULL_KERNEL, k):
             js["attn_split"] = {"kernel": k, "fetch_kib": a, "write_kib": b}
-        if "attn_split_kernel" in k and ", false, true, false, " in k:
+        if re.search(PARTIAL_KERNEL, k):
             js["partial_attn"] = {"kernel": k, "fetch_kib": a, "write_kib": b}
     out += ["", "(a kernel launched with several shapes in one run, e.g. the first kernel of a full step over the policy runs'",
             " short caches, shows the median shape; the bench's own shape dominates the dispatch counts above)"]

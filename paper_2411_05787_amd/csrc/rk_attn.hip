@@ -1343,7 +1343,7 @@ void finish_pool_kernel(const AttnParams p, const float* __restrict__ scores, in
 // passed by value.
 // With many layers in one launch the workgroups come in rounds and each pays its own chain of
 // round trips (statistics, lse, scores, histogram): larger tiles, fewer rounds.
-constexpr int kBatchedPoolTile = 1024;       // (512: 38.8, 1024: 38.4, 2048: 38.8 us per layer of a full step at 32k)
+constexpr int kBatchedPoolTile = 2048;       // (the launch alone, 32 layers of 33k rows or 8 of 131k: 1024: 81, 2048: 72, 4096: 85, 8192: 103 us)
 
 struct PoolBatch {
     const float* part_ml[kBatchLayers];

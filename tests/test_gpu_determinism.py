@@ -190,3 +190,65 @@ def test_topk_select_long_rows_repeats_bit_for_bit(rk):
     torch.cuda.synchronize()
     i_ref2, _ = oracle.topk_select(w2.numpy(), [n], Hkv, k, 7)
     assert (idx2.cpu().numpy() == i_ref2).all()
+
+
+def test_partial_attn_triggered_repeats_bit_for_bit(rk):
+    """The partial step with the query-similarity test inside: sequences that ask for a full step and
+    sequences that do not in one batch; every call gives the same output, similarity, decision and
+    reference, and leaves the test's ticket clean for the next one."""
+    say("determinism: rk_partial_attn_triggered", N_CALLS, "calls")
+    B, Hq, Hkv, k = 4, 32, 8, 1024
+    lens, recent = [9000, 5000, 7000, 4100], [5, 1, 0, 8]
+    scale = float(np.float32(1 / np.sqrt(128)))
+    geom = rk.Geom(B, Hq, Hkv, 128, scale)
+    q, K, V, tail, idx, cap = partial_inputs(rk, 92, B, Hq, Hkv, k, lens, recent)
+    Kd, Vd, qd = K.cuda(), V.cuda(), q.cuda()
+    sK = torch.zeros(B, Hkv, k, 128, dtype=torch.bfloat16, device="cuda"); sV = torch.zeros_like(sK)
+    rk.rk_gather_small_kv(geom, Kd, Vd, idx.cuda(), k, sK, sV)
+    ws = rk.Workspace(geom, cap, k)
+    tail_d = torch.tensor(tail, dtype=torch.int32, device="cuda")
+    lens_d = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    ref = torch.randn(B, 128, generator=torch.Generator().manual_seed(3))
+    ref[0] = q[0].float().mean(0); ref[2] = q[2].float().mean(0) * 0.5          # sequences 0 and 2: no full step
+    s_ref, n_ref, r_ref = oracle.query_sim(gen.bf16_bits(q), ref.double().numpy(), 0.5, False)
+    assert n_ref.tolist() == [False, True, False, True]
+    outs = torch.full((N_CALLS, B, Hq, 128), 3.0, dtype=torch.bfloat16, device="cuda")
+    refs = ref.cuda().repeat(N_CALLS, 1, 1).contiguous()
+    sims = torch.zeros(N_CALLS, B, device="cuda")
+    needs = torch.full((N_CALLS, B), -1, dtype=torch.int32, device="cuda")
+    for i in range(N_CALLS):
+        rk.rk_partial_attn_triggered(geom, qd, sK, sV, k, Kd, Vd, tail_d, lens_d, 8, outs[i], refs[i], 0.5, sims[i], needs[i],
+                                     workspace=ws)
+    torch.cuda.synchronize()
+    for what, t in (("out", outs.view(torch.int16)), ("q_ref", refs.view(torch.int32)), ("sim", sims.view(torch.int32)),
+                    ("need_full", needs)):
+        bad = first_mismatch(t)
+        assert bad is None, "%s of call %d differs from call 0" % (what, bad)
+    assert (needs[0].cpu().numpy().astype(bool) == n_ref).all()
+    assert np.abs(refs[0].cpu().numpy() - r_ref).max() < 1e-6
+    rK = np.zeros((B, Hkv, k, 128), dtype=np.uint16); rV = rK.copy()
+    oracle.gather_small_kv(gen.bf16_bits(K), gen.bf16_bits(V), idx.numpy(), rK, rV)
+    o_ref = oracle.partial_attn(gen.bf16_bits(q), rK, rV, k, gen.bf16_bits(K), gen.bf16_bits(V), tail, lens, scale)
+    got = gen.bf16_bits(outs[0])
+    assert_out_close(got[~n_ref], o_ref[~n_ref], "sequences without a full step")
+    assert (got[n_ref] == gen.bf16_bits(torch.tensor(3.0, dtype=torch.bfloat16))).all()
+
+
+def test_topk_select_128k_runs_repeat_bit_for_bit(rk):
+    """131072 positions, K = 8192: 32 workgroups list runs of equal pooled scores, the last one ranks them."""
+    n_calls = 500
+    say("determinism: rk_topk_select over 131072 positions", n_calls, "calls")
+    B, Hq, Hkv, n, k = 1, 8, 2, 131072, 8192
+    w = gen.make_weights(B, Hq, n, seed=14, kind="lognormal")
+    geom = rk.Geom(B, Hq, Hkv, 128, 1.0)
+    ws = rk.Workspace(geom, n, k)
+    sl = torch.tensor([n], dtype=torch.int32, device="cuda")
+    wd = w.cuda()
+    idxs = torch.full((n_calls, B, Hkv, k), -5, dtype=torch.int32, device="cuda")
+    for i in range(n_calls):
+        rk.rk_topk_select(geom, wd, sl, n, k, 7, idxs[i], workspace=ws)
+    torch.cuda.synchronize()
+    bad = first_mismatch(idxs)
+    assert bad is None, "idx of call %d differs from call 0" % bad
+    i_ref, _ = oracle.topk_select(w.numpy(), [n], Hkv, k, 7)
+    assert (idxs[0].cpu().numpy() == i_ref).all()

@@ -1677,7 +1677,7 @@ static int launch_partial(const rk_geom* geom, const void* q, rk_kv small, int32
     // a few rows decoded since the refresh: a workgroup of their own (see the kernel), the others split the small cache
     // (ticketed merge: a 17th partial result costs it a second round trip, more than the tail workgroup gains)
     p.tail_wg = (tagged && lazy_idx == nullptr && n_sel > 0 && max_recent <= kMinChunk) ? 1 : 0;
-    p.nch = merged_split_workgroups(n_sel, p.tail_wg ? 0 : max_recent, (int64_t)geom->batch * geom->n_kv_heads);
+    p.nch = merged_split_workgroups(n_sel, p.tail_wg ? 0 : max_recent, (int64_t)geom->batch * geom->n_kv_heads, !tagged);
     if (!tagged && p.nch > p.max_chunks) p.nch = p.max_chunks;      // fewer, longer chunks: what the workspace has slots for
     if (p.nch > kMergeChunks || p.nch < 1) return RK_ERR_WORKSPACE;
     if (lazy_idx != nullptr) {      // rows of the selection come from the full cache and are written to `small` on the way
@@ -1805,7 +1805,7 @@ static size_t carve_static(const rk_geom* g, int32_t n_sel, int32_t max_recent, 
     const size_t problems = (size_t)g->batch * g->n_kv_heads;
     const size_t G = (size_t)(g->n_q_heads / g->n_kv_heads);
     *w = Workspace{};
-    w->max_chunks = merged_split_workgroups(n_sel, max_recent, (int64_t)problems);     // the launch's own count
+    w->max_chunks = merged_split_workgroups(n_sel, max_recent, (int64_t)problems, true);     // the launch's own count (ticketed merge)
     size_t off = 0;
     w->counters = (int32_t*)(base + off); off += (size_t)kStaticMaxProblems * kCounterStride * sizeof(int32_t);
     w->lse = (float*)(base + off);        off += align_up((size_t)g->batch * g->n_q_heads * sizeof(float), 256);

@@ -67,7 +67,13 @@ static inline int split_workgroups(int64_t max_rows, int64_t n_problems, int lim
 // 6: 33.8, 16: 40.0;  8 x 4096: 2: 33.0, 4: 28.5, 12: 32.1, 32: 45.1;  4 x 2048: 4: 16.5, 8: 13.7,
 // 16: 14.1;  64 x 512: 1: 30.1, 2: 33.6), so the upper bound is 256 workgroups in all, not the 768 of
 // the kernels that leave the merge to a second launch.
-static inline int merged_split_workgroups(int64_t rows, int64_t tail_rows, int64_t n_problems) {
+// two_batches: the ticketed merge, which requests two batches of 16 partial outputs before it waits
+// for the first: 32 partial results cost it one round trip, so where 16 workgroups would leave every
+// wavefront two or more tiles, 32 halve the tiles for nothing (one sequence, 4 KV heads, 7 heads per
+// group: K = 4096 10.4 -> 10.0 us, K = 8192 13.8 -> 12.5; 48 and 64 workgroups: 10.3 / 13.0 and more; the
+// tagged merge reads 20 partial results per round trip and more rows per result: 32 cost it 16.2
+// against 13.0 us at K = 8192, groups of 4).
+static inline int merged_split_workgroups(int64_t rows, int64_t tail_rows, int64_t n_problems, bool two_batches = false) {
     const int64_t all_rows = rows + tail_rows;
     const int64_t counted = (rows > 0 && tail_rows <= 32) ? rows : all_rows;
     const int64_t problems = n_problems > 0 ? n_problems : 1;
@@ -77,6 +83,7 @@ static inline int merged_split_workgroups(int64_t rows, int64_t tail_rows, int64
     if (per > kMergeChunks) per = kMergeChunks;
     if (per < 1) per = 1;
     const int64_t tiles = (all_rows + 31) / 32;
+    if (two_batches && per >= 32 && tiles > 4 * 16) return 32;
     for (int64_t n = 16; n < per; n += 16)
         if ((tiles + 4 * n - 1) / (4 * n) <= 5) return (int)n;
     return (int)per;

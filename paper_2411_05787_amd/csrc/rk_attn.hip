@@ -1678,6 +1678,8 @@ static int launch_partial(const rk_geom* geom, const void* q, rk_kv small, int32
     // (ticketed merge: a 17th partial result costs it a second round trip, more than the tail workgroup gains)
     p.tail_wg = (tagged && lazy_idx == nullptr && n_sel > 0 && max_recent <= kMinChunk) ? 1 : 0;
     p.nch = merged_split_workgroups(n_sel, p.tail_wg ? 0 : max_recent, (int64_t)geom->batch * geom->n_kv_heads, !tagged);
+    if (tagged && lazy_idx == nullptr && (int64_t)geom->batch * geom->n_kv_heads >= 32)      // many (sequence, KV head) pairs: see there
+        p.nch = batched_tagged_workgroups(p.tail_wg ? n_sel : n_sel + (int64_t)max_recent, p.tail_wg, (int64_t)geom->batch * geom->n_kv_heads);
     if (!tagged && p.nch > p.max_chunks) p.nch = p.max_chunks;      // fewer, longer chunks: what the workspace has slots for
     if (p.nch > kMergeChunks || p.nch < 1) return RK_ERR_WORKSPACE;
     if (lazy_idx != nullptr) {      // rows of the selection come from the full cache and are written to `small` on the way

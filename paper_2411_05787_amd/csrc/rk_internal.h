@@ -89,6 +89,29 @@ static inline int merged_split_workgroups(int64_t rows, int64_t tail_rows, int64
     return (int)per;
 }
 
+// The same for the tagged merge (groups of up to 4 heads) from 32 (sequence, KV head) pairs on.
+// With many pairs the launch is bound by what a CU gets through, not by one workgroup's chain:
+// it takes about (workgroups per CU, rounded up) x (tiles per wavefront + 1 for a workgroup's
+// fixed costs), plus a round trip of the merge per 20 partial results beyond the first 20.  A
+// total just above a multiple of the 256 CUs is what hurts: the few CUs with one workgroup more set
+// the time.  `tail` = 1: the rows decoded since the refresh have a workgroup of their own.
+// Measured, us per launch, old rule -> this one (8 KV heads, groups of 4): 16 sequences, K = 1024:
+// 22.1 -> 18.9; K = 2048: 37.1 -> 32.3; K = 4096: 68.3 -> 54.1; 8 sequences, K = 1024: 14.6 -> 12.8;
+// K = 2048: 23.7 -> 20.6; 4 sequences, K = 2048: 14.4 -> 13.0; K = 8192: 38.2 -> 29.9; 32 x 1024:
+// 38.3 -> 33.8 - 35.5; 64 x 512: 39.9 -> 35.0.
+static inline int batched_tagged_workgroups(int64_t rows, int tail, int64_t n_problems) {
+    const int64_t stretches = (rows + kMinChunk - 1) / kMinChunk;
+    const int64_t tiles = (rows + 31) / 32;
+    int64_t best = 1, best_cost = -1;
+    for (int64_t n = 1; n <= stretches && n <= kMergeChunks; ++n) {
+        const int64_t per_cu = ((n + tail) * n_problems + kComputeUnits - 1) / kComputeUnits;
+        const int64_t rounds = (tiles + 4 * n - 1) / (4 * n);
+        const int64_t cost = per_cu * (rounds + 1 + (n + tail - 1) / 20);
+        if (best_cost < 0 || cost < best_cost) { best = n; best_cost = cost; }
+    }
+    return (int)best;
+}
+
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 constexpr int kBatchLayers = 32;         // layers one batched launch (rk_refresh_batched) takes; more go in several launches

@@ -1673,11 +1673,15 @@ static int launch_partial(const rk_geom* geom, const void* q, rk_kv small, int32
     p.epochs = ws.epochs; p.tag_rows = ws.tag_rows;
     // Tagged hand-over where a wavefront merges one head (groups of up to 4); with two heads per
     // wavefront the ticketed form is the faster one (measured at 7 heads per group, 4096 rows: 9.9 against 10.7 us).
-    const bool tagged = ws.tag_rows != nullptr && G <= kSplitWaves;          // (the built-in scratch array has no tagged region)
+    // Rows enough for 32 workgroups: the ticketed form whatever the group (see two_batches_pay).
+    const bool wide = lazy_idx == nullptr && trig == nullptr &&
+                      two_batches_pay(n_sel, max_recent, (int64_t)geom->batch * geom->n_kv_heads);
+    const bool tagged = ws.tag_rows != nullptr && G <= kSplitWaves && !wide;          // (the built-in scratch array has no tagged region)
     // a few rows decoded since the refresh: a workgroup of their own (see the kernel), the others split the small cache
     // (ticketed merge: a 17th partial result costs it a second round trip, more than the tail workgroup gains)
     p.tail_wg = (tagged && lazy_idx == nullptr && n_sel > 0 && max_recent <= kMinChunk) ? 1 : 0;
-    p.nch = merged_split_workgroups(n_sel, p.tail_wg ? 0 : max_recent, (int64_t)geom->batch * geom->n_kv_heads, !tagged);
+    p.nch = merged_split_workgroups(n_sel, p.tail_wg ? 0 : max_recent, (int64_t)geom->batch * geom->n_kv_heads,
+                                    !tagged && lazy_idx == nullptr && (trig == nullptr || G > kSplitWaves));
     if (tagged && lazy_idx == nullptr && (int64_t)geom->batch * geom->n_kv_heads >= 32)      // many (sequence, KV head) pairs: see there
         p.nch = batched_tagged_workgroups(p.tail_wg ? n_sel : n_sel + (int64_t)max_recent, p.tail_wg, (int64_t)geom->batch * geom->n_kv_heads);
     if (!tagged && p.nch > p.max_chunks) p.nch = p.max_chunks;      // fewer, longer chunks: what the workspace has slots for

@@ -73,6 +73,14 @@ static inline int split_workgroups(int64_t max_rows, int64_t n_problems, int lim
 // group: K = 4096 10.4 -> 10.0 us, K = 8192 13.8 -> 12.5; 48 and 64 workgroups: 10.3 / 13.0 and more; the
 // tagged merge reads 20 partial results per round trip and more rows per result: 32 cost it 16.2
 // against 13.0 us at K = 8192, groups of 4).
+// (Groups of up to 4 heads: the tagged merge wins while 16 workgroups give a wavefront one tile, the
+// ticketed one with 32 workgroups beyond: K = 2048 7.5 / 7.7 us, 4096 9.8 / 9.3, 8192 13.0 / 12.5,
+// 16384 23.9 / 18.1; so where this is true the partial step takes the ticketed form whatever the group.)
+static inline bool two_batches_pay(int64_t rows, int64_t tail_rows, int64_t n_problems) {
+    const int64_t problems = n_problems > 0 ? n_problems : 1;
+    const int64_t main_rows = (rows > 0 && tail_rows <= kMinChunk) ? rows : rows + tail_rows;     // a few rows decoded since the refresh do not count
+    return (kComputeUnits + problems / 2) / problems >= 32 && (main_rows + 31) / 32 > 4 * 16;
+}
 static inline int merged_split_workgroups(int64_t rows, int64_t tail_rows, int64_t n_problems, bool two_batches = false) {
     const int64_t all_rows = rows + tail_rows;
     const int64_t counted = (rows > 0 && tail_rows <= 32) ? rows : all_rows;
@@ -83,7 +91,7 @@ static inline int merged_split_workgroups(int64_t rows, int64_t tail_rows, int64
     if (per > kMergeChunks) per = kMergeChunks;
     if (per < 1) per = 1;
     const int64_t tiles = (all_rows + 31) / 32;
-    if (two_batches && per >= 32 && tiles > 4 * 16) return 32;
+    if (two_batches && two_batches_pay(rows, tail_rows, n_problems)) return 32;
     for (int64_t n = 16; n < per; n += 16)
         if ((tiles + 4 * n - 1) / (4 * n) <= 5) return (int)n;
     return (int)per;

@@ -1682,7 +1682,7 @@ static int launch_partial(const rk_geom* geom, const void* q, rk_kv small, int32
     p.tail_wg = (tagged && lazy_idx == nullptr && n_sel > 0 && max_recent <= kMinChunk) ? 1 : 0;
     p.nch = merged_split_workgroups(n_sel, p.tail_wg ? 0 : max_recent, (int64_t)geom->batch * geom->n_kv_heads,
                                     !tagged && lazy_idx == nullptr && (trig == nullptr || G > kSplitWaves));
-    if (tagged && lazy_idx == nullptr && (int64_t)geom->batch * geom->n_kv_heads >= 32)      // many (sequence, KV head) pairs: see there
+    if (tagged && lazy_idx == nullptr && (int64_t)geom->batch * geom->n_kv_heads >= 16)      // many (sequence, KV head) pairs: see there
         p.nch = batched_tagged_workgroups(p.tail_wg ? n_sel : n_sel + (int64_t)max_recent, p.tail_wg, (int64_t)geom->batch * geom->n_kv_heads);
     if (!tagged && p.nch > p.max_chunks) p.nch = p.max_chunks;      // fewer, longer chunks: what the workspace has slots for
     if (p.nch > kMergeChunks || p.nch < 1) return RK_ERR_WORKSPACE;

@@ -97,7 +97,7 @@ static inline int merged_split_workgroups(int64_t rows, int64_t tail_rows, int64
     return (int)per;
 }
 
-// The same for the tagged merge (groups of up to 4 heads) from 32 (sequence, KV head) pairs on.
+// The same for the tagged merge (groups of up to 4 heads) from 16 (sequence, KV head) pairs on; first for 32 and more.
 // With many pairs the launch is bound by what a CU gets through, not by one workgroup's chain:
 // it takes about (workgroups per CU, rounded up) x (tiles per wavefront + 1 for a workgroup's
 // fixed costs), plus a round trip of the merge per 20 partial results beyond the first 20.  A
@@ -107,15 +107,24 @@ static inline int merged_split_workgroups(int64_t rows, int64_t tail_rows, int64
 // 22.1 -> 18.9; K = 2048: 37.1 -> 32.3; K = 4096: 68.3 -> 54.1; 8 sequences, K = 1024: 14.6 -> 12.8;
 // K = 2048: 23.7 -> 20.6; 4 sequences, K = 2048: 14.4 -> 13.0; K = 8192: 38.2 -> 29.9; 32 x 1024:
 // 38.3 -> 33.8 - 35.5; 64 x 512: 39.9 -> 35.0.
+// With 16 to 31 pairs (2 or 3 sequences of 8 KV heads) the workgroups that share a CU overlap their
+// fixed costs, so only the tiles count twice there: (tiles per wavefront + 1) + (workgroups per CU - 1) x
+// tiles per wavefront, fewer tiles per wavefront on a tie (3 sequences, K = 2048: 288 workgroups 12.7 -> 408
+// workgroups 10.4; K = 4096: 17.5 -> 14.7; K = 8192: 29.7 -> 25.2; 2 sequences, K = 4096: 272 workgroups
+// 13.9 -> 192 or 256 workgroups 12.3; K = 8192: 22.1 -> 18.1 - 18.4; K = 2048 stays at 272 workgroups, 9.8).
 static inline int batched_tagged_workgroups(int64_t rows, int tail, int64_t n_problems) {
     const int64_t stretches = (rows + kMinChunk - 1) / kMinChunk;
     const int64_t tiles = (rows + 31) / 32;
-    int64_t best = 1, best_cost = -1;
+    int64_t best = 1, best_cost = -1, best_rounds = 0;
     for (int64_t n = 1; n <= stretches && n <= kMergeChunks; ++n) {
         const int64_t per_cu = ((n + tail) * n_problems + kComputeUnits - 1) / kComputeUnits;
         const int64_t rounds = (tiles + 4 * n - 1) / (4 * n);
-        const int64_t cost = per_cu * (rounds + 1 + (n + tail - 1) / 20);
-        if (best_cost < 0 || cost < best_cost) { best = n; best_cost = cost; }
+        const int64_t fixed = 1 + (n + tail - 1) / 20;
+        const bool few = n_problems < 32;
+        const int64_t cost = few ? rounds + fixed + (per_cu - 1) * rounds : per_cu * (rounds + fixed);
+        if (best_cost < 0 || cost < best_cost || (few && cost == best_cost && rounds < best_rounds)) {      // ties (few pairs): fewer tiles per wavefront
+            best = n; best_cost = cost; best_rounds = rounds;
+        }
     }
     return (int)best;
 }

@@ -123,8 +123,10 @@ def pmc(workload, layers, fetch_csv, write_csv, copy_bytes):
         out.append("%-60s %6d %14.1f %14.1f %12.2f %12.2f" % (k[-60:], len(f[k]), a, b, a * 1024 * fs / 1e6, b * 1024 * wsc / 1e6))
         if re.search(FULL_KERNEL, k):
             js["attn_split"] = {"kernel": k, "fetch_kib": a, "write_kib": b}
-        if re.search(PARTIAL_KERNEL, k):
-            js["partial_attn"] = {"kernel": k, "fetch_kib": a, "write_kib": b}
+        if re.search(PARTIAL_KERNEL, k) and len(f[k]) > js.get("partial_attn", {}).get("dispatches", 0):
+            # (both hand-overs can be in one run: the comparison policies' short caches take the tagged one; the bench's own
+            # partial steps are the form with the most dispatches)
+            js["partial_attn"] = {"kernel": k, "fetch_kib": a, "write_kib": b, "dispatches": len(f[k])}
     out += ["", "(a kernel launched with several shapes in one run, e.g. the first kernel of a full step over the policy runs'",
             " short caches, shows the median shape; the bench's own shape dominates the dispatch counts above)"]
     open(os.path.join(ROOT, "profiles", "bench_%s_pmc.txt" % workload), "w").write("\n".join(out) + "\n")

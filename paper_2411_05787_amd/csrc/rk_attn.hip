@@ -1330,11 +1330,11 @@ void finish_pool_body(const AttnParams& p, const float* __restrict__ scores, int
     }
 }
 
-template <int G>
+template <int G, int TILE>
 __global__ __launch_bounds__(256)
 void finish_pool_kernel(const AttnParams p, const float* __restrict__ scores, int64_t s_stride, int half, int agg,
                         float* __restrict__ pooled, int64_t pooled_stride, uint32_t* __restrict__ hist) {
-    finish_pool_body<G, kPoolTile>(p, scores, s_stride, half, agg, pooled, pooled_stride, hist, (int)blockIdx.z);
+    finish_pool_body<G, TILE>(p, scores, s_stride, half, agg, pooled, pooled_stride, hist, (int)blockIdx.z);
 }
 
 // The pooling half of the finishing kernel for several layers in one launch (grid z = layer *
@@ -1377,9 +1377,13 @@ static int launch_pool_batched(const PoolBatch& tab, const AttnParams& p, int n,
 template <int G>
 static int launch_finish_pool(const AttnParams& p, int batch, int32_t max_len, const Workspace& ws, int half, int agg,
                               hipStream_t st) {
-    dim3 grid((p.out != nullptr ? G : 0) + (max_len + kPoolTile - 1) / kPoolTile, p.Hkv, batch);
+    const int tile = pool_tile_for(max_len);
+    dim3 grid((p.out != nullptr ? G : 0) + (max_len + tile - 1) / tile, p.Hkv, batch);
     const int64_t stride = pooled_row_stride(max_len);
-    hipLaunchKernelGGL((finish_pool_kernel<G>), grid, dim3(256), 0, st, p, ws.scores, stride, half, agg, ws.pooled, stride, ws.hist);
+    if (tile == kPoolTileLong)
+        hipLaunchKernelGGL((finish_pool_kernel<G, kPoolTileLong>), grid, dim3(256), 0, st, p, ws.scores, stride, half, agg, ws.pooled, stride, ws.hist);
+    else
+        hipLaunchKernelGGL((finish_pool_kernel<G, kPoolTile>), grid, dim3(256), 0, st, p, ws.scores, stride, half, agg, ws.pooled, stride, ws.hist);
     return launch_status();
 }
 

@@ -135,7 +135,12 @@ constexpr int kBatchLayers = 32;         // layers one batched launch (rk_refres
 constexpr int kHistBins = 2048;          // first-level histogram of the selection: top 11 key bits
 constexpr int kMaxCandidates = 16384;    // most candidates the fast selection path sorts in LDS
 constexpr int kHistShift = 32 - 11;      // key bits below the first-level histogram bin
-constexpr int kPoolTile = 512;           // positions one workgroup pools and histograms
+constexpr int kPoolTile = 512;           // positions one workgroup pools and histograms ...
+constexpr int kPoolTileLong = 1024;      // ... over rows of kPoolLongFrom positions or more: there the chip is full
+constexpr int kPoolLongFrom = 98304;     // anyway and fewer, larger tiles win (per call at 131072 positions: selection
+                                         // 38.2 -> 35.6 us, full step with selection 151.7 -> 144.9; at 32k and 64k
+                                         // larger tiles lose: 17.4 -> 18.4 and 21.6 -> 22.2 us)
+static inline int pool_tile_for(int64_t max_len) { return max_len >= kPoolLongFrom ? kPoolTileLong : kPoolTile; }
 
 // Candidate slots per (sequence, KV head) of the selection: the K winners plus the rest of the
 // histogram bin that holds the K-th score.

@@ -3,7 +3,7 @@
 // The order is decided on the order-preserving 32-bit image of the pooled score P (integer
 // compares only, so the result is exact): larger image first, equal images by lower position.
 //
-// Kernel 1, whole chip (pool_hist_kernel): P[j] = max over the G heads of the group and over the
+// Kernel 1, whole chip (pool_hist_kernel, tiles of 512 positions, 1024 from 98304 positions on): P[j] = max over the G heads of the group and over the
 //   pooling window, staged through LDS so that every weight is read once; P is stored and its
 //   top 11 image bits are histogrammed (LDS, then one global atomic per non-empty bin).
 // Kernel 2 (select_kernel), workgroups of 1024 threads: from the histogram, the bin b1 that holds
@@ -61,6 +61,7 @@ __device__ __forceinline__ uint64_t item_of(uint32_t key, int j, int len = 1) {
 __device__ __forceinline__ int item_pos(uint64_t item) { return (int)(kPosTop - ((uint32_t)item >> 4)); }
 __device__ __forceinline__ uint32_t item_len(uint64_t item) { return ((uint32_t)item & 15u) + 1u; }
 
+template <int TILE>
 __global__ __launch_bounds__(256)
 void pool_hist_kernel(const float* __restrict__ weights, int64_t w_stride, const int32_t* seq_lens,
                       int32_t max_len, int32_t Hq, int32_t Hkv, int32_t G, int32_t half, int32_t agg,
@@ -69,12 +70,12 @@ void pool_hist_kernel(const float* __restrict__ weights, int64_t w_stride, const
     const int g = blockIdx.y, b = blockIdx.z;
     if (pred != nullptr && pred[b] != pred_val) return;
     const int len = min(seq_lens[b], max_len);
-    const int j0 = blockIdx.x * kPoolTile;
+    const int j0 = blockIdx.x * TILE;
     if (j0 >= len) return;
-    __shared__ float sA[kPoolTile + RK_MAX_POOL_W - 1];
+    __shared__ float sA[TILE + RK_MAX_POOL_W - 1];
     __shared__ uint32_t sH[kHistBins];
     const float* wg = weights + ((int64_t)b * Hq + (int64_t)g * G) * w_stride;
-    const int span = kPoolTile + 2 * half;
+    const int span = TILE + 2 * half;
     for (int i = threadIdx.x; i < kHistBins; i += 256) sH[i] = 0;
     for (int i = threadIdx.x; i < span; i += 256) {
         const int j = j0 - half + i;
@@ -88,7 +89,7 @@ void pool_hist_kernel(const float* __restrict__ weights, int64_t w_stride, const
     __syncthreads();
     const int64_t bg = (int64_t)b * Hkv + g;
     float* out = pooled + bg * pooled_stride;
-    for (int i = threadIdx.x; i < kPoolTile; i += 256) {
+    for (int i = threadIdx.x; i < TILE; i += 256) {
         const int j = j0 + i;
         if (j < len) {
             float m = sA[i];
@@ -732,10 +733,16 @@ int pool_stage(const rk_geom* geom, const float* weights, int64_t w_stride, cons
                int32_t max_len, int32_t pool_w, int32_t agg, const int32_t* pred, int32_t pred_val,
                const Workspace& ws, hipStream_t st) {
     const int G = geom->n_q_heads / geom->n_kv_heads;
-    dim3 pgrid((max_len + kPoolTile - 1) / kPoolTile, geom->n_kv_heads, geom->batch);
-    hipLaunchKernelGGL(pool_hist_kernel, pgrid, dim3(256), 0, st, weights, w_stride, seq_lens, max_len,
-                       geom->n_q_heads, geom->n_kv_heads, G, (pool_w - 1) / 2, agg, ws.pooled, pooled_row_stride(max_len), ws.hist,
-                       pred, pred_val);
+    const int tile = pool_tile_for(max_len);
+    dim3 pgrid((max_len + tile - 1) / tile, geom->n_kv_heads, geom->batch);
+    if (tile == kPoolTileLong)
+        hipLaunchKernelGGL((pool_hist_kernel<kPoolTileLong>), pgrid, dim3(256), 0, st, weights, w_stride, seq_lens, max_len,
+                           geom->n_q_heads, geom->n_kv_heads, G, (pool_w - 1) / 2, agg, ws.pooled, pooled_row_stride(max_len), ws.hist,
+                           pred, pred_val);
+    else
+        hipLaunchKernelGGL((pool_hist_kernel<kPoolTile>), pgrid, dim3(256), 0, st, weights, w_stride, seq_lens, max_len,
+                           geom->n_q_heads, geom->n_kv_heads, G, (pool_w - 1) / 2, agg, ws.pooled, pooled_row_stride(max_len), ws.hist,
+                           pred, pred_val);
     return launch_status();
 }
 

@@ -3,9 +3,10 @@
 // The order is decided on the order-preserving 32-bit image of the pooled score P (integer
 // compares only, so the result is exact): larger image first, equal images by lower position.
 //
-// Kernel 1, whole chip (pool_hist_kernel, tiles of 512 positions, 1024 from 98304 positions on): P[j] = max over the G heads of the group and over the
-//   pooling window, staged through LDS so that every weight is read once; P is stored and its
-//   top 11 image bits are histogrammed (LDS, then one global atomic per non-empty bin).
+// Kernel 1, whole chip (pool_hist_kernel; tiles of 512 positions, of 1024 from 98304 positions on):
+//   P[j] = max over the G heads of the group and over the pooling window, staged through LDS so
+//   that every weight is read once; P is stored and its top 11 image bits are histogrammed (LDS,
+//   then one global atomic per non-empty bin).
 // Kernel 2 (select_kernel), workgroups of 1024 threads: from the histogram, the bin b1 that holds
 //   the K-th largest score; every position in that bin or a higher one is a candidate (the K
 //   winners plus the rest of one bin).  What is listed and ranked are runs of candidates: up to

@@ -211,6 +211,10 @@ def make_weights(batch: int, n_q_heads: int, length: int, seed: int, kind: str =
 
     lognormal: exp(N(0,1)) normalised per row by its sum (shape of real softmax rows).
     ties: values drawn from 8 distinct levels, so equal scores are the norm.
+    plateaus: about 50 stretches of one value each (runs of equal pooled scores far longer than the window).
+    narrow: all values within one part in a thousand of 0.5 (one bin of any coarse histogram).
+    spiky: one position in a hundred carries a value of order 1, the rest of order 1e-6.
+    zeros: all zero (every position ties with every other).
     """
     g = torch.Generator(device="cpu")
     g.manual_seed((BASE_SEED + 7919 * seed) % (2 ** 63 - 1))
@@ -219,6 +223,18 @@ def make_weights(batch: int, n_q_heads: int, length: int, seed: int, kind: str =
         x = x / x.sum(dim=-1, keepdim=True)
     elif kind == "ties":
         x = torch.randint(0, 8, (batch, n_q_heads, length), generator=g).to(torch.float64) / 8.0
+    elif kind == "plateaus":
+        seg = max(length // 50, 1)
+        x = torch.rand(batch, n_q_heads, (length + seg - 1) // seg, generator=g, dtype=torch.float64)
+        x = x.repeat_interleave(seg, dim=-1)[..., :length]
+    elif kind == "narrow":
+        x = 0.5 + torch.rand(batch, n_q_heads, length, generator=g, dtype=torch.float64) * 1e-3
+    elif kind == "spiky":
+        x = torch.rand(batch, n_q_heads, length, generator=g, dtype=torch.float64) * 1e-6
+        where = torch.randint(0, length, (batch, n_q_heads, max(length // 100, 1)), generator=g)
+        x.scatter_(-1, where, torch.rand(where.shape, generator=g, dtype=torch.float64))
+    elif kind == "zeros":
+        x = torch.zeros(batch, n_q_heads, length, dtype=torch.float64)
     else:
         raise ValueError(kind)
     return x.to(torch.float32).to(torch.device(device))

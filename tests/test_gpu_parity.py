@@ -175,6 +175,11 @@ TOPK_CASES = [
     ("runs_fit_one_workgroup", 2, 4, 2, [8100, 6000], 1100, 7, "lognormal"),
     ("dense_one_workgroup_ties", 1, 4, 1, [8192], 1500, 7, "ties"),
     ("pool3_runs_cut_by_k", 1, 2, 2, [20000], 999, 3, "lognormal"),
+    # score distributions far from a softmax row's: stretches of one value, one histogram bin, rare spikes, all equal
+    ("plateaus_70k", 2, 4, 2, [70000, 41234], 5000, 7, "plateaus"),
+    ("narrow_band_40k", 1, 4, 1, [40000], 8192, 7, "narrow"),
+    ("spiky_140k", 1, 7, 1, [140000], 2048, 15, "spiky"),
+    ("all_zero_9k", 2, 2, 2, [9000, 5], 1000, 7, "zeros"),
 ]
 
 

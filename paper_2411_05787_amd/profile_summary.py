@@ -33,7 +33,7 @@ LEGEND = [
     ("attn_split_kernel<G, 4, false, true, false, *, true>", "rk_partial_attn_triggered: the partial step of a trigger test step, with the query-similarity test inside"),
     ("attn_split_kernel<G, 4, false, false, false, true, false>", "rk_full_attn without weights over short rows: one launch, merged inside"),
     ("merge_normalise_kernel", "output merge of rk_full_attn / rk_full_attn_deferred (+ weights in place for rk_full_attn)"),
-    ("finish_pool_kernel<G>", "second kernel of rk_full_attn_select: merge, weights, group max, max-pool, histogram"),
+    ("finish_pool_kernel<G, TILE>", "second kernel of rk_full_attn_select: merge, weights, group max, max-pool, histogram"),
     ("pool_batched_kernel<G>", "pooling tiles of the finishing kernel for all layers in one launch (rk_refresh_batched)"),
     ("select_kernel / select_batched_kernel", "top-K: per call / for all layers in one launch"),
     ("gather_rows_kernel / gather_rows_batched_kernel", "rk_gather_small_kv: per call / for all layers in one launch"),

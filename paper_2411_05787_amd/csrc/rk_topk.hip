@@ -263,10 +263,10 @@ __device__ void bitonic_sort_desc(uint64_t* sKeys, int npad) {
 
 // Grid (tiles, KV heads, sequences).  With one tile the workgroup does everything.  With more,
 // every workgroup derives the thresholds from the histogram, packs the runs of candidates among
-// its own tile_vecs * kSelTile positions into a list in the workspace (one atomic add per workgroup reserves the
-// space), and the workgroup that arrives last (ticket, as in the attention kernels) takes the
-// list into registers and ranks it: the pass over all positions, which is what a single
-// workgroup spends most of its time on, is spread over the chip.
+// its own tile_vecs * kSelTile positions into a list in the workspace (one atomic add per
+// workgroup reserves the space), and the workgroup that arrives last (ticket, as in the attention
+// kernels) takes the list into registers and ranks it: the pass over all positions, which is what
+// a single workgroup spends most of its time on, is spread over the chip.
 // The selection of one (sequence b, KV head blockIdx.y), by the workgroups blockIdx.x = 0 .. gridDim.x - 1.
 template <bool ADAPT>                    // ADAPT: compiled with the histogram-driven bucket layout (large K only)
 __device__ __forceinline__

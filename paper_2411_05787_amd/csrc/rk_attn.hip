@@ -1358,8 +1358,11 @@ struct PoolBatch {
     const int32_t* pred[kBatchLayers];       // NULL: every sequence of the layer
 };
 
+// (Groups of up to 4 heads are compiled for 5 workgroups per CU: a workgroup is a chain of phases, each
+// waiting on the one before, and more of them in flight fill the waits: 72 -> 66 us per launch over 32
+// layers of 33k rows; for 6 it spills and gains nothing more, for 8: 75 us.  Larger groups hold more scores per thread.)
 template <int G>
-__global__ __launch_bounds__(256)
+__global__ __launch_bounds__(256, G <= 4 ? 5 : 1)
 void pool_batched_kernel(const PoolBatch tab, const AttnParams common, int32_t batch, int64_t stride, int half, int agg) {
     const int layer = blockIdx.z / batch, b = blockIdx.z - layer * batch;
     AttnParams p = common;                   // out == NULL and weights == NULL: pooling tiles only

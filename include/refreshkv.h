@@ -375,6 +375,15 @@ int rk_calibration_copy(void* dst, const void* src, size_t bytes, void* stream);
  * kernel that only reads reaches on the same GPU. */
 int rk_calibration_read(const void* src, size_t bytes, uint32_t* sink, void* stream);
 
+/* Test hook.  In launches small enough for all their workgroups to run at once, the partial step and
+ * rk_full_attn without weights let every workgroup merge a share of the output, each re-reading the
+ * other workgroups' partial results while these are still on their way.  `spin` (>= 0; default 256) bounds
+ * those re-reads: a workgroup that exceeds it leaves its share to the workgroup that publishes last, which
+ * waits for nobody.  0 makes every workgroup hand over at once, so that a test can drive that path; results
+ * are the same bits for any value.  Process-wide, read when a call is enqueued.  Returns RK_ERR_INVALID_ARG
+ * for a negative value. */
+int rk_debug_set_slice_spin(int32_t spin);
+
 /* Bookkeeping of a refresh: tail_start[b] = seq_lens[b] for every sequence the predicate
  * selects (all when pred is NULL).  After a full step + refresh the rows "decoded since the
  * refresh" start at the current length (Section 2.2: the partial cache then grows by the

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(HERE, "librefreshkv.so")
 
 EXPORTS = ["rk_version", "rk_status_string", "rk_workspace_bytes", "rk_workspace_init",
            "rk_full_attn", "rk_full_attn_scores", "rk_topk_select", "rk_full_attn_select", "rk_full_attn_pool", "rk_full_attn_deferred", "rk_select_pooled", "rk_score_select", "rk_window_select", "rk_gather_small_kv", "rk_partial_attn", "rk_partial_attn_static", "rk_partial_attn_static_bytes", "rk_partial_attn_fixed", "rk_partial_attn_lazy", "rk_partial_attn_triggered", "rk_decode_step", "rk_decode_step_overlapped", "rk_refresh_batched", "rk_decode_step_batched",
-           "rk_query_sim", "rk_mark_refresh", "rk_calibration_copy", "rk_calibration_read", "rk_h2o_append", "rk_h2o_update", "rk_h2o_step"]
+           "rk_query_sim", "rk_mark_refresh", "rk_calibration_copy", "rk_calibration_read", "rk_debug_set_slice_spin", "rk_h2o_append", "rk_h2o_update", "rk_h2o_step"]
 
 RK_AGG_MAX, RK_AGG_MEAN, RK_AGG_FIRST = 0, 1, 2
 
@@ -124,6 +124,8 @@ def _load(path: str = LIB_PATH) -> C.CDLL:
     l.rk_query_sim.argtypes = [G, P, P, C.c_float, I32, P, P, P]
     l.rk_calibration_copy.restype = C.c_int
     l.rk_calibration_copy.argtypes = [P, P, SZ, P]
+    l.rk_debug_set_slice_spin.restype = C.c_int
+    l.rk_debug_set_slice_spin.argtypes = [C.c_int32]
     l.rk_calibration_read.restype = C.c_int
     l.rk_calibration_read.argtypes = [P, SZ, P, P]
     l.rk_mark_refresh.restype = C.c_int
@@ -538,6 +540,12 @@ def rk_mark_refresh(geom: Geom, seq_lens, tail_start, pred=None, pred_val: int =
         C.byref(geom.c()), _dev(seq_lens, torch.int32, "seq_lens", (B,)),
         _dev(tail_start, torch.int32, "tail_start", (B,)),
         _dev(pred, torch.int32, "pred", (B,), optional=True), int(pred_val), _stream(stream)))
+
+
+def rk_debug_set_slice_spin(spin: int) -> None:
+    """Test hook: how often a workgroup of the merge by slices re-reads rows still in flight before it hands its
+    share over (default 256; 0: every workgroup hands over at once).  Results do not depend on it."""
+    _check("rk_debug_set_slice_spin", lib.rk_debug_set_slice_spin(int(spin)))
 
 
 def rk_calibration_read(src: torch.Tensor, sink: torch.Tensor, nbytes: int = None, offset: int = 0, stream=None) -> int:

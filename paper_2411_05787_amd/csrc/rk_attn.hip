@@ -39,6 +39,7 @@
 #include "rk_internal.h"
 #include "rk_device.h"
 
+#include <atomic>
 #include <mutex>
 
 namespace rk {
@@ -69,6 +70,8 @@ struct AttnParams {
     const int32_t* idx; int32_t idx_stride;   // LAZY only: the selection [B, Hkv, idx_stride] whose rows are not gathered yet
     float* trig_q_ref; float* trig_sim; int32_t* trig_need; float trig_threshold;   // TRIG only: the query-similarity test
     int32_t ragged_batch;              // != 0 (= batch): workgroups are shared out by length, see ragged_share_lane
+    int32_t slice_merge;               // TAGGED: every workgroup merges a slice of the output (all workgroups of the launch are resident together)
+    int32_t slice_spin;                // ... re-reading rows still in flight at most this often before it leaves its slice to the last one
 };
 
 // Work split of the split kernels.  The rows of a (sequence, KV head) are cut into tiles of 32;
@@ -404,6 +407,93 @@ __device__ __forceinline__ void merge_tagged_heads(const AttnParams& p, int b, i
             if (lane == 0) p.lse[bh] = den[i] > 0.f ? Lam[i] + __logf(den[i]) : -INFINITY;
         }
     }
+}
+
+// The same merge for a slice of the output of a (sequence, KV head): n_rows consecutive data rows of head gi
+// from row r0 on, one per lane, by one wavefront.  Same operations in the same order per (head, row) as
+// merge_tagged_heads: the same bits, whoever merges which slice.  Rows still in flight are re-read at most
+// `spin` times; if some are still missing then, the output is left alone and the result is false (final: NaN
+// is written instead, as above).  The offset of a chunk travels as the scalar operand of the loads.
+template <int G, int TB>
+__device__ __forceinline__ bool merge_tagged_slice(const AttnParams& p, int b, int g, int gi_any_lane, int r0_any_lane, int n_rows_any_lane,
+                                                   int nchunks_any_lane, uint32_t tag, int spin, bool final) {
+    constexpr int ROWS = G * kTagRowsPerHead;
+    static_assert(TB <= 64, "one chunk per lane");
+    const int nchunks = __builtin_amdgcn_readfirstlane(nchunks_any_lane);
+    const int gi = __builtin_amdgcn_readfirstlane(gi_any_lane);
+    const int r0 = __builtin_amdgcn_readfirstlane(r0_any_lane);
+    const int n_rows = __builtin_amdgcn_readfirstlane(n_rows_any_lane);
+    const int lane = threadIdx.x & 63;
+    const int64_t bg = (int64_t)b * p.Hkv + g;
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        p.tag_rows + bg * kTagSlots * ROWS * 4, 0, kTagSlots * ROWS * 16, 0x00020000);
+    const int r = r0 + min(lane, n_rows - 1);
+    const int row_off = (gi * kTagRowsPerHead + r) * 16;                         // this lane's data row inside a partial result
+    const int lam_off = (gi * kTagRowsPerHead + kTagDataRows) * 16;              // the head's lambda row
+    float num[3] = {0.f, 0.f, 0.f}, den = 0.f, Lam = -INFINITY;
+    bool good = true;
+#pragma unroll 1
+    for (int c0 = 0; c0 < nchunks; c0 += TB) {
+        u32x4 v[TB], lt;
+        bool ok = false;
+        int tries = 0;
+        const int nb = min(nchunks - c0, TB);
+        const int cl = c0 + min(lane, nb - 1);
+        while (!__all(ok) && tries++ < spin) {
+            if (tries > 1) __builtin_amdgcn_s_sleep(2);
+            lt = __builtin_amdgcn_raw_buffer_load_b128(rsrc, cl * (ROWS * 16) + lam_off, 0, kAgentScopeAux);
+#pragma unroll
+            for (int u = 0; u < TB; ++u)
+                v[u] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, row_off, (c0 + min(u, nb - 1)) * (ROWS * 16), kAgentScopeAux);
+            uint32_t bad = lt.w ^ tag;
+#pragma unroll
+            for (int u = 0; u < TB; ++u) bad |= v[u].w ^ tag;
+            ok = bad == 0u;
+        }
+        if (!__all(ok)) { good = false; break; }
+        const float lam = lane < nb ? __uint_as_float(lt.x) : -INFINITY;
+        const float nl = fmaxf(fmaxf(Lam, wave_max(lam)), -3.0e38f);
+        const float wv = fast_exp2((lam - nl) * kLog2e);
+        const float so = fast_exp2((Lam - nl) * kLog2e);
+        float a0 = num[0] * so, a1 = num[1] * so, a2 = num[2] * so;
+        den = fmaf(den, so, wave_sum(wv));
+#pragma unroll
+        for (int u = 0; u < TB; ++u) {
+            const float wu = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(wv), u));
+            a0 = fmaf(wu, __uint_as_float(v[u].x), a0);
+            a1 = fmaf(wu, __uint_as_float(v[u].y), a1);
+            a2 = fmaf(wu, __uint_as_float(v[u].z), a2);
+        }
+        num[0] = a0; num[1] = a1; num[2] = a2; Lam = nl;
+    }
+    if (!good && !final) return false;
+    const float inv = den > 0.f ? __builtin_amdgcn_rcpf(den) : 0.f;
+    const float nan = __uint_as_float(0x7fc00000u);
+    const uint32_t p01 = good ? pack_bf16(num[0] * inv, num[1] * inv) : pack_bf16(nan, nan);
+    const uint32_t p2 = good ? pack_bf16(num[2] * inv, 0.f) : pack_bf16(nan, 0.f);
+    const int64_t bh = (int64_t)b * p.Hq + g * G + gi;
+    uint16_t* o = p.out + bh * kD + 3 * r;
+    if (lane < n_rows) {
+        o[0] = (uint16_t)p01; o[1] = (uint16_t)(p01 >> 16);
+        if (r < kTagDataRows - 1) o[2] = (uint16_t)p2;
+        if (r == 0) p.lse[bh] = (good && den > 0.f) ? Lam + __logf(den) : (good ? -INFINITY : nan);
+    }
+    return true;
+}
+
+// Which slice workgroup c of the nchunks of a (sequence, KV head) merges: the workgroups c with c % G == gi share
+// the 43 data rows of head gi (needs nchunks >= G: every head has a workgroup).
+template <int G>
+struct TagSlice { int gi, r0, n_rows; };
+template <int G>
+__device__ __forceinline__ TagSlice<G> tag_slice_of(int c, int nchunks) {
+    TagSlice<G> s;
+    s.gi = c % G;
+    const int readers = (nchunks - s.gi + G - 1) / G;             // workgroups of this head
+    const int per = (kTagDataRows + readers - 1) / readers;
+    s.r0 = (c / G) * per;
+    s.n_rows = min(per, kTagDataRows - s.r0);
+    return s;
 }
 
 // Roles of lane (n16, c4) = (lane % 16, lane / 16) of a wavefront, per tile of 32 rows:
@@ -889,15 +979,68 @@ void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t
             }
         }
         int32_t* counter = p.counters + bg * kCounterStride;
+        // Merge by slices: every workgroup merges its share of the (head, data row) units, reading them from
+        // all partial results as soon as its own are on their way; no workgroup waits for a ticket first, and
+        // the merge is the work of all of them instead of one.  The ticket is still drawn: the workgroup that
+        // publishes last does the bookkeeping, and takes over the slices of workgroups that gave up waiting
+        // (words 2 and 3 of the counter line, as one: a bit per workgroup).  A workgroup gives up after slice_spin
+        // re-reads, so that it never holds a compute unit that another workgroup of the launch is waiting for;
+        // it then sets its bit and looks at the call number: still the old one, and the last workgroup has yet to
+        // store it, which it does before it collects the bits, so it will see this one; already this call's, and
+        // every workgroup has published, so the rows will arrive and the slice can be finished here after all
+        // (if the last workgroup saw the bit as well, both write the same values).
+        const bool slices = p.slice_merge != 0 && nchunks >= G && nchunks <= 64;
+        unsigned long long* pend = reinterpret_cast<unsigned long long*>(counter + 2);
+        __shared__ unsigned long long sPend;
         asm volatile("s_barrier" ::: "memory");
-        if (tid == 0) sTicket = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (w == 0) {
+            // the ticket, and for the workgroup that publishes last the bookkeeping, beside the merge of the slice
+            int ticket = 0;
+            if (lane == 0) ticket = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            ticket = __builtin_amdgcn_readfirstlane(ticket);
+            if (slices && ticket == nchunks - 1 && lane == 0) {
+                __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);           // next call
+                __hip_atomic_store(&p.epochs[bg], tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                wait_stores_acknowledged();                                                           // the call number is out before the bits are collected
+                sPend = __hip_atomic_exchange(pend, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+            if (lane == 0) sTicket = ticket;
+        }
+        if (slices && w == NW - 1) {
+            const TagSlice<G> sl = tag_slice_of<G>(c_rec, nchunks);
+            if (sl.n_rows > 0 && !merge_tagged_slice<G, 20>(p, b, g, sl.gi, sl.r0, sl.n_rows, nchunks, tag, p.slice_spin, false)) {
+                const unsigned long long bit = 1ull << c_rec;
+                uint32_t seen = 0;
+                if (lane == 0) {
+                    const unsigned long long before = __hip_atomic_fetch_or(pend, bit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    asm volatile("s_waitcnt vmcnt(0)" :: "v"(before) : "memory");       // the bit is set before the call number is read
+                    seen = __hip_atomic_load(&p.epochs[bg], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+                seen = __builtin_amdgcn_readfirstlane(seen);
+                if (seen == tag) {
+                    merge_tagged_slice<G, 20>(p, b, g, sl.gi, sl.r0, sl.n_rows, nchunks, tag, kTagSpinLimit, true);
+                    if (lane == 0) __hip_atomic_fetch_and(pend, ~bit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+        }
         __syncthreads();
         if (sTicket != nchunks - 1) return;
-        // last arrival: every wavefront merges its heads
-        merge_tagged_heads<G, UPW, (UPW == 1 ? 20 : 17)>(p, b, g, w, nchunks, tag);
-        if (tid == 0) {
-            __hip_atomic_store(&p.epochs[bg], tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);       // next call
+        if (!slices) {
+            // last arrival: every wavefront merges its heads
+            merge_tagged_heads<G, UPW, (UPW == 1 ? 20 : 17)>(p, b, g, w, nchunks, tag);
+            if (tid == 0) {
+                __hip_atomic_store(&p.epochs[bg], tag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);       // next call
+            }
+            return;
+        }
+        unsigned long long left = sPend;
+        for (int k = 0; left != 0; ++k) {
+            const int cb = __builtin_ctzll(left);
+            left &= left - 1;
+            const TagSlice<G> sl = tag_slice_of<G>(cb, nchunks);
+            if ((k & (NW - 1)) == w && cb < nchunks && sl.n_rows > 0)
+                merge_tagged_slice<G, 20>(p, b, g, sl.gi, sl.r0, sl.n_rows, nchunks, tag, kTagSpinLimit, true);
         }
         return;
     }
@@ -1394,6 +1537,16 @@ static int launch_finish_pool(const AttnParams& p, int batch, int32_t max_len, c
     return launch_status();
 }
 
+// Merge by slices (see the kernel) where every workgroup of the launch is resident at once: the kernels are
+// compiled for at least two workgroups per compute unit.  A larger launch keeps the merge by the last workgroup,
+// which waits for nobody.  g_slice_spin: how often a workgroup re-reads rows that are still in flight before it
+// leaves its slice to the last one (rk_debug_set_slice_spin: a test hook; 0 makes every workgroup give up at once).
+static std::atomic<int32_t> g_slice_spin{256};
+static void set_slice_merge(AttnParams& p, bool tagged, int64_t workgroups) {
+    p.slice_merge = (tagged && workgroups <= 2 * kComputeUnits) ? 1 : 0;
+    p.slice_spin = g_slice_spin.load(std::memory_order_relaxed);
+}
+
 template <int G, bool EMIT, bool TWO_SEG, bool TAGGED, bool TRIG = false>
 static int launch_split_g(const AttnParams& p, int batch, int nchunk_grid, hipStream_t st) {
     // (measured on the kernel alone, us per launch, chunk as grid x / KV head as grid x: 8 KV heads, 512
@@ -1517,6 +1670,7 @@ int full_attn_stage(const rk_geom* geom, const void* q, rk_kv full, const int32_
         const int wide = split_workgroups(max_len, (int64_t)geom->batch * geom->n_kv_heads, kMaxChunks);
         if (wide <= kMergeChunks) {
             p.nch = merged_split_workgroups(max_len, 0, (int64_t)geom->batch * geom->n_kv_heads);
+            set_slice_merge(p, true, (int64_t)p.nch * geom->batch * geom->n_kv_heads);
             return launch_split<false, false>(p, geom->batch, G, p.nch, st);
         }
         p.nch = wide;
@@ -1697,6 +1851,7 @@ static int launch_partial(const rk_geom* geom, const void* q, rk_kv small, int32
         p.nch = batched_tagged_workgroups(p.tail_wg ? n_sel : n_sel + (int64_t)max_recent, p.tail_wg, (int64_t)geom->batch * geom->n_kv_heads);
     if (!tagged && p.nch > p.max_chunks) p.nch = p.max_chunks;      // fewer, longer chunks: what the workspace has slots for
     if (p.nch > kMergeChunks || p.nch < 1) return RK_ERR_WORKSPACE;
+    set_slice_merge(p, tagged, (int64_t)(p.nch + (lazy_idx == nullptr ? p.tail_wg : 0)) * geom->batch * geom->n_kv_heads);
     if (lazy_idx != nullptr) {      // rows of the selection come from the full cache and are written to `small` on the way
         if (n_sel < 1 || small.capacity < n_sel) return RK_ERR_INVALID_ARG;
         p.idx = lazy_idx; p.idx_stride = n_sel;
@@ -1734,6 +1889,12 @@ static int partial_attn_impl(const rk_geom* geom, const void* q, rk_kv small, in
     ws.max_chunks = slots < (size_t)kMergeChunks ? (int)slots : kMergeChunks;     // the launch takes no more workgroups than this
     return launch_partial(geom, q, small, n_sel, evict, full, tail_start, seq_lens, max_recent, out, pred, pred_val,
                           ws, stream, lazy_idx, trig);
+}
+
+extern "C" int rk_debug_set_slice_spin(int32_t spin) {
+    if (spin < 0) return RK_ERR_INVALID_ARG;
+    rk::g_slice_spin.store(spin, std::memory_order_relaxed);
+    return RK_OK;
 }
 
 extern "C" int rk_partial_attn(const rk_geom* geom, const void* q, rk_kv small, int32_t n_sel,

@@ -688,6 +688,56 @@ def test_partial_attn_triggered_equals_test_then_step(rk, heads, fixed_size):
     assert torch.equal(out_c[torch.from_numpy(keep).cuda()], out_a[torch.from_numpy(keep).cuda()])
 
 
+@pytest.mark.parametrize("shape", [(1, 32, 8, 2048, 5), (1, 28, 4, 4096, 3), (4, 32, 8, 700, 9), (2, 8, 8, 1500, 0), (1, 32, 8, 2048, 40)],
+                         ids=["llama_k2048", "qwen_k4096_two_rounds", "batch4_k700", "g1_k1500_no_tail", "llama_k2048_long_tail"])
+def test_partial_attn_merge_by_slices_handover(rk, shape):
+    """The merge by slices of the partial step with the bound on its re-reads at 0 (every workgroup leaves its share
+    to the one that publishes last), at 1 and 2 (some do, some do not) and at its default: the same bits every time,
+    against the oracle once, and the workspace left clean for the next call (also rk_full_attn without weights)."""
+    B, Hq, Hkv, k, recent = shape
+    say("merge_by_slices_handover", shape)
+    cap = 6000
+    g = torch.Generator().manual_seed(500 + k + B)
+    q = torch.randn(B, Hq, 128, generator=g).to(torch.bfloat16)
+    K = torch.randn(B, Hkv, cap, 128, generator=g).to(torch.bfloat16)
+    V = torch.randn(B, Hkv, cap, 128, generator=g).to(torch.bfloat16)
+    sK = torch.randn(B, Hkv, k, 128, generator=g).to(torch.bfloat16)
+    sV = torch.randn(B, Hkv, k, 128, generator=g).to(torch.bfloat16)
+    lens_h = np.array([5000 - 37 * b for b in range(B)], dtype=np.int32)
+    tail_h = lens_h - recent
+    geom = rk.Geom(B, Hq, Hkv, 128, float(np.float32(1 / np.sqrt(128))))
+    ws = rk.Workspace(geom, cap, k)
+    dK, dV, dsK, dsV, dq = K.cuda(), V.cuda(), sK.cuda(), sV.cuda(), q.cuda()
+    lens, tail = torch.from_numpy(lens_h).cuda(), torch.from_numpy(tail_h).cuda()
+    outs = []
+    try:
+        for spin in (256, 0, 1, 2, 0, 256):
+            rk.rk_debug_set_slice_spin(spin)
+            out = torch.full((B, Hq, 128), 3.0, dtype=torch.bfloat16, device="cuda")
+            rk.rk_partial_attn(geom, dq, dsK, dsV, k, dK, dV, tail, lens, max(recent, 1), out, workspace=ws)
+            torch.cuda.synchronize()
+            outs.append(out.cpu())
+        # rk_full_attn without weights over short rows takes the same merge
+        full = []
+        for spin in (256, 0, 1):
+            rk.rk_debug_set_slice_spin(spin)
+            out = torch.full((B, Hq, 128), 3.0, dtype=torch.bfloat16, device="cuda")
+            rk.rk_full_attn(geom, dq, dK, dV, lens, int(lens_h.max()), out, workspace=ws)
+            torch.cuda.synchronize()
+            full.append(out.cpu())
+    finally:
+        rk.rk_debug_set_slice_spin(256)
+    for o in outs[1:]:
+        assert torch.equal(o, outs[0])
+    for o in full[1:]:
+        assert torch.equal(o, full[0])
+    o_ref = oracle.partial_attn(gen.bf16_bits(q), gen.bf16_bits(sK), gen.bf16_bits(sV), k, gen.bf16_bits(K), gen.bf16_bits(V),
+                                tail_h.tolist(), lens_h.tolist(), geom.scale)
+    assert_out_close(gen.bf16_bits(outs[0]), o_ref, "merge by slices")
+    f_ref, _, _ = oracle.full_attn(gen.bf16_bits(q), gen.bf16_bits(K), gen.bf16_bits(V), lens_h.tolist(), geom.scale)
+    assert_out_close(gen.bf16_bits(full[0]), f_ref, "full attention, merge by slices")
+
+
 # ----------------------------------------------------------------------------- whole loop
 def run_gpu_loop(rk, w: gen.Workload, layer: int, K, V, q_steps, new_k, new_v, lens0, evict_lowest=False,
                  scores_only=False):

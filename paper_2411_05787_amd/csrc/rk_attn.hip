@@ -409,85 +409,21 @@ __device__ __forceinline__ void merge_tagged_heads(const AttnParams& p, int b, i
     }
 }
 
-// The same merge for a slice of the output of a (sequence, KV head): n_rows consecutive data rows of head gi
-// from row r0 on, one per lane, by one wavefront.  Same operations in the same order per (head, row) as
-// merge_tagged_heads: the same bits, whoever merges which slice.  Rows still in flight are re-read at most
-// `spin` times; if some are still missing then, the output is left alone and the result is false (final: NaN
-// is written instead, as above).  The offset of a chunk travels as the scalar operand of the loads.
-template <int G, int TB>
-__device__ __forceinline__ bool merge_tagged_slice(const AttnParams& p, int b, int g, int gi_any_lane, int r0_any_lane, int n_rows_any_lane,
-                                                   int nchunks_any_lane, uint32_t tag, int spin, bool final) {
-    constexpr int ROWS = G * kTagRowsPerHead;
-    static_assert(TB <= 64, "one chunk per lane");
-    const int nchunks = __builtin_amdgcn_readfirstlane(nchunks_any_lane);
-    const int gi = __builtin_amdgcn_readfirstlane(gi_any_lane);
-    const int r0 = __builtin_amdgcn_readfirstlane(r0_any_lane);
-    const int n_rows = __builtin_amdgcn_readfirstlane(n_rows_any_lane);
-    const int lane = threadIdx.x & 63;
-    const int64_t bg = (int64_t)b * p.Hkv + g;
-    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(
-        p.tag_rows + bg * kTagSlots * ROWS * 4, 0, kTagSlots * ROWS * 16, 0x00020000);
-    const int r = r0 + min(lane, n_rows - 1);
-    const int row_off = (gi * kTagRowsPerHead + r) * 16;                         // this lane's data row inside a partial result
-    const int lam_off = (gi * kTagRowsPerHead + kTagDataRows) * 16;              // the head's lambda row
-    float num[3] = {0.f, 0.f, 0.f}, den = 0.f, Lam = -INFINITY;
-    bool good = true;
-#pragma unroll 1
-    for (int c0 = 0; c0 < nchunks; c0 += TB) {
-        u32x4 v[TB], lt;
-        bool ok = false;
-        int tries = 0;
-        const int nb = min(nchunks - c0, TB);
-        const int cl = c0 + min(lane, nb - 1);
-        while (!__all(ok) && tries++ < spin) {
-            if (tries > 1) __builtin_amdgcn_s_sleep(2);
-            lt = __builtin_amdgcn_raw_buffer_load_b128(rsrc, cl * (ROWS * 16) + lam_off, 0, kAgentScopeAux);
-#pragma unroll
-            for (int u = 0; u < TB; ++u)
-                v[u] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, row_off, (c0 + min(u, nb - 1)) * (ROWS * 16), kAgentScopeAux);
-            uint32_t bad = lt.w ^ tag;
-#pragma unroll
-            for (int u = 0; u < TB; ++u) bad |= v[u].w ^ tag;
-            ok = bad == 0u;
-        }
-        if (!__all(ok)) { good = false; break; }
-        const float lam = lane < nb ? __uint_as_float(lt.x) : -INFINITY;
-        const float nl = fmaxf(fmaxf(Lam, wave_max(lam)), -3.0e38f);
-        const float wv = fast_exp2((lam - nl) * kLog2e);
-        const float so = fast_exp2((Lam - nl) * kLog2e);
-        float a0 = num[0] * so, a1 = num[1] * so, a2 = num[2] * so;
-        den = fmaf(den, so, wave_sum(wv));
-#pragma unroll
-        for (int u = 0; u < TB; ++u) {
-            const float wu = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(wv), u));
-            a0 = fmaf(wu, __uint_as_float(v[u].x), a0);
-            a1 = fmaf(wu, __uint_as_float(v[u].y), a1);
-            a2 = fmaf(wu, __uint_as_float(v[u].z), a2);
-        }
-        num[0] = a0; num[1] = a1; num[2] = a2; Lam = nl;
-    }
-    if (!good && !final) return false;
-    const float inv = den > 0.f ? __builtin_amdgcn_rcpf(den) : 0.f;
-    const float nan = __uint_as_float(0x7fc00000u);
-    const uint32_t p01 = good ? pack_bf16(num[0] * inv, num[1] * inv) : pack_bf16(nan, nan);
-    const uint32_t p2 = good ? pack_bf16(num[2] * inv, 0.f) : pack_bf16(nan, 0.f);
-    const int64_t bh = (int64_t)b * p.Hq + g * G + gi;
-    uint16_t* o = p.out + bh * kD + 3 * r;
-    if (lane < n_rows) {
-        o[0] = (uint16_t)p01; o[1] = (uint16_t)(p01 >> 16);
-        if (r < kTagDataRows - 1) o[2] = (uint16_t)p2;
-        if (r == 0) p.lse[bh] = (good && den > 0.f) ? Lam + __logf(den) : (good ? -INFINITY : nan);
-    }
-    return true;
-}
-
-// Which slice workgroup c of the nchunks of a (sequence, KV head) merges: the workgroups c with c % G == gi share
-// the 43 data rows of head gi (needs nchunks >= G: every head has a workgroup).
-template <int G>
+// ---- merge by slices ----
+// The same merge, shared out: workgroup c of the nchunks of a (sequence, KV head) merges a slice of its output,
+// some consecutive data rows of one head (one per lane), reading them from every partial result.  One wavefront
+// executes an instruction every 8 to 12 cycles however few lanes it uses (measured: 12 in a dependent chain), so
+// the time of a merge is its instruction count, and this one is written for that: the offset of a chunk travels
+// as the scalar operand of the loads, the slice is worked out long before (tag_slice_of, below), and the
+// weights are taken against the first chunk's lambda, which every lane reads for itself, where that is safe
+// (it saves the reduction for the maximum; any common reference gives the same quotient).  Whoever merges a
+// slice: the same operations in the same order, the same bits.
 struct TagSlice { int gi, r0, n_rows; };
+// Which slice workgroup c merges: the workgroups c with c % G == gi share the 43 data rows of head gi
+// (needs nchunks >= G: every head has a workgroup).
 template <int G>
-__device__ __forceinline__ TagSlice<G> tag_slice_of(int c, int nchunks) {
-    TagSlice<G> s;
+__device__ __forceinline__ TagSlice tag_slice_of(int c, int nchunks) {
+    TagSlice s;
     s.gi = c % G;
     const int readers = (nchunks - s.gi + G - 1) / G;             // workgroups of this head
     const int per = (kTagDataRows + readers - 1) / readers;
@@ -495,6 +431,149 @@ __device__ __forceinline__ TagSlice<G> tag_slice_of(int c, int nchunks) {
     s.n_rows = min(per, kTagDataRows - s.r0);
     return s;
 }
+
+// TB: partial results read (at least nchunks).  Rows still in flight are re-read at most `spin` times; if
+// some are still missing then, the output is left alone and the result is false (final: NaN is written instead).
+template <int G, int TB>
+__device__ __forceinline__ bool merge_tagged_slice(const AttnParams& p, int b, int g, const __amdgpu_buffer_rsrc_t rsrc, const TagSlice sl,
+                                                   int nchunks, uint32_t tag, int spin, bool final) {
+    constexpr int STRIDE = G * kTagRowsPerHead * 16;               // bytes of a partial result
+    static_assert(TB <= 64, "one chunk per lane");
+    const int lane = threadIdx.x & 63;
+    const int r = sl.r0 + min(lane, sl.n_rows - 1);
+    const int row_off = (sl.gi * kTagRowsPerHead + r) * 16;                                        // this lane's data row inside a partial result
+    const int lam_off = min(lane, nchunks - 1) * STRIDE + (sl.gi * kTagRowsPerHead + kTagDataRows) * 16;   // lane u: chunk u's lambda row
+    const int lam0_off = (sl.gi * kTagRowsPerHead + kTagDataRows) * 16;                            // the first chunk's, for every lane
+    const int last = (nchunks - 1) * STRIDE;
+    u32x4 v[TB], lt, l0;
+    bool ok = false;
+    int tries = 0;
+    while (!__all(ok) && tries++ < spin) {
+        if (tries > 1) __builtin_amdgcn_s_sleep(2);
+        lt = __builtin_amdgcn_raw_buffer_load_b128(rsrc, lam_off, 0, kAgentScopeAux);
+        l0 = __builtin_amdgcn_raw_buffer_load_b128(rsrc, lam0_off, 0, kAgentScopeAux);
+#pragma unroll
+        for (int u = 0; u < TB; ++u)
+            v[u] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, row_off, min(u * STRIDE, last), kAgentScopeAux);
+        uint32_t bad = (lt.w ^ tag) | (l0.w ^ tag);
+#pragma unroll
+        for (int u = 0; u < TB; ++u) bad |= v[u].w ^ tag;
+        ok = bad == 0u;
+    }
+    const bool good = __all(ok);
+    if (!good && !final) return false;
+    const float lam = lane < nchunks ? __uint_as_float(lt.x) : -INFINITY;
+    // reference: the first chunk's lambda, unless some chunk lies so far from it that a weight could overflow
+    // or all could vanish (then the largest, by a reduction)
+    float ref = __uint_as_float(l0.x);
+    const bool near = lane >= nchunks || lam == -INFINITY || fabsf(lam - ref) < 20.f;
+    if (!(ref > -3.0e38f) || !__all(near)) ref = fmaxf(wave_max(lam), -3.0e38f);
+    const float wv = fast_exp2((lam - ref) * kLog2e);              // 0 for lanes without a chunk and for empty chunks
+    const float den = wave_sum(wv);
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f;
+#pragma unroll
+    for (int u = 0; u < TB; ++u) {
+        const float wu = __uint_as_float(__builtin_amdgcn_readlane(__float_as_uint(wv), u));      // 0 beyond nchunks
+        a0 = fmaf(wu, __uint_as_float(v[u].x), a0);
+        a1 = fmaf(wu, __uint_as_float(v[u].y), a1);
+        a2 = fmaf(wu, __uint_as_float(v[u].z), a2);
+    }
+    const float inv = den > 0.f ? __builtin_amdgcn_rcpf(den) : 0.f;
+    const float nan = __uint_as_float(0x7fc00000u);
+    const uint32_t p01 = good ? pack_bf16(a0 * inv, a1 * inv) : pack_bf16(nan, nan);
+    const uint32_t p2 = good ? pack_bf16(a2 * inv, 0.f) : pack_bf16(nan, 0.f);
+    const int64_t bh = (int64_t)b * p.Hq + g * G + sl.gi;
+    uint16_t* o = p.out + bh * kD + 3 * r;
+    if (lane < sl.n_rows) {
+        o[0] = (uint16_t)p01; o[1] = (uint16_t)(p01 >> 16);
+        if (r < kTagDataRows - 1) o[2] = (uint16_t)p2;
+    }
+    if (sl.r0 == 0) {                                              // (one slice per head)
+        if (lane == 0) p.lse[bh] = good ? (den > 0.f ? ref + __logf(den) : -INFINITY) : nan;
+    }
+    return true;
+}
+// The same for slices of at most 16 rows, with four lanes to a row: lane 16 q + i sums the chunks q * per ..
+// q * per + per - 1 (per = a quarter of the chunks, rounded up; TBP: at least that) for row r0 + i, and the four
+// sums are added across the lanes, (q0 + q1) + (q2 + q3).  A lane's chunks are a quarter of the loads, checks and
+// multiply-adds of the loop above; the weight of a chunk comes from the lane that holds it (ds_bpermute).
+// Slots past the last chunk re-read the last chunk's row, with weight 0 (their weight lanes hold none).
+template <int G, int TBP>
+__device__ __forceinline__ bool merge_tagged_slice4(const AttnParams& p, int b, int g, const __amdgpu_buffer_rsrc_t rsrc, const TagSlice sl,
+                                                    int nchunks, uint32_t tag, int spin, bool final) {
+    constexpr int STRIDE = G * kTagRowsPerHead * 16;               // bytes of a partial result
+    const int lane = threadIdx.x & 63;
+    const int i = lane & 15, q = lane >> 4;
+    const int per = (nchunks + 3) >> 2;
+    const int r = sl.r0 + min(i, sl.n_rows - 1);
+    const int row_off = (sl.gi * kTagRowsPerHead + r) * 16;
+    const int lam_off = min(lane, nchunks - 1) * STRIDE + (sl.gi * kTagRowsPerHead + kTagDataRows) * 16;   // lane u: chunk u's lambda row
+    const int lam0_off = (sl.gi * kTagRowsPerHead + kTagDataRows) * 16;                            // the first chunk's, for every lane
+    const int first = q * per;                                     // this lane's first chunk
+    const int base_v = row_off + first * STRIDE;
+    const int limit_v = row_off + (nchunks - 1) * STRIDE;
+    u32x4 v[TBP], lt, l0;
+    bool ok = false;
+    int tries = 0;
+    while (!__all(ok) && tries++ < spin) {
+        if (tries > 1) __builtin_amdgcn_s_sleep(2);
+        lt = __builtin_amdgcn_raw_buffer_load_b128(rsrc, lam_off, 0, kAgentScopeAux);
+        l0 = __builtin_amdgcn_raw_buffer_load_b128(rsrc, lam0_off, 0, kAgentScopeAux);
+#pragma unroll
+        for (int u = 0; u < TBP; ++u)
+            v[u] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, min(base_v + u * STRIDE, limit_v), 0, kAgentScopeAux);
+        uint32_t bad = (lt.w ^ tag) | (l0.w ^ tag);
+#pragma unroll
+        for (int u = 0; u < TBP; ++u) bad |= v[u].w ^ tag;
+        ok = bad == 0u;
+    }
+    const bool good = __all(ok);
+    if (!good && !final) return false;
+    const float lam = lane < nchunks ? __uint_as_float(lt.x) : -INFINITY;
+    float ref = __uint_as_float(l0.x);
+    const bool near = lane >= nchunks || lam == -INFINITY || fabsf(lam - ref) < 20.f;
+    if (!(ref > -3.0e38f) || !__all(near)) ref = fmaxf(wave_max(lam), -3.0e38f);
+    const float wv = fast_exp2((lam - ref) * kLog2e);              // 0 for lanes without a chunk and for empty chunks
+    float a0 = 0.f, a1 = 0.f, a2 = 0.f, den = 0.f;
+#pragma unroll
+    for (int u = 0; u < TBP; ++u) {
+        // (slot u of quarter q is chunk first + u; for u >= per it belongs to the next quarter: weight 0)
+        const float wu = __int_as_float(__builtin_amdgcn_ds_bpermute((first + u) * 4, __float_as_int(wv)));
+        const float wq = u < per ? wu : 0.f;
+        a0 = fmaf(wq, __uint_as_float(v[u].x), a0);
+        a1 = fmaf(wq, __uint_as_float(v[u].y), a1);
+        a2 = fmaf(wq, __uint_as_float(v[u].z), a2);
+        den += wq;
+    }
+    a0 = sum_xor32(sum_xor16(a0)); a1 = sum_xor32(sum_xor16(a1)); a2 = sum_xor32(sum_xor16(a2)); den = sum_xor32(sum_xor16(den));
+    const float inv = den > 0.f ? __builtin_amdgcn_rcpf(den) : 0.f;
+    const float nan = __uint_as_float(0x7fc00000u);
+    const uint32_t p01 = good ? pack_bf16(a0 * inv, a1 * inv) : pack_bf16(nan, nan);
+    const uint32_t p2 = good ? pack_bf16(a2 * inv, 0.f) : pack_bf16(nan, 0.f);
+    const int64_t bh = (int64_t)b * p.Hq + g * G + sl.gi;
+    uint16_t* o = p.out + bh * kD + 3 * r;
+    if (lane < sl.n_rows) {
+        o[0] = (uint16_t)p01; o[1] = (uint16_t)(p01 >> 16);
+        if (r < kTagDataRows - 1) o[2] = (uint16_t)p2;
+    }
+    if (sl.r0 == 0) {                                              // (one slice per head)
+        if (lane == 0) p.lse[bh] = good ? (den > 0.f ? ref + __logf(den) : -INFINITY) : nan;
+    }
+    return true;
+}
+// (17 partial results at the shape that matters most: 16 workgroups for 2048 selected rows and one for the
+// rows decoded since; otherwise up to 20)
+template <int G>
+__device__ __forceinline__ bool merge_tagged_slice_n(const AttnParams& p, int b, int g, const __amdgpu_buffer_rsrc_t rsrc, const TagSlice sl,
+                                                     int nchunks, uint32_t tag, int spin, bool final) {
+    if (sl.n_rows <= 16 && nchunks > 4) {
+        if (nchunks <= 20) return merge_tagged_slice4<G, 5>(p, b, g, rsrc, sl, nchunks, tag, spin, final);
+        return merge_tagged_slice4<G, 8>(p, b, g, rsrc, sl, nchunks, tag, spin, final);
+    }
+    if (nchunks <= 17) return merge_tagged_slice<G, 17>(p, b, g, rsrc, sl, nchunks, tag, spin, final);
+    return merge_tagged_slice<G, 20>(p, b, g, rsrc, sl, nchunks, tag, spin, final);
+}
+constexpr int kSliceChunks = 20, kSliceChunks4 = 32;   // the merge by slices serves up to this many partial results (slices of up to 16 rows: the latter)
 
 // Roles of lane (n16, c4) = (lane % 16, lane / 16) of a wavefront, per tile of 32 rows:
 //   K operand   row n16 of a 16-row half tile, dims 8*(4*kk + c4) .. +7, kk = 0..3
@@ -724,6 +803,24 @@ void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t
     // row r of the list lives at base2 + (start2 + r - n1) * 128 once r >= n1
     const uint16_t* kb2 = p.k2 + (int64_t)b * p.s2_b + (int64_t)g * p.s2_h + (int64_t)(start2 - n1) * kD;
     const uint16_t* vb2 = p.v2 + (int64_t)b * p.s2_b + (int64_t)g * p.s2_h + (int64_t)(start2 - n1) * kD;
+
+    // TAGGED: this workgroup's share of the merge by slices (see there), worked out here, while the first tile is
+    // on its way, and not between publishing and merging
+    TagSlice my_slice = {0, 0, 0};
+    bool slices_fit = false;                  // every head has a workgroup, and the merge has a form for this many partial results
+    __amdgpu_buffer_rsrc_t tag_rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)nullptr, 0, 0, 0x00020000);
+    if (TAGGED) {
+        if (nchunks >= G) {
+            my_slice = tag_slice_of<G>(c_rec, nchunks);
+            const int fewest = nchunks / G;                        // workgroups of the head that has fewest: the longest slices
+            slices_fit = nchunks <= kSliceChunks || (nchunks <= kSliceChunks4 && (kTagDataRows + fewest - 1) / fewest <= 16);
+        }
+        my_slice.gi = __builtin_amdgcn_readfirstlane(my_slice.gi);
+        my_slice.r0 = __builtin_amdgcn_readfirstlane(my_slice.r0);
+        my_slice.n_rows = __builtin_amdgcn_readfirstlane(my_slice.n_rows);
+        tag_rsrc = __builtin_amdgcn_make_buffer_rsrc(p.tag_rows + ((int64_t)b * p.Hkv + g) * kTagSlots * (G * kTagRowsPerHead) * 4, 0,
+                                                     kTagSlots * G * kTagRowsPerHead * 16, 0x00020000);
+    }
 
     __shared__ __attribute__((aligned(16))) uint16_t sV[NW][ROWS][VS];
     __shared__ __attribute__((aligned(16))) float sAlpha[NW][16];
@@ -989,7 +1086,7 @@ void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t
         // store it, which it does before it collects the bits, so it will see this one; already this call's, and
         // every workgroup has published, so the rows will arrive and the slice can be finished here after all
         // (if the last workgroup saw the bit as well, both write the same values).
-        const bool slices = p.slice_merge != 0 && nchunks >= G && nchunks <= 64;
+        const bool slices = p.slice_merge != 0 && slices_fit;
         unsigned long long* pend = reinterpret_cast<unsigned long long*>(counter + 2);
         __shared__ unsigned long long sPend;
         asm volatile("s_barrier" ::: "memory");
@@ -1007,8 +1104,8 @@ void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t
             if (lane == 0) sTicket = ticket;
         }
         if (slices && w == NW - 1) {
-            const TagSlice<G> sl = tag_slice_of<G>(c_rec, nchunks);
-            if (sl.n_rows > 0 && !merge_tagged_slice<G, 20>(p, b, g, sl.gi, sl.r0, sl.n_rows, nchunks, tag, p.slice_spin, false)) {
+            const TagSlice sl = my_slice;
+            if (sl.n_rows > 0 && !merge_tagged_slice_n<G>(p, b, g, tag_rsrc, sl, nchunks, tag, p.slice_spin, false)) {
                 const unsigned long long bit = 1ull << c_rec;
                 uint32_t seen = 0;
                 if (lane == 0) {
@@ -1018,7 +1115,7 @@ void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t
                 }
                 seen = __builtin_amdgcn_readfirstlane(seen);
                 if (seen == tag) {
-                    merge_tagged_slice<G, 20>(p, b, g, sl.gi, sl.r0, sl.n_rows, nchunks, tag, kTagSpinLimit, true);
+                    merge_tagged_slice_n<G>(p, b, g, tag_rsrc, sl, nchunks, tag, kTagSpinLimit, true);
                     if (lane == 0) __hip_atomic_fetch_and(pend, ~bit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
             }
@@ -1038,9 +1135,11 @@ void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t
         for (int k = 0; left != 0; ++k) {
             const int cb = __builtin_ctzll(left);
             left &= left - 1;
-            const TagSlice<G> sl = tag_slice_of<G>(cb, nchunks);
+            TagSlice sl = tag_slice_of<G>(cb, nchunks);
+            sl.gi = __builtin_amdgcn_readfirstlane(sl.gi); sl.r0 = __builtin_amdgcn_readfirstlane(sl.r0);
+            sl.n_rows = __builtin_amdgcn_readfirstlane(sl.n_rows);
             if ((k & (NW - 1)) == w && cb < nchunks && sl.n_rows > 0)
-                merge_tagged_slice<G, 20>(p, b, g, sl.gi, sl.r0, sl.n_rows, nchunks, tag, kTagSpinLimit, true);
+                merge_tagged_slice_n<G>(p, b, g, tag_rsrc, sl, nchunks, tag, kTagSpinLimit, true);
         }
         return;
     }

@@ -568,12 +568,12 @@ __device__ __forceinline__ bool merge_tagged_slice_n(const AttnParams& p, int b,
                                                      int nchunks, uint32_t tag, int spin, bool final) {
     if (sl.n_rows <= 16 && nchunks > 4) {
         if (nchunks <= 20) return merge_tagged_slice4<G, 5>(p, b, g, rsrc, sl, nchunks, tag, spin, final);
-        return merge_tagged_slice4<G, 8>(p, b, g, rsrc, sl, nchunks, tag, spin, final);
+        return merge_tagged_slice4<G, 9>(p, b, g, rsrc, sl, nchunks, tag, spin, final);
     }
     if (nchunks <= 17) return merge_tagged_slice<G, 17>(p, b, g, rsrc, sl, nchunks, tag, spin, final);
     return merge_tagged_slice<G, 20>(p, b, g, rsrc, sl, nchunks, tag, spin, final);
 }
-constexpr int kSliceChunks = 20, kSliceChunks4 = 32;   // the merge by slices serves up to this many partial results (slices of up to 16 rows: the latter)
+constexpr int kSliceChunks = 20, kSliceChunks4 = 36;   // the merge by slices serves up to this many partial results (slices of up to 16 rows: the latter)
 
 // Roles of lane (n16, c4) = (lane % 16, lane / 16) of a wavefront, per tile of 32 rows:
 //   K operand   row n16 of a 16-row half tile, dims 8*(4*kk + c4) .. +7, kk = 0..3
@@ -1704,17 +1704,18 @@ static int launch_split(const AttnParams& p, int batch, int G, int nchunk_grid, 
     }
 }
 
-// The partial step that tests the trigger itself: tagged hand-over for groups of up to 4 heads, ticketed beyond.
-static int launch_split_triggered(const AttnParams& p, int batch, int G, int nchunk_grid, hipStream_t st) {
+// The partial step that tests the trigger itself: tagged hand-over for groups of up to 4 heads; beyond, tagged
+// where the merge by slices applies and ticketed otherwise (as without the trigger, see launch_partial).
+static int launch_split_triggered(const AttnParams& p, int batch, int G, int nchunk_grid, bool tagged, hipStream_t st) {
     switch (G) {
         case 1: return launch_split_g<1, false, true, true, true>(p, batch, nchunk_grid, st);
         case 2: return launch_split_g<2, false, true, true, true>(p, batch, nchunk_grid, st);
         case 3: return launch_split_g<3, false, true, true, true>(p, batch, nchunk_grid, st);
         case 4: return launch_split_g<4, false, true, true, true>(p, batch, nchunk_grid, st);
-        case 5: return launch_split_g<5, false, true, false, true>(p, batch, nchunk_grid, st);
-        case 6: return launch_split_g<6, false, true, false, true>(p, batch, nchunk_grid, st);
-        case 7: return launch_split_g<7, false, true, false, true>(p, batch, nchunk_grid, st);
-        case 8: return launch_split_g<8, false, true, false, true>(p, batch, nchunk_grid, st);
+#define RK_CASE(g) case g: return tagged ? launch_split_g<g, false, true, true, true>(p, batch, nchunk_grid, st) \
+                                         : launch_split_g<g, false, true, false, true>(p, batch, nchunk_grid, st);
+        RK_CASE(5) RK_CASE(6) RK_CASE(7) RK_CASE(8)
+#undef RK_CASE
         default: return RK_ERR_UNSUPPORTED;
     }
 }
@@ -1935,32 +1936,44 @@ static int launch_partial(const rk_geom* geom, const void* q, rk_kv small, int32
     p.pred = pred; p.pred_val = pred_val;
     p.counters = ws.counters; p.part_ml = ws.part_ml; p.part_o = ws.part_o; p.max_chunks = ws.max_chunks;
     p.epochs = ws.epochs; p.tag_rows = ws.tag_rows;
-    // Tagged hand-over where a wavefront merges one head (groups of up to 4); with two heads per
-    // wavefront the ticketed form is the faster one (measured at 7 heads per group, 4096 rows: 9.9 against 10.7 us).
-    // Rows enough for 32 workgroups: the ticketed form whatever the group (see two_batches_pay).
-    const bool wide = lazy_idx == nullptr && trig == nullptr &&
-                      two_batches_pay(n_sel, max_recent, (int64_t)geom->batch * geom->n_kv_heads);
-    const bool tagged = ws.tag_rows != nullptr && G <= kSplitWaves && !wide;          // (the built-in scratch array has no tagged region)
+    // Which hand-over.  Tagged partial results merged by slices (every workgroup its share, see the kernel) wherever
+    // that merge applies: a launch whose workgroups are all resident at once, with no more partial results per
+    // (sequence, KV head) than it has a form for.  Otherwise: rows enough for 32 workgroups per pair of a launch over
+    // few pairs take the ticketed form with two batches of partial results (see two_batches_pay); groups of up to 4
+    // heads the tagged form merged by the last workgroup, one head per wavefront; larger groups the ticketed form
+    // (two heads per wavefront: measured at 7 heads per group, 4096 rows, 9.9 against 10.7 us).
+    const int64_t problems = (int64_t)geom->batch * geom->n_kv_heads;
+    const bool can_tag = ws.tag_rows != nullptr;                                       // (the built-in scratch array has no tagged region)
     // a few rows decoded since the refresh: a workgroup of their own (see the kernel), the others split the small cache
     // (ticketed merge: a 17th partial result costs it a second round trip, more than the tail workgroup gains)
-    p.tail_wg = (tagged && lazy_idx == nullptr && n_sel > 0 && max_recent <= kMinChunk) ? 1 : 0;
-    p.nch = merged_split_workgroups(n_sel, p.tail_wg ? 0 : max_recent, (int64_t)geom->batch * geom->n_kv_heads,
-                                    !tagged && lazy_idx == nullptr && (trig == nullptr || G > kSplitWaves));
-    if (tagged && lazy_idx == nullptr && (int64_t)geom->batch * geom->n_kv_heads >= 16)      // many (sequence, KV head) pairs: see there
-        p.nch = batched_tagged_workgroups(p.tail_wg ? n_sel : n_sel + (int64_t)max_recent, p.tail_wg, (int64_t)geom->batch * geom->n_kv_heads);
+    const int tail_wg_tagged = (can_tag && lazy_idx == nullptr && n_sel > 0 && max_recent <= kMinChunk) ? 1 : 0;
+    int nch_tagged = merged_split_workgroups(n_sel, tail_wg_tagged ? 0 : max_recent, problems, false);
+    if (lazy_idx == nullptr && problems >= 16)                                         // many (sequence, KV head) pairs: see there
+        nch_tagged = batched_tagged_workgroups(tail_wg_tagged ? n_sel : n_sel + (int64_t)max_recent, tail_wg_tagged, problems);
+    // (larger groups, whose wavefronts publish two heads each: only where the launch is a matter of latency, few
+    // pairs; measured at 7 and 8 heads per group, 2048 rows: 32 pairs 13.5 -> 14.9 us, 64 pairs 19.5 -> 21.4,
+    // against 16 pairs of 4096 rows 13.1 -> 12.6 and 4 pairs 9.7 -> 9.0)
+    const bool by_slices = can_tag && nch_tagged + tail_wg_tagged <= kSliceChunks4 &&
+                           (int64_t)(nch_tagged + tail_wg_tagged) * problems <= 2 * kComputeUnits &&
+                           (G <= kSplitWaves || problems <= 16);
+    const bool wide = !by_slices && lazy_idx == nullptr && trig == nullptr && two_batches_pay(n_sel, max_recent, problems);
+    const bool tagged = can_tag && !wide && (by_slices || G <= kSplitWaves);
+    p.tail_wg = tagged ? tail_wg_tagged : 0;
+    p.nch = tagged ? nch_tagged
+                   : merged_split_workgroups(n_sel, max_recent, problems, lazy_idx == nullptr && (trig == nullptr || G > kSplitWaves));
     if (!tagged && p.nch > p.max_chunks) p.nch = p.max_chunks;      // fewer, longer chunks: what the workspace has slots for
     if (p.nch > kMergeChunks || p.nch < 1) return RK_ERR_WORKSPACE;
-    set_slice_merge(p, tagged, (int64_t)(p.nch + (lazy_idx == nullptr ? p.tail_wg : 0)) * geom->batch * geom->n_kv_heads);
+    set_slice_merge(p, tagged, (int64_t)(p.nch + (lazy_idx == nullptr ? p.tail_wg : 0)) * problems);
     if (lazy_idx != nullptr) {      // rows of the selection come from the full cache and are written to `small` on the way
         if (n_sel < 1 || small.capacity < n_sel) return RK_ERR_INVALID_ARG;
         p.idx = lazy_idx; p.idx_stride = n_sel;
         return launch_lazy(p, geom->batch, G, (hipStream_t)stream);
     }
     const int nchunk_grid = p.nch + p.tail_wg;
-    if (trig != nullptr) {          // (groups of more than 4 heads take the ticketed form, as without the trigger)
+    if (trig != nullptr) {
         if (ws.tag_rows == nullptr || pred != nullptr) return RK_ERR_INVALID_ARG;
         p.trig_q_ref = trig->q_ref; p.trig_sim = trig->sim; p.trig_need = trig->need_full; p.trig_threshold = trig->threshold;
-        return launch_split_triggered(p, geom->batch, G, nchunk_grid, (hipStream_t)stream);
+        return launch_split_triggered(p, geom->batch, G, nchunk_grid, tagged, (hipStream_t)stream);
     }
     if (!tagged) return launch_split<false, true, false>(p, geom->batch, G, nchunk_grid, (hipStream_t)stream);
     return launch_split<false, true>(p, geom->batch, G, nchunk_grid, (hipStream_t)stream);

@@ -568,12 +568,13 @@ __device__ __forceinline__ bool merge_tagged_slice_n(const AttnParams& p, int b,
                                                      int nchunks, uint32_t tag, int spin, bool final) {
     if (sl.n_rows <= 16 && nchunks > 4) {
         if (nchunks <= 20) return merge_tagged_slice4<G, 5>(p, b, g, rsrc, sl, nchunks, tag, spin, final);
-        return merge_tagged_slice4<G, 9>(p, b, g, rsrc, sl, nchunks, tag, spin, final);
+        if (nchunks <= 36) return merge_tagged_slice4<G, 9>(p, b, g, rsrc, sl, nchunks, tag, spin, final);
+        return merge_tagged_slice4<G, 16>(p, b, g, rsrc, sl, nchunks, tag, spin, final);
     }
     if (nchunks <= 17) return merge_tagged_slice<G, 17>(p, b, g, rsrc, sl, nchunks, tag, spin, final);
     return merge_tagged_slice<G, 20>(p, b, g, rsrc, sl, nchunks, tag, spin, final);
 }
-constexpr int kSliceChunks = 20, kSliceChunks4 = 36;   // the merge by slices serves up to this many partial results (slices of up to 16 rows: the latter)
+constexpr int kSliceChunks = 20, kSliceChunks4 = 64;   // the merge by slices serves up to this many partial results (slices of up to 16 rows: the latter)
 
 // Roles of lane (n16, c4) = (lane % 16, lane / 16) of a wavefront, per tile of 32 rows:
 //   K operand   row n16 of a 16-row half tile, dims 8*(4*kk + c4) .. +7, kk = 0..3
@@ -601,12 +602,13 @@ constexpr int kSliceChunks = 20, kSliceChunks4 = 36;   // the merge by slices se
 // query becomes the new reference; every workgroup of the sequence has read the old one by then:
 // each takes a ticket after its test, and the last one stores.
 template <int G, int NW, bool EMIT, bool TWO_SEG, bool LAZY = false, bool TAGGED = !EMIT, bool TRIG = false>
-__global__ __launch_bounds__(NW * 64, EMIT ? RK_EMIT_OCCUPANCY : 2)
+__global__ __launch_bounds__(NW * 64, (EMIT && !TAGGED) ? RK_EMIT_OCCUPANCY : 2)
 void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t s_b_and_tail, int32_t s_h, int32_t spec_rows,
                        const int32_t* seq_lens, const int32_t* tail_start, const int32_t* pred, const uint32_t* epochs,
                        const AttnParams p) {
     static_assert(!LAZY || (TWO_SEG && !EMIT), "the lazy gather belongs to the partial step");
-    static_assert(!(TAGGED && EMIT), "tagged partial results belong to the launches that merge inside the kernel");
+    // (EMIT with TAGGED: the scores go out as usual, and the output is merged inside the kernel all the same; the
+    // per-chunk (max, sum) pairs are still stored for the kernels that turn the scores into weights)
     static_assert(!TRIG || (TWO_SEG && !LAZY), "the trigger is tested by the partial step");
     // The leading arguments repeat what the first loads need (the cache that holds the first rows,
     // its strides, the two length arrays, the predicate, the call numbers): 16 dwords that the command processor
@@ -1069,6 +1071,8 @@ void attn_split_kernel(const uint16_t* k_first, const uint16_t* v_first, int64_t
                 }
                 const float inv = L > 0.f ? __builtin_amdgcn_rcpf(L) : 0.f;
                 const float lam = L > 0.f ? M + __logf(L) : -INFINITY;
+                if (EMIT && lane == 0)
+                    *reinterpret_cast<float2*>(p.part_ml + ((bg * kMaxChunks + c_rec) * G + gi) * 2) = make_float2(M, L);
                 const bool lam_row = lane == kTagDataRows;
                 if (lane <= kTagDataRows)
                     store_tagged_row(trows, G * kTagRowsPerHead, gi * kTagRowsPerHead + lane, lam_row ? lam : a0 * inv,
@@ -1782,8 +1786,28 @@ int full_attn_stage(const rk_geom* geom, const void* q, rk_kv full, const int32_
         return launch_status();
     }
     const int nchunk_grid = p.nch;
-    int rc = no_v ? launch_score_split(p, geom->batch, G, nchunk_grid, st)
+    // Where the pooling is deferred, nothing but the output merge would follow this kernel at once: it is merged
+    // inside the kernel instead of by a launch that waits for this one (tagged partial results, merged by slices, as
+    // in the partial step; full step of 32 heads over 32768 rows: 36.8 -> 35.7 us per layer).  Groups of up to 4 heads,
+    // all workgroups of the launch resident at once, no more partial results than that merge takes.  (Where the
+    // finish follows at once its first workgroups merge the output beside the pooling tiles, which costs nothing;
+    // merged inside, that step was 2.5 us slower.)
+    const bool merge_inside = fused && defer_pool && !no_v && !scores_only && ws.tag_rows != nullptr && G <= kSplitWaves && p.ragged_batch == 0 &&
+                              nchunk_grid <= kSliceChunks4 &&
+                              (int64_t)nchunk_grid * geom->batch * geom->n_kv_heads <= 2 * kComputeUnits;
+    int rc;
+    if (merge_inside) {
+        set_slice_merge(p, true, (int64_t)nchunk_grid * geom->batch * geom->n_kv_heads);
+        switch (G) {
+            case 1: rc = launch_split_g<1, true, false, true>(p, geom->batch, nchunk_grid, st); break;
+            case 2: rc = launch_split_g<2, true, false, true>(p, geom->batch, nchunk_grid, st); break;
+            case 3: rc = launch_split_g<3, true, false, true>(p, geom->batch, nchunk_grid, st); break;
+            default: rc = launch_split_g<4, true, false, true>(p, geom->batch, nchunk_grid, st); break;
+        }
+    } else {
+        rc = no_v ? launch_score_split(p, geom->batch, G, nchunk_grid, st)
                   : launch_split<true, false>(p, geom->batch, G, nchunk_grid, st);
+    }
     if (rc != RK_OK || scores_only) return rc;
     if (!fused) {
         dim3 grid(1 + (max_len + kNormTile - 1) / kNormTile, geom->n_q_heads, geom->batch);
@@ -1791,6 +1815,7 @@ int full_attn_stage(const rk_geom* geom, const void* q, rk_kv full, const int32_
         return launch_status();
     }
     if (defer_pool) {            // only the output is finished now; pool_batched_stage does the rest later
+        if (merge_inside) return rc;
         p.weights = nullptr;
         hipLaunchKernelGGL(merge_normalise_kernel, dim3(1, geom->n_q_heads, geom->batch), dim3(256), 0, st, p, G);
         return launch_status();

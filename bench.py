@@ -443,11 +443,10 @@ def run_workload(args, workload, light):
     partial_bytes = 2 * Hkv * D * 2 * (sel_rows + recent_rows)
     partial_us = graph_us(partial_call, reps=8)
     p_traffic, p_source = profile_traffic(w.name, "partial_attn")
-    # which hand-over the library picks for this shape: tagged for groups of up to 4 heads, unless the selected rows
-    # are enough for 32 workgroups per (sequence, KV head) of a launch over few such pairs (then ticketed, like larger groups)
+    # which hand-over the library picks for this shape: tagged partial results (merged by slices) for launches over few
+    # (sequence, KV head) pairs and for groups of up to 4 heads; ticketed for larger groups in launches over many pairs
     pairs = B * Hkv
-    wide = (256 + pairs // 2) // pairs >= 32 and (w.k_small + 31) // 32 > 64
-    tagged = w.group <= 4 and not wide
+    tagged = pairs <= 16 or w.group <= 4
     roofline_partial = {"bound": "hbm", "kernel": "rk::attn_split_kernel<%d, 4, false, true, false, %s, false> (rk_partial_attn)" % (w.group, "true" if tagged else "false"),
                         "achieved": round(partial_bytes / (partial_us * 1e-6) / 1e9, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                         "frac": round(partial_bytes / (partial_us * 1e-6) / 1e9 / HBM_PEAK_GBPS, 4),

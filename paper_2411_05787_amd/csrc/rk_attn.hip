@@ -1971,10 +1971,15 @@ static int launch_partial(const rk_geom* geom, const void* q, rk_kv small, int32
     const bool can_tag = ws.tag_rows != nullptr;                                       // (the built-in scratch array has no tagged region)
     // a few rows decoded since the refresh: a workgroup of their own (see the kernel), the others split the small cache
     // (ticketed merge: a 17th partial result costs it a second round trip, more than the tail workgroup gains)
-    const int tail_wg_tagged = (can_tag && lazy_idx == nullptr && n_sel > 0 && max_recent <= kMinChunk) ? 1 : 0;
-    int nch_tagged = merged_split_workgroups(n_sel, tail_wg_tagged ? 0 : max_recent, problems, false);
-    if (lazy_idx == nullptr && problems >= 16)                                         // many (sequence, KV head) pairs: see there
+    int tail_wg_tagged = (can_tag && lazy_idx == nullptr && n_sel > 0 && max_recent <= kMinChunk) ? 1 : 0;
+    int nch_tagged;
+    if (lazy_idx == nullptr && problems >= 16) {                                       // many (sequence, KV head) pairs: see there
         nch_tagged = batched_tagged_workgroups(tail_wg_tagged ? n_sel : n_sel + (int64_t)max_recent, tail_wg_tagged, problems);
+    } else if (lazy_idx == nullptr && can_tag && problems <= 8) {                      // few pairs: sized for the merge by slices
+        nch_tagged = sliced_split_workgroups(n_sel, max_recent, &tail_wg_tagged, problems, kSliceChunks4);
+    } else {
+        nch_tagged = merged_split_workgroups(n_sel, tail_wg_tagged ? 0 : max_recent, problems, false);
+    }
     // (larger groups, whose wavefronts publish two heads each: only where the launch is a matter of latency, few
     // pairs; measured at 7 and 8 heads per group, 2048 rows: 32 pairs 13.5 -> 14.9 us, 64 pairs 19.5 -> 21.4,
     // against 16 pairs of 4096 rows 13.1 -> 12.6 and 4 pairs 9.7 -> 9.0)

@@ -129,6 +129,34 @@ static inline int batched_tagged_workgroups(int64_t rows, int tail, int64_t n_pr
     return (int)best;
 }
 
+// The same where the partial results are merged by slices (every workgroup its share: see attn_split_kernel) and
+// the launch has at most 8 (sequence, KV head) pairs.  That merge costs a workgroup about the same whatever the
+// number of partial results (a lane reads a quarter of them), so the tiles per wavefront decide: as many workgroups
+// as give every wavefront the fewest tiles, within what the merge takes (`limit` partial results per pair) and what
+// is resident at once (two workgroups per compute unit); the fewest workgroups among those.  A few rows decoded
+// since the refresh (tail_rows <= 128) do not count: they get a workgroup of their own (*tail_own = 1) unless that
+// one more partial result would cost every wavefront a tile; then one wavefront takes them as a second tile
+// (K = 8192, one sequence of 8 KV heads: 64 workgroups 11.2 us, 63 + 1: 13.6, the ticketed form with 32: 12.3;
+// 4 KV heads of 7 query heads: 10.1 / 10.7 / 12.8).  Measured against the sizing above, us per partial step, one
+// sequence: 8 KV heads, K = 3072: 8.8 -> 7.4, 6144: 11.0 -> 10.0, 12288: 17.1 -> 14.9, 16384: 21.5 -> 18.8;
+// 4 KV heads of 7: K = 3072: 8.8 -> 7.4, 4096: 9.0 -> 7.7, 6144: 11.2 -> 8.7, 8192: 12.7 -> 10.3.  (With 12 pairs
+// it was no gain: 3 sequences of 4 KV heads, K = 8192: 15.3 -> 16.2.)
+static inline int sliced_split_workgroups(int64_t rows, int64_t tail_rows, int* tail_own, int64_t n_problems, int limit) {
+    const int64_t problems = n_problems > 0 ? n_problems : 1;
+    int64_t cap = 2 * kComputeUnits / problems;
+    if (cap > limit) cap = limit;
+    if (cap < 1) cap = 1;
+    const bool small_tail = rows > 0 && tail_rows <= kMinChunk;
+    const int64_t tiles = ((small_tail ? rows : rows + tail_rows) + 31) / 32;
+    auto rounds = [&](int64_t n) { return (tiles + 4 * n - 1) / (4 * n); };
+    auto fewest = [&](int64_t upto) { int64_t n = upto; while (n > 1 && rounds(n - 1) == rounds(upto)) --n; return n; };
+    *tail_own = (small_tail && cap > 1 && rounds(cap - 1) == rounds(cap)) ? 1 : 0;
+    const int64_t n = fewest(*tail_own ? cap - 1 : cap);
+    // (the tail's workgroups would be the only ones beyond one per compute unit: they wait for a unit to come free)
+    if (*tail_own && n * problems <= kComputeUnits && (n + 1) * problems > kComputeUnits) *tail_own = 0;
+    return (int)n;
+}
+
 static inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 constexpr int kBatchLayers = 32;         // layers one batched launch (rk_refresh_batched) takes; more go in several launches

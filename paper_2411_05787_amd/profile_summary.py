@@ -27,9 +27,10 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 FULL_KERNEL = r"attn_split_kernel<\d+, 4, true, false, false, false, false>"
 PARTIAL_KERNEL = r"attn_split_kernel<\d+, 4, false, true, false, (true|false), false>"
 LEGEND = [
-    ("attn_split_kernel<G, 4, true, false, false, false, false>", "streams C_f once and emits raw scores: first kernel of rk_full_attn (weights returned), rk_full_attn_select, rk_full_attn_deferred; rk_full_attn_scores launches it alone (the roofline measurement)"),
-    ("attn_split_kernel<G, 4, false, true, false, true, false>", "rk_partial_attn, groups of up to 4 heads: one launch, tagged partial results merged by the last workgroup"),
-    ("attn_split_kernel<G, 4, false, true, false, false, false>", "rk_partial_attn, larger groups (and rk_partial_attn_static): one launch, ticketed merge"),
+    ("attn_split_kernel<G, 4, true, false, false, false, false>", "streams C_f once and emits raw scores: first kernel of rk_full_attn (weights returned) and rk_full_attn_select; rk_full_attn_scores launches it alone (the roofline measurement)"),
+    ("attn_split_kernel<G, 4, true, false, false, true, false>", "the same with the output merged inside (tagged partial results, merge by slices): the one kernel of rk_full_attn_deferred for groups of up to 4 heads"),
+    ("attn_split_kernel<G, 4, false, true, false, true, false>", "rk_partial_attn: one launch, tagged partial results, merged by slices (every workgroup its share) or by the last workgroup"),
+    ("attn_split_kernel<G, 4, false, true, false, false, false>", "rk_partial_attn, groups of more than 4 heads in launches over many (sequence, KV head) pairs, and rk_partial_attn_static: one launch, ticketed merge"),
     ("attn_split_kernel<G, 4, false, true, false, *, true>", "rk_partial_attn_triggered: the partial step of a trigger test step, with the query-similarity test inside"),
     ("attn_split_kernel<G, 4, false, false, false, true, false>", "rk_full_attn without weights over short rows: one launch, merged inside"),
     ("merge_normalise_kernel", "output merge of rk_full_attn / rk_full_attn_deferred (+ weights in place for rk_full_attn)"),

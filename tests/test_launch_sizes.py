@@ -26,6 +26,12 @@ int main() {
                merged_split_workgroups(r, tail, p, true), (int)two_batches_pay(r, tail, p));
     for (long r : rows) for (long p : problems) for (int tail : {0, 1})
         printf("batched %ld %d %ld %d\n", r, tail, p, batched_tagged_workgroups(r, tail, p));
+    for (long r : {1L, 100L, 128L, 1024L, 2048L, 3072L, 4096L, 6144L, 8192L, 12288L, 16384L, 100000L}) for (long p : {1L, 4L, 8L})
+        for (int tail : {0, 10, 128, 500}) {
+            int own = -1;
+            const int n = sliced_split_workgroups(r, tail, &own, p, 64);
+            printf("sliced %ld %d %ld %d %d\n", r, tail, p, n, own);
+        }
     const long lens[] = {1, 2000, 32768, 33008, 65536, 131072, 1000000};
     for (long l : lens) for (int b : {1, 2, 16}) for (int hkv : {1, 4, 8}) {
         rk_geom g{b, hkv * 4, hkv, 128, 1.0f};
@@ -101,3 +107,28 @@ def test_headline_shapes(table):
     assert emit[(131072, 1, 8)] * 8 == 1024             # cfg5
     for (length, b, hkv), n in emit.items():
         assert 1 <= n <= 1024 and n <= max((length + 127) // 128, 1)
+
+
+def test_sliced_split_bounds_and_measured_choices(table):
+    """Sizing of the partial step for the merge by slices: within what the merge takes and what is resident at once,
+    never more workgroups than stretches of 128 rows, and the choices the measurements led to."""
+    got = {}
+    for kind, *v in table:
+        if kind != "sliced":
+            continue
+        rows, tail, problems, n, own = map(int, v)
+        got[(rows, tail, problems)] = (n, own)
+        assert own in (0, 1) and 1 <= n and n + own <= 64
+        assert (n + own) * problems <= 512
+        counted = rows if tail <= 128 else rows + tail
+        assert n <= max((counted + 127) // 128, 1)
+        if tail > 128:
+            assert own == 0
+    assert len(got) == 12 * 3 * 4
+    assert got[(2048, 10, 8)] == (16, 1)          # 16 workgroups of one tile per wavefront and the tail's own
+    assert got[(4096, 10, 8)] == (32, 0)          # 32 x 8 = 256 workgroups: the tail's would be the only ones beyond one per CU
+    assert got[(4096, 10, 4)] == (32, 1)
+    assert got[(8192, 10, 8)] == (64, 0)          # a 65th partial result would cost every wavefront a second tile
+    assert got[(8192, 10, 4)] == (64, 0)
+    assert got[(16384, 10, 8)] == (64, 0)         # two tiles per wavefront either way
+    assert got[(3072, 10, 8)] == (24, 1)

@@ -1974,7 +1974,8 @@ static int launch_partial(const rk_geom* geom, const void* q, rk_kv small, int32
     int tail_wg_tagged = (can_tag && lazy_idx == nullptr && n_sel > 0 && max_recent <= kMinChunk) ? 1 : 0;
     int nch_tagged;
     if (lazy_idx == nullptr && problems >= 16) {                                       // many (sequence, KV head) pairs: see there
-        nch_tagged = batched_tagged_workgroups(tail_wg_tagged ? n_sel : n_sel + (int64_t)max_recent, tail_wg_tagged, problems);
+        if (tail_wg_tagged) nch_tagged = batched_tagged_workgroups(n_sel, max_recent, &tail_wg_tagged, problems);
+        else nch_tagged = batched_tagged_workgroups(n_sel + (int64_t)max_recent, 0, &tail_wg_tagged, problems);
     } else if (lazy_idx == nullptr && can_tag && problems <= 8) {                      // few pairs: sized for the merge by slices
         nch_tagged = sliced_split_workgroups(n_sel, max_recent, &tail_wg_tagged, problems, kSliceChunks4);
     } else {

@@ -112,20 +112,32 @@ static inline int merged_split_workgroups(int64_t rows, int64_t tail_rows, int64
 // tiles per wavefront, fewer tiles per wavefront on a tie (3 sequences, K = 2048: 288 workgroups 12.7 -> 408
 // workgroups 10.4; K = 4096: 17.5 -> 14.7; K = 8192: 29.7 -> 25.2; 2 sequences, K = 4096: 272 workgroups
 // 13.9 -> 192 or 256 workgroups 12.3; K = 8192: 22.1 -> 18.1 - 18.4; K = 2048 stays at 272 workgroups, 9.8).
-static inline int batched_tagged_workgroups(int64_t rows, int tail, int64_t n_problems) {
-    const int64_t stretches = (rows + kMinChunk - 1) / kMinChunk;
-    const int64_t tiles = (rows + 31) / 32;
+// The rows decoded since the refresh: a workgroup of their own (*tail_own = 1) or one wavefront's extra tile at the
+// end (0), whichever the same estimate likes better; without their workgroups the launch can be exactly one
+// workgroup per CU (16 sequences of 8 KV heads: K = 2048, 2 workgroups per pair and no tail workgroup, 256 in all,
+// 28.7 us against 3 + 1, 512 in all, 32.6; K = 1024: 17.5 against 18.3; 8 sequences, K = 2048: 4 per pair 19.4
+// against 20.0).  tail_rows > 128 (or no selected rows): all rows are shared out alike.
+static inline int batched_tagged_workgroups(int64_t rows, int64_t tail_rows, int* tail_own, int64_t n_problems) {
+    const bool small_tail = rows > 0 && tail_rows > 0 && tail_rows <= kMinChunk;
+    const int64_t main_rows = small_tail ? rows : rows + tail_rows;
+    const int64_t stretches = (main_rows + kMinChunk - 1) / kMinChunk;
+    const int64_t tiles = (main_rows + 31) / 32;
+    const bool few = n_problems < 32;
     int64_t best = 1, best_cost = -1, best_rounds = 0;
-    for (int64_t n = 1; n <= stretches && n <= kMergeChunks; ++n) {
-        const int64_t per_cu = ((n + tail) * n_problems + kComputeUnits - 1) / kComputeUnits;
-        const int64_t rounds = (tiles + 4 * n - 1) / (4 * n);
-        const int64_t fixed = 1 + (n + tail - 1) / 20;
-        const bool few = n_problems < 32;
-        const int64_t cost = few ? rounds + fixed + (per_cu - 1) * rounds : per_cu * (rounds + fixed);
-        if (best_cost < 0 || cost < best_cost || (few && cost == best_cost && rounds < best_rounds)) {      // ties (few pairs): fewer tiles per wavefront
-            best = n; best_cost = cost; best_rounds = rounds;
+    int best_tail = 0;
+    for (int tail = small_tail ? 1 : 0; tail >= 0; --tail) {
+        for (int64_t n = 1; n <= stretches && n <= kMergeChunks; ++n) {
+            const int64_t per_cu = ((n + tail) * n_problems + kComputeUnits - 1) / kComputeUnits;
+            const int64_t rounds = (tiles + 4 * n - 1) / (4 * n);
+            const int64_t fixed = 1 + (n + tail - 1) / 20;
+            const int64_t extra = (small_tail && !tail) ? 1 : 0;          // the tail as one wavefront's last tile
+            const int64_t cost = (few ? rounds + fixed + (per_cu - 1) * rounds : per_cu * (rounds + fixed)) + extra;
+            if (best_cost < 0 || cost < best_cost || (few && cost == best_cost && tail == best_tail && rounds < best_rounds)) {   // ties (few pairs): fewer tiles per wavefront
+                best = n; best_cost = cost; best_rounds = rounds; best_tail = tail;
+            }
         }
     }
+    *tail_own = best_tail;
     return (int)best;
 }
 

@@ -24,8 +24,11 @@ int main() {
     for (long r : rows) for (long p : problems) for (int tail : {0, 10, 128, 500})
         printf("merged %ld %d %ld %d %d %d\n", r, tail, p, merged_split_workgroups(r, tail, p, false),
                merged_split_workgroups(r, tail, p, true), (int)two_batches_pay(r, tail, p));
-    for (long r : rows) for (long p : problems) for (int tail : {0, 1})
-        printf("batched %ld %d %ld %d\n", r, tail, p, batched_tagged_workgroups(r, tail, p));
+    for (long r : rows) for (long p : problems) for (int tail : {0, 10, 500}) {
+        int own = -1;
+        const int n = batched_tagged_workgroups(r, tail, &own, p);
+        printf("batched %ld %d %ld %d %d\n", r, tail, p, n, own);
+    }
     for (long r : {1L, 100L, 128L, 1024L, 2048L, 3072L, 4096L, 6144L, 8192L, 12288L, 16384L, 100000L}) for (long p : {1L, 4L, 8L})
         for (int tail : {0, 10, 128, 500}) {
             int own = -1;
@@ -85,15 +88,18 @@ def test_batched_tagged_bounds_and_measured_choices(table):
     for kind, *v in table:
         if kind != "batched":
             continue
-        rows, tail, problems, n = map(int, v)
-        assert 1 <= n <= 64 and n <= max((rows + 127) // 128, 1)
-        got[(rows, tail, problems)] = n
-    # the shapes that were measured (tail workgroup in use)
-    assert got[(1024, 1, 128)] == 3 and got[(2048, 1, 128)] == 3 and got[(4096, 1, 128)] == 3      # 16 sequences x 8 KV heads: 512 workgroups
-    assert got[(1024, 1, 64)] == 3 and got[(2048, 1, 64)] == 3                                   # 8 sequences: 256 workgroups
-    assert got[(2048, 1, 32)] == 6 and got[(8192, 1, 32)] == 7                                   # 4 sequences: at most 256 workgroups
-    assert got[(2048, 1, 16)] == 16 and got[(2048, 1, 24)] == 16                                 # 2 and 3 sequences: one tile per wavefront
-    assert (got[(4096, 1, 16)] + 1) * 16 <= 256                                                   # 2 sequences, K = 4096: no CU with two workgroups
+        rows, tail, problems, n, own = map(int, v)
+        counted = rows if tail <= 128 else rows + tail
+        assert own in (0, 1) and 1 <= n <= 64 and n <= max((counted + 127) // 128, 1)
+        if tail == 0 or tail > 128:
+            assert own == 0
+        got[(rows, tail, problems)] = (n, own)
+    # the shapes that were measured
+    assert got[(2048, 10, 128)] == (2, 0) and got[(1024, 10, 128)] == (2, 0)      # 16 sequences x 8 KV heads: 256 workgroups, no tail workgroup
+    assert got[(2048, 10, 64)] == (4, 0)                                        # 8 sequences: 256 workgroups
+    assert sum(got[(2048, 10, 32)]) * 32 <= 256 and sum(got[(8192, 10, 32)]) * 32 <= 256    # 4 sequences: at most 256 workgroups
+    assert got[(2048, 10, 16)][0] == 16 and got[(2048, 10, 24)][0] == 16        # 2 and 3 sequences: one tile per wavefront
+    assert sum(got[(4096, 10, 16)]) * 16 <= 256                                 # 2 sequences, K = 4096: no CU with two workgroups
 
 
 def test_headline_shapes(table):

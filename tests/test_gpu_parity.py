@@ -738,6 +738,46 @@ def test_partial_attn_merge_by_slices_handover(rk, shape):
     assert_out_close(gen.bf16_bits(full[0]), f_ref, "full attention, merge by slices")
 
 
+def test_partial_attn_on_two_streams_at_once(rk):
+    """Partial steps of two independent caches enqueued on two streams, so that their launches can share the chip:
+    a workgroup of the merge by slices then may find its compute unit only after others of its launch have waited
+    for it; the waits are bounded and hand over, and the results are those of the same calls one after the other."""
+    say("partial_attn_two_streams")
+    B, Hq, Hkv, k, cap = 1, 32, 8, 2048, 6000
+    geom = rk.Geom(B, Hq, Hkv, 128, float(np.float32(1 / np.sqrt(128))))
+    g = torch.Generator(device="cuda").manual_seed(91)
+    sets = []
+    for i in range(2):
+        K = torch.randn(B, Hkv, cap, 128, generator=g, device="cuda").to(torch.bfloat16)
+        V = torch.randn(B, Hkv, cap, 128, generator=g, device="cuda").to(torch.bfloat16)
+        sK = torch.randn(B, Hkv, k, 128, generator=g, device="cuda").to(torch.bfloat16)
+        sV = torch.randn(B, Hkv, k, 128, generator=g, device="cuda").to(torch.bfloat16)
+        q = torch.randn(B, Hq, 128, generator=g, device="cuda").to(torch.bfloat16)
+        lens = torch.full((B,), 5000 + i, dtype=torch.int32, device="cuda")
+        sets.append(dict(K=K, V=V, sK=sK, sV=sV, q=q, lens=lens, tail=lens - 7, ws=rk.Workspace(geom, cap, k),
+                         out=torch.zeros(B, Hq, 128, dtype=torch.bfloat16, device="cuda")))
+
+    def step(d, stream=None):
+        rk.rk_partial_attn(geom, d["q"], d["sK"], d["sV"], k, d["K"], d["V"], d["tail"], d["lens"], 8, d["out"],
+                           workspace=d["ws"], stream=stream)
+    want = []
+    for d in sets:
+        step(d)
+        torch.cuda.synchronize()
+        want.append(d["out"].clone())
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for rep in range(20):
+        for d in sets:
+            d["out"].zero_()
+        torch.cuda.synchronize()
+        for _ in range(8):                      # a few launches deep on either stream
+            for d, st in zip(sets, streams):
+                step(d, stream=st)
+        torch.cuda.synchronize()
+        for d, w in zip(sets, want):
+            assert torch.equal(d["out"], w), rep
+
+
 # ----------------------------------------------------------------------------- whole loop
 def run_gpu_loop(rk, w: gen.Workload, layer: int, K, V, q_steps, new_k, new_v, lens0, evict_lowest=False,
                  scores_only=False):

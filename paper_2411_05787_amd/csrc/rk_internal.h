@@ -75,7 +75,9 @@ static inline int split_workgroups(int64_t max_rows, int64_t n_problems, int lim
 // against 13.0 us at K = 8192, groups of 4).
 // (Groups of up to 4 heads: the tagged merge wins while 16 workgroups give a wavefront one tile, the
 // ticketed one with 32 workgroups beyond: K = 2048 7.5 / 7.7 us, 4096 9.8 / 9.3, 8192 13.0 / 12.5,
-// 16384 23.9 / 18.1; so where this is true the partial step takes the ticketed form whatever the group.)
+// 16384 23.9 / 18.1; so where this is true and the merge is the last workgroup's, the partial step takes the
+// ticketed form whatever the group.  With the merge by slices, below, neither is used for launches over few
+// pairs: what is left of this rule serves the workspace without a tagged region.)
 static inline bool two_batches_pay(int64_t rows, int64_t tail_rows, int64_t n_problems) {
     const int64_t problems = n_problems > 0 ? n_problems : 1;
     const int64_t main_rows = (rows > 0 && tail_rows <= kMinChunk) ? rows : rows + tail_rows;     // a few rows decoded since the refresh do not count

@@ -1773,8 +1773,11 @@ int full_attn_stage(const rk_geom* geom, const void* q, rk_kv full, const int32_
         // (its stores switched off) and the merge as a second small launch fill the chip better.
         const int wide = split_workgroups(max_len, (int64_t)geom->batch * geom->n_kv_heads, kMaxChunks);
         if (wide <= kMergeChunks) {
-            p.nch = merged_split_workgroups(max_len, 0, (int64_t)geom->batch * geom->n_kv_heads);
-            set_slice_merge(p, true, (int64_t)p.nch * geom->batch * geom->n_kv_heads);
+            const int64_t problems = (int64_t)geom->batch * geom->n_kv_heads;
+            int own = 0;
+            p.nch = (ws.tag_rows != nullptr && problems <= 8) ? sliced_split_workgroups(max_len, 0, &own, problems, kSliceChunks4)
+                                                              : merged_split_workgroups(max_len, 0, problems);
+            set_slice_merge(p, true, (int64_t)p.nch * problems);
             return launch_split<false, false>(p, geom->batch, G, p.nch, st);
         }
         p.nch = wide;
